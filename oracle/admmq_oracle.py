@@ -1,0 +1,415 @@
+"""Float64 CPU oracle for the ADMM-Q layer solver.  TEST INFRASTRUCTURE ONLY.
+
+Only the test-suite, the smoke check and the benchmark's cpu_baseline leg may import this file.  The
+HIP library and its Python binding never do, and nothing here imports them.
+
+The solver is a heuristic iteration for an NP-hard problem, so there is no closed-form result to write
+down: the oracle takes the algorithm's steps in the paper's order and notation (Alg. 1, eqs. 7-10,
+Sec. 3.5), in NumPy float64, with the W-update in the literal form of eq. 7 through the
+eigendecomposition of Sec. 3.3.  No blocking, fusion or algebraic rearrangement.
+
+Notation: X [N][n] activations, W0 = dense weights [n][p] (n input channels, p output channels),
+H = X^T X, H' = H + lambda I, Sigma = Diag(H')^{-1/2} with d_i = sqrt(H'_ii) = 1/Sigma_ii,
+scaled problem Hs = Sigma H' Sigma, Ws = Sigma^{-1} W0, split variable D, unscaled dual V.
+
+Where the paper leaves a choice open the reading taken is stated at the function that takes it.
+
+Pins (tests/test_oracle_*.py): Hessian against a triple loop; unit diagonal of Hs; the W-update
+against numpy.linalg.solve; projection against brute force over the 2^b levels; first iterate equals
+round-to-nearest of W0; key inequality of App. C each iteration; rho_t * residual bounded; eq. 11
+against recomputed objectives; maintained gradient against a recomputed one; n <= 6, 2-bit exhaustive
+enumeration for the local search.  The absolute objective values of the five workloads are
+"parity unpinned": the paper prints no worked numeric example of the solver.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+# ----------------------------------------------------------------------------------------------
+# Problem set-up
+# ----------------------------------------------------------------------------------------------
+
+
+def hessian(chunks) -> np.ndarray:
+    """H = X^T X accumulated over row chunks (Sec. 3.1, text after eq. 1), un-normalised sum."""
+    H = None
+    for xc in chunks:
+        xc = np.asarray(xc, dtype=np.float64)
+        H = xc.T @ xc if H is None else H + xc.T @ xc
+    return H
+
+
+def damp_hessian(H: np.ndarray, damp: float = 0.01):
+    """H' = H + lambda I (App. D, implementation details).
+
+    Reading: the printed constant multiplies Tr(X^T X); taken literally at n in the thousands this
+    would make H' nearly a multiple of I.  The sentence says it follows GPTQ, whose convention is a
+    fraction of the MEAN diagonal, so lambda = damp * Tr(H) / n.  The literal reading is damp*n.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    n = H.shape[0]
+    lam = damp * np.trace(H) / n
+    return H + lam * np.eye(n), lam
+
+
+def scale_problem(Hd: np.ndarray, W0: np.ndarray, precondition: bool = True):
+    """Alg. 1 lines 1-2 (eqs. 3-4): d_i = sqrt(H'_ii); Hs = Sigma H' Sigma; Ws = Sigma^{-1} W0.
+    With ``precondition`` off (the paper's ablation) Sigma = I."""
+    Hd = np.asarray(Hd, dtype=np.float64)
+    n = Hd.shape[0]
+    diag = np.diag(Hd)
+    if np.any(diag <= 0) or not np.all(np.isfinite(diag)):
+        raise ValueError("non-positive diagonal entry in the damped Hessian (dead input channel)")
+    d = np.sqrt(diag) if precondition else np.ones(n)
+    Hs = Hd / d[:, None] / d[None, :]
+    Ws = np.asarray(W0, dtype=np.float64) * d[:, None]
+    return d, Hs, Ws
+
+
+def grid_init(W0: np.ndarray, bits: int, group_size: int = 0):
+    """Min/max grid of the dense weights, no clipping (Sec. 3.4 "Clipping heuristics"; Sec. 3.3 grid
+    refresh paragraph: initialised by round-to-nearest on the dense weights).
+
+    Reading: a group is ``group_size`` consecutive INPUT channels (rows) inside one output column;
+    group_size = 0 means one grid per output column.  delta = (max-min)/(2^b-1), z0 = min (the
+    real-valued offset of eq. 10).  A group with max == min gets delta = 1 and is marked degenerate:
+    all its codes stay 0.  Returns delta, z0 with shape [n/g][p].
+    """
+    W0 = np.asarray(W0, dtype=np.float64)
+    n, p = W0.shape
+    g = n if group_size in (0, None) else int(group_size)
+    if n % g != 0:
+        raise ValueError("group_size must divide n")
+    Wg = W0.reshape(n // g, g, p)
+    mn = Wg.min(axis=1)
+    mx = Wg.max(axis=1)
+    delta = (mx - mn) / float(2 ** bits - 1)
+    delta = np.where(mx > mn, delta, 1.0)
+    return delta, mn
+
+
+def _expand(a: np.ndarray, n: int) -> np.ndarray:
+    """[n/g][p] -> [n][p] by repeating each group row g times."""
+    g = n // a.shape[0]
+    return np.repeat(a, g, axis=0)
+
+
+@dataclass
+class Grid:
+    """Quantization grid theta = (delta, z0) per group, plus the degenerate-group flag.
+
+    ``codes`` is eq. 10 on unscaled values x [n][p]: k = clamp(Round((x - z0)/delta), 0, 2^b-1).
+    Round is round-half-to-even; the clamp keeps k inside the finite grid of Sec. 3.5 "Setup"."""
+    delta: np.ndarray      # [n/g][p]
+    z0: np.ndarray         # [n/g][p]
+    bits: int
+    degenerate: np.ndarray  # [n/g][p] bool
+
+    @staticmethod
+    def fit(W0, bits, group_size=0) -> "Grid":
+        W0 = np.asarray(W0, dtype=np.float64)
+        n, p = W0.shape
+        g = n if group_size in (0, None) else int(group_size)
+        delta, z0 = grid_init(W0, bits, group_size)
+        mx = W0.reshape(n // g, g, p).max(axis=1)
+        return Grid(delta, z0, bits, mx <= z0)
+
+    def codes(self, x: np.ndarray) -> np.ndarray:
+        n = x.shape[0]
+        k = np.clip(np.rint((x - _expand(self.z0, n)) / _expand(self.delta, n)), 0, 2 ** self.bits - 1)
+        k = np.where(_expand(self.degenerate, n), 0.0, k)
+        return k.astype(np.int64)
+
+    def dequant(self, k: np.ndarray) -> np.ndarray:
+        n = k.shape[0]
+        return _expand(self.z0, n) + k.astype(np.float64) * _expand(self.delta, n)
+
+
+def rtn(W0: np.ndarray, grid: Grid):
+    """Round-to-nearest of the dense weights on the grid (the data-free baseline of Sec. 3.1)."""
+    k = grid.codes(np.asarray(W0, dtype=np.float64))
+    return k, grid.dequant(k)
+
+
+def objective(Hm: np.ndarray, W0: np.ndarray, Wq: np.ndarray) -> float:
+    """Tr((Wq-W0)^T Hm (Wq-W0)) : eq. 2 without the 1/2, as the column sum of Sec. 3.5 writes it."""
+    E = np.asarray(Wq, dtype=np.float64) - np.asarray(W0, dtype=np.float64)
+    return float(np.sum(E * (np.asarray(Hm, dtype=np.float64) @ E)))
+
+
+# ----------------------------------------------------------------------------------------------
+# ADMM loop (Alg. 1 lines 3-10)
+# ----------------------------------------------------------------------------------------------
+
+
+def w_update(U, lam, HWs, D, V, rho):
+    """Eq. 7 through the eigendecomposition of Sec. 3.3:
+    W = U (Lambda + rho I)^{-1} U^T (Hs Ws + rho D - V)."""
+    rhs = HWs + rho * D - V
+    return U @ ((U.T @ rhs) / (lam + rho)[:, None])
+
+
+def d_update(W, V, rho, d, grid: Grid):
+    """Eqs. 8 and 10: target Wt = W + V/rho; Sigma Wt is rounded on the grid; D = Sigma^{-1}(...)."""
+    Wt = W + V / rho
+    x = Wt / d[:, None]
+    k = grid.codes(x)
+    Dn = d[:, None] * grid.dequant(k)
+    return k, Dn, Wt
+
+
+@dataclass
+class AdmmResult:
+    codes: np.ndarray
+    Wq: np.ndarray
+    primal: list = field(default_factory=list)     # ||W^{t+1} - D^{t+1}||_F
+    dual: list = field(default_factory=list)       # ||D^{t+1} - D^{t}||_F
+    rho: list = field(default_factory=list)
+    key_lhs: list = field(default_factory=list)    # ||D^{t+1} - Wt||^2
+    key_rhs: list = field(default_factory=list)    # ||D^{t}   - Wt||^2
+    first_codes: np.ndarray | None = None
+    d: np.ndarray | None = None
+    lam_eig: np.ndarray | None = None
+
+
+def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True) -> AdmmResult:
+    """Alg. 1 lines 1-10 on the damped Hessian Hd.  rho_t = rho0 * gamma^t (Sec. 3.6), exactly T
+    iterations (no early stop).  Tiny negative eigenvalues from round-off are clamped at 0."""
+    W0 = np.asarray(W0, dtype=np.float64)
+    d, Hs, Ws = scale_problem(Hd, W0, precondition)
+    lam, U = np.linalg.eigh(Hs)
+    lam = np.maximum(lam, 0.0)
+    HWs = Hs @ Ws
+    D = Ws.copy()
+    V = np.zeros_like(Ws)
+    rho = float(rho0)
+    res = AdmmResult(codes=None, Wq=None, d=d, lam_eig=lam)
+    k = None
+    for t in range(T):
+        W = w_update(U, lam, HWs, D, V, rho)
+        k, Dn, Wt = d_update(W, V, rho, d, grid)
+        res.key_lhs.append(float(np.sum((Dn - Wt) ** 2)))
+        res.key_rhs.append(float(np.sum((D - Wt) ** 2)))
+        V = V + rho * (W - Dn)
+        res.primal.append(float(np.linalg.norm(W - Dn)))
+        res.dual.append(float(np.linalg.norm(Dn - D)))
+        res.rho.append(rho)
+        if t == 0:
+            res.first_codes = k.copy()
+        D = Dn
+        rho = rho * gamma
+    res.codes = k
+    res.Wq = grid.dequant(k)        # = Sigma D^(T)  (Alg. 1 line 10)
+    return res
+
+
+# ----------------------------------------------------------------------------------------------
+# fp32 mirror of one projection + dual step, for bit-exact comparison of integer codes.
+# Where floating point decides an integer both sides must decide in the same precision; the HIP
+# kernel works in fp32 with this exact operation order (every operation rounded once, no fused
+# multiply-add), and with reciprocals of rho, d_i and delta formed once in fp32.
+# ----------------------------------------------------------------------------------------------
+
+
+def project_dual_step_f32(W, V, rho, rho_next, d, delta, z0, degenerate, bits):
+    """One pass of eqs. 8-10 in fp32.  Returns codes (uint8), V_new, B_new = D_new - V_new/rho_next,
+    and the float64 sum of squares of (W - D_new) over the fp32 differences."""
+    f = np.float32
+    W = np.asarray(W, dtype=f)
+    V = np.asarray(V, dtype=f)
+    n = W.shape[0]
+    rho = f(rho)
+    inv_rho = f(1.0) / rho
+    inv_rho_next = f(1.0) / f(rho_next)
+    d = np.asarray(d, dtype=f)
+    inv_d = (f(1.0) / d)[:, None]
+    dl = np.asarray(delta, dtype=f)
+    inv_dl = np.where(np.asarray(degenerate), f(0.0), f(1.0) / dl).astype(f)
+    dl_e = _expand(dl, n)
+    inv_dl_e = _expand(inv_dl, n)
+    z_e = _expand(np.asarray(z0, dtype=f), n)
+    q = V * inv_rho
+    wt = W + q
+    x = wt * inv_d
+    y = x - z_e
+    t = y * inv_dl_e
+    k = np.minimum(np.maximum(np.rint(t), f(0.0)), f(2 ** bits - 1))
+    xq = k * dl_e + z_e          # two roundings: product, then sum
+    Dn = d[:, None] * xq
+    r = W - Dn
+    Vn = V + rho * r
+    Bn = Dn - Vn * inv_rho_next
+    ss = float(np.sum(r.astype(np.float64) ** 2))
+    return k.astype(np.uint8), Vn.astype(f), Bn.astype(f), ss
+
+
+# ----------------------------------------------------------------------------------------------
+# Pair-swap local search (Sec. 3.5)
+# ----------------------------------------------------------------------------------------------
+
+_M64 = (1 << 64) - 1
+
+
+def _mix64(x: int) -> int:
+    """The SplitMix64 output function (Steele, Lea, Flood 2014) applied to x + golden-ratio gamma."""
+    x = (x + 0x9E3779B97F4A7C15) & _M64
+    z = x
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    return z ^ (z >> 31)
+
+
+def sample_pair(seed: int, rnd: int, batch: int, slot: int, n: int):
+    """Counter-based draw of an ordered row pair i1 != i2 for (round, batch, slot).
+    key = round*2^48 + batch*2^16 + slot; c = mix(seed xor mix(key));
+    i1 = low32(c) mod n; i2 = (i1 + 1 + high32(c) mod (n-1)) mod n."""
+    key = ((rnd << 48) ^ (batch << 16) ^ slot) & _M64
+    c = _mix64((seed & _M64) ^ _mix64(key))
+    i1 = (c & 0xFFFFFFFF) % n
+    i2 = (i1 + 1 + ((c >> 32) % (n - 1))) % n
+    return int(i1), int(i2)
+
+
+def sample_batch(seed, rnd, batch, B, n):
+    return [sample_pair(seed, rnd, batch, s, n) for s in range(B)]
+
+
+_SIGNS = ((1, 1), (1, -1), (-1, 1), (-1, -1))   # fixed evaluation order of the four combinations
+
+
+def pair_gains(Hd, G, codes, grid: Grid, i1: int, i2: int):
+    """Eq. 11 for one row pair, all columns, all four sign combinations.
+    Returns dL [4][p] with +inf where a combination leaves the grid bounds (or the group is
+    degenerate), and the per-row step sizes (delta of that row's group: per-group extension of the
+    per-channel delta_j of the paper)."""
+    n, p = codes.shape
+    g = n // grid.delta.shape[0]
+    L = 2 ** grid.bits - 1
+    d1 = grid.delta[i1 // g]
+    d2 = grid.delta[i2 // g]
+    dead = grid.degenerate[i1 // g] | grid.degenerate[i2 // g]
+    k1 = codes[i1]
+    k2 = codes[i2]
+    dL = np.empty((4, p))
+    for c, (s1, s2) in enumerate(_SIGNS):
+        a = s1 * d1
+        b = s2 * d2
+        val = (-2.0 * a * G[i1] + a * a * Hd[i1, i1] - 2.0 * b * G[i2] + b * b * Hd[i2, i2]
+               + 2.0 * a * b * Hd[i1, i2])
+        ok = (k1 + s1 >= 0) & (k1 + s1 <= L) & (k2 + s2 >= 0) & (k2 + s2 <= L) & (~dead)
+        dL[c] = np.where(ok, val, np.inf)
+    return dL, d1, d2
+
+
+def column_moves(dL):
+    """Per column: index of the feasible combination with the smallest dL (first in the fixed order
+    on ties), the move is taken only if that dL < 0.  Returns (combo index or -1, gain = -dL or 0)."""
+    best = np.argmin(dL, axis=0)                  # argmin returns the first minimiser
+    val = dL[best, np.arange(dL.shape[1])]
+    take = val < 0.0
+    return np.where(take, best, -1), np.where(take, -val, 0.0)
+
+
+@dataclass
+class LocalSearchResult:
+    codes: np.ndarray
+    moves: int                 # number of applied pairs
+    entries_changed: int       # number of (row, column) code changes
+    applied: list              # (round, batch, slot, i1, i2, total gain)
+    objective_drop: float      # sum of the applied totals (= J_before - J_after)
+    G: np.ndarray | None = None  # maintained gradient H'(W0 - Wq) at exit
+
+
+def local_search(Hd, W0, codes, grid: Grid, rounds=5, batches_per_round=None, pairs_per_batch=64,
+                 seed=0, pairs_fn=None, G=None) -> LocalSearchResult:
+    """Pair-swap refinement in the UNSCALED space on the damped Hessian (objective of eq. 2).
+
+    Reading of Sec. 3.5 (its list of steps skips one number and leaves sizes open): G = H'(W0 - Wq).
+    Each round runs ``batches_per_round`` batches (default ceil(n/2), about one visit per row); a
+    batch draws ``pairs_per_batch`` ordered pairs with the counter-based generator above; for every
+    pair each column picks its best feasible sign combination by eq. 11 and moves only if that
+    lowers the loss; the pair's total is the sum of the columns' gains; the pair with the largest
+    total (lowest slot on ties) is applied if its total is positive, and G gets the rank-2
+    correction.  A round that applies nothing ends the search.  ``pairs_fn(round, batch)`` may
+    replace the generator (the exhaustive variant of the brute-force tests passes all pairs).
+    """
+    Hd = np.asarray(Hd, dtype=np.float64)
+    W0 = np.asarray(W0, dtype=np.float64)
+    codes = np.array(codes, dtype=np.int64, copy=True)
+    n, p = codes.shape
+    M = (n + 1) // 2 if batches_per_round is None else int(batches_per_round)
+    if G is None:
+        G = Hd @ (W0 - grid.dequant(codes))
+    else:
+        G = np.array(G, dtype=np.float64, copy=True)
+    out = LocalSearchResult(codes, 0, 0, [], 0.0)
+    for r in range(rounds):
+        applied_this_round = 0
+        for m in range(M):
+            pairs = pairs_fn(r, m) if pairs_fn is not None else sample_batch(seed, r, m, pairs_per_batch, n)
+            best_total, best_slot, best_plan = 0.0, -1, None
+            for slot, (i1, i2) in enumerate(pairs):
+                dL, d1, d2 = pair_gains(Hd, G, codes, grid, i1, i2)
+                combo, gain = column_moves(dL)
+                total = float(np.sum(gain))
+                if total > best_total:
+                    best_total, best_slot, best_plan = total, slot, (i1, i2, combo, d1, d2)
+            if best_slot < 0:
+                continue
+            i1, i2, combo, d1, d2 = best_plan
+            s1 = np.array([_SIGNS[c][0] if c >= 0 else 0 for c in combo], dtype=np.int64)
+            s2 = np.array([_SIGNS[c][1] if c >= 0 else 0 for c in combo], dtype=np.int64)
+            codes[i1] += s1
+            codes[i2] += s2
+            G -= np.outer(Hd[:, i1], s1 * d1) + np.outer(Hd[:, i2], s2 * d2)
+            out.moves += 1
+            out.entries_changed += int(np.count_nonzero(s1) + np.count_nonzero(s2))
+            out.applied.append((r, m, best_slot, i1, i2, best_total))
+            out.objective_drop += best_total
+            applied_this_round += 1
+        if applied_this_round == 0:
+            break
+    out.codes = codes
+    out.G = G
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# Whole layer (Alg. 1)
+# ----------------------------------------------------------------------------------------------
+
+
+@dataclass
+class LayerResult:
+    codes: np.ndarray
+    scales: np.ndarray
+    zeros: np.ndarray
+    Wq: np.ndarray
+    j_damp: float          # objective on H' after ADMM + local search
+    j_damp_admm: float     # after ADMM, before local search
+    j_damp_rtn: float      # round-to-nearest on the same grid
+    j_recon: float         # ||X (Wq - W0)||_F^2  (objective on the undamped H)
+    admm: AdmmResult
+    ls: LocalSearchResult | None
+    lam: float
+
+
+def quantize_layer(H, W0, bits, group_size=0, T=300, rho0=0.1, gamma=1.1, damp=0.01, precondition=True,
+                   ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0) -> LayerResult:
+    """Alg. 1 end to end from the raw (undamped) Hessian H = X^T X."""
+    H = np.asarray(H, dtype=np.float64)
+    W0 = np.asarray(W0, dtype=np.float64)
+    Hd, lam = damp_hessian(H, damp)
+    grid = Grid.fit(W0, bits, group_size)
+    k_rtn, W_rtn = rtn(W0, grid)
+    a = admm(Hd, W0, grid, T, rho0, gamma, precondition)
+    j_admm = objective(Hd, W0, a.Wq)
+    codes, ls = a.codes, None
+    if ls_rounds > 0:
+        ls = local_search(Hd, W0, a.codes, grid, ls_rounds, ls_batches, ls_pairs, seed)
+        codes = ls.codes
+    Wq = grid.dequant(codes)
+    return LayerResult(codes, grid.delta, grid.z0, Wq, objective(Hd, W0, Wq), j_admm,
+                       objective(Hd, W0, W_rtn), objective(H, W0, Wq), a, ls, lam)

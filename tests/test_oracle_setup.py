@@ -1,0 +1,226 @@
+"""Pins for the oracle's problem set-up and ADMM loop (none of them re-types the oracle's formula)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import admmq_oracle as orc
+
+
+def tiny_problem(n=12, p=5, N=40, seed=3, bits=3, g=0):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((N, n)) * np.exp(rng.standard_normal(n))
+    W0 = rng.standard_normal((n, p)) * 0.02
+    return X, W0
+
+
+def cfg1_problem():
+    cfg = si.CONFIGS["cfg1"]
+    H = orc.hessian(si.chunk_as_f64(cfg, xc) for _, xc in si.iter_x_chunks(cfg))
+    W0 = si.layer_weights(cfg).astype(np.float64)
+    return cfg, H, W0
+
+
+def test_hessian_is_xtx_triple_loop_and_chunking():
+    X, _ = tiny_problem(n=5, N=9)
+    H = orc.hessian([X])
+    ref = np.zeros((5, 5))
+    for i in range(5):
+        for j in range(5):
+            for r in range(9):
+                ref[i, j] += X[r, i] * X[r, j]
+    assert np.allclose(H, ref, rtol=1e-13, atol=1e-13)
+    assert np.array_equal(H, H.T)
+    Hc = orc.hessian([X[:4], X[4:7], X[7:]])
+    assert np.allclose(Hc, H, rtol=1e-13)
+
+
+def test_damping_is_fraction_of_mean_diagonal():
+    X, _ = tiny_problem()
+    H = orc.hessian([X])
+    Hd, lam = orc.damp_hessian(H, 0.01)
+    assert lam == pytest.approx(0.01 * np.mean(np.sum(X * X, axis=0)))
+    assert np.allclose(Hd - H, lam * np.eye(H.shape[0]))
+
+
+def test_scaled_hessian_unit_diagonal_and_objective_invariance():
+    X, W0 = tiny_problem()
+    Hd, _ = orc.damp_hessian(orc.hessian([X]))
+    d, Hs, Ws = orc.scale_problem(Hd, W0)
+    assert np.allclose(np.diag(Hs), 1.0, rtol=0, atol=1e-14)
+    # Sigma change of variables leaves the objective unchanged (eqs. 2 and 3)
+    rng = np.random.default_rng(0)
+    Wq = W0 + 0.003 * rng.standard_normal(W0.shape)
+    j_unscaled = orc.objective(Hd, W0, Wq)
+    j_scaled = orc.objective(Hs, Ws, Wq * d[:, None])
+    assert j_scaled == pytest.approx(j_unscaled, rel=1e-12)
+    # and equals the reconstruction form of eq. 1 (damped)
+    lam = Hd[0, 0] - orc.hessian([X])[0, 0]
+    direct = np.sum((X @ (Wq - W0)) ** 2) + lam * np.sum((Wq - W0) ** 2)
+    assert j_unscaled == pytest.approx(direct, rel=1e-12)
+
+
+def test_dead_channel_raises():
+    X, W0 = tiny_problem()
+    X[:] = 0.0
+    Hd, _ = orc.damp_hessian(orc.hessian([X]))
+    with pytest.raises(ValueError):
+        orc.scale_problem(Hd, W0)
+
+
+@pytest.mark.parametrize("bits,g", [(2, 0), (3, 4), (4, 0)])
+def test_projection_is_nearest_level_brute_force(bits, g):
+    rng = np.random.default_rng(5)
+    n, p = 12, 7
+    W0 = rng.standard_normal((n, p))
+    grid = orc.Grid.fit(W0, bits, g)
+    x = W0 + 0.6 * rng.standard_normal((n, p))          # some targets fall outside the range
+    k = grid.codes(x)
+    gg = n if g == 0 else g
+    for i in range(n):
+        for j in range(p):
+            levels = grid.z0[i // gg, j] + np.arange(2 ** bits) * grid.delta[i // gg, j]
+            assert k[i, j] == int(np.argmin(np.abs(levels - x[i, j])))
+    # grid end points are the group's min and max
+    Wg = W0.reshape(n // gg, gg, p)
+    assert np.allclose(grid.z0, Wg.min(axis=1))
+    assert np.allclose(grid.z0 + (2 ** bits - 1) * grid.delta, Wg.max(axis=1))
+
+
+def test_degenerate_group_codes_zero():
+    W0 = np.full((8, 3), 0.25)
+    W0[:, 1] = np.linspace(-1, 1, 8)
+    grid = orc.Grid.fit(W0, 3, 0)
+    assert grid.degenerate.tolist() == [[True, False, True]]
+    k = grid.codes(W0 + 5.0)
+    assert np.all(k[:, 0] == 0) and np.all(k[:, 2] == 0)
+    assert np.allclose(grid.dequant(k)[:, 0], 0.25)
+
+
+def test_w_update_solves_eq7_linear_system():
+    X, W0 = tiny_problem(n=40, p=6, N=100)
+    Hd, _ = orc.damp_hessian(orc.hessian([X]))
+    d, Hs, Ws = orc.scale_problem(Hd, W0)
+    lam, U = np.linalg.eigh(Hs)
+    rng = np.random.default_rng(1)
+    D = Ws + 0.1 * rng.standard_normal(Ws.shape)
+    V = 0.05 * rng.standard_normal(Ws.shape)
+    for rho in (0.1, 3.0, 1e4):
+        W = orc.w_update(U, lam, Hs @ Ws, D, V, rho)
+        ref = np.linalg.solve(Hs + rho * np.eye(40), Hs @ Ws + rho * D - V)
+        assert np.linalg.norm(W - ref) <= 1e-11 * np.linalg.norm(ref)
+
+
+def test_first_iterate_is_dense_weights_and_rtn():
+    """D0 = Ws, V0 = 0 make the first W-update return Ws exactly, so the first projection is
+    round-to-nearest of W0 (Alg. 1 lines 4, 6, 7)."""
+    cfg, H, W0 = cfg1_problem()
+    Hd, _ = orc.damp_hessian(H)
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    res = orc.admm(Hd, W0, grid, T=1)
+    # RTN computed here, directly in the unscaled space, by brute force over the levels
+    levels = grid.z0[0][None, :, None] + np.arange(2 ** cfg.bits)[None, None, :] * grid.delta[0][None, :, None]
+    k_rtn = np.argmin(np.abs(levels - W0[:, :, None]), axis=2)
+    assert np.array_equal(res.first_codes, k_rtn)
+    assert np.array_equal(orc.rtn(W0, grid)[0], k_rtn)
+
+
+def test_key_inequality_residual_decay_and_rtn_no_worse_cfg1():
+    cfg, H, W0 = cfg1_problem()
+    Hd, _ = orc.damp_hessian(H)
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    res = orc.admm(Hd, W0, grid, T=200)
+    # App. C key inequality, every iteration whose D^(t) is on the grid (D^(0) is the dense weights)
+    for lhs, rhs in list(zip(res.key_lhs, res.key_rhs))[1:]:
+        assert lhs <= rhs * (1 + 1e-12) + 1e-30
+    # Thm. 1: rho_t * max(residuals) bounded, residual -> 0, codes freeze
+    prim = np.array(res.primal)
+    dual = np.array(res.dual)
+    rho = np.array(res.rho)
+    bound = rho * np.maximum(prim, dual)
+    quarter = len(prim) // 4
+    assert bound[quarter:].max() <= bound[:quarter].max()      # rho_t * residual stays below a constant
+    assert prim[-1] <= 1e-3 * prim[1]
+    assert np.all(dual[-20:] == 0.0)
+    live = np.nonzero(prim > 1e-9 * prim[1])[0]                 # before the float64 round-off floor
+    live = live[live >= np.argmax(bound)]
+    slope = np.polyfit(np.log(rho[live]), np.log(prim[live]), 1)[0]
+    assert slope <= -0.9
+    # reconstruction objective no worse than RTN (expected from Fig. 3 / Table 6, not a theorem)
+    j_admm = orc.objective(Hd, W0, res.Wq)
+    j_rtn = orc.objective(Hd, W0, orc.rtn(W0, grid)[1])
+    assert j_admm <= j_rtn
+    j_admm_u = orc.objective(H, W0, res.Wq)
+    assert j_admm_u <= orc.objective(H, W0, orc.rtn(W0, grid)[1])
+
+
+def test_codes_invariant_under_hessian_rescaling_and_column_separable():
+    cfg, H, W0 = cfg1_problem()
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    a = orc.admm(orc.damp_hessian(H)[0], W0, grid, T=30)
+    b = orc.admm(orc.damp_hessian(4.0 * H)[0], W0, grid, T=30)   # power of two: exact rescale
+    assert np.array_equal(a.codes, b.codes)
+    cols = slice(5, 21)
+    gs = orc.Grid.fit(W0[:, cols], cfg.bits, cfg.group_size)
+    c = orc.admm(orc.damp_hessian(H)[0], W0[:, cols], gs, T=30)
+    assert np.array_equal(c.codes, a.codes[:, cols])
+
+
+def test_diagonal_hessian_makes_rtn_optimal_and_admm_returns_it():
+    rng = np.random.default_rng(11)
+    n, p = 10, 4
+    Hd = np.diag(np.exp(rng.standard_normal(n)))
+    W0 = rng.standard_normal((n, p))
+    grid = orc.Grid.fit(W0, 2, 0)
+    res = orc.admm(Hd, W0, grid, T=40)
+    assert np.array_equal(res.codes, orc.rtn(W0, grid)[0])
+
+
+def test_fp32_mirror_agrees_with_float64_projection_away_from_midpoints():
+    cfg, H, W0 = cfg1_problem()
+    Hd, _ = orc.damp_hessian(H)
+    d, Hs, Ws = orc.scale_problem(Hd, W0)
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    rng = np.random.default_rng(2)
+    W = (Ws + 0.2 * np.abs(Ws).mean() * rng.standard_normal(Ws.shape)).astype(np.float32)
+    V = (0.01 * np.abs(Ws).mean() * rng.standard_normal(Ws.shape)).astype(np.float32)
+    rho, rho_next = 0.5, 0.55
+    k32, Vn, Bn, ss = orc.project_dual_step_f32(W, V, rho, rho_next, d, grid.delta, grid.z0,
+                                                grid.degenerate, cfg.bits)
+    k64, Dn, Wt = orc.d_update(W.astype(np.float64), V.astype(np.float64), rho, d, grid)
+    t = (Wt / d[:, None] - grid.z0) / grid.delta
+    near_mid = np.abs(t - np.floor(t) - 0.5) < 1e-4
+    assert np.all((k32 == k64) | near_mid)
+    assert np.mean(k32 != k64) < 1e-3
+    ok = k32 == k64
+    Vref = V.astype(np.float64) + rho * (W.astype(np.float64) - Dn)
+    wmax = float(np.abs(W).max())
+    assert np.allclose(Vn[ok], Vref[ok], rtol=1e-5, atol=2e-6 * wmax)
+    Bref = Dn - Vref / rho_next
+    assert np.allclose(Bn[ok], Bref[ok], rtol=1e-4, atol=4e-6 * wmax)
+    assert ss == pytest.approx(float(np.sum((W.astype(np.float64) - Dn)[ok] ** 2)) +
+                               float(np.sum((W.astype(np.float64) - d[:, None] * grid.dequant(k32.astype(np.int64)))[~ok] ** 2)),
+                               rel=1e-5)
+
+
+def test_splitmix_matches_published_vectors_and_pairs_are_valid():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "splitmix64_vectors.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        tok = line.split()
+        seed = int(tok[0], 0)
+        s = seed
+        for want in tok[1:]:
+            assert orc._mix64(s) == int(want, 0)
+            s = (s + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+    seen = set()
+    for n in (2, 3, 7, 128):
+        for slot in range(200):
+            i1, i2 = orc.sample_pair(9, 1, 4, slot, n)
+            assert 0 <= i1 < n and 0 <= i2 < n and i1 != i2
+            seen.add((n, i1, i2))
+    assert orc.sample_pair(9, 1, 4, 3, 128) == orc.sample_pair(9, 1, 4, 3, 128)
+    assert len({orc.sample_pair(9, r, b, 0, 4096) for r in range(3) for b in range(50)}) > 140
