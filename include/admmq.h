@@ -1,0 +1,173 @@
+/*
+ * admmq.h - C ABI of the MI355X (gfx950) ADMM-Q layer solver.
+ *
+ * One linear layer Y = X W with X [N][n] calibration activations and dense weights W0 [n][p]
+ * (n input channels, p output channels; paper Sec. 3.1).  The library accumulates the Hessian
+ * H = X^T X, runs the diagonally scaled ADMM loop of Alg. 1 (eqs. 7-10) under the geometric
+ * penalty schedule rho_t = rho0 * gamma^t (Sec. 3.6), and refines the result with the pair-swap
+ * local search of Sec. 3.5.  Results are integer codes with per-group scales and real-valued
+ * zero offsets:  Wq[i][j] = zeros[i/g][j] + codes[i][j] * scales[i/g][j].
+ *
+ * Conventions
+ *   - Every array argument marked "device" is a pointer to GPU memory owned by the caller, on the
+ *     context's device; "host" marks ordinary host memory.  All matrices are row-major.
+ *   - The library never hands out memory of its own.  Scratch comes from an arena the context grows
+ *     with hipMalloc on demand, or from caller memory given to admmq_set_workspace.
+ *   - Work is enqueued on the context's stream; calls that return host values (stats, objectives)
+ *     synchronise that stream before returning, the others return after enqueueing.
+ *   - Errors are return codes only.  Arguments are validated on the host before any device work,
+ *     so a failed validation leaves all outputs untouched and needs no GPU.
+ *   - One context may be used by one host thread at a time.
+ */
+#ifndef ADMMQ_H
+#define ADMMQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct admmq_ctx admmq_ctx;
+
+typedef enum {
+    ADMMQ_OK = 0,
+    ADMMQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    ADMMQ_ERR_SHAPE = 2,       /* n, p, rows, leading dimension or group size do not fit */
+    ADMMQ_ERR_PARAM = 3,       /* bits, T, rho0, gamma, damp ... out of range */
+    ADMMQ_ERR_NOT_FINITE = 4,  /* H or W0 holds a NaN or an infinity */
+    ADMMQ_ERR_ZERO_DIAG = 5,   /* a diagonal entry of the damped Hessian is <= 0 (dead channel) */
+    ADMMQ_ERR_WORKSPACE = 6,   /* caller workspace too small / allocation failed */
+    ADMMQ_ERR_STATE = 7,       /* step call without the factorisation it needs */
+    ADMMQ_ERR_DEVICE = 8       /* a HIP call failed */
+} admmq_status;
+
+typedef enum { ADMMQ_F32 = 0, ADMMQ_BF16 = 1 } admmq_dtype;
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on `device`.  `hip_stream` is a borrowed hipStream_t (NULL = the default
+ * stream); the caller keeps it alive for the context's lifetime.  device = -1 gives a context
+ * without a GPU: every call still validates its arguments and then returns ADMMQ_ERR_DEVICE. */
+admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stream);
+void admmq_destroy(admmq_ctx *ctx);
+const char *admmq_status_string(admmq_status s);
+
+/* Bytes of scratch admmq_quantize_layer needs for an n x p layer (pure host function). */
+size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T);
+/* Optional: use caller memory (device, 256-byte aligned) as the scratch arena from now on. */
+admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/* ---- Hessian accumulation (Sec. 3.1: H = X^T X) ------------------------------------------- */
+
+/* H [n][n] (device fp32, caller zero-initialises before the first chunk) += X^T X for a chunk
+ * X [rows][ldx] (device; fp32 or bf16 bit patterns), ldx >= n.  Both triangles of H are kept
+ * up to date.  *n_samples (host, may be NULL) += rows.  bf16 inputs are widened to fp32 on the way
+ * into the fp32 matrix-core contraction, so every product is exact. */
+admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const void *X,
+                                      admmq_dtype xdt, int64_t rows, int64_t ldx, uint64_t *n_samples);
+
+/* ---- whole layer (Alg. 1) ----------------------------------------------------------------- */
+
+typedef struct {
+    int32_t T;             /* ADMM iterations, run exactly (paper: 300)                      */
+    double rho0;           /* initial penalty (paper: 0.1)                                   */
+    double gamma;          /* growth factor > 1, or exactly 1 for a fixed penalty (paper: 1.1) */
+    double damp;           /* lambda = damp * Tr(H)/n added to the diagonal (paper App. D: 0.01) */
+    int32_t precondition;  /* 1 = diagonal scaling Sigma = Diag(H')^{-1/2} (Sec. 3.2); 0 = Sigma = I */
+    int32_t ls_rounds;     /* local-search rounds, 0 = none (paper: at most 5)                */
+    int32_t ls_batches;    /* batches per round, 0 = ceil(n/2)                                */
+    int32_t ls_pairs;      /* row pairs per batch, 0 = 64                                     */
+    uint64_t seed;         /* seed of the pair sampler                                        */
+} admmq_schedule;
+
+typedef struct {            /* host struct, filled when the pointer is not NULL */
+    float ms_total, ms_setup, ms_factor, ms_admm, ms_local_search;
+    double j_damp;          /* Tr(E^T H' E), E = Wq - W0, after ADMM + local search (eq. 2 x 2) */
+    double j_damp_admm;     /* same, before local search */
+    double j_damp_rtn;      /* same, for round-to-nearest on the same grid */
+    double lambda;          /* the damping added to the diagonal */
+    int32_t iters_done;
+    int32_t ls_moves;       /* applied row pairs */
+    float *primal_res;      /* optional host array [T]: ||W - D||_F per iteration, or NULL */
+    int64_t *code_flips;    /* optional host array [T]: codes changed per iteration, or NULL */
+} admmq_stats;
+
+/* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.
+ * bits in [2,8].  group_size = 0 means one grid per output column, otherwise it must divide n and
+ * a group is group_size consecutive input channels inside one column.
+ * Outputs (device): codes u8 [n][p]; scales, zeros fp32 [n/g][p].  The grid is the min/max grid
+ * of W0 (Sec. 3.4, no clipping) with zeros = group minimum (the real offset z0 of eq. 10). */
+admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, const float *W0, int64_t n,
+                                  int64_t p, int64_t ldw, int32_t bits, int32_t group_size,
+                                  const admmq_schedule *sched, uint8_t *codes, float *scales,
+                                  float *zeros, admmq_stats *stats);
+
+/* ---- local search alone (Sec. 3.5, eq. 11) ------------------------------------------------ */
+
+typedef struct {
+    int32_t rounds, batches_per_round, pairs_per_batch;   /* 0 = defaults 5, ceil(n/2), 64 */
+    double damp;
+    uint64_t seed;
+} admmq_ls_params;
+
+/* Refines `codes` in place on the fixed grid (scales, zeros) against the damped Hessian
+ * H' = H + damp*Tr(H)/n I.  Usable on any codes (ADMM output or round-to-nearest).
+ * explicit_pairs (host int32 [rounds*batches*pairs][2], may be NULL) replaces the sampler.
+ * moves_out / drop_out (host, may be NULL): applied pairs and the summed objective decrease. */
+admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                int64_t ldw, int32_t bits, int32_t group_size, const float *scales,
+                                const float *zeros, uint8_t *codes, const admmq_ls_params *prm,
+                                const int32_t *explicit_pairs, int32_t *moves_out, double *drop_out);
+
+/* The pair sampler of the local search, on the host: SplitMix64 (Steele, Lea, Flood 2014) keyed by
+ * (seed, round, batch, slot); writes i1 != i2 in [0, n). */
+void admmq_sample_pair(uint64_t seed, int32_t round, int32_t batch, int32_t slot, int64_t n,
+                       int32_t *i1, int32_t *i2);
+
+/* ---- single steps, exposed so that each can be checked on identical inputs ---------------- */
+
+/* Grid fit (Sec. 3.4): per column and group, scales = (max-min)/(2^bits-1), zeros = min.
+ * A group with max == min gets scale 0 by that formula: all its codes stay 0. */
+admmq_status admmq_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                             int32_t bits, int32_t group_size, float *scales, float *zeros);
+
+/* Alg. 1 lines 1-3: damp, scale and factorise H once; the result stays in the context and serves
+ * every rho.  d_out (device fp32 [n], may be NULL) receives d_i = sqrt(H'_ii) = 1/Sigma_ii.
+ * The factorisation is Hs = Q T Q^T with T tridiagonal (Householder, fp64): (Hs + rho I)^{-1} =
+ * Q (T + rho I)^{-1} Q^T for any rho, which plays the part of the eigendecomposition of Sec. 3.3. */
+admmq_status admmq_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp,
+                             int32_t precondition, float *d_out, double *lambda_out);
+
+/* Eq. 7 with the kept factorisation: W = (Hs + rho I)^{-1}(Hs Ws + rho D - V).
+ * Ws, D, V, W_out: device fp32 [n][p] contiguous, in the scaled space. */
+admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const float *D, const float *V,
+                            int64_t n, int64_t p, double rho, float *W_out);
+
+/* Eqs. 8-10 and 9 fused, one streaming pass: target W + V/rho, project Sigma(.) on the grid,
+ * D = Sigma^{-1}(z0 + k*delta), V += rho (W - D), B_out = D - V_new / rho_next.
+ * V is updated in place.  codes (u8, may be NULL) receives k.  res_sq (host, may be NULL) gets
+ * ||W - D||_F^2.  d: device fp32 [n]. */
+admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                const float *d, int32_t bits, int32_t group_size, const float *scales,
+                                const float *zeros, double rho, double rho_next, uint8_t *codes,
+                                float *B_out, double *res_sq);
+
+/* Tr(E^T (H + lambda I) E) with E = dequant(codes) - W0, lambda = damp * Tr(H)/n (eq. 2 x 2). */
+admmq_status admmq_objective(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                             int64_t ldw, int32_t group_size, const float *scales, const float *zeros,
+                             const uint8_t *codes, double damp, double *j_out);
+
+/* One batch of eq. 11: for `npairs` row pairs (device int32 [npairs][2]) the summed gain over the
+ * columns, each column taking its best feasible sign combination if that lowers the loss.
+ * G: device fp32 [n][p] = H'(W0 - Wq).  totals: device fp32 [npairs]. */
+admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double lambda, const float *G,
+                               const uint8_t *codes, int64_t n, int64_t p, int32_t bits,
+                               int32_t group_size, const float *scales, const int32_t *pairs,
+                               int32_t npairs, float *totals);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADMMQ_H */

@@ -74,8 +74,8 @@ def grid_init(W0: np.ndarray, bits: int, group_size: int = 0):
 
     Reading: a group is ``group_size`` consecutive INPUT channels (rows) inside one output column;
     group_size = 0 means one grid per output column.  delta = (max-min)/(2^b-1), z0 = min (the
-    real-valued offset of eq. 10).  A group with max == min gets delta = 1 and is marked degenerate:
-    all its codes stay 0.  Returns delta, z0 with shape [n/g][p].
+    real-valued offset of eq. 10).  A group with max == min gets delta = 0 by that formula; it is
+    degenerate: all its codes stay 0 and it dequantizes to z0.  Returns delta, z0 with shape [n/g][p].
     """
     W0 = np.asarray(W0, dtype=np.float64)
     n, p = W0.shape
@@ -86,7 +86,6 @@ def grid_init(W0: np.ndarray, bits: int, group_size: int = 0):
     mn = Wg.min(axis=1)
     mx = Wg.max(axis=1)
     delta = (mx - mn) / float(2 ** bits - 1)
-    delta = np.where(mx > mn, delta, 1.0)
     return delta, mn
 
 
@@ -113,13 +112,14 @@ class Grid:
         n, p = W0.shape
         g = n if group_size in (0, None) else int(group_size)
         delta, z0 = grid_init(W0, bits, group_size)
-        mx = W0.reshape(n // g, g, p).max(axis=1)
-        return Grid(delta, z0, bits, mx <= z0)
+        return Grid(delta, z0, bits, delta == 0.0)
 
     def codes(self, x: np.ndarray) -> np.ndarray:
         n = x.shape[0]
-        k = np.clip(np.rint((x - _expand(self.z0, n)) / _expand(self.delta, n)), 0, 2 ** self.bits - 1)
-        k = np.where(_expand(self.degenerate, n), 0.0, k)
+        dead = _expand(self.degenerate, n)
+        step = np.where(dead, 1.0, _expand(self.delta, n))
+        k = np.clip(np.rint((x - _expand(self.z0, n)) / step), 0, 2 ** self.bits - 1)
+        k = np.where(dead, 0.0, k)
         return k.astype(np.int64)
 
     def dequant(self, k: np.ndarray) -> np.ndarray:
@@ -226,7 +226,8 @@ def project_dual_step_f32(W, V, rho, rho_next, d, delta, z0, degenerate, bits):
     d = np.asarray(d, dtype=f)
     inv_d = (f(1.0) / d)[:, None]
     dl = np.asarray(delta, dtype=f)
-    inv_dl = np.where(np.asarray(degenerate), f(0.0), f(1.0) / dl).astype(f)
+    with np.errstate(divide="ignore"):
+        inv_dl = np.where(dl == f(0.0), f(0.0), f(1.0) / dl).astype(f)
     dl_e = _expand(dl, n)
     inv_dl_e = _expand(inv_dl, n)
     z_e = _expand(np.asarray(z0, dtype=f), n)

@@ -1,0 +1,277 @@
+"""ctypes binding with the same names as include/admmq.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTED_SYMBOLS = [
+    "admmq_create", "admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_set_workspace",
+    "admmq_accumulate_hessian", "admmq_quantize_layer", "admmq_local_search", "admmq_sample_pair",
+    "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
+    "admmq_ls_evaluate",
+]
+
+ADMMQ_F32, ADMMQ_BF16 = 0, 1
+
+
+class AdmmqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"admmq: {what} (status {code})")
+        self.code = code
+
+
+class _Schedule(C.Structure):
+    _fields_ = [("T", C.c_int32), ("rho0", C.c_double), ("gamma", C.c_double), ("damp", C.c_double),
+                ("precondition", C.c_int32), ("ls_rounds", C.c_int32), ("ls_batches", C.c_int32),
+                ("ls_pairs", C.c_int32), ("seed", C.c_uint64)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("ms_total", C.c_float), ("ms_setup", C.c_float), ("ms_factor", C.c_float),
+                ("ms_admm", C.c_float), ("ms_local_search", C.c_float),
+                ("j_damp", C.c_double), ("j_damp_admm", C.c_double), ("j_damp_rtn", C.c_double),
+                ("lambda_", C.c_double), ("iters_done", C.c_int32), ("ls_moves", C.c_int32),
+                ("primal_res", C.POINTER(C.c_float)), ("code_flips", C.POINTER(C.c_int64))]
+
+
+class _LsParams(C.Structure):
+    _fields_ = [("rounds", C.c_int32), ("batches_per_round", C.c_int32), ("pairs_per_batch", C.c_int32),
+                ("damp", C.c_double), ("seed", C.c_uint64)]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libadmmq.so")
+
+
+def load_library():
+    """Loads libadmmq.so (built in-tree by paper_2605_11222_amd/csrc/build.sh).  No fallback."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise AdmmqError(-1, f"{path} is missing: run paper_2605_11222_amd/csrc/build.sh (there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int32, C.c_double
+    lib.admmq_create.argtypes = [C.POINTER(vp), C.c_int, vp]
+    lib.admmq_destroy.argtypes = [vp]
+    lib.admmq_destroy.restype = None
+    lib.admmq_status_string.argtypes = [C.c_int]
+    lib.admmq_status_string.restype = C.c_char_p
+    lib.admmq_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.admmq_workspace_bytes.restype = C.c_size_t
+    lib.admmq_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    lib.admmq_accumulate_hessian.argtypes = [vp, vp, i64, vp, C.c_int, i64, i64, C.POINTER(C.c_uint64)]
+    lib.admmq_quantize_layer.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, C.POINTER(_Schedule), vp, vp, vp,
+                                         C.POINTER(_Stats)]
+    lib.admmq_local_search.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, C.POINTER(_LsParams),
+                                       C.POINTER(i32), C.POINTER(i32), C.POINTER(dbl)]
+    lib.admmq_sample_pair.argtypes = [C.c_uint64, i32, i32, i32, i64, C.POINTER(i32), C.POINTER(i32)]
+    lib.admmq_sample_pair.restype = None
+    lib.admmq_grid_init.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp]
+    lib.admmq_factorize.argtypes = [vp, vp, i64, dbl, i32, vp, C.POINTER(dbl)]
+    lib.admmq_w_update.argtypes = [vp, vp, vp, vp, i64, i64, dbl, vp]
+    lib.admmq_project_dual.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp,
+                                       C.POINTER(dbl)]
+    lib.admmq_objective.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, dbl, C.POINTER(dbl)]
+    lib.admmq_ls_evaluate.argtypes = [vp, vp, dbl, vp, vp, i64, i64, i32, i32, vp, vp, i32, vp]
+    for name in EXPORTED_SYMBOLS:
+        fn = getattr(lib, name)
+        if name not in ("admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_sample_pair"):
+            fn.restype = C.c_int
+    _LIB = lib
+    return lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise AdmmqError(code, load_library().admmq_status_string(code).decode())
+
+
+def workspace_bytes(n: int, p: int, T: int) -> int:
+    return int(load_library().admmq_workspace_bytes(n, p, T))
+
+
+def sample_pair(seed: int, rnd: int, batch: int, slot: int, n: int):
+    a, b = C.c_int32(), C.c_int32()
+    load_library().admmq_sample_pair(seed, rnd, batch, slot, n, C.byref(a), C.byref(b))
+    return a.value, b.value
+
+
+@dataclass
+class Schedule:
+    T: int = 300
+    rho0: float = 0.1
+    gamma: float = 1.1
+    damp: float = 0.01
+    precondition: bool = True
+    ls_rounds: int = 5
+    ls_batches: int = 0
+    ls_pairs: int = 0
+    seed: int = 0
+
+
+@dataclass
+class LayerStats:
+    ms_total: float = 0.0
+    ms_setup: float = 0.0
+    ms_factor: float = 0.0
+    ms_admm: float = 0.0
+    ms_local_search: float = 0.0
+    j_damp: float = 0.0
+    j_damp_admm: float = 0.0
+    j_damp_rtn: float = 0.0
+    lam: float = 0.0
+    iters_done: int = 0
+    ls_moves: int = 0
+    primal_res: list = field(default_factory=list)
+    code_flips: list = field(default_factory=list)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+class Context:
+    """admmq_ctx bound to a torch device and to torch's current stream on it."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        self._lib = load_library()
+        self._torch = torch
+        self.device = int(device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        self.stream = stream
+        h = C.c_void_p()
+        _check(self._lib.admmq_create(C.byref(h), self.device, C.c_void_p(stream.cuda_stream)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.admmq_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    # -- entry points (names follow include/admmq.h without the prefix) ------------------------
+    def set_workspace(self, buf):
+        _check(self._lib.admmq_set_workspace(self._h, _ptr(buf), buf.numel() * buf.element_size()))
+        self._ws = buf
+
+    def accumulate_hessian(self, H, X):
+        """H fp32 [n][n] += X^T X for a chunk X [rows][n] (float32 or bfloat16 tensor)."""
+        torch = self._torch
+        n = H.shape[0]
+        dt = ADMMQ_BF16 if X.dtype == torch.bfloat16 else ADMMQ_F32
+        cnt = C.c_uint64(0)
+        _check(self._lib.admmq_accumulate_hessian(self._h, _ptr(H), n, _ptr(X), dt, X.shape[0], X.stride(0),
+                                                  C.byref(cnt)))
+        return cnt.value
+
+    def quantize_layer(self, H, W0, bits, group_size=0, sched: Schedule | None = None, want_stats=True,
+                       want_history=False):
+        torch = self._torch
+        sched = sched or Schedule()
+        n, p = W0.shape
+        g = group_size if group_size else n
+        codes = torch.empty((n, p), dtype=torch.uint8, device=W0.device)
+        scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
+                       sched.ls_batches, sched.ls_pairs, sched.seed)
+        st = _Stats()
+        res = (C.c_float * sched.T)() if want_history else None
+        flips = (C.c_int64 * sched.T)() if want_history else None
+        if want_history:
+            st.primal_res = C.cast(res, C.POINTER(C.c_float))
+            st.code_flips = C.cast(flips, C.POINTER(C.c_int64))
+        _check(self._lib.admmq_quantize_layer(self._h, _ptr(H), _ptr(W0), n, p, W0.stride(0), bits, group_size,
+                                              C.byref(cs), _ptr(codes), _ptr(scales), _ptr(zeros),
+                                              C.byref(st) if want_stats else None))
+        out = None
+        if want_stats:
+            out = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
+                             st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
+                             list(res) if want_history else [], list(flips) if want_history else [])
+        return codes, scales, zeros, out
+
+    def local_search(self, H, W0, bits, group_size, scales, zeros, codes, rounds=5, batches_per_round=0,
+                     pairs_per_batch=0, damp=0.01, seed=0, explicit_pairs=None):
+        n, p = W0.shape
+        prm = _LsParams(rounds, batches_per_round, pairs_per_batch, damp, seed)
+        moves, drop = C.c_int32(0), C.c_double(0.0)
+        ep = None
+        if explicit_pairs is not None:
+            flat = [int(v) for pr in explicit_pairs for v in pr]
+            ep = (C.c_int32 * len(flat))(*flat)
+        _check(self._lib.admmq_local_search(self._h, _ptr(H), _ptr(W0), n, p, W0.stride(0), bits, group_size,
+                                            _ptr(scales), _ptr(zeros), _ptr(codes), C.byref(prm), ep,
+                                            C.byref(moves), C.byref(drop)))
+        return moves.value, drop.value
+
+    def grid_init(self, W0, bits, group_size=0):
+        torch = self._torch
+        n, p = W0.shape
+        g = group_size if group_size else n
+        scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        _check(self._lib.admmq_grid_init(self._h, _ptr(W0), n, p, W0.stride(0), bits, group_size, _ptr(scales),
+                                         _ptr(zeros)))
+        return scales, zeros
+
+    def factorize(self, H, damp=0.01, precondition=True):
+        torch = self._torch
+        n = H.shape[0]
+        d = torch.empty((n,), dtype=torch.float32, device=H.device)
+        lam = C.c_double(0.0)
+        _check(self._lib.admmq_factorize(self._h, _ptr(H), n, damp, int(precondition), _ptr(d), C.byref(lam)))
+        return d, lam.value
+
+    def w_update(self, Ws, D, V, rho):
+        torch = self._torch
+        n, p = Ws.shape
+        W = torch.empty_like(Ws)
+        _check(self._lib.admmq_w_update(self._h, _ptr(Ws), _ptr(D), _ptr(V), n, p, float(rho), _ptr(W)))
+        return W
+
+    def project_dual(self, W, V, d, bits, group_size, scales, zeros, rho, rho_next, want_codes=True):
+        """V is updated in place; returns codes, B, ||W-D||_F^2."""
+        torch = self._torch
+        n, p = W.shape
+        codes = torch.empty((n, p), dtype=torch.uint8, device=W.device) if want_codes else None
+        B = torch.empty_like(W)
+        rs = C.c_double(0.0)
+        _check(self._lib.admmq_project_dual(self._h, _ptr(W), _ptr(V), n, p, _ptr(d), bits, group_size,
+                                            _ptr(scales), _ptr(zeros), float(rho), float(rho_next), _ptr(codes),
+                                            _ptr(B), C.byref(rs)))
+        return codes, B, rs.value
+
+    def objective(self, H, W0, group_size, scales, zeros, codes, damp=0.01):
+        n, p = W0.shape
+        j = C.c_double(0.0)
+        _check(self._lib.admmq_objective(self._h, _ptr(H), _ptr(W0), n, p, W0.stride(0), group_size, _ptr(scales),
+                                         _ptr(zeros), _ptr(codes), damp, C.byref(j)))
+        return j.value
+
+    def ls_evaluate(self, H, lam, G, codes, bits, group_size, scales, pairs):
+        torch = self._torch
+        n, p = G.shape
+        totals = torch.empty((pairs.shape[0],), dtype=torch.float32, device=G.device)
+        _check(self._lib.admmq_ls_evaluate(self._h, _ptr(H), float(lam), _ptr(G), _ptr(codes), n, p, bits,
+                                           group_size, _ptr(scales), _ptr(pairs), pairs.shape[0], _ptr(totals)))
+        return totals

@@ -1,0 +1,752 @@
+// C ABI of the ADMM-Q library: argument validation, scratch arena, and the orchestration of Alg. 1.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+// ---- declarations of launchers defined in the other translation units -----------------------
+admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double lambda, int precondition, float *d,
+                             float *inv_d, double *dev_flags);
+admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double lambda, const float *d,
+                               double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
+                               double *tb);
+int admmq_ls_chunks(int64_t p);
+admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
+                              int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs,
+                              int npairs, float *partial, float *totals_or_null, int32_t *choice, float *dstep,
+                              int *dev_moves, double *dev_drop, int apply);
+admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
+
+// ---- arena -------------------------------------------------------------------------------------
+admmq_status admmq_arena_reserve(admmq_ctx *ctx, size_t bytes) {
+    const size_t need = ctx->persist_top + admmq_align_up(bytes) + 4096;
+    if (need <= ctx->arena_bytes) return ADMMQ_OK;
+    if (!ctx->arena_owned) return ADMMQ_ERR_WORKSPACE;
+    char *fresh = nullptr;
+    if (hipMalloc((void **)&fresh, need) != hipSuccess) {
+        (void)hipGetLastError();
+        return ADMMQ_ERR_WORKSPACE;
+    }
+    if (ctx->arena) {
+        if (ctx->persist_top > 0) {
+            ADMMQ_HIP(hipMemcpyAsync(fresh, ctx->arena, ctx->persist_top, hipMemcpyDeviceToDevice, ctx->stream));
+            // persistent pointers move with the arena
+            const ptrdiff_t shift = fresh - ctx->arena;
+            admmq_factor &f = ctx->fac;
+            auto mvf = [shift](float *&ptr) { if (ptr) ptr = (float *)((char *)ptr + shift); };
+            auto mvd = [shift](double *&ptr) { if (ptr) ptr = (double *)((char *)ptr + shift); };
+            mvf(f.d); mvf(f.inv_d); mvf(f.Q); mvf(f.Qt); mvd(f.ta); mvd(f.tb);
+        }
+        ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+        ADMMQ_HIP(hipFree(ctx->arena));
+    }
+    ctx->arena = fresh;
+    ctx->arena_bytes = need;
+    return ADMMQ_OK;
+}
+
+void *admmq_arena_alloc(admmq_ctx *ctx, size_t bytes) {
+    const size_t off = admmq_align_up(ctx->top);
+    if (off + bytes > ctx->arena_bytes) return nullptr;
+    ctx->top = off + bytes;
+    return ctx->arena + off;
+}
+
+namespace {
+
+template <typename T>
+admmq_status take(admmq_ctx *ctx, T *&ptr, size_t count) {
+    ptr = (T *)admmq_arena_alloc(ctx, count * sizeof(T));
+    return ptr ? ADMMQ_OK : ADMMQ_ERR_WORKSPACE;
+}
+
+size_t factor_persist_bytes(int64_t n) {
+    const size_t N = (size_t)n;
+    return 2 * admmq_align_up(N * 4) + 2 * admmq_align_up(N * N * 4) + 2 * admmq_align_up(N * 8) + 4096;
+}
+size_t factor_transient_bytes(int64_t n) {
+    const size_t N = (size_t)n;
+    return 2 * admmq_align_up(N * N * 8) + admmq_align_up(8 * N * 8) + 4096;
+}
+size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
+    const size_t np = (size_t)n * (size_t)p;
+    return 6 * admmq_align_up(np * 4) + admmq_align_up(np * 8) + 2 * admmq_align_up((size_t)T * n * 8) +
+           4 * admmq_align_up((size_t)T * 8) + 65536;
+}
+size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
+    const size_t np = (size_t)n * (size_t)p;
+    return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
+           admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) + admmq_align_up((size_t)2 * p * 4) +
+           admmq_align_up((size_t)pairs_per_batch * 4) + 65536;
+}
+
+admmq_status read_back(admmq_ctx *ctx, void *host, const void *dev, size_t bytes) {
+    ADMMQ_HIP(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    return ADMMQ_OK;
+}
+
+inline uint64_t mix64(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    uint64_t z = x;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+admmq_status check_layer_args(const void *H, const void *W0, int64_t n, int64_t p, int64_t ldw, int32_t bits,
+                              int32_t group_size) {
+    if (!H || !W0) return ADMMQ_ERR_NULL;
+    if (n < 1 || p < 1 || ldw < p || n > (1 << 20) || p > (1 << 24)) return ADMMQ_ERR_SHAPE;
+    if (group_size < 0 || (group_size > 0 && n % group_size != 0)) return ADMMQ_ERR_SHAPE;
+    if (bits < 2 || bits > 8) return ADMMQ_ERR_PARAM;
+    return ADMMQ_OK;
+}
+
+struct Timer {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipStream_t st;
+    bool on;
+    Timer(hipStream_t s, bool enable) : st(s), on(enable) {
+        if (on) {
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) on = false;
+        }
+    }
+    ~Timer() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+    void start() { if (on) (void)hipEventRecord(a, st); }
+    float stop() {
+        if (!on) return 0.f;
+        (void)hipEventRecord(b, st);
+        (void)hipEventSynchronize(b);
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, a, b);
+        return ms;
+    }
+};
+
+// trace, finiteness and lambda of a raw Hessian (synchronises)
+admmq_status hessian_scalars(admmq_ctx *ctx, const float *H, int64_t n, double damp, double *lambda) {
+    double *dev = nullptr;
+    ADMMQ_TRY(take(ctx, dev, 4));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 32));
+    ADMMQ_TRY(admmq_k_matrix_check(ctx, H, n, dev));
+    double host[4];
+    ADMMQ_TRY(read_back(ctx, host, dev, 32));
+    if (host[1] > 0.0 || !isfinite(host[0])) return ADMMQ_ERR_NOT_FINITE;
+    *lambda = damp * host[0] / (double)n;
+    return ADMMQ_OK;
+}
+
+// Alg. 1 lines 1-3 into the persistent region; leaves the transient region reset.
+admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp, int precondition,
+                          double *lambda_out) {
+    ctx->fac.valid = false;
+    ctx->persist_top = 0;
+    ctx->top = 0;
+    ADMMQ_TRY(admmq_arena_reserve(ctx, factor_persist_bytes(n) + factor_transient_bytes(n)));
+    admmq_factor &f = ctx->fac;
+    f = admmq_factor();
+    ADMMQ_TRY(take(ctx, f.d, (size_t)n));
+    ADMMQ_TRY(take(ctx, f.inv_d, (size_t)n));
+    ADMMQ_TRY(take(ctx, f.Q, (size_t)n * n));
+    ADMMQ_TRY(take(ctx, f.Qt, (size_t)n * n));
+    ADMMQ_TRY(take(ctx, f.ta, (size_t)n));
+    ADMMQ_TRY(take(ctx, f.tb, (size_t)n));
+    ctx->persist_top = admmq_align_up(ctx->top);
+    ctx->top = ctx->persist_top;
+
+    double lambda = 0.0;
+    ADMMQ_TRY(hessian_scalars(ctx, H, n, damp, &lambda));
+    double *flags = nullptr;
+    ADMMQ_TRY(take(ctx, flags, 4));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, flags, 0, 32));
+    ADMMQ_TRY(admmq_k_scaling(ctx, H, n, lambda, precondition, f.d, f.inv_d, flags));
+    double hflag[4];
+    ADMMQ_TRY(read_back(ctx, hflag, flags, 32));
+    if (hflag[0] > 0.0) {
+        ctx->persist_top = 0;
+        ctx->top = 0;
+        return ADMMQ_ERR_ZERO_DIAG;
+    }
+    double *A64 = nullptr, *R64 = nullptr, *vecs = nullptr;
+    ADMMQ_TRY(take(ctx, A64, (size_t)n * n));
+    ADMMQ_TRY(take(ctx, R64, (size_t)n * n));
+    ADMMQ_TRY(take(ctx, vecs, (size_t)8 * n));
+    ADMMQ_TRY(admmq_k_factorize(ctx, H, n, lambda, f.d, A64, R64, vecs, f.Q, f.Qt, f.ta, f.tb));
+    f.n = n;
+    f.lambda = lambda;
+    f.valid = true;
+    if (lambda_out) *lambda_out = lambda;
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+// W = B + Q (T + rho I)^{-1} T (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho)
+admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const double *dinv,
+                           const double *lfac, float *Y, double *F, float *W) {
+    const admmq_factor &f = ctx->fac;
+    gemm_tn_args g1 = {};
+    g1.A = f.Q; g1.lda = n; g1.B = B; g1.ldb = p; g1.M = n; g1.N = p; g1.K = n;
+    g1.alpha = -1.f; g1.beta = 1.f; g1.Z = C0; g1.ldz = p; g1.out = Y; g1.ldo = p; g1.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g1));
+    ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, F, Y));
+    gemm_tn_args g2 = {};
+    g2.A = f.Qt; g2.lda = n; g2.B = Y; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
+    g2.alpha = 1.f; g2.beta = 1.f; g2.Z = B; g2.ldz = p; g2.out = W; g2.ldo = p; g2.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g2));
+    return ADMMQ_OK;
+}
+
+// J = sum E .* (H E + lambda E); E and tmp are n x p scratch; the scalar lands in dev_out[0]
+admmq_status objective_core(admmq_ctx *ctx, const float *H, double lambda, int64_t n, int64_t p, const float *E,
+                            float *tmp, double *dev_out) {
+    gemm_tn_args g = {};
+    g.A = H; g.lda = n; g.B = E; g.ldb = p; g.M = n; g.N = p; g.K = n;
+    g.alpha = 1.f; g.beta = (float)lambda; g.Z = E; g.ldz = p; g.out = tmp; g.ldo = p; g.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_out, 0, 8));
+    ADMMQ_TRY(admmq_k_dot(ctx, E, tmp, n * p, dev_out));
+    return ADMMQ_OK;
+}
+
+struct LsPlan {
+    int rounds, batches, pairs;
+};
+
+LsPlan ls_plan(int64_t n, int rounds, int batches, int pairs) {
+    LsPlan q;
+    q.rounds = rounds;
+    q.batches = batches > 0 ? batches : (int)((n + 1) / 2);
+    q.pairs = pairs > 0 ? pairs : 64;
+    return q;
+}
+
+// the search itself; arena must already be reserved for ls_transient_bytes
+admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, const float *W0, int64_t n, int64_t p,
+                               int64_t ldw, int bits, int64_t g, const float *scales, const float *zeros,
+                               uint8_t *codes, LsPlan plan, uint64_t seed, const int32_t *explicit_pairs,
+                               int32_t *moves_out, double *drop_out) {
+    if (moves_out) *moves_out = 0;
+    if (drop_out) *drop_out = 0.0;
+    if (plan.rounds <= 0 || n < 2) return ADMMQ_OK;
+    const size_t total = (size_t)plan.rounds * plan.batches * plan.pairs;
+    float *E = nullptr, *G = nullptr, *partial = nullptr, *dstep = nullptr;
+    int32_t *pairs = nullptr, *choice = nullptr;
+    double *scal = nullptr;
+    ADMMQ_TRY(take(ctx, E, (size_t)n * p));
+    ADMMQ_TRY(take(ctx, G, (size_t)n * p));
+    ADMMQ_TRY(take(ctx, pairs, total * 2));
+    ADMMQ_TRY(take(ctx, partial, (size_t)plan.pairs * admmq_ls_chunks(p)));
+    ADMMQ_TRY(take(ctx, dstep, (size_t)2 * p));
+    ADMMQ_TRY(take(ctx, choice, 4));
+    ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double), scal[1] reinterpreted: moves (int)
+    int *dev_moves = (int *)(scal + 1);
+
+    std::vector<int32_t> hp;
+    const int32_t *src = explicit_pairs;
+    if (!src) {
+        hp.resize(total * 2);
+        size_t q = 0;
+        for (int r = 0; r < plan.rounds; ++r)
+            for (int m = 0; m < plan.batches; ++m)
+                for (int s = 0; s < plan.pairs; ++s, ++q) admmq_sample_pair(seed, r, m, s, n, &hp[2 * q], &hp[2 * q + 1]);
+        src = hp.data();
+    } else {
+        for (size_t q = 0; q < total; ++q) {
+            const int32_t a = src[2 * q], b = src[2 * q + 1];
+            if (a < 0 || b < 0 || a >= n || b >= n || a == b) return ADMMQ_ERR_PARAM;
+        }
+    }
+    ADMMQ_HIP(hipMemcpyAsync(pairs, src, total * 2 * sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));   // hp may go out of scope only after the copy
+
+    // G = H'(W0 - Wq)
+    ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 1, E));
+    gemm_tn_args gg = {};
+    gg.A = H; gg.lda = n; gg.B = E; gg.ldb = p; gg.M = n; gg.N = p; gg.K = n;
+    gg.alpha = 1.f; gg.beta = (float)lambda; gg.Z = E; gg.ldz = p; gg.out = G; gg.ldo = p; gg.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, gg));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, scal, 0, 32));
+
+    int moves_total = 0;
+    for (int r = 0; r < plan.rounds; ++r) {
+        for (int m = 0; m < plan.batches; ++m) {
+            const int32_t *bp = pairs + ((size_t)r * plan.batches + m) * plan.pairs * 2;
+            ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, bp, plan.pairs, partial,
+                                       nullptr, choice, dstep, dev_moves, scal, 1));
+        }
+        double host[2];
+        ADMMQ_TRY(read_back(ctx, host, scal, 16));
+        int mv;
+        memcpy(&mv, &host[1], sizeof(int));
+        const bool none = mv == moves_total;
+        moves_total = mv;
+        if (drop_out) *drop_out = host[0];
+        if (none) break;
+    }
+    if (moves_out) *moves_out = moves_total;
+    return ADMMQ_OK;
+}
+
+}  // namespace
+
+// ---- context -----------------------------------------------------------------------------------
+extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stream) {
+    if (!out) return ADMMQ_ERR_NULL;
+    *out = nullptr;
+    if (device == -1) {
+        // validation-only context: every call still checks its arguments, then stops at the device
+        admmq_ctx *c = new admmq_ctx();
+        c->device = -1;
+        *out = c;
+        return ADMMQ_OK;
+    }
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) {
+        (void)hipGetLastError();
+        return ADMMQ_ERR_DEVICE;
+    }
+    ADMMQ_HIP(hipSetDevice(device));
+    admmq_ctx *c = new admmq_ctx();
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    *out = c;
+    return ADMMQ_OK;
+}
+
+extern "C" void admmq_destroy(admmq_ctx *ctx) {
+    if (!ctx) return;
+    if (ctx->device >= 0) {
+        (void)hipStreamSynchronize(ctx->stream);
+        if (ctx->arena && ctx->arena_owned) (void)hipFree(ctx->arena);
+    }
+    delete ctx;
+}
+
+extern "C" const char *admmq_status_string(admmq_status s) {
+    switch (s) {
+        case ADMMQ_OK: return "ok";
+        case ADMMQ_ERR_NULL: return "null pointer";
+        case ADMMQ_ERR_SHAPE: return "bad shape";
+        case ADMMQ_ERR_PARAM: return "bad parameter";
+        case ADMMQ_ERR_NOT_FINITE: return "non-finite input";
+        case ADMMQ_ERR_ZERO_DIAG: return "non-positive Hessian diagonal";
+        case ADMMQ_ERR_WORKSPACE: return "workspace too small or allocation failed";
+        case ADMMQ_ERR_STATE: return "no factorisation in the context";
+        case ADMMQ_ERR_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+extern "C" size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T) {
+    if (n < 1 || p < 1 || T < 1) return 0;
+    const int64_t batches = (n + 1) / 2;
+    size_t a = factor_transient_bytes(n);
+    size_t b = admm_transient_bytes(n, p, T);
+    size_t c = ls_transient_bytes(n, p, (int64_t)5 * batches * 64, 64) + 2 * admmq_align_up((size_t)n * p * 4);
+    size_t m = a > b ? a : b;
+    m = m > c ? m : c;
+    return factor_persist_bytes(n) + m + 65536;
+}
+
+extern "C" admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes) {
+    if (!ctx || !dev_ptr) return ADMMQ_ERR_NULL;
+    if (((uintptr_t)dev_ptr & 255) != 0) return ADMMQ_ERR_WORKSPACE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    if (ctx->arena && ctx->arena_owned) ADMMQ_HIP(hipFree(ctx->arena));
+    ctx->arena = (char *)dev_ptr;
+    ctx->arena_bytes = bytes;
+    ctx->arena_owned = false;
+    ctx->persist_top = ctx->top = 0;
+    ctx->fac = admmq_factor();
+    return ADMMQ_OK;
+}
+
+// ---- Hessian -----------------------------------------------------------------------------------
+extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const void *X,
+                                                 admmq_dtype xdt, int64_t rows, int64_t ldx, uint64_t *n_samples) {
+    if (!ctx || !H || !X) return ADMMQ_ERR_NULL;
+    if (n < 1 || rows < 0 || ldx < n || n > (1 << 20)) return ADMMQ_ERR_SHAPE;
+    if (xdt != ADMMQ_F32 && xdt != ADMMQ_BF16) return ADMMQ_ERR_PARAM;
+    if (rows == 0) return ADMMQ_OK;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    // split the token axis so that the triangular tile set fills the chip a few times over
+    const int64_t t256 = (n + 255) / 256, t128 = (n + 127) / 128, t64 = (n + 63) / 64;
+    int64_t tiles = t256 * (t256 + 1) / 2;
+    if (tiles * 8 < 200) tiles = t128 * (t128 + 1) / 2;
+    if (tiles * 8 < 128) tiles = t64 * (t64 + 1) / 2;
+    int64_t split = (1024 + tiles - 1) / tiles;
+    const int64_t max_by_rows = rows / 256 > 0 ? rows / 256 : 1;
+    if (split > max_by_rows) split = max_by_rows;
+    if (split > 64) split = 64;
+    if (split < 1) split = 1;
+    // the partial slices must fit the arena: shrink the split for very large n
+    const size_t slice = (size_t)n * n;
+    while (split > 1 && split * slice * 4 > ((size_t)8 << 30)) --split;
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, (size_t)split * admmq_align_up(slice * 4) + 4096));
+    float *P = nullptr;
+    ADMMQ_TRY(take(ctx, P, (size_t)split * slice));
+    gemm_tn_args g = {};
+    g.A = X; g.B = X; g.lda = ldx; g.ldb = ldx;
+    g.a_bf16 = g.b_bf16 = (xdt == ADMMQ_BF16);
+    g.M = n; g.N = n; g.K = rows; g.alpha = 1.f; g.beta = 0.f; g.Z = nullptr;
+    g.out = P; g.ldo = n; g.lower_only = 1; g.split_k = (int)split; g.slice_stride = (int64_t)slice;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g));
+    ADMMQ_TRY(admmq_sym_reduce(ctx, H, n, P, (int)split, (int64_t)slice, 1));
+    if (n_samples) *n_samples += (uint64_t)rows;
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+// ---- single steps --------------------------------------------------------------------------------
+extern "C" admmq_status admmq_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                                        int32_t bits, int32_t group_size, float *scales, float *zeros) {
+    if (!ctx || !scales || !zeros) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(W0, W0, n, p, ldw, bits, group_size));
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    return admmq_k_grid_init(ctx, W0, n, p, ldw, bits, g, scales, zeros);
+}
+
+extern "C" admmq_status admmq_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp,
+                                        int32_t precondition, float *d_out, double *lambda_out) {
+    if (!ctx || !H) return ADMMQ_ERR_NULL;
+    if (n < 1 || n > (1 << 20)) return ADMMQ_ERR_SHAPE;
+    if (!(damp >= 0.0) || !isfinite(damp)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    ADMMQ_TRY(do_factorize(ctx, H, n, damp, precondition, lambda_out));
+    if (d_out)
+        ADMMQ_HIP(hipMemcpyAsync(d_out, ctx->fac.d, (size_t)n * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    return ADMMQ_OK;
+}
+
+extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const float *D, const float *V, int64_t n,
+                                       int64_t p, double rho, float *W_out) {
+    if (!ctx || !Ws || !D || !V || !W_out) return ADMMQ_ERR_NULL;
+    if (n < 1 || p < 1) return ADMMQ_ERR_SHAPE;
+    if (!(rho > 0.0) || !isfinite(rho)) return ADMMQ_ERR_PARAM;
+    if (!ctx->fac.valid || ctx->fac.n != n) return ADMMQ_ERR_STATE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    admmq_arena_reset_transient(ctx);
+    const size_t np = (size_t)n * p;
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 3 * admmq_align_up(np * 4) + admmq_align_up(np * 8) +
+                                           3 * admmq_align_up((size_t)n * 8) + 8192));
+    float *B = nullptr, *C0 = nullptr, *Y = nullptr;
+    double *F = nullptr, *dinv = nullptr, *lfac = nullptr, *rho_dev = nullptr;
+    ADMMQ_TRY(take(ctx, B, np));
+    ADMMQ_TRY(take(ctx, C0, np));
+    ADMMQ_TRY(take(ctx, Y, np));
+    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, dinv, (size_t)n));
+    ADMMQ_TRY(take(ctx, lfac, (size_t)n));
+    ADMMQ_TRY(take(ctx, rho_dev, 1));
+    const admmq_factor &f = ctx->fac;
+    ADMMQ_HIP(hipMemcpyAsync(rho_dev, &rho, 8, hipMemcpyHostToDevice, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rho_dev, 1, dinv, lfac));
+    gemm_tn_args g0 = {};
+    g0.A = f.Q; g0.lda = n; g0.B = Ws; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
+    g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
+    const float inv_rho = 1.0f / (float)rho;
+    ADMMQ_TRY(admmq_k_form_b(ctx, D, V, inv_rho, (int64_t)np, B));
+    ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv, lfac, Y, F, W_out));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+extern "C" admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                           const float *d, int32_t bits, int32_t group_size, const float *scales,
+                                           const float *zeros, double rho, double rho_next, uint8_t *codes,
+                                           float *B_out, double *res_sq) {
+    if (!ctx || !W || !V || !d || !scales || !zeros || !B_out) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(W, W, n, p, p, bits, group_size));
+    if (!(rho > 0.0) || !(rho_next > 0.0) || !isfinite(rho) || !isfinite(rho_next)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    const size_t ng = (size_t)(n / g) * p;
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, admmq_align_up(ng * 4) + admmq_align_up((size_t)n * 4) + 8192));
+    float *inv_scales = nullptr, *inv_d = nullptr;
+    double *dev_res = nullptr;
+    ADMMQ_TRY(take(ctx, inv_scales, ng));
+    ADMMQ_TRY(take(ctx, inv_d, (size_t)n));
+    ADMMQ_TRY(take(ctx, dev_res, 2));
+    ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
+    ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_res, 0, 16));
+    const float rf = (float)rho;
+    ADMMQ_TRY(admmq_k_project_dual(ctx, W, V, n, p, d, inv_d, bits, g, scales, inv_scales, zeros, rf, 1.0f / rf,
+                                   1.0f / (float)rho_next, codes, 0, B_out, res_sq ? dev_res : nullptr, nullptr));
+    if (res_sq) ADMMQ_TRY(read_back(ctx, res_sq, dev_res, 8));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+extern "C" admmq_status admmq_objective(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                        int64_t ldw, int32_t group_size, const float *scales, const float *zeros,
+                                        const uint8_t *codes, double damp, double *j_out) {
+    if (!ctx || !scales || !zeros || !codes || !j_out) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, 8, group_size));
+    if (!(damp >= 0.0)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    const size_t np = (size_t)n * p;
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 2 * admmq_align_up(np * 4) + 8192));
+    double lambda = 0.0;
+    ADMMQ_TRY(hessian_scalars(ctx, H, n, damp, &lambda));
+    float *E = nullptr, *tmp = nullptr;
+    double *dev = nullptr;
+    ADMMQ_TRY(take(ctx, E, np));
+    ADMMQ_TRY(take(ctx, tmp, np));
+    ADMMQ_TRY(take(ctx, dev, 2));
+    ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, (uint8_t *)codes, n, p, g, scales, zeros, 8, 0, E));
+    ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, E, tmp, dev));
+    ADMMQ_TRY(read_back(ctx, j_out, dev, 8));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+extern "C" admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double lambda, const float *G,
+                                          const uint8_t *codes, int64_t n, int64_t p, int32_t bits,
+                                          int32_t group_size, const float *scales, const int32_t *pairs,
+                                          int32_t npairs, float *totals) {
+    if (!ctx || !G || !codes || !scales || !pairs || !totals) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(H, G, n, p, p, bits, group_size));
+    if (npairs < 1) return ADMMQ_ERR_SHAPE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    const int chunks = admmq_ls_chunks(p);
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, admmq_align_up((size_t)npairs * chunks * 4) + 4096));
+    float *partial = nullptr;
+    ADMMQ_TRY(take(ctx, partial, (size_t)npairs * chunks));
+    ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, (float *)G, (uint8_t *)codes, n, p, bits, g, scales, pairs,
+                               npairs, partial, nullptr, nullptr, nullptr, nullptr, nullptr, 0));
+    ADMMQ_TRY(admmq_k_ls_totals(ctx, partial, chunks, npairs, totals));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+extern "C" void admmq_sample_pair(uint64_t seed, int32_t round, int32_t batch, int32_t slot, int64_t n,
+                                  int32_t *i1, int32_t *i2) {
+    const uint64_t key = ((uint64_t)(uint32_t)round << 48) ^ ((uint64_t)(uint32_t)batch << 16) ^ (uint64_t)(uint32_t)slot;
+    const uint64_t c = mix64(seed ^ mix64(key));
+    const uint64_t a = (c & 0xFFFFFFFFull) % (uint64_t)n;
+    const uint64_t b = (a + 1 + ((c >> 32) % (uint64_t)(n - 1))) % (uint64_t)n;
+    *i1 = (int32_t)a;
+    *i2 = (int32_t)b;
+}
+
+// ---- local search alone --------------------------------------------------------------------------
+extern "C" admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                           int64_t ldw, int32_t bits, int32_t group_size, const float *scales,
+                                           const float *zeros, uint8_t *codes, const admmq_ls_params *prm,
+                                           const int32_t *explicit_pairs, int32_t *moves_out, double *drop_out) {
+    if (!ctx || !scales || !zeros || !codes || !prm) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
+    if (prm->rounds < 0 || prm->batches_per_round < 0 || prm->pairs_per_batch < 0 || !(prm->damp >= 0.0))
+        return ADMMQ_ERR_PARAM;
+    if (n < 2) return ADMMQ_ERR_SHAPE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    LsPlan plan = ls_plan(n, prm->rounds > 0 ? prm->rounds : 5, prm->batches_per_round, prm->pairs_per_batch);
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(
+        ctx, ls_transient_bytes(n, p, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs)));
+    double lambda = 0.0;
+    ADMMQ_TRY(hessian_scalars(ctx, H, n, prm->damp, &lambda));
+    admmq_status s = local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, scales, zeros, codes, plan, prm->seed,
+                                       explicit_pairs, moves_out, drop_out);
+    admmq_arena_reset_transient(ctx);
+    return s;
+}
+
+// ---- whole layer -----------------------------------------------------------------------------------
+extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                             int64_t ldw, int32_t bits, int32_t group_size,
+                                             const admmq_schedule *sched, uint8_t *codes, float *scales, float *zeros,
+                                             admmq_stats *stats) {
+    if (!ctx || !sched || !codes || !scales || !zeros) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
+    if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
+        !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds < 0 ||
+        sched->ls_batches < 0 || sched->ls_pairs < 0)
+        return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    const int T = sched->T;
+    const size_t np = (size_t)n * p;
+    const size_t ng = (size_t)(n / g) * p;
+    const bool want = stats != nullptr;
+    Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
+    t_total.start();
+
+    // --- input checks on the device, before anything is written -------------------------------
+    t_phase.start();
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 4096));
+    {
+        double *dev = nullptr;
+        ADMMQ_TRY(take(ctx, dev, 2));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
+        ADMMQ_TRY(admmq_k_count_nonfinite(ctx, W0, n, p, ldw, dev));
+        double bad = 0.0;
+        ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
+        if (bad > 0.0) return ADMMQ_ERR_NOT_FINITE;
+    }
+    float ms_setup = t_phase.stop();
+
+    // --- Alg. 1 lines 1-3 ----------------------------------------------------------------------
+    t_phase.start();
+    double lambda = 0.0;
+    ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
+    float ms_factor = t_phase.stop();
+    const admmq_factor &f = ctx->fac;
+
+    // --- grid, initial state, schedule -----------------------------------------------------------
+    t_phase.start();
+    LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
+    size_t need = admm_transient_bytes(n, p, T) + admmq_align_up(ng * 4);
+    if (plan.rounds > 0 && n >= 2) {
+        const size_t ls = ls_transient_bytes(n, p, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
+        if (ls > need) need = ls;
+    }
+    ADMMQ_TRY(admmq_arena_reserve(ctx, need));
+    float *B = nullptr, *V = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr, *inv_scales = nullptr;
+    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *res = nullptr, *jdev = nullptr;
+    unsigned long long *flips = nullptr;
+    ADMMQ_TRY(take(ctx, B, np));
+    ADMMQ_TRY(take(ctx, V, np));
+    ADMMQ_TRY(take(ctx, W, np));
+    ADMMQ_TRY(take(ctx, C0, np));
+    ADMMQ_TRY(take(ctx, Y, np));
+    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, inv_scales, ng));
+    ADMMQ_TRY(take(ctx, rhos, (size_t)T));
+    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, res, (size_t)T));
+    ADMMQ_TRY(take(ctx, flips, (size_t)T));
+    ADMMQ_TRY(take(ctx, jdev, 4));
+
+    ADMMQ_TRY(admmq_k_grid_init(ctx, W0, n, p, ldw, bits, g, scales, zeros));
+    ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
+    // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
+    ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, flips, 0, (size_t)T * 8));
+    const bool want_flips = want && stats->code_flips != nullptr;
+    if (want_flips) ADMMQ_TRY(admmq_k_fill_bytes(ctx, codes, 0, np));
+    std::vector<double> hrho((size_t)T + 1);
+    {
+        double r = sched->rho0;
+        for (int t = 0; t <= T; ++t) {
+            hrho[t] = r;
+            r *= sched->gamma;
+        }
+    }
+    ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
+    // C0 = Q^T Ws
+    gemm_tn_args g0 = {};
+    g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
+    g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
+    ms_setup += t_phase.stop();
+
+    // --- ADMM loop (Alg. 1 lines 5-9) -------------------------------------------------------------
+    t_phase.start();
+    for (int t = 0; t < T; ++t) {
+        const float rf = (float)hrho[t];
+        if (t == 0) {
+            // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
+            ADMMQ_HIP(hipMemcpyAsync(W, B, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        } else {
+            ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, W));
+        }
+        const bool last = t == T - 1;
+        ADMMQ_TRY(admmq_k_project_dual(ctx, W, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
+                                       1.0f / rf, 1.0f / (float)hrho[t + 1], (last || want_flips) ? codes : nullptr,
+                                       want_flips ? 1 : 0, B, res + t, want_flips ? flips + t : nullptr));
+    }
+    float ms_admm = t_phase.stop();
+
+    if (want) {
+        stats->iters_done = T;
+        stats->lambda = lambda;
+        if (stats->primal_res) {
+            std::vector<double> h((size_t)T);
+            ADMMQ_TRY(read_back(ctx, h.data(), res, (size_t)T * 8));
+            for (int t = 0; t < T; ++t) stats->primal_res[t] = (float)sqrt(h[t]);
+        }
+        if (want_flips) {
+            std::vector<unsigned long long> h((size_t)T);
+            ADMMQ_TRY(read_back(ctx, h.data(), flips, (size_t)T * 8));
+            for (int t = 0; t < T; ++t) stats->code_flips[t] = (int64_t)h[t];
+        }
+        // objectives: round-to-nearest (into scratch codes) and the ADMM result; W, Y are free now
+        uint8_t *tmp_codes = (uint8_t *)C0;
+        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, tmp_codes, n, p, g, scales, zeros, bits, 2, W));
+        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
+        ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
+        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, W));
+        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
+        ADMMQ_TRY(read_back(ctx, &stats->j_damp_admm, jdev, 8));
+        stats->j_damp = stats->j_damp_admm;
+        stats->ls_moves = 0;
+    }
+
+    // --- local search (Alg. 1 line 11) ----------------------------------------------------------
+    t_phase.start();
+    float ms_ls = 0.f;
+    if (plan.rounds > 0 && n >= 2) {
+        admmq_arena_reset_transient(ctx);
+        int32_t moves = 0;
+        double drop = 0.0;
+        ADMMQ_TRY(local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, scales, zeros, codes, plan, sched->seed,
+                                    nullptr, &moves, &drop));
+        ms_ls = t_phase.stop();
+        if (want) {
+            stats->ls_moves = moves;
+            admmq_arena_reset_transient(ctx);
+            float *E = nullptr, *tmp = nullptr;
+            double *jd = nullptr;
+            ADMMQ_TRY(take(ctx, E, np));
+            ADMMQ_TRY(take(ctx, tmp, np));
+            ADMMQ_TRY(take(ctx, jd, 2));
+            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, E));
+            ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, E, tmp, jd));
+            ADMMQ_TRY(read_back(ctx, &stats->j_damp, jd, 8));
+        }
+    }
+    if (want) {
+        stats->ms_setup = ms_setup;
+        stats->ms_factor = ms_factor;
+        stats->ms_admm = ms_admm;
+        stats->ms_local_search = ms_ls;
+        stats->ms_total = t_total.stop();
+    }
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}

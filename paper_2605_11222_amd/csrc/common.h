@@ -1,0 +1,118 @@
+// Shared host-side declarations of the ADMM-Q library: context, scratch arena, launch wrappers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/admmq.h"
+
+#define ADMMQ_HIP(call)                                  \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) return ADMMQ_ERR_DEVICE;   \
+    } while (0)
+
+#define ADMMQ_TRY(call)                     \
+    do {                                    \
+        admmq_status s_ = (call);           \
+        if (s_ != ADMMQ_OK) return s_;      \
+    } while (0)
+
+// Factorisation of the scaled, damped Hessian kept between calls:  Hs = Q T Q^T.
+struct admmq_factor {
+    int64_t n = 0;
+    double lambda = 0.0;
+    float *d = nullptr;       // [n] d_i = sqrt(H'_ii)
+    float *inv_d = nullptr;   // [n] fp32 reciprocal of d_i
+    float *Q = nullptr;       // [n][n] fp32, row-major Q
+    float *Qt = nullptr;      // [n][n] fp32, row-major Q^T
+    double *ta = nullptr;     // [n]   diagonal of T
+    double *tb = nullptr;     // [n]   sub-diagonal of T (tb[n-1] = 0)
+    bool valid = false;
+};
+
+struct admmq_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    // bump arena: [0, persist_top) holds the factorisation, [persist_top, top) transient scratch
+    char *arena = nullptr;
+    size_t arena_bytes = 0;
+    bool arena_owned = true;
+    size_t persist_top = 0;
+    size_t top = 0;
+    admmq_factor fac;
+    // small pinned host buffer for scalar read-backs
+    double *host_scalars = nullptr;   // 64 doubles
+};
+
+static inline size_t admmq_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Makes sure the arena can hold `bytes` above the persistent region; keeps the persistent region.
+admmq_status admmq_arena_reserve(admmq_ctx *ctx, size_t bytes);
+// Bump allocation inside the reserved arena (never fails after a sufficient reserve).
+void *admmq_arena_alloc(admmq_ctx *ctx, size_t bytes);
+static inline void admmq_arena_reset_transient(admmq_ctx *ctx) { ctx->top = ctx->persist_top; }
+
+// ---- GEMM family (gemm_tn.hip) -------------------------------------------------------------
+// out[m][n] = alpha * sum_{k in [0,K)} A[k][m] * B[k][n] + beta * Z[m][n]
+// A is [K][lda] (fp32, or bf16 bit patterns when a_bf16), B is [K][ldb] likewise; both operands are
+// "k-major": consecutive m (or n) are contiguous.  Z may be NULL (beta ignored) and may alias out.
+struct gemm_tn_args {
+    const void *A;
+    const void *B;
+    int64_t lda, ldb;
+    int a_bf16, b_bf16;
+    int64_t M, N, K;
+    float alpha, beta;
+    const float *Z;
+    int64_t ldz;
+    float *out;
+    int64_t ldo;
+    int lower_only;      // 1: only tiles that touch the lower triangle (m >= n) are computed
+    int split_k;         // >1: slice s handles k in [s*Kc,(s+1)*Kc) and writes out + s*slice_stride
+    int64_t slice_stride;
+};
+admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a);
+// H[i][j] (+)= sum_s P[s][i][j] for i >= j and mirrors the result into the upper triangle.
+admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
+                              int64_t slice_stride, int accumulate);
+
+// ---- streaming kernels (stream.hip) --------------------------------------------------------
+admmq_status admmq_k_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
+                               int64_t g, float *scales, float *zeros);
+admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p, const float *d,
+                                  const float *inv_d, int bits, int64_t g, const float *scales,
+                                  const float *inv_scales, const float *zeros, float rho, float inv_rho,
+                                  float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
+                                  double *dev_res_sq, unsigned long long *dev_flips);
+// inv[i] = 1/x[i] in fp32 with IEEE division, 0 where x[i] == 0
+admmq_status admmq_k_recip(admmq_ctx *ctx, const float *x, float *inv, int64_t n);
+admmq_status admmq_k_scale_rows(admmq_ctx *ctx, const float *W0, int64_t ldw, const float *d, int64_t n, int64_t p,
+                                float *out);
+// B = D - V * inv_rho
+admmq_status admmq_k_form_b(admmq_ctx *ctx, const float *D, const float *V, float inv_rho, int64_t count,
+                            float *B);
+admmq_status admmq_k_fill_f32(admmq_ctx *ctx, float *x, float v, int64_t count);
+admmq_status admmq_k_fill_bytes(admmq_ctx *ctx, void *x, int v, size_t bytes);
+// mode 0: E = dequant(codes) - W0; mode 1: E = W0 - dequant(codes); mode 2: codes := round-to-nearest
+// of W0 on the grid first, then E = dequant(codes) - W0
+admmq_status admmq_k_quant_error(admmq_ctx *ctx, const float *W0, int64_t ldw, uint8_t *codes, int64_t n,
+                                 int64_t p, int64_t g, const float *scales, const float *zeros, int bits, int mode,
+                                 float *E);
+// *dev_out = sum_{i,j} A[i][j] * B[i][j]  (double accumulation)
+admmq_status admmq_k_dot(admmq_ctx *ctx, const float *A, const float *B, int64_t count, double *dev_out);
+// trace and finiteness of a square fp32 matrix; dev_out[0] = trace, dev_out[1] = #non-finite entries,
+// dev_out[2] = #diagonal entries <= 0 after adding nothing (raw diagonal)
+admmq_status admmq_k_matrix_check(admmq_ctx *ctx, const float *H, int64_t n, double *dev_out);
+admmq_status admmq_k_count_nonfinite(admmq_ctx *ctx, const float *A, int64_t rows, int64_t cols, int64_t ld,
+                                     double *dev_out);
+
+// ---- factorisation (factor.hip) ------------------------------------------------------------
+// LDL^T factors of T + rho_t I for `count` values of rho: dinv[t][i], l[t][i] (fp64).
+admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const double *tb, int64_t n,
+                                    const double *rhos_dev, int count, double *dinv, double *lfac);
+// S = (T + rho I)^{-1} T Y, column by column (Y, S fp32 [n][p]; may alias), F fp64 scratch [n][p]
+admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
+                                   const double *lfac, int64_t n, int64_t p, const float *Y, double *F,
+                                   float *S);

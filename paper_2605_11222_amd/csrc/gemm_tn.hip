@@ -1,0 +1,370 @@
+// fp32 matrix-core GEMM family for gfx950:  out = alpha * A^T B + beta * Z.
+//
+// Both operands are k-major ([K][M] and [K][N], consecutive m / n contiguous), which is the natural
+// layout of every dense contraction on the ADMM-Q path:
+//   Hessian (Sec. 3.1)      H += X^T X             A = B = X [rows][n]
+//   W-update (eq. 7)        Y = Q^T R, W = B + Q S  A = Q resp. Q^T stored row-major
+//   gradient (Sec. 3.5)     G = H' (W0 - Wq)        A = H (symmetric)
+// Tiles of A and B for KT consecutive k are staged through LDS (double buffered, register
+// prefetch of the next tile while the current one is consumed); each 64-lane wave owns a
+// (32*FA) x (32*FB) block of the output as FA*FB accumulators of v_mfma_f32_32x32x2_f32.
+// Lane l of the wave feeds matrix row  FA*(l%32)+a  and column  FB*(l%32)+b  of its block, so one
+// LDS read of FA (FB) consecutive floats serves all FA (FB) accumulators and the epilogue writes
+// FB consecutive outputs per lane.
+#include "common.h"
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int KT = 16;   // k rows per LDS stage
+
+struct GemmParams {
+    const void *A;
+    const void *B;
+    long lda, ldb;
+    long M, N, K;
+    float alpha, beta;
+    const float *Z;
+    long ldz;
+    float *out;
+    long ldo;
+    int tiles_m, tiles_n;
+    int lower_only;
+    int split_k;
+    long k_chunk;
+    long slice_stride;
+    int vec_ok;     // 1: all rows 16-byte aligned and M, N multiples of 4 (vector global access)
+};
+
+__device__ inline float bf16_to_f32(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+
+// Loads 4 consecutive elements of row k starting at column c (zero outside [0,cols) x [0,K)).
+template <bool BF16>
+__device__ inline floatx4 load4(const void *base, long ld, long k, long kend, long c, long cols, bool vec_ok) {
+    floatx4 r = {0.f, 0.f, 0.f, 0.f};
+    if (k >= kend) return r;
+    if (BF16) {
+        const unsigned short *row = (const unsigned short *)base + k * ld;
+        if (vec_ok && c + 3 < cols) {
+            uint2 u = *(const uint2 *)(row + c);
+            r.x = __uint_as_float(u.x << 16);
+            r.y = __uint_as_float(u.x & 0xFFFF0000u);
+            r.z = __uint_as_float(u.y << 16);
+            r.w = __uint_as_float(u.y & 0xFFFF0000u);
+        } else {
+            if (c + 0 < cols) r.x = bf16_to_f32(row[c + 0]);
+            if (c + 1 < cols) r.y = bf16_to_f32(row[c + 1]);
+            if (c + 2 < cols) r.z = bf16_to_f32(row[c + 2]);
+            if (c + 3 < cols) r.w = bf16_to_f32(row[c + 3]);
+        }
+    } else {
+        const float *row = (const float *)base + k * ld;
+        if (vec_ok && c + 3 < cols) {
+            r = *(const floatx4 *)(row + c);
+        } else {
+            if (c + 0 < cols) r.x = row[c + 0];
+            if (c + 1 < cols) r.y = row[c + 1];
+            if (c + 2 < cols) r.z = row[c + 2];
+            if (c + 3 < cols) r.w = row[c + 3];
+        }
+    }
+    return r;
+}
+
+// Maps a linear block id to a tile so that (i) the blocks one XCD receives (ids congruent mod 8)
+// form a compact patch of the tile grid and share operand panels in that XCD's L2, and (ii) inside
+// the patch consecutive blocks walk down short columns of GROUP tiles.
+__device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int &tm, int &tn) {
+    int pid = bid;
+    if ((nblocks & 7) == 0) pid = (bid & 7) * (nblocks >> 3) + (bid >> 3);
+    const int GROUP = 4;
+    int per_group = GROUP * tiles_n;
+    int grp = pid / per_group;
+    int first_m = grp * GROUP;
+    int gsz = min(tiles_m - first_m, GROUP);
+    int in_grp = pid - grp * per_group;
+    tm = first_m + in_grp % gsz;
+    tn = in_grp / gsz;
+}
+
+template <int FA, int FB, int WGM, int WGN, bool ABF16, bool BBF16>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
+    constexpr int BM = 32 * FA * WGM;
+    constexpr int BN = 32 * FB * WGN;
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int A4 = KT * BM / 4;            // float4 slots in an A stage
+    constexpr int B4 = KT * BN / 4;
+    constexpr int A_PER = (A4 + NT - 1) / NT;  // float4 loads per thread
+    constexpr int B_PER = (B4 + NT - 1) / NT;
+    extern __shared__ float lds[];
+    float *sA = lds;                      // [2][KT][BM]
+    float *sB = lds + 2 * KT * BM;        // [2][KT][BN]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WGM;
+    const int wn = wave / WGM;
+
+    int tile_id = blockIdx.x;
+    int slice = 0;
+    const int tiles_total = (int)(gridDim.x / P.split_k);
+    if (P.split_k > 1) {
+        slice = tile_id / tiles_total;
+        tile_id -= slice * tiles_total;
+    }
+    int tm, tn;
+    if (P.lower_only) {
+        // tile_id enumerates pairs tm >= tn row by row of the triangle: id = tm(tm+1)/2 + tn
+        tm = (int)((sqrtf(8.f * (float)tile_id + 1.f) - 1.f) * 0.5f);
+        while ((long)(tm + 1) * (tm + 2) / 2 <= tile_id) ++tm;
+        while ((long)tm * (tm + 1) / 2 > tile_id) --tm;
+        tn = tile_id - tm * (tm + 1) / 2;
+    } else {
+        tile_of_block(tile_id, tiles_total, P.tiles_m, P.tiles_n, tm, tn);
+    }
+    const long m0 = (long)tm * BM;
+    const long n0 = (long)tn * BN;
+    const long kbeg = (long)slice * P.k_chunk;
+    const long kend = min(P.K, kbeg + P.k_chunk);
+    const bool vec_ok = P.vec_ok != 0;
+
+    floatx16 acc[FA][FB];
+#pragma unroll
+    for (int a = 0; a < FA; ++a)
+#pragma unroll
+        for (int b = 0; b < FB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    floatx4 ra[A_PER], rb[B_PER];
+
+    auto fetch = [&](long k0) {
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) {
+            int s = tid + i * NT;
+            if (A4 % NT == 0 || s < A4) {
+                int kr = s / (BM / 4);
+                int c4 = s % (BM / 4);
+                ra[i] = load4<ABF16>(P.A, P.lda, k0 + kr, kend, m0 + 4 * c4, P.M, vec_ok);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) {
+            int s = tid + i * NT;
+            if (B4 % NT == 0 || s < B4) {
+                int kr = s / (BN / 4);
+                int c4 = s % (BN / 4);
+                rb[i] = load4<BBF16>(P.B, P.ldb, k0 + kr, kend, n0 + 4 * c4, P.N, vec_ok);
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+        floatx4 *dA = (floatx4 *)(sA + buf * KT * BM);
+        floatx4 *dB = (floatx4 *)(sB + buf * KT * BN);
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) {
+            int s = tid + i * NT;
+            if (A4 % NT == 0 || s < A4) dA[s] = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) {
+            int s = tid + i * NT;
+            if (B4 % NT == 0 || s < B4) dB[s] = rb[i];
+        }
+    };
+
+    const long nkt = (kend - kbeg + KT - 1) / KT;
+    if (nkt > 0) {
+        fetch(kbeg);
+        stash(0);
+    }
+    __syncthreads();
+
+    const int l32 = lane & 31;
+    const int khalf = lane >> 5;
+    for (long kt = 0; kt < nkt; ++kt) {
+        const int buf = (int)(kt & 1);
+        if (kt + 1 < nkt) fetch(kbeg + (kt + 1) * KT);
+        const float *cA = sA + buf * KT * BM + wm * (32 * FA) + FA * l32;
+        const float *cB = sB + buf * KT * BN + wn * (32 * FB) + FB * l32;
+#pragma unroll
+        for (int kk = 0; kk < KT / 2; ++kk) {
+            const int kr = 2 * kk + khalf;
+            float fa[FA], fb[FB];
+            if constexpr (FA == 4) {
+                floatx4 t = *(const floatx4 *)(cA + kr * BM);
+                fa[0] = t.x; fa[1] = t.y; fa[2] = t.z; fa[3] = t.w;
+            } else if constexpr (FA == 2) {
+                floatx2 t = *(const floatx2 *)(cA + kr * BM);
+                fa[0] = t.x; fa[1] = t.y;
+            } else {
+                fa[0] = cA[kr * BM];
+            }
+            if constexpr (FB == 4) {
+                floatx4 t = *(const floatx4 *)(cB + kr * BN);
+                fb[0] = t.x; fb[1] = t.y; fb[2] = t.z; fb[3] = t.w;
+            } else if constexpr (FB == 2) {
+                floatx2 t = *(const floatx2 *)(cB + kr * BN);
+                fb[0] = t.x; fb[1] = t.y;
+            } else {
+                fb[0] = cB[kr * BN];
+            }
+#pragma unroll
+            for (int a = 0; a < FA; ++a)
+#pragma unroll
+                for (int b = 0; b < FB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        if (kt + 1 < nkt) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Epilogue.  Accumulator register v of lane l holds matrix-core row 8*(v/4) + 4*(l/32) + v%4 and
+    // column l%32 of the 32x32 result.
+    float *outp = P.out + (long)slice * P.slice_stride;
+    const long wm0 = m0 + wm * (32 * FA);
+    const long wn0 = n0 + wn * (32 * FB);
+#pragma unroll
+    for (int a = 0; a < FA; ++a) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int ic = 8 * (v / 4) + 4 * khalf + (v % 4);
+            const long m = wm0 + FA * ic + a;
+            if (m >= P.M) continue;
+            const long n = wn0 + FB * l32;
+            float r[FB];
+#pragma unroll
+            for (int b = 0; b < FB; ++b) r[b] = P.alpha * acc[a][b][v];
+            bool done = false;
+            if constexpr (FB == 4) {
+              if (vec_ok && n + 3 < P.N) {
+                floatx4 o = {r[0], r[1], r[2], r[3]};
+                if (P.Z) {
+                    floatx4 z = *(const floatx4 *)(P.Z + m * P.ldz + n);
+                    o.x += P.beta * z.x; o.y += P.beta * z.y; o.z += P.beta * z.z; o.w += P.beta * z.w;
+                }
+                *(floatx4 *)(outp + m * P.ldo + n) = o;
+                done = true;
+              }
+            }
+            if (!done) {
+#pragma unroll
+                for (int b = 0; b < FB; ++b) {
+                    if (n + b < P.N) {
+                        float o = r[b];
+                        if (P.Z) o += P.beta * P.Z[m * P.ldz + n + b];
+                        outp[m * P.ldo + n + b] = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int FA, int FB, int WGM, int WGN>
+admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
+    constexpr int BM = 32 * FA * WGM;
+    constexpr int BN = 32 * FB * WGN;
+    GemmParams P;
+    P.A = a.A; P.B = a.B; P.lda = a.lda; P.ldb = a.ldb;
+    P.M = a.M; P.N = a.N; P.K = a.K;
+    P.alpha = a.alpha; P.beta = a.beta; P.Z = a.Z; P.ldz = a.ldz;
+    P.out = a.out; P.ldo = a.ldo;
+    P.tiles_m = (int)((a.M + BM - 1) / BM);
+    P.tiles_n = (int)((a.N + BN - 1) / BN);
+    P.lower_only = a.lower_only;
+    P.split_k = a.split_k > 1 ? a.split_k : 1;
+    long kc = (a.K + P.split_k - 1) / P.split_k;
+    kc = (kc + KT - 1) / KT * KT;
+    P.k_chunk = kc;
+    P.slice_stride = a.slice_stride;
+    auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+    const long esz_a = a.a_bf16 ? 2 : 4, esz_b = a.b_bf16 ? 2 : 4;
+    bool ok = (a.M % 4 == 0) && (a.N % 4 == 0) && al16(a.out) && (a.ldo % 4 == 0) &&
+              ((uintptr_t)a.A % (4 * esz_a) == 0) && (a.lda % 4 == 0) &&
+              ((uintptr_t)a.B % (4 * esz_b) == 0) && (a.ldb % 4 == 0) && (a.slice_stride % 4 == 0);
+    if (a.Z) ok = ok && al16(a.Z) && (a.ldz % 4 == 0);
+    P.vec_ok = ok ? 1 : 0;
+    long tiles;
+    if (a.lower_only) {
+        if (BM != BN) return ADMMQ_ERR_PARAM;
+        tiles = (long)P.tiles_m * (P.tiles_m + 1) / 2;
+    } else {
+        tiles = (long)P.tiles_m * P.tiles_n;
+    }
+    const size_t lds_bytes = (size_t)2 * KT * (BM + BN) * sizeof(float);
+    dim3 grid((unsigned)(tiles * P.split_k)), block(64 * WGM * WGN);
+#define ADMMQ_GEMM_LAUNCH(AB, BB)                                                                      \
+    do {                                                                                               \
+        auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, AB, BB>;                                          \
+        static bool attr_set = false;                                                                  \
+        if (!attr_set) {                                                                               \
+            ADMMQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                          (int)lds_bytes));                                            \
+            attr_set = true;                                                                           \
+        }                                                                                              \
+        hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, P);                              \
+    } while (0)
+    if (a.a_bf16 && a.b_bf16) ADMMQ_GEMM_LAUNCH(true, true);
+    else if (!a.a_bf16 && !a.b_bf16) ADMMQ_GEMM_LAUNCH(false, false);
+    else return ADMMQ_ERR_PARAM;
+#undef ADMMQ_GEMM_LAUNCH
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+__global__ void sym_reduce_kernel(float *H, long n, const float *P, int slices, long stride, int accumulate) {
+    // one thread per lower-triangle element (i >= j) of a 32x32 patch; patch grid covers the square
+    __shared__ float tile[32][33];
+    const int bi = blockIdx.y, bj = blockIdx.x;
+    if (bj > bi) return;
+    const int tx = threadIdx.x, ty = threadIdx.y;   // 32 x 8
+    for (int r = ty; r < 32; r += 8) {
+        long i = (long)bi * 32 + r, j = (long)bj * 32 + tx;
+        float s = 0.f;
+        if (i < n && j < n && i >= j) {
+            for (int q = 0; q < slices; ++q) s += P[(long)q * stride + i * n + j];
+            if (accumulate) s += H[i * n + j];
+            H[i * n + j] = s;
+        }
+        tile[r][tx] = s;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        // element (j', i') of the upper triangle = tile[i' - bi*32][j' - bj*32]
+        long jj = (long)bj * 32 + r, ii = (long)bi * 32 + tx;
+        if (ii < n && jj < n && ii > jj) H[jj * n + ii] = tile[tx][r];
+    }
+}
+
+}  // namespace
+
+admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
+    if (a.M <= 0 || a.N <= 0 || a.K < 0) return ADMMQ_ERR_SHAPE;
+    // tile choice: the largest tile that still gives every CU work
+    const long t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+    const long t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    const long work = a.split_k > 1 ? a.split_k : 1;
+    if (a.lower_only) {
+        const long tm256 = (a.M + 255) / 256, tm128 = (a.M + 127) / 128;
+        if (tm256 * (tm256 + 1) / 2 * work >= 200) return launch_cfg<4, 4, 2, 2>(ctx, a);
+        if (tm128 * (tm128 + 1) / 2 * work >= 128) return launch_cfg<2, 2, 2, 2>(ctx, a);
+        return launch_cfg<1, 1, 2, 2>(ctx, a);
+    }
+    if (t256 * work >= 200) return launch_cfg<4, 4, 2, 2>(ctx, a);
+    if (t128 * work >= 128) return launch_cfg<2, 2, 2, 2>(ctx, a);
+    return launch_cfg<1, 1, 2, 2>(ctx, a);
+}
+
+admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
+                              int64_t slice_stride, int accumulate) {
+    dim3 block(32, 8), grid((unsigned)((n + 31) / 32), (unsigned)((n + 31) / 32));
+    hipLaunchKernelGGL(sym_reduce_kernel, grid, block, 0, ctx->stream, H, (long)n, P, slices, (long)slice_stride,
+                       accumulate);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}

@@ -1,0 +1,96 @@
+"""CPU checks of the C-ABI library: it loads, exports every declared symbol, validates arguments
+before touching a device, and its host-side pair sampler agrees with the oracle's."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2605_11222_amd as admmq
+from paper_2605_11222_amd import binding
+from oracle import admmq_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return admmq.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "admmq.h")).read()
+    declared = set(re.findall(r"\b(admmq_[a-z_]+)\s*\(", header))
+    assert declared == set(admmq.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert lib.admmq_status_string(0) == b"ok"
+    assert all(lib.admmq_status_string(c) for c in range(9))
+
+
+def test_workspace_bytes_monotone(lib):
+    a = admmq.workspace_bytes(128, 64, 50)
+    b = admmq.workspace_bytes(4096, 4096, 200)
+    c = admmq.workspace_bytes(25600, 5120, 300)
+    assert 0 < a < b < c
+    assert c < 200 * 2 ** 30            # the largest workload fits one 288 GB GPU several times over
+    assert admmq.workspace_bytes(0, 4, 4) == 0
+
+
+def test_pair_sampler_matches_oracle_generator(lib):
+    for seed, n in ((0, 2), (7, 128), (2 ** 63 + 5, 4096), (12345, 25600)):
+        for r in (0, 3):
+            for b in (0, 17, 12799):
+                for s in (0, 1, 63):
+                    assert admmq.sample_pair(seed, r, b, s, n) == orc.sample_pair(seed, r, b, s, n)
+
+
+def _ctx(lib):
+    h = C.c_void_p()
+    assert lib.admmq_create(C.byref(h), -1, None) == 0
+    return h
+
+
+def test_argument_validation_without_a_gpu(lib):
+    h = _ctx(lib)
+    one = C.c_void_p(256)      # any non-null address: validation must not dereference it
+    sched = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 0)
+    q = lambda **k: lib.admmq_quantize_layer(
+        h, k.get("H", one), k.get("W0", one), k.get("n", 8), k.get("p", 4), k.get("ldw", 4), k.get("bits", 4),
+        k.get("g", 0), C.byref(k.get("sched", sched)), k.get("codes", one), one, one, None)
+    assert q(H=None) == 1 and q(W0=None) == 1 and q(codes=None) == 1
+    assert q(n=0) == 2 and q(p=0) == 2 and q(ldw=3) == 2 and q(g=3) == 2 and q(g=-1) == 2
+    assert q(bits=1) == 3 and q(bits=9) == 3
+    for bad in (binding._Schedule(0, 0.1, 1.1, 0.01, 1, 0, 0, 0, 0),
+                binding._Schedule(10, 0.0, 1.1, 0.01, 1, 0, 0, 0, 0),
+                binding._Schedule(10, 0.1, 0.9, 0.01, 1, 0, 0, 0, 0),
+                binding._Schedule(10, 0.1, 1.1, -1.0, 1, 0, 0, 0, 0),
+                binding._Schedule(10, float("nan"), 1.1, 0.01, 1, 0, 0, 0, 0),
+                binding._Schedule(10, 0.1, 1.1, 0.01, 1, -1, 0, 0, 0)):
+        assert q(sched=bad) == 3
+    assert q() == 8                       # valid arguments: stops at the missing device
+    cnt = C.c_uint64(0)
+    assert lib.admmq_accumulate_hessian(h, None, 8, one, 0, 4, 8, C.byref(cnt)) == 1
+    assert lib.admmq_accumulate_hessian(h, one, 8, one, 0, 4, 7, C.byref(cnt)) == 2
+    assert lib.admmq_accumulate_hessian(h, one, 8, one, 5, 4, 8, C.byref(cnt)) == 3
+    assert lib.admmq_accumulate_hessian(h, one, 8, one, 0, 0, 8, C.byref(cnt)) == 0 and cnt.value == 0
+    assert lib.admmq_accumulate_hessian(h, one, 8, one, 0, 4, 8, C.byref(cnt)) == 8 and cnt.value == 0
+    assert lib.admmq_w_update(h, one, one, one, 8, 4, 0.5, one) == 7      # no factorisation yet
+    assert lib.admmq_w_update(h, one, one, one, 8, 4, -1.0, one) == 3
+    assert lib.admmq_project_dual(h, one, one, 8, 4, one, 4, 3, one, one, 0.5, 0.55, None, one, None) == 2
+    assert lib.admmq_project_dual(h, one, one, 8, 4, one, 4, 0, one, one, 0.0, 0.55, None, one, None) == 3
+    prm = binding._LsParams(1, 1, 4, 0.01, 0)
+    assert lib.admmq_local_search(h, one, one, 1, 4, 4, 4, 0, one, one, one, C.byref(prm), None, None, None) == 2
+    assert lib.admmq_set_workspace(h, C.c_void_p(100), 1 << 20) == 6
+    lib.admmq_destroy(h)
+    assert lib.admmq_create(None, 0, None) == 1
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libadmmq.so")
+    with pytest.raises(admmq.AdmmqError):
+        binding.load_library()

@@ -96,6 +96,7 @@ def test_degenerate_group_codes_zero():
     k = grid.codes(W0 + 5.0)
     assert np.all(k[:, 0] == 0) and np.all(k[:, 2] == 0)
     assert np.allclose(grid.dequant(k)[:, 0], 0.25)
+    assert grid.delta[0, 0] == 0.0 and grid.delta[0, 1] > 0
 
 
 def test_w_update_solves_eq7_linear_system():
