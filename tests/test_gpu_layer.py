@@ -1,0 +1,260 @@
+"""GPU parity of the whole layer solver and of the local search against the float64 oracle.
+
+The ADMM trajectory is a discrete dynamical system: one rounding that falls the other way near a
+midpoint (fp32 against float64) changes later iterates, and the local search breaks near-ties by
+floating-point totals.  Several final code matrices are therefore correct; what is unique is compared
+(grid, first-iteration codes, objectives within 0.5 %), the rest is checked for validity (codes in
+range, objective recomputed in float64 from the returned codes equals the reported one, local search
+never raises the objective, determinism)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import admmq_oracle as orc
+from gpu_util import to_dev, correlated_problem
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+OBJ_TOL = 5e-3       # final layer objective within 0.5 % relative of the oracle's
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_11222_amd as admmq
+    c = admmq.Context(0)
+    yield c
+    c.close()
+
+
+def cfg1_inputs(ctx):
+    cfg = si.CONFIGS["cfg1"]
+    H = torch.zeros((cfg.n, cfg.n), dtype=torch.float32, device="cuda")
+    chunks = []
+    for _, xc in si.iter_x_chunks(cfg):
+        ctx.accumulate_hessian(H, to_dev(xc))
+        chunks.append(si.chunk_as_f64(cfg, xc))
+    W0 = si.layer_weights(cfg)
+    return cfg, H, W0, orc.hessian(chunks)
+
+
+def f64_objective(H32, lam, W0, codes, scales, zeros, g):
+    n = W0.shape[0]
+    gg = n if g == 0 else g
+    Wq = np.repeat(zeros.astype(np.float64), gg, 0) + codes.astype(np.float64) * np.repeat(scales.astype(np.float64), gg, 0)
+    Hd = H32.astype(np.float64) + lam * np.eye(n)
+    return orc.objective(Hd, W0.astype(np.float64), Wq)
+
+
+def test_cfg1_whole_layer_against_oracle(ctx):
+    import paper_2605_11222_amd as admmq
+    cfg, H, W0, H64 = cfg1_inputs(ctx)
+    sched = admmq.Schedule(T=cfg.T, ls_rounds=5, seed=0)
+    codes, scales, zeros, st = ctx.quantize_layer(H, to_dev(W0), cfg.bits, cfg.group_size, sched, want_history=True)
+    torch.cuda.synchronize()
+    ref = orc.quantize_layer(H64, W0.astype(np.float64), cfg.bits, cfg.group_size, T=cfg.T, ls_rounds=5, seed=0)
+    k = codes.cpu().numpy()
+    assert k.max() <= 2 ** cfg.bits - 1
+    assert np.array_equal(zeros.cpu().numpy(), ref.zeros.astype(np.float32))
+    assert np.allclose(scales.cpu().numpy(), ref.scales, rtol=3e-7)
+    # objectives: reported == recomputed in float64 from the returned codes; within 0.5 % of the oracle
+    H32 = H.cpu().numpy()
+    j64 = f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), cfg.group_size)
+    assert st.j_damp == pytest.approx(j64, rel=1e-4)
+    assert st.j_damp_rtn == pytest.approx(ref.j_damp_rtn, rel=1e-4)
+    assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+    assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    assert st.j_damp <= st.j_damp_admm * (1 + 1e-6) <= st.j_damp_rtn
+    # residual history: same decay as the oracle's until the fp32 floor
+    pr = np.array(st.primal_res)
+    assert pr[0] == pytest.approx(ref.admm.primal[0], rel=1e-4)
+    live = np.array(ref.admm.primal) > 1e-4 * ref.admm.primal[0]
+    assert np.allclose(pr[live], np.array(ref.admm.primal)[live], rtol=0.05)
+    assert st.code_flips[0] > 0 and st.code_flips[-1] == 0
+    print(f"cfg1: J rtn {st.j_damp_rtn:.4f} admm {st.j_damp_admm:.4f} (oracle {ref.j_damp_admm:.4f}) "
+          f"final {st.j_damp:.4f} (oracle {ref.j_damp:.4f}) moves {st.ls_moves} vs {ref.ls.moves}")
+
+
+def test_one_iteration_returns_round_to_nearest(ctx):
+    import paper_2605_11222_amd as admmq
+    cfg, H, W0, H64 = cfg1_inputs(ctx)
+    codes, scales, zeros, st = ctx.quantize_layer(H, to_dev(W0), cfg.bits, 0, admmq.Schedule(T=1, ls_rounds=0))
+    grid = orc.Grid.fit(W0.astype(np.float64), cfg.bits, 0)
+    k_rtn, _ = orc.rtn(W0.astype(np.float64), grid)
+    k = codes.cpu().numpy().astype(np.int64)
+    t = (W0.astype(np.float64) - grid.z0) / grid.delta
+    near = np.abs(t - np.floor(t) - 0.5) < 1e-4
+    assert np.all((k == k_rtn) | near) and np.mean(k != k_rtn) < 1e-3
+    assert st.j_damp_admm == pytest.approx(st.j_damp_rtn, rel=1e-3)
+
+
+@pytest.mark.parametrize("n,p,N,bits,g,T,seed", [(256, 96, 800, 3, 64, 120, 1), (384, 200, 1500, 2, 32, 150, 2),
+                                                  (192, 130, 150, 4, 0, 100, 3)])
+def test_layer_objective_parity_other_shapes(ctx, n, p, N, bits, g, T, seed):
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(n, p, N, seed, outliers=3)
+    H64 = orc.hessian([X.astype(np.float64)])
+    H32 = H64.astype(np.float32)
+    sched = admmq.Schedule(T=T, ls_rounds=2, ls_pairs=32, seed=seed)
+    codes, scales, zeros, st = ctx.quantize_layer(to_dev(H32), to_dev(W0), bits, g, sched)
+    ref = orc.quantize_layer(H32.astype(np.float64), W0.astype(np.float64), bits, g, T=T, ls_rounds=2, ls_pairs=32,
+                             seed=seed)
+    k = codes.cpu().numpy()
+    assert k.max() <= 2 ** bits - 1
+    j64 = f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), g)
+    assert st.j_damp == pytest.approx(j64, rel=1e-4)
+    assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+    assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    assert st.j_damp <= st.j_damp_admm * (1 + 1e-6)
+    print(f"n={n} p={p} b={bits} g={g}: admm {st.j_damp_admm:.5g}/{ref.j_damp_admm:.5g} final {st.j_damp:.5g}/{ref.j_damp:.5g}"
+          f" rtn {st.j_damp_rtn:.5g} code mismatch {np.mean(k != ref.codes):.4f}")
+
+
+def test_layer_is_deterministic(ctx):
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(256, 64, 700, 9)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    sched = admmq.Schedule(T=60, ls_rounds=2, ls_pairs=16, seed=4)
+    a = ctx.quantize_layer(H, to_dev(W0), 3, 64, sched)[0].cpu().numpy()
+    b = ctx.quantize_layer(H, to_dev(W0), 3, 64, sched)[0].cpu().numpy()
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------------
+# local search
+# ---------------------------------------------------------------------------------------------
+def ls_problem(n, p, bits, g, seed):
+    X, W0 = correlated_problem(n, p, 4 * n, seed, sigma_w=1.0)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    Hd, lam = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    return H32, Hd, lam, W0
+
+
+def test_eq11_batch_totals_match_oracle(ctx):
+    n, p, bits, g = 96, 1500, 3, 32
+    H32, Hd, lam, W0 = ls_problem(n, p, bits, g, 5)
+    W0d = to_dev(W0)
+    scales, zeros = ctx.grid_init(W0d, bits, g)
+    grid = orc.Grid(scales.cpu().numpy().astype(np.float64), zeros.cpu().numpy().astype(np.float64), bits,
+                    scales.cpu().numpy() == 0)
+    rng = np.random.default_rng(3)
+    codes = rng.integers(0, 2 ** bits, size=(n, p)).astype(np.uint8)
+    G64 = Hd @ (W0.astype(np.float64) - grid.dequant(codes.astype(np.int64)))
+    pairs = np.array(orc.sample_batch(11, 0, 0, 64, n), dtype=np.int32)
+    tot = ctx.ls_evaluate(to_dev(H32), lam, to_dev(G64.astype(np.float32)), to_dev(codes), bits, g, scales,
+                          to_dev(pairs)).cpu().numpy()
+    want = []
+    for i1, i2 in pairs:
+        dL, _, _ = orc.pair_gains(Hd, G64, codes.astype(np.int64), grid, int(i1), int(i2))
+        want.append(orc.column_moves(dL)[1].sum())
+    assert np.allclose(tot, want, rtol=2e-4, atol=1e-4 * max(want))
+
+
+@pytest.mark.parametrize("n,p,bits,g,seed", [(64, 40, 3, 16, 1), (128, 300, 2, 0, 2), (48, 1100, 4, 24, 3)])
+def test_local_search_against_oracle(ctx, n, p, bits, g, seed):
+    H32, Hd, lam, W0 = ls_problem(n, p, bits, g, seed)
+    W0d, Hdv = to_dev(W0), to_dev(H32)
+    scales, zeros = ctx.grid_init(W0d, bits, g)
+    sc, zr = scales.cpu().numpy(), zeros.cpu().numpy()
+    grid = orc.Grid(sc.astype(np.float64), zr.astype(np.float64), bits, sc == 0)
+    k0, _ = orc.rtn(W0.astype(np.float64), grid)
+    codes = to_dev(k0.astype(np.uint8))
+    j0 = ctx.objective(Hdv, W0d, g, scales, zeros, codes)
+    assert j0 == pytest.approx(orc.objective(Hd, W0.astype(np.float64), grid.dequant(k0)), rel=1e-4)
+    moves, drop = ctx.local_search(Hdv, W0d, bits, g, scales, zeros, codes, rounds=3, pairs_per_batch=16, seed=seed)
+    ref = orc.local_search(Hd, W0.astype(np.float64), k0, grid, rounds=3, pairs_per_batch=16, seed=seed)
+    k = codes.cpu().numpy().astype(np.int64)
+    assert 0 <= k.min() and k.max() <= 2 ** bits - 1
+    j1 = orc.objective(Hd, W0.astype(np.float64), grid.dequant(k))
+    jr = orc.objective(Hd, W0.astype(np.float64), grid.dequant(ref.codes))
+    assert moves > 0 and j1 < j0
+    assert j0 - j1 == pytest.approx(drop, rel=2e-3)              # the reported decrease is the true one
+    assert abs(j1 - jr) <= OBJ_TOL * jr
+    assert ctx.objective(Hdv, W0d, g, scales, zeros, codes) == pytest.approx(j1, rel=1e-4)
+    print(f"n={n} p={p}: J {j0:.5g} -> gpu {j1:.5g} / oracle {jr:.5g}; moves {moves} vs {ref.moves}; "
+          f"identical codes: {np.array_equal(k, ref.codes)}")
+
+
+def test_local_search_tiny_exhaustive_matches_oracle_moves(ctx):
+    """n = 6, 2-bit, every ordered pair in every batch: gains are well separated, so the GPU must
+    apply the same moves as the oracle, whose result the CPU suite checks against enumeration."""
+    n, p, bits = 6, 3, 2
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((24, n)) * np.exp(0.7 * rng.standard_normal(n))
+    X[:, 1:] += 0.6 * X[:, :-1]
+    W0 = rng.standard_normal((n, p)).astype(np.float32)
+    H32 = orc.hessian([X]).astype(np.float32)
+    Hd, lam = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    W0d, Hdv = to_dev(W0), to_dev(H32)
+    scales, zeros = ctx.grid_init(W0d, bits, 0)
+    sc, zr = scales.cpu().numpy(), zeros.cpu().numpy()
+    grid = orc.Grid(sc.astype(np.float64), zr.astype(np.float64), bits, sc == 0)
+    k0, _ = orc.rtn(W0.astype(np.float64), grid)
+    allp = list(itertools.permutations(range(n), 2))
+    rounds = 12
+    ref = orc.local_search(Hd, W0.astype(np.float64), k0, grid, rounds=rounds, batches_per_round=1,
+                           pairs_fn=lambda r, m: allp)
+    codes = to_dev(k0.astype(np.uint8))
+    moves, drop = ctx.local_search(Hdv, W0d, bits, 0, scales, zeros, codes, rounds=rounds, batches_per_round=1,
+                                   pairs_per_batch=len(allp), explicit_pairs=allp * rounds)
+    assert np.array_equal(codes.cpu().numpy().astype(np.int64), ref.codes)
+    assert moves == ref.moves
+    G = Hd @ (W0.astype(np.float64) - grid.dequant(ref.codes))
+    for i1, i2 in allp:                                              # exhausted neighbourhood
+        assert np.all(orc.pair_gains(Hd, G, ref.codes, grid, i1, i2)[0] >= -1e-9)
+
+
+def test_diagonal_hessian_applies_no_move(ctx):
+    rng = np.random.default_rng(4)
+    n, p = 32, 20
+    H32 = np.diag(np.exp(rng.standard_normal(n))).astype(np.float32)
+    W0 = rng.standard_normal((n, p)).astype(np.float32)
+    W0d, Hdv = to_dev(W0), to_dev(H32)
+    scales, zeros = ctx.grid_init(W0d, 3, 0)
+    grid = orc.Grid(scales.cpu().numpy().astype(np.float64), zeros.cpu().numpy().astype(np.float64), 3,
+                    scales.cpu().numpy() == 0)
+    k0, _ = orc.rtn(W0.astype(np.float64), grid)
+    t = (W0.astype(np.float64) - grid.z0) / grid.delta
+    assert np.all(np.abs(t - np.floor(t) - 0.5) > 1e-3)             # no element sits on a midpoint
+    codes = to_dev(k0.astype(np.uint8))
+    moves, drop = ctx.local_search(Hdv, W0d, 3, 0, scales, zeros, codes, rounds=2, pairs_per_batch=32, seed=1)
+    assert moves == 0 and drop == 0.0 and np.array_equal(codes.cpu().numpy(), k0.astype(np.uint8))
+
+
+# ---------------------------------------------------------------------------------------------
+# error paths that need the device
+# ---------------------------------------------------------------------------------------------
+def test_device_side_input_checks_leave_outputs_untouched(ctx):
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(64, 16, 200, 0)
+    H = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    bad = H.copy()
+    bad[3, 5] = np.nan
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layer(to_dev(bad), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=0))
+    assert e.value.code == 4
+    Wbad = W0.copy()
+    Wbad[0, 0] = np.inf
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layer(to_dev(H), to_dev(Wbad), 4, 0, admmq.Schedule(T=5, ls_rounds=0))
+    assert e.value.code == 4
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layer(to_dev(np.zeros_like(H)), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=0))
+    assert e.value.code == 5
+    # caller workspace too small
+    small = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    c2 = admmq.Context(0)
+    c2.set_workspace(small)
+    with pytest.raises(admmq.AdmmqError) as e:
+        c2.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=0))
+    assert e.value.code == 6
+    big = torch.empty(admmq.workspace_bytes(64, 16, 5), dtype=torch.uint8, device="cuda")
+    c2.set_workspace(big)
+    a = c2.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=1))[0]
+    b = ctx.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=1))[0]
+    assert torch.equal(a, b)
+    c2.close()
