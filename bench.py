@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADMM-Q layer solver hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic layer: Hessian accumulation over all
+calibration tokens, then admmq_quantize_layer (damping, scaling, factorisation, T ADMM iterations,
+pair-swap local search).  Inputs are resident in HBM before the timed region starts.  Prints ONE JSON
+line.  `value` is ADMM iterations per second over the ADMM loop alone; the layer time and the Hessian
+time are reported beside it.  The oracle (float64 NumPy) is timed on the host on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+
+
+def make_inputs(cfg, tokens, torch):
+    """X (bf16 or fp32) and W0 on the device, generated chunk by chunk by the shared seeded generator."""
+    dt = torch.bfloat16 if cfg.x_dtype == "bf16" else torch.float32
+    X = torch.empty((tokens, cfg.n), dtype=dt, device="cuda")
+    row = 0
+    for _, xc in si.iter_x_chunks(cfg, tokens):
+        t = torch.from_numpy(xc.view(np.int16) if cfg.x_dtype == "bf16" else xc)
+        if cfg.x_dtype == "bf16":
+            X[row:row + xc.shape[0]].view(torch.int16).copy_(t, non_blocking=False)
+        else:
+            X[row:row + xc.shape[0]].copy_(t)
+        row += xc.shape[0]
+    W0 = torch.from_numpy(si.layer_weights(cfg)).cuda()
+    return X, W0
+
+
+def cpu_baseline(cfg, sample_cols=64, sample_iters=20, sample_tokens=8192):
+    """The float64 oracle, untouched, on a bounded sample of the same workload."""
+    from oracle import admmq_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    chunks = [si.chunk_as_f64(cfg, xc) for _, xc in si.iter_x_chunks(cfg, min(sample_tokens, cfg.tokens))]
+    H = orc.hessian(chunks)
+    t_h = time.perf_counter() - t0
+    W0 = si.layer_weights(cfg, p_slice=sample_cols).astype(np.float64)
+    Hd, _ = orc.damp_hessian(H)
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    t0 = time.perf_counter()
+    d, Hs, Ws = orc.scale_problem(Hd, W0)
+    np.linalg.eigh(Hs)
+    t_eig = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.admm(Hd, W0, grid, T=sample_iters)          # includes its own eigh: subtract the one timed above
+    t_admm = max(time.perf_counter() - t0 - t_eig, 1e-9)
+    its_slice = sample_iters / t_admm
+    its_full = its_slice * sample_cols / cfg.p      # the loop is linear in the number of columns
+    return {
+        "value": its_full, "unit": "ADMM iterations/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"{cfg.name}: first {sample_cols} of {cfg.p} columns, {sample_iters} of {cfg.T} iterations, "
+                   f"H from the first {min(sample_tokens, cfg.tokens)} tokens; measured {its_slice:.3f} it/s on the "
+                   f"slice, scaled by {sample_cols}/{cfg.p}; eigh({cfg.n}) {t_eig:.1f} s, "
+                   f"Hessian {min(sample_tokens, cfg.tokens) / t_h:.0f} tokens/s"),
+        "eig_s": t_eig,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(si.CONFIGS))
+    ap.add_argument("--tokens", type=int, default=0, help="truncate the calibration set (0 = the workload's N)")
+    ap.add_argument("--iters", type=int, default=0, help="ADMM iterations (0 = the workload's T)")
+    ap.add_argument("--ls-rounds", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over output columns without "
+              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2605_11222_amd as admmq
+
+    cfg = si.CONFIGS[args.workload]
+    tokens = args.tokens or cfg.tokens
+    T = args.iters or cfg.T
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    X, W0 = make_inputs(cfg, tokens, torch)
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    H = torch.empty((cfg.n, cfg.n), dtype=torch.float32, device="cuda")
+    ctx = admmq.Context(0)
+    sched = admmq.Schedule(T=T, ls_rounds=args.ls_rounds, seed=cfg.seed)
+
+    def step(profile):
+        H.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ctx.accumulate_hessian(H, X)
+        e1.record()
+        out = ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size, sched, want_stats=True, profile=profile)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), out[3]
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    hs, stats = [], []
+    for _ in range(args.steps):
+        h_ms, st = step(True)
+        hs.append(h_ms)
+        stats.append(st)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+
+    mean = lambda f: float(np.mean([f(s) for s in stats]))
+    admm_ms = mean(lambda s: s.ms_admm)
+    its = T / (admm_ms * 1e-3)
+    n, p = cfg.n, cfg.p
+    gemm_ms = mean(lambda s: s.ms_gemm / max(s.n_gemm, 1))
+    proj_ms = mean(lambda s: s.ms_project / max(s.n_project, 1))
+    tri_ms = mean(lambda s: s.ms_tridiag / max(s.n_tridiag, 1))
+    lsa_ms = mean(lambda s: s.ms_ls_apply / max(s.n_ls_apply, 1))
+    gemm_tf = 2.0 * n * n * p / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    proj_gbs = 16.0 * n * p / (proj_ms * 1e-3) / 1e9 if proj_ms > 0 else 0.0
+    lsa_gbs = (8.0 * n * p + 8.0 * n) / (lsa_ms * 1e-3) / 1e9 if lsa_ms > 0 else 0.0
+    hess_ms = float(np.mean(hs))
+    hess_tf = tokens * n * (n + 1) / (hess_ms * 1e-3) / 1e12
+
+    line = {
+        "metric": "layer quantize time (s) & ADMM iters/s, 4096x4096 W3; % fp32 MFMA peak",
+        "value": its, "unit": "ADMM iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={n} p={p} tokens={tokens} W{cfg.bits} group={cfg.group_size or 'per-channel'} "
+                               f"T={T} ls_rounds={args.ls_rounds}"},
+        "layer_quantize_time_s": mean(lambda s: s.ms_total) * 1e-3,
+        "phases_s": {"hessian": hess_ms * 1e-3, "setup": mean(lambda s: s.ms_setup) * 1e-3,
+                     "factorise": mean(lambda s: s.ms_factor) * 1e-3, "admm": admm_ms * 1e-3,
+                     "local_search": mean(lambda s: s.ms_local_search) * 1e-3},
+        "objective": {"j_damp": stats[-1].j_damp, "j_damp_admm": stats[-1].j_damp_admm,
+                      "j_damp_rtn": stats[-1].j_damp_rtn, "ls_moves": stats[-1].ls_moves},
+        "roofline": {"kernel": "gemm_tn (W-update, 2 launches per iteration)", "bound": "mfma",
+                     "achieved": gemm_tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tf / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "ms_per_launch": gemm_ms, "flop_per_launch": 2.0 * n * n * p},
+        "roofline_projection": {"kernel": "project_dual", "bound": "hbm", "achieved": proj_gbs, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": proj_gbs / PEAK_HBM_GBS, "traffic": None,
+                                "ms_per_launch": proj_ms, "bytes_per_launch": 16.0 * n * p},
+        "roofline_ls_apply": {"kernel": "ls_apply", "bound": "hbm", "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
+        "roofline_hessian": {"kernel": "gemm_tn (Hessian, lower triangle)", "bound": "mfma", "achieved": hess_tf,
+                             "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": hess_tf / PEAK_FP32_MFMA_TFLOPS},
+        "tridiag_ms_per_launch": tri_ms,
+        "input_generation_s": gen_s,
+    }
+    ctx.close()
+    del X
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

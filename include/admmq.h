@@ -92,6 +92,14 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     int32_t ls_moves;       /* applied row pairs */
     float *primal_res;      /* optional host array [T]: ||W - D||_F per iteration, or NULL */
     int64_t *code_flips;    /* optional host array [T]: codes changed per iteration, or NULL */
+    /* in: non-zero = bracket every launch of the kernels below with HIP events on the context's
+     * stream; out: summed device time (ms) and launch counts inside the ADMM loop / local search */
+    int32_t profile;
+    int32_t n_gemm, n_tridiag, n_project, n_ls_apply;
+    float ms_gemm;          /* the two n x n x p products of each W-update (eq. 7)            */
+    float ms_tridiag;       /* the tridiagonal solve between them                             */
+    float ms_project;       /* fused projection + dual + residual pass (eqs. 8-10, 9)         */
+    float ms_ls_apply;      /* rank-2 gradient correction passes of the local search          */
 } admmq_stats;
 
 /* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.

@@ -35,7 +35,10 @@ class _Stats(C.Structure):
                 ("ms_admm", C.c_float), ("ms_local_search", C.c_float),
                 ("j_damp", C.c_double), ("j_damp_admm", C.c_double), ("j_damp_rtn", C.c_double),
                 ("lambda_", C.c_double), ("iters_done", C.c_int32), ("ls_moves", C.c_int32),
-                ("primal_res", C.POINTER(C.c_float)), ("code_flips", C.POINTER(C.c_int64))]
+                ("primal_res", C.POINTER(C.c_float)), ("code_flips", C.POINTER(C.c_int64)),
+                ("profile", C.c_int32), ("n_gemm", C.c_int32), ("n_tridiag", C.c_int32), ("n_project", C.c_int32),
+                ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
+                ("ms_project", C.c_float), ("ms_ls_apply", C.c_float)]
 
 
 class _LsParams(C.Structure):
@@ -130,6 +133,14 @@ class LayerStats:
     ls_moves: int = 0
     primal_res: list = field(default_factory=list)
     code_flips: list = field(default_factory=list)
+    n_gemm: int = 0
+    n_tridiag: int = 0
+    n_project: int = 0
+    n_ls_apply: int = 0
+    ms_gemm: float = 0.0
+    ms_tridiag: float = 0.0
+    ms_project: float = 0.0
+    ms_ls_apply: float = 0.0
 
 
 def _ptr(t):
@@ -184,7 +195,7 @@ class Context:
         return cnt.value
 
     def quantize_layer(self, H, W0, bits, group_size=0, sched: Schedule | None = None, want_stats=True,
-                       want_history=False):
+                       want_history=False, profile=False):
         torch = self._torch
         sched = sched or Schedule()
         n, p = W0.shape
@@ -195,6 +206,7 @@ class Context:
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
                        sched.ls_batches, sched.ls_pairs, sched.seed)
         st = _Stats()
+        st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
         flips = (C.c_int64 * sched.T)() if want_history else None
         if want_history:
@@ -207,7 +219,9 @@ class Context:
         if want_stats:
             out = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
                              st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
-                             list(res) if want_history else [], list(flips) if want_history else [])
+                             list(res) if want_history else [], list(flips) if want_history else [],
+                             st.n_gemm, st.n_tridiag, st.n_project, st.n_ls_apply, st.ms_gemm, st.ms_tridiag,
+                             st.ms_project, st.ms_ls_apply)
         return codes, scales, zeros, out
 
     def local_search(self, H, W0, bits, group_size, scales, zeros, codes, rounds=5, batches_per_round=0,

@@ -20,6 +20,50 @@ admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, floa
                               int *dev_moves, double *dev_drop, int apply);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
 
+// ---- per-launch profiler ---------------------------------------------------------------------
+int admmq_prof_begin(admmq_ctx *ctx, int tag) {
+    admmq_profiler &pf = ctx->prof;
+    if (!pf.on) return -1;
+    if (pf.count == pf.cap) {
+        const int ncap = pf.cap ? pf.cap * 2 : 1024;
+        admmq_profiler::span *ns = (admmq_profiler::span *)realloc(pf.spans, (size_t)ncap * sizeof(*ns));
+        if (!ns) return -1;
+        pf.spans = ns;
+        pf.cap = ncap;
+    }
+    admmq_profiler::span &sp = pf.spans[pf.count];
+    if (hipEventCreate(&sp.a) != hipSuccess) return -1;
+    if (hipEventCreate(&sp.b) != hipSuccess) {
+        (void)hipEventDestroy(sp.a);
+        return -1;
+    }
+    sp.tag = tag;
+    (void)hipEventRecord(sp.a, ctx->stream);
+    return pf.count++;
+}
+
+void admmq_prof_end(admmq_ctx *ctx, int span) {
+    if (span >= 0) (void)hipEventRecord(ctx->prof.spans[span].b, ctx->stream);
+}
+
+// sums and releases the recorded spans (synchronises the stream)
+static void prof_collect(admmq_ctx *ctx, float ms[ADMMQ_TAGS], int cnt[ADMMQ_TAGS]) {
+    admmq_profiler &pf = ctx->prof;
+    for (int t = 0; t < ADMMQ_TAGS; ++t) { ms[t] = 0.f; cnt[t] = 0; }
+    if (pf.count > 0) (void)hipStreamSynchronize(ctx->stream);
+    for (int i = 0; i < pf.count; ++i) {
+        float e = 0.f;
+        if (hipEventElapsedTime(&e, pf.spans[i].a, pf.spans[i].b) == hipSuccess) {
+            ms[pf.spans[i].tag] += e;
+            cnt[pf.spans[i].tag] += 1;
+        }
+        (void)hipEventDestroy(pf.spans[i].a);
+        (void)hipEventDestroy(pf.spans[i].b);
+    }
+    pf.count = 0;
+    pf.on = false;
+}
+
 // ---- arena -------------------------------------------------------------------------------------
 admmq_status admmq_arena_reserve(admmq_ctx *ctx, size_t bytes) {
     const size_t need = ctx->persist_top + admmq_align_up(bytes) + 4096;
@@ -194,12 +238,18 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
     gemm_tn_args g1 = {};
     g1.A = f.Q; g1.lda = n; g1.B = B; g1.ldb = p; g1.M = n; g1.N = p; g1.K = n;
     g1.alpha = -1.f; g1.beta = 1.f; g1.Z = C0; g1.ldz = p; g1.out = Y; g1.ldo = p; g1.split_k = 1;
+    int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
     ADMMQ_TRY(admmq_gemm_tn(ctx, g1));
+    admmq_prof_end(ctx, sp);
+    sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
     ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, F, Y));
+    admmq_prof_end(ctx, sp);
     gemm_tn_args g2 = {};
     g2.A = f.Qt; g2.lda = n; g2.B = Y; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
     g2.alpha = 1.f; g2.beta = 1.f; g2.Z = B; g2.ldz = p; g2.out = W; g2.ldo = p; g2.split_k = 1;
+    sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
     ADMMQ_TRY(admmq_gemm_tn(ctx, g2));
+    admmq_prof_end(ctx, sp);
     return ADMMQ_OK;
 }
 
@@ -323,9 +373,13 @@ extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stre
 extern "C" void admmq_destroy(admmq_ctx *ctx) {
     if (!ctx) return;
     if (ctx->device >= 0) {
+        float ms[ADMMQ_TAGS];
+        int cnt[ADMMQ_TAGS];
+        prof_collect(ctx, ms, cnt);
         (void)hipStreamSynchronize(ctx->stream);
         if (ctx->arena && ctx->arena_owned) (void)hipFree(ctx->arena);
     }
+    free(ctx->prof.spans);
     delete ctx;
 }
 
@@ -599,6 +653,10 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     const bool want = stats != nullptr;
     Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
     t_total.start();
+    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
+    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
+    prof_collect(ctx, prof_ms, prof_cnt);            // drops spans a failed earlier call may have left
+    ctx->prof.on = want && stats->profile != 0;
 
     // --- input checks on the device, before anything is written -------------------------------
     t_phase.start();
@@ -686,9 +744,11 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, W));
         }
         const bool last = t == T - 1;
+        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
         ADMMQ_TRY(admmq_k_project_dual(ctx, W, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
                                        1.0f / rf, 1.0f / (float)hrho[t + 1], (last || want_flips) ? codes : nullptr,
                                        want_flips ? 1 : 0, B, res + t, want_flips ? flips + t : nullptr));
+        admmq_prof_end(ctx, sp);
     }
     float ms_admm = t_phase.stop();
 
@@ -740,7 +800,12 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(read_back(ctx, &stats->j_damp, jd, 8));
         }
     }
+    prof_collect(ctx, prof_ms, prof_cnt);
     if (want) {
+        stats->ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       stats->n_gemm = prof_cnt[ADMMQ_TAG_GEMM];
+        stats->ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; stats->n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
+        stats->ms_project = prof_ms[ADMMQ_TAG_PROJECT]; stats->n_project = prof_cnt[ADMMQ_TAG_PROJECT];
+        stats->ms_ls_apply = prof_ms[ADMMQ_TAG_LS_APPLY]; stats->n_ls_apply = prof_cnt[ADMMQ_TAG_LS_APPLY];
         stats->ms_setup = ms_setup;
         stats->ms_factor = ms_factor;
         stats->ms_admm = ms_admm;

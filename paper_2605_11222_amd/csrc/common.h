@@ -32,8 +32,18 @@ struct admmq_factor {
     bool valid = false;
 };
 
+// Optional per-launch timing: pairs of HIP events on the context's stream, summed per tag at the end.
+struct admmq_profiler {
+    struct span { hipEvent_t a, b; int tag; };
+    span *spans = nullptr;
+    int count = 0, cap = 0;
+    bool on = false;
+};
+enum { ADMMQ_TAG_GEMM = 0, ADMMQ_TAG_TRIDIAG = 1, ADMMQ_TAG_PROJECT = 2, ADMMQ_TAG_LS_APPLY = 3, ADMMQ_TAGS = 4 };
+
 struct admmq_ctx {
     int device = 0;
+    admmq_profiler prof;
     hipStream_t stream = nullptr;
     // bump arena: [0, persist_top) holds the factorisation, [persist_top, top) transient scratch
     char *arena = nullptr;
@@ -45,6 +55,10 @@ struct admmq_ctx {
     // small pinned host buffer for scalar read-backs
     double *host_scalars = nullptr;   // 64 doubles
 };
+
+// Returns a span index (or -1 when profiling is off); call admmq_prof_end with it after the launch.
+int admmq_prof_begin(admmq_ctx *ctx, int tag);
+void admmq_prof_end(admmq_ctx *ctx, int span);
 
 static inline size_t admmq_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 

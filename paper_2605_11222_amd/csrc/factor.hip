@@ -11,6 +11,8 @@
 // matrix per step: the rank-2 (rank-1) update left pending by the previous step is applied while the
 // matrix-vector product needed by the current step is formed, so each trailing element is read and
 // written once per step.  One 64-lane wave owns one matrix row, so every reduction has a fixed order.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -263,55 +265,154 @@ __global__ void tridiag_factor_kernel(const double *__restrict__ ta, const doubl
     }
 }
 
-// S = (T + rho I)^{-1} T Y for every column; one thread per column, rows in sequence.
-//   z_i = b_{i-1} y_{i-1} + a_i y_i + b_i y_{i+1};  f_i = z_i - l_{i-1} f_{i-1};  s_i = f_i/delta_i - l_i s_{i+1}
-__global__ __launch_bounds__(64) void tridiag_apply_kernel(const double *__restrict__ ta,
-                                                           const double *__restrict__ tb,
-                                                           const double *__restrict__ dinv,
-                                                           const double *__restrict__ lfac, long n, long p,
-                                                           const float *Y, double *__restrict__ F, float *S) {
-    const long j = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= p) return;
-    double yprev = 0.0, ycur = (double)Y[j], f = 0.0, lprev = 0.0, bprev = 0.0;
-    constexpr int U = 8;
-    for (long i0 = 0; i0 < n; i0 += U) {
-        double ynext[U];
+// S = (T + rho I)^{-1} T Y, all columns.
+//   z_i = b_{i-1} y_{i-1} + a_i y_i + b_i y_{i+1}
+//   f_i = z_i - l_{i-1} f_{i-1}                         (forward recurrence)
+//   s_i = f_i / delta_i - l_i s_{i+1}                   (backward recurrence)
+// A first-order linear recurrence splits exactly: over a segment of rows a..b with incoming value c,
+//   f_i = ft_i + P_i c,  ft = the recurrence started from 0,  P_i = prod_{k=a..i} (-l_{k-1}).
+// A block owns C columns and walks the rows in tiles of TR = NS*SL rows; thread (s, c) runs the local
+// recurrence of segment s (SL rows) of column c in registers, all NS segments at once; the NS segment
+// ends are then chained (NS short steps, done redundantly by every thread, so one barrier per tile
+// suffices) and each thread corrects its own rows.  The sequential depth per tile is SL + NS instead
+// of TR.  Row coefficients, which all columns share, are staged in LDS once per tile.
+template <int C>
+__global__ __launch_bounds__(256) void tridiag_apply_split_kernel(const double *__restrict__ ta,
+                                                                  const double *__restrict__ tb,
+                                                                  const double *__restrict__ dinv,
+                                                                  const double *__restrict__ lfac, long n, long p,
+                                                                  const float *Y, double *__restrict__ F, float *S) {
+    constexpr int NS = 256 / C;               // segments per tile
+    constexpr int SL = 32;                    // rows per segment
+    constexpr int TR = NS * SL;               // rows per tile
+    __shared__ double s_a[TR], s_b[TR + 1], s_l[TR + 1], s_di[TR];
+    __shared__ double endf[2][NS][C], endP[2][NS][C];
+    const int tid = threadIdx.x;
+    const int c = tid % C, sg = tid / C;
+    const long j = (long)blockIdx.x * C + c;
+    const bool jok = j < p;
+    const long ntile = (n + TR - 1) / TR;
+
+    // ---------------- forward ----------------
+    float ycur[SL + 2], ynext[SL + 2];
+    auto load_y = [&](long t, float *dst) {
+        const long a = t * TR + (long)sg * SL;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long i = i0 + u;
-            ynext[u] = (i + 1 < n) ? (double)Y[(i + 1) * p + j] : 0.0;
+        for (int u = 0; u < SL + 2; ++u) {
+            const long i = a - 1 + u;
+            dst[u] = (jok && i >= 0 && i < n) ? Y[i * p + j] : 0.f;
         }
+    };
+    double carry = 0.0;                       // f of the row just above the current tile
+    load_y(0, ycur);
+    for (long t = 0; t < ntile; ++t) {
+        const long i0 = t * TR;
+        const int par = (int)(t & 1);
+        // stage the tile's coefficients: s_a[r] = a_i, s_b[r] = b_{i-1}, s_l[r] = l_{i-1}, i = i0 + r
+        for (int r = tid; r <= TR; r += 256) {
+            const long i = i0 + r;
+            if (r < TR) s_a[r] = i < n ? ta[i] : 0.0;
+            s_b[r] = (i >= 1 && i < n) ? tb[i - 1] : 0.0;
+            s_l[r] = (i >= 1 && i < n) ? lfac[i - 1] : 0.0;
+        }
+        __syncthreads();
+        if (t + 1 < ntile) load_y(t + 1, ynext);
+        double fl[SL], Pl[SL];
+        {
+            double f = 0.0, P = 1.0;
+            const int r0 = sg * SL;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long i = i0 + u;
-            if (i < n) {
-                const double b = (i + 1 < n) ? tb[i] : 0.0;
-                const double z = bprev * yprev + ta[i] * ycur + b * ynext[u];
-                f = z - lprev * f;
-                F[i * p + j] = f;
-                lprev = lfac[i];
-                bprev = b;
-                yprev = ycur;
-                ycur = ynext[u];
+            for (int u = 0; u < SL; ++u) {
+                const int r = r0 + u;
+                const double z = s_b[r] * (double)ycur[u] + s_a[r] * (double)ycur[u + 1] +
+                                 s_b[r + 1] * (double)ycur[u + 2];
+                const double ml = -s_l[r];
+                f = fma(ml, f, z);
+                P = ml * P;
+                fl[u] = f;
+                Pl[u] = P;
+            }
+            endf[par][sg][c] = f;
+            endP[par][sg][c] = P;
+        }
+        __syncthreads();
+        double cin = carry, run = carry;
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            if (q == sg) cin = run;
+            run = fma(endP[par][q][c], run, endf[par][q][c]);
+        }
+        carry = run;
+        {
+            const long a = i0 + (long)sg * SL;
+#pragma unroll
+            for (int u = 0; u < SL; ++u) {
+                const long i = a + u;
+                if (jok && i < n) F[i * p + j] = fma(Pl[u], cin, fl[u]);
             }
         }
+#pragma unroll
+        for (int u = 0; u < SL + 2; ++u) ycur[u] = ynext[u];
     }
-    double s = 0.0;
-    for (long i1 = n; i1 > 0; i1 -= U) {
-        double fv[U];
+
+    // ---------------- backward ----------------
+    __syncthreads();
+    double gcur[SL], gnext[SL];
+    auto load_f = [&](long t, double *dst) {
+        const long a = t * TR + (long)sg * SL;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long i = i1 - 1 - u;
-            fv[u] = i >= 0 ? F[i * p + j] : 0.0;
+        for (int u = 0; u < SL; ++u) {
+            const long i = a + u;
+            dst[u] = (jok && i < n) ? F[i * p + j] : 0.0;
         }
+    };
+    carry = 0.0;                              // s of the row just below the current tile
+    load_f(ntile - 1, gcur);
+    for (long t = ntile - 1; t >= 0; --t) {
+        const long i0 = t * TR;
+        const int par = (int)(t & 1);
+        // s_l[r] = l_i, s_di[r] = 1/delta_i, i = i0 + r
+        for (int r = tid; r < TR; r += 256) {
+            const long i = i0 + r;
+            s_l[r] = i < n ? lfac[i] : 0.0;
+            s_di[r] = i < n ? dinv[i] : 0.0;
+        }
+        __syncthreads();
+        if (t > 0) load_f(t - 1, gnext);
+        double sl[SL], Pl[SL];
+        {
+            double sv = 0.0, P = 1.0;
+            const int r0 = sg * SL;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long i = i1 - 1 - u;
-            if (i >= 0) {
-                s = fv[u] * dinv[i] - lfac[i] * s;
-                S[i * p + j] = (float)s;
+            for (int u = SL - 1; u >= 0; --u) {
+                const int r = r0 + u;
+                const double ml = -s_l[r];
+                sv = fma(ml, sv, gcur[u] * s_di[r]);
+                P = ml * P;
+                sl[u] = sv;
+                Pl[u] = P;
+            }
+            endf[par][sg][c] = sv;
+            endP[par][sg][c] = P;
+        }
+        __syncthreads();
+        double cin = carry, run = carry;
+#pragma unroll
+        for (int q = NS - 1; q >= 0; --q) {
+            if (q == sg) cin = run;
+            run = fma(endP[par][q][c], run, endf[par][q][c]);
+        }
+        carry = run;
+        {
+            const long a = i0 + (long)sg * SL;
+#pragma unroll
+            for (int u = 0; u < SL; ++u) {
+                const long i = a + u;
+                if (jok && i < n) S[i * p + j] = (float)fma(Pl[u], cin, sl[u]);
             }
         }
+#pragma unroll
+        for (int u = 0; u < SL; ++u) gcur[u] = gnext[u];
     }
 }
 
@@ -387,8 +488,26 @@ admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const doub
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
                                    const double *lfac, int64_t n, int64_t p, const float *Y, double *F,
                                    float *S) {
-    hipLaunchKernelGGL(tridiag_apply_kernel, dim3(blocks_for(p, 64)), dim3(64), 0, ctx->stream, ta, tb, dinv, lfac,
-                       (long)n, (long)p, Y, F, S);
+    // the widest column strip that still gives every CU a block
+    int C = 64;
+    if ((p + 63) / 64 < 256) C = 32;
+    if ((p + 31) / 32 < 256) C = 16;
+    static int forced = -1;
+    if (forced < 0) {
+        const char *e = getenv("ADMMQ_TRIDIAG_COLS");
+        forced = e ? atoi(e) : 0;
+    }
+    if (forced == 16 || forced == 32 || forced == 64) C = forced;
+    const unsigned nb = (unsigned)((p + C - 1) / C);
+    if (C == 64)
+        hipLaunchKernelGGL(tridiag_apply_split_kernel<64>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
+                           (long)n, (long)p, Y, F, S);
+    else if (C == 32)
+        hipLaunchKernelGGL(tridiag_apply_split_kernel<32>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
+                           (long)n, (long)p, Y, F, S);
+    else
+        hipLaunchKernelGGL(tridiag_apply_split_kernel<16>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
+                           (long)n, (long)p, Y, F, S);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

@@ -214,8 +214,10 @@ admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, floa
                            (long)p, levels, (long)g, scales, pairs, npairs, partial, chunks, totals_or_null, choice,
                            dstep, dev_moves, dev_drop);
         dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
+        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
         hipLaunchKernelGGL(ls_apply_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, (long)n, (long)p, choice,
                            dstep);
+        admmq_prof_end(ctx, sp);
     }
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;

@@ -7,6 +7,8 @@
 //   xq = k*delta; xq = xq+z0; Dn = d[i]*xq; r = W-Dn; Vn = V + rho*r; Bn = Dn - Vn*inv_rho_next
 // inv_rho, inv_d, inv_delta are fp32 reciprocals formed once with IEEE division (inv_delta = 0 for a
 // group whose scale is 0, which pins its codes to 0).
+#include <stdlib.h>
+
 #include "common.h"
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -75,7 +77,7 @@ __global__ void recip_kernel(const float *__restrict__ x, float *__restrict__ in
 // ---- fused projection + dual + residual -------------------------------------------------------
 // Each thread owns 4 consecutive columns and walks ROWS rows of one group, so the grid parameters of
 // its columns are read once.  grid: (ceil(p4 / 256), ceil(n / ROWS)), block 256.
-constexpr int PD_ROWS = 16;
+constexpr int PD_ROWS = 32;
 
 template <bool CODES, bool FLIPS, bool VEC>
 __global__ __launch_bounds__(256) void project_dual_kernel(
@@ -83,17 +85,17 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
     const float *__restrict__ inv_d, float levels, long g, const float *__restrict__ scales,
     const float *__restrict__ inv_scales, const float *__restrict__ zeros, float rho, float inv_rho,
     float inv_rho_next, uint8_t *__restrict__ codes, float *__restrict__ B, double *__restrict__ res_sq,
-    unsigned long long *__restrict__ flips) {
+    unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal) {
     __shared__ double sh[4];
     const long c0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
-    const long row0 = (long)blockIdx.y * PD_ROWS;      // g is a multiple of PD_ROWS or rows are checked
+    const long row0 = (long)blockIdx.y * rows_per_block;
     float acc = 0.f;
     unsigned nflip = 0;
     if (c0 < p) {
         const int nc = (int)min(4L, p - c0);
         long grp = -1;
         float dl[4], idl[4], z0[4];
-        for (int r4 = 0; r4 < PD_ROWS; r4 += 4) {
+        for (int r4 = 0; r4 < rows_per_block; r4 += 4) {
             // stage 1: issue the loads of up to 4 rows before any arithmetic depends on them
             float w[4][4], v[4][4];
 #pragma unroll
@@ -102,8 +104,14 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                 const long off = i * p + c0;
                 if (i < n) {
                     if (VEC) {
-                        floatx4 tw = *(const floatx4 *)(W + off);
-                        floatx4 tv = *(const floatx4 *)(V + off);
+                        floatx4 tw, tv;
+                        if (nontemporal) {
+                            tw = __builtin_nontemporal_load((const floatx4 *)(W + off));
+                            tv = __builtin_nontemporal_load((const floatx4 *)(V + off));
+                        } else {
+                            tw = *(const floatx4 *)(W + off);
+                            tv = *(const floatx4 *)(V + off);
+                        }
                         w[rr][0] = tw.x; w[rr][1] = tw.y; w[rr][2] = tw.z; w[rr][3] = tw.w;
                         v[rr][0] = tv.x; v[rr][1] = tv.y; v[rr][2] = tv.z; v[rr][3] = tv.w;
                     } else {
@@ -157,8 +165,13 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                 if (VEC) {
                     floatx4 ov = {vn[0], vn[1], vn[2], vn[3]};
                     floatx4 ob = {bn[0], bn[1], bn[2], bn[3]};
-                    *(floatx4 *)(V + off) = ov;
-                    *(floatx4 *)(B + off) = ob;
+                    if (nontemporal) {
+                        __builtin_nontemporal_store(ov, (floatx4 *)(V + off));
+                        __builtin_nontemporal_store(ob, (floatx4 *)(B + off));
+                    } else {
+                        *(floatx4 *)(V + off) = ov;
+                        *(floatx4 *)(B + off) = ob;
+                    }
                     if (CODES) {
                         uint32_t packed = (uint32_t)kq[0] | ((uint32_t)kq[1] << 8) | ((uint32_t)kq[2] << 16) |
                                           ((uint32_t)kq[3] << 24);
@@ -323,14 +336,23 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
                                   double *dev_res_sq, unsigned long long *dev_flips) {
     const long p4 = (p + 3) / 4;
-    dim3 block(256), grid((unsigned)((p4 + 255) / 256), (unsigned)((n + PD_ROWS - 1) / PD_ROWS));
+    static int rows_cfg = -1, nt_cfg = 0;
+    if (rows_cfg < 0) {
+        const char *e = getenv("ADMMQ_PD_ROWS");
+        rows_cfg = e ? atoi(e) : PD_ROWS;
+        if (rows_cfg < 4 || rows_cfg % 4 != 0 || rows_cfg > 256) rows_cfg = PD_ROWS;
+        const char *e2 = getenv("ADMMQ_PD_NT");
+        nt_cfg = e2 ? atoi(e2) : 0;
+    }
+    const int rows_per_block = rows_cfg;
+    dim3 block(256), grid((unsigned)((p4 + 255) / 256), (unsigned)((n + rows_per_block - 1) / rows_per_block));
     const bool vec = (p % 4 == 0) && (((uintptr_t)W | (uintptr_t)V | (uintptr_t)B_out) % 16 == 0) &&
                      (codes == nullptr || (uintptr_t)codes % 4 == 0);
     const float levels = (float)((1 << bits) - 1);
 #define ADMMQ_PD(C, F, VV)                                                                                   \
     hipLaunchKernelGGL((project_dual_kernel<C, F, VV>), grid, block, 0, ctx->stream, W, V, (long)n, (long)p, d, \
                        inv_d, levels, (long)g, scales, inv_scales, zeros, rho, inv_rho, inv_rho_next, codes,  \
-                       B_out, dev_res_sq, dev_flips)
+                       B_out, dev_res_sq, dev_flips, rows_per_block, nt_cfg)
     if (codes && count_flips) { if (vec) ADMMQ_PD(true, true, true); else ADMMQ_PD(true, true, false); }
     else if (codes)           { if (vec) ADMMQ_PD(true, false, true); else ADMMQ_PD(true, false, false); }
     else                      { if (vec) ADMMQ_PD(false, false, true); else ADMMQ_PD(false, false, false); }
