@@ -14,10 +14,13 @@ admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double
                                double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
                                double *tb);
 int admmq_ls_chunks(int64_t p);
+int admmq_ls_defer();
 admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
                               int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs,
-                              int npairs, float *partial, float *totals_or_null, int32_t *choice, float *dstep,
-                              int *dev_moves, double *dev_drop, int apply);
+                              int npairs, float *partial, int32_t *pend_idx, float *pend_d, int slot,
+                              int32_t *choice, int *dev_moves, double *dev_drop, int apply);
+admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, int64_t n, int64_t p,
+                              const int32_t *pend_idx, const float *pend_d, int count);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
 
 // ---- per-launch profiler ---------------------------------------------------------------------
@@ -123,8 +126,8 @@ size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
 size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
     const size_t np = (size_t)n * (size_t)p;
     return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
-           admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) + admmq_align_up((size_t)2 * p * 4) +
-           admmq_align_up((size_t)pairs_per_batch * 4) + 65536;
+           admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
+           admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) + 65536;
 }
 
 admmq_status read_back(admmq_ctx *ctx, void *host, const void *dev, size_t bytes) {
@@ -286,14 +289,16 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     if (drop_out) *drop_out = 0.0;
     if (plan.rounds <= 0 || n < 2) return ADMMQ_OK;
     const size_t total = (size_t)plan.rounds * plan.batches * plan.pairs;
-    float *E = nullptr, *G = nullptr, *partial = nullptr, *dstep = nullptr;
-    int32_t *pairs = nullptr, *choice = nullptr;
+    float *E = nullptr, *G = nullptr, *partial = nullptr, *pend_d = nullptr;
+    int32_t *pairs = nullptr, *choice = nullptr, *pend_idx = nullptr;
+    const int K = admmq_ls_defer();
     double *scal = nullptr;
     ADMMQ_TRY(take(ctx, E, (size_t)n * p));
     ADMMQ_TRY(take(ctx, G, (size_t)n * p));
     ADMMQ_TRY(take(ctx, pairs, total * 2));
     ADMMQ_TRY(take(ctx, partial, (size_t)plan.pairs * admmq_ls_chunks(p)));
-    ADMMQ_TRY(take(ctx, dstep, (size_t)2 * p));
+    ADMMQ_TRY(take(ctx, pend_d, (size_t)2 * K * p));
+    ADMMQ_TRY(take(ctx, pend_idx, (size_t)2 * K));
     ADMMQ_TRY(take(ctx, choice, 4));
     ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double), scal[1] reinterpreted: moves (int)
     int *dev_moves = (int *)(scal + 1);
@@ -328,8 +333,11 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     for (int r = 0; r < plan.rounds; ++r) {
         for (int m = 0; m < plan.batches; ++m) {
             const int32_t *bp = pairs + ((size_t)r * plan.batches + m) * plan.pairs * 2;
+            const int slot = m % K;
             ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, bp, plan.pairs, partial,
-                                       nullptr, choice, dstep, dev_moves, scal, 1));
+                                       pend_idx, pend_d, slot, choice, dev_moves, scal, 1));
+            if (slot == K - 1 || m == plan.batches - 1)
+                ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, n, p, pend_idx, pend_d, slot + 1));
         }
         double host[2];
         ADMMQ_TRY(read_back(ctx, host, scal, 16));
@@ -592,7 +600,7 @@ extern "C" admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double
     float *partial = nullptr;
     ADMMQ_TRY(take(ctx, partial, (size_t)npairs * chunks));
     ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, (float *)G, (uint8_t *)codes, n, p, bits, g, scales, pairs,
-                               npairs, partial, nullptr, nullptr, nullptr, nullptr, nullptr, 0));
+                               npairs, partial, nullptr, nullptr, 0, nullptr, nullptr, nullptr, 0));
     ADMMQ_TRY(admmq_k_ls_totals(ctx, partial, chunks, npairs, totals));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;

@@ -4,10 +4,14 @@
 //   evaluate : one block per (pair, column chunk); every column takes the best feasible sign
 //              combination of (+-delta_i1, +-delta_i2) by eq. 11 if it lowers the loss; the chunk's
 //              summed gain goes to partial[pair][chunk]
-//   select   : one block; sums the chunks in a fixed order, picks the largest total (lowest slot on
-//              ties), and for the winner writes the per-column steps dstep[2][p] and the new codes
-//   apply    : streams G once:  G[i][j] -= H'[i][i1] dstep1[j] + H'[i][i2] dstep2[j]
-// Nothing is applied when the best total is not positive (the apply kernel returns at once).
+//   plan     : every block sums the chunks in a fixed order and picks the largest total (lowest slot
+//              on ties) - the same winner in every block - then writes, for its own columns, the new
+//              codes and the applied steps of the winner into slot (batch mod K) of a pending list
+//   flush    : every K batches G is streamed ONCE for all pending pairs:
+//              G[i][j] -= sum_k H'[i][a_k] d1_k[j] + H'[i][b_k] d2_k[j]          (rank-2K correction)
+// Between flushes the two gradient rows a candidate pair needs are corrected on the fly from the
+// pending list, so every evaluation sees the gradient of the current codes (Sec. 3.5 step (v)) while
+// the n x p array is read and written once per K applied pairs instead of once per pair.
 #include "common.h"
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -53,20 +57,57 @@ __device__ inline float wave_sum_f(float v) {
     return v;
 }
 
+constexpr int LS_K = 16;          // pending pairs between two passes over G
+
+// coefficients of the pending corrections for gradient rows i1 and i2:
+//   coef[k][0..3] = H'[i1][a_k], H'[i1][b_k], H'[i2][a_k], H'[i2][b_k]   (0 for an empty slot)
+__device__ inline void load_pending_coef(const float *__restrict__ H, float lambda, long n, long i1, long i2,
+                                         const int32_t *__restrict__ pend_idx, int npend, float (*coef)[4]) {
+    for (int e = threadIdx.x; e < npend * 4; e += blockDim.x) {
+        const int k = e >> 2, w = e & 3;
+        const long row = (w & 2) ? i2 : i1;
+        const long col = pend_idx[2 * k + (w & 1)];
+        float h = 0.f;
+        if (pend_idx[2 * k] >= 0) {
+            h = H[row * n + col];
+            if (row == col) h += lambda;
+        }
+        coef[k][w] = h;
+    }
+}
+
+// gradient entries of rows i1, i2 at column j for the CURRENT codes
+__device__ inline void current_g(const float *__restrict__ G, long p, long i1, long i2, long j,
+                                 const float *__restrict__ pend_d, int npend, const float (*coef)[4], float &g1,
+                                 float &g2) {
+    g1 = G[i1 * p + j];
+    g2 = G[i2 * p + j];
+    for (int k = 0; k < npend; ++k) {
+        const float d1 = pend_d[(long)(2 * k) * p + j], d2 = pend_d[(long)(2 * k + 1) * p + j];
+        g1 -= coef[k][0] * d1 + coef[k][1] * d2;
+        g2 -= coef[k][2] * d1 + coef[k][3] * d2;
+    }
+}
+
 // grid (chunks, npairs), block 256
 __global__ __launch_bounds__(256) void ls_evaluate_kernel(const float *__restrict__ H, float lambda,
                                                           const float *__restrict__ G,
                                                           const uint8_t *__restrict__ codes, long n, long p,
                                                           int levels, long g, const float *__restrict__ scales,
                                                           const int32_t *__restrict__ pairs,
+                                                          const int32_t *__restrict__ pend_idx,
+                                                          const float *__restrict__ pend_d, int npend,
                                                           float *__restrict__ partial, int chunks) {
     __shared__ float sh[4];
+    __shared__ float coef[LS_K][4];
     const int pr = blockIdx.y;
     const long i1 = pairs[2 * pr], i2 = pairs[2 * pr + 1];
     if (i1 < 0 || i2 < 0 || i1 >= n || i2 >= n || i1 == i2) {      // not a row pair: contributes nothing
         if (threadIdx.x == 0) partial[(long)pr * chunks + blockIdx.x] = 0.f;
         return;
     }
+    load_pending_coef(H, lambda, n, i1, i2, pend_idx, npend, coef);
+    __syncthreads();
     const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
     const float *s1 = scales + (i1 / g) * p, *s2 = scales + (i2 / g) * p;
     float sum = 0.f;
@@ -74,8 +115,10 @@ __global__ __launch_bounds__(256) void ls_evaluate_kernel(const float *__restric
     for (int q = 0; q < 4; ++q) {
         const long j = jbase + q * 256 + threadIdx.x;
         if (j < p) {
-            PairEval e = eval_column(G[i1 * p + j], G[i2 * p + j], codes[i1 * p + j], codes[i2 * p + j], s1[j],
-                                     s2[j], h11, h22, h12, levels);
+            float g1, g2;
+            current_g(G, p, i1, i2, j, pend_d, npend, coef, g1, g2);
+            PairEval e = eval_column(g1, g2, codes[i1 * p + j], codes[i2 * p + j], s1[j], s2[j], h11, h22, h12,
+                                     levels);
             sum += e.gain;
         }
     }
@@ -86,25 +129,25 @@ __global__ __launch_bounds__(256) void ls_evaluate_kernel(const float *__restric
     if (threadIdx.x == 0) partial[(long)pr * chunks + blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
-// one block of 256 threads
-__global__ __launch_bounds__(256) void ls_select_kernel(const float *__restrict__ H, float lambda,
-                                                        const float *__restrict__ G, uint8_t *__restrict__ codes,
-                                                        long n, long p, int levels, long g,
-                                                        const float *__restrict__ scales,
-                                                        const int32_t *__restrict__ pairs, int npairs,
-                                                        const float *__restrict__ partial, int chunks,
-                                                        float *__restrict__ totals, int32_t *__restrict__ choice,
-                                                        float *__restrict__ dstep, int *__restrict__ moves,
-                                                        double *__restrict__ drop) {
+// grid ceil(p/256), block 256.  Every block finds the same winner; block 0 records it.
+__global__ __launch_bounds__(256) void ls_plan_kernel(const float *__restrict__ H, float lambda,
+                                                      const float *__restrict__ G, uint8_t *__restrict__ codes,
+                                                      long n, long p, int levels, long g,
+                                                      const float *__restrict__ scales,
+                                                      const int32_t *__restrict__ pairs, int npairs,
+                                                      const float *__restrict__ partial, int chunks,
+                                                      int32_t *__restrict__ pend_idx, float *__restrict__ pend_d,
+                                                      int slot, int32_t *__restrict__ choice,
+                                                      int *__restrict__ moves, double *__restrict__ drop) {
     __shared__ float stot[256];
     __shared__ int sidx[256];
+    __shared__ float coef[LS_K][4];
     const int tid = threadIdx.x;
     float best = 0.f;
     int bidx = -1;
     for (int pr = tid; pr < npairs; pr += 256) {
         float t = 0.f;
         for (int c = 0; c < chunks; ++c) t += partial[(long)pr * chunks + c];
-        if (totals) totals[pr] = t;
         if (t > best) {            // strictly larger: within a thread slots come in increasing order
             best = t;
             bidx = pr;
@@ -127,72 +170,101 @@ __global__ __launch_bounds__(256) void ls_select_kernel(const float *__restrict_
     }
     const int win = sidx[0];
     const float wtot = stot[0];
-    if (tid == 0) {
+    if (blockIdx.x == 0 && tid == 0) {
         choice[0] = win;
         choice[1] = win >= 0 ? pairs[2 * win] : -1;
         choice[2] = win >= 0 ? pairs[2 * win + 1] : -1;
+        pend_idx[2 * slot] = win >= 0 ? pairs[2 * win] : -1;
+        pend_idx[2 * slot + 1] = win >= 0 ? pairs[2 * win + 1] : -1;
         if (win >= 0) {
             *moves += 1;
             *drop += (double)wtot;
         }
     }
-    if (win < 0) return;
-    const long i1 = pairs[2 * win], i2 = pairs[2 * win + 1];
-    const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
-    const float *s1 = scales + (i1 / g) * p, *s2 = scales + (i2 / g) * p;
-    for (long j = tid; j < p; j += 256) {
-        const int k1 = codes[i1 * p + j], k2 = codes[i2 * p + j];
-        PairEval e = eval_column(G[i1 * p + j], G[i2 * p + j], k1, k2, s1[j], s2[j], h11, h22, h12, levels);
-        float d1 = 0.f, d2 = 0.f;
-        if (e.combo >= 0) {
-            const int sg1 = (e.combo & 2) ? -1 : 1, sg2 = (e.combo & 1) ? -1 : 1;
-            d1 = (float)sg1 * s1[j];
-            d2 = (float)sg2 * s2[j];
-            codes[i1 * p + j] = (uint8_t)(k1 + sg1);
-            codes[i2 * p + j] = (uint8_t)(k2 + sg2);
+    if (win < 0) {
+        // empty slot: zero steps, so that a later on-the-fly correction reads finite values
+        const long j = (long)blockIdx.x * 256 + tid;
+        if (j < p) {
+            pend_d[(long)(2 * slot) * p + j] = 0.f;
+            pend_d[(long)(2 * slot + 1) * p + j] = 0.f;
         }
-        dstep[j] = d1;
-        dstep[p + j] = d2;
+        return;
     }
+    const long i1 = pairs[2 * win], i2 = pairs[2 * win + 1];
+    load_pending_coef(H, lambda, n, i1, i2, pend_idx, slot, coef);     // slots before this one
+    __syncthreads();
+    const long j = (long)blockIdx.x * 256 + tid;
+    if (j >= p) return;
+    const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
+    const float sc1 = scales[(i1 / g) * p + j], sc2 = scales[(i2 / g) * p + j];
+    const int k1 = codes[i1 * p + j], k2 = codes[i2 * p + j];
+    float g1, g2;
+    current_g(G, p, i1, i2, j, pend_d, slot, coef, g1, g2);
+    PairEval e = eval_column(g1, g2, k1, k2, sc1, sc2, h11, h22, h12, levels);
+    float d1 = 0.f, d2 = 0.f;
+    if (e.combo >= 0) {
+        const int sg1 = (e.combo & 2) ? -1 : 1, sg2 = (e.combo & 1) ? -1 : 1;
+        d1 = (float)sg1 * sc1;
+        d2 = (float)sg2 * sc2;
+        codes[i1 * p + j] = (uint8_t)(k1 + sg1);
+        codes[i2 * p + j] = (uint8_t)(k2 + sg2);
+    }
+    pend_d[(long)(2 * slot) * p + j] = d1;
+    pend_d[(long)(2 * slot + 1) * p + j] = d2;
 }
 
-// grid (ceil(p/1024), ceil(n/8)), block 256: each thread 4 columns x 8 rows
-__global__ __launch_bounds__(256) void ls_apply_kernel(const float *__restrict__ H, float lambda,
+// grid (ceil(p/1024), ceil(n/8)), block 256: each thread 4 columns x 8 rows; applies `count` slots
+__global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__ H, float lambda,
                                                        float *__restrict__ G, long n, long p,
-                                                       const int32_t *__restrict__ choice,
-                                                       const float *__restrict__ dstep) {
-    if (choice[0] < 0) return;
-    const long i1 = choice[1], i2 = choice[2];
+                                                       const int32_t *__restrict__ pend_idx,
+                                                       const float *__restrict__ pend_d, int count) {
     const long j0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
     if (j0 >= p) return;
-    float d1[4], d2[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        d1[c] = j0 + c < p ? dstep[j0 + c] : 0.f;
-        d2[c] = j0 + c < p ? dstep[p + j0 + c] : 0.f;
-    }
-    const bool vec = (p % 4 == 0);
     const long r0 = (long)blockIdx.y * 8;
+    float acc[8][4];
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
+    bool any = false;
+    for (int k = 0; k < count; ++k) {
+        const long a = pend_idx[2 * k], b = pend_idx[2 * k + 1];
+        if (a < 0) continue;
+        any = true;
+        float d1[4], d2[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            d1[c] = j0 + c < p ? pend_d[(long)(2 * k) * p + j0 + c] : 0.f;
+            d2[c] = j0 + c < p ? pend_d[(long)(2 * k + 1) * p + j0 + c] : 0.f;
+        }
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            const long i = r0 + rr;
+            if (i < n) {
+                // column a of the symmetric H' read as row a
+                float c1 = H[a * n + i], c2 = H[b * n + i];
+                if (i == a) c1 += lambda;
+                if (i == b) c2 += lambda;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[rr][c] += c1 * d1[c] + c2 * d2[c];
+            }
+        }
+    }
+    if (!any) return;
+    const bool vec = (p % 4 == 0);
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) {
         const long i = r0 + rr;
         if (i >= n) break;
-        // column i1 of the symmetric H' read as row i1
-        float c1 = H[i1 * n + i], c2 = H[i2 * n + i];
-        if (i == i1) c1 += lambda;
-        if (i == i2) c2 += lambda;
         float *row = G + i * p + j0;
         if (vec) {
             floatx4 gq = *(floatx4 *)row;
-            gq.x -= c1 * d1[0] + c2 * d2[0];
-            gq.y -= c1 * d1[1] + c2 * d2[1];
-            gq.z -= c1 * d1[2] + c2 * d2[2];
-            gq.w -= c1 * d1[3] + c2 * d2[3];
+            gq.x -= acc[rr][0]; gq.y -= acc[rr][1]; gq.z -= acc[rr][2]; gq.w -= acc[rr][3];
             *(floatx4 *)row = gq;
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (j0 + c < p) row[c] -= c1 * d1[c] + c2 * d2[c];
+                if (j0 + c < p) row[c] -= acc[rr][c];
         }
     }
 }
@@ -200,25 +272,36 @@ __global__ __launch_bounds__(256) void ls_apply_kernel(const float *__restrict__
 }  // namespace
 
 int admmq_ls_chunks(int64_t p) { return (int)((p + LS_CHUNK - 1) / LS_CHUNK); }
+int admmq_ls_defer() { return LS_K; }
 
+// One batch: evaluate the candidate pairs against the current codes, then (if `apply`) record the best
+// one in pending slot `slot` (= batch index mod K).  The caller flushes after slot K-1 and at the end.
 admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
                               int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs,
-                              int npairs, float *partial, float *totals_or_null, int32_t *choice, float *dstep,
-                              int *dev_moves, double *dev_drop, int apply) {
+                              int npairs, float *partial, int32_t *pend_idx, float *pend_d, int slot,
+                              int32_t *choice, int *dev_moves, double *dev_drop, int apply) {
     const int chunks = admmq_ls_chunks(p);
     const int levels = (1 << bits) - 1;
     hipLaunchKernelGGL(ls_evaluate_kernel, dim3((unsigned)chunks, (unsigned)npairs), dim3(256), 0, ctx->stream, H,
-                       lambda, G, codes, (long)n, (long)p, levels, (long)g, scales, pairs, partial, chunks);
+                       lambda, G, codes, (long)n, (long)p, levels, (long)g, scales, pairs, pend_idx, pend_d, slot,
+                       partial, chunks);
     if (apply) {
-        hipLaunchKernelGGL(ls_select_kernel, dim3(1), dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n,
-                           (long)p, levels, (long)g, scales, pairs, npairs, partial, chunks, totals_or_null, choice,
-                           dstep, dev_moves, dev_drop);
-        dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
-        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
-        hipLaunchKernelGGL(ls_apply_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, (long)n, (long)p, choice,
-                           dstep);
-        admmq_prof_end(ctx, sp);
+        hipLaunchKernelGGL(ls_plan_kernel, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, ctx->stream, H, lambda, G,
+                           codes, (long)n, (long)p, levels, (long)g, scales, pairs, npairs, partial, chunks, pend_idx,
+                           pend_d, slot, choice, dev_moves, dev_drop);
     }
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, int64_t n, int64_t p,
+                              const int32_t *pend_idx, const float *pend_d, int count) {
+    if (count <= 0) return ADMMQ_OK;
+    dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
+    const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
+    hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, (long)n, (long)p, pend_idx,
+                       pend_d, count);
+    admmq_prof_end(ctx, sp);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
