@@ -1,0 +1,112 @@
+"""GPU parity at the full sizes of the 4096-wide workloads, in the launch configuration bench.py times.
+
+The float64 oracle cannot run 4096 x 4096 x 200 iterations in a test, so:
+  * Hessian (all 262144 tokens): sampled entries, each computed in float64 from the same bf16 bits;
+  * layer solver: the problem separates over output columns (Sec. 3.5 "Closed-form cost"; eqs. 7-9 act column by
+    column), so the oracle runs the whole algorithm on a 32-column slice as its own problem and the GPU does the
+    same; the GPU's full-width run must reproduce its own slice run on those columns (up to near-midpoint
+    roundings), and its reported objective must equal a float64 recomputation from the returned codes.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import admmq_oracle as orc
+from gpu_util import to_dev, bf16_bits_to_dev
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+OBJ_TOL = 5e-3
+SLICE = 32
+H_TOKENS = 16384          # tokens behind the Hessian of the layer tests (the oracle forms it in float64)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_11222_amd as admmq
+    c = admmq.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def hessian_16k():
+    cfg = si.CONFIGS["cfg2"]
+    chunks = [si.chunk_as_f64(cfg, xc) for _, xc in si.iter_x_chunks(cfg, H_TOKENS)]
+    H64 = orc.hessian(chunks)
+    return H64.astype(np.float32)
+
+
+def test_hessian_full_token_count_sampled_entries(ctx):
+    cfg = si.CONFIGS["cfg2"]
+    n = cfg.n
+    rng = np.random.default_rng(123)
+    scales = si.channel_scales(cfg.seed, n, cfg.n_outliers)
+    big = np.argsort(scales)[-4:]                       # outlier channels
+    ii = np.concatenate([rng.integers(0, n, 40), big, big, [0, n - 1, 255, 256]])
+    jj = np.concatenate([rng.integers(0, n, 40), big, big[::-1], [0, n - 1, 256, 255]])
+    want = np.zeros(len(ii))
+    X = torch.empty((cfg.tokens, n), dtype=torch.bfloat16, device="cuda")
+    row = 0
+    for c, xc in si.iter_x_chunks(cfg):
+        x64 = si.chunk_as_f64(cfg, xc)
+        want += np.einsum("rk,rk->k", x64[:, ii], x64[:, jj])
+        X[row:row + xc.shape[0]] = bf16_bits_to_dev(xc)
+        row += xc.shape[0]
+        if c % 16 == 0:
+            print(f"chunk {c}", flush=True)
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    assert ctx.accumulate_hessian(H, X) == cfg.tokens          # one call, as bench.py does
+    torch.cuda.synchronize()
+    Hg = H.cpu().numpy().astype(np.float64)
+    assert np.array_equal(Hg, Hg.T)
+    got = Hg[ii, jj]
+    diag = np.sqrt(Hg[ii, ii] * Hg[jj, jj])
+    assert np.max(np.abs(got - want) / diag) < 2e-6 * np.sqrt(cfg.tokens / 16) / 8
+    print("max scaled Hessian error", np.max(np.abs(got - want) / diag))
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
+    import paper_2605_11222_amd as admmq
+    cfg = si.CONFIGS[name]
+    H32 = hessian_16k
+    W0 = si.layer_weights(cfg)
+    Hd_, W0d = to_dev(H32), to_dev(W0)
+    g = cfg.group_size
+    # --- ADMM only: full width on the GPU reproduces its own slice run (column separability) ----------
+    s0 = admmq.Schedule(T=cfg.T, ls_rounds=0)
+    full_codes, scales, zeros, st_full = ctx.quantize_layer(Hd_, W0d, cfg.bits, g, s0)
+    W0s = np.ascontiguousarray(W0[:, :SLICE])
+    sl_codes, sl_scales, sl_zeros, st_sl = ctx.quantize_layer(Hd_, to_dev(W0s), cfg.bits, g, s0)
+    fc, sc = full_codes.cpu().numpy()[:, :SLICE], sl_codes.cpu().numpy()
+    assert np.array_equal(scales.cpu().numpy()[:, :SLICE], sl_scales.cpu().numpy())
+    mismatch = np.mean(fc != sc)
+    print(f"{name}: full-width vs slice code mismatch {mismatch:.2e}")
+    assert mismatch < 2e-3
+    # --- reported objective == float64 recomputation from the returned codes ------------------------------
+    gg = cfg.n if g == 0 else g
+    k = full_codes.cpu().numpy().astype(np.float64)
+    Wq = np.repeat(zeros.cpu().numpy().astype(np.float64), gg, 0) + k * np.repeat(scales.cpu().numpy().astype(np.float64), gg, 0)
+    E = Wq - W0.astype(np.float64)
+    H64 = H32.astype(np.float64)
+    j64 = float(np.sum(E * (H64 @ E))) + st_full.lam * float(np.sum(E * E))
+    assert st_full.j_damp_admm == pytest.approx(j64, rel=1e-4)
+    assert st_full.j_damp_admm <= st_full.j_damp_rtn
+    # --- the oracle on the slice, whole algorithm incl. local search ---------------------------------------
+    ls_rounds = 2
+    ref = orc.quantize_layer(H64, W0s.astype(np.float64), cfg.bits, g, T=cfg.T, ls_rounds=ls_rounds, seed=cfg.seed)
+    s1 = admmq.Schedule(T=cfg.T, ls_rounds=ls_rounds, seed=cfg.seed)
+    codes, _, _, st = ctx.quantize_layer(Hd_, to_dev(W0s), cfg.bits, g, s1)
+    print(f"{name} slice: rtn {st.j_damp_rtn:.6g}/{ref.j_damp_rtn:.6g} admm {st.j_damp_admm:.6g}/{ref.j_damp_admm:.6g} "
+          f"final {st.j_damp:.6g}/{ref.j_damp:.6g} moves {st.ls_moves}/{ref.ls.moves} "
+          f"code mismatch {np.mean(codes.cpu().numpy() != ref.codes):.2e}")
+    assert st.j_damp_rtn == pytest.approx(ref.j_damp_rtn, rel=1e-4)
+    assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+    assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    # codes themselves may differ: one near-midpoint rounding that falls the other way (fp32 / float64) changes
+    # the later trajectory; both end points are valid and their objectives agree (asserted above)
+    print(f"{name} slice: ADMM codes differing from the oracle's: {np.mean(sc != ref.admm.codes):.3f}")
