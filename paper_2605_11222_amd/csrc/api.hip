@@ -13,6 +13,7 @@ admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double l
 admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double lambda, const float *d,
                                double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
                                double *tb);
+size_t admmq_householder_scratch_doubles(int64_t n);
 int admmq_ls_chunks(int64_t p);
 int admmq_ls_defer();
 admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
@@ -116,7 +117,7 @@ size_t factor_persist_bytes(int64_t n) {
 }
 size_t factor_transient_bytes(int64_t n) {
     const size_t N = (size_t)n;
-    return 2 * admmq_align_up(N * N * 8) + admmq_align_up(8 * N * 8) + 4096;
+    return 2 * admmq_align_up(N * N * 8) + admmq_align_up(admmq_householder_scratch_doubles(n) * 8) + 4096;
 }
 size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
     const size_t np = (size_t)n * (size_t)p;
@@ -224,7 +225,7 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
     double *A64 = nullptr, *R64 = nullptr, *vecs = nullptr;
     ADMMQ_TRY(take(ctx, A64, (size_t)n * n));
     ADMMQ_TRY(take(ctx, R64, (size_t)n * n));
-    ADMMQ_TRY(take(ctx, vecs, (size_t)8 * n));
+    ADMMQ_TRY(take(ctx, vecs, admmq_householder_scratch_doubles(n)));
     ADMMQ_TRY(admmq_k_factorize(ctx, H, n, lambda, f.d, A64, R64, vecs, f.Q, f.Qt, f.ta, f.tb));
     f.n = n;
     f.lambda = lambda;

@@ -7,39 +7,13 @@
 // tridiagonal-to-diagonal stage of an eigensolver is serial and gains nothing here: the per-iteration
 // cost stays two n x n x p products plus an O(np) pass.
 //
-// Both the reduction and the accumulation of Q^T are written as ONE streaming pass over the trailing
-// matrix per step: the rank-2 (rank-1) update left pending by the previous step is applied while the
-// matrix-vector product needed by the current step is formed, so each trailing element is read and
-// written once per step.  One 64-lane wave owns one matrix row, so every reduction has a fixed order.
+// The reduction itself lives in householder.hip; this file holds the scaling, the LDL^T factors of
+// T + rho I for the whole penalty schedule, and the per-iteration tridiagonal solve.
 #include <stdlib.h>
 
 #include "common.h"
 
 namespace {
-
-__device__ inline double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-    return v;
-}
-__device__ inline double wave_bcast_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-// sum over a 1024-thread block, result in every thread
-__device__ inline double block_sum_all(double v, double *sh) {
-    v = wave_bcast_sum(v);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    __syncthreads();
-    if (lane == 0) sh[w] = v;
-    __syncthreads();
-    double r = 0.0;
-    const int nw = blockDim.x >> 6;
-    for (int q = 0; q < nw; ++q) r += sh[q];
-    return r;
-}
 
 // d_i = fp32(sqrt(H_ii + lambda)), inv_d = 1/d (fp32), flags[0] += 1 for a non-positive diagonal
 __global__ void scaling_kernel(const float *__restrict__ H, long n, double lambda, int precondition,
@@ -67,179 +41,6 @@ __global__ void build_scaled_kernel(const float *__restrict__ H, long n, double 
     double h = 0.5 * ((double)H[idx] + (double)H[j * n + i]);
     if (i == j) h += lambda;
     A[idx] = h / ((double)d[i] * (double)d[j]);
-}
-
-// ---- Householder reduction to tridiagonal form ----------------------------------------------
-// Vector step k (single block).  Finishes step k-1 (w from p), forms row k of the virtually updated
-// matrix, extracts T's entries and builds the reflector v_k = (1, x_tail/(alpha-beta)), tau_k.
-__global__ __launch_bounds__(1024) void tridiag_vec_kernel(double *__restrict__ A, long n, long k,
-                                                           const double *__restrict__ vprev,
-                                                           double *__restrict__ vcur, double *__restrict__ w,
-                                                           const double *__restrict__ p, double *__restrict__ xbuf,
-                                                           double *__restrict__ tau, double *__restrict__ ta,
-                                                           double *__restrict__ tb) {
-    __shared__ double sh[16];
-    const int tid = threadIdx.x;
-    double *rowk = A + k * n;
-    if (k > 0) {
-        const double tp = tau[k - 1];
-        double dot = 0.0;
-        for (long i = k + tid; i < n; i += 1024) dot += p[i] * vprev[i];
-        dot = block_sum_all(dot, sh);
-        const double c = 0.5 * tp * tp * dot;
-        for (long i = k + tid; i < n; i += 1024) w[i] = tp * p[i] - c * vprev[i];
-        __syncthreads();
-        const double vk = vprev[k], wk = w[k];
-        for (long j = k + tid; j < n; j += 1024) xbuf[j] = rowk[j] - vk * w[j] - wk * vprev[j];
-    } else {
-        for (long j = tid; j < n; j += 1024) xbuf[j] = rowk[j];
-    }
-    __syncthreads();
-    if (tid == 0) ta[k] = xbuf[k];
-    if (k >= n - 1) {            // last row: nothing below the diagonal
-        if (tid == 0) tb[k] = 0.0;
-        return;
-    }
-    double sig = 0.0;
-    for (long j = k + 2 + tid; j < n; j += 1024) {
-        double x = xbuf[j];
-        sig += x * x;
-    }
-    sig = block_sum_all(sig, sh);
-    const double alpha = xbuf[k + 1];
-    double beta, tk, scale;
-    if (sig == 0.0) {
-        beta = alpha; tk = 0.0; scale = 0.0;
-    } else {
-        const double nrm = sqrt(alpha * alpha + sig);
-        beta = alpha >= 0.0 ? -nrm : nrm;
-        tk = (beta - alpha) / beta;
-        scale = 1.0 / (alpha - beta);
-    }
-    if (tid == 0) {
-        tb[k] = beta;
-        tau[k] = tk;
-    }
-    for (long j = k + 1 + tid; j < n; j += 1024) {
-        double v = j == k + 1 ? 1.0 : xbuf[j] * scale;
-        vcur[j] = v;
-        rowk[j] = v;            // permanent home of the reflector: row k, right of the diagonal
-    }
-}
-
-// Matrix step k: rows/cols >= k+1.  Applies the pending update of step k-1 (if any) and forms
-// p[i] = sum_j A_new[i][j] * v[j].  One wave per row.
-__global__ __launch_bounds__(256) void tridiag_mat_kernel(double *__restrict__ A, long n, long k, int pending,
-                                                          const double *__restrict__ vprev,
-                                                          const double *__restrict__ w,
-                                                          const double *__restrict__ v, double *__restrict__ p) {
-    const int lane = threadIdx.x & 63;
-    const long i = k + 1 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (i >= n) return;
-    double *row = A + i * n;
-    double acc = 0.0;
-    if (pending) {
-        const double vi = vprev[i], wi = w[i];
-        for (long j = k + 1 + lane; j < n; j += 64) {
-            double a = row[j] - vi * w[j] - wi * vprev[j];
-            row[j] = a;
-            acc += a * v[j];
-        }
-    } else {
-        for (long j = k + 1 + lane; j < n; j += 64) acc += row[j] * v[j];
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) p[i] = acc;
-}
-
-// Closes the reduction: the last pending update (step n-3) on the trailing 2 x 2 block.
-__global__ void tridiag_tail_kernel(const double *__restrict__ A, long n, const double *__restrict__ vprev,
-                                    const double *__restrict__ p, const double *__restrict__ tau,
-                                    double *__restrict__ ta, double *__restrict__ tb) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const long k = n - 2;            // vprev = v_{n-3} lives on indices n-2, n-1
-    const double tp = tau[n - 3];
-    const double dot = p[k] * vprev[k] + p[k + 1] * vprev[k + 1];
-    const double c = 0.5 * tp * tp * dot;
-    const double w0 = tp * p[k] - c * vprev[k], w1 = tp * p[k + 1] - c * vprev[k + 1];
-    ta[k] = A[k * n + k] - 2.0 * vprev[k] * w0;
-    tb[k] = A[k * n + k + 1] - vprev[k] * w1 - w0 * vprev[k + 1];
-    ta[k + 1] = A[(k + 1) * n + k + 1] - 2.0 * vprev[k + 1] * w1;
-    tb[k + 1] = 0.0;
-}
-
-// ---- accumulation of R = Q^T = H_{n-3} ... H_0 -----------------------------------------------
-__global__ void identity_kernel(double *__restrict__ R, long n) {
-    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n * n) return;
-    long i = idx / n;
-    R[idx] = (idx - i * n == i) ? 1.0 : 0.0;
-}
-
-// Step k (k = n-3 ... 0), rows j and columns i >= k+2 of R:
-//   pending (reflector k+1):  R[j][i] -= tau_{k+1} g'[j] v_{k+1}[i]
-//   g[j] = sum_i R_new[j][i] v_k[i];   row k+1 of R is still a unit row, so g[k+1] = v_k[k+1] = 1.
-// Reflector v_q is read from row q of A (entries right of the diagonal).
-__global__ __launch_bounds__(256) void qform_kernel(double *__restrict__ R, const double *__restrict__ A, long n,
-                                                    long k, int pending, const double *__restrict__ tau,
-                                                    const double *__restrict__ gprev, double *__restrict__ g) {
-    const int lane = threadIdx.x & 63;
-    const long j = k + 1 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= n) return;
-    if (j == k + 1) {
-        if (lane == 0) g[j] = 1.0;
-        return;
-    }
-    double *row = R + j * n;
-    const double *vk = A + k * n;
-    double acc = 0.0;
-    if (pending) {
-        const double *vp = A + (k + 1) * n;
-        const double c = tau[k + 1] * gprev[j];
-        for (long i = k + 2 + lane; i < n; i += 64) {
-            double r = row[i] - c * vp[i];
-            row[i] = r;
-            acc += r * vk[i];
-        }
-    } else {
-        for (long i = k + 2 + lane; i < n; i += 64) acc += row[i] * vk[i];
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) g[j] = acc;
-}
-
-// Applies the last pending reflector (k = 0): rows/cols >= 1.
-__global__ __launch_bounds__(256) void qform_last_kernel(double *__restrict__ R, const double *__restrict__ A,
-                                                         long n, const double *__restrict__ tau,
-                                                         const double *__restrict__ g) {
-    const int lane = threadIdx.x & 63;
-    const long j = 1 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= n) return;
-    double *row = R + j * n;
-    const double c = tau[0] * g[j];
-    for (long i = 1 + lane; i < n; i += 64) row[i] -= c * A[i];   // v_0 = row 0 of A
-}
-
-// Qt = fp32(R) row-major, Q = fp32(R^T) row-major, through a 32 x 32 LDS tile.
-__global__ void emit_q_kernel(const double *__restrict__ R, long n, float *__restrict__ Q,
-                              float *__restrict__ Qt) {
-    __shared__ float tile[32][33];
-    const int tx = threadIdx.x, ty = threadIdx.y;     // 32 x 8
-    const long r0 = (long)blockIdx.y * 32, c0 = (long)blockIdx.x * 32;
-    for (int r = ty; r < 32; r += 8) {
-        long i = r0 + r, j = c0 + tx;
-        float v = 0.f;
-        if (i < n && j < n) {
-            v = (float)R[i * n + j];
-            Qt[i * n + j] = v;
-        }
-        tile[r][tx] = v;
-    }
-    __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        long i = c0 + r, j = r0 + tx;                 // Q[i][j] = R[j][i]
-        if (i < n && j < n) Q[i * n + j] = tile[tx][r];
-    }
 }
 
 // ---- (T + rho I) = L D L^T for a whole schedule of rho, one thread per rho -------------------
@@ -428,53 +229,17 @@ admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double l
     return ADMMQ_OK;
 }
 
+admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double *R64, double *vecs, float *Q,
+                                 float *Qt, double *ta, double *tb);
+
 admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double lambda, const float *d,
                                double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
                                double *tb) {
-    hipStream_t st = ctx->stream;
     const long N = (long)n;
-    double *v0 = vecs, *v1 = vecs + N, *w = vecs + 2 * N, *pv = vecs + 3 * N, *xbuf = vecs + 4 * N,
-           *tau = vecs + 5 * N, *g0 = vecs + 6 * N, *g1 = vecs + 7 * N;
-    hipLaunchKernelGGL(build_scaled_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, H, N, lambda, d, A64);
-    if (N == 1) {
-        // T = A, Q = 1
-        hipLaunchKernelGGL(tridiag_vec_kernel, dim3(1), dim3(1024), 0, st, A64, N, 0L, v1, v0, w, pv, xbuf, tau, ta,
-                           tb);
-    } else if (N == 2) {
-        hipLaunchKernelGGL(tridiag_vec_kernel, dim3(1), dim3(1024), 0, st, A64, N, 0L, v1, v0, w, pv, xbuf, tau, ta,
-                           tb);
-        // v_0 = (1) has tau = 0: the trailing 1 x 1 block is A[1][1] itself
-        hipLaunchKernelGGL(tridiag_mat_kernel, dim3(1), dim3(256), 0, st, A64, N, 0L, 0, v1, w, v0, pv);
-        hipLaunchKernelGGL(tridiag_vec_kernel, dim3(1), dim3(1024), 0, st, A64, N, 1L, v0, v1, w, pv, xbuf, tau, ta,
-                           tb);
-    } else {
-        for (long k = 0; k <= N - 3; ++k) {
-            double *vc = (k & 1) ? v1 : v0, *vp = (k & 1) ? v0 : v1;
-            hipLaunchKernelGGL(tridiag_vec_kernel, dim3(1), dim3(1024), 0, st, A64, N, k, vp, vc, w, pv, xbuf, tau,
-                               ta, tb);
-            const long m = N - k - 1;
-            hipLaunchKernelGGL(tridiag_mat_kernel, dim3(blocks_for(m, 4)), dim3(256), 0, st, A64, N, k, k > 0 ? 1 : 0,
-                               vp, w, vc, pv);
-        }
-        double *vlast = ((N - 3) & 1) ? v1 : v0;
-        hipLaunchKernelGGL(tridiag_tail_kernel, dim3(1), dim3(64), 0, st, A64, N, vlast, pv, tau, ta, tb);
-    }
+    hipLaunchKernelGGL(build_scaled_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, ctx->stream, H, N, lambda, d,
+                       A64);
     ADMMQ_HIP(hipGetLastError());
-    // R = Q^T
-    hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, R64, N);
-    if (N >= 3) {
-        for (long k = N - 3; k >= 0; --k) {
-            double *gc = (k & 1) ? g1 : g0, *gp = (k & 1) ? g0 : g1;
-            const long m = N - k - 1;
-            hipLaunchKernelGGL(qform_kernel, dim3(blocks_for(m, 4)), dim3(256), 0, st, R64, A64, N, k,
-                               k < N - 3 ? 1 : 0, tau, gp, gc);
-        }
-        hipLaunchKernelGGL(qform_last_kernel, dim3(blocks_for(N - 1, 4)), dim3(256), 0, st, R64, A64, N, tau, g0);
-    }
-    dim3 tb32(32, 8), tg((unsigned)((N + 31) / 32), (unsigned)((N + 31) / 32));
-    hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
-    ADMMQ_HIP(hipGetLastError());
-    return ADMMQ_OK;
+    return admmq_k_householder(ctx, A64, n, R64, vecs, Q, Qt, ta, tb);
 }
 
 admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const double *tb, int64_t n,
