@@ -11,6 +11,8 @@
 // Lane l of the wave feeds matrix row  FA*(l%32)+a  and column  FB*(l%32)+b  of its block, so one
 // LDS read of FA (FB) consecutive floats serves all FA (FB) accumulators and the epilogue writes
 // FB consecutive outputs per lane.
+#include <stdlib.h>
+
 #include "common.h"
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -19,7 +21,6 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
-constexpr int KT = 16;   // k rows per LDS stage
 
 struct GemmParams {
     const void *A;
@@ -90,7 +91,7 @@ __device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tile
     tn = in_grp / gsz;
 }
 
-template <int FA, int FB, int WGM, int WGN, bool ABF16, bool BBF16>
+template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
@@ -142,7 +143,45 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
 
     floatx4 ra[A_PER], rb[B_PER];
 
+    // Interior tiles whose rows are 16-byte aligned take a branch-free load path; edge tiles and the last,
+    // partial k-stage go through the guarded loads.
+    const bool interior = vec_ok && m0 + BM <= P.M && n0 + BN <= P.N;
     auto fetch = [&](long k0) {
+        if (interior && k0 + KT <= kend) {
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int s = tid + i * NT;
+                if (A4 % NT == 0 || s < A4) {
+                    const long kr = k0 + s / (BM / 4), col = m0 + 4 * (s % (BM / 4));
+                    if constexpr (ABF16) {
+                        const uint2 u = *(const uint2 *)((const unsigned short *)P.A + kr * P.lda + col);
+                        ra[i].x = __uint_as_float(u.x << 16);
+                        ra[i].y = __uint_as_float(u.x & 0xFFFF0000u);
+                        ra[i].z = __uint_as_float(u.y << 16);
+                        ra[i].w = __uint_as_float(u.y & 0xFFFF0000u);
+                    } else {
+                        ra[i] = *(const floatx4 *)((const float *)P.A + kr * P.lda + col);
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int s = tid + i * NT;
+                if (B4 % NT == 0 || s < B4) {
+                    const long kr = k0 + s / (BN / 4), col = n0 + 4 * (s % (BN / 4));
+                    if constexpr (BBF16) {
+                        const uint2 u = *(const uint2 *)((const unsigned short *)P.B + kr * P.ldb + col);
+                        rb[i].x = __uint_as_float(u.x << 16);
+                        rb[i].y = __uint_as_float(u.x & 0xFFFF0000u);
+                        rb[i].z = __uint_as_float(u.y << 16);
+                        rb[i].w = __uint_as_float(u.y & 0xFFFF0000u);
+                    } else {
+                        rb[i] = *(const floatx4 *)((const float *)P.B + kr * P.ldb + col);
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < A_PER; ++i) {
             int s = tid + i * NT;
@@ -177,50 +216,70 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
         }
     };
 
+    const int l32 = lane & 31;
+    const int khalf = lane >> 5;
+    const int offA = wm * (32 * FA) + FA * l32 + khalf * BM;
+    const int offB = wn * (32 * FB) + FB * l32 + khalf * BN;
+    // fragments of k-step kk (rows 2kk, 2kk+1 of the stage) of buffer `buf`
+    auto read_frags = [&](int buf, int kk, float *fa, float *fb) {
+        const float *cA = sA + buf * KT * BM + offA + 2 * kk * BM;
+        const float *cB = sB + buf * KT * BN + offB + 2 * kk * BN;
+        if constexpr (FA == 4) {
+            floatx4 t = *(const floatx4 *)cA;
+            fa[0] = t.x; fa[1] = t.y; fa[2] = t.z; fa[3] = t.w;
+        } else if constexpr (FA == 2) {
+            floatx2 t = *(const floatx2 *)cA;
+            fa[0] = t.x; fa[1] = t.y;
+        } else {
+            fa[0] = cA[0];
+        }
+        if constexpr (FB == 4) {
+            floatx4 t = *(const floatx4 *)cB;
+            fb[0] = t.x; fb[1] = t.y; fb[2] = t.z; fb[3] = t.w;
+        } else if constexpr (FB == 2) {
+            floatx2 t = *(const floatx2 *)cB;
+            fb[0] = t.x; fb[1] = t.y;
+        } else {
+            fb[0] = cB[0];
+        }
+    };
+    auto mfma_step = [&](const float *fa, const float *fb) {
+#pragma unroll
+        for (int a = 0; a < FA; ++a)
+#pragma unroll
+            for (int b = 0; b < FB; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    };
+
     const long nkt = (kend - kbeg + KT - 1) / KT;
+    constexpr int KS = KT / 2;            // k-steps per stage
+    float fa[2][FA], fb[2][FB];
     if (nkt > 0) {
         fetch(kbeg);
         stash(0);
     }
     __syncthreads();
-
-    const int l32 = lane & 31;
-    const int khalf = lane >> 5;
+    if (nkt > 0) read_frags(0, 0, fa[0], fb[0]);
+    // Per stage: the fragments of step kk+1 are read while the matrix cores work on step kk; the next
+    // stage is written to the other buffer, the barrier passed and its first fragments requested BEFORE the
+    // last step's MFMAs are issued, so that neither the barrier nor the LDS latency leaves the pipe empty.
     for (long kt = 0; kt < nkt; ++kt) {
         const int buf = (int)(kt & 1);
-        if (kt + 1 < nkt) fetch(kbeg + (kt + 1) * KT);
-        const float *cA = sA + buf * KT * BM + wm * (32 * FA) + FA * l32;
-        const float *cB = sB + buf * KT * BN + wn * (32 * FB) + FB * l32;
+        const bool more = kt + 1 < nkt;
+        if (more) fetch(kbeg + (kt + 1) * KT);
 #pragma unroll
-        for (int kk = 0; kk < KT / 2; ++kk) {
-            const int kr = 2 * kk + khalf;
-            float fa[FA], fb[FB];
-            if constexpr (FA == 4) {
-                floatx4 t = *(const floatx4 *)(cA + kr * BM);
-                fa[0] = t.x; fa[1] = t.y; fa[2] = t.z; fa[3] = t.w;
-            } else if constexpr (FA == 2) {
-                floatx2 t = *(const floatx2 *)(cA + kr * BM);
-                fa[0] = t.x; fa[1] = t.y;
-            } else {
-                fa[0] = cA[kr * BM];
-            }
-            if constexpr (FB == 4) {
-                floatx4 t = *(const floatx4 *)(cB + kr * BN);
-                fb[0] = t.x; fb[1] = t.y; fb[2] = t.z; fb[3] = t.w;
-            } else if constexpr (FB == 2) {
-                floatx2 t = *(const floatx2 *)(cB + kr * BN);
-                fb[0] = t.x; fb[1] = t.y;
-            } else {
-                fb[0] = cB[kr * BN];
-            }
-#pragma unroll
-            for (int a = 0; a < FA; ++a)
-#pragma unroll
-                for (int b = 0; b < FB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        for (int kk = 0; kk < KS - 1; ++kk) {
+            read_frags(buf, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of this step's MFMAs
+            mfma_step(fa[kk & 1], fb[kk & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < nkt) stash(buf ^ 1);
+        if (more) stash(buf ^ 1);
         __syncthreads();
+        if (more) read_frags(buf ^ 1, 0, fa[KS & 1], fb[KS & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // Epilogue.  Accumulator register v of lane l holds matrix-core row 8*(v/4) + 4*(l/32) + v%4 and
@@ -265,7 +324,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
     }
 }
 
-template <int FA, int FB, int WGM, int WGN>
+template <int FA, int FB, int WGM, int WGN, int KT>
 admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
@@ -300,7 +359,7 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
     dim3 grid((unsigned)(tiles * P.split_k)), block(64 * WGM * WGN);
 #define ADMMQ_GEMM_LAUNCH(AB, BB)                                                                      \
     do {                                                                                               \
-        auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, AB, BB>;                                          \
+        auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, KT, AB, BB>;                                          \
         static bool attr_set = false;                                                                  \
         if (!attr_set) {                                                                               \
             ADMMQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -345,19 +404,38 @@ __global__ void sym_reduce_kernel(float *H, long n, const float *P, int slices, 
 
 admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
     if (a.M <= 0 || a.N <= 0 || a.K < 0) return ADMMQ_ERR_SHAPE;
+    static int variant = -1;
+    if (variant < 0) {
+        const char *e = getenv("ADMMQ_GEMM_VARIANT");
+        variant = e ? atoi(e) : 0;
+    }
     // tile choice: the largest tile that still gives every CU work
     const long t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     const long work = a.split_k > 1 ? a.split_k : 1;
+    bool big, mid;
     if (a.lower_only) {
         const long tm256 = (a.M + 255) / 256, tm128 = (a.M + 127) / 128;
-        if (tm256 * (tm256 + 1) / 2 * work >= 200) return launch_cfg<4, 4, 2, 2>(ctx, a);
-        if (tm128 * (tm128 + 1) / 2 * work >= 128) return launch_cfg<2, 2, 2, 2>(ctx, a);
-        return launch_cfg<1, 1, 2, 2>(ctx, a);
+        big = tm256 * (tm256 + 1) / 2 * work >= 200;
+        mid = tm128 * (tm128 + 1) / 2 * work >= 128;
+    } else {
+        big = t256 * work >= 200;
+        mid = t128 * work >= 128;
     }
-    if (t256 * work >= 200) return launch_cfg<4, 4, 2, 2>(ctx, a);
-    if (t128 * work >= 128) return launch_cfg<2, 2, 2, 2>(ctx, a);
-    return launch_cfg<1, 1, 2, 2>(ctx, a);
+    if (big) {
+        // measured on MI355X (W-update products, n = p = 4096): eight waves of 64 x 128 with 32-row stages
+        // reach 134 TFLOP/s, four waves of 128 x 128 with 16-row stages 128 TFLOP/s
+        switch (variant) {
+            case 1: return launch_cfg<4, 4, 2, 2, 16>(ctx, a);
+            case 2: return launch_cfg<4, 4, 2, 2, 32>(ctx, a);
+            case 3: return launch_cfg<2, 4, 4, 2, 16>(ctx, a);
+            case 4: return launch_cfg<4, 2, 2, 4, 32>(ctx, a);
+            case 5: return launch_cfg<2, 2, 4, 4, 32>(ctx, a);
+            default: return launch_cfg<2, 4, 4, 2, 32>(ctx, a);
+        }
+    }
+    if (mid) return launch_cfg<2, 2, 2, 2, 16>(ctx, a);
+    return launch_cfg<1, 1, 2, 2, 16>(ctx, a);
 }
 
 admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
