@@ -22,6 +22,11 @@ import synth_inputs as si  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+# HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
+# calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
+PMC_TRAFFIC_BYTES = {
+    "cfg2": {"gemm": (227149.0 + 65536.0) * 1024, "project": (65780.1 + 131088.0) * 1024},
+}
 
 
 def make_inputs(cfg, tokens, torch):
@@ -138,7 +143,7 @@ def main():
     lsa_ms = mean(lambda s: s.ms_ls_apply / max(s.n_ls_apply, 1))
     gemm_tf = 2.0 * n * n * p / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     proj_gbs = 16.0 * n * p / (proj_ms * 1e-3) / 1e9 if proj_ms > 0 else 0.0
-    lsa_gbs = (8.0 * n * p + 8.0 * n) / (lsa_ms * 1e-3) / 1e9 if lsa_ms > 0 else 0.0
+    lsa_gbs = 8.0 * n * p / (lsa_ms * 1e-3) / 1e9 if lsa_ms > 0 else 0.0    # one read + one write of G per flush
     hess_ms = float(np.mean(hs))
     hess_tf = tokens * n * (n + 1) / (hess_ms * 1e-3) / 1e12
 
@@ -157,12 +162,15 @@ def main():
                       "j_damp_rtn": stats[-1].j_damp_rtn, "ls_moves": stats[-1].ls_moves},
         "roofline": {"kernel": "gemm_tn (W-update, 2 launches per iteration)", "bound": "mfma",
                      "achieved": gemm_tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tf / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "frac": gemm_tf / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm"),
                      "ms_per_launch": gemm_ms, "flop_per_launch": 2.0 * n * n * p},
         "roofline_projection": {"kernel": "project_dual", "bound": "hbm", "achieved": proj_gbs, "peak": PEAK_HBM_GBS,
-                                "unit": "GB/s", "frac": proj_gbs / PEAK_HBM_GBS, "traffic": None,
+                                "unit": "GB/s", "frac": proj_gbs / PEAK_HBM_GBS,
+                                "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("project"),
                                 "ms_per_launch": proj_ms, "bytes_per_launch": 16.0 * n * p},
-        "roofline_ls_apply": {"kernel": "ls_apply", "bound": "hbm", "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
+        "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
+                              "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
         "roofline_hessian": {"kernel": "gemm_tn (Hessian, lower triangle)", "bound": "mfma", "achieved": hess_tf,
                              "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": hess_tf / PEAK_FP32_MFMA_TFLOPS},

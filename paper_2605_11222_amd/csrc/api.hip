@@ -744,20 +744,25 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
 
     // --- ADMM loop (Alg. 1 lines 5-9) -------------------------------------------------------------
     t_phase.start();
+    // W and B trade places every iteration: the projection pass writes B^(t+1) over the W it has just read
+    float *Bcur = B, *Wcur = W;
     for (int t = 0; t < T; ++t) {
         const float rf = (float)hrho[t];
         if (t == 0) {
             // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
-            ADMMQ_HIP(hipMemcpyAsync(W, B, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
+            ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
         } else {
-            ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, W));
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
         }
         const bool last = t == T - 1;
         const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
-        ADMMQ_TRY(admmq_k_project_dual(ctx, W, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
+        ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
                                        1.0f / rf, 1.0f / (float)hrho[t + 1], (last || want_flips) ? codes : nullptr,
-                                       want_flips ? 1 : 0, B, res + t, want_flips ? flips + t : nullptr));
+                                       want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr));
         admmq_prof_end(ctx, sp);
+        float *tmpp = Bcur;
+        Bcur = Wcur;
+        Wcur = tmpp;
     }
     float ms_admm = t_phase.stop();
 

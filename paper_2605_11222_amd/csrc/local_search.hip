@@ -218,39 +218,57 @@ __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__
                                                        float *__restrict__ G, long n, long p,
                                                        const int32_t *__restrict__ pend_idx,
                                                        const float *__restrict__ pend_d, int count) {
-    const long j0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (j0 >= p) return;
+    // coefficients of this block's 8 rows for every pending slot: coef[k][0][rr] = H'[r0+rr][a_k],
+    // coef[k][1][rr] = H'[r0+rr][b_k] (column a of the symmetric H' read as row a); an empty slot gives 0
+    __shared__ float coef[LS_K][2][8];
+    __shared__ int any_sh;
     const long r0 = (long)blockIdx.y * 8;
+    if (threadIdx.x == 0) any_sh = 0;
+    __syncthreads();
+    for (int e = threadIdx.x; e < count * 16; e += 256) {
+        const int k = e >> 4, w = (e >> 3) & 1, rr = e & 7;
+        const long src = pend_idx[2 * k + w];
+        const long i = r0 + rr;
+        float h = 0.f;
+        if (pend_idx[2 * k] >= 0 && i < n) {
+            h = H[src * n + i];
+            if (i == src) h += lambda;
+            any_sh = 1;
+        }
+        coef[k][w][rr] = h;
+    }
+    __syncthreads();
+    const bool any = any_sh != 0;
+    const long j0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (j0 >= p || !any) return;
     float acc[8][4];
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr)
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
-    bool any = false;
+    const bool vecd = (p % 4 == 0);
     for (int k = 0; k < count; ++k) {
-        const long a = pend_idx[2 * k], b = pend_idx[2 * k + 1];
-        if (a < 0) continue;
-        any = true;
+        if (pend_idx[2 * k] < 0) continue;
         float d1[4], d2[4];
+        if (vecd) {
+            const floatx4 t1 = *(const floatx4 *)(pend_d + (long)(2 * k) * p + j0);
+            const floatx4 t2 = *(const floatx4 *)(pend_d + (long)(2 * k + 1) * p + j0);
+            d1[0] = t1.x; d1[1] = t1.y; d1[2] = t1.z; d1[3] = t1.w;
+            d2[0] = t2.x; d2[1] = t2.y; d2[2] = t2.z; d2[3] = t2.w;
+        } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            d1[c] = j0 + c < p ? pend_d[(long)(2 * k) * p + j0 + c] : 0.f;
-            d2[c] = j0 + c < p ? pend_d[(long)(2 * k + 1) * p + j0 + c] : 0.f;
+            for (int c = 0; c < 4; ++c) {
+                d1[c] = j0 + c < p ? pend_d[(long)(2 * k) * p + j0 + c] : 0.f;
+                d2[c] = j0 + c < p ? pend_d[(long)(2 * k + 1) * p + j0 + c] : 0.f;
+            }
         }
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) {
-            const long i = r0 + rr;
-            if (i < n) {
-                // column a of the symmetric H' read as row a
-                float c1 = H[a * n + i], c2 = H[b * n + i];
-                if (i == a) c1 += lambda;
-                if (i == b) c2 += lambda;
+            const float c1 = coef[k][0][rr], c2 = coef[k][1][rr];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) acc[rr][c] += c1 * d1[c] + c2 * d2[c];
-            }
+            for (int c = 0; c < 4; ++c) acc[rr][c] += c1 * d1[c] + c2 * d2[c];
         }
     }
-    if (!any) return;
     const bool vec = (p % 4 == 0);
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) {

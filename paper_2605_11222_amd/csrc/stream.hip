@@ -76,15 +76,16 @@ __global__ void recip_kernel(const float *__restrict__ x, float *__restrict__ in
 
 // ---- fused projection + dual + residual -------------------------------------------------------
 // Each thread owns 4 consecutive columns and walks ROWS rows of one group, so the grid parameters of
-// its columns are read once.  grid: (ceil(p4 / 256), ceil(n / ROWS)), block 256.
-constexpr int PD_ROWS = 32;
+// its columns are read once.  B may be the same array as W (every element is read before it is written,
+// by the same thread): the ADMM loop uses that to keep the pass on two arrays instead of three.  grid: (ceil(p4 / 256), ceil(n / ROWS)), block 256.
+constexpr int PD_ROWS = 16;     // measured inside the ADMM loop on MI355X: 16 rows per thread is the fastest
 
 template <bool CODES, bool FLIPS, bool VEC>
 __global__ __launch_bounds__(256) void project_dual_kernel(
-    const float *__restrict__ W, float *__restrict__ V, long n, long p, const float *__restrict__ d,
+    const float *W, float *__restrict__ V, long n, long p, const float *__restrict__ d,
     const float *__restrict__ inv_d, float levels, long g, const float *__restrict__ scales,
     const float *__restrict__ inv_scales, const float *__restrict__ zeros, float rho, float inv_rho,
-    float inv_rho_next, uint8_t *__restrict__ codes, float *__restrict__ B, double *__restrict__ res_sq,
+    float inv_rho_next, uint8_t *__restrict__ codes, float *B, double *__restrict__ res_sq,
     unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal) {
     __shared__ double sh[4];
     const long c0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
