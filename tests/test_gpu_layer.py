@@ -258,3 +258,60 @@ def test_device_side_input_checks_leave_outputs_untouched(ctx):
     b = ctx.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=1))[0]
     assert torch.equal(a, b)
     c2.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# switches, strides and bit-width extremes
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("precondition,gamma", [(False, 1.1), (True, 1.0), (False, 1.0)])
+def test_ablation_switches_match_oracle(ctx, precondition, gamma):
+    """Without the diagonal scaling (Sigma = I) and / or with a fixed penalty (gamma = 1): the paper's ablations."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(160, 48, 500, 21, outliers=2)
+    H64 = orc.hessian([X.astype(np.float64)])
+    H32 = H64.astype(np.float32)
+    T = 60
+    sched = admmq.Schedule(T=T, gamma=gamma, precondition=precondition, ls_rounds=0)
+    codes, scales, zeros, st = ctx.quantize_layer(to_dev(H32), to_dev(W0), 3, 0, sched)
+    grid = orc.Grid.fit(W0.astype(np.float64), 3, 0)
+    Hd, lam = orc.damp_hessian(H32.astype(np.float64))
+    ref = orc.admm(Hd, W0.astype(np.float64), grid, T=T, gamma=gamma, precondition=precondition)
+    j_ref = orc.objective(Hd, W0.astype(np.float64), ref.Wq)
+    assert abs(st.j_damp_admm - j_ref) <= OBJ_TOL * j_ref
+    print(f"precondition={precondition} gamma={gamma}: J {st.j_damp_admm:.6g} / oracle {j_ref:.6g}, "
+          f"code mismatch {np.mean(codes.cpu().numpy() != ref.codes):.4f}")
+
+
+def test_strided_weights_and_explicit_full_group(ctx):
+    """W0 with a leading dimension larger than p; group_size = n is the same grid as per-channel."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(128, 40, 400, 31)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    wide = torch.zeros((128, 64), dtype=torch.float32, device="cuda")
+    wide[:, :40] = to_dev(W0)
+    wide[:, 40:] = float("nan")                       # must never be read
+    view = wide[:, :40]
+    assert view.stride(0) == 64
+    sched = admmq.Schedule(T=40, ls_rounds=1, ls_pairs=16, seed=2)
+    a = ctx.quantize_layer(H, view, 4, 0, sched)
+    b = ctx.quantize_layer(H, to_dev(W0), 4, 0, sched)
+    c = ctx.quantize_layer(H, to_dev(W0), 4, 128, sched)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x, y)
+    for x, y in zip(b[:3], c[:3]):
+        assert torch.equal(x, y)
+    assert a[3].j_damp == pytest.approx(b[3].j_damp, rel=1e-12)
+
+
+@pytest.mark.parametrize("bits", [2, 8])
+def test_bit_width_extremes(ctx, bits):
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(96, 33, 300, 40 + bits)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    sched = admmq.Schedule(T=50, ls_rounds=1, ls_pairs=16, seed=1)
+    codes, scales, zeros, st = ctx.quantize_layer(to_dev(H32), to_dev(W0), bits, 32, sched)
+    ref = orc.quantize_layer(H32.astype(np.float64), W0.astype(np.float64), bits, 32, T=50, ls_rounds=1, ls_pairs=16, seed=1)
+    k = codes.cpu().numpy()
+    assert k.max() <= 2 ** bits - 1 and (bits < 8 or k.max() > 127)
+    assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    assert st.j_damp == pytest.approx(f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), 32), rel=1e-4)
