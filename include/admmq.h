@@ -79,6 +79,7 @@ typedef struct {
     int32_t ls_rounds;     /* local-search rounds, 0 = none (paper: at most 5)                */
     int32_t ls_batches;    /* batches per round, 0 = ceil(n/2)                                */
     int32_t ls_pairs;      /* row pairs per batch, 0 = 64                                     */
+    int32_t refresh_iter;  /* iteration at which one grid refresh is tried (App. B), -1 = never */
     uint64_t seed;         /* seed of the pair sampler                                        */
 } admmq_schedule;
 
@@ -100,6 +101,8 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     float ms_tridiag;       /* the tridiagonal solve between them                             */
     float ms_project;       /* fused projection + dual + residual pass (eqs. 8-10, 9)         */
     float ms_ls_apply;      /* rank-2 gradient correction passes of the local search          */
+    int32_t refresh_accepted;          /* 1 if the grid refresh was tried and accepted (eq. 12)  */
+    double refresh_err_old, refresh_err_new;   /* the two sides of eq. 12 at the attempt        */
 } admmq_stats;
 
 /* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.
@@ -161,6 +164,15 @@ admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_
                                 const float *d, int32_t bits, int32_t group_size, const float *scales,
                                 const float *zeros, double rho, double rho_next, uint8_t *codes,
                                 float *B_out, double *res_sq);
+
+/* Grid refresh (Sec. 3.3, App. B) on the state of one iteration: refits (scales, zeros) by min/max of
+ * the projection target Sigma (W + V/rho) per group, projects the target on the old and on the refitted
+ * grid, and accepts the refit iff ||D_new - Wt||_F^2 <= ||D_old - Wt||_F^2 (eq. 12, scaled variables).
+ * On acceptance scales/zeros (device, [n/g][p]) are overwritten.  W, V: device fp32 [n][p]; d: [n].
+ * accepted, err_old, err_new: host outputs (err_* may be NULL). */
+admmq_status admmq_grid_refresh(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                const float *d, int32_t bits, int32_t group_size, double rho, float *scales,
+                                float *zeros, int32_t *accepted, double *err_old, double *err_new);
 
 /* Tr(E^T (H + lambda I) E) with E = dequant(codes) - W0, lambda = damp * Tr(H)/n (eq. 2 x 2). */
 admmq_status admmq_objective(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,

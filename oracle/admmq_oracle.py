@@ -172,11 +172,30 @@ class AdmmResult:
     first_codes: np.ndarray | None = None
     d: np.ndarray | None = None
     lam_eig: np.ndarray | None = None
+    grid: "Grid | None" = None                      # the grid in force at exit (refreshed or not)
+    refresh_tried: int = 0
+    refresh_accepted_at: int = -1
+    refresh_err_old: float = float("nan")           # ||D_old - Wt||_F^2 at the attempt
+    refresh_err_new: float = float("nan")           # ||D_new - Wt||_F^2 at the attempt
 
 
-def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True) -> AdmmResult:
+def refit_grid(x: np.ndarray, grid: Grid) -> Grid:
+    """The fitting routine of the initialisation (min/max per group, no clipping) applied to the current
+    continuous point x = Sigma Wt in the unscaled space (App. B "Refreshed grid")."""
+    n = x.shape[0]
+    g = n // grid.delta.shape[0]
+    return Grid.fit(x, grid.bits, 0 if g == n else g)
+
+
+def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refresh_iter=-1) -> AdmmResult:
     """Alg. 1 lines 1-10 on the damped Hessian Hd.  rho_t = rho0 * gamma^t (Sec. 3.6), exactly T
-    iterations (no early stop).  Tiny negative eigenvalues from round-off are clamped at 0."""
+    iterations (no early stop).  Tiny negative eigenvalues from round-off are clamped at 0.
+
+    Grid refresh (Sec. 3.3 "Grid refresh", App. B).  Reading: the paper does not say when a refresh is tried
+    nor which continuous weights are refitted; here one attempt is made at iteration ``refresh_iter`` (-1 = never),
+    the grid is refitted on the projection target Sigma Wt of that iteration, the refreshed projection is accepted
+    iff eq. 12 holds (Frobenius norms over the whole layer, in the scaled variables), the discrete point is replaced
+    and the dual corrected by V += rho_t (D_old - D_new), as the appendix prints it.  At most one accepted refresh."""
     W0 = np.asarray(W0, dtype=np.float64)
     d, Hs, Ws = scale_problem(Hd, W0, precondition)
     lam, U = np.linalg.eigh(Hs)
@@ -190,9 +209,20 @@ def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True) -> A
     for t in range(T):
         W = w_update(U, lam, HWs, D, V, rho)
         k, Dn, Wt = d_update(W, V, rho, d, grid)
+        V_next = V + rho * (W - Dn)                                  # eq. 9 with the current grid
+        if t == refresh_iter and res.refresh_accepted_at < 0:
+            res.refresh_tried += 1
+            new_grid = refit_grid(Wt / d[:, None], grid)
+            k_new, D_new, _ = d_update(W, V, rho, d, new_grid)
+            res.refresh_err_old = float(np.sum((Dn - Wt) ** 2))
+            res.refresh_err_new = float(np.sum((D_new - Wt) ** 2))
+            if res.refresh_err_new <= res.refresh_err_old:            # eq. 12
+                V_next = V_next + rho * (Dn - D_new)                  # dual consistency (App. B)
+                grid, k, Dn = new_grid, k_new, D_new
+                res.refresh_accepted_at = t
         res.key_lhs.append(float(np.sum((Dn - Wt) ** 2)))
         res.key_rhs.append(float(np.sum((D - Wt) ** 2)))
-        V = V + rho * (W - Dn)
+        V = V_next
         res.primal.append(float(np.linalg.norm(W - Dn)))
         res.dual.append(float(np.linalg.norm(Dn - D)))
         res.rho.append(rho)
@@ -201,6 +231,7 @@ def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True) -> A
         D = Dn
         rho = rho * gamma
     res.codes = k
+    res.grid = grid
     res.Wq = grid.dequant(k)        # = Sigma D^(T)  (Alg. 1 line 10)
     return res
 
@@ -398,19 +429,21 @@ class LayerResult:
 
 
 def quantize_layer(H, W0, bits, group_size=0, T=300, rho0=0.1, gamma=1.1, damp=0.01, precondition=True,
-                   ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0) -> LayerResult:
+                   ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0, refresh_iter=-1) -> LayerResult:
     """Alg. 1 end to end from the raw (undamped) Hessian H = X^T X."""
     H = np.asarray(H, dtype=np.float64)
     W0 = np.asarray(W0, dtype=np.float64)
     Hd, lam = damp_hessian(H, damp)
     grid = Grid.fit(W0, bits, group_size)
     k_rtn, W_rtn = rtn(W0, grid)
-    a = admm(Hd, W0, grid, T, rho0, gamma, precondition)
+    a = admm(Hd, W0, grid, T, rho0, gamma, precondition, refresh_iter)
     j_admm = objective(Hd, W0, a.Wq)
+    j_rtn = objective(Hd, W0, W_rtn)                # on the initial grid
+    grid = a.grid                                    # the local search moves on the grid in force
     codes, ls = a.codes, None
     if ls_rounds > 0:
         ls = local_search(Hd, W0, a.codes, grid, ls_rounds, ls_batches, ls_pairs, seed)
         codes = ls.codes
     Wq = grid.dequant(codes)
-    return LayerResult(codes, grid.delta, grid.z0, Wq, objective(Hd, W0, Wq), j_admm,
-                       objective(Hd, W0, W_rtn), objective(H, W0, Wq), a, ls, lam)
+    return LayerResult(codes, grid.delta, grid.z0, Wq, objective(Hd, W0, Wq), j_admm, j_rtn,
+                       objective(H, W0, Wq), a, ls, lam)

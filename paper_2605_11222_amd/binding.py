@@ -12,7 +12,7 @@ EXPORTED_SYMBOLS = [
     "admmq_create", "admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_set_workspace",
     "admmq_accumulate_hessian", "admmq_quantize_layer", "admmq_local_search", "admmq_sample_pair",
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
-    "admmq_ls_evaluate",
+    "admmq_ls_evaluate", "admmq_grid_refresh",
 ]
 
 ADMMQ_F32, ADMMQ_BF16 = 0, 1
@@ -27,7 +27,7 @@ class AdmmqError(RuntimeError):
 class _Schedule(C.Structure):
     _fields_ = [("T", C.c_int32), ("rho0", C.c_double), ("gamma", C.c_double), ("damp", C.c_double),
                 ("precondition", C.c_int32), ("ls_rounds", C.c_int32), ("ls_batches", C.c_int32),
-                ("ls_pairs", C.c_int32), ("seed", C.c_uint64)]
+                ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("seed", C.c_uint64)]
 
 
 class _Stats(C.Structure):
@@ -38,7 +38,8 @@ class _Stats(C.Structure):
                 ("primal_res", C.POINTER(C.c_float)), ("code_flips", C.POINTER(C.c_int64)),
                 ("profile", C.c_int32), ("n_gemm", C.c_int32), ("n_tridiag", C.c_int32), ("n_project", C.c_int32),
                 ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
-                ("ms_project", C.c_float), ("ms_ls_apply", C.c_float)]
+                ("ms_project", C.c_float), ("ms_ls_apply", C.c_float), ("refresh_accepted", C.c_int32),
+                ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double)]
 
 
 class _LsParams(C.Structure):
@@ -82,6 +83,8 @@ def load_library():
                                        C.POINTER(dbl)]
     lib.admmq_objective.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.admmq_ls_evaluate.argtypes = [vp, vp, dbl, vp, vp, i64, i64, i32, i32, vp, vp, i32, vp]
+    lib.admmq_grid_refresh.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, dbl, vp, vp, C.POINTER(i32),
+                                       C.POINTER(dbl), C.POINTER(dbl)]
     for name in EXPORTED_SYMBOLS:
         fn = getattr(lib, name)
         if name not in ("admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_sample_pair"):
@@ -115,6 +118,7 @@ class Schedule:
     ls_rounds: int = 5
     ls_batches: int = 0
     ls_pairs: int = 0
+    refresh_iter: int = -1
     seed: int = 0
 
 
@@ -141,6 +145,9 @@ class LayerStats:
     ms_tridiag: float = 0.0
     ms_project: float = 0.0
     ms_ls_apply: float = 0.0
+    refresh_accepted: bool = False
+    refresh_err_old: float = 0.0
+    refresh_err_new: float = 0.0
 
 
 def _ptr(t):
@@ -204,7 +211,7 @@ class Context:
         scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
-                       sched.ls_batches, sched.ls_pairs, sched.seed)
+                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, sched.seed)
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
@@ -221,7 +228,8 @@ class Context:
                              st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
                              list(res) if want_history else [], list(flips) if want_history else [],
                              st.n_gemm, st.n_tridiag, st.n_project, st.n_ls_apply, st.ms_gemm, st.ms_tridiag,
-                             st.ms_project, st.ms_ls_apply)
+                             st.ms_project, st.ms_ls_apply, bool(st.refresh_accepted), st.refresh_err_old,
+                             st.refresh_err_new)
         return codes, scales, zeros, out
 
     def local_search(self, H, W0, bits, group_size, scales, zeros, codes, rounds=5, batches_per_round=0,
@@ -274,6 +282,14 @@ class Context:
                                             _ptr(scales), _ptr(zeros), float(rho), float(rho_next), _ptr(codes),
                                             _ptr(B), C.byref(rs)))
         return codes, B, rs.value
+
+    def grid_refresh(self, W, V, d, bits, group_size, rho, scales, zeros):
+        """scales/zeros are overwritten when the refit is accepted; returns (accepted, err_old, err_new)."""
+        n, p = W.shape
+        acc, eo, en = C.c_int32(0), C.c_double(0.0), C.c_double(0.0)
+        _check(self._lib.admmq_grid_refresh(self._h, _ptr(W), _ptr(V), n, p, _ptr(d), bits, group_size, float(rho),
+                                            _ptr(scales), _ptr(zeros), C.byref(acc), C.byref(eo), C.byref(en)))
+        return bool(acc.value), eo.value, en.value
 
     def objective(self, H, W0, group_size, scales, zeros, codes, damp=0.01):
         n, p = W0.shape

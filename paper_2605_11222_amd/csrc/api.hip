@@ -269,6 +269,35 @@ admmq_status objective_core(admmq_ctx *ctx, const float *H, double lambda, int64
     return ADMMQ_OK;
 }
 
+// One grid-refresh attempt (App. B).  new_sc / new_zr: [n/g][p] scratch; part: 2*blocks doubles scratch.
+// On acceptance scales/zeros are overwritten (and inv_scales, when given).  Synchronises the stream.
+admmq_status grid_refresh_core(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p, const float *d,
+                               const float *inv_d, int bits, int64_t g, double rho, float *scales, float *zeros,
+                               float *inv_scales, float *new_sc, float *new_zr, double *part, int *accepted,
+                               double *err_old, double *err_new) {
+    const float inv_rho = 1.0f / (float)rho;
+    const size_t ng = (size_t)(n / g) * p;
+    ADMMQ_TRY(admmq_k_refit_grid(ctx, W, V, n, p, inv_d, inv_rho, bits, g, new_sc, new_zr));
+    ADMMQ_TRY(admmq_k_refresh_error(ctx, W, V, n, p, d, inv_d, inv_rho, bits, g, scales, zeros, new_sc, new_zr, part));
+    const int nb = admmq_refresh_error_blocks();
+    std::vector<double> h((size_t)2 * nb);
+    ADMMQ_TRY(read_back(ctx, h.data(), part, h.size() * 8));
+    double eo = 0.0, en = 0.0;
+    for (int b = 0; b < nb; ++b) {          // fixed order: the decision is reproducible
+        eo += h[2 * b];
+        en += h[2 * b + 1];
+    }
+    *accepted = en <= eo ? 1 : 0;
+    if (err_old) *err_old = eo;
+    if (err_new) *err_new = en;
+    if (*accepted) {
+        ADMMQ_HIP(hipMemcpyAsync(scales, new_sc, ng * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        ADMMQ_HIP(hipMemcpyAsync(zeros, new_zr, ng * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        if (inv_scales) ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
+    }
+    return ADMMQ_OK;
+}
+
 struct LsPlan {
     int rounds, batches, pairs;
 };
@@ -559,6 +588,36 @@ extern "C" admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float
     return ADMMQ_OK;
 }
 
+extern "C" admmq_status admmq_grid_refresh(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                           const float *d, int32_t bits, int32_t group_size, double rho,
+                                           float *scales, float *zeros, int32_t *accepted, double *err_old,
+                                           double *err_new) {
+    if (!ctx || !W || !V || !d || !scales || !zeros || !accepted) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(W, W, n, p, p, bits, group_size));
+    if (!(rho > 0.0) || !isfinite(rho)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    const size_t ng = (size_t)(n / g) * p;
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 2 * admmq_align_up(ng * 4) + admmq_align_up((size_t)n * 4) +
+                                           admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8) + 8192));
+    float *new_sc = nullptr, *new_zr = nullptr, *inv_d = nullptr;
+    double *part = nullptr;
+    ADMMQ_TRY(take(ctx, new_sc, ng));
+    ADMMQ_TRY(take(ctx, new_zr, ng));
+    ADMMQ_TRY(take(ctx, inv_d, (size_t)n));
+    ADMMQ_TRY(take(ctx, part, (size_t)2 * admmq_refresh_error_blocks()));
+    ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
+    int acc = 0;
+    ADMMQ_TRY(grid_refresh_core(ctx, W, V, n, p, d, inv_d, bits, g, rho, scales, zeros, nullptr, new_sc, new_zr, part,
+                                &acc, err_old, err_new));
+    *accepted = acc;
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
 extern "C" admmq_status admmq_objective(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
                                         int64_t ldw, int32_t group_size, const float *scales, const float *zeros,
                                         const uint8_t *codes, double damp, double *j_out) {
@@ -651,7 +710,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
     if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
         !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds < 0 ||
-        sched->ls_batches < 0 || sched->ls_pairs < 0)
+        sched->ls_batches < 0 || sched->ls_pairs < 0 || sched->refresh_iter < -1)
         return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
@@ -692,7 +751,8 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     // --- grid, initial state, schedule -----------------------------------------------------------
     t_phase.start();
     LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
-    size_t need = admm_transient_bytes(n, p, T) + admmq_align_up(ng * 4);
+    size_t need = admm_transient_bytes(n, p, T) + 3 * admmq_align_up(ng * 4) +
+                  admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8);
     if (plan.rounds > 0 && n >= 2) {
         const size_t ls = ls_transient_bytes(n, p, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
         if (ls > need) need = ls;
@@ -708,6 +768,13 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(take(ctx, Y, np));
     ADMMQ_TRY(take(ctx, F, np));
     ADMMQ_TRY(take(ctx, inv_scales, ng));
+    float *new_sc = nullptr, *new_zr = nullptr;
+    double *rpart = nullptr;
+    ADMMQ_TRY(take(ctx, new_sc, ng));
+    ADMMQ_TRY(take(ctx, new_zr, ng));
+    ADMMQ_TRY(take(ctx, rpart, (size_t)2 * admmq_refresh_error_blocks()));
+    int refresh_accepted = 0;
+    double refresh_eo = 0.0, refresh_en = 0.0;
     ADMMQ_TRY(take(ctx, rhos, (size_t)T));
     ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
     ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
@@ -740,6 +807,12 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
     ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
+    if (want) {
+        // round-to-nearest on the initial grid, as the baseline objective (W, Y and F are still free)
+        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, (uint8_t *)F, n, p, g, scales, zeros, bits, 2, W));
+        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
+        ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
+    }
     ms_setup += t_phase.stop();
 
     // --- ADMM loop (Alg. 1 lines 5-9) -------------------------------------------------------------
@@ -755,6 +828,9 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
         }
         const bool last = t == T - 1;
+        if (t == sched->refresh_iter)
+            ADMMQ_TRY(grid_refresh_core(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, hrho[t], scales, zeros, inv_scales,
+                                        new_sc, new_zr, rpart, &refresh_accepted, &refresh_eo, &refresh_en));
         const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
         ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
                                        1.0f / rf, 1.0f / (float)hrho[t + 1], (last || want_flips) ? codes : nullptr,
@@ -769,6 +845,9 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     if (want) {
         stats->iters_done = T;
         stats->lambda = lambda;
+        stats->refresh_accepted = refresh_accepted;
+        stats->refresh_err_old = refresh_eo;
+        stats->refresh_err_new = refresh_en;
         if (stats->primal_res) {
             std::vector<double> h((size_t)T);
             ADMMQ_TRY(read_back(ctx, h.data(), res, (size_t)T * 8));
@@ -779,11 +858,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(read_back(ctx, h.data(), flips, (size_t)T * 8));
             for (int t = 0; t < T; ++t) stats->code_flips[t] = (int64_t)h[t];
         }
-        // objectives: round-to-nearest (into scratch codes) and the ADMM result; W, Y are free now
-        uint8_t *tmp_codes = (uint8_t *)C0;
-        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, tmp_codes, n, p, g, scales, zeros, bits, 2, W));
-        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
-        ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
+        // objective of the ADMM result; W, Y are free now
         ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, W));
         ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
         ADMMQ_TRY(read_back(ctx, &stats->j_damp_admm, jdev, 8));

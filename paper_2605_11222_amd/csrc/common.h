@@ -100,6 +100,14 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
                                   double *dev_res_sq, unsigned long long *dev_flips);
+// grid refresh (App. B): refit by min/max of the projection target; both sides of eq. 12 as per-block partials
+admmq_status admmq_k_refit_grid(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                const float *inv_d, float inv_rho, int bits, int64_t g, float *scales, float *zeros);
+int admmq_refresh_error_blocks();
+admmq_status admmq_k_refresh_error(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                   const float *d, const float *inv_d, float inv_rho, int bits, int64_t g,
+                                   const float *sc_old, const float *zr_old, const float *sc_new,
+                                   const float *zr_new, double *part);
 // inv[i] = 1/x[i] in fp32 with IEEE division, 0 where x[i] == 0
 admmq_status admmq_k_recip(admmq_ctx *ctx, const float *x, float *inv, int64_t n);
 admmq_status admmq_k_scale_rows(admmq_ctx *ctx, const float *W0, int64_t ldw, const float *d, int64_t n, int64_t p,

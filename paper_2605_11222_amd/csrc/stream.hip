@@ -210,6 +210,80 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
     }
 }
 
+// ---- grid refresh (App. B) ----------------------------------------------------------------------
+// min / max per group of the projection target x = (W + V*inv_rho)*inv_d -> refitted (scale, zero).
+// Same block shape as grid_init_kernel.
+__global__ __launch_bounds__(1024) void refit_grid_kernel(const float *__restrict__ W, const float *__restrict__ V,
+                                                          long n, long p, const float *__restrict__ inv_d,
+                                                          float inv_rho, long g, float levels,
+                                                          float *__restrict__ scales, float *__restrict__ zeros) {
+    __shared__ float smn[16][64], smx[16][64];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const long j = (long)blockIdx.x * 64 + tx;
+    const long r0 = (long)blockIdx.y * g;
+    float mn = INFINITY, mx = -INFINITY;
+    if (j < p) {
+        for (long i = ty; i < g; i += 16) {
+            const long off = (r0 + i) * p + j;
+            const float x = __fmul_rn(__fadd_rn(W[off], __fmul_rn(V[off], inv_rho)), inv_d[r0 + i]);
+            mn = fminf(mn, x);
+            mx = fmaxf(mx, x);
+        }
+    }
+    smn[ty][tx] = mn;
+    smx[ty][tx] = mx;
+    __syncthreads();
+    if (ty == 0 && j < p) {
+        for (int q = 1; q < 16; ++q) {
+            mn = fminf(mn, smn[q][tx]);
+            mx = fmaxf(mx, smx[q][tx]);
+        }
+        scales[(long)blockIdx.y * p + j] = __fdiv_rn(__fsub_rn(mx, mn), levels);
+        zeros[(long)blockIdx.y * p + j] = mn;
+    }
+}
+
+// Both sides of eq. 12: part[2*b] = sum (D_old - Wt)^2, part[2*b+1] = sum (D_new - Wt)^2 over block b's
+// elements (scaled variables).  One element per thread, grid-stride; fixed order inside a block.
+__global__ __launch_bounds__(256) void refresh_error_kernel(const float *__restrict__ W, const float *__restrict__ V,
+                                                            long n, long p, const float *__restrict__ d,
+                                                            const float *__restrict__ inv_d, float inv_rho, long g,
+                                                            float levels, const float *__restrict__ sc_old,
+                                                            const float *__restrict__ zr_old,
+                                                            const float *__restrict__ sc_new,
+                                                            const float *__restrict__ zr_new,
+                                                            double *__restrict__ part) {
+    __shared__ double sh[4];
+    double eo = 0.0, en = 0.0;
+    const long total = n * p;
+    for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+        const long i = idx / p, j = idx - i * p;
+        const long gi = (i / g) * p + j;
+        const float wt = __fadd_rn(W[idx], __fmul_rn(V[idx], inv_rho));
+        const float x = __fmul_rn(wt, inv_d[i]);
+        {
+            const float dl = sc_old[gi], z0 = zr_old[gi];
+            const float idl = dl == 0.f ? 0.f : __fdiv_rn(1.0f, dl);
+            const float k = fminf(fmaxf(rintf(__fmul_rn(__fsub_rn(x, z0), idl)), 0.f), levels);
+            const float e = __fsub_rn(__fmul_rn(d[i], __fadd_rn(__fmul_rn(k, dl), z0)), wt);
+            eo += (double)e * (double)e;
+        }
+        {
+            const float dl = sc_new[gi], z0 = zr_new[gi];
+            const float idl = dl == 0.f ? 0.f : __fdiv_rn(1.0f, dl);
+            const float k = fminf(fmaxf(rintf(__fmul_rn(__fsub_rn(x, z0), idl)), 0.f), levels);
+            const float e = __fsub_rn(__fmul_rn(d[i], __fadd_rn(__fmul_rn(k, dl), z0)), wt);
+            en += (double)e * (double)e;
+        }
+    }
+    const double to = block_sum(eo, sh);
+    const double tn = block_sum(en, sh);
+    if (threadIdx.x == 0) {
+        part[2 * blockIdx.x] = to;
+        part[2 * blockIdx.x + 1] = tn;
+    }
+}
+
 // ---- helpers ----------------------------------------------------------------------------------
 __global__ void scale_rows_kernel(const float *__restrict__ W0, long ldw, const float *__restrict__ d, long n,
                                   long p, float *__restrict__ out) {
@@ -432,6 +506,28 @@ admmq_status admmq_k_count_nonfinite(admmq_ctx *ctx, const float *A, int64_t row
     unsigned nb = (unsigned)min((long)2048, (long)((rows * cols + 255) / 256));
     hipLaunchKernelGGL(count_nonfinite_kernel, dim3(nb), dim3(256), 0, ctx->stream, A, (long)rows, (long)cols,
                        (long)ld, dev_out);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+admmq_status admmq_k_refit_grid(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                const float *inv_d, float inv_rho, int bits, int64_t g, float *scales, float *zeros) {
+    dim3 block(64, 16), grid((unsigned)((p + 63) / 64), (unsigned)(n / g));
+    hipLaunchKernelGGL(refit_grid_kernel, grid, block, 0, ctx->stream, W, V, (long)n, (long)p, inv_d, inv_rho,
+                       (long)g, (float)((1 << bits) - 1), scales, zeros);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+int admmq_refresh_error_blocks() { return 1024; }
+
+admmq_status admmq_k_refresh_error(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
+                                   const float *d, const float *inv_d, float inv_rho, int bits, int64_t g,
+                                   const float *sc_old, const float *zr_old, const float *sc_new,
+                                   const float *zr_new, double *part) {
+    hipLaunchKernelGGL(refresh_error_kernel, dim3(admmq_refresh_error_blocks()), dim3(256), 0, ctx->stream, W, V,
+                       (long)n, (long)p, d, inv_d, inv_rho, (long)g, (float)((1 << bits) - 1), sc_old, zr_old, sc_new,
+                       zr_new, part);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
