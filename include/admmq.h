@@ -80,6 +80,9 @@ typedef struct {
     int32_t ls_batches;    /* batches per round, 0 = ceil(n/2)                                */
     int32_t ls_pairs;      /* row pairs per batch, 0 = 64                                     */
     int32_t refresh_iter;  /* iteration at which one grid refresh is tried (App. B), -1 = never */
+    int32_t reuse_factor;  /* 1 = H, damp and precondition are those of the factorisation the context
+                              already holds (admmq_factorize or an earlier layer): skip Alg. 1 lines 1-3.
+                              Matrices that see the same activations (q/k/v, gate/up) share one Hessian. */
     uint64_t seed;         /* seed of the pair sampler                                        */
 } admmq_schedule;
 

@@ -27,7 +27,8 @@ class AdmmqError(RuntimeError):
 class _Schedule(C.Structure):
     _fields_ = [("T", C.c_int32), ("rho0", C.c_double), ("gamma", C.c_double), ("damp", C.c_double),
                 ("precondition", C.c_int32), ("ls_rounds", C.c_int32), ("ls_batches", C.c_int32),
-                ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("seed", C.c_uint64)]
+                ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("reuse_factor", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 class _Stats(C.Structure):
@@ -119,6 +120,7 @@ class Schedule:
     ls_batches: int = 0
     ls_pairs: int = 0
     refresh_iter: int = -1
+    reuse_factor: bool = False
     seed: int = 0
 
 
@@ -211,7 +213,7 @@ class Context:
         scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
-                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, sched.seed)
+                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.reuse_factor), sched.seed)
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None

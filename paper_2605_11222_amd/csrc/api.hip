@@ -229,6 +229,9 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
     ADMMQ_TRY(admmq_k_factorize(ctx, H, n, lambda, f.d, A64, R64, vecs, f.Q, f.Qt, f.ta, f.tb));
     f.n = n;
     f.lambda = lambda;
+    f.H_src = H;
+    f.damp = damp;
+    f.precondition = precondition;
     f.valid = true;
     if (lambda_out) *lambda_out = lambda;
     admmq_arena_reset_transient(ctx);
@@ -744,7 +747,16 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     // --- Alg. 1 lines 1-3 ----------------------------------------------------------------------
     t_phase.start();
     double lambda = 0.0;
-    ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
+    if (sched->reuse_factor) {
+        const admmq_factor &have = ctx->fac;
+        if (!have.valid || have.n != n || have.H_src != H || have.damp != sched->damp ||
+            have.precondition != sched->precondition)
+            return ADMMQ_ERR_STATE;
+        lambda = have.lambda;
+        admmq_arena_reset_transient(ctx);
+    } else {
+        ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
+    }
     float ms_factor = t_phase.stop();
     const admmq_factor &f = ctx->fac;
 

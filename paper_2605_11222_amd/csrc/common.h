@@ -30,6 +30,9 @@ struct admmq_factor {
     double *ta = nullptr;     // [n]   diagonal of T
     double *tb = nullptr;     // [n]   sub-diagonal of T (tb[n-1] = 0)
     bool valid = false;
+    const float *H_src = nullptr;   // the raw Hessian it was made from (identity check for reuse)
+    double damp = 0.0;
+    int precondition = 1;
 };
 
 // Optional per-launch timing: pairs of HIP events on the context's stream, summed per tag at the end.

@@ -315,3 +315,25 @@ def test_bit_width_extremes(ctx, bits):
     assert k.max() <= 2 ** bits - 1 and (bits < 8 or k.max() > 127)
     assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
     assert st.j_damp == pytest.approx(f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), 32), rel=1e-4)
+
+
+def test_shared_hessian_reuses_the_factorisation(ctx):
+    """Two weight matrices that see the same activations: the second call skips Alg. 1 lines 1-3 and must return
+    exactly what a call with its own factorisation returns; a different H is refused."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(192, 64, 600, 50)
+    _, W1 = correlated_problem(192, 40, 600, 51)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    s = admmq.Schedule(T=40, ls_rounds=1, ls_pairs=16, seed=3)
+    first = ctx.quantize_layer(H, to_dev(W0), 3, 64, s)
+    own = ctx.quantize_layer(H, to_dev(W1), 4, 0, s)
+    ctx.quantize_layer(H, to_dev(W0), 3, 64, s)                      # the context now holds H's factorisation
+    s2 = admmq.Schedule(T=40, ls_rounds=1, ls_pairs=16, seed=3, reuse_factor=True)
+    shared = ctx.quantize_layer(H, to_dev(W1), 4, 0, s2)
+    for a, b in zip(own[:3], shared[:3]):
+        assert torch.equal(a, b)
+    assert shared[3].ms_factor < 0.2 * own[3].ms_factor
+    other = H.clone()
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layer(other, to_dev(W1), 4, 0, s2)
+    assert e.value.code == 7
