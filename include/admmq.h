@@ -80,6 +80,9 @@ typedef struct {
     int32_t ls_batches;    /* batches per round, 0 = ceil(n/2)                                */
     int32_t ls_pairs;      /* row pairs per batch, 0 = 64                                     */
     int32_t refresh_iter;  /* iteration at which one grid refresh is tried (App. B), -1 = never */
+    int32_t symmetric;     /* 1 = symmetric grid: range [-a, a], a = max|w| of the group (Table 1 setting) */
+    int32_t clip_points;   /* MSE clipping search (Sec. 3.4, App. D: 100), 0 = plain min/max fit       */
+    double clip_shrink;    /* largest shrink of the range searched (App. D: 0.8)                       */
     int32_t reuse_factor;  /* 1 = H, damp and precondition are those of the factorisation the context
                               already holds (admmq_factorize or an earlier layer): skip Alg. 1 lines 1-3.
                               Matrices that see the same activations (q/k/v, gate/up) share one Hessian. */
@@ -146,6 +149,14 @@ void admmq_sample_pair(uint64_t seed, int32_t round, int32_t batch, int32_t slot
  * A group with max == min gets scale 0 by that formula: all its codes stay 0. */
 admmq_status admmq_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
                              int32_t bits, int32_t group_size, float *scales, float *zeros);
+
+/* Grid fit with the options of Sec. 3.4 / App. D.  symmetric: the range of a group becomes [-a, a] with
+ * a = max|w|.  clip_points > 0: MSE search over the ranges r_i*(min, max), r_i = 1 - i/clip_points for
+ * i < floor(clip_shrink*clip_points); the candidate with the smallest squared error on the group's weights
+ * wins (the widest on ties).  With symmetric = 0 and clip_points = 0 this is admmq_grid_init. */
+admmq_status admmq_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int32_t bits,
+                            int32_t group_size, int32_t symmetric, int32_t clip_points, double clip_shrink,
+                            float *scales, float *zeros);
 
 /* Alg. 1 lines 1-3: damp, scale and factorise H once; the result stays in the context and serves
  * every rho.  d_out (device fp32 [n], may be NULL) receives d_i = sqrt(H'_ii) = 1/Sigma_ii.

@@ -89,6 +89,54 @@ def grid_init(W0: np.ndarray, bits: int, group_size: int = 0):
     return delta, mn
 
 
+def grid_fit_options(W0: np.ndarray, bits: int, group_size: int = 0, symmetric: bool = False,
+                     clip_points: int = 0, clip_shrink: float = 0.8):
+    """Grid fit with the two options the paper's experiments use besides the plain min/max fit.
+
+    symmetric (Table 1 is "symmetric per-channel"; the paper gives no formula).  Reading: the printed formula
+    delta = (max-min)/(2^b-1) applied to the symmetrised range [-a, a], a = max(|min|, |max|): z0 = -a,
+    delta = 2a/(2^b-1); the levels are symmetric about 0.
+
+    clip_points > 0 (Sec. 3.4 "Clipping heuristics", App. D: MSE grid search, 100 points, maximum shrink 0.8).
+    Reading: candidate i = 0 .. floor(clip_shrink*clip_points)-1 shrinks the range towards 0 by the ratio
+    r_i = 1 - i/clip_points, i.e. (r_i*min, r_i*max); each candidate's grid quantizes the group's dense weights
+    and the candidate with the smallest squared error wins (the first one on ties, i.e. the widest).
+    Returns delta, z0 [n/g][p]."""
+    W0 = np.asarray(W0, dtype=np.float64)
+    n, p = W0.shape
+    g = n if group_size in (0, None) else int(group_size)
+    if n % g != 0:
+        raise ValueError("group_size must divide n")
+    L = float(2 ** bits - 1)
+    Wg = W0.reshape(n // g, g, p)
+    mn = Wg.min(axis=1)
+    mx = Wg.max(axis=1)
+    if symmetric:
+        a = np.maximum(np.abs(mn), np.abs(mx))
+        mn, mx = -a, a
+    best_delta = (mx - mn) / L
+    best_z0 = mn.copy()
+    if clip_points <= 0:
+        return best_delta, best_z0
+    best_err = None
+    for i in range(int(clip_shrink * clip_points)):
+        r = 1.0 - i / float(clip_points)
+        z0 = r * mn
+        delta = r * (mx - mn) / L
+        step = np.where(delta == 0.0, 1.0, delta)
+        k = np.clip(np.rint((Wg - z0[:, None, :]) / step[:, None, :]), 0, L)
+        k = np.where((delta == 0.0)[:, None, :], 0.0, k)
+        err = np.sum((z0[:, None, :] + k * delta[:, None, :] - Wg) ** 2, axis=1)
+        if best_err is None:
+            best_err = err
+        else:
+            better = err < best_err
+            best_err = np.where(better, err, best_err)
+            best_delta = np.where(better, delta, best_delta)
+            best_z0 = np.where(better, z0, best_z0)
+    return best_delta, best_z0
+
+
 def _expand(a: np.ndarray, n: int) -> np.ndarray:
     """[n/g][p] -> [n][p] by repeating each group row g times."""
     g = n // a.shape[0]
@@ -107,11 +155,12 @@ class Grid:
     degenerate: np.ndarray  # [n/g][p] bool
 
     @staticmethod
-    def fit(W0, bits, group_size=0) -> "Grid":
+    def fit(W0, bits, group_size=0, symmetric=False, clip_points=0, clip_shrink=0.8) -> "Grid":
         W0 = np.asarray(W0, dtype=np.float64)
-        n, p = W0.shape
-        g = n if group_size in (0, None) else int(group_size)
-        delta, z0 = grid_init(W0, bits, group_size)
+        if symmetric or clip_points > 0:
+            delta, z0 = grid_fit_options(W0, bits, group_size, symmetric, clip_points, clip_shrink)
+        else:
+            delta, z0 = grid_init(W0, bits, group_size)
         return Grid(delta, z0, bits, delta == 0.0)
 
     def codes(self, x: np.ndarray) -> np.ndarray:
@@ -429,12 +478,13 @@ class LayerResult:
 
 
 def quantize_layer(H, W0, bits, group_size=0, T=300, rho0=0.1, gamma=1.1, damp=0.01, precondition=True,
-                   ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0, refresh_iter=-1) -> LayerResult:
+                   ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0, refresh_iter=-1, symmetric=False,
+                   clip_points=0, clip_shrink=0.8) -> LayerResult:
     """Alg. 1 end to end from the raw (undamped) Hessian H = X^T X."""
     H = np.asarray(H, dtype=np.float64)
     W0 = np.asarray(W0, dtype=np.float64)
     Hd, lam = damp_hessian(H, damp)
-    grid = Grid.fit(W0, bits, group_size)
+    grid = Grid.fit(W0, bits, group_size, symmetric, clip_points, clip_shrink)
     k_rtn, W_rtn = rtn(W0, grid)
     a = admm(Hd, W0, grid, T, rho0, gamma, precondition, refresh_iter)
     j_admm = objective(Hd, W0, a.Wq)

@@ -12,7 +12,7 @@ EXPORTED_SYMBOLS = [
     "admmq_create", "admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_set_workspace",
     "admmq_accumulate_hessian", "admmq_quantize_layer", "admmq_local_search", "admmq_sample_pair",
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
-    "admmq_ls_evaluate", "admmq_grid_refresh",
+    "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit",
 ]
 
 ADMMQ_F32, ADMMQ_BF16 = 0, 1
@@ -27,7 +27,8 @@ class AdmmqError(RuntimeError):
 class _Schedule(C.Structure):
     _fields_ = [("T", C.c_int32), ("rho0", C.c_double), ("gamma", C.c_double), ("damp", C.c_double),
                 ("precondition", C.c_int32), ("ls_rounds", C.c_int32), ("ls_batches", C.c_int32),
-                ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("reuse_factor", C.c_int32),
+                ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("symmetric", C.c_int32),
+                ("clip_points", C.c_int32), ("clip_shrink", C.c_double), ("reuse_factor", C.c_int32),
                 ("seed", C.c_uint64)]
 
 
@@ -78,6 +79,7 @@ def load_library():
     lib.admmq_sample_pair.argtypes = [C.c_uint64, i32, i32, i32, i64, C.POINTER(i32), C.POINTER(i32)]
     lib.admmq_sample_pair.restype = None
     lib.admmq_grid_init.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp]
+    lib.admmq_grid_fit.argtypes = [vp, vp, i64, i64, i64, i32, i32, i32, i32, dbl, vp, vp]
     lib.admmq_factorize.argtypes = [vp, vp, i64, dbl, i32, vp, C.POINTER(dbl)]
     lib.admmq_w_update.argtypes = [vp, vp, vp, vp, i64, i64, dbl, vp]
     lib.admmq_project_dual.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp,
@@ -120,6 +122,9 @@ class Schedule:
     ls_batches: int = 0
     ls_pairs: int = 0
     refresh_iter: int = -1
+    symmetric: bool = False
+    clip_points: int = 0
+    clip_shrink: float = 0.8
     reuse_factor: bool = False
     seed: int = 0
 
@@ -213,7 +218,8 @@ class Context:
         scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
-                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.reuse_factor), sched.seed)
+                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
@@ -256,6 +262,16 @@ class Context:
         zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         _check(self._lib.admmq_grid_init(self._h, _ptr(W0), n, p, W0.stride(0), bits, group_size, _ptr(scales),
                                          _ptr(zeros)))
+        return scales, zeros
+
+    def grid_fit(self, W0, bits, group_size=0, symmetric=False, clip_points=0, clip_shrink=0.8):
+        torch = self._torch
+        n, p = W0.shape
+        g = group_size if group_size else n
+        scales = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
+        _check(self._lib.admmq_grid_fit(self._h, _ptr(W0), n, p, W0.stride(0), bits, group_size, int(symmetric),
+                                        clip_points, float(clip_shrink), _ptr(scales), _ptr(zeros)))
         return scales, zeros
 
     def factorize(self, H, damp=0.01, precondition=True):

@@ -513,6 +513,18 @@ extern "C" admmq_status admmq_grid_init(admmq_ctx *ctx, const float *W0, int64_t
     return admmq_k_grid_init(ctx, W0, n, p, ldw, bits, g, scales, zeros);
 }
 
+extern "C" admmq_status admmq_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                                       int32_t bits, int32_t group_size, int32_t symmetric, int32_t clip_points,
+                                       double clip_shrink, float *scales, float *zeros) {
+    if (!ctx || !scales || !zeros) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(W0, W0, n, p, ldw, bits, group_size));
+    if (clip_points < 0 || clip_points > 100000 || !(clip_shrink >= 0.0) || !(clip_shrink < 1.0)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = group_size > 0 ? group_size : n;
+    return admmq_k_grid_fit(ctx, W0, n, p, ldw, bits, g, symmetric != 0, clip_points, clip_shrink, scales, zeros);
+}
+
 extern "C" admmq_status admmq_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp,
                                         int32_t precondition, float *d_out, double *lambda_out) {
     if (!ctx || !H) return ADMMQ_ERR_NULL;
@@ -713,7 +725,8 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
     if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
         !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds < 0 ||
-        sched->ls_batches < 0 || sched->ls_pairs < 0 || sched->refresh_iter < -1)
+        sched->ls_batches < 0 || sched->ls_pairs < 0 || sched->refresh_iter < -1 || sched->clip_points < 0 ||
+        sched->clip_points > 100000 || (sched->clip_points > 0 && !(sched->clip_shrink >= 0.0 && sched->clip_shrink < 1.0)))
         return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
@@ -794,7 +807,8 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(take(ctx, flips, (size_t)T));
     ADMMQ_TRY(take(ctx, jdev, 4));
 
-    ADMMQ_TRY(admmq_k_grid_init(ctx, W0, n, p, ldw, bits, g, scales, zeros));
+    ADMMQ_TRY(admmq_k_grid_fit(ctx, W0, n, p, ldw, bits, g, sched->symmetric != 0, sched->clip_points,
+                               sched->clip_shrink, scales, zeros));
     ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
     // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
     ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));

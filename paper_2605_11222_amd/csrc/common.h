@@ -98,6 +98,10 @@ admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *
 // ---- streaming kernels (stream.hip) --------------------------------------------------------
 admmq_status admmq_k_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
                                int64_t g, float *scales, float *zeros);
+// min/max fit with the options of Sec. 3.4: symmetric range and MSE clipping search (clip_points = 0: off)
+admmq_status admmq_k_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
+                              int64_t g, int symmetric, int clip_points, double clip_shrink, float *scales,
+                              float *zeros);
 admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p, const float *d,
                                   const float *inv_d, int bits, int64_t g, const float *scales,
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,

@@ -66,6 +66,74 @@ __global__ __launch_bounds__(1024) void grid_init_kernel(const float *__restrict
     }
 }
 
+// Grid fit with options (Sec. 3.4 "Clipping heuristics", App. D): symmetric range [-a, a] and / or an MSE
+// search over ranges shrunk towards 0 by r_i = 1 - i/points, i < ncand; the candidate with the smallest
+// squared quantization error of the group's dense weights wins (the widest one on ties).
+// Same block shape as grid_init_kernel: 64 columns x 16 row lanes per (column block, group).
+__global__ __launch_bounds__(1024) void grid_fit_search_kernel(const float *__restrict__ W0, long n, long p, long ldw,
+                                                               long g, float levels, int symmetric, int points,
+                                                               int ncand, float *__restrict__ scales,
+                                                               float *__restrict__ zeros) {
+    __shared__ float smn[16][64], smx[16][64];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const long j = (long)blockIdx.x * 64 + tx;
+    const long r0 = (long)blockIdx.y * g;
+    float mn = INFINITY, mx = -INFINITY;
+    if (j < p) {
+        for (long i = ty; i < g; i += 16) {
+            float w = W0[(r0 + i) * ldw + j];
+            mn = fminf(mn, w);
+            mx = fmaxf(mx, w);
+        }
+    }
+    smn[ty][tx] = mn;
+    smx[ty][tx] = mx;
+    __syncthreads();
+    for (int q = 0; q < 16; ++q) {
+        mn = fminf(mn, smn[q][tx]);
+        mx = fmaxf(mx, smx[q][tx]);
+    }
+    __syncthreads();
+    if (symmetric) {
+        const float a = fmaxf(fabsf(mn), fabsf(mx));
+        mn = -a;
+        mx = a;
+    }
+    const float range = __fsub_rn(mx, mn);
+    float best_err = INFINITY, best_dl = __fdiv_rn(range, levels), best_z0 = mn;
+    for (int c = 0; c < ncand; ++c) {
+        const float r = __fsub_rn(1.0f, __fdiv_rn((float)c, (float)points));
+        const float z0 = __fmul_rn(r, mn);
+        const float dl = __fdiv_rn(__fmul_rn(r, range), levels);
+        const float idl = dl == 0.f ? 0.f : __fdiv_rn(1.0f, dl);
+        float e = 0.f;
+        if (j < p) {
+            for (long i = ty; i < g; i += 16) {
+                const float w = W0[(r0 + i) * ldw + j];
+                const float k = fminf(fmaxf(rintf(__fmul_rn(__fsub_rn(w, z0), idl)), 0.f), levels);
+                const float q = __fsub_rn(__fadd_rn(__fmul_rn(k, dl), z0), w);
+                e += q * q;
+            }
+        }
+        smn[ty][tx] = e;
+        __syncthreads();
+        if (ty == 0) {
+            float tot = 0.f;
+            for (int q = 0; q < 16; ++q) tot += smn[q][tx];
+            if (tot < best_err) {
+                best_err = tot;
+                best_dl = dl;
+                best_z0 = z0;
+            }
+        }
+        __syncthreads();
+    }
+    if (ty == 0 && j < p) {
+        scales[(long)blockIdx.y * p + j] = best_dl;
+        zeros[(long)blockIdx.y * p + j] = best_z0;
+    }
+}
+
 __global__ void recip_kernel(const float *__restrict__ x, float *__restrict__ inv, long count) {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) {
@@ -395,6 +463,18 @@ admmq_status admmq_k_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64
     dim3 block(64, 16), grid((unsigned)((p + 63) / 64), (unsigned)(n / g));
     hipLaunchKernelGGL(grid_init_kernel, grid, block, 0, ctx->stream, W0, (long)n, (long)p, (long)ldw, (long)g,
                        (float)((1 << bits) - 1), scales, zeros);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+admmq_status admmq_k_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
+                              int64_t g, int symmetric, int clip_points, double clip_shrink, float *scales,
+                              float *zeros) {
+    if (!symmetric && clip_points <= 0) return admmq_k_grid_init(ctx, W0, n, p, ldw, bits, g, scales, zeros);
+    const int ncand = clip_points > 0 ? (int)(clip_shrink * (double)clip_points) : 0;
+    dim3 block(64, 16), grid((unsigned)((p + 63) / 64), (unsigned)(n / g));
+    hipLaunchKernelGGL(grid_fit_search_kernel, grid, block, 0, ctx->stream, W0, (long)n, (long)p, (long)ldw, (long)g,
+                       (float)((1 << bits) - 1), symmetric, clip_points > 0 ? clip_points : 1, ncand, scales, zeros);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

@@ -57,20 +57,20 @@ def _ctx(lib):
 def test_argument_validation_without_a_gpu(lib):
     h = _ctx(lib)
     one = C.c_void_p(256)      # any non-null address: validation must not dereference it
-    sched = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0)
+    sched = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0)
     q = lambda **k: lib.admmq_quantize_layer(
         h, k.get("H", one), k.get("W0", one), k.get("n", 8), k.get("p", 4), k.get("ldw", 4), k.get("bits", 4),
         k.get("g", 0), C.byref(k.get("sched", sched)), k.get("codes", one), one, one, None)
     assert q(H=None) == 1 and q(W0=None) == 1 and q(codes=None) == 1
     assert q(n=0) == 2 and q(p=0) == 2 and q(ldw=3) == 2 and q(g=3) == 2 and q(g=-1) == 2
     assert q(bits=1) == 3 and q(bits=9) == 3
-    for bad in (binding._Schedule(0, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0),
-                binding._Schedule(10, 0.0, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0),
-                binding._Schedule(10, 0.1, 0.9, 0.01, 1, 0, 0, 0, -1, 0, 0),
-                binding._Schedule(10, 0.1, 1.1, -1.0, 1, 0, 0, 0, -1, 0, 0),
+    for bad in (binding._Schedule(0, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
+                binding._Schedule(10, 0.0, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
+                binding._Schedule(10, 0.1, 0.9, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
+                binding._Schedule(10, 0.1, 1.1, -1.0, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
                 binding._Schedule(10, float("nan"), 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0),
-                binding._Schedule(10, 0.1, 1.1, 0.01, 1, -1, 0, 0, -1, 0, 0),
-                binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -2, 0, 0)):
+                binding._Schedule(10, 0.1, 1.1, 0.01, 1, -1, 0, 0, -1, 0, 0, 0.8, 0, 0),
+                binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -2, 0, 0, 0.8, 0, 0)):
         assert q(sched=bad) == 3
     assert q() == 8                       # valid arguments: stops at the missing device
     cnt = C.c_uint64(0)
