@@ -18,7 +18,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int LS_CHUNK = 1024;   // columns per evaluate block (256 threads x 4)
+constexpr int LS_CHUNK = 256;    // columns per evaluate block (one per thread)
 
 struct PairEval {
     float gain;   // -dL of the chosen combination, 0 if none improves
@@ -82,10 +82,22 @@ __device__ inline void current_g(const float *__restrict__ G, long p, long i1, l
                                  float &g2) {
     g1 = G[i1 * p + j];
     g2 = G[i2 * p + j];
-    for (int k = 0; k < npend; ++k) {
-        const float d1 = pend_d[(long)(2 * k) * p + j], d2 = pend_d[(long)(2 * k + 1) * p + j];
-        g1 -= coef[k][0] * d1 + coef[k][1] * d2;
-        g2 -= coef[k][2] * d1 + coef[k][3] * d2;
+    // four pending slots per trip, so that their loads are in flight together
+    for (int k0 = 0; k0 < npend; k0 += 4) {
+        float d1[4], d2[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = min(k0 + u, npend - 1);
+            d1[u] = pend_d[(long)(2 * k) * p + j];
+            d2[u] = pend_d[(long)(2 * k + 1) * p + j];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (k0 + u < npend) {
+                g1 -= coef[k0 + u][0] * d1[u] + coef[k0 + u][1] * d2[u];
+                g2 -= coef[k0 + u][2] * d1[u] + coef[k0 + u][3] * d2[u];
+            }
+        }
     }
 }
 
@@ -111,16 +123,12 @@ __global__ __launch_bounds__(256) void ls_evaluate_kernel(const float *__restric
     const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
     const float *s1 = scales + (i1 / g) * p, *s2 = scales + (i2 / g) * p;
     float sum = 0.f;
-    const long jbase = (long)blockIdx.x * LS_CHUNK;
-    for (int q = 0; q < 4; ++q) {
-        const long j = jbase + q * 256 + threadIdx.x;
-        if (j < p) {
-            float g1, g2;
-            current_g(G, p, i1, i2, j, pend_d, npend, coef, g1, g2);
-            PairEval e = eval_column(g1, g2, codes[i1 * p + j], codes[i2 * p + j], s1[j], s2[j], h11, h22, h12,
-                                     levels);
-            sum += e.gain;
-        }
+    const long j = (long)blockIdx.x * LS_CHUNK + threadIdx.x;
+    if (j < p) {
+        float g1, g2;
+        current_g(G, p, i1, i2, j, pend_d, npend, coef, g1, g2);
+        PairEval e = eval_column(g1, g2, codes[i1 * p + j], codes[i2 * p + j], s1[j], s2[j], h11, h22, h12, levels);
+        sum = e.gain;
     }
     sum = wave_sum_f(sum);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;

@@ -110,3 +110,32 @@ def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
     # codes themselves may differ: one near-midpoint rounding that falls the other way (fp32 / float64) changes
     # the later trajectory; both end points are valid and their objectives agree (asserted above)
     print(f"{name} slice: ADMM codes differing from the oracle's: {np.mean(sc != ref.admm.codes):.3f}")
+
+
+def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k):
+    """The W-update of the 4096-wide workloads (factorisation of the full Hessian, both products in the tile
+    configuration the layer uses, tridiagonal solve) against the oracle's literal eq. 7 through eigh, within the
+    1e-5 relative Frobenius bar."""
+    cfg = si.CONFIGS["cfg2"]
+    H32 = hessian_16k
+    n, cols = cfg.n, 512                                  # 512 columns: the 256 x 256 tile path is taken
+    W0 = si.layer_weights(cfg)[:, :cols]
+    d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+    dg = d.cpu().numpy()
+    Hd, _ = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    d64 = dg.astype(np.float64)
+    Hs = Hd / d64[:, None] / d64[None, :]
+    lam_e, U = np.linalg.eigh(Hs)
+    lam_e = np.maximum(lam_e, 0)
+    Ws = (W0 * dg[:, None]).astype(np.float32)
+    HWs = Hs @ Ws.astype(np.float64)
+    rng = np.random.default_rng(77)
+    scale = np.abs(Ws).mean()
+    for rho in (0.1, 4.0, 1.7e7):
+        D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        Wref = orc.w_update(U, lam_e, HWs, D.astype(np.float64), V.astype(np.float64), rho)
+        err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
+        print(f"n=4096 rho={rho:g}: relative W-update error {err:.2e}")
+        assert err < 1e-5
