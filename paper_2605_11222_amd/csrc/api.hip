@@ -478,11 +478,20 @@ extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64
     int64_t tiles = t256 * (t256 + 1) / 2;
     if (tiles * 8 < 200) tiles = t128 * (t128 + 1) / 2;
     if (tiles * 8 < 128) tiles = t64 * (t64 + 1) / 2;
-    int64_t split = (1024 + tiles - 1) / tiles;
+    // one 256 x 256 tile block occupies a CU (128 KB of LDS), so blocks run in rounds of 256: pick the split
+    // (at most 64 slices, at least 256 rows each) whose last round is fullest
     const int64_t max_by_rows = rows / 256 > 0 ? rows / 256 : 1;
-    if (split > max_by_rows) split = max_by_rows;
-    if (split > 64) split = 64;
-    if (split < 1) split = 1;
+    int64_t split = 1;
+    double best_fill = 0.0;
+    for (int64_t s = 1; s <= 64 && s <= max_by_rows; ++s) {
+        const int64_t blocks = tiles * s;
+        if (blocks < 256 && s < 64 && s < max_by_rows) continue;      // not even one full round yet
+        const double fill = (double)blocks / (double)(((blocks + 255) / 256) * 256);
+        if (fill > best_fill + 1e-9) {
+            best_fill = fill;
+            split = s;
+        }
+    }
     // the partial slices must fit the arena: shrink the split for very large n
     const size_t slice = (size_t)n * n;
     while (split > 1 && split * slice * 4 > ((size_t)8 << 30)) --split;

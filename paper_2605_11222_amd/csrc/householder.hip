@@ -37,7 +37,7 @@ __device__ inline double coherent_load(const double *ptr) {
 //   sc[2 + 2q] = W_q . v,  sc[3 + 2q] = V_q . v   for the earlier panel slots q.
 // Block-level partial sums are combined by the block that finishes last, in index order, so every
 // reduction has a fixed order although many blocks take part.
-enum { SC_DOT = 0, SC_SCALE = 1, SC_DOTS = 2, SC_COUNT = 2 + 2 * NB };
+enum { SC_SCALE = 1, SC_DOTS = 2, SC_COUNT = 2 + 2 * NB };
 constexpr int ROW_CHUNK = 256;       // elements per block of tri_row_kernel (one per thread)
 constexpr int PART_W = 2 * NB + 1;   // partials per block: squared norm + 2 dots per slot
 
@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
                                                       unsigned *__restrict__ counter,
                                                       const double *__restrict__ part2, int nparts2) {
     __shared__ double vk[NB], wk[NB];
-    __shared__ double xs[ROW_CHUNK], ws[ROW_CHUNK];
+    __shared__ double xs[ROW_CHUNK];
+    __shared__ double red[4][PART_W];
     __shared__ double tot[PART_W];
     __shared__ double scale_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -99,52 +100,61 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
         vk[tid] = Vp[(long)tid * n + k];
         wk[tid] = (tid == c - 1) ? wk_last : Wp[(long)tid * n + k];
     }
-    ws[tid] = wnew;
     __syncthreads();
-    double x = ok ? A[k * n + j] : 0.0;
+    // This element's entries of every earlier slot are loaded once (all loads in flight together) and serve
+    // both the row update and the dots below.  Slots >= c are predicated off; c is uniform.
     const long jj = ok ? j : n - 1;              // clamped index: loads stay in bounds, results unused
-    for (int q0 = 0; q0 < c; q0 += 8) {
-        double wq[8], vq[8];
+    double wq[NB], vq[NB];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int q = min(q0 + u, c - 1);
-            wq[u] = (q == c - 1) ? wnew : Wp[(long)q * n + jj];
-            vq[u] = Vp[(long)q * n + jj];
+    for (int q = 0; q < NB; ++q) {
+        if (q < c) {
+            wq[q] = (q == c - 1) ? wnew : Wp[(long)q * n + jj];
+            vq[q] = Vp[(long)q * n + jj];
+        } else {
+            wq[q] = 0.0;
+            vq[q] = 0.0;
         }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (q0 + u < c) x -= vk[q0 + u] * wq[u] + wk[q0 + u] * vq[u];
     }
+    double x = ok ? A[k * n + j] : 0.0;
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+        if (q < c) x -= vk[q] * wq[q] + wk[q] * vq[q];
     if (ok) xbuf[j] = x;
     const double xt = (ok && j >= k + 2) ? x : 0.0;      // the reflector's tail
-    xs[tid] = xt;
-    __syncthreads();
     // block partials: [0] squared tail norm, [1+2q] W_q . x_tail, [2+2q] V_q . x_tail
-    const long jb = k + (long)blockIdx.x * ROW_CHUNK;
     const int nred = 1 + 2 * c;
-    for (int r = wave; r < nred; r += 4) {
-        double s = 0.0;
+    {
+        const double s0 = wave_sum(xt * xt);
+        if (lane == 0) red[wave][0] = s0;
+    }
 #pragma unroll
-        for (int h = 0; h < ROW_CHUNK / 64; ++h) {
-            const int o = lane + 64 * h;
-            const long jo = min(jb + o, n - 1);
-            double y;
-            if (r == 0) y = xs[o];
-            else {
-                const int q = (r - 1) >> 1;
-                y = ((r - 1) & 1) ? Vp[(long)q * n + jo] : ((q == c - 1) ? ws[o] : Wp[(long)q * n + jo]);
+    for (int q = 0; q < NB; ++q) {
+        if (q < c) {
+            const double sw = wave_sum(wq[q] * xt);
+            const double sv = wave_sum(vq[q] * xt);
+            if (lane == 0) {
+                red[wave][1 + 2 * q] = sw;
+                red[wave][2 + 2 * q] = sv;
             }
-            s += y * xs[o];
         }
-        s = wave_sum(s);
-        if (lane == 0) part[(long)blockIdx.x * PART_W + r] = s;
     }
+    __syncthreads();
+    if (tid < nred)
+        part[(long)blockIdx.x * PART_W + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
     if (!last_block_done(counter, gridDim.x)) return;
-    if (tid < nred) {
-        double s = 0.0;
-        for (unsigned b = 0; b < gridDim.x; ++b) s += coherent_load(part + (long)b * PART_W + tid);
-        tot[tid] = s;
+    // add the block partials in block order; four blocks' worth is fetched per round trip by the whole block
+    double run = 0.0;
+    for (unsigned b0 = 0; b0 < gridDim.x; b0 += 4) {
+        for (int e = tid; e < 4 * PART_W; e += 256) {
+            const unsigned b = b0 + e / PART_W;
+            const int r = e % PART_W;
+            red[e / PART_W][r] = (b < gridDim.x && r < nred) ? coherent_load(part + (long)b * PART_W + r) : 0.0;
+        }
+        __syncthreads();
+        if (tid < nred) run += ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+        __syncthreads();
     }
+    if (tid < nred) tot[tid] = run;
     __syncthreads();
     if (tid == 0) {
         const double sig = tot[0];
