@@ -16,12 +16,13 @@ admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double
 size_t admmq_householder_scratch_doubles(int64_t n);
 int admmq_ls_chunks(int64_t p);
 int admmq_ls_defer();
-admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
-                              int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs,
-                              int npairs, float *partial, int32_t *pend_idx, float *pend_d, int slot,
-                              int32_t *choice, int *dev_moves, double *dev_drop, int apply);
-admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, int64_t n, int64_t p,
-                              const int32_t *pend_idx, const float *pend_d, int count);
+admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes, int64_t n,
+                             int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs_prev,
+                             int npairs_prev, const float *partial_prev, int slot_prev, const int32_t *pairs_cur,
+                             int npairs_cur, int npend, int32_t *pend_idx, float *pend_d, float *partial_cur,
+                             int32_t *choice, int *dev_moves, double *dev_drop);
+admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
+                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
 
 // ---- per-launch profiler ---------------------------------------------------------------------
@@ -127,7 +128,7 @@ size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
 size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
     const size_t np = (size_t)n * (size_t)p;
     return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
-           admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
+           2 * admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
            admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) + 65536;
 }
 
@@ -322,7 +323,7 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     if (drop_out) *drop_out = 0.0;
     if (plan.rounds <= 0 || n < 2) return ADMMQ_OK;
     const size_t total = (size_t)plan.rounds * plan.batches * plan.pairs;
-    float *E = nullptr, *G = nullptr, *partial = nullptr, *pend_d = nullptr;
+    float *E = nullptr, *G = nullptr, *partial = nullptr, *partial_b = nullptr, *pend_d = nullptr;
     int32_t *pairs = nullptr, *choice = nullptr, *pend_idx = nullptr;
     const int K = admmq_ls_defer();
     double *scal = nullptr;
@@ -330,6 +331,7 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     ADMMQ_TRY(take(ctx, G, (size_t)n * p));
     ADMMQ_TRY(take(ctx, pairs, total * 2));
     ADMMQ_TRY(take(ctx, partial, (size_t)plan.pairs * admmq_ls_chunks(p)));
+    ADMMQ_TRY(take(ctx, partial_b, (size_t)plan.pairs * admmq_ls_chunks(p)));
     ADMMQ_TRY(take(ctx, pend_d, (size_t)2 * K * p));
     ADMMQ_TRY(take(ctx, pend_idx, (size_t)2 * K));
     ADMMQ_TRY(take(ctx, choice, 4));
@@ -363,14 +365,19 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, scal, 0, 32));
 
     int moves_total = 0;
+    float *part[2] = {partial, partial_b};
     for (int r = 0; r < plan.rounds; ++r) {
-        for (int m = 0; m < plan.batches; ++m) {
-            const int32_t *bp = pairs + ((size_t)r * plan.batches + m) * plan.pairs * 2;
-            const int slot = m % K;
-            ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, bp, plan.pairs, partial,
-                                       pend_idx, pend_d, slot, choice, dev_moves, scal, 1));
-            if (slot == K - 1 || m == plan.batches - 1)
-                ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, n, p, pend_idx, pend_d, slot + 1));
+        // step s evaluates batch s (s < M) and plans batch s-1 (s > 0) in one launch; G is flushed after the
+        // step that fills the last pending slot, and at the end of the round
+        for (int s = 0; s <= plan.batches; ++s) {
+            const int32_t *cur = s < plan.batches ? pairs + ((size_t)r * plan.batches + s) * plan.pairs * 2 : nullptr;
+            const int32_t *prev = s > 0 ? pairs + ((size_t)r * plan.batches + s - 1) * plan.pairs * 2 : nullptr;
+            const int slot_prev = s > 0 ? (s - 1) % K : 0;
+            ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, prev,
+                                      s > 0 ? plan.pairs : 0, part[(s + 1) & 1], slot_prev, cur, plan.pairs,
+                                      s > 0 ? slot_prev : 0, pend_idx, pend_d, part[s & 1], choice, dev_moves, scal));
+            if (s > 0 && (slot_prev == K - 1 || s == plan.batches))
+                ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, slot_prev + 1));
         }
         double host[2];
         ADMMQ_TRY(read_back(ctx, host, scal, 16));
@@ -683,8 +690,8 @@ extern "C" admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double
     ADMMQ_TRY(admmq_arena_reserve(ctx, admmq_align_up((size_t)npairs * chunks * 4) + 4096));
     float *partial = nullptr;
     ADMMQ_TRY(take(ctx, partial, (size_t)npairs * chunks));
-    ADMMQ_TRY(admmq_k_ls_batch(ctx, H, (float)lambda, (float *)G, (uint8_t *)codes, n, p, bits, g, scales, pairs,
-                               npairs, partial, nullptr, nullptr, 0, nullptr, nullptr, nullptr, 0));
+    ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, (uint8_t *)codes, n, p, bits, g, scales, nullptr, 0, nullptr, 0,
+                              pairs, npairs, 0, nullptr, nullptr, partial, nullptr, nullptr, nullptr));
     ADMMQ_TRY(admmq_k_ls_totals(ctx, partial, chunks, npairs, totals));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;

@@ -5,10 +5,12 @@
 //              combination of (+-delta_i1, +-delta_i2) by eq. 11 if it lowers the loss; the chunk's
 //              summed gain goes to partial[pair][chunk]
 //   plan     : every block sums the chunks in a fixed order and picks the largest total (lowest slot
-//              on ties) - the same winner in every block - then writes, for its own columns, the new
-//              codes and the applied steps of the winner into slot (batch mod K) of a pending list
+//              on ties) - the same winner in every block - then works out, for its own column, the new
+//              codes and the applied steps of the winner: slot (batch mod K) of a pending list
+//   (the plan of batch m and the evaluation of batch m+1 share ONE launch, ls_step_kernel)
 //   flush    : every K batches G is streamed ONCE for all pending pairs:
 //              G[i][j] -= sum_k H'[i][a_k] d1_k[j] + H'[i][b_k] d2_k[j]          (rank-2K correction)
+//              and the stored codes of the pending rows take their moves
 // Between flushes the two gradient rows a candidate pair needs are corrected on the fly from the
 // pending list, so every evaluation sees the gradient of the current codes (Sec. 3.5 step (v)) while
 // the n x p array is read and written once per K applied pairs instead of once per pair.
@@ -61,8 +63,15 @@ constexpr int LS_K = 16;          // pending pairs between two passes over G
 
 // coefficients of the pending corrections for gradient rows i1 and i2:
 //   coef[k][0..3] = H'[i1][a_k], H'[i1][b_k], H'[i2][a_k], H'[i2][b_k]   (0 for an empty slot)
+// and which = bit w set when that slot's row (a_k for even w, b_k for odd w) IS row i1 (w < 2) or i2 (w >= 2):
+// the codes of such a row have moved by the sign of the slot's step
 __device__ inline void load_pending_coef(const float *__restrict__ H, float lambda, long n, long i1, long i2,
-                                         const int32_t *__restrict__ pend_idx, int npend, float (*coef)[4]) {
+                                         const int32_t *__restrict__ pend_idx, int npend, float (*coef)[4],
+                                         int *which) {
+    for (int e = threadIdx.x; e < npend; e += blockDim.x) {
+        const long a = pend_idx[2 * e], b = pend_idx[2 * e + 1];
+        which[e] = a < 0 ? 0 : ((a == i1) | ((b == i1) << 1) | ((a == i2) << 2) | ((b == i2) << 3));
+    }
     for (int e = threadIdx.x; e < npend * 4; e += blockDim.x) {
         const int k = e >> 2, w = e & 3;
         const long row = (w & 2) ? i2 : i1;
@@ -76,154 +85,217 @@ __device__ inline void load_pending_coef(const float *__restrict__ H, float lamb
     }
 }
 
-// gradient entries of rows i1, i2 at column j for the CURRENT codes
-__device__ inline void current_g(const float *__restrict__ G, long p, long i1, long i2, long j,
-                                 const float *__restrict__ pend_d, int npend, const float (*coef)[4], float &g1,
-                                 float &g2) {
-    g1 = G[i1 * p + j];
-    g2 = G[i2 * p + j];
-    // four pending slots per trip, so that their loads are in flight together
-    for (int k0 = 0; k0 < npend; k0 += 4) {
-        float d1[4], d2[4];
+__device__ inline int step_sign(float d) { return (d > 0.f) - (d < 0.f); }
+
+// the pending steps of column j, all slots, in registers (zero beyond npend): the same values serve the
+// winner's rows and the block's own pair
+struct PendCol {
+    float d1[LS_K], d2[LS_K];
+};
+
+__device__ inline void load_pending_col(const float *__restrict__ pend_d, long p, long j, int npend, PendCol &pc) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int k = min(k0 + u, npend - 1);
-            d1[u] = pend_d[(long)(2 * k) * p + j];
-            d2[u] = pend_d[(long)(2 * k + 1) * p + j];
-        }
+    for (int k = 0; k < LS_K; ++k) {
+        const bool on = k < npend;
+        pc.d1[k] = on ? pend_d[(long)(2 * k) * p + j] : 0.f;
+        pc.d2[k] = on ? pend_d[(long)(2 * k + 1) * p + j] : 0.f;
+    }
+}
+
+// stored gradient entries and codes of a row pair at one column -> those of the CURRENT codes: the pending
+// moves are added (codes and G are both brought up to date by the flush)
+__device__ inline void apply_pending(const PendCol &pc, int npend, const float (*coef)[4], const int *which,
+                                     float &g1, float &g2, int &k1, int &k2) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (k0 + u < npend) {
-                g1 -= coef[k0 + u][0] * d1[u] + coef[k0 + u][1] * d2[u];
-                g2 -= coef[k0 + u][2] * d1[u] + coef[k0 + u][3] * d2[u];
+    for (int k = 0; k < LS_K; ++k) {
+        if (k < npend) {
+            g1 -= coef[k][0] * pc.d1[k] + coef[k][1] * pc.d2[k];
+            g2 -= coef[k][2] * pc.d1[k] + coef[k][3] * pc.d2[k];
+            const int wh = which[k];
+            if (wh) {
+                const int s1 = step_sign(pc.d1[k]), s2 = step_sign(pc.d2[k]);
+                k1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
+                k2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
             }
         }
     }
 }
 
-// grid (chunks, npairs), block 256
-__global__ __launch_bounds__(256) void ls_evaluate_kernel(const float *__restrict__ H, float lambda,
-                                                          const float *__restrict__ G,
-                                                          const uint8_t *__restrict__ codes, long n, long p,
-                                                          int levels, long g, const float *__restrict__ scales,
-                                                          const int32_t *__restrict__ pairs,
-                                                          const int32_t *__restrict__ pend_idx,
-                                                          const float *__restrict__ pend_d, int npend,
-                                                          float *__restrict__ partial, int chunks) {
-    __shared__ float sh[4];
-    __shared__ float coef[LS_K][4];
-    const int pr = blockIdx.y;
-    const long i1 = pairs[2 * pr], i2 = pairs[2 * pr + 1];
-    if (i1 < 0 || i2 < 0 || i1 >= n || i2 >= n || i1 == i2) {      // not a row pair: contributes nothing
-        if (threadIdx.x == 0) partial[(long)pr * chunks + blockIdx.x] = 0.f;
-        return;
+// larger total wins; equal totals: the lower slot wins; slot -1 = no candidate
+__device__ inline void better(float &t, int &i, float ot, int oi) {
+    if (oi >= 0 && (ot > t || (ot == t && (i < 0 || oi < i)))) {
+        t = ot;
+        i = oi;
     }
-    load_pending_coef(H, lambda, n, i1, i2, pend_idx, npend, coef);
-    __syncthreads();
-    const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
-    const float *s1 = scales + (i1 / g) * p, *s2 = scales + (i2 / g) * p;
-    float sum = 0.f;
-    const long j = (long)blockIdx.x * LS_CHUNK + threadIdx.x;
-    if (j < p) {
-        float g1, g2;
-        current_g(G, p, i1, i2, j, pend_d, npend, coef, g1, g2);
-        PairEval e = eval_column(g1, g2, codes[i1 * p + j], codes[i2 * p + j], s1[j], s2[j], h11, h22, h12, levels);
-        sum = e.gain;
-    }
-    sum = wave_sum_f(sum);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    if (lane == 0) sh[w] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) partial[(long)pr * chunks + blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
-// grid ceil(p/256), block 256.  Every block finds the same winner; block 0 records it.
-__global__ __launch_bounds__(256) void ls_plan_kernel(const float *__restrict__ H, float lambda,
-                                                      const float *__restrict__ G, uint8_t *__restrict__ codes,
+// One step of the search, grid (chunks, npairs), block 256, one column per thread:
+//   plan     (when a previous batch exists): every block adds that batch's chunk partials in a fixed order and
+//            finds its winner (largest total, lowest slot on ties) - the same winner in every block - and works
+//            out the winner's move at its own column; the blocks of pair 0 store the applied steps into
+//            pending slot `slot_prev`, one thread records the pair;
+//   evaluate (when a current batch exists): the block's own candidate pair at its column, against the codes and
+//            the gradient AFTER the winner's move: the move just planned is taken from registers, never from
+//            memory that another block may be writing.
+// Nothing a block reads is written in the same launch: codes and G change only in the flush, slot `slot_prev`
+// is written here and first read by the next launch.
+// The chunk partials of the two batches live in two buffers that trade places every step.
+// npend = pending slots already in memory (== slot_prev whenever there is a previous batch).
+// The loads that do not depend on the winner (the own pair's rows, the pending steps) are issued before the
+// selection, so that the launch costs two memory round trips in a row, not five.
+__global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ H, float lambda,
+                                                      const float *__restrict__ G, const uint8_t *__restrict__ codes,
                                                       long n, long p, int levels, long g,
                                                       const float *__restrict__ scales,
-                                                      const int32_t *__restrict__ pairs, int npairs,
-                                                      const float *__restrict__ partial, int chunks,
-                                                      int32_t *__restrict__ pend_idx, float *__restrict__ pend_d,
-                                                      int slot, int32_t *__restrict__ choice,
-                                                      int *__restrict__ moves, double *__restrict__ drop) {
-    __shared__ float stot[256];
-    __shared__ int sidx[256];
-    __shared__ float coef[LS_K][4];
-    const int tid = threadIdx.x;
-    float best = 0.f;
-    int bidx = -1;
-    for (int pr = tid; pr < npairs; pr += 256) {
-        float t = 0.f;
-        for (int c = 0; c < chunks; ++c) t += partial[(long)pr * chunks + c];
-        if (t > best) {            // strictly larger: within a thread slots come in increasing order
-            best = t;
-            bidx = pr;
+                                                      const int32_t *__restrict__ pairs_prev, int npairs_prev,
+                                                      const float *__restrict__ partial_prev, int slot_prev,
+                                                      const int32_t *__restrict__ pairs_cur, int npend,
+                                                      int32_t *pend_idx, float *pend_d,
+                                                      float *__restrict__ partial_cur, int chunks,
+                                                      int32_t *__restrict__ choice, int *__restrict__ moves,
+                                                      double *__restrict__ drop) {
+    __shared__ float coef_o[LS_K][4], coef_w[LS_K][4];
+    __shared__ int which_o[LS_K], which_w[LS_K];
+    __shared__ float wtot_sh[4];
+    __shared__ int widx_sh[4];
+    __shared__ float extra[4];
+    __shared__ float sh[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const long j = (long)blockIdx.x * LS_CHUNK + tid;
+    const bool first_block = blockIdx.x == 0 && blockIdx.y == 0;
+    const bool in = j < p;
+
+    // ---- loads that need no winner ---------------------------------------------------------------------
+    long i1 = -1, i2 = -1;
+    bool own = false;
+    if (pairs_cur) {
+        i1 = pairs_cur[2 * blockIdx.y];
+        i2 = pairs_cur[2 * blockIdx.y + 1];
+        own = !(i1 < 0 || i2 < 0 || i1 >= n || i2 >= n || i1 == i2);      // else: not a row pair
+    }
+    PendCol pc;
+    if (in) load_pending_col(pend_d, p, j, npend, pc);
+    float og1 = 0.f, og2 = 0.f, oh11 = 0.f, oh22 = 0.f, oh12 = 0.f, osc1 = 0.f, osc2 = 0.f;
+    int ok1 = 0, ok2 = 0;
+    if (own) {
+        load_pending_coef(H, lambda, n, i1, i2, pend_idx, npend, coef_o, which_o);
+        if (in) {
+            og1 = G[i1 * p + j];
+            og2 = G[i2 * p + j];
+            ok1 = codes[i1 * p + j];
+            ok2 = codes[i2 * p + j];
+            osc1 = scales[(i1 / g) * p + j];
+            osc2 = scales[(i2 / g) * p + j];
+            oh11 = H[i1 * n + i1] + lambda;
+            oh22 = H[i2 * n + i2] + lambda;
+            oh12 = H[i1 * n + i2];
         }
     }
-    stot[tid] = best;
-    sidx[tid] = bidx;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) {
-            const float o = stot[tid + s];
-            const int oi = sidx[tid + s];
-            // larger total wins; equal totals: the lower slot wins
-            if (oi >= 0 && (o > stot[tid] || (o == stot[tid] && (sidx[tid] < 0 || oi < sidx[tid])))) {
-                stot[tid] = o;
-                sidx[tid] = oi;
+    // ---- the previous batch's winner ----------------------------------------------------------------------
+    int win = -1;
+    float wtot = 0.f;
+    if (npairs_prev > 0) {
+        float best = 0.f;
+        int bidx = -1;
+        for (int pr = tid; pr < npairs_prev; pr += 256) {
+            float t = 0.f;
+            for (int c = 0; c < chunks; ++c) t += partial_prev[(long)pr * chunks + c];
+            if (t > best) {        // strictly larger: within a thread slots come in increasing order
+                best = t;
+                bidx = pr;
             }
         }
-        __syncthreads();
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) better(best, bidx, __shfl_xor(best, o, 64), __shfl_xor(bidx, o, 64));
+        if (lane == 0) {
+            wtot_sh[wv] = best;
+            widx_sh[wv] = bidx;
+        }
     }
-    const int win = sidx[0];
-    const float wtot = stot[0];
-    if (blockIdx.x == 0 && tid == 0) {
+    __syncthreads();                         // wave results, coef_o, which_o
+    if (npairs_prev > 0) {
+        wtot = wtot_sh[0];
+        win = widx_sh[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) better(wtot, win, wtot_sh[w], widx_sh[w]);
+    }
+    // ---- the winner's move at column j --------------------------------------------------------------------
+    long wi1 = -1, wi2 = -1;
+    float nd1 = 0.f, nd2 = 0.f;
+    int ws1 = 0, ws2 = 0;
+    if (win >= 0) {
+        wi1 = pairs_prev[2 * win];
+        wi2 = pairs_prev[2 * win + 1];
+        load_pending_coef(H, lambda, n, wi1, wi2, pend_idx, npend, coef_w, which_w);
+        if (own && tid >= 64 && tid < 68) {
+            // the planned move changes the own pair's gradient rows by H'[i][wi1] nd1 + H'[i][wi2] nd2
+            const int e = tid - 64;
+            const long row = (e & 2) ? i2 : i1, col = (e & 1) ? wi2 : wi1;
+            extra[e] = H[row * n + col] + (row == col ? lambda : 0.f);
+        }
+        float g1 = 0.f, g2 = 0.f, h11 = 0.f, h22 = 0.f, h12 = 0.f, sc1 = 0.f, sc2 = 0.f;
+        int k1 = 0, k2 = 0;
+        if (in) {
+            g1 = G[wi1 * p + j];
+            g2 = G[wi2 * p + j];
+            k1 = codes[wi1 * p + j];
+            k2 = codes[wi2 * p + j];
+            sc1 = scales[(wi1 / g) * p + j];
+            sc2 = scales[(wi2 / g) * p + j];
+            h11 = H[wi1 * n + wi1] + lambda;
+            h22 = H[wi2 * n + wi2] + lambda;
+            h12 = H[wi1 * n + wi2];
+        }
+        __syncthreads();                     // coef_w, which_w, extra (win is the same in every thread)
+        if (in) {
+            apply_pending(pc, npend, coef_w, which_w, g1, g2, k1, k2);
+            const PairEval e = eval_column(g1, g2, k1, k2, sc1, sc2, h11, h22, h12, levels);
+            if (e.combo >= 0) {
+                ws1 = (e.combo & 2) ? -1 : 1;
+                ws2 = (e.combo & 1) ? -1 : 1;
+                nd1 = (float)ws1 * sc1;
+                nd2 = (float)ws2 * sc2;
+            }
+        }
+    }
+    if (npairs_prev > 0 && blockIdx.y == 0 && in) {
+        pend_d[(long)(2 * slot_prev) * p + j] = nd1;        // zero steps for an empty slot
+        pend_d[(long)(2 * slot_prev + 1) * p + j] = nd2;
+    }
+    if (npairs_prev > 0 && first_block && tid == 0) {
         choice[0] = win;
-        choice[1] = win >= 0 ? pairs[2 * win] : -1;
-        choice[2] = win >= 0 ? pairs[2 * win + 1] : -1;
-        pend_idx[2 * slot] = win >= 0 ? pairs[2 * win] : -1;
-        pend_idx[2 * slot + 1] = win >= 0 ? pairs[2 * win + 1] : -1;
+        choice[1] = (int32_t)wi1;
+        choice[2] = (int32_t)wi2;
+        pend_idx[2 * slot_prev] = (int32_t)wi1;
+        pend_idx[2 * slot_prev + 1] = (int32_t)wi2;
         if (win >= 0) {
             *moves += 1;
             *drop += (double)wtot;
         }
     }
-    if (win < 0) {
-        // empty slot: zero steps, so that a later on-the-fly correction reads finite values
-        const long j = (long)blockIdx.x * 256 + tid;
-        if (j < p) {
-            pend_d[(long)(2 * slot) * p + j] = 0.f;
-            pend_d[(long)(2 * slot + 1) * p + j] = 0.f;
+    if (!pairs_cur) return;
+    // ---- this block's candidate pair ----------------------------------------------------------------------
+    float gain = 0.f;
+    if (own && in) {
+        apply_pending(pc, npend, coef_o, which_o, og1, og2, ok1, ok2);
+        if (win >= 0) {
+            og1 -= extra[0] * nd1 + extra[1] * nd2;
+            og2 -= extra[2] * nd1 + extra[3] * nd2;
+            ok1 += i1 == wi1 ? ws1 : (i1 == wi2 ? ws2 : 0);
+            ok2 += i2 == wi1 ? ws1 : (i2 == wi2 ? ws2 : 0);
         }
-        return;
+        gain = eval_column(og1, og2, ok1, ok2, osc1, osc2, oh11, oh22, oh12, levels).gain;
     }
-    const long i1 = pairs[2 * win], i2 = pairs[2 * win + 1];
-    load_pending_coef(H, lambda, n, i1, i2, pend_idx, slot, coef);     // slots before this one
+    gain = wave_sum_f(gain);
+    if (lane == 0) sh[wv] = gain;
     __syncthreads();
-    const long j = (long)blockIdx.x * 256 + tid;
-    if (j >= p) return;
-    const float h11 = H[i1 * n + i1] + lambda, h22 = H[i2 * n + i2] + lambda, h12 = H[i1 * n + i2];
-    const float sc1 = scales[(i1 / g) * p + j], sc2 = scales[(i2 / g) * p + j];
-    const int k1 = codes[i1 * p + j], k2 = codes[i2 * p + j];
-    float g1, g2;
-    current_g(G, p, i1, i2, j, pend_d, slot, coef, g1, g2);
-    PairEval e = eval_column(g1, g2, k1, k2, sc1, sc2, h11, h22, h12, levels);
-    float d1 = 0.f, d2 = 0.f;
-    if (e.combo >= 0) {
-        const int sg1 = (e.combo & 2) ? -1 : 1, sg2 = (e.combo & 1) ? -1 : 1;
-        d1 = (float)sg1 * sc1;
-        d2 = (float)sg2 * sc2;
-        codes[i1 * p + j] = (uint8_t)(k1 + sg1);
-        codes[i2 * p + j] = (uint8_t)(k2 + sg2);
-    }
-    pend_d[(long)(2 * slot) * p + j] = d1;
-    pend_d[(long)(2 * slot + 1) * p + j] = d2;
+    if (tid == 0) partial_cur[(long)blockIdx.y * chunks + blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
 // grid (ceil(p/1024), ceil(n/8)), block 256: each thread 4 columns x 8 rows; applies `count` slots
 __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__ H, float lambda,
-                                                       float *__restrict__ G, long n, long p,
+                                                       float *__restrict__ G, uint8_t *__restrict__ codes, long n,
+                                                       long p,
                                                        const int32_t *__restrict__ pend_idx,
                                                        const float *__restrict__ pend_d, int count) {
     // coefficients of this block's 8 rows for every pending slot: coef[k][0][rr] = H'[r0+rr][a_k],
@@ -270,6 +342,19 @@ __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__
                 d2[c] = j0 + c < p ? pend_d[(long)(2 * k + 1) * p + j0 + c] : 0.f;
             }
         }
+        // the block that owns a pending row brings its stored codes up to date (one owner per row and
+        // column, slots in order: a row may sit in several slots)
+        const long a = pend_idx[2 * k], b = pend_idx[2 * k + 1];
+        if (a >= r0 && a < r0 + 8) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j0 + c < p && d1[c] != 0.f) codes[a * p + j0 + c] = (uint8_t)((int)codes[a * p + j0 + c] + step_sign(d1[c]));
+        }
+        if (b >= r0 && b < r0 + 8) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j0 + c < p && d2[c] != 0.f) codes[b * p + j0 + c] = (uint8_t)((int)codes[b * p + j0 + c] + step_sign(d2[c]));
+        }
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) {
             const float c1 = coef[k][0][rr], c2 = coef[k][1][rr];
@@ -300,33 +385,31 @@ __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__
 int admmq_ls_chunks(int64_t p) { return (int)((p + LS_CHUNK - 1) / LS_CHUNK); }
 int admmq_ls_defer() { return LS_K; }
 
-// One batch: evaluate the candidate pairs against the current codes, then (if `apply`) record the best
-// one in pending slot `slot` (= batch index mod K).  The caller flushes after slot K-1 and at the end.
-admmq_status admmq_k_ls_batch(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
-                              int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs,
-                              int npairs, float *partial, int32_t *pend_idx, float *pend_d, int slot,
-                              int32_t *choice, int *dev_moves, double *dev_drop, int apply) {
+// One step: plan the previous batch (if npairs_prev > 0) into pending slot slot_prev, and evaluate the current
+// batch (if pairs_cur) against the state after that move.  npend = pending slots already in memory, i.e. slots
+// 0 .. npend-1 hold earlier moves of the current group (npend == slot_prev whenever there is a previous batch).
+admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes, int64_t n,
+                             int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs_prev,
+                             int npairs_prev, const float *partial_prev, int slot_prev, const int32_t *pairs_cur,
+                             int npairs_cur, int npend, int32_t *pend_idx, float *pend_d, float *partial_cur,
+                             int32_t *choice, int *dev_moves, double *dev_drop) {
     const int chunks = admmq_ls_chunks(p);
     const int levels = (1 << bits) - 1;
-    hipLaunchKernelGGL(ls_evaluate_kernel, dim3((unsigned)chunks, (unsigned)npairs), dim3(256), 0, ctx->stream, H,
-                       lambda, G, codes, (long)n, (long)p, levels, (long)g, scales, pairs, pend_idx, pend_d, slot,
-                       partial, chunks);
-    if (apply) {
-        hipLaunchKernelGGL(ls_plan_kernel, dim3((unsigned)((p + 255) / 256)), dim3(256), 0, ctx->stream, H, lambda, G,
-                           codes, (long)n, (long)p, levels, (long)g, scales, pairs, npairs, partial, chunks, pend_idx,
-                           pend_d, slot, choice, dev_moves, dev_drop);
-    }
+    const unsigned gy = (unsigned)(pairs_cur ? npairs_cur : 1);
+    hipLaunchKernelGGL(ls_step_kernel, dim3((unsigned)chunks, gy), dim3(256), 0, ctx->stream, H, lambda, G, codes,
+                       (long)n, (long)p, levels, (long)g, scales, pairs_prev, npairs_prev, partial_prev, slot_prev,
+                       pairs_cur, npend, pend_idx, pend_d, partial_cur, chunks, choice, dev_moves, dev_drop);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
 
-admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, int64_t n, int64_t p,
-                              const int32_t *pend_idx, const float *pend_d, int count) {
+admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
+                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count) {
     if (count <= 0) return ADMMQ_OK;
     dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
     const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
-    hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, (long)n, (long)p, pend_idx,
-                       pend_d, count);
+    hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n, (long)p,
+                       pend_idx, pend_d, count);
     admmq_prof_end(ctx, sp);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
