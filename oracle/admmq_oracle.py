@@ -18,7 +18,8 @@ Pins (tests/test_oracle_*.py): Hessian against a triple loop; unit diagonal of H
 against numpy.linalg.solve; projection against brute force over the 2^b levels; first iterate equals
 round-to-nearest of W0; key inequality of App. C each iteration; rho_t * residual bounded; eq. 11
 against recomputed objectives; maintained gradient against a recomputed one; n <= 6, 2-bit exhaustive
-enumeration for the local search.  The absolute objective values of the five workloads are
+enumeration for the local search; the dual-grid and codebook projections against the uniform grid they
+reduce to, brute force over the levels, and the key inequality.  The absolute objective values of the five workloads are
 "parity unpinned": the paper prints no worked numeric example of the solver.
 """
 from __future__ import annotations
@@ -200,12 +201,21 @@ def w_update(U, lam, HWs, D, V, rho):
     return U @ ((U.T @ rhs) / (lam + rho)[:, None])
 
 
-def d_update(W, V, rho, d, grid: Grid):
-    """Eqs. 8 and 10: target Wt = W + V/rho; Sigma Wt is rounded on the grid; D = Sigma^{-1}(...)."""
+def project_unscaled(grid, x: np.ndarray):
+    """Projection of unscaled values x onto the admissible set, as (codes, projected values).  A uniform
+    ``Grid`` rounds by eq. 10; the other formats of Sec. 4.3 bring their own ``project``."""
+    if hasattr(grid, "project"):
+        return grid.project(x)
+    k = grid.codes(x)
+    return k, grid.dequant(k)
+
+
+def d_update(W, V, rho, d, grid):
+    """Eqs. 8 and 10: target Wt = W + V/rho; Sigma Wt is projected on the format's set; D = Sigma^{-1}(...)."""
     Wt = W + V / rho
     x = Wt / d[:, None]
-    k = grid.codes(x)
-    Dn = d[:, None] * grid.dequant(k)
+    k, xq = project_unscaled(grid, x)
+    Dn = d[:, None] * xq
     return k, Dn, Wt
 
 
@@ -281,8 +291,140 @@ def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refr
         rho = rho * gamma
     res.codes = k
     res.grid = grid
-    res.Wq = grid.dequant(k)        # = Sigma D^(T)  (Alg. 1 line 10)
+    if hasattr(grid, "project"):
+        res.Wq = D / d[:, None]     # Sigma D^(T); entries a format leaves free have no code to decode
+    else:
+        res.Wq = grid.dequant(k)    # = Sigma D^(T)  (Alg. 1 line 10)
     return res
+
+
+# ----------------------------------------------------------------------------------------------
+# Other formats (Sec. 4.3): only the projection changes, the W- and V-updates stay as they are.
+# The paper names the two formats and gives no formulas; the readings are stated at each class.
+# ----------------------------------------------------------------------------------------------
+
+
+@dataclass
+class DualGridProjection:
+    """Inliers and outliers of every group on separate uniform grids (Sec. 4.3, the ICQuant format).
+
+    Reading: the outlier set is an input, a fixed boolean mask [n][p]; within each group of each output channel
+    the entries flagged as outliers share one grid and the rest another, both with the same number of bits;
+    each grid is fitted by min/max over its own subset of W0 (an empty subset gives a degenerate grid); every
+    entry is rounded by eq. 10 on the grid of its own subset."""
+    inlier: Grid
+    outlier: Grid
+    mask: np.ndarray       # [n][p] bool, True = outlier
+
+    @staticmethod
+    def fit(W0, bits, mask, group_size=0) -> "DualGridProjection":
+        W0 = np.asarray(W0, dtype=np.float64)
+        mask = np.asarray(mask, dtype=bool)
+        n, p = W0.shape
+        g = group_size if group_size > 0 else n
+        levels = 2 ** bits - 1
+        out = []
+        for sel in (~mask, mask):
+            lo = np.where(sel, W0, np.inf).reshape(n // g, g, p).min(axis=1)
+            hi = np.where(sel, W0, -np.inf).reshape(n // g, g, p).max(axis=1)
+            empty = hi < lo
+            lo = np.where(empty, 0.0, lo)
+            hi = np.where(empty, 0.0, hi)
+            delta = (hi - lo) / levels
+            out.append(Grid(delta, lo, bits, delta == 0.0))
+        return DualGridProjection(out[0], out[1], mask)
+
+    def project(self, x: np.ndarray):
+        k_in, k_out = self.inlier.codes(x), self.outlier.codes(x)
+        k = np.where(self.mask, k_out, k_in)
+        xq = np.where(self.mask, self.outlier.dequant(k_out), self.inlier.dequant(k_in))
+        return k, xq
+
+
+@dataclass
+class CodebookProjection:
+    """A non-uniform codebook per output channel, optionally with entries kept dense (Sec. 4.3, the
+    SqueezeLLM format).
+
+    Reading: codebook [L][p], strictly ascending in each column, and the optional mask of kept entries are
+    inputs.  A constrained entry goes to the nearest level of its column (the lower one when two are equally
+    near); a kept entry is unconstrained, so its projection is the entry itself (code 0 by convention)."""
+    codebook: np.ndarray               # [L][p]
+    free: np.ndarray | None = None     # [n][p] bool, True = kept dense
+
+    def project(self, x: np.ndarray):
+        dist = np.abs(x[None, :, :] - self.codebook[:, None, :])       # [L][n][p]
+        k = np.argmin(dist, axis=0)                                    # first minimum = lowest level on ties
+        xq = np.take_along_axis(self.codebook, k, axis=0)
+        if self.free is not None:
+            k = np.where(self.free, 0, k)
+            xq = np.where(self.free, x, xq)
+        return k.astype(np.int64), xq
+
+
+def quantize_layer_format(H, W0, fmt, T=300, rho0=0.1, gamma=1.1, damp=0.01, precondition=True):
+    """Alg. 1 lines 1-10 with the projection of another format (no local search: its unit moves of one grid step
+    are defined for uniform grids only).  Returns (AdmmResult, J of the result, J of the plain projection of W0),
+    both objectives on the damped Hessian."""
+    H = np.asarray(H, dtype=np.float64)
+    W0 = np.asarray(W0, dtype=np.float64)
+    Hd, _ = damp_hessian(H, damp)
+    a = admm(Hd, W0, fmt, T, rho0, gamma, precondition)
+    _, W_near = project_unscaled(fmt, W0)
+    return a, objective(Hd, W0, a.Wq), objective(Hd, W0, W_near)
+
+
+def project_dual_step_format_f32(W, V, rho, rho_next, d, fmt):
+    """fp32 mirror of one projection + dual pass for the formats above (the uniform grid has its own below).
+    Same operation order as there up to the unscaled target x; then
+      dual grid : eq. 10 with the (delta, 1/delta, z0) of the entry's own subset;
+      codebook  : code = number of midpoints m_l = fl(fl(c_l + c_{l+1}) / 2) strictly below x; a kept entry
+                  takes D = Wt itself and a zero dual.
+    Returns codes (uint8), V_new, B_new, the projected unscaled values, and the float64 sum of (W - D_new)^2."""
+    f = np.float32
+    W = np.asarray(W, dtype=f)
+    V = np.asarray(V, dtype=f)
+    n = W.shape[0]
+    rho = f(rho)
+    inv_rho = f(1.0) / rho
+    inv_rho_next = f(1.0) / f(rho_next)
+    d = np.asarray(d, dtype=f)
+    inv_d = (f(1.0) / d)[:, None]
+    q = V * inv_rho
+    wt = W + q
+    x = wt * inv_d
+    free = None
+    if isinstance(fmt, DualGridProjection):
+        parts = []
+        for gr in (fmt.inlier, fmt.outlier):
+            dl = np.asarray(gr.delta, dtype=f)
+            with np.errstate(divide="ignore"):
+                inv_dl = np.where(dl == f(0.0), f(0.0), f(1.0) / dl).astype(f)
+            parts.append((_expand(dl, n), _expand(inv_dl, n), _expand(np.asarray(gr.z0, dtype=f), n)))
+        dl_e, inv_dl_e, z_e = (np.where(fmt.mask, parts[1][i], parts[0][i]) for i in range(3))
+        t = (x - z_e) * inv_dl_e
+        k = np.minimum(np.maximum(np.rint(t), f(0.0)), f(2 ** fmt.inlier.bits - 1))
+        xq = k * dl_e + z_e
+    else:
+        cb = np.asarray(fmt.codebook, dtype=f)
+        mid = (cb[:-1] + cb[1:]) * f(0.5)
+        k = np.zeros(W.shape, dtype=np.int64)
+        for l in range(mid.shape[0]):
+            k += (x > mid[l][None, :])
+        xq = np.take_along_axis(cb, k, axis=0)
+        free = fmt.free
+    Dn = d[:, None] * xq
+    if free is not None:
+        Dn = np.where(free, wt, Dn)
+        xq = np.where(free, x, xq)
+        k = np.where(free, 0, k)
+    r = W - Dn
+    Vn = V + rho * r
+    if free is not None:
+        Vn = np.where(free, f(0.0), Vn)
+    Bn = Dn - Vn * inv_rho_next
+    ss = float(np.sum(r.astype(np.float64) ** 2))
+    return k.astype(np.uint8), Vn.astype(f), Bn.astype(f), xq.astype(f), ss
 
 
 # ----------------------------------------------------------------------------------------------

@@ -131,3 +131,29 @@ def chunk_as_f64(cfg: LayerConfig, xc: np.ndarray) -> np.ndarray:
     if cfg.x_dtype == "bf16":
         return bf16_bits_to_f32(xc).astype(np.float64)
     return xc.astype(np.float64)
+
+
+# ---- inputs of the other formats (Sec. 4.3): the paper takes them from other methods' artefacts, which are not
+# ---- here; these stand in for them ---------------------------------------------------------------------------
+
+
+def outlier_mask(W0: np.ndarray, frac: float = 0.05) -> np.ndarray:
+    """[n][p] bool: in every column, the ceil(frac * n) entries of largest magnitude (ties: lowest row first)."""
+    n, p = W0.shape
+    k = int(np.ceil(frac * n))
+    order = np.argsort(-np.abs(W0), axis=0, kind="stable")[:k]
+    mask = np.zeros((n, p), dtype=bool)
+    np.put_along_axis(mask, order, True, axis=0)
+    return mask
+
+
+def column_codebook(W0: np.ndarray, bits: int) -> np.ndarray:
+    """[2^bits][p] float32, strictly ascending per column: the (l + 1/2)/L quantiles of the column, pushed apart
+    by one float32 step wherever two of them coincide."""
+    L = 1 << bits
+    qs = (np.arange(L) + 0.5) / L
+    cb = np.quantile(W0.astype(np.float64), qs, axis=0).astype(np.float32)
+    for l in range(1, L):
+        bump = np.nextafter(cb[l - 1], np.float32(np.inf))
+        cb[l] = np.where(cb[l] <= cb[l - 1], bump, cb[l])
+    return cb
