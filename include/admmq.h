@@ -201,6 +201,53 @@ admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double lambda, co
                                int32_t group_size, const float *scales, const int32_t *pairs,
                                int32_t npairs, float *totals);
 
+/* ---- other quantization formats (Sec. 4.3) ------------------------------------------------------------
+ * Only the projection of the D-update changes; the W- and V-updates, the schedule and the factorisation
+ * are those of admmq_quantize_layer.  The paper names the two formats and prints no formulas; the
+ * conventions below are this library's.
+ *
+ * ADMMQ_FORMAT_DUAL_GRID: flags[i][j] != 0 marks an outlier.  Within each group of each output channel
+ *   the inliers share one uniform grid and the outliers another (same bits); scales / zeros are
+ *   [2][n/g][p] (inlier grid first), fitted by min/max over each subset of W0 (an empty subset gets
+ *   scale 0: its codes stay 0).
+ * ADMMQ_FORMAT_CODEBOOK: codebook[l][j], l < 2^bits, strictly ascending in l, holds the levels of output
+ *   channel j (bits 1..4, group_size must be 0).  An entry goes to the nearest level, the lower one when
+ *   two are equally near.  flags (may be NULL) marks entries kept dense: they are unconstrained, their
+ *   projection is the target itself, their dual is 0 and their code is 0.
+ * All pointers are device pointers; flags is u8 [n][p] contiguous. */
+typedef enum admmq_format_kind { ADMMQ_FORMAT_DUAL_GRID = 1, ADMMQ_FORMAT_CODEBOOK = 2 } admmq_format_kind;
+
+typedef struct admmq_format {
+    int32_t kind;            /* admmq_format_kind */
+    int32_t bits;
+    int32_t group_size;      /* dual grid: 0 = one group per column; codebook: 0 */
+    const uint8_t *flags;    /* [n][p]; dual grid: required; codebook: optional */
+    const float *codebook;   /* codebook only: [2^bits][p] */
+    float *scales;           /* dual grid only: [2][n/g][p]; written by admmq_quantize_layer_format and */
+    float *zeros;            /*   admmq_grid_init_dual, read by admmq_project_dual_format             */
+} admmq_format;
+
+/* Dual-grid fit on W0 (see above); fmt->scales / fmt->zeros receive the two grids. */
+admmq_status admmq_grid_init_dual(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                                  const admmq_format *fmt);
+
+/* The fused projection + dual pass of admmq_project_dual with the projection of `fmt` (eqs. 8 and 9 with
+ * the format's own admissible set in place of eq. 10).  Xq_out (device fp32 [n][p], may be NULL) receives the
+ * projected values in the unscaled space, Sigma D.  ADMMQ_ERR_PARAM for a codebook that is not finite and
+ * strictly ascending. */
+admmq_status admmq_project_dual_format(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                       const float *d, const admmq_format *fmt, double rho, double rho_next,
+                                       uint8_t *codes, float *B_out, float *Xq_out, double *res_sq);
+
+/* Alg. 1 lines 1-10 with the projection of `fmt`.  codes: device u8 [n][p]; Wq: device fp32 [n][p], the
+ * quantized weights Sigma D^(T) in the unscaled space (kept entries hold their dense values).  No local
+ * search (its moves of one grid step are defined for uniform grids): sched->ls_rounds, refresh_iter (other
+ * than -1), symmetric and clip_points must be 0, else ADMMQ_ERR_PARAM; stats->code_flips must be NULL.
+ * stats->j_damp_rtn is the objective of the plain projection of W0. */
+admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                         int64_t ldw, const admmq_format *fmt, const admmq_schedule *sched,
+                                         uint8_t *codes, float *Wq, admmq_stats *stats);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,4 +14,6 @@ from .binding import (  # noqa: F401
     sample_pair,
     workspace_bytes,
     EXPORTED_SYMBOLS,
+    FORMAT_DUAL_GRID,
+    FORMAT_CODEBOOK,
 )

@@ -12,8 +12,11 @@ EXPORTED_SYMBOLS = [
     "admmq_create", "admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_set_workspace",
     "admmq_accumulate_hessian", "admmq_quantize_layer", "admmq_local_search", "admmq_sample_pair",
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
-    "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit",
+    "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit", "admmq_grid_init_dual",
+    "admmq_project_dual_format", "admmq_quantize_layer_format",
 ]
+
+FORMAT_DUAL_GRID, FORMAT_CODEBOOK = 1, 2
 
 ADMMQ_F32, ADMMQ_BF16 = 0, 1
 
@@ -42,6 +45,11 @@ class _Stats(C.Structure):
                 ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
                 ("ms_project", C.c_float), ("ms_ls_apply", C.c_float), ("refresh_accepted", C.c_int32),
                 ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double)]
+
+
+class _Format(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("bits", C.c_int32), ("group_size", C.c_int32), ("flags", C.c_void_p),
+                ("codebook", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p)]
 
 
 class _LsParams(C.Structure):
@@ -86,6 +94,11 @@ def load_library():
                                        C.POINTER(dbl)]
     lib.admmq_objective.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.admmq_ls_evaluate.argtypes = [vp, vp, dbl, vp, vp, i64, i64, i32, i32, vp, vp, i32, vp]
+    lib.admmq_grid_init_dual.argtypes = [vp, vp, i64, i64, i64, C.POINTER(_Format)]
+    lib.admmq_project_dual_format.argtypes = [vp, vp, vp, i64, i64, vp, C.POINTER(_Format), dbl, dbl, vp, vp, vp,
+                                              C.POINTER(dbl)]
+    lib.admmq_quantize_layer_format.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_Format),
+                                                C.POINTER(_Schedule), vp, vp, C.POINTER(_Stats)]
     lib.admmq_grid_refresh.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, dbl, vp, vp, C.POINTER(i32),
                                        C.POINTER(dbl), C.POINTER(dbl)]
     for name in EXPORTED_SYMBOLS:
@@ -300,6 +313,64 @@ class Context:
                                             _ptr(scales), _ptr(zeros), float(rho), float(rho_next), _ptr(codes),
                                             _ptr(B), C.byref(rs)))
         return codes, B, rs.value
+
+    # ---- other formats (Sec. 4.3) -------------------------------------------------------------------------
+    def _format(self, kind, bits, group_size, n, p, device, flags=None, codebook=None, scales=None, zeros=None):
+        """Marshals an admmq_format; a dual grid without scales / zeros gets fresh [2][n/g][p] arrays."""
+        torch = self._torch
+        if kind == FORMAT_DUAL_GRID and scales is None:
+            g = group_size if group_size else n
+            scales = torch.empty((2, n // g, p), dtype=torch.float32, device=device)
+            zeros = torch.empty((2, n // g, p), dtype=torch.float32, device=device)
+        fmt = _Format(kind, bits, group_size, _ptr(flags), _ptr(codebook), _ptr(scales), _ptr(zeros))
+        return fmt, scales, zeros
+
+    def grid_init_dual(self, W0, bits, flags, group_size=0):
+        n, p = W0.shape
+        fmt, scales, zeros = self._format(FORMAT_DUAL_GRID, bits, group_size, n, p, W0.device, flags=flags)
+        _check(self._lib.admmq_grid_init_dual(self._h, _ptr(W0), n, p, W0.stride(0), C.byref(fmt)))
+        return scales, zeros
+
+    def project_dual_format(self, W, V, d, kind, bits, rho, rho_next, group_size=0, flags=None, codebook=None,
+                            scales=None, zeros=None):
+        """V is updated in place; returns codes, B, Xq (projected unscaled values), ||W-D||_F^2."""
+        torch = self._torch
+        n, p = W.shape
+        fmt, _, _ = self._format(kind, bits, group_size, n, p, W.device, flags, codebook, scales, zeros)
+        codes = torch.empty((n, p), dtype=torch.uint8, device=W.device)
+        B = torch.empty_like(W)
+        Xq = torch.empty_like(W)
+        rs = C.c_double(0.0)
+        _check(self._lib.admmq_project_dual_format(self._h, _ptr(W), _ptr(V), n, p, _ptr(d), C.byref(fmt),
+                                                   float(rho), float(rho_next), _ptr(codes), _ptr(B), _ptr(Xq),
+                                                   C.byref(rs)))
+        return codes, B, Xq, rs.value
+
+    def quantize_layer_format(self, H, W0, kind, bits, group_size=0, flags=None, codebook=None,
+                              sched: Schedule | None = None, want_history=False, profile=False):
+        """Alg. 1 with the projection of another format.  Returns codes, Wq, (scales, zeros) of a dual grid
+        (else None), stats."""
+        torch = self._torch
+        sched = sched or Schedule(ls_rounds=0)
+        n, p = W0.shape
+        fmt, scales, zeros = self._format(kind, bits, group_size, n, p, W0.device, flags, codebook)
+        codes = torch.empty((n, p), dtype=torch.uint8, device=W0.device)
+        Wq = torch.empty((n, p), dtype=torch.float32, device=W0.device)
+        cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
+                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
+        st = _Stats()
+        st.profile = int(bool(profile))
+        res = (C.c_float * sched.T)() if want_history else None
+        if want_history:
+            st.primal_res = C.cast(res, C.POINTER(C.c_float))
+        _check(self._lib.admmq_quantize_layer_format(self._h, _ptr(H), _ptr(W0), n, p, W0.stride(0), C.byref(fmt),
+                                                     C.byref(cs), _ptr(codes), _ptr(Wq), C.byref(st)))
+        out = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
+                         st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
+                         list(res) if want_history else [], [], st.n_gemm, st.n_tridiag, st.n_project,
+                         st.n_ls_apply, st.ms_gemm, st.ms_tridiag, st.ms_project, st.ms_ls_apply, False, 0.0, 0.0)
+        return codes, Wq, (scales, zeros) if kind == FORMAT_DUAL_GRID else None, out
 
     def grid_refresh(self, W, V, d, bits, group_size, rho, scales, zeros):
         """scales/zeros are overwritten when the refit is accepted; returns (accepted, err_old, err_new)."""

@@ -24,6 +24,20 @@ admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const
 admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
                               int64_t p, const int32_t *pend_idx, const float *pend_d, int count);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
+admmq_status admmq_k_dual_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
+                                    int64_t g, const uint8_t *flags, float *scales, float *zeros);
+admmq_status admmq_k_codebook_check(admmq_ctx *ctx, const float *codebook, int L, int64_t p, double *dev_bad);
+admmq_status admmq_k_project_format(admmq_ctx *ctx, int kind, const float *W, float *V, int64_t n, int64_t p,
+                                    const float *d, const float *inv_d, int bits, int64_t g,
+                                    const uint8_t *flags, const float *scales, const float *inv_scales,
+                                    const float *zeros, const float *codebook, float rho, float inv_rho,
+                                    float inv_rho_next, int last, uint8_t *codes, float *B_out, float *Xq,
+                                    double *dev_res_sq);
+admmq_status admmq_k_nearest_error(admmq_ctx *ctx, int kind, const float *W0, int64_t ldw, int64_t n, int64_t p,
+                                   int bits, int64_t g, const uint8_t *flags, const float *scales,
+                                   const float *zeros, const float *codebook, uint8_t *codes, float *E);
+admmq_status admmq_k_diff(admmq_ctx *ctx, const float *A, const float *W0, int64_t ldw, int64_t n, int64_t p,
+                          float *E);
 
 // ---- per-launch profiler ---------------------------------------------------------------------
 int admmq_prof_begin(admmq_ctx *ctx, int tag) {
@@ -941,6 +955,246 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
         stats->ms_factor = ms_factor;
         stats->ms_admm = ms_admm;
         stats->ms_local_search = ms_ls;
+        stats->ms_total = t_total.stop();
+    }
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+// ---- other formats (Sec. 4.3) --------------------------------------------------------------------------
+namespace {
+
+admmq_status check_format(const admmq_format *fmt, int64_t n) {
+    if (!fmt) return ADMMQ_ERR_NULL;
+    if (fmt->kind == ADMMQ_FORMAT_DUAL_GRID) {
+        if (!fmt->flags || !fmt->scales || !fmt->zeros) return ADMMQ_ERR_NULL;
+        if (fmt->bits < 2 || fmt->bits > 8) return ADMMQ_ERR_PARAM;
+        if (fmt->group_size < 0 || (fmt->group_size > 0 && n % fmt->group_size != 0)) return ADMMQ_ERR_SHAPE;
+    } else if (fmt->kind == ADMMQ_FORMAT_CODEBOOK) {
+        if (!fmt->codebook) return ADMMQ_ERR_NULL;
+        if (fmt->bits < 1 || fmt->bits > 4 || fmt->group_size != 0) return ADMMQ_ERR_PARAM;
+    } else {
+        return ADMMQ_ERR_PARAM;
+    }
+    return ADMMQ_OK;
+}
+
+// a codebook must be finite and strictly ascending per column (synchronises)
+admmq_status check_codebook(admmq_ctx *ctx, const admmq_format *fmt, int64_t p) {
+    if (fmt->kind != ADMMQ_FORMAT_CODEBOOK) return ADMMQ_OK;
+    double *dev = nullptr;
+    ADMMQ_TRY(take(ctx, dev, 2));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
+    ADMMQ_TRY(admmq_k_codebook_check(ctx, fmt->codebook, 1 << fmt->bits, p, dev));
+    double bad = 0.0;
+    ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
+    return bad > 0.0 ? ADMMQ_ERR_PARAM : ADMMQ_OK;
+}
+
+}  // namespace
+
+extern "C" admmq_status admmq_grid_init_dual(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                                             const admmq_format *fmt) {
+    if (!ctx || !W0) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_format(fmt, n));
+    if (fmt->kind != ADMMQ_FORMAT_DUAL_GRID) return ADMMQ_ERR_PARAM;
+    ADMMQ_TRY(check_layer_args(W0, W0, n, p, ldw, fmt->bits, fmt->group_size));
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = fmt->group_size > 0 ? fmt->group_size : n;
+    return admmq_k_dual_grid_init(ctx, W0, n, p, ldw, fmt->bits, g, fmt->flags, fmt->scales, fmt->zeros);
+}
+
+extern "C" admmq_status admmq_project_dual_format(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                                  const float *d, const admmq_format *fmt, double rho,
+                                                  double rho_next, uint8_t *codes, float *B_out, float *Xq_out,
+                                                  double *res_sq) {
+    if (!ctx || !W || !V || !d || !B_out) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_format(fmt, n));
+    ADMMQ_TRY(check_layer_args(W, W, n, p, p, 2, fmt->group_size));
+    if (!(rho > 0.0) || !(rho_next > 0.0) || !isfinite(rho) || !isfinite(rho_next)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int64_t g = fmt->group_size > 0 ? fmt->group_size : n;
+    const size_t ng2 = 2 * (size_t)(n / g) * p;
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, admmq_align_up(ng2 * 4) + admmq_align_up((size_t)n * 4) + 8192));
+    float *inv_scales = nullptr, *inv_d = nullptr;
+    double *dev_res = nullptr;
+    ADMMQ_TRY(take(ctx, inv_scales, ng2));
+    ADMMQ_TRY(take(ctx, inv_d, (size_t)n));
+    ADMMQ_TRY(take(ctx, dev_res, 2));
+    ADMMQ_TRY(check_codebook(ctx, fmt, p));
+    if (fmt->kind == ADMMQ_FORMAT_DUAL_GRID) ADMMQ_TRY(admmq_k_recip(ctx, fmt->scales, inv_scales, (int64_t)ng2));
+    ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_res, 0, 16));
+    const float rf = (float)rho;
+    ADMMQ_TRY(admmq_k_project_format(ctx, fmt->kind, W, V, n, p, d, inv_d, fmt->bits, g, fmt->flags, fmt->scales,
+                                     inv_scales, fmt->zeros, fmt->codebook, rf, 1.0f / rf, 1.0f / (float)rho_next, 1,
+                                     codes, B_out, Xq_out, res_sq ? dev_res : nullptr));
+    if (res_sq) ADMMQ_TRY(read_back(ctx, res_sq, dev_res, 8));
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
+extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float *H, const float *W0, int64_t n,
+                                                    int64_t p, int64_t ldw, const admmq_format *fmt,
+                                                    const admmq_schedule *sched, uint8_t *codes, float *Wq,
+                                                    admmq_stats *stats) {
+    if (!ctx || !sched || !codes || !Wq) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_format(fmt, n));
+    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, 2, fmt->group_size));
+    if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
+        !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds != 0 ||
+        sched->refresh_iter != -1 || sched->symmetric != 0 || sched->clip_points != 0)
+        return ADMMQ_ERR_PARAM;
+    if (stats && stats->code_flips) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    const int kind = fmt->kind, bits = fmt->bits;
+    const int64_t g = fmt->group_size > 0 ? fmt->group_size : n;
+    const int T = sched->T;
+    const size_t np = (size_t)n * p;
+    const size_t ng2 = 2 * (size_t)(n / g) * p;
+    const bool want = stats != nullptr;
+    Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
+    t_total.start();
+    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
+    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
+    prof_collect(ctx, prof_ms, prof_cnt);
+    ctx->prof.on = want && stats->profile != 0;
+
+    // --- input checks on the device, before anything is written ------------------------------------------
+    t_phase.start();
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 8192));
+    {
+        double *dev = nullptr;
+        ADMMQ_TRY(take(ctx, dev, 2));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
+        ADMMQ_TRY(admmq_k_count_nonfinite(ctx, W0, n, p, ldw, dev));
+        double bad = 0.0;
+        ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
+        if (bad > 0.0) return ADMMQ_ERR_NOT_FINITE;
+        ADMMQ_TRY(check_codebook(ctx, fmt, p));
+    }
+    float ms_setup = t_phase.stop();
+
+    // --- Alg. 1 lines 1-3 ------------------------------------------------------------------------------------
+    t_phase.start();
+    double lambda = 0.0;
+    if (sched->reuse_factor) {
+        const admmq_factor &have = ctx->fac;
+        if (!have.valid || have.n != n || have.H_src != H || have.damp != sched->damp ||
+            have.precondition != sched->precondition)
+            return ADMMQ_ERR_STATE;
+        lambda = have.lambda;
+        admmq_arena_reset_transient(ctx);
+    } else {
+        ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
+    }
+    float ms_factor = t_phase.stop();
+    const admmq_factor &f = ctx->fac;
+
+    // --- format, initial state, schedule ------------------------------------------------------------------------
+    t_phase.start();
+    ADMMQ_TRY(admmq_arena_reserve(ctx, admm_transient_bytes(n, p, T) + admmq_align_up(ng2 * 4) + 8192));
+    float *B = nullptr, *V = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr, *inv_scales = nullptr;
+    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *res = nullptr, *jdev = nullptr;
+    unsigned long long *unused_flips = nullptr;
+    ADMMQ_TRY(take(ctx, B, np));
+    ADMMQ_TRY(take(ctx, V, np));
+    ADMMQ_TRY(take(ctx, W, np));
+    ADMMQ_TRY(take(ctx, C0, np));
+    ADMMQ_TRY(take(ctx, Y, np));
+    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, inv_scales, ng2));
+    ADMMQ_TRY(take(ctx, rhos, (size_t)T));
+    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, res, (size_t)T));
+    ADMMQ_TRY(take(ctx, unused_flips, (size_t)T));
+    ADMMQ_TRY(take(ctx, jdev, 4));
+    if (kind == ADMMQ_FORMAT_DUAL_GRID) {
+        ADMMQ_TRY(admmq_k_dual_grid_init(ctx, W0, n, p, ldw, bits, g, fmt->flags, fmt->scales, fmt->zeros));
+        ADMMQ_TRY(admmq_k_recip(ctx, fmt->scales, inv_scales, (int64_t)ng2));
+    }
+    ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));      // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
+    std::vector<double> hrho((size_t)T + 1);
+    {
+        double r = sched->rho0;
+        for (int t = 0; t <= T; ++t) {
+            hrho[t] = r;
+            r *= sched->gamma;
+        }
+    }
+    ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
+    gemm_tn_args g0 = {};
+    g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
+    g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g0));                              // C0 = Q^T Ws
+    if (want) {
+        // the plain projection of W0 as the baseline objective (W and Y are still free)
+        ADMMQ_TRY(admmq_k_nearest_error(ctx, kind, W0, ldw, n, p, bits, g, fmt->flags, fmt->scales, fmt->zeros,
+                                        fmt->codebook, nullptr, W));
+        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
+        ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
+    }
+    ms_setup += t_phase.stop();
+
+    // --- ADMM loop (Alg. 1 lines 5-9) with the format's projection ------------------------------------------
+    t_phase.start();
+    float *Bcur = B, *Wcur = W;
+    for (int t = 0; t < T; ++t) {
+        const float rf = (float)hrho[t];
+        if (t == 0) {
+            ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        } else {
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
+        }
+        const bool last = t == T - 1;
+        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
+        ADMMQ_TRY(admmq_k_project_format(ctx, kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, fmt->flags, fmt->scales,
+                                         inv_scales, fmt->zeros, fmt->codebook, rf, 1.0f / rf,
+                                         1.0f / (float)hrho[t + 1], last ? 1 : 0, codes, Wcur, Wq, res + t));
+        admmq_prof_end(ctx, sp);
+        float *tmpp = Bcur;
+        Bcur = Wcur;
+        Wcur = tmpp;
+    }
+    float ms_admm = t_phase.stop();
+
+    if (want) {
+        stats->iters_done = T;
+        stats->lambda = lambda;
+        stats->refresh_accepted = 0;
+        stats->refresh_err_old = 0.0;
+        stats->refresh_err_new = 0.0;
+        if (stats->primal_res) {
+            std::vector<double> h((size_t)T);
+            ADMMQ_TRY(read_back(ctx, h.data(), res, (size_t)T * 8));
+            for (int t = 0; t < T; ++t) stats->primal_res[t] = (float)sqrt(h[t]);
+        }
+        ADMMQ_TRY(admmq_k_diff(ctx, Wq, W0, ldw, n, p, W));         // W, Y are free now
+        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
+        ADMMQ_TRY(read_back(ctx, &stats->j_damp_admm, jdev, 8));
+        stats->j_damp = stats->j_damp_admm;
+        stats->ls_moves = 0;
+    }
+    prof_collect(ctx, prof_ms, prof_cnt);
+    if (want) {
+        stats->ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       stats->n_gemm = prof_cnt[ADMMQ_TAG_GEMM];
+        stats->ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; stats->n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
+        stats->ms_project = prof_ms[ADMMQ_TAG_PROJECT]; stats->n_project = prof_cnt[ADMMQ_TAG_PROJECT];
+        stats->ms_ls_apply = 0.f;                       stats->n_ls_apply = 0;
+        stats->ms_setup = ms_setup;
+        stats->ms_factor = ms_factor;
+        stats->ms_admm = ms_admm;
+        stats->ms_local_search = 0.f;
         stats->ms_total = t_total.stop();
     }
     admmq_arena_reset_transient(ctx);

@@ -139,3 +139,47 @@ def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k):
         err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
         print(f"n=4096 rho={rho:g}: relative W-update error {err:.2e}")
         assert err < 1e-5
+
+
+@pytest.mark.parametrize("kind", ["dual", "codebook"])
+def test_format_projection_at_4096x4096_against_the_mirror(ctx, kind):
+    """Sec. 4.3 projections at the headline layer's size: codes, dual and B bit-exact against the oracle's fp32
+    mirror on a band of rows that spans several thread tiles and both ends of the matrix."""
+    import paper_2605_11222_amd as admmq
+    cfg = si.CONFIGS["cfg2"]
+    n, p = cfg.n, cfg.p
+    rng = np.random.default_rng(77)
+    W0 = si.layer_weights(cfg)
+    d = np.exp(rng.standard_normal(n) * 0.3).astype(np.float32)
+    W = (d[:, None] * W0 + rng.standard_normal((n, p)).astype(np.float32) * 0.003).astype(np.float32)
+    V = (rng.standard_normal((n, p)) * 0.001).astype(np.float32)
+    mask = si.outlier_mask(W0, 0.01)
+    rho, rho_next = 0.5, 0.55
+    Vd = to_dev(V)
+    flags = to_dev(mask.astype(np.uint8))
+    if kind == "dual":
+        g = 128
+        scales, zeros = ctx.grid_init_dual(to_dev(W0), 3, flags, g)
+        codes, B, Xq, rs = ctx.project_dual_format(to_dev(W), Vd, to_dev(d), admmq.FORMAT_DUAL_GRID, 3, rho, rho_next,
+                                                   group_size=g, flags=flags, scales=scales, zeros=zeros)
+        sc, zr = scales.cpu().numpy(), zeros.cpu().numpy()
+    else:
+        cb = si.column_codebook(W0, 3)
+        codes, B, Xq, rs = ctx.project_dual_format(to_dev(W), Vd, to_dev(d), admmq.FORMAT_CODEBOOK, 3, rho, rho_next,
+                                                   flags=flags, codebook=to_dev(cb))
+    codes, B, Vn_g = codes.cpu().numpy(), B.cpu().numpy(), Vd.cpu().numpy()
+    ss_total = 0.0
+    for lo in (0, 1024 - 24, n - 256):                   # 256-row bands; group boundaries (g = 128) inside each
+        rows = slice(lo - lo % 128, lo - lo % 128 + 256)
+        if kind == "dual":
+            gs = slice(rows.start // 128, rows.stop // 128)
+            fmt = orc.DualGridProjection(orc.Grid(sc[0, gs], zr[0, gs], 3, sc[0, gs] == 0),
+                                         orc.Grid(sc[1, gs], zr[1, gs], 3, sc[1, gs] == 0), mask[rows])
+        else:
+            fmt = orc.CodebookProjection(cb, mask[rows])
+        k, Vn, Bn, xq, ss = orc.project_dual_step_format_f32(W[rows], V[rows], rho, rho_next, d[rows], fmt)
+        np.testing.assert_array_equal(codes[rows], k)
+        np.testing.assert_array_equal(Vn_g[rows], Vn)
+        np.testing.assert_array_equal(B[rows], Bn)
+        ss_total += ss
+    assert rs > ss_total > 0

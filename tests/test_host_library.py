@@ -90,6 +90,43 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.admmq_create(None, 0, None) == 1
 
 
+def test_format_argument_validation_without_a_gpu(lib):
+    h = _ctx(lib)
+    one = 256
+    sched = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0)
+    F = binding._Format
+
+    def q(fmt, sched=sched, n=8, stats=None):
+        return lib.admmq_quantize_layer_format(h, C.c_void_p(one), C.c_void_p(one), n, 4, 4, C.byref(fmt),
+                                               C.byref(sched), C.c_void_p(one), C.c_void_p(one), stats)
+    dual = F(binding.FORMAT_DUAL_GRID, 3, 4, one, None, one, one)
+    book = F(binding.FORMAT_CODEBOOK, 3, 0, None, one, None, None)
+    assert q(dual) == 8 and q(book) == 8                                  # valid: stops at the missing device
+    assert q(F(binding.FORMAT_DUAL_GRID, 3, 4, None, None, one, one)) == 1       # a dual grid needs its flags
+    assert q(F(binding.FORMAT_DUAL_GRID, 3, 4, one, None, None, one)) == 1
+    assert q(F(binding.FORMAT_DUAL_GRID, 3, 3, one, None, one, one)) == 2        # group does not divide n
+    assert q(F(binding.FORMAT_DUAL_GRID, 1, 4, one, None, one, one)) == 3
+    assert q(F(binding.FORMAT_CODEBOOK, 3, 0, None, None, None, None)) == 1      # a codebook format needs one
+    assert q(F(binding.FORMAT_CODEBOOK, 5, 0, None, one, None, None)) == 3       # at most 16 levels
+    assert q(F(binding.FORMAT_CODEBOOK, 3, 4, None, one, None, None)) == 3       # levels are per column
+    assert q(F(7, 3, 0, None, one, None, None)) == 3
+    with_ls = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 2, 0, 0, -1, 0, 0, 0.8, 0, 0)
+    with_refresh = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 5, 0, 0, 0.8, 0, 0)
+    assert q(book, sched=with_ls) == 3 and q(dual, sched=with_refresh) == 3
+    st = binding._Stats()
+    flips = (C.c_int64 * 10)()
+    st.code_flips = C.cast(flips, C.POINTER(C.c_int64))
+    assert q(book, stats=C.byref(st)) == 3
+    pd = lambda fmt, rho=0.5: lib.admmq_project_dual_format(
+        h, C.c_void_p(one), C.c_void_p(one), 8, 4, C.c_void_p(one), C.byref(fmt), rho, 0.55, None,
+        C.c_void_p(one), None, None)
+    assert pd(dual) == 8 and pd(book) == 8 and pd(book, rho=0.0) == 3
+    assert lib.admmq_grid_init_dual(h, C.c_void_p(one), 8, 4, 4, C.byref(dual)) == 8
+    assert lib.admmq_grid_init_dual(h, C.c_void_p(one), 8, 4, 4, C.byref(book)) == 3
+    assert lib.admmq_grid_init_dual(h, C.c_void_p(one), 8, 4, 3, C.byref(dual)) == 2
+    lib.admmq_destroy(h)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libadmmq.so")
