@@ -168,7 +168,8 @@ def main():
                      "factorise": mean(lambda s: s.ms_factor) * 1e-3, "admm": admm_ms * 1e-3,
                      "local_search": mean(lambda s: s.ms_local_search) * 1e-3},
         "objective": {"j_damp": stats[-1].j_damp, "j_damp_admm": stats[-1].j_damp_admm,
-                      "j_damp_rtn": stats[-1].j_damp_rtn, "ls_moves": stats[-1].ls_moves},
+                      "j_damp_rtn": stats[-1].j_damp_rtn, "j_recon": stats[-1].j_recon,
+                      "ls_moves": stats[-1].ls_moves},
         "roofline": {"kernel": "gemm_tn (W-update, 2 launches per iteration)", "bound": "mfma",
                      "achieved": gemm_tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tf / PEAK_FP32_MFMA_TFLOPS,

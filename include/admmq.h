@@ -109,6 +109,7 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     float ms_ls_apply;      /* rank-2 gradient correction passes of the local search          */
     int32_t refresh_accepted;          /* 1 if the grid refresh was tried and accepted (eq. 12)  */
     double refresh_err_old, refresh_err_new;   /* the two sides of eq. 12 at the attempt        */
+    double j_recon;         /* Tr(E^T H E) = ||X (Wq - W0)||_F^2 of the final result: j_damp without the damping term */
 } admmq_stats;
 
 /* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.

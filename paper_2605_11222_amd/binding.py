@@ -44,7 +44,7 @@ class _Stats(C.Structure):
                 ("profile", C.c_int32), ("n_gemm", C.c_int32), ("n_tridiag", C.c_int32), ("n_project", C.c_int32),
                 ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
                 ("ms_project", C.c_float), ("ms_ls_apply", C.c_float), ("refresh_accepted", C.c_int32),
-                ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double)]
+                ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double), ("j_recon", C.c_double)]
 
 
 class _Format(C.Structure):
@@ -168,6 +168,7 @@ class LayerStats:
     refresh_accepted: bool = False
     refresh_err_old: float = 0.0
     refresh_err_new: float = 0.0
+    j_recon: float = 0.0
 
 
 def _ptr(t):
@@ -250,7 +251,7 @@ class Context:
                              list(res) if want_history else [], list(flips) if want_history else [],
                              st.n_gemm, st.n_tridiag, st.n_project, st.n_ls_apply, st.ms_gemm, st.ms_tridiag,
                              st.ms_project, st.ms_ls_apply, bool(st.refresh_accepted), st.refresh_err_old,
-                             st.refresh_err_new)
+                             st.refresh_err_new, st.j_recon)
         return codes, scales, zeros, out
 
     def local_search(self, H, W0, bits, group_size, scales, zeros, codes, rounds=5, batches_per_round=0,
@@ -369,7 +370,8 @@ class Context:
         out = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
                          st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
                          list(res) if want_history else [], [], st.n_gemm, st.n_tridiag, st.n_project,
-                         st.n_ls_apply, st.ms_gemm, st.ms_tridiag, st.ms_project, st.ms_ls_apply, False, 0.0, 0.0)
+                         st.n_ls_apply, st.ms_gemm, st.ms_tridiag, st.ms_project, st.ms_ls_apply, False, 0.0, 0.0,
+                         st.j_recon)
         return codes, Wq, (scales, zeros) if kind == FORMAT_DUAL_GRID else None, out
 
     def grid_refresh(self, W, V, d, bits, group_size, rho, scales, zeros):

@@ -287,6 +287,20 @@ admmq_status objective_core(admmq_ctx *ctx, const float *H, double lambda, int64
     return ADMMQ_OK;
 }
 
+// both objectives of a result: J' = Tr(E^T H' E) and J = Tr(E^T H E) = J' - lambda ||E||_F^2 (the reconstruction
+// error ||X E||_F^2 of eq. 2 without the damping term); dev_out: 2 doubles
+admmq_status objectives_core(admmq_ctx *ctx, const float *H, double lambda, int64_t n, int64_t p, const float *E,
+                             float *tmp, double *dev_out, double *j_damp, double *j_recon) {
+    ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, E, tmp, dev_out));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_out + 1, 0, 8));
+    ADMMQ_TRY(admmq_k_dot(ctx, E, E, n * p, dev_out + 1));
+    double h[2];
+    ADMMQ_TRY(read_back(ctx, h, dev_out, 16));
+    *j_damp = h[0];
+    *j_recon = h[0] - lambda * h[1];
+    return ADMMQ_OK;
+}
+
 // One grid-refresh attempt (App. B).  new_sc / new_zr: [n/g][p] scratch; part: 2*blocks doubles scratch.
 // On acceptance scales/zeros are overwritten (and inv_scales, when given).  Synchronises the stream.
 admmq_status grid_refresh_core(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p, const float *d,
@@ -916,8 +930,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
         }
         // objective of the ADMM result; W, Y are free now
         ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, W));
-        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
-        ADMMQ_TRY(read_back(ctx, &stats->j_damp_admm, jdev, 8));
+        ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
         stats->j_damp = stats->j_damp_admm;
         stats->ls_moves = 0;
     }
@@ -941,8 +954,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(take(ctx, tmp, np));
             ADMMQ_TRY(take(ctx, jd, 2));
             ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, E));
-            ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, E, tmp, jd));
-            ADMMQ_TRY(read_back(ctx, &stats->j_damp, jd, 8));
+            ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, E, tmp, jd, &stats->j_damp, &stats->j_recon));
         }
     }
     prof_collect(ctx, prof_ms, prof_cnt);
@@ -1180,8 +1192,7 @@ extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float 
             for (int t = 0; t < T; ++t) stats->primal_res[t] = (float)sqrt(h[t]);
         }
         ADMMQ_TRY(admmq_k_diff(ctx, Wq, W0, ldw, n, p, W));         // W, Y are free now
-        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
-        ADMMQ_TRY(read_back(ctx, &stats->j_damp_admm, jdev, 8));
+        ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
         stats->j_damp = stats->j_damp_admm;
         stats->ls_moves = 0;
     }

@@ -156,6 +156,7 @@ def test_layer_with_another_format_matches_the_oracle(ctx, kind, n, p, N, bits, 
     Hd, _ = orc.damp_hessian(H64)
     Wq_h = Wq.cpu().numpy().astype(np.float64)
     assert abs(orc.objective(Hd, W0.astype(np.float64), Wq_h) - st.j_damp_admm) <= 1e-4 * st.j_damp_admm
+    assert abs(orc.objective(H64, W0.astype(np.float64), Wq_h) - st.j_recon) <= 1e-4 * st.j_recon
     # the returned weights are feasible: every constrained entry is the level its code names
     k = codes.cpu().numpy()
     if kind == "dual":

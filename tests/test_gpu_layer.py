@@ -65,6 +65,11 @@ def test_cfg1_whole_layer_against_oracle(ctx):
     H32 = H.cpu().numpy()
     j64 = f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), cfg.group_size)
     assert st.j_damp == pytest.approx(j64, rel=1e-4)
+    # the reconstruction error ||X (Wq - W0)||_F^2 (undamped H): recomputed in float64, and against the oracle's
+    assert st.j_recon == pytest.approx(f64_objective(H32, 0.0, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(),
+                                                     cfg.group_size), rel=1e-4)
+    assert abs(st.j_recon - ref.j_recon) <= OBJ_TOL * ref.j_recon
+    assert st.j_recon < st.j_damp
     assert st.j_damp_rtn == pytest.approx(ref.j_damp_rtn, rel=1e-4)
     assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
     assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
