@@ -15,11 +15,15 @@
 //   R <- R (I - V T^T V^T) = R - ((R V) T^T) V^T, two tall-skinny products per block, so R is read and
 //   written once per NB reflectors.
 // Every reduction has a fixed order (one wave or one thread per output), so the result is reproducible.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
 
 constexpr int NB = 32;
+
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 __device__ inline double wave_sum(double v) {
 #pragma unroll
@@ -63,7 +67,7 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
                                                       double *__restrict__ ta, double *__restrict__ tb,
                                                       double *__restrict__ sc, double *__restrict__ part,
                                                       unsigned *__restrict__ counter,
-                                                      const double *__restrict__ part2, int nparts2) {
+                                                      const double *__restrict__ part2, int nparts2, int sym) {
     __shared__ double vk[NB], wk[NB];
     __shared__ double xs[ROW_CHUNK];
     __shared__ double red[4][PART_W];
@@ -115,7 +119,8 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
             vq[q] = 0.0;
         }
     }
-    double x = ok ? A[k * n + j] : 0.0;
+    // with only the lower triangle of the trailing matrix kept up to date, row k is read as column k
+    double x = ok ? (sym ? A[j * n + k] : A[k * n + j]) : 0.0;
 #pragma unroll
     for (int q = 0; q < NB; ++q)
         if (q < c) x -= vk[q] * wq[q] + wk[q] * vq[q];
@@ -232,12 +237,213 @@ __global__ __launch_bounds__(256) void tri_mat_kernel(double *__restrict__ A, lo
     if (tid == 0) part[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
+// ---- the same product from the lower triangle alone (large trailing matrices) ---------------------------------
+// While the trailing matrix is too large for the caches the product is bound by reading it; a symmetric matrix
+// needs only its lower triangle read: tile (I, J), J <= I, of 64 x 64 entries adds A_IJ v_J to rows I and
+// A_IJ^T v_I to rows J.  Every tile writes its two pieces to slots of their own, Pb[T][S][64] (T = the tile row
+// the piece belongs to, S = the other tile index), and tri_symv_finish_kernel adds the slots of a row in index
+// order: no atomics, a fixed order.  In this mode only entries with i >= j of the trailing matrix are kept up to
+// date (tri_update_kernel skips the strictly upper tiles, tri_row_kernel reads column k for row k).
+// Tiles are anchored at multiples of 64 of the global index; t0 = (k+1)/64 is the first tile, nt their number.
+constexpr int ST = 64;
+
+__device__ inline void tri_tile_of(int id, int &ti, int &tj) {
+    ti = (int)((sqrtf(8.f * (float)id + 1.f) - 1.f) * 0.5f);
+    while ((long)(ti + 1) * (ti + 2) / 2 <= id) ++ti;
+    while ((long)ti * (ti + 1) / 2 > id) --ti;
+    tj = id - ti * (ti + 1) / 2;
+}
+
+// grid nt (nt + 1) / 2 blocks of 256 threads, one per tile on or below the diagonal; thread (ty, tx) owns rows
+// ty*4.., columns tx*4.. of it.  (Measured at n = 25600: two or four tiles per block, or a square grid whose
+// upper blocks leave at once, are 3 to 10 % slower.)
+constexpr int SG = 1;
+__global__ __launch_bounds__(256) void tri_symv_tile_kernel(const double *__restrict__ A, long n, long k,
+                                                            const double *__restrict__ xbuf,
+                                                            const double *__restrict__ sc, double *__restrict__ Pb,
+                                                            int t0, int nt) {
+    __shared__ double rs[SG][ST], cs[SG][4][ST];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4, wave = tid >> 6;
+    int ti, tj0;
+    tri_tile_of((int)blockIdx.x, ti, tj0);           // one block per tile of the lower triangle, none idle
+    if (ti >= nt) return;                            // cannot happen with that grid; keeps indices in range
+    const long i0 = ((long)t0 + ti) * ST + ty * 4;
+    const double scale = sc[SC_SCALE];
+    const long lead = k + 1;                         // v[lead] = 1, v = 0 before it
+    double xr[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const long i = i0 + a;
+        xr[a] = (i < lead || i >= n) ? 0.0 : (i == lead ? 1.0 : xbuf[i] * scale);
+    }
+    // a tile strictly below the diagonal and wholly inside the trailing block, rows 32-byte aligned: four
+    // 32-byte loads per thread, no masks (the block decides as one)
+    doublex4 rowv[SG][4];
+    bool whole[SG];
+#pragma unroll
+    for (int u = 0; u < SG; ++u) {
+        const int tj = tj0 + u;
+        whole[u] = tj < ti && ((long)t0 + tj) * ST >= lead && ((long)t0 + ti + 1) * ST <= n && (n & 3) == 0;
+        if (whole[u]) {
+            const long j0 = ((long)t0 + tj) * ST + tx * 4;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) rowv[u][a] = *(const doublex4 *)(A + (i0 + a) * n + j0);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < SG; ++u) {
+        const int tj = tj0 + u;
+        if (tj > ti) break;
+        const long j0 = ((long)t0 + tj) * ST + tx * 4;
+        const bool diag = ti == tj;
+        double xc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const long j = j0 + b;
+            xc[b] = (j < lead || j >= n) ? 0.0 : (j == lead ? 1.0 : xbuf[j] * scale);
+        }
+        double rsum[4] = {0.0, 0.0, 0.0, 0.0}, csum[4] = {0.0, 0.0, 0.0, 0.0};
+        if (whole[u]) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    rsum[a] += rowv[u][a][b] * xc[b];
+                    csum[b] += rowv[u][a][b] * xr[a];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const long i = i0 + a;
+                double row[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const long j = j0 + b;
+                    // entries outside the trailing block, and above the diagonal, are never read
+                    row[b] = (i >= lead && i < n && j >= lead && j <= i) ? A[i * n + j] : 0.0;
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    rsum[a] += row[b] * xc[b];
+                    // the transposed piece: strictly below the diagonal only (the diagonal is in the row piece)
+                    if (!diag || j0 + b < i) csum[b] += row[b] * xr[a];
+                }
+            }
+        }
+        // row pieces: add over the 16 tx lanes (adjacent lanes of one wave)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) rsum[a] += __shfl_xor(rsum[a], o, 64);
+        }
+        // column pieces: add over the ty groups of the wave, then over the four waves through LDS
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            csum[b] += __shfl_xor(csum[b], 16, 64);
+            csum[b] += __shfl_xor(csum[b], 32, 64);
+        }
+        if (tx == 0) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) rs[u][ty * 4 + a] = rsum[a];
+        }
+        if ((tid & 63) < 16) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) cs[u][wave][tx * 4 + b] = csum[b];
+        }
+    }
+    __syncthreads();
+    {
+        // thread (u, e): piece e of the group's tile u
+        const int u = tid >> 6, e = tid & 63, tj = tj0 + u;
+        if (u < SG && tj <= ti) {
+            const double col = (cs[u][0][e] + cs[u][1][e]) + (cs[u][2][e] + cs[u][3][e]);
+            if (tj == ti) {
+                Pb[((long)ti * nt + ti) * ST + e] = rs[u][e] + col;
+            } else {
+                Pb[((long)ti * nt + tj) * ST + e] = rs[u][e];
+                Pb[((long)tj * nt + ti) * ST + e] = col;
+            }
+        }
+    }
+}
+
+// p'[i] = sum_S Pb[T][S][e] - sum_q (V_q[i] (W_q.v) + W_q[i] (V_q.v)); stores the normalised v in panel slot c and
+// in row k of A, and the block partials of p'.v, exactly as tri_mat_kernel does.  Block = one tile row: wave w
+// adds the slots S = w, w+4, ... (four loads in flight each), the four sums are combined in a fixed order.
+__global__ __launch_bounds__(256) void tri_symv_finish_kernel(double *__restrict__ A, long n, long k, int c,
+                                                              double *__restrict__ Vp,
+                                                              const double *__restrict__ Wp,
+                                                              const double *__restrict__ xbuf,
+                                                              double *__restrict__ pbuf,
+                                                              const double *__restrict__ sc,
+                                                              const double *__restrict__ Pb, int t0, int nt,
+                                                              double *__restrict__ part) {
+    __shared__ double ad[NB], bd[NB];
+    __shared__ double ys[4][ST];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double scale = sc[SC_SCALE];
+    if (tid < c) {
+        ad[tid] = sc[SC_DOTS + 2 * tid];
+        bd[tid] = sc[SC_DOTS + 2 * tid + 1];
+    }
+    const int T = (int)blockIdx.x;
+    const double *src = Pb + (long)T * nt * ST + lane;
+    double y0 = 0.0, y1 = 0.0, y2 = 0.0, y3 = 0.0;
+    int S = wave;
+    for (; S + 12 < nt; S += 16) {
+        y0 += src[(long)S * ST];
+        y1 += src[(long)(S + 4) * ST];
+        y2 += src[(long)(S + 8) * ST];
+        y3 += src[(long)(S + 12) * ST];
+    }
+    for (; S < nt; S += 4) y0 += src[(long)S * ST];
+    ys[wave][lane] = (y0 + y1) + (y2 + y3);
+    __syncthreads();
+    const long i = ((long)t0 + T) * ST + lane;
+    double wdot = 0.0;
+    if (wave == 0) {
+        if (i >= k + 1 && i < n) {
+            double t = (ys[0][lane] + ys[1][lane]) + (ys[2][lane] + ys[3][lane]);
+            for (int q = 0; q < c; ++q) t -= Vp[(long)q * n + i] * ad[q] + Wp[(long)q * n + i] * bd[q];
+            const double vi = (i == k + 1) ? 1.0 : xbuf[i] * scale;
+            pbuf[i] = t;
+            Vp[(long)c * n + i] = vi;
+            A[k * n + i] = vi;
+            wdot = t * vi;
+        }
+        wdot = wave_sum(wdot);
+        if (lane == 0) part[blockIdx.x] = wdot;
+    }
+}
+
+// A[j][i] = A[i][j] for i > j >= r0: the upper triangle of the trailing block is brought up to date when the
+// factorisation leaves the lower-triangle mode.  32 x 32 tiles through LDS; grid over tile pairs with ti >= tj.
+__global__ void tri_mirror_kernel(double *__restrict__ A, long n, long r0) {
+    __shared__ double tile[32][33];
+    const int tx = threadIdx.x, ty = threadIdx.y;     // 32 x 8
+    int ti, tj;
+    tri_tile_of((int)blockIdx.x, ti, tj);
+    const long i0 = r0 + (long)ti * 32, j0 = r0 + (long)tj * 32;
+    for (int r = ty; r < 32; r += 8) {
+        const long i = i0 + r, j = j0 + tx;
+        tile[r][tx] = (i < n && j < n) ? A[i * n + j] : 0.0;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const long j = j0 + r, i = i0 + tx;           // writes A[j][i], contiguous in i
+        if (i < n && j < n && i > j) A[j * n + i] = tile[tx][r];
+    }
+}
+
 // A[i][j] -= sum_c V_c[i] W_c[j] + W_c[i] V_c[j] for i, j >= r0.  64 x 64 tile per block, 4 x 4 per thread.
+// lower_only: tiles strictly above the diagonal are left alone (only entries with i >= j are kept up to date).
 __global__ __launch_bounds__(256) void tri_update_kernel(double *__restrict__ A, long n, long r0, int nbc,
                                                          const double *__restrict__ Vp,
-                                                         const double *__restrict__ Wp) {
+                                                         const double *__restrict__ Wp, int lower_only) {
     constexpr int CC = 16;
     __shared__ double Vi[CC][64], Wi[CC][64], Vj[CC][64], Wj[CC][64];
+    if (lower_only && blockIdx.x > blockIdx.y) return;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const long i0 = r0 + (long)blockIdx.y * 64, j0 = r0 + (long)blockIdx.x * 64;
     double acc[4][4];
@@ -360,7 +566,7 @@ __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__r
 
 // Gp[s][j][c] = sum over slice s of i of R[j][i] v_c[i]  for rows j >= k0+1 (the slices of the
 // contraction index give the chip enough blocks; they are added in a fixed order by the consumer).
-// Block: 64 rows x NB columns, thread (ty, tx): rows ty*4..+3, columns tx*2, tx*2+1.
+// Block: 64 rows x NB columns on the fp64 matrix cores (v_mfma_f64_16x16x4), one 16-row strip per wave.
 // grid (ceil((n-k0-1)/64), KS).
 constexpr int WY_KS_MAX = 16;
 __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ R, const double *__restrict__ A,
@@ -369,13 +575,13 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
     constexpr int KC = 32;
     __shared__ double Rs[64][KC + 1];
     __shared__ double Vs[NB][KC + 1];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
     const long j0 = k0 + 1 + (long)blockIdx.x * 64;
     const long ibeg = k0 + 1 + (long)blockIdx.y * chunk;
     const long iend = min(n, ibeg + chunk);
-    double acc[4][2];
-#pragma unroll
-    for (int a = 0; a < 4; ++a) acc[a][0] = acc[a][1] = 0.0;
+    // wave w owns rows 16w..16w+15 of the block, both halves of the NB columns: two 16 x 16 accumulators
+    doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
     for (long i0 = ibeg; i0 < iend; i0 += KC) {
         __syncthreads();
         for (int e = tid; e < 64 * KC; e += 256) {
@@ -389,88 +595,99 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
             Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
         }
         __syncthreads();
-#pragma unroll 8
-        for (int q = 0; q < KC; ++q) {
-            const double v0 = Vs[tx * 2][q], v1 = Vs[tx * 2 + 1][q];
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const double r = Rs[ty * 4 + a][q];
-                acc[a][0] += r * v0;
-                acc[a][1] += r * v1;
-            }
+        for (int q = 0; q < KC; q += 4) {
+            // matrix-core operands: A[row = lane%16][k = lane/16], B[k = lane/16][col = lane%16]
+            const double a = Rs[wave * 16 + l16][q + lq];
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[l16][q + lq], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[16 + l16][q + lq], acc1, 0, 0, 0);
         }
     }
+    // accumulator register r of lane l holds row 4r + l/16, column l%16 of its 16 x 16 block
     double *out = Gp + (long)blockIdx.y * n * NB;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const long j = j0 + ty * 4 + a;
+    for (int r = 0; r < 4; ++r) {
+        const long j = j0 + wave * 16 + 4 * r + lq;
         if (j < n) {
-            out[j * NB + tx * 2] = acc[a][0];
-            out[j * NB + tx * 2 + 1] = acc[a][1];
+            out[j * NB + l16] = acc0[r];
+            out[j * NB + 16 + l16] = acc1[r];
         }
     }
 }
 
-// R[j][i] -= sum_c G2[j][c] v_c[i]  for j, i >= k0+1, with G2 = (sum_s Gp[s]) T^T formed per tile.
-// 64 x 64 tile per block, 4 x 4 per thread.
-__global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R, const double *__restrict__ A,
-                                                          long n, long k0, int nbc, int ks,
-                                                          const double *__restrict__ Gp,
-                                                          const double *__restrict__ T) {
-    __shared__ double Gs[64][NB + 1];
-    __shared__ double G2s[64][NB + 1];
-    __shared__ double Vs[NB][64];
+// G2[j][c] = sum_q (sum_s Gp[s][j][q]) T[c][q] for rows j >= k0+1: the slices of the contraction are added in
+// index order and the small triangular factor applied once per row (not once per tile of the update).
+// One thread per (row, c); block 256 = 8 rows.
+__global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__ Gp, const double *__restrict__ T,
+                                                      long n, long k0, int nbc, int ks,
+                                                      double *__restrict__ G2) {
     __shared__ double Ts[NB][NB + 1];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-    const long j0 = k0 + 1 + (long)blockIdx.y * 64, i0 = k0 + 1 + (long)blockIdx.x * 64;
+    __shared__ double Gs[8][NB + 1];
+    const int tid = threadIdx.x, c = tid & (NB - 1), r = tid / NB;
     for (int e = tid; e < NB * NB; e += 256) Ts[e / NB][e % NB] = T[e];
+    const long j = k0 + 1 + (long)blockIdx.x * 8 + r;
+    double g = 0.0;
+    if (j < n && c < nbc)
+        for (int s = 0; s < ks; ++s) g += Gp[((long)s * n + j) * NB + c];
+    Gs[r][c] = g;
+    __syncthreads();
+    if (j < n) {
+        double t = 0.0;
+        for (int q = c; q < nbc; ++q) t += Gs[r][q] * Ts[c][q];          // T is upper triangular
+        G2[j * NB + c] = t;
+    }
+}
+
+// R[j][i] -= sum_c G2[j][c] v_c[i]  for j, i >= k0+1.  64 x 64 tile per block; the product runs on the fp64
+// matrix cores: wave w owns rows 16w..16w+15 of the tile, four 16-column blocks, NB/4 steps each.
+__global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R, const double *__restrict__ A,
+                                                          long n, long k0, int nbc,
+                                                          const double *__restrict__ G2) {
+    __shared__ double G2s[64][NB + 1];
+    __shared__ double Vs[NB][80];          // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
+    const int tid = threadIdx.x;
+    const long j0 = k0 + 1 + (long)blockIdx.y * 64, i0 = k0 + 1 + (long)blockIdx.x * 64;
     for (int e = tid; e < 64 * NB; e += 256) {
         const int r = e / NB, c = e % NB;
         const long j = j0 + r;
-        double g = 0.0;
-        if (j < n && c < nbc)
-            for (int s = 0; s < ks; ++s) g += Gp[((long)s * n + j) * NB + c];
-        Gs[r][c] = g;
+        G2s[r][c] = (j < n && c < nbc) ? G2[j * NB + c] : 0.0;
     }
     for (int e = tid; e < NB * 64; e += 256) {
         const int c = e >> 6, o = e & 63;
         const long i = i0 + o;
         Vs[c][o] = (c < nbc && i < n && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
     }
-    __syncthreads();
-    for (int e = tid; e < 64 * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        double s = 0.0;
-        for (int q = c; q < nbc; ++q) s += Gs[r][q] * Ts[c][q];          // T is upper triangular
-        G2s[r][c] = s;
-    }
-    __syncthreads();
-    double acc[4][4];
+    const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    // the tile's own entries are requested before the operands are waited for
+    double rv[4][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int r = 0; r < 4; ++r) {
+        const long j = j0 + wave * 16 + 4 * r + lq;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
-#pragma unroll 8
-    for (int c = 0; c < NB; ++c) {
-        double g[4], v[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            g[a] = G2s[ty * 4 + a][c];
-            v[a] = Vs[c][tx * 4 + a];
+        for (int b = 0; b < 4; ++b) {
+            const long i = i0 + b * 16 + l16;
+            rv[r][b] = (j < n && i < n) ? R[j * n + i] : 0.0;
         }
+    }
+    __syncthreads();
+    doublex4 acc[4];
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b) acc[b] = doublex4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int b = 0; b < 4; ++b) acc[a][b] += g[a] * v[b];
+    for (int c = 0; c < NB; c += 4) {
+        const double g = G2s[wave * 16 + l16][c + lq];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(g, Vs[c + lq][b * 16 + l16], acc[b], 0, 0, 0);
     }
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const long j = j0 + ty * 4 + a;
+    for (int r = 0; r < 4; ++r) {
+        const long j = j0 + wave * 16 + 4 * r + lq;
         if (j >= n) continue;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const long i = i0 + tx * 4 + b;
-            if (i < n) R[j * n + i] -= acc[a][b];
+            const long i = i0 + b * 16 + l16;
+            if (i < n) R[j * n + i] = rv[r][b] - acc[b][r];
         }
     }
 }
@@ -503,7 +720,17 @@ inline unsigned blocks_for(long count, int bs) { return (unsigned)((count + bs -
 
 size_t admmq_householder_scratch_doubles(int64_t n) {
     const size_t N = (size_t)n;
-    return (3 + 2 * NB + WY_KS_MAX * NB) * N + 2 * NB * NB + SC_COUNT + (N / ROW_CHUNK + 2) * PART_W + (N / 4 + 2) + 64;
+    const size_t nt = N / ST + 2;                 // slots of the lower-triangle product: nt x nt pieces of ST
+    return (3 + 2 * NB + WY_KS_MAX * NB + NB) * N + 2 * NB * NB + SC_COUNT + (N / ROW_CHUNK + 2) * PART_W + (N / 4 + 2) + 64 +
+           nt * nt * ST;
+}
+
+// trailing size from which a panel runs in the lower-triangle mode (the matrix no longer fits the caches);
+// ADMMQ_SYMV_MIN overrides it (read at every factorisation; values below 128 switch the mode off)
+static long symv_min_size() {
+    const char *e = getenv("ADMMQ_SYMV_MIN");
+    long v = e ? atol(e) : 5120;
+    return v < 128 ? (1L << 60) : v;
 }
 
 // A64: [n][n] scaled Hessian (destroyed: reflectors end up in its rows); R64: [n][n] scratch;
@@ -514,8 +741,12 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
     const long N = (long)n;
     double *pbuf = vecs, *xbuf = vecs + N, *tau = vecs + 2 * N, *Vp = vecs + 3 * N, *Wp = Vp + (long)NB * N,
            *Gp = Wp + (long)NB * N, *S = Gp + (long)WY_KS_MAX * NB * N, *T = S + NB * NB, *sc = T + NB * NB,
-           *part1 = sc + SC_COUNT, *part2 = part1 + (N / ROW_CHUNK + 2) * PART_W, *cnt = part2 + (N / 4 + 2);
+           *part1 = sc + SC_COUNT, *part2 = part1 + (N / ROW_CHUNK + 2) * PART_W, *cnt = part2 + (N / 4 + 2),
+           *G2 = cnt + 64, *Pb = G2 + (long)NB * N;
     unsigned *counters = (unsigned *)cnt;          // [0]: tri_row, [2]: tri_mat (8-byte slots)
+    const long sym_min = symv_min_size();
+    bool was_sym = false;
+    int parts_prev = 0;                            // block partials of p'.v left by the previous column's product
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, cnt, 0, 32));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, sc, 0, SC_COUNT * 8));
     if (N <= 2) {
@@ -523,22 +754,45 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
     } else {
         for (long k0 = 0; k0 <= N - 3; k0 += NB) {
             const int nbc = (int)((N - 2 - k0) < NB ? (N - 2 - k0) : NB);
+            const bool sym = N - k0 >= sym_min;
+            if (was_sym && !sym) {
+                // leaving the lower-triangle mode: the upper triangle of the trailing block is stale
+                const long t32 = (N - k0 + 31) / 32;
+                hipLaunchKernelGGL(tri_mirror_kernel, dim3((unsigned)(t32 * (t32 + 1) / 2)), dim3(32, 8), 0, st, A64,
+                                   N, k0);
+            }
+            was_sym = sym;
             for (int c = 0; c < nbc; ++c) {
                 const long k = k0 + c;
-                // the previous column's tri_mat_kernel had blocks_for(N - k, 4) blocks
                 hipLaunchKernelGGL(tri_row_kernel, dim3(blocks_for(N - k, ROW_CHUNK)), dim3(256), 0, st, A64, N, k, c,
                                    c > 0 ? 1 : 0, 1, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2,
-                                   (int)blocks_for(N - k, 4));
-                hipLaunchKernelGGL(tri_mat_kernel, dim3(blocks_for(N - k - 1, 4)), dim3(256), 0, st, A64, N, k, c, Vp,
-                                   Wp, xbuf, pbuf, sc, part2);
+                                   parts_prev, sym ? 1 : 0);
+                if (sym) {
+                    const int t0 = (int)((k + 1) / ST);
+                    const int nt = (int)((N - 1) / ST) - t0 + 1;
+                    hipLaunchKernelGGL(tri_symv_tile_kernel, dim3((unsigned)((long)nt * (nt + 1) / 2)), dim3(256), 0,
+                                       st, A64, N, k, xbuf, sc, Pb, t0, nt);
+                    parts_prev = nt;
+                    hipLaunchKernelGGL(tri_symv_finish_kernel, dim3((unsigned)parts_prev), dim3(256), 0, st, A64, N, k,
+                                       c, Vp, Wp, xbuf, pbuf, sc, Pb, t0, nt, part2);
+                } else {
+                    parts_prev = (int)blocks_for(N - k - 1, 4);
+                    hipLaunchKernelGGL(tri_mat_kernel, dim3((unsigned)parts_prev), dim3(256), 0, st, A64, N, k, c, Vp,
+                                       Wp, xbuf, pbuf, sc, part2);
+                }
             }
             // close the panel's last column, then apply the panel to the trailing matrix
             const long r0 = k0 + nbc;
             hipLaunchKernelGGL(tri_row_kernel, dim3(blocks_for(N - r0, ROW_CHUNK)), dim3(256), 0, st, A64, N, r0, nbc,
-                               1, 0, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2,
-                               (int)blocks_for(N - r0, 4));
+                               1, 0, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2, parts_prev,
+                               sym ? 1 : 0);
             const unsigned tiles = blocks_for(N - r0, 64);
-            hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, nbc, Vp, Wp);
+            hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, nbc, Vp, Wp,
+                               sym ? 1 : 0);
+        }
+        if (was_sym) {
+            // (only when the override keeps the mode on to the end) the closing 2 x 2 block is read as stored
+            hipLaunchKernelGGL(tri_mirror_kernel, dim3(1), dim3(32, 8), 0, st, A64, N, N - 2);
         }
         hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, st, A64, N, ta, tb);
     }
@@ -554,7 +808,7 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
             hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, st, S, tau, k0, nbc, T);
             const long m = N - k0 - 1;
             const unsigned tiles = blocks_for(m, 64);
-            long ks = 512 / (long)tiles;
+            long ks = (2048 + (long)tiles - 1) / (long)tiles;      // eight blocks per compute unit or more
             if (ks > WY_KS_MAX) ks = WY_KS_MAX;
             if (ks > m / 256) ks = m / 256;
             if (ks < 1) ks = 1;
@@ -562,8 +816,8 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
             chunk = (chunk + 31) / 32 * 32;
             hipLaunchKernelGGL(q_wy_g_kernel, dim3(tiles, (unsigned)ks), dim3(256), 0, st, R64, A64, N, k0, nbc, chunk,
                                Gp);
-            hipLaunchKernelGGL(q_wy_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, R64, A64, N, k0, nbc, (int)ks,
-                               Gp, T);
+            hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(m, 8)), dim3(256), 0, st, Gp, T, N, k0, nbc, (int)ks, G2);
+            hipLaunchKernelGGL(q_wy_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, R64, A64, N, k0, nbc, G2);
         }
     }
     dim3 tb32(32, 8), tg((unsigned)((N + 31) / 32), (unsigned)((N + 31) / 32));

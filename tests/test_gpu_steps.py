@@ -171,3 +171,37 @@ def test_w_update_matches_literal_eq7_in_float64(ctx, n, p, N, seed):
         worst = max(worst, err)
         assert err < W_UPDATE_TOL, (rho, err)
     print(f"n={n} p={p}: worst relative W-update error {worst:.2e}")
+
+
+@pytest.mark.parametrize("n,p,N,switch", [(300, 40, 900, 128), (1030, 64, 2100, 512), (640, 33, 400, 128),
+                                          (200, 16, 500, 129)])
+def test_factorisation_from_the_lower_triangle_matches_literal_eq7(ctx, monkeypatch, n, p, N, switch):
+    """The factorisation's mode for large matrices (trailing products read the lower triangle only; the library
+    enters it at sizes no test reaches by default) forced on from n down to `switch`, where it hands over to the
+    ordinary mode: same bar as above, and the same W as the ordinary mode to rounding."""
+    X, W0 = correlated_problem(n, p, N, seed=n, outliers=2)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    Hd, _ = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    rng = np.random.default_rng(n)
+    got = {}
+    for mode, env in (("plain", "0"), ("lower", str(switch))):
+        monkeypatch.setenv("ADMMQ_SYMV_MIN", env)
+        d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+        dg = d.cpu().numpy()
+        Ws = (W0 * dg[:, None]).astype(np.float32)
+        if mode == "plain":
+            scale = np.abs(Ws).mean()
+            D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+            V = (0.05 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        got[mode] = [ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+                     for rho in (0.1, 5.0)]
+    d64 = dg.astype(np.float64)
+    Hs = Hd / d64[:, None] / d64[None, :]
+    lam_e, U = np.linalg.eigh(Hs)
+    lam_e = np.maximum(lam_e, 0)
+    for idx, rho in enumerate((0.1, 5.0)):
+        Wref = orc.w_update(U, lam_e, Hs @ Ws.astype(np.float64), D.astype(np.float64), V.astype(np.float64), rho)
+        for mode in ("plain", "lower"):
+            err = np.linalg.norm(got[mode][idx] - Wref) / np.linalg.norm(Wref)
+            assert err < W_UPDATE_TOL, (mode, rho, err)
+        assert np.linalg.norm(got["lower"][idx] - got["plain"][idx]) <= 2e-6 * np.linalg.norm(Wref)
