@@ -43,7 +43,8 @@ __device__ inline double coherent_load(const double *ptr) {
 // reduction has a fixed order although many blocks take part.
 enum { SC_SCALE = 1, SC_DOTS = 2, SC_COUNT = 2 + 2 * NB };
 constexpr int ROW_CHUNK = 256;       // elements per block of tri_row_kernel (one per thread)
-constexpr int PART_W = 2 * NB + 1;   // partials per block: squared norm + 2 dots per slot
+constexpr int PART_W = 2 * NB + 4;   // partials per block: squared norm + 2 dots per slot (+ 3 values of block 0)
+constexpr int PX_DIAG = 2 * NB + 1, PX_LEAD = 2 * NB + 2, PX_WLEAD = 2 * NB + 3;
 
 __device__ inline bool last_block_done(unsigned *counter, unsigned nblocks) {
     __shared__ int is_last;
@@ -69,101 +70,141 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
                                                       unsigned *__restrict__ counter,
                                                       const double *__restrict__ part2, int nparts2, int sym) {
     __shared__ double vk[NB], wk[NB];
-    __shared__ double xs[ROW_CHUNK];
+    __shared__ double xs[4];
     __shared__ double red[4][PART_W];
     __shared__ double tot[PART_W];
     __shared__ double scale_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long j = k + (long)blockIdx.x * ROW_CHUNK + tid;
     const bool ok = j < n;
+    const long jj = ok ? j : n - 1;              // clamped index: loads stay in bounds, results unused
+    const int cf = c - 1;                        // the slot that do_finish completes
+    // ---- every load that depends on nothing computed here is issued first: one round trip, not four ----------
+    double ds = 0.0;
+    if (do_finish)
+        for (int b = tid; b < nparts2; b += 256) ds += part2[b];
+    double tp = 0.0, pj = 0.0, vpj = 0.0, pk = 0.0, vpk = 0.0;
+    if (do_finish) {
+        tp = tau[k - 1];
+        pj = pbuf[jj];
+        vpj = Vp[(long)cf * n + jj];
+        pk = pbuf[k];
+        vpk = Vp[(long)cf * n + k];
+    }
+    double vk_raw = 0.0, wk_raw = 0.0, w_lead = 0.0, v_lead = 0.0;
+    double wq[NB], vq[NB];
+    double x = 0.0;
+    if (do_start) {
+        if (tid < c) {
+            vk_raw = Vp[(long)tid * n + k];
+            v_lead = Vp[(long)tid * n + k + 1];
+            if (!(do_finish && tid == cf)) {     // that slot's W is being written by this launch
+                wk_raw = Wp[(long)tid * n + k];
+                w_lead = Wp[(long)tid * n + k + 1];
+            }
+        }
+        // this element's entries of every earlier slot serve both the row update and the dots below;
+        // slots >= c are predicated off (c is uniform)
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            wq[q] = (q < c && !(do_finish && q == cf)) ? Wp[(long)q * n + jj] : 0.0;
+            vq[q] = q < c ? Vp[(long)q * n + jj] : 0.0;
+        }
+        // with only the lower triangle of the trailing matrix kept up to date, row k is read as column k
+        x = ok ? (sym ? A[j * n + k] : A[k * n + j]) : 0.0;
+    }
+    // ---- finish column k-1 ---------------------------------------------------------------------------------
     double wnew = 0.0, wk_last = 0.0;
     if (do_finish) {
-        const int cf = c - 1;
-        // p'.v of column k-1: the block partials of its tri_mat_kernel, added in a fixed order
-        double ds = 0.0;
-        for (int b = tid; b < nparts2; b += 256) ds += part2[b];
-        xs[tid] = ds;
+        // p'.v of column k-1: the block partials of its product kernel, added in a fixed order
+        ds = wave_sum(ds);
+        if (lane == 0) xs[wave] = ds;
         __syncthreads();
-        for (int h = 128; h > 0; h >>= 1) {
-            if (tid < h) xs[tid] += xs[tid + h];
-            __syncthreads();
-        }
-        const double pdotv = xs[0];
-        __syncthreads();
-        const double tp = tau[k - 1];
+        const double pdotv = (xs[0] + xs[1]) + (xs[2] + xs[3]);
         const double cc = 0.5 * tp * tp * pdotv;
-        const double *vprev = Vp + (long)cf * n;
         if (ok) {
-            wnew = tp * pbuf[j] - cc * vprev[j];
+            wnew = tp * pj - cc * vpj;
             Wp[(long)cf * n + j] = wnew;
         }
-        wk_last = tp * pbuf[k] - cc * vprev[k];
+        wk_last = tp * pk - cc * vpk;
     }
     if (!do_start) return;
     if (tid < c) {
-        vk[tid] = Vp[(long)tid * n + k];
-        wk[tid] = (tid == c - 1) ? wk_last : Wp[(long)tid * n + k];
+        vk[tid] = vk_raw;
+        wk[tid] = (do_finish && tid == cf) ? wk_last : wk_raw;
     }
-    __syncthreads();
-    // This element's entries of every earlier slot are loaded once (all loads in flight together) and serve
-    // both the row update and the dots below.  Slots >= c are predicated off; c is uniform.
-    const long jj = ok ? j : n - 1;              // clamped index: loads stay in bounds, results unused
-    double wq[NB], vq[NB];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) {
-        if (q < c) {
-            wq[q] = (q == c - 1) ? wnew : Wp[(long)q * n + jj];
-            vq[q] = Vp[(long)q * n + jj];
-        } else {
-            wq[q] = 0.0;
-            vq[q] = 0.0;
-        }
-    }
-    // with only the lower triangle of the trailing matrix kept up to date, row k is read as column k
-    double x = ok ? (sym ? A[j * n + k] : A[k * n + j]) : 0.0;
+    for (int q = 0; q < NB; ++q)
+        if (do_finish && q == cf) wq[q] = wnew;
+    __syncthreads();
 #pragma unroll
     for (int q = 0; q < NB; ++q)
         if (q < c) x -= vk[q] * wq[q] + wk[q] * vq[q];
     if (ok) xbuf[j] = x;
     const double xt = (ok && j >= k + 2) ? x : 0.0;      // the reflector's tail
-    // block partials: [0] squared tail norm, [1+2q] W_q . x_tail, [2+2q] V_q . x_tail
+    // block partials: [0] squared tail norm, [1+2q] W_q . x_tail, [2+2q] V_q . x_tail; block 0 adds
+    // [PX_DIAG] x[k], [PX_LEAD] x[k+1], [PX_WLEAD] the W entry at k+1 of the slot completed above
     const int nred = 1 + 2 * c;
     {
         const double s0 = wave_sum(xt * xt);
         if (lane == 0) red[wave][0] = s0;
     }
+    // The 2 NB dots of the wave are reduced together: at the step with lane distance h every lane keeps the half
+    // of its values whose slot has bit h equal to its own lane bit and hands the other half to its partner, so
+    // after six steps lane L holds the complete sum of slot L.  63 exchanges instead of 6 per dot, no branches
+    // (slots >= c hold zeros), the same pairwise order every time.
+    {
+        double v[2 * NB];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) {
-        if (q < c) {
-            const double sw = wave_sum(wq[q] * xt);
-            const double sv = wave_sum(vq[q] * xt);
-            if (lane == 0) {
-                red[wave][1 + 2 * q] = sw;
-                red[wave][2 + 2 * q] = sv;
+        for (int q = 0; q < NB; ++q) {
+            v[2 * q] = wq[q] * xt;
+            v[2 * q + 1] = vq[q] * xt;
+        }
+#pragma unroll
+        for (int h = NB; h >= 1; h >>= 1) {
+            const bool up = (lane & h) != 0;
+#pragma unroll
+            for (int i = 0; i < h; ++i) {
+                const double keep = up ? v[i + h] : v[i];
+                const double send = up ? v[i] : v[i + h];
+                v[i] = keep + __shfl_xor(send, h, 64);
             }
         }
+        red[wave][1 + lane] = v[0];
     }
     __syncthreads();
     if (tid < nred)
         part[(long)blockIdx.x * PART_W + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-    if (!last_block_done(counter, gridDim.x)) return;
-    // add the block partials in block order; four blocks' worth is fetched per round trip by the whole block
-    double run = 0.0;
-    for (unsigned b0 = 0; b0 < gridDim.x; b0 += 4) {
-        for (int e = tid; e < 4 * PART_W; e += 256) {
-            const unsigned b = b0 + e / PART_W;
-            const int r = e % PART_W;
-            red[e / PART_W][r] = (b < gridDim.x && r < nred) ? coherent_load(part + (long)b * PART_W + r) : 0.0;
+    if (blockIdx.x == 0) {
+        if (tid == 0) part[PX_DIAG] = x;
+        if (tid == 1) {
+            part[PX_LEAD] = x;
+            part[PX_WLEAD] = wnew;
         }
-        __syncthreads();
-        if (tid < nred) run += ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
-        __syncthreads();
     }
-    if (tid < nred) tot[tid] = run;
+    if (!last_block_done(counter, gridDim.x)) return;
+    // add the block partials in block order: thread r owns partial r; eight blocks' worth of its loads are in
+    // flight at a time, the additions stay in index order
+    double run = 0.0;
+    if (tid < nred) {
+        const double *src = part + tid;
+        unsigned b0 = 0;
+        for (; b0 + 8 <= gridDim.x; b0 += 8) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = coherent_load(src + (long)(b0 + u) * PART_W);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) run += v[u];
+        }
+        for (; b0 < gridDim.x; ++b0) run += coherent_load(src + (long)b0 * PART_W);
+    } else if (tid >= PX_DIAG && tid < PART_W) {
+        run = coherent_load(part + tid);         // block 0's three plain values
+    }
+    if (tid < PART_W) tot[tid] = run;
     __syncthreads();
     if (tid == 0) {
         const double sig = tot[0];
-        const double alpha = coherent_load(xbuf + k + 1);
+        const double alpha = tot[PX_LEAD];
         double beta, tk, scale;
         if (sig == 0.0) {
             beta = alpha; tk = 0.0; scale = 0.0;
@@ -173,7 +214,7 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
             tk = (beta - alpha) / beta;
             scale = 1.0 / (alpha - beta);
         }
-        ta[k] = coherent_load(xbuf + k);
+        ta[k] = tot[PX_DIAG];
         tb[k] = beta;
         tau[k] = tk;
         sc[SC_SCALE] = scale;
@@ -184,8 +225,9 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
     if (tid < c) {
         // v = (1, scale * x_tail): dots with the earlier slots, the leading 1 sits at index k+1
         const double scale = scale_sh;
-        sc[SC_DOTS + 2 * tid] = scale * tot[1 + 2 * tid] + coherent_load(Wp + (long)tid * n + k + 1);
-        sc[SC_DOTS + 2 * tid + 1] = scale * tot[2 + 2 * tid] + Vp[(long)tid * n + k + 1];
+        const double wl = (do_finish && tid == cf) ? tot[PX_WLEAD] : w_lead;
+        sc[SC_DOTS + 2 * tid] = scale * tot[1 + 2 * tid] + wl;
+        sc[SC_DOTS + 2 * tid + 1] = scale * tot[2 + 2 * tid] + v_lead;
     }
 }
 
@@ -436,21 +478,31 @@ __global__ void tri_mirror_kernel(double *__restrict__ A, long n, long r0) {
     }
 }
 
-// A[i][j] -= sum_c V_c[i] W_c[j] + W_c[i] V_c[j] for i, j >= r0.  64 x 64 tile per block, 4 x 4 per thread.
+// A[i][j] -= sum_c V_c[i] W_c[j] + W_c[i] V_c[j] for i, j >= r0.  64 x 64 tile per block on the fp64 matrix
+// cores: wave w owns rows 16w..16w+15, four 16-column blocks, two products per step of four panel slots.
 // lower_only: tiles strictly above the diagonal are left alone (only entries with i >= j are kept up to date).
 __global__ __launch_bounds__(256) void tri_update_kernel(double *__restrict__ A, long n, long r0, int nbc,
                                                          const double *__restrict__ Vp,
                                                          const double *__restrict__ Wp, int lower_only) {
-    constexpr int CC = 16;
-    __shared__ double Vi[CC][64], Wi[CC][64], Vj[CC][64], Wj[CC][64];
+    constexpr int CC = 16, LD = 80;      // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
+    __shared__ double Vi[CC][LD], Wi[CC][LD], Vj[CC][LD], Wj[CC][LD];
     if (lower_only && blockIdx.x > blockIdx.y) return;
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
     const long i0 = r0 + (long)blockIdx.y * 64, j0 = r0 + (long)blockIdx.x * 64;
-    double acc[4][4];
+    // the tile's own entries are requested first
+    double av[4][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int r = 0; r < 4; ++r) {
+        const long i = i0 + wave * 16 + 4 * r + lq;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+        for (int bb = 0; bb < 4; ++bb) {
+            const long j = j0 + bb * 16 + l16;
+            av[r][bb] = (i < n && j < n) ? A[i * n + j] : 0.0;
+        }
+    }
+    doublex4 acc[4];
+#pragma unroll
+    for (int bb = 0; bb < 4; ++bb) acc[bb] = doublex4{0.0, 0.0, 0.0, 0.0};
     for (int cb = 0; cb < nbc; cb += CC) {
         __syncthreads();
         for (int e = tid; e < CC * 64; e += 256) {
@@ -464,29 +516,23 @@ __global__ __launch_bounds__(256) void tri_update_kernel(double *__restrict__ A,
         }
         __syncthreads();
 #pragma unroll
-        for (int c = 0; c < CC; ++c) {
-            double vi[4], wi[4], vj[4], wj[4];
+        for (int c = 0; c < CC; c += 4) {
+            const double v = Vi[c + lq][wave * 16 + l16], w = Wi[c + lq][wave * 16 + l16];
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                vi[a] = Vi[c][ty * 4 + a];
-                wi[a] = Wi[c][ty * 4 + a];
-                vj[a] = Vj[c][tx * 4 + a];
-                wj[a] = Wj[c][tx * 4 + a];
+            for (int bb = 0; bb < 4; ++bb) {
+                acc[bb] = __builtin_amdgcn_mfma_f64_16x16x4f64(v, Wj[c + lq][bb * 16 + l16], acc[bb], 0, 0, 0);
+                acc[bb] = __builtin_amdgcn_mfma_f64_16x16x4f64(w, Vj[c + lq][bb * 16 + l16], acc[bb], 0, 0, 0);
             }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) acc[a][b] += vi[a] * wj[b] + wi[a] * vj[b];
         }
     }
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const long i = i0 + ty * 4 + a;
+    for (int r = 0; r < 4; ++r) {
+        const long i = i0 + wave * 16 + 4 * r + lq;
         if (i >= n) continue;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const long j = j0 + tx * 4 + b;
-            if (j < n) A[i * n + j] -= acc[a][b];
+        for (int bb = 0; bb < 4; ++bb) {
+            const long j = j0 + bb * 16 + l16;
+            if (j < n) A[i * n + j] = av[r][bb] - acc[bb][r];
         }
     }
 }
@@ -546,15 +592,20 @@ __global__ __launch_bounds__(256) void q_gram_kernel(const double *__restrict__ 
 // T[0:c, c] = -tau_c T[0:c, 0:c] S[0:c, c].  One block of NB threads (thread r owns row r).
 __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__restrict__ tau, long k0, int nbc,
                                  double *__restrict__ T) {
-    __shared__ double Ts[NB][NB + 1];
+    __shared__ double Ts[NB][NB + 1], Ss[NB][NB + 1];
+    __shared__ double taus[NB];
     const int r = threadIdx.x;
-    for (int c = 0; c < NB; ++c) Ts[r][c] = 0.0;
+    for (int c = 0; c < NB; ++c) {
+        Ts[r][c] = 0.0;
+        Ss[c][r] = S[c * NB + r];                  // the Gram matrix and the taus are fetched once, up front
+    }
+    taus[r] = r < nbc ? tau[k0 + r] : 0.0;
     __syncthreads();
     for (int c = 0; c < nbc; ++c) {
-        const double tc = tau[k0 + c];
+        const double tc = taus[c];
         if (r < c) {
             double s = 0.0;
-            for (int q = r; q < c; ++q) s += Ts[r][q] * S[q * NB + c];
+            for (int q = r; q < c; ++q) s += Ts[r][q] * Ss[q][c];
             Ts[r][c] = -tc * s;
         } else if (r == c) {
             Ts[r][c] = tc;
