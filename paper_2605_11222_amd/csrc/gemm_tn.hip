@@ -92,7 +92,7 @@ __device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tile
 }
 
 template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_tn_kernel(GemmParams P) {
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 2 : 1) void gemm_tn_kernel(GemmParams P) {
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
     constexpr int NT = 64 * WGM * WGN;
@@ -449,13 +449,16 @@ admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
     }
     if (big) {
         // measured on MI355X (W-update products, n = p = 4096): eight waves of 64 x 128 with 32-row stages
-        // reach 134 TFLOP/s, four waves of 128 x 128 with 16-row stages 128 TFLOP/s
-        switch (variant) {
+        // reach 135 TFLOP/s, four waves of 128 x 128 with 16-row stages 128 TFLOP/s; variant 6 (128 x 256 tiles,
+        // four waves, two blocks per compute unit whose barriers fall at different times) reaches the same
+        // 135: the barrier is not what keeps the matrix pipe at 86 % busy
+        switch (a.lower_only ? 0 : variant) {      // the triangle enumeration needs square tiles
             case 1: return launch_cfg<4, 4, 2, 2, 16>(ctx, a);
             case 2: return launch_cfg<4, 4, 2, 2, 32>(ctx, a);
             case 3: return launch_cfg<2, 4, 4, 2, 16>(ctx, a);
             case 4: return launch_cfg<4, 2, 2, 4, 32>(ctx, a);
             case 5: return launch_cfg<2, 2, 4, 4, 32>(ctx, a);
+            case 6: return launch_cfg<2, 4, 2, 2, 16>(ctx, a);
             default: return launch_cfg<2, 4, 4, 2, 32>(ctx, a);
         }
     }
