@@ -16,11 +16,12 @@ admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double
 size_t admmq_householder_scratch_doubles(int64_t n);
 int admmq_ls_chunks(int64_t p);
 int admmq_ls_defer();
-admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes, int64_t n,
-                             int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs_prev,
-                             int npairs_prev, const float *partial_prev, int slot_prev, const int32_t *pairs_cur,
-                             int npairs_cur, int npend, int32_t *pend_idx, float *pend_d, float *partial_cur,
-                             int32_t *choice, int *dev_moves, double *dev_drop);
+admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes,
+                             int64_t n, int64_t p, int bits, int64_t g, const float *scales,
+                             const int32_t *pairs_prev, int npairs_prev, const float *partial_prev,
+                             const uint8_t *mv_prev, int slot_prev, const int32_t *pairs_cur, int npairs_cur,
+                             int npend, int32_t *pend_idx, float *pend_d, float *hcol, float *partial_cur,
+                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop);
 admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
                               int64_t p, const int32_t *pend_idx, const float *pend_d, int count);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
@@ -143,7 +144,8 @@ size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_p
     const size_t np = (size_t)n * (size_t)p;
     return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
            2 * admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
-           admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) + 65536;
+           admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) +
+           2 * admmq_align_up((size_t)pairs_per_batch * p) + admmq_align_up((size_t)2 * admmq_ls_defer() * n * 4) + 65536;
 }
 
 admmq_status read_back(admmq_ctx *ctx, void *host, const void *dev, size_t bytes) {
@@ -353,6 +355,8 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     const size_t total = (size_t)plan.rounds * plan.batches * plan.pairs;
     float *E = nullptr, *G = nullptr, *partial = nullptr, *partial_b = nullptr, *pend_d = nullptr;
     int32_t *pairs = nullptr, *choice = nullptr, *pend_idx = nullptr;
+    uint8_t *mv_a = nullptr, *mv_b = nullptr;
+    float *hcol = nullptr;
     const int K = admmq_ls_defer();
     double *scal = nullptr;
     ADMMQ_TRY(take(ctx, E, (size_t)n * p));
@@ -361,6 +365,9 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     ADMMQ_TRY(take(ctx, partial, (size_t)plan.pairs * admmq_ls_chunks(p)));
     ADMMQ_TRY(take(ctx, partial_b, (size_t)plan.pairs * admmq_ls_chunks(p)));
     ADMMQ_TRY(take(ctx, pend_d, (size_t)2 * K * p));
+    ADMMQ_TRY(take(ctx, mv_a, (size_t)plan.pairs * p));
+    ADMMQ_TRY(take(ctx, mv_b, (size_t)plan.pairs * p));
+    ADMMQ_TRY(take(ctx, hcol, (size_t)2 * K * n));
     ADMMQ_TRY(take(ctx, pend_idx, (size_t)2 * K));
     ADMMQ_TRY(take(ctx, choice, 4));
     ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double), scal[1] reinterpreted: moves (int)
@@ -391,9 +398,12 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     gg.alpha = 1.f; gg.beta = (float)lambda; gg.Z = E; gg.ldz = p; gg.out = G; gg.ldo = p; gg.split_k = 1;
     ADMMQ_TRY(admmq_gemm_tn(ctx, gg));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, scal, 0, 32));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, hcol, 0, (size_t)2 * K * n * 4));     // finite before any slot is filled
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, pend_d, 0, (size_t)2 * K * p * 4));
 
     int moves_total = 0;
     float *part[2] = {partial, partial_b};
+    uint8_t *mv[2] = {mv_a, mv_b};
     for (int r = 0; r < plan.rounds; ++r) {
         // step s evaluates batch s (s < M) and plans batch s-1 (s > 0) in one launch; G is flushed after the
         // step that fills the last pending slot, and at the end of the round
@@ -402,8 +412,9 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
             const int32_t *prev = s > 0 ? pairs + ((size_t)r * plan.batches + s - 1) * plan.pairs * 2 : nullptr;
             const int slot_prev = s > 0 ? (s - 1) % K : 0;
             ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, prev,
-                                      s > 0 ? plan.pairs : 0, part[(s + 1) & 1], slot_prev, cur, plan.pairs,
-                                      s > 0 ? slot_prev : 0, pend_idx, pend_d, part[s & 1], choice, dev_moves, scal));
+                                      s > 0 ? plan.pairs : 0, part[(s + 1) & 1], mv[(s + 1) & 1], slot_prev, cur,
+                                      plan.pairs, s > 0 ? slot_prev : 0, pend_idx, pend_d, hcol, part[s & 1],
+                                      mv[s & 1], choice, dev_moves, scal));
             if (s > 0 && (slot_prev == K - 1 || s == plan.batches))
                 ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, slot_prev + 1));
         }
@@ -718,8 +729,9 @@ extern "C" admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double
     ADMMQ_TRY(admmq_arena_reserve(ctx, admmq_align_up((size_t)npairs * chunks * 4) + 4096));
     float *partial = nullptr;
     ADMMQ_TRY(take(ctx, partial, (size_t)npairs * chunks));
-    ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, (uint8_t *)codes, n, p, bits, g, scales, nullptr, 0, nullptr, 0,
-                              pairs, npairs, 0, nullptr, nullptr, partial, nullptr, nullptr, nullptr));
+    ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, (uint8_t *)codes, n, p, bits, g, scales, nullptr, 0, nullptr,
+                              nullptr, 0, pairs, npairs, 0, nullptr, nullptr, nullptr, partial, nullptr, nullptr,
+                              nullptr, nullptr));
     ADMMQ_TRY(admmq_k_ls_totals(ctx, partial, chunks, npairs, totals));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;

@@ -5,8 +5,8 @@
 //              combination of (+-delta_i1, +-delta_i2) by eq. 11 if it lowers the loss; the chunk's
 //              summed gain goes to partial[pair][chunk]
 //   plan     : every block sums the chunks in a fixed order and picks the largest total (lowest slot
-//              on ties) - the same winner in every block - then works out, for its own column, the new
-//              codes and the applied steps of the winner: slot (batch mod K) of a pending list
+//              on ties) - the same winner in every block - and takes, for its own column, the winner's
+//              move from the byte its evaluation left: slot (batch mod K) of a pending list
 //   (the plan of batch m and the evaluation of batch m+1 share ONE launch, ls_step_kernel)
 //   flush    : every K batches G is streamed ONCE for all pending pairs:
 //              G[i][j] -= sum_k H'[i][a_k] d1_k[j] + H'[i][b_k] d2_k[j]          (rank-2K correction)
@@ -61,30 +61,6 @@ __device__ inline float wave_sum_f(float v) {
 
 constexpr int LS_K = 16;          // pending pairs between two passes over G
 
-// coefficients of the pending corrections for gradient rows i1 and i2:
-//   coef[k][0..3] = H'[i1][a_k], H'[i1][b_k], H'[i2][a_k], H'[i2][b_k]   (0 for an empty slot)
-// and which = bit w set when that slot's row (a_k for even w, b_k for odd w) IS row i1 (w < 2) or i2 (w >= 2):
-// the codes of such a row have moved by the sign of the slot's step
-__device__ inline void load_pending_coef(const float *__restrict__ H, float lambda, long n, long i1, long i2,
-                                         const int32_t *__restrict__ pend_idx, int npend, float (*coef)[4],
-                                         int *which) {
-    for (int e = threadIdx.x; e < npend; e += blockDim.x) {
-        const long a = pend_idx[2 * e], b = pend_idx[2 * e + 1];
-        which[e] = a < 0 ? 0 : ((a == i1) | ((b == i1) << 1) | ((a == i2) << 2) | ((b == i2) << 3));
-    }
-    for (int e = threadIdx.x; e < npend * 4; e += blockDim.x) {
-        const int k = e >> 2, w = e & 3;
-        const long row = (w & 2) ? i2 : i1;
-        const long col = pend_idx[2 * k + (w & 1)];
-        float h = 0.f;
-        if (pend_idx[2 * k] >= 0) {
-            h = H[row * n + col];
-            if (row == col) h += lambda;
-        }
-        coef[k][w] = h;
-    }
-}
-
 __device__ inline int step_sign(float d) { return (d > 0.f) - (d < 0.f); }
 
 // the pending steps of column j, all slots, in registers (zero beyond npend): the same values serve the
@@ -129,43 +105,54 @@ __device__ inline void better(float &t, int &i, float ot, int oi) {
     }
 }
 
+constexpr int LS_FAST_PAIRS = 64;      // candidate pairs per batch up to which the winner's data is prefetched
+
 // One step of the search, grid (chunks, npairs), block 256, one column per thread:
 //   plan     (when a previous batch exists): every block adds that batch's chunk partials in a fixed order and
-//            finds its winner (largest total, lowest slot on ties) - the same winner in every block - and works
-//            out the winner's move at its own column; the blocks of pair 0 store the applied steps into
-//            pending slot `slot_prev`, one thread records the pair;
+//            finds its winner (largest total, lowest slot on ties) - the same winner in every block.  The winner's
+//            move at each column is the one its evaluation chose in the previous launch (kept as one byte per
+//            pair and column); the blocks of pair 0 store the applied steps into pending slot `slot_prev`, the
+//            blocks of pair 1 copy the two H' columns of the winner's rows into the slot's coefficient cache,
+//            one thread records the pair;
 //   evaluate (when a current batch exists): the block's own candidate pair at its column, against the codes and
-//            the gradient AFTER the winner's move: the move just planned is taken from registers, never from
-//            memory that another block may be writing.
+//            the gradient AFTER the winner's move, which is taken from registers, never from memory that another
+//            block may be writing; the chosen sign combination goes to the byte array of this batch.
 // Nothing a block reads is written in the same launch: codes and G change only in the flush, slot `slot_prev`
-// is written here and first read by the next launch.
-// The chunk partials of the two batches live in two buffers that trade places every step.
+// of the pending arrays is written here and first read by the next launch, the partials and the move bytes of
+// the two batches live in buffers that trade places every step.
 // npend = pending slots already in memory (== slot_prev whenever there is a previous batch).
-// The loads that do not depend on the winner (the own pair's rows, the pending steps) are issued before the
-// selection, so that the launch costs two memory round trips in a row, not five.
+// Latency is what this launch costs, so everything that does not depend on the winner is requested up front,
+// including (for up to LS_FAST_PAIRS candidates) every candidate's move byte at this column and the four
+// H' entries that couple the own pair with every candidate: after the selection no load from DRAM remains.
+// hcol[(2k + w) n + r] = H'[r][row w of slot k]: coefficients of the pending corrections without a dependent
+// look-up of the slot's rows; empty slots keep finite stale entries (their steps are zero).
 __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ H, float lambda,
                                                       const float *__restrict__ G, const uint8_t *__restrict__ codes,
                                                       long n, long p, int levels, long g,
                                                       const float *__restrict__ scales,
                                                       const int32_t *__restrict__ pairs_prev, int npairs_prev,
-                                                      const float *__restrict__ partial_prev, int slot_prev,
+                                                      const float *__restrict__ partial_prev,
+                                                      const uint8_t *__restrict__ mv_prev, int slot_prev,
                                                       const int32_t *__restrict__ pairs_cur, int npend,
-                                                      int32_t *pend_idx, float *pend_d,
-                                                      float *__restrict__ partial_cur, int chunks,
-                                                      int32_t *__restrict__ choice, int *__restrict__ moves,
-                                                      double *__restrict__ drop) {
-    __shared__ float coef_o[LS_K][4], coef_w[LS_K][4];
-    __shared__ int which_o[LS_K], which_w[LS_K];
+                                                      int32_t *pend_idx, float *pend_d, float *hcol,
+                                                      float *__restrict__ partial_cur, uint8_t *__restrict__ mv_cur,
+                                                      int chunks, int32_t *__restrict__ choice,
+                                                      int *__restrict__ moves, double *__restrict__ drop) {
+    __shared__ float coef_o[LS_K][4];
+    __shared__ int which_o[LS_K];
+    __shared__ int cand[2 * LS_FAST_PAIRS];
+    __shared__ float exs[LS_FAST_PAIRS][4];
+    __shared__ __align__(16) uint8_t smv[LS_FAST_PAIRS][LS_CHUNK];
     __shared__ float wtot_sh[4];
     __shared__ int widx_sh[4];
-    __shared__ float extra[4];
     __shared__ float sh[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long j = (long)blockIdx.x * LS_CHUNK + tid;
     const bool first_block = blockIdx.x == 0 && blockIdx.y == 0;
     const bool in = j < p;
+    const bool fast = npairs_prev <= LS_FAST_PAIRS;
 
-    // ---- loads that need no winner ---------------------------------------------------------------------
+    // ---- loads that need no winner: all of them are requested before the first one is used -------------
     long i1 = -1, i2 = -1;
     bool own = false;
     if (pairs_cur) {
@@ -173,38 +160,98 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
         i2 = pairs_cur[2 * blockIdx.y + 1];
         own = !(i1 < 0 || i2 < 0 || i1 >= n || i2 >= n || i1 == i2);      // else: not a row pair
     }
+    const bool prev_fast = npairs_prev > 0 && fast;
+    const bool mv_vec = fast && (p & 15) == 0;
+    // (1) the oldest request is the one a second request depends on: candidate row -> coupling entry of H'
+    long ex_col = -1;
+    const bool ex_on = prev_fast && own && tid < 4 * npairs_prev;
+    if (ex_on) ex_col = pairs_prev[2 * (tid >> 2) + (tid & 1)];
+    // (2) everything else
+    int cand_r = 0;
+    if (prev_fast && tid < 2 * npairs_prev) cand_r = pairs_prev[tid];
+    long pa = -1, pb = -1;
+    float coef_r = 0.f;
+    if (own) {
+        if (tid < npend) {
+            pa = pend_idx[2 * tid];
+            pb = pend_idx[2 * tid + 1];
+        }
+        if (tid < npend * 4) coef_r = hcol[(long)(2 * (tid >> 2) + (tid & 1)) * n + ((tid & 2) ? i2 : i1)];
+    }
     PendCol pc;
     if (in) load_pending_col(pend_d, p, j, npend, pc);
     float og1 = 0.f, og2 = 0.f, oh11 = 0.f, oh22 = 0.f, oh12 = 0.f, osc1 = 0.f, osc2 = 0.f;
     int ok1 = 0, ok2 = 0;
-    if (own) {
-        load_pending_coef(H, lambda, n, i1, i2, pend_idx, npend, coef_o, which_o);
-        if (in) {
-            og1 = G[i1 * p + j];
-            og2 = G[i2 * p + j];
-            ok1 = codes[i1 * p + j];
-            ok2 = codes[i2 * p + j];
-            osc1 = scales[(i1 / g) * p + j];
-            osc2 = scales[(i2 / g) * p + j];
-            oh11 = H[i1 * n + i1] + lambda;
-            oh22 = H[i2 * n + i2] + lambda;
-            oh12 = H[i1 * n + i2];
+    if (own && in) {
+        og1 = G[i1 * p + j];
+        og2 = G[i2 * p + j];
+        ok1 = codes[i1 * p + j];
+        ok2 = codes[i2 * p + j];
+        osc1 = scales[(i1 / g) * p + j];
+        osc2 = scales[(i2 / g) * p + j];
+        oh11 = H[i1 * n + i1] + lambda;
+        oh22 = H[i2 * n + i2] + lambda;
+        oh12 = H[i1 * n + i2];
+    }
+    // with one group per column the winner's grid steps do not depend on its rows
+    const bool one_group = g >= n;
+    float sc_col = 0.f;
+    if (one_group && in && npairs_prev > 0) sc_col = scales[j];
+    // every candidate's move bytes for the block's 256 columns go through LDS: 16-byte loads, 16 threads to a
+    // candidate's row segment (four loads per thread when there are 64 candidates)
+    uint4 mvr[LS_FAST_PAIRS / 16];
+    if (prev_fast && mv_vec) {
+        const long c0 = (long)blockIdx.x * LS_CHUNK + (tid & 15) * 16;
+#pragma unroll
+        for (int r = 0; r < LS_FAST_PAIRS / 16; ++r) {
+            const int q = (tid >> 4) + 16 * r;
+            mvr[r] = (q < npairs_prev && c0 < p) ? *(const uint4 *)(mv_prev + (long)q * p + c0) : uint4{0u, 0u, 0u, 0u};
         }
+    }
+    // the candidates' chunk partials: sixteen are requested at a time (a loop of single loads would pay the cache
+    // latency once per chunk) and added in chunk order; they come last so that nothing above waits for them
+    float best = 0.f;
+    int bidx = -1;
+    if (npairs_prev > 0) {
+        for (int pr = tid; pr < npairs_prev; pr += 256) {
+            const float *src = partial_prev + (long)pr * chunks;
+            float psum = 0.f;
+            int c = 0;
+            for (; c + 16 <= chunks; c += 16) {
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = src[c + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) psum += v[u];
+            }
+            for (; c < chunks; ++c) psum += src[c];
+            if (psum > best) {     // strictly larger: within a thread slots come in increasing order
+                best = psum;
+                bidx = pr;
+            }
+        }
+    }
+    // (3) the dependent request, then the hand-over to LDS
+    if (ex_on) {
+        const long row = (tid & 2) ? i2 : i1;
+        float h = 0.f;
+        if (ex_col >= 0 && ex_col < n) h = H[row * n + ex_col] + (row == ex_col ? lambda : 0.f);
+        exs[tid >> 2][tid & 3] = h;
+    }
+    if (prev_fast && tid < 2 * npairs_prev) cand[tid] = cand_r;
+    if (own) {
+        if (tid < npend) which_o[tid] = pa < 0 ? 0 : ((pa == i1) | ((pb == i1) << 1) | ((pa == i2) << 2) | ((pb == i2) << 3));
+        if (tid < npend * 4) coef_o[tid >> 2][tid & 3] = coef_r;
+    }
+    if (prev_fast && mv_vec) {
+#pragma unroll
+        for (int r = 0; r < LS_FAST_PAIRS / 16; ++r)
+            *(uint4 *)(&smv[(tid >> 4) + 16 * r][(tid & 15) * 16]) = mvr[r];
     }
     // ---- the previous batch's winner ----------------------------------------------------------------------
     int win = -1;
     float wtot = 0.f;
     if (npairs_prev > 0) {
-        float best = 0.f;
-        int bidx = -1;
-        for (int pr = tid; pr < npairs_prev; pr += 256) {
-            float t = 0.f;
-            for (int c = 0; c < chunks; ++c) t += partial_prev[(long)pr * chunks + c];
-            if (t > best) {        // strictly larger: within a thread slots come in increasing order
-                best = t;
-                bidx = pr;
-            }
-        }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) better(best, bidx, __shfl_xor(best, o, 64), __shfl_xor(bidx, o, 64));
         if (lane == 0) {
@@ -212,7 +259,7 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
             widx_sh[wv] = bidx;
         }
     }
-    __syncthreads();                         // wave results, coef_o, which_o
+    __syncthreads();                         // wave results, coef_o, which_o, cand, exs, smv
     if (npairs_prev > 0) {
         wtot = wtot_sh[0];
         win = widx_sh[0];
@@ -223,44 +270,48 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
     long wi1 = -1, wi2 = -1;
     float nd1 = 0.f, nd2 = 0.f;
     int ws1 = 0, ws2 = 0;
+    float ex[4] = {0.f, 0.f, 0.f, 0.f};
     if (win >= 0) {
-        wi1 = pairs_prev[2 * win];
-        wi2 = pairs_prev[2 * win + 1];
-        load_pending_coef(H, lambda, n, wi1, wi2, pend_idx, npend, coef_w, which_w);
-        if (own && tid >= 64 && tid < 68) {
-            // the planned move changes the own pair's gradient rows by H'[i][wi1] nd1 + H'[i][wi2] nd2
-            const int e = tid - 64;
-            const long row = (e & 2) ? i2 : i1, col = (e & 1) ? wi2 : wi1;
-            extra[e] = H[row * n + col] + (row == col ? lambda : 0.f);
-        }
-        float g1 = 0.f, g2 = 0.f, h11 = 0.f, h22 = 0.f, h12 = 0.f, sc1 = 0.f, sc2 = 0.f;
-        int k1 = 0, k2 = 0;
-        if (in) {
-            g1 = G[wi1 * p + j];
-            g2 = G[wi2 * p + j];
-            k1 = codes[wi1 * p + j];
-            k2 = codes[wi2 * p + j];
-            sc1 = scales[(wi1 / g) * p + j];
-            sc2 = scales[(wi2 / g) * p + j];
-            h11 = H[wi1 * n + wi1] + lambda;
-            h22 = H[wi2 * n + wi2] + lambda;
-            h12 = H[wi1 * n + wi2];
-        }
-        __syncthreads();                     // coef_w, which_w, extra (win is the same in every thread)
-        if (in) {
-            apply_pending(pc, npend, coef_w, which_w, g1, g2, k1, k2);
-            const PairEval e = eval_column(g1, g2, k1, k2, sc1, sc2, h11, h22, h12, levels);
-            if (e.combo >= 0) {
-                ws1 = (e.combo & 2) ? -1 : 1;
-                ws2 = (e.combo & 1) ? -1 : 1;
-                nd1 = (float)ws1 * sc1;
-                nd2 = (float)ws2 * sc2;
+        uint32_t mb = 0u;
+        if (fast) {
+            wi1 = cand[2 * win];
+            wi2 = cand[2 * win + 1];
+            if (mv_vec) mb = smv[win][tid];
+            else if (in) mb = mv_prev[(long)win * p + j];
+            if (own) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) ex[w] = exs[win][w];
             }
+        } else {
+            wi1 = pairs_prev[2 * win];
+            wi2 = pairs_prev[2 * win + 1];
+            if (in) mb = mv_prev[(long)win * p + j];
+            if (own) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const long row = (w & 2) ? i2 : i1, col = (w & 1) ? wi2 : wi1;
+                    ex[w] = H[row * n + col] + (row == col ? lambda : 0.f);
+                }
+            }
+        }
+        if (in && mb != 0u) {
+            const int combo = (int)mb - 1;
+            ws1 = (combo & 2) ? -1 : 1;
+            ws2 = (combo & 1) ? -1 : 1;
+            nd1 = (float)ws1 * (one_group ? sc_col : scales[(wi1 / g) * p + j]);
+            nd2 = (float)ws2 * (one_group ? sc_col : scales[(wi2 / g) * p + j]);
         }
     }
     if (npairs_prev > 0 && blockIdx.y == 0 && in) {
         pend_d[(long)(2 * slot_prev) * p + j] = nd1;        // zero steps for an empty slot
         pend_d[(long)(2 * slot_prev + 1) * p + j] = nd2;
+    }
+    if (win >= 0 && blockIdx.y == (gridDim.y > 1 ? 1u : 0u)) {
+        // coefficient cache of the new slot: the two H' columns (rows of the symmetric H) of the winner's rows
+        for (long r = (long)blockIdx.x * LS_CHUNK + tid; r < n; r += (long)gridDim.x * LS_CHUNK) {
+            hcol[(long)(2 * slot_prev) * n + r] = H[wi1 * n + r] + (r == wi1 ? lambda : 0.f);
+            hcol[(long)(2 * slot_prev + 1) * n + r] = H[wi2 * n + r] + (r == wi2 ? lambda : 0.f);
+        }
     }
     if (npairs_prev > 0 && first_block && tid == 0) {
         choice[0] = win;
@@ -276,16 +327,21 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
     if (!pairs_cur) return;
     // ---- this block's candidate pair ----------------------------------------------------------------------
     float gain = 0.f;
+    uint32_t mine = 0u;
     if (own && in) {
         apply_pending(pc, npend, coef_o, which_o, og1, og2, ok1, ok2);
         if (win >= 0) {
-            og1 -= extra[0] * nd1 + extra[1] * nd2;
-            og2 -= extra[2] * nd1 + extra[3] * nd2;
+            // the move planned above changes the own pair's gradient rows by H'[i][wi1] nd1 + H'[i][wi2] nd2
+            og1 -= ex[0] * nd1 + ex[1] * nd2;
+            og2 -= ex[2] * nd1 + ex[3] * nd2;
             ok1 += i1 == wi1 ? ws1 : (i1 == wi2 ? ws2 : 0);
             ok2 += i2 == wi1 ? ws1 : (i2 == wi2 ? ws2 : 0);
         }
-        gain = eval_column(og1, og2, ok1, ok2, osc1, osc2, oh11, oh22, oh12, levels).gain;
+        const PairEval e = eval_column(og1, og2, ok1, ok2, osc1, osc2, oh11, oh22, oh12, levels);
+        gain = e.gain;
+        mine = e.combo >= 0 ? (uint32_t)(e.combo + 1) : 0u;
     }
+    if (in && mv_cur) mv_cur[(long)blockIdx.y * p + j] = (uint8_t)mine;
     gain = wave_sum_f(gain);
     if (lane == 0) sh[wv] = gain;
     __syncthreads();
@@ -388,17 +444,20 @@ int admmq_ls_defer() { return LS_K; }
 // One step: plan the previous batch (if npairs_prev > 0) into pending slot slot_prev, and evaluate the current
 // batch (if pairs_cur) against the state after that move.  npend = pending slots already in memory, i.e. slots
 // 0 .. npend-1 hold earlier moves of the current group (npend == slot_prev whenever there is a previous batch).
-admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes, int64_t n,
-                             int64_t p, int bits, int64_t g, const float *scales, const int32_t *pairs_prev,
-                             int npairs_prev, const float *partial_prev, int slot_prev, const int32_t *pairs_cur,
-                             int npairs_cur, int npend, int32_t *pend_idx, float *pend_d, float *partial_cur,
-                             int32_t *choice, int *dev_moves, double *dev_drop) {
+// mv_prev / mv_cur: [npairs][p] bytes, the sign combination each evaluation chose; hcol: [2 K][n] floats.
+admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const float *G, const uint8_t *codes,
+                             int64_t n, int64_t p, int bits, int64_t g, const float *scales,
+                             const int32_t *pairs_prev, int npairs_prev, const float *partial_prev,
+                             const uint8_t *mv_prev, int slot_prev, const int32_t *pairs_cur, int npairs_cur,
+                             int npend, int32_t *pend_idx, float *pend_d, float *hcol, float *partial_cur,
+                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop) {
     const int chunks = admmq_ls_chunks(p);
     const int levels = (1 << bits) - 1;
     const unsigned gy = (unsigned)(pairs_cur ? npairs_cur : 1);
     hipLaunchKernelGGL(ls_step_kernel, dim3((unsigned)chunks, gy), dim3(256), 0, ctx->stream, H, lambda, G, codes,
-                       (long)n, (long)p, levels, (long)g, scales, pairs_prev, npairs_prev, partial_prev, slot_prev,
-                       pairs_cur, npend, pend_idx, pend_d, partial_cur, chunks, choice, dev_moves, dev_drop);
+                       (long)n, (long)p, levels, (long)g, scales, pairs_prev, npairs_prev, partial_prev, mv_prev,
+                       slot_prev, pairs_cur, npend, pend_idx, pend_d, hcol, partial_cur, mv_cur, chunks, choice,
+                       dev_moves, dev_drop);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
