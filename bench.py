@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
 # calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
 PMC_TRAFFIC_BYTES = {
-    "cfg2": {"gemm": (227149.0 + 65536.0) * 1024, "project": (65780.1 + 131088.0) * 1024},
+    "cfg2": {"gemm": (227277.1 + 65536.0) * 1024, "project": (65775.1 + 131104.0) * 1024},
 }
 
 
@@ -41,6 +41,8 @@ def make_inputs(cfg, tokens, torch):
         else:
             X[row:row + xc.shape[0]].copy_(t)
         row += xc.shape[0]
+        if (row // xc.shape[0]) % 32 == 0:
+            print(f"[bench] inputs: {row} of {tokens} rows generated", file=sys.stderr, flush=True)
     W0 = torch.from_numpy(si.layer_weights(cfg)).cuda()
     return X, W0
 
@@ -129,8 +131,9 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1), out[3]
 
-    for _ in range(args.warmup):
+    for w in range(args.warmup):
         step(False)
+        print(f"[bench] warm-up step {w + 1} of {args.warmup} done", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     hs, stats = [], []
@@ -138,6 +141,7 @@ def main():
         h_ms, st = step(True)
         hs.append(h_ms)
         stats.append(st)
+        print(f"[bench] timed step {len(hs)} of {args.steps} done", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
