@@ -54,7 +54,8 @@ admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stream);
 void admmq_destroy(admmq_ctx *ctx);
 const char *admmq_status_string(admmq_status s);
 
-/* Bytes of scratch admmq_quantize_layer needs for an n x p layer (pure host function). */
+/* Bytes of scratch admmq_quantize_layer and admmq_quantize_layer_format need for an n x p layer, for any
+ * group size of 3 rows or more, up to 5 local-search rounds of (n+1)/2 batches of 64 pairs (pure host function). */
 size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T);
 /* Optional: use caller memory (device, 256-byte aligned) as the scratch arena from now on. */
 admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);

@@ -489,7 +489,9 @@ extern "C" size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T) {
     if (n < 1 || p < 1 || T < 1) return 0;
     const int64_t batches = (n + 1) / 2;
     size_t a = factor_transient_bytes(n);
-    size_t b = admm_transient_bytes(n, p, T);
+    // + the per-group arrays of the loop (reciprocal scales, a refreshed grid, both grids of a dual-grid format):
+    // at most three [n/g][p] arrays, bounded by one n x p array for any group size of 3 rows or more
+    size_t b = admm_transient_bytes(n, p, T) + admmq_align_up((size_t)n * p * 4) + (1u << 20);
     size_t c = ls_transient_bytes(n, p, (int64_t)5 * batches * 64, 64) + 2 * admmq_align_up((size_t)n * p * 4);
     size_t m = a > b ? a : b;
     m = m > c ? m : c;

@@ -262,6 +262,17 @@ def test_device_side_input_checks_leave_outputs_untouched(ctx):
     a = c2.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=1))[0]
     b = ctx.quantize_layer(to_dev(H), to_dev(W0), 4, 0, admmq.Schedule(T=5, ls_rounds=1))[0]
     assert torch.equal(a, b)
+    # the same caller workspace serves grouped grids and the other formats
+    import synth_inputs as si
+    a = c2.quantize_layer(to_dev(H), to_dev(W0), 3, 8, admmq.Schedule(T=5, ls_rounds=1, refresh_iter=2))[0]
+    b = ctx.quantize_layer(to_dev(H), to_dev(W0), 3, 8, admmq.Schedule(T=5, ls_rounds=1, refresh_iter=2))[0]
+    assert torch.equal(a, b)
+    flags = to_dev(si.outlier_mask(W0, 0.1).astype(np.uint8))
+    a = c2.quantize_layer_format(to_dev(H), to_dev(W0), admmq.FORMAT_DUAL_GRID, 3, group_size=4, flags=flags,
+                                 sched=admmq.Schedule(T=5, ls_rounds=0))[0]
+    b = ctx.quantize_layer_format(to_dev(H), to_dev(W0), admmq.FORMAT_DUAL_GRID, 3, group_size=4, flags=flags,
+                                  sched=admmq.Schedule(T=5, ls_rounds=0))[0]
+    assert torch.equal(a, b)
     c2.close()
 
 
