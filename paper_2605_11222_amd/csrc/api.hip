@@ -137,7 +137,7 @@ size_t factor_transient_bytes(int64_t n) {
 }
 size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
     const size_t np = (size_t)n * (size_t)p;
-    return 6 * admmq_align_up(np * 4) + admmq_align_up(np * 8) + 2 * admmq_align_up((size_t)T * n * 8) +
+    return 6 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) + 2 * admmq_align_up((size_t)T * n * 8) +
            4 * admmq_align_up((size_t)T * 8) + 65536;
 }
 size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
@@ -256,6 +256,7 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
 }
 
 // W = B + Q (T + rho I)^{-1} T (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho)
+// F: n p + p doubles of scratch: the solve's fp32 result [n][p] in front, its per-tile checkpoints behind
 admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const double *dinv,
                            const double *lfac, float *Y, double *F, float *W) {
     const admmq_factor &f = ctx->fac;
@@ -265,11 +266,13 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
     int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
     ADMMQ_TRY(admmq_gemm_tn(ctx, g1));
     admmq_prof_end(ctx, sp);
+    float *S = (float *)F;
+    double *carries = F + ((size_t)n * p + 1) / 2;
     sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
-    ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, F, Y));
+    ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S));
     admmq_prof_end(ctx, sp);
     gemm_tn_args g2 = {};
-    g2.A = f.Qt; g2.lda = n; g2.B = Y; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
+    g2.A = f.Qt; g2.lda = n; g2.B = S; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
     g2.alpha = 1.f; g2.beta = 1.f; g2.Z = B; g2.ldz = p; g2.out = W; g2.ldo = p; g2.split_k = 1;
     sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
     ADMMQ_TRY(admmq_gemm_tn(ctx, g2));
@@ -605,14 +608,14 @@ extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const fl
     ADMMQ_HIP(hipSetDevice(ctx->device));
     admmq_arena_reset_transient(ctx);
     const size_t np = (size_t)n * p;
-    ADMMQ_TRY(admmq_arena_reserve(ctx, 3 * admmq_align_up(np * 4) + admmq_align_up(np * 8) +
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 3 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) +
                                            3 * admmq_align_up((size_t)n * 8) + 8192));
     float *B = nullptr, *C0 = nullptr, *Y = nullptr;
     double *F = nullptr, *dinv = nullptr, *lfac = nullptr, *rho_dev = nullptr;
     ADMMQ_TRY(take(ctx, B, np));
     ADMMQ_TRY(take(ctx, C0, np));
     ADMMQ_TRY(take(ctx, Y, np));
-    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, F, np + (size_t)p));
     ADMMQ_TRY(take(ctx, dinv, (size_t)n));
     ADMMQ_TRY(take(ctx, lfac, (size_t)n));
     ADMMQ_TRY(take(ctx, rho_dev, 1));
@@ -849,7 +852,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(take(ctx, W, np));
     ADMMQ_TRY(take(ctx, C0, np));
     ADMMQ_TRY(take(ctx, Y, np));
-    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, F, np + (size_t)p));
     ADMMQ_TRY(take(ctx, inv_scales, ng));
     float *new_sc = nullptr, *new_zr = nullptr;
     double *rpart = nullptr;
@@ -1133,7 +1136,7 @@ extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float 
     ADMMQ_TRY(take(ctx, W, np));
     ADMMQ_TRY(take(ctx, C0, np));
     ADMMQ_TRY(take(ctx, Y, np));
-    ADMMQ_TRY(take(ctx, F, np));
+    ADMMQ_TRY(take(ctx, F, np + (size_t)p));
     ADMMQ_TRY(take(ctx, inv_scales, ng2));
     ADMMQ_TRY(take(ctx, rhos, (size_t)T));
     ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));

@@ -143,5 +143,5 @@ admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const doub
                                     const double *rhos_dev, int count, double *dinv, double *lfac);
 // S = (T + rho I)^{-1} T Y, column by column (Y, S fp32 [n][p]; may alias), F fp64 scratch [n][p]
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
-                                   const double *lfac, int64_t n, int64_t p, const float *Y, double *F,
+                                   const double *lfac, int64_t n, int64_t p, const float *Y, double *carries,
                                    float *S);

@@ -77,14 +77,21 @@ __global__ void tridiag_factor_kernel(const double *__restrict__ ta, const doubl
 // ends are then chained (NS short steps, done redundantly by every thread, so one barrier per tile
 // suffices) and each thread corrects its own rows.  The sequential depth per tile is SL + NS instead
 // of TR.  Row coefficients, which all columns share, are staged in LDS once per tile.
-template <int C>
-__global__ __launch_bounds__(256) void tridiag_apply_split_kernel(const double *__restrict__ ta,
+// The forward pass keeps only the value of f that enters each tile (`carries`, [tiles][p] doubles); the
+// backward pass, tile by tile from the bottom, forms the tile's f again from Y and consumes it in registers.
+// HBM traffic: Y twice, S once = 12 B per element (with f stored in fp64 in between it was 24).
+// S must not be Y: the backward pass reads Y rows next to tiles it has already written.
+// (Measured at n = p = 4096: 0.120 ms; it is bound by the latency of its dependent steps with one block per
+// compute unit, not by bytes: 1024-thread blocks of 8-row segments take 0.152 ms.)
+template <int C, int NT, int SL>
+__global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *__restrict__ ta,
                                                                   const double *__restrict__ tb,
                                                                   const double *__restrict__ dinv,
                                                                   const double *__restrict__ lfac, long n, long p,
-                                                                  const float *Y, double *__restrict__ F, float *S) {
-    constexpr int NS = 256 / C;               // segments per tile
-    constexpr int SL = 32;                    // rows per segment
+                                                                  const float *__restrict__ Y,
+                                                                  double *__restrict__ carries,
+                                                                  float *__restrict__ S) {
+    constexpr int NS = NT / C;                // segments per tile (SL rows each)
     constexpr int TR = NS * SL;               // rows per tile
     __shared__ double s_a[TR], s_b[TR + 1], s_l[TR + 1], s_di[TR];
     __shared__ double endf[2][NS][C], endP[2][NS][C];
@@ -94,7 +101,6 @@ __global__ __launch_bounds__(256) void tridiag_apply_split_kernel(const double *
     const bool jok = j < p;
     const long ntile = (n + TR - 1) / TR;
 
-    // ---------------- forward ----------------
     float ycur[SL + 2], ynext[SL + 2];
     auto load_y = [&](long t, float *dst) {
         const long a = t * TR + (long)sg * SL;
@@ -104,116 +110,116 @@ __global__ __launch_bounds__(256) void tridiag_apply_split_kernel(const double *
             dst[u] = (jok && i >= 0 && i < n) ? Y[i * p + j] : 0.f;
         }
     };
-    double carry = 0.0;                       // f of the row just above the current tile
-    load_y(0, ycur);
-    for (long t = 0; t < ntile; ++t) {
-        const long i0 = t * TR;
-        const int par = (int)(t & 1);
-        // stage the tile's coefficients: s_a[r] = a_i, s_b[r] = b_{i-1}, s_l[r] = l_{i-1}, i = i0 + r
-        for (int r = tid; r <= TR; r += 256) {
+    // s_a[r] = a_i, s_b[r] = b_{i-1}, s_l[r] = l_{i-1}, s_di[r] = 1/delta_i, i = i0 + r (s_l[r + 1] = l_i)
+    auto stage = [&](long i0) {
+        for (int r = tid; r <= TR; r += NT) {
             const long i = i0 + r;
-            if (r < TR) s_a[r] = i < n ? ta[i] : 0.0;
+            if (r < TR) {
+                s_a[r] = i < n ? ta[i] : 0.0;
+                s_di[r] = i < n ? dinv[i] : 0.0;
+            }
             s_b[r] = (i >= 1 && i < n) ? tb[i - 1] : 0.0;
             s_l[r] = (i >= 1 && i < n) ? lfac[i - 1] : 0.0;
         }
+    };
+    // the segment's forward recurrence from zero: fl[u] = local f, Pl[u] = product of the -l up to row u
+    auto forward_local = [&](const float *y, double *fl, double *Pl) {
+        double f = 0.0, P = 1.0;
+        const int r0 = sg * SL;
+#pragma unroll
+        for (int u = 0; u < SL; ++u) {
+            const int r = r0 + u;
+            const double z = s_b[r] * (double)y[u] + s_a[r] * (double)y[u + 1] + s_b[r + 1] * (double)y[u + 2];
+            const double ml = -s_l[r];
+            f = fma(ml, f, z);
+            P = ml * P;
+            fl[u] = f;
+            Pl[u] = P;
+        }
+    };
+
+    // ---------------- forward: only the value of f entering each tile is kept ----------------
+    double carry = 0.0;                       // f of the row just above the current tile
+    load_y(0, ycur);
+    for (long t = 0; t < ntile; ++t) {
+        const int par = (int)(t & 1);
+        stage(t * TR);
         __syncthreads();
         if (t + 1 < ntile) load_y(t + 1, ynext);
-        double fl[SL], Pl[SL];
+        if (jok && sg == 0) carries[t * p + j] = carry;
         {
-            double f = 0.0, P = 1.0;
-            const int r0 = sg * SL;
-#pragma unroll
-            for (int u = 0; u < SL; ++u) {
-                const int r = r0 + u;
-                const double z = s_b[r] * (double)ycur[u] + s_a[r] * (double)ycur[u + 1] +
-                                 s_b[r + 1] * (double)ycur[u + 2];
-                const double ml = -s_l[r];
-                f = fma(ml, f, z);
-                P = ml * P;
-                fl[u] = f;
-                Pl[u] = P;
-            }
-            endf[par][sg][c] = f;
-            endP[par][sg][c] = P;
+            double fl[SL], Pl[SL];
+            forward_local(ycur, fl, Pl);
+            endf[par][sg][c] = fl[SL - 1];
+            endP[par][sg][c] = Pl[SL - 1];
         }
         __syncthreads();
-        double cin = carry, run = carry;
+        double run = carry;
 #pragma unroll
-        for (int q = 0; q < NS; ++q) {
-            if (q == sg) cin = run;
-            run = fma(endP[par][q][c], run, endf[par][q][c]);
-        }
+        for (int q = 0; q < NS; ++q) run = fma(endP[par][q][c], run, endf[par][q][c]);
         carry = run;
-        {
-            const long a = i0 + (long)sg * SL;
-#pragma unroll
-            for (int u = 0; u < SL; ++u) {
-                const long i = a + u;
-                if (jok && i < n) F[i * p + j] = fma(Pl[u], cin, fl[u]);
-            }
-        }
 #pragma unroll
         for (int u = 0; u < SL + 2; ++u) ycur[u] = ynext[u];
     }
 
-    // ---------------- backward ----------------
+    // ---------------- backward: each tile's f is formed again from Y, then consumed in registers --------
     __syncthreads();
-    double gcur[SL], gnext[SL];
-    auto load_f = [&](long t, double *dst) {
-        const long a = t * TR + (long)sg * SL;
-#pragma unroll
-        for (int u = 0; u < SL; ++u) {
-            const long i = a + u;
-            dst[u] = (jok && i < n) ? F[i * p + j] : 0.0;
-        }
-    };
-    carry = 0.0;                              // s of the row just below the current tile
-    load_f(ntile - 1, gcur);
+    double below = 0.0;                       // s of the row just below the current tile
+    load_y(ntile - 1, ycur);
     for (long t = ntile - 1; t >= 0; --t) {
         const long i0 = t * TR;
-        const int par = (int)(t & 1);
-        // s_l[r] = l_i, s_di[r] = 1/delta_i, i = i0 + r
-        for (int r = tid; r < TR; r += 256) {
-            const long i = i0 + r;
-            s_l[r] = i < n ? lfac[i] : 0.0;
-            s_di[r] = i < n ? dinv[i] : 0.0;
-        }
+        stage(i0);
         __syncthreads();
-        if (t > 0) load_f(t - 1, gnext);
-        double sl[SL], Pl[SL];
+        if (t > 0) load_y(t - 1, ynext);
+        const double tile_in = jok ? carries[t * p + j] : 0.0;
+        double fl[SL], Pl[SL];
+        forward_local(ycur, fl, Pl);
+        endf[0][sg][c] = fl[SL - 1];
+        endP[0][sg][c] = Pl[SL - 1];
+        __syncthreads();
+        {
+            double cin = tile_in, run = tile_in;
+#pragma unroll
+            for (int q = 0; q < NS; ++q) {
+                if (q == sg) cin = run;
+                run = fma(endP[0][q][c], run, endf[0][q][c]);
+            }
+#pragma unroll
+            for (int u = 0; u < SL; ++u) fl[u] = fma(Pl[u], cin, fl[u]);      // the f of rows a .. a + SL - 1
+        }
         {
             double sv = 0.0, P = 1.0;
             const int r0 = sg * SL;
 #pragma unroll
             for (int u = SL - 1; u >= 0; --u) {
                 const int r = r0 + u;
-                const double ml = -s_l[r];
-                sv = fma(ml, sv, gcur[u] * s_di[r]);
+                const double ml = -s_l[r + 1];                                 // l_i
+                sv = fma(ml, sv, fl[u] * s_di[r]);
                 P = ml * P;
-                sl[u] = sv;
+                fl[u] = sv;
                 Pl[u] = P;
             }
-            endf[par][sg][c] = sv;
-            endP[par][sg][c] = P;
+            endf[1][sg][c] = sv;
+            endP[1][sg][c] = P;
         }
         __syncthreads();
-        double cin = carry, run = carry;
+        double cin = below, run = below;
 #pragma unroll
         for (int q = NS - 1; q >= 0; --q) {
             if (q == sg) cin = run;
-            run = fma(endP[par][q][c], run, endf[par][q][c]);
+            run = fma(endP[1][q][c], run, endf[1][q][c]);
         }
-        carry = run;
+        below = run;
         {
             const long a = i0 + (long)sg * SL;
 #pragma unroll
             for (int u = 0; u < SL; ++u) {
                 const long i = a + u;
-                if (jok && i < n) S[i * p + j] = (float)fma(Pl[u], cin, sl[u]);
+                if (jok && i < n) S[i * p + j] = (float)fma(Pl[u], cin, fl[u]);
             }
         }
 #pragma unroll
-        for (int u = 0; u < SL; ++u) gcur[u] = gnext[u];
+        for (int u = 0; u < SL + 2; ++u) ycur[u] = ynext[u];
     }
 }
 
@@ -251,28 +257,33 @@ admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const doub
 }
 
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
-                                   const double *lfac, int64_t n, int64_t p, const float *Y, double *F,
+                                   const double *lfac, int64_t n, int64_t p, const float *Y, double *carries,
                                    float *S) {
+    if ((const float *)S == Y) return ADMMQ_ERR_PARAM;       // the second pass reads Y again: not in place
     // the widest column strip that still gives every CU a block
     int C = 64;
     if ((p + 63) / 64 < 256) C = 32;
     if ((p + 31) / 32 < 256) C = 16;
+    if ((p + 15) / 16 < 128) C = 8;           // measured at p = 1024: 0.081 ms against 0.107 ms with 16 columns
     static int forced = -1;
     if (forced < 0) {
         const char *e = getenv("ADMMQ_TRIDIAG_COLS");
         forced = e ? atoi(e) : 0;
     }
-    if (forced == 16 || forced == 32 || forced == 64) C = forced;
+    if (forced == 8 || forced == 16 || forced == 32 || forced == 64) C = forced;
     const unsigned nb = (unsigned)((p + C - 1) / C);
-    if (C == 64)
-        hipLaunchKernelGGL(tridiag_apply_split_kernel<64>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
-                           (long)n, (long)p, Y, F, S);
+    if (C == 8)
+        hipLaunchKernelGGL((tridiag_apply_split_kernel<8, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
+                           lfac, (long)n, (long)p, Y, carries, S);
+    else if (C == 64)
+        hipLaunchKernelGGL((tridiag_apply_split_kernel<64, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
+                           lfac, (long)n, (long)p, Y, carries, S);
     else if (C == 32)
-        hipLaunchKernelGGL(tridiag_apply_split_kernel<32>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
-                           (long)n, (long)p, Y, F, S);
+        hipLaunchKernelGGL((tridiag_apply_split_kernel<32, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
+                           lfac, (long)n, (long)p, Y, carries, S);
     else
-        hipLaunchKernelGGL(tridiag_apply_split_kernel<16>, dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv, lfac,
-                           (long)n, (long)p, Y, F, S);
+        hipLaunchKernelGGL((tridiag_apply_split_kernel<16, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
+                           lfac, (long)n, (long)p, Y, carries, S);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
