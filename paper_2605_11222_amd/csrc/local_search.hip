@@ -306,11 +306,24 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
         pend_d[(long)(2 * slot_prev) * p + j] = nd1;        // zero steps for an empty slot
         pend_d[(long)(2 * slot_prev + 1) * p + j] = nd2;
     }
-    if (win >= 0 && blockIdx.y == (gridDim.y > 1 ? 1u : 0u)) {
-        // coefficient cache of the new slot: the two H' columns (rows of the symmetric H) of the winner's rows
-        for (long r = (long)blockIdx.x * LS_CHUNK + tid; r < n; r += (long)gridDim.x * LS_CHUNK) {
-            hcol[(long)(2 * slot_prev) * n + r] = H[wi1 * n + r] + (r == wi1 ? lambda : 0.f);
-            hcol[(long)(2 * slot_prev + 1) * n + r] = H[wi2 * n + r] + (r == wi2 ? lambda : 0.f);
+    if (win >= 0) {
+        // coefficient cache of the new slot: the two H' columns (rows of the symmetric H) of the winner's rows.
+        // The blocks of the pairs 1, 2, ... share the n entries out, one per thread (a loop in one row of blocks
+        // would pay the memory latency once per trip); a launch without candidates has only row 0 and loops.
+        if (gridDim.y > 1) {
+            if (blockIdx.y >= 1) {
+                const long r = (((long)blockIdx.y - 1) * gridDim.x + blockIdx.x) * LS_CHUNK + tid;
+                const long cover = ((long)gridDim.y - 1) * gridDim.x * LS_CHUNK;
+                for (long rr = r; rr < n; rr += cover) {
+                    hcol[(long)(2 * slot_prev) * n + rr] = H[wi1 * n + rr] + (rr == wi1 ? lambda : 0.f);
+                    hcol[(long)(2 * slot_prev + 1) * n + rr] = H[wi2 * n + rr] + (rr == wi2 ? lambda : 0.f);
+                }
+            }
+        } else {
+            for (long r = (long)blockIdx.x * LS_CHUNK + tid; r < n; r += (long)gridDim.x * LS_CHUNK) {
+                hcol[(long)(2 * slot_prev) * n + r] = H[wi1 * n + r] + (r == wi1 ? lambda : 0.f);
+                hcol[(long)(2 * slot_prev + 1) * n + r] = H[wi2 * n + r] + (r == wi2 ? lambda : 0.f);
+            }
         }
     }
     if (npairs_prev > 0 && first_block && tid == 0) {
