@@ -59,7 +59,8 @@ __device__ inline float wave_sum_f(float v) {
     return v;
 }
 
-constexpr int LS_K = 16;          // pending pairs between two passes over G
+constexpr int LS_K = 16;          // pending pairs between two passes over G (cfg2 on MI355X: 8 -> 0.132 s,
+                                  // 16 -> 0.120 s, 32 -> 0.181 s for the whole search)
 
 __device__ inline int step_sign(float d) { return (d > 0.f) - (d < 0.f); }
 
