@@ -159,8 +159,12 @@ def test_eq11_batch_totals_match_oracle(ctx):
     assert np.allclose(tot, want, rtol=2e-4, atol=1e-4 * max(want))
 
 
-@pytest.mark.parametrize("n,p,bits,g,seed", [(64, 40, 3, 16, 1), (128, 300, 2, 0, 2), (48, 1100, 4, 24, 3)])
-def test_local_search_against_oracle(ctx, n, p, bits, g, seed):
+@pytest.mark.parametrize("n,p,bits,g,seed,pairs", [(64, 40, 3, 16, 1, 16), (128, 300, 2, 0, 2, 16), (48, 1100, 4, 24, 3, 16),
+                                                   (96, 512, 3, 0, 4, 64),      # move bytes staged 16 at a time
+                                                   (80, 272, 3, 16, 5, 64),     # the last column chunk is ragged
+                                                   (72, 130, 2, 0, 6, 96),      # more candidates than are prefetched
+                                                   (40, 48, 3, 8, 7, 3)])
+def test_local_search_against_oracle(ctx, n, p, bits, g, seed, pairs):
     H32, Hd, lam, W0 = ls_problem(n, p, bits, g, seed)
     W0d, Hdv = to_dev(W0), to_dev(H32)
     scales, zeros = ctx.grid_init(W0d, bits, g)
@@ -170,8 +174,8 @@ def test_local_search_against_oracle(ctx, n, p, bits, g, seed):
     codes = to_dev(k0.astype(np.uint8))
     j0 = ctx.objective(Hdv, W0d, g, scales, zeros, codes)
     assert j0 == pytest.approx(orc.objective(Hd, W0.astype(np.float64), grid.dequant(k0)), rel=1e-4)
-    moves, drop = ctx.local_search(Hdv, W0d, bits, g, scales, zeros, codes, rounds=3, pairs_per_batch=16, seed=seed)
-    ref = orc.local_search(Hd, W0.astype(np.float64), k0, grid, rounds=3, pairs_per_batch=16, seed=seed)
+    moves, drop = ctx.local_search(Hdv, W0d, bits, g, scales, zeros, codes, rounds=3, pairs_per_batch=pairs, seed=seed)
+    ref = orc.local_search(Hd, W0.astype(np.float64), k0, grid, rounds=3, pairs_per_batch=pairs, seed=seed)
     k = codes.cpu().numpy().astype(np.int64)
     assert 0 <= k.min() and k.max() <= 2 ** bits - 1
     j1 = orc.objective(Hd, W0.astype(np.float64), grid.dequant(k))
