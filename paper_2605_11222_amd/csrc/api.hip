@@ -778,23 +778,61 @@ extern "C" admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const
 }
 
 // ---- whole layer -----------------------------------------------------------------------------------
-extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
-                                             int64_t ldw, int32_t bits, int32_t group_size,
-                                             const admmq_schedule *sched, uint8_t *codes, float *scales, float *zeros,
-                                             admmq_stats *stats) {
-    if (!ctx || !sched || !codes || !scales || !zeros) return ADMMQ_ERR_NULL;
-    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
-    if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
-        !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds < 0 ||
-        sched->ls_batches < 0 || sched->ls_pairs < 0 || sched->refresh_iter < -1 || sched->clip_points < 0 ||
-        sched->clip_points > 100000 || (sched->clip_points > 0 && !(sched->clip_shrink >= 0.0 && sched->clip_shrink < 1.0)))
+// ---- other formats (Sec. 4.3) --------------------------------------------------------------------------
+namespace {
+
+admmq_status check_format(const admmq_format *fmt, int64_t n) {
+    if (!fmt) return ADMMQ_ERR_NULL;
+    if (fmt->kind == ADMMQ_FORMAT_DUAL_GRID) {
+        if (!fmt->flags || !fmt->scales || !fmt->zeros) return ADMMQ_ERR_NULL;
+        if (fmt->bits < 2 || fmt->bits > 8) return ADMMQ_ERR_PARAM;
+        if (fmt->group_size < 0 || (fmt->group_size > 0 && n % fmt->group_size != 0)) return ADMMQ_ERR_SHAPE;
+    } else if (fmt->kind == ADMMQ_FORMAT_CODEBOOK) {
+        if (!fmt->codebook) return ADMMQ_ERR_NULL;
+        if (fmt->bits < 1 || fmt->bits > 4 || fmt->group_size != 0) return ADMMQ_ERR_PARAM;
+    } else {
         return ADMMQ_ERR_PARAM;
-    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
-    ADMMQ_HIP(hipSetDevice(ctx->device));
-    const int64_t g = group_size > 0 ? group_size : n;
+    }
+    return ADMMQ_OK;
+}
+
+// a codebook must be finite and strictly ascending per column (synchronises)
+admmq_status check_codebook(admmq_ctx *ctx, const float *codebook, int bits, int64_t p) {
+    double *dev = nullptr;
+    ADMMQ_TRY(take(ctx, dev, 2));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
+    ADMMQ_TRY(admmq_k_codebook_check(ctx, codebook, 1 << bits, p, dev));
+    double bad = 0.0;
+    ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
+    return bad > 0.0 ? ADMMQ_ERR_PARAM : ADMMQ_OK;
+}
+
+}  // namespace
+
+// ---- the whole layer (Alg. 1), for the uniform grid and for the other formats of Sec. 4.3 ------------------
+namespace {
+
+// What the D-update projects onto.  kind 0: the uniform grid of eq. 10 (scales / zeros [n/g][p], fitted here with
+// the schedule's options, refreshed if asked, local search afterwards).  kind 1 / 2: admmq_format_kind (dual grid:
+// scales / zeros [2][n/g][p]; codebook: levels and optional flags); Wq receives the dense result.
+struct Projection {
+    int kind;
+    int bits;
+    int64_t g;
+    float *scales, *zeros;
+    const uint8_t *flags;
+    const float *codebook;
+    float *Wq;
+};
+
+admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p, int64_t ldw,
+                           const Projection &pj, const admmq_schedule *sched, uint8_t *codes, admmq_stats *stats) {
+    const bool uniform = pj.kind == 0;
+    const int bits = pj.bits;
+    const int64_t g = pj.g;
     const int T = sched->T;
     const size_t np = (size_t)n * p;
-    const size_t ng = (size_t)(n / g) * p;
+    const size_t ng = (size_t)(n / g) * p * (pj.kind == ADMMQ_FORMAT_DUAL_GRID ? 2 : 1);     // grid entries
     const bool want = stats != nullptr;
     Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
     t_total.start();
@@ -806,7 +844,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     // --- input checks on the device, before anything is written -------------------------------
     t_phase.start();
     admmq_arena_reset_transient(ctx);
-    ADMMQ_TRY(admmq_arena_reserve(ctx, 4096));
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 8192));
     {
         double *dev = nullptr;
         ADMMQ_TRY(take(ctx, dev, 2));
@@ -815,6 +853,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
         double bad = 0.0;
         ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
         if (bad > 0.0) return ADMMQ_ERR_NOT_FINITE;
+        if (pj.kind == ADMMQ_FORMAT_CODEBOOK) ADMMQ_TRY(check_codebook(ctx, pj.codebook, bits, p));
     }
     float ms_setup = t_phase.stop();
 
@@ -836,7 +875,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
 
     // --- grid, initial state, schedule -----------------------------------------------------------
     t_phase.start();
-    LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
+    LsPlan plan = ls_plan(n, uniform ? sched->ls_rounds : 0, sched->ls_batches, sched->ls_pairs);
     size_t need = admm_transient_bytes(n, p, T) + 3 * admmq_align_up(ng * 4) +
                   admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8);
     if (plan.rounds > 0 && n >= 2) {
@@ -868,15 +907,18 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_TRY(take(ctx, flips, (size_t)T));
     ADMMQ_TRY(take(ctx, jdev, 4));
 
-    ADMMQ_TRY(admmq_k_grid_fit(ctx, W0, n, p, ldw, bits, g, sched->symmetric != 0, sched->clip_points,
-                               sched->clip_shrink, scales, zeros));
-    ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
+    if (uniform)
+        ADMMQ_TRY(admmq_k_grid_fit(ctx, W0, n, p, ldw, bits, g, sched->symmetric != 0, sched->clip_points,
+                                   sched->clip_shrink, pj.scales, pj.zeros));
+    else if (pj.kind == ADMMQ_FORMAT_DUAL_GRID)
+        ADMMQ_TRY(admmq_k_dual_grid_init(ctx, W0, n, p, ldw, bits, g, pj.flags, pj.scales, pj.zeros));
+    if (pj.kind != ADMMQ_FORMAT_CODEBOOK) ADMMQ_TRY(admmq_k_recip(ctx, pj.scales, inv_scales, (int64_t)ng));
     // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
     ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, flips, 0, (size_t)T * 8));
-    const bool want_flips = want && stats->code_flips != nullptr;
+    const bool want_flips = uniform && want && stats->code_flips != nullptr;
     if (want_flips) ADMMQ_TRY(admmq_k_fill_bytes(ctx, codes, 0, np));
     std::vector<double> hrho((size_t)T + 1);
     {
@@ -895,8 +937,13 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
     ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
     if (want) {
-        // round-to-nearest on the initial grid, as the baseline objective (W, Y and F are still free)
-        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, (uint8_t *)F, n, p, g, scales, zeros, bits, 2, W));
+        // the plain projection of W0 (round-to-nearest on the initial grid) as the baseline objective; W, Y and F
+        // are still free
+        if (uniform)
+            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, (uint8_t *)F, n, p, g, pj.scales, pj.zeros, bits, 2, W));
+        else
+            ADMMQ_TRY(admmq_k_nearest_error(ctx, pj.kind, W0, ldw, n, p, bits, g, pj.flags, pj.scales, pj.zeros,
+                                            pj.codebook, nullptr, W));
         ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
         ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
     }
@@ -907,7 +954,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     // W and B trade places every iteration: the projection pass writes B^(t+1) over the W it has just read
     float *Bcur = B, *Wcur = W;
     for (int t = 0; t < T; ++t) {
-        const float rf = (float)hrho[t];
+        const float rf = (float)hrho[t], rf_next = (float)hrho[t + 1];
         if (t == 0) {
             // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
@@ -915,13 +962,19 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
         }
         const bool last = t == T - 1;
-        if (t == sched->refresh_iter)
-            ADMMQ_TRY(grid_refresh_core(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, hrho[t], scales, zeros, inv_scales,
-                                        new_sc, new_zr, rpart, &refresh_accepted, &refresh_eo, &refresh_en));
+        if (uniform && t == sched->refresh_iter)
+            ADMMQ_TRY(grid_refresh_core(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, hrho[t], pj.scales, pj.zeros,
+                                        inv_scales, new_sc, new_zr, rpart, &refresh_accepted, &refresh_eo,
+                                        &refresh_en));
         const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
-        ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, scales, inv_scales, zeros, rf,
-                                       1.0f / rf, 1.0f / (float)hrho[t + 1], (last || want_flips) ? codes : nullptr,
-                                       want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr));
+        if (uniform)
+            ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.scales, inv_scales, pj.zeros,
+                                           rf, 1.0f / rf, 1.0f / rf_next, (last || want_flips) ? codes : nullptr,
+                                           want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr));
+        else
+            ADMMQ_TRY(admmq_k_project_format(ctx, pj.kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.flags, pj.scales,
+                                             inv_scales, pj.zeros, pj.codebook, rf, 1.0f / rf, 1.0f / rf_next,
+                                             last ? 1 : 0, codes, Wcur, pj.Wq, res + t));
         admmq_prof_end(ctx, sp);
         float *tmpp = Bcur;
         Bcur = Wcur;
@@ -946,21 +999,24 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             for (int t = 0; t < T; ++t) stats->code_flips[t] = (int64_t)h[t];
         }
         // objective of the ADMM result; W, Y are free now
-        ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, W));
+        if (uniform)
+            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, pj.scales, pj.zeros, bits, 0, W));
+        else
+            ADMMQ_TRY(admmq_k_diff(ctx, pj.Wq, W0, ldw, n, p, W));
         ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
         stats->j_damp = stats->j_damp_admm;
         stats->ls_moves = 0;
     }
 
-    // --- local search (Alg. 1 line 11) ----------------------------------------------------------
+    // --- local search (Alg. 1 line 11; uniform grids only) -----------------------------------------
     t_phase.start();
     float ms_ls = 0.f;
     if (plan.rounds > 0 && n >= 2) {
         admmq_arena_reset_transient(ctx);
         int32_t moves = 0;
         double drop = 0.0;
-        ADMMQ_TRY(local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, scales, zeros, codes, plan, sched->seed,
-                                    nullptr, &moves, &drop));
+        ADMMQ_TRY(local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, pj.scales, pj.zeros, codes, plan,
+                                    sched->seed, nullptr, &moves, &drop));
         ms_ls = t_phase.stop();
         if (want) {
             stats->ls_moves = moves;
@@ -970,7 +1026,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
             ADMMQ_TRY(take(ctx, E, np));
             ADMMQ_TRY(take(ctx, tmp, np));
             ADMMQ_TRY(take(ctx, jd, 2));
-            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, scales, zeros, bits, 0, E));
+            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, pj.scales, pj.zeros, bits, 0, E));
             ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, E, tmp, jd, &stats->j_damp, &stats->j_recon));
         }
     }
@@ -990,37 +1046,27 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     return ADMMQ_OK;
 }
 
-// ---- other formats (Sec. 4.3) --------------------------------------------------------------------------
-namespace {
-
-admmq_status check_format(const admmq_format *fmt, int64_t n) {
-    if (!fmt) return ADMMQ_ERR_NULL;
-    if (fmt->kind == ADMMQ_FORMAT_DUAL_GRID) {
-        if (!fmt->flags || !fmt->scales || !fmt->zeros) return ADMMQ_ERR_NULL;
-        if (fmt->bits < 2 || fmt->bits > 8) return ADMMQ_ERR_PARAM;
-        if (fmt->group_size < 0 || (fmt->group_size > 0 && n % fmt->group_size != 0)) return ADMMQ_ERR_SHAPE;
-    } else if (fmt->kind == ADMMQ_FORMAT_CODEBOOK) {
-        if (!fmt->codebook) return ADMMQ_ERR_NULL;
-        if (fmt->bits < 1 || fmt->bits > 4 || fmt->group_size != 0) return ADMMQ_ERR_PARAM;
-    } else {
-        return ADMMQ_ERR_PARAM;
-    }
-    return ADMMQ_OK;
-}
-
-// a codebook must be finite and strictly ascending per column (synchronises)
-admmq_status check_codebook(admmq_ctx *ctx, const admmq_format *fmt, int64_t p) {
-    if (fmt->kind != ADMMQ_FORMAT_CODEBOOK) return ADMMQ_OK;
-    double *dev = nullptr;
-    ADMMQ_TRY(take(ctx, dev, 2));
-    ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
-    ADMMQ_TRY(admmq_k_codebook_check(ctx, fmt->codebook, 1 << fmt->bits, p, dev));
-    double bad = 0.0;
-    ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
-    return bad > 0.0 ? ADMMQ_ERR_PARAM : ADMMQ_OK;
+bool schedule_ok(const admmq_schedule *s) {
+    return s->T >= 1 && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
+           isfinite(s->gamma) && isfinite(s->damp) && s->ls_rounds >= 0 && s->ls_batches >= 0 && s->ls_pairs >= 0 &&
+           s->refresh_iter >= -1 && s->clip_points >= 0 && s->clip_points <= 100000 &&
+           (s->clip_points == 0 || (s->clip_shrink >= 0.0 && s->clip_shrink < 1.0));
 }
 
 }  // namespace
+
+extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
+                                             int64_t ldw, int32_t bits, int32_t group_size,
+                                             const admmq_schedule *sched, uint8_t *codes, float *scales, float *zeros,
+                                             admmq_stats *stats) {
+    if (!ctx || !sched || !codes || !scales || !zeros) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, bits, group_size));
+    if (!schedule_ok(sched)) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    Projection pj = {0, bits, group_size > 0 ? group_size : n, scales, zeros, nullptr, nullptr, nullptr};
+    return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats);
+}
 
 extern "C" admmq_status admmq_grid_init_dual(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
                                              const admmq_format *fmt) {
@@ -1053,7 +1099,7 @@ extern "C" admmq_status admmq_project_dual_format(admmq_ctx *ctx, const float *W
     ADMMQ_TRY(take(ctx, inv_scales, ng2));
     ADMMQ_TRY(take(ctx, inv_d, (size_t)n));
     ADMMQ_TRY(take(ctx, dev_res, 2));
-    ADMMQ_TRY(check_codebook(ctx, fmt, p));
+    if (fmt->kind == ADMMQ_FORMAT_CODEBOOK) ADMMQ_TRY(check_codebook(ctx, fmt->codebook, fmt->bits, p));
     if (fmt->kind == ADMMQ_FORMAT_DUAL_GRID) ADMMQ_TRY(admmq_k_recip(ctx, fmt->scales, inv_scales, (int64_t)ng2));
     ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_res, 0, 16));
@@ -1073,158 +1119,13 @@ extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float 
     if (!ctx || !sched || !codes || !Wq) return ADMMQ_ERR_NULL;
     ADMMQ_TRY(check_format(fmt, n));
     ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, 2, fmt->group_size));
-    if (sched->T < 1 || !(sched->rho0 > 0.0) || !(sched->gamma >= 1.0) || !(sched->damp >= 0.0) ||
-        !isfinite(sched->rho0) || !isfinite(sched->gamma) || !isfinite(sched->damp) || sched->ls_rounds != 0 ||
-        sched->refresh_iter != -1 || sched->symmetric != 0 || sched->clip_points != 0)
+    if (!schedule_ok(sched) || sched->ls_rounds != 0 || sched->refresh_iter != -1 || sched->symmetric != 0 ||
+        sched->clip_points != 0)
         return ADMMQ_ERR_PARAM;
     if (stats && stats->code_flips) return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
-    const int kind = fmt->kind, bits = fmt->bits;
-    const int64_t g = fmt->group_size > 0 ? fmt->group_size : n;
-    const int T = sched->T;
-    const size_t np = (size_t)n * p;
-    const size_t ng2 = 2 * (size_t)(n / g) * p;
-    const bool want = stats != nullptr;
-    Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
-    t_total.start();
-    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
-    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
-    prof_collect(ctx, prof_ms, prof_cnt);
-    ctx->prof.on = want && stats->profile != 0;
-
-    // --- input checks on the device, before anything is written ------------------------------------------
-    t_phase.start();
-    admmq_arena_reset_transient(ctx);
-    ADMMQ_TRY(admmq_arena_reserve(ctx, 8192));
-    {
-        double *dev = nullptr;
-        ADMMQ_TRY(take(ctx, dev, 2));
-        ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
-        ADMMQ_TRY(admmq_k_count_nonfinite(ctx, W0, n, p, ldw, dev));
-        double bad = 0.0;
-        ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
-        if (bad > 0.0) return ADMMQ_ERR_NOT_FINITE;
-        ADMMQ_TRY(check_codebook(ctx, fmt, p));
-    }
-    float ms_setup = t_phase.stop();
-
-    // --- Alg. 1 lines 1-3 ------------------------------------------------------------------------------------
-    t_phase.start();
-    double lambda = 0.0;
-    if (sched->reuse_factor) {
-        const admmq_factor &have = ctx->fac;
-        if (!have.valid || have.n != n || have.H_src != H || have.damp != sched->damp ||
-            have.precondition != sched->precondition)
-            return ADMMQ_ERR_STATE;
-        lambda = have.lambda;
-        admmq_arena_reset_transient(ctx);
-    } else {
-        ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
-    }
-    float ms_factor = t_phase.stop();
-    const admmq_factor &f = ctx->fac;
-
-    // --- format, initial state, schedule ------------------------------------------------------------------------
-    t_phase.start();
-    ADMMQ_TRY(admmq_arena_reserve(ctx, admm_transient_bytes(n, p, T) + admmq_align_up(ng2 * 4) + 8192));
-    float *B = nullptr, *V = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr, *inv_scales = nullptr;
-    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *res = nullptr, *jdev = nullptr;
-    unsigned long long *unused_flips = nullptr;
-    ADMMQ_TRY(take(ctx, B, np));
-    ADMMQ_TRY(take(ctx, V, np));
-    ADMMQ_TRY(take(ctx, W, np));
-    ADMMQ_TRY(take(ctx, C0, np));
-    ADMMQ_TRY(take(ctx, Y, np));
-    ADMMQ_TRY(take(ctx, F, np + (size_t)p));
-    ADMMQ_TRY(take(ctx, inv_scales, ng2));
-    ADMMQ_TRY(take(ctx, rhos, (size_t)T));
-    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
-    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
-    ADMMQ_TRY(take(ctx, res, (size_t)T));
-    ADMMQ_TRY(take(ctx, unused_flips, (size_t)T));
-    ADMMQ_TRY(take(ctx, jdev, 4));
-    if (kind == ADMMQ_FORMAT_DUAL_GRID) {
-        ADMMQ_TRY(admmq_k_dual_grid_init(ctx, W0, n, p, ldw, bits, g, fmt->flags, fmt->scales, fmt->zeros));
-        ADMMQ_TRY(admmq_k_recip(ctx, fmt->scales, inv_scales, (int64_t)ng2));
-    }
-    ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));      // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
-    ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
-    ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
-    std::vector<double> hrho((size_t)T + 1);
-    {
-        double r = sched->rho0;
-        for (int t = 0; t <= T; ++t) {
-            hrho[t] = r;
-            r *= sched->gamma;
-        }
-    }
-    ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
-    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
-    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
-    gemm_tn_args g0 = {};
-    g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
-    g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
-    ADMMQ_TRY(admmq_gemm_tn(ctx, g0));                              // C0 = Q^T Ws
-    if (want) {
-        // the plain projection of W0 as the baseline objective (W and Y are still free)
-        ADMMQ_TRY(admmq_k_nearest_error(ctx, kind, W0, ldw, n, p, bits, g, fmt->flags, fmt->scales, fmt->zeros,
-                                        fmt->codebook, nullptr, W));
-        ADMMQ_TRY(objective_core(ctx, H, lambda, n, p, W, Y, jdev));
-        ADMMQ_TRY(read_back(ctx, &stats->j_damp_rtn, jdev, 8));
-    }
-    ms_setup += t_phase.stop();
-
-    // --- ADMM loop (Alg. 1 lines 5-9) with the format's projection ------------------------------------------
-    t_phase.start();
-    float *Bcur = B, *Wcur = W;
-    for (int t = 0; t < T; ++t) {
-        const float rf = (float)hrho[t];
-        if (t == 0) {
-            ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
-        } else {
-            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
-        }
-        const bool last = t == T - 1;
-        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
-        ADMMQ_TRY(admmq_k_project_format(ctx, kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, fmt->flags, fmt->scales,
-                                         inv_scales, fmt->zeros, fmt->codebook, rf, 1.0f / rf,
-                                         1.0f / (float)hrho[t + 1], last ? 1 : 0, codes, Wcur, Wq, res + t));
-        admmq_prof_end(ctx, sp);
-        float *tmpp = Bcur;
-        Bcur = Wcur;
-        Wcur = tmpp;
-    }
-    float ms_admm = t_phase.stop();
-
-    if (want) {
-        stats->iters_done = T;
-        stats->lambda = lambda;
-        stats->refresh_accepted = 0;
-        stats->refresh_err_old = 0.0;
-        stats->refresh_err_new = 0.0;
-        if (stats->primal_res) {
-            std::vector<double> h((size_t)T);
-            ADMMQ_TRY(read_back(ctx, h.data(), res, (size_t)T * 8));
-            for (int t = 0; t < T; ++t) stats->primal_res[t] = (float)sqrt(h[t]);
-        }
-        ADMMQ_TRY(admmq_k_diff(ctx, Wq, W0, ldw, n, p, W));         // W, Y are free now
-        ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
-        stats->j_damp = stats->j_damp_admm;
-        stats->ls_moves = 0;
-    }
-    prof_collect(ctx, prof_ms, prof_cnt);
-    if (want) {
-        stats->ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       stats->n_gemm = prof_cnt[ADMMQ_TAG_GEMM];
-        stats->ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; stats->n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
-        stats->ms_project = prof_ms[ADMMQ_TAG_PROJECT]; stats->n_project = prof_cnt[ADMMQ_TAG_PROJECT];
-        stats->ms_ls_apply = 0.f;                       stats->n_ls_apply = 0;
-        stats->ms_setup = ms_setup;
-        stats->ms_factor = ms_factor;
-        stats->ms_admm = ms_admm;
-        stats->ms_local_search = 0.f;
-        stats->ms_total = t_total.stop();
-    }
-    admmq_arena_reset_transient(ctx);
-    return ADMMQ_OK;
+    Projection pj = {fmt->kind, fmt->bits, fmt->group_size > 0 ? fmt->group_size : n, fmt->scales, fmt->zeros,
+                     fmt->flags, fmt->codebook, Wq};
+    return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats);
 }
