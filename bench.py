@@ -102,8 +102,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over output columns without "
-              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard over output columns without "
+              "communication, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
