@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
                                                       double *__restrict__ ta, double *__restrict__ tb,
                                                       double *__restrict__ sc, double *__restrict__ part,
                                                       unsigned *__restrict__ counter,
-                                                      const double *__restrict__ part2, int nparts2, int sym) {
+                                                      const double *__restrict__ part2, int nparts2, int sym,
+                                                      int finalise) {
     __shared__ double vk[NB], wk[NB];
     __shared__ double xs[4];
     __shared__ double red[4][PART_W];
@@ -182,6 +183,9 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
             part[PX_WLEAD] = wnew;
         }
     }
+    // without `finalise` the product kernel that follows adds the partials up itself, while its first loads are
+    // in flight: the fence, the counter and a second pass over the partials drop out of the column's critical path
+    if (!finalise) return;
     if (!last_block_done(counter, gridDim.x)) return;
     // add the block partials in block order: thread r owns partial r; eight blocks' worth of its loads are in
     // flight at a time, the additions stay in index order
@@ -232,41 +236,103 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
 }
 
 // p'[i] = sum_{j >= k+1} A[i][j] v[j] - sum_q (V_q[i] (W_q.v) + W_q[i] (V_q.v)) for i >= k+1, with
-// v = (1, scale * xbuf) formed on the fly.  A is only read below row k; the normalised v is stored
-// in panel slot c and in row k of A (its permanent home).  One wave per row, 4 rows per block.
+// v = (1, scale * xbuf).  A is only read below row k; the normalised v is stored in panel slot c and in row k
+// of A (its permanent home).  One wave per row, 4 rows per block.
+// The reflector's scalars are formed here, by every block for itself, from the block partials that
+// tri_row_kernel left (nparts1 of them, added in block order): the loads of the partials and of the matrix rows
+// are in flight together, and the row dots are taken with the unscaled xbuf and scaled afterwards
+// (p'[i] = A[i][k+1] + scale * sum_{j > k+1} A[i][j] xbuf[j]), so nothing waits for the scalars.  Block 0 records
+// T's entries, tau and the scale.
 __global__ __launch_bounds__(256) void tri_mat_kernel(double *__restrict__ A, long n, long k, int c,
                                                       double *__restrict__ Vp, const double *__restrict__ Wp,
                                                       const double *__restrict__ xbuf, double *__restrict__ pbuf,
-                                                      const double *__restrict__ sc, double *__restrict__ part) {
+                                                      double *__restrict__ sc, double *__restrict__ part,
+                                                      const double *__restrict__ part1, int nparts1,
+                                                      double *__restrict__ tau, double *__restrict__ ta,
+                                                      double *__restrict__ tb) {
     __shared__ double ad[NB], bd[NB];
+    __shared__ double tot[PART_W];
     __shared__ double wsum[4];
+    __shared__ double scale_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const double scale = sc[SC_SCALE];
-    if (tid < c) {
-        ad[tid] = sc[SC_DOTS + 2 * tid];
-        bd[tid] = sc[SC_DOTS + 2 * tid + 1];
+    const int nred = 1 + 2 * c;
+    // ---- requests first: this thread's partial column, the leading entries, the matrix row -----------------
+    double run = 0.0;
+    if (tid < nred) {
+        const double *src = part1 + tid;
+        int b0 = 0;
+        for (; b0 + 8 <= nparts1; b0 += 8) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(long)(b0 + u) * PART_W];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) run += v[u];
+        }
+        for (; b0 < nparts1; ++b0) run += src[(long)b0 * PART_W];
     }
-    __syncthreads();
-    double wdot = 0.0;
+    double w_lead = 0.0, v_lead = 0.0;
+    if (tid < c) {
+        w_lead = Wp[(long)tid * n + k + 1];
+        v_lead = Vp[(long)tid * n + k + 1];
+    }
+    const double x_diag = xbuf[k], alpha = xbuf[k + 1];
     const long i = k + 1 + (long)blockIdx.x * 4 + wave;
+    double a0 = 0.0, a1 = 0.0, lead = 0.0, xi = 0.0, vcorr = 0.0, wcorr = 0.0;
     if (i < n) {
         const double *row = A + i * n;
-        double a0 = 0.0, a1 = 0.0;
         long j = k + 1 + lane;
         if (lane == 0) {                     // v[k+1] = 1
-            a0 = row[j];
+            lead = row[j];
             j += 64;
         }
         for (; j + 64 < n; j += 128) {
-            a0 += row[j] * (xbuf[j] * scale);
-            a1 += row[j + 64] * (xbuf[j + 64] * scale);
+            a0 += row[j] * xbuf[j];
+            a1 += row[j + 64] * xbuf[j + 64];
         }
-        if (j < n) a0 += row[j] * (xbuf[j] * scale);
-        double t = a0 + a1;
-        if (lane < c) t -= Vp[(long)lane * n + i] * ad[lane] + Wp[(long)lane * n + i] * bd[lane];
+        if (j < n) a0 += row[j] * xbuf[j];
+        if (lane < c) {
+            vcorr = Vp[(long)lane * n + i];
+            wcorr = Wp[(long)lane * n + i];
+        }
+        xi = xbuf[i];
+    }
+    // ---- the reflector's scalars --------------------------------------------------------------------------------
+    if (tid < nred) tot[tid] = run;
+    __syncthreads();
+    if (tid == 0) {
+        const double sig = tot[0];
+        double beta, tk, scale;
+        if (sig == 0.0) {
+            beta = alpha; tk = 0.0; scale = 0.0;
+        } else {
+            const double nrm = sqrt(alpha * alpha + sig);
+            beta = alpha >= 0.0 ? -nrm : nrm;
+            tk = (beta - alpha) / beta;
+            scale = 1.0 / (alpha - beta);
+        }
+        scale_sh = scale;
+        if (blockIdx.x == 0) {
+            ta[k] = x_diag;
+            tb[k] = beta;
+            tau[k] = tk;
+            sc[SC_SCALE] = scale;
+        }
+    }
+    __syncthreads();
+    const double scale = scale_sh;
+    if (tid < c) {
+        // v = (1, scale * x_tail): dots with the earlier slots, the leading 1 sits at index k+1
+        ad[tid] = scale * tot[1 + 2 * tid] + w_lead;
+        bd[tid] = scale * tot[2 + 2 * tid] + v_lead;
+    }
+    __syncthreads();
+    double wdot = 0.0;
+    if (i < n) {
+        double t = lead + scale * (a0 + a1);
+        if (lane < c) t -= vcorr * ad[lane] + wcorr * bd[lane];
         t = wave_sum(t);
         if (lane == 0) {
-            const double vi = (i == k + 1) ? 1.0 : xbuf[i] * scale;
+            const double vi = (i == k + 1) ? 1.0 : xi * scale;
             pbuf[i] = t;
             Vp[(long)c * n + i] = vi;
             A[k * n + i] = vi;
@@ -815,9 +881,10 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
             was_sym = sym;
             for (int c = 0; c < nbc; ++c) {
                 const long k = k0 + c;
-                hipLaunchKernelGGL(tri_row_kernel, dim3(blocks_for(N - k, ROW_CHUNK)), dim3(256), 0, st, A64, N, k, c,
-                                   c > 0 ? 1 : 0, 1, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2,
-                                   parts_prev, sym ? 1 : 0);
+                const unsigned row_blocks = blocks_for(N - k, ROW_CHUNK);
+                hipLaunchKernelGGL(tri_row_kernel, dim3(row_blocks), dim3(256), 0, st, A64, N, k, c, c > 0 ? 1 : 0, 1,
+                                   Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2, parts_prev,
+                                   sym ? 1 : 0, sym ? 1 : 0);
                 if (sym) {
                     const int t0 = (int)((k + 1) / ST);
                     const int nt = (int)((N - 1) / ST) - t0 + 1;
@@ -829,14 +896,14 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
                 } else {
                     parts_prev = (int)blocks_for(N - k - 1, 4);
                     hipLaunchKernelGGL(tri_mat_kernel, dim3((unsigned)parts_prev), dim3(256), 0, st, A64, N, k, c, Vp,
-                                       Wp, xbuf, pbuf, sc, part2);
+                                       Wp, xbuf, pbuf, sc, part2, part1, (int)row_blocks, tau, ta, tb);
                 }
             }
             // close the panel's last column, then apply the panel to the trailing matrix
             const long r0 = k0 + nbc;
             hipLaunchKernelGGL(tri_row_kernel, dim3(blocks_for(N - r0, ROW_CHUNK)), dim3(256), 0, st, A64, N, r0, nbc,
                                1, 0, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2, parts_prev,
-                               sym ? 1 : 0);
+                               sym ? 1 : 0, 1);
             const unsigned tiles = blocks_for(N - r0, 64);
             hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, nbc, Vp, Wp,
                                sym ? 1 : 0);
