@@ -25,9 +25,31 @@ constexpr int NB = 32;
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 
+// Sum over the 64 lanes, left in every lane, without a trip through LDS: the two halves and the 16-lane rows are
+// folded with the gfx950 lane-swap instructions, the rows with DPP rotations by 8, 4, 2, 1 (a fixed order).
+template <int N>
+__device__ inline double row_ror_add(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x120 + N, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x120 + N, 0xF, 0xF, true);
+    return v + __hiloint2double(hi, lo);
+}
+__device__ inline double swap_fold32(double a) {
+    const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(a), (unsigned)__double2loint(a), false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(a), (unsigned)__double2hiint(a), false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
+__device__ inline double swap_fold16(double a) {
+    const auto lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(a), (unsigned)__double2loint(a), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(a), (unsigned)__double2hiint(a), false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
 __device__ inline double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    v = swap_fold32(v);
+    v = swap_fold16(v);
+    v = row_ror_add<8>(v);
+    v = row_ror_add<4>(v);
+    v = row_ror_add<2>(v);
+    v = row_ror_add<1>(v);
     return v;
 }
 // load that is coherent across the chip (bypasses the per-CU cache): used by the block that finishes last
@@ -45,6 +67,23 @@ enum { SC_SCALE = 1, SC_DOTS = 2, SC_COUNT = 2 + 2 * NB };
 constexpr int ROW_CHUNK = 256;       // elements per block of tri_row_kernel (one per thread)
 constexpr int PART_W = 2 * NB + 4;   // partials per block: squared norm + 2 dots per slot (+ 3 values of block 0)
 constexpr int PX_DIAG = 2 * NB + 1, PX_LEAD = 2 * NB + 2, PX_WLEAD = 2 * NB + 3;
+
+// One butterfly step of a two-slot reduction over the lane halves (32) or alternating 16-lane rows (16): on return
+// the lanes of the lower half / even rows hold a + (a from the partner lane), the others b + (b from the partner).
+__device__ inline double swap_add32(double a, double b) {
+    const unsigned alo = (unsigned)__double2loint(a), ahi = (unsigned)__double2hiint(a);
+    const unsigned blo = (unsigned)__double2loint(b), bhi = (unsigned)__double2hiint(b);
+    const auto lo = __builtin_amdgcn_permlane32_swap(alo, blo, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap(ahi, bhi, false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
+__device__ inline double swap_add16(double a, double b) {
+    const unsigned alo = (unsigned)__double2loint(a), ahi = (unsigned)__double2hiint(a);
+    const unsigned blo = (unsigned)__double2loint(b), bhi = (unsigned)__double2hiint(b);
+    const auto lo = __builtin_amdgcn_permlane16_swap(alo, blo, false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(ahi, bhi, false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
 
 __device__ inline bool last_block_done(unsigned *counter, unsigned nblocks) {
     __shared__ int is_last;
@@ -161,15 +200,25 @@ __global__ __launch_bounds__(256) void tri_row_kernel(const double *__restrict__
             v[2 * q] = wq[q] * xt;
             v[2 * q + 1] = vq[q] * xt;
         }
+        // lane distances 32 and 16: the gfx950 lane-swap instructions do the exchange and the selection in one
+        // step (checked on the device: permlane32_swap(a, b) returns (a_low, b_low) and (a_high, b_high) over the
+        // two halves of the wave; permlane16_swap the same over alternating rows of 16 lanes)
 #pragma unroll
-        for (int h = NB; h >= 1; h >>= 1) {
+        for (int i = 0; i < NB; ++i) v[i] = swap_add32(v[i], v[i + NB]);
+#pragma unroll
+        for (int i = 0; i < NB / 2; ++i) v[i] = swap_add16(v[i], v[i + NB / 2]);
+#pragma unroll
+        for (int h = NB / 4; h >= 1; h >>= 1) {
             const bool up = (lane & h) != 0;
+            // all exchanges of a level are issued before the first sum waits for one of them (the scheduling
+            // barrier keeps the compiler from pairing every exchange with its own wait)
+            double recv[NB / 4];
 #pragma unroll
-            for (int i = 0; i < h; ++i) {
-                const double keep = up ? v[i + h] : v[i];
-                const double send = up ? v[i] : v[i + h];
-                v[i] = keep + __shfl_xor(send, h, 64);
-            }
+            for (int i = 0; i < h; ++i) recv[i] = __shfl_xor(up ? v[i] : v[i + h], h, 64);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < h; ++i) v[i] = (up ? v[i + h] : v[i]) + recv[i];
+            __builtin_amdgcn_sched_barrier(0);
         }
         red[wave][1 + lane] = v[0];
     }

@@ -53,9 +53,22 @@ __device__ inline PairEval eval_column(float g1, float g2, int k1, int k2, float
     return r;
 }
 
+// Wave-wide reductions without a trip through LDS: the halves of the wave and the 16-lane rows are folded with the
+// gfx950 lane-swap instructions (permlane32_swap(x, x) hands every lane its own half's value and the other
+// half's), the rows with DPP rotations by 8, 4, 2, 1.  The result is left in every lane; the order is fixed.
+template <int N>
+__device__ inline unsigned row_ror(unsigned x) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xF, 0xF, true);
+}
 __device__ inline float wave_sum_f(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    v += __uint_as_float(row_ror<8>(__float_as_uint(v)));
+    v += __uint_as_float(row_ror<4>(__float_as_uint(v)));
+    v += __uint_as_float(row_ror<2>(__float_as_uint(v)));
+    v += __uint_as_float(row_ror<1>(__float_as_uint(v)));
     return v;
 }
 
@@ -107,6 +120,28 @@ __device__ inline void better(float &t, int &i, float ot, int oi) {
 }
 
 constexpr int LS_FAST_PAIRS = 64;      // candidate pairs per batch up to which the winner's data is prefetched
+
+// the best (total, slot) of the wave, in every lane (same folding as wave_sum_f; `better` is commutative)
+__device__ inline void wave_best(float &t, int &i) {
+    {
+        const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+        const auto b = __builtin_amdgcn_permlane32_swap((unsigned)i, (unsigned)i, false, false);
+        t = __uint_as_float(a[0]);
+        i = (int)b[0];
+        better(t, i, __uint_as_float(a[1]), (int)b[1]);
+    }
+    {
+        const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+        const auto b = __builtin_amdgcn_permlane16_swap((unsigned)i, (unsigned)i, false, false);
+        t = __uint_as_float(a[0]);
+        i = (int)b[0];
+        better(t, i, __uint_as_float(a[1]), (int)b[1]);
+    }
+    better(t, i, __uint_as_float(row_ror<8>(__float_as_uint(t))), (int)row_ror<8>((unsigned)i));
+    better(t, i, __uint_as_float(row_ror<4>(__float_as_uint(t))), (int)row_ror<4>((unsigned)i));
+    better(t, i, __uint_as_float(row_ror<2>(__float_as_uint(t))), (int)row_ror<2>((unsigned)i));
+    better(t, i, __uint_as_float(row_ror<1>(__float_as_uint(t))), (int)row_ror<1>((unsigned)i));
+}
 
 // One step of the search, grid (chunks, npairs), block 256, one column per thread:
 //   plan     (when a previous batch exists): every block adds that batch's chunk partials in a fixed order and
@@ -253,8 +288,7 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
     int win = -1;
     float wtot = 0.f;
     if (npairs_prev > 0) {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) better(best, bidx, __shfl_xor(best, o, 64), __shfl_xor(bidx, o, 64));
+        wave_best(best, bidx);
         if (lane == 0) {
             wtot_sh[wv] = best;
             widx_sh[wv] = bidx;
