@@ -132,3 +132,11 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libadmmq.so")
     with pytest.raises(admmq.AdmmqError):
         binding.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
