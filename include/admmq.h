@@ -123,6 +123,32 @@ admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, const float *W
                                   const admmq_schedule *sched, uint8_t *codes, float *scales,
                                   float *zeros, admmq_stats *stats);
 
+/* ---- several matrices on one Hessian (Sec. 3.5: the objective separates over output columns) -- */
+
+/* One matrix of a group that sees the same activations (q/k/v, gate/up): its own width, bit width,
+ * group size and outputs.  All pointers are device memory; layouts as in admmq_quantize_layer. */
+typedef struct {
+    const float *W0;        /* [n][ldw], read only                                             */
+    int64_t p, ldw;         /* ldw >= p                                                        */
+    int32_t bits;           /* [2,8]                                                           */
+    int32_t group_size;     /* 0 = one grid per column, else divides n                         */
+    uint8_t *codes;         /* out [n][p]                                                      */
+    float *scales, *zeros;  /* out [n/g][p]                                                    */
+} admmq_layer;
+
+/* Runs Alg. 1 once for `count` matrices (1..64) that share the Hessian H [n][n]: one damping, one scaling and one
+ * factorisation (lines 1-3), then every W-update (eq. 7) as one pair of products over the concatenated columns
+ * [W0_1 | W0_2 | ...], and projection, dual update and local search matrix by matrix on each one's own grid.
+ * Columns never interact in eqs. 7-11, so every matrix receives exactly what admmq_quantize_layer would give it
+ * alone with the same schedule (the same codes when the local search is off or the seeds agree).
+ * `layers` is a host array; outputs of different matrices must not overlap.  sched->refresh_iter must be -1
+ * (the refresh decision of eq. 12 is taken per matrix, which a shared iteration cannot follow) ->
+ * ADMMQ_ERR_PARAM otherwise.  The scratch needed is admmq_workspace_bytes(n, sum of p, T).
+ * stats: NULL or a host array [count]; objectives, moves and residual arrays are per matrix, the timing and
+ * profile fields describe the whole call and are repeated in every entry (profile is read from stats[0]). */
+admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, int64_t n, const admmq_layer *layers,
+                                   int32_t count, const admmq_schedule *sched, admmq_stats *stats);
+
 /* ---- local search alone (Sec. 3.5, eq. 11) ------------------------------------------------ */
 
 typedef struct {

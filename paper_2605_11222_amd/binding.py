@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = [
     "admmq_accumulate_hessian", "admmq_quantize_layer", "admmq_local_search", "admmq_sample_pair",
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
     "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit", "admmq_grid_init_dual",
-    "admmq_project_dual_format", "admmq_quantize_layer_format",
+    "admmq_project_dual_format", "admmq_quantize_layer_format", "admmq_quantize_layers",
 ]
 
 FORMAT_DUAL_GRID, FORMAT_CODEBOOK = 1, 2
@@ -50,6 +50,11 @@ class _Stats(C.Structure):
 class _Format(C.Structure):
     _fields_ = [("kind", C.c_int32), ("bits", C.c_int32), ("group_size", C.c_int32), ("flags", C.c_void_p),
                 ("codebook", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [("W0", C.c_void_p), ("p", C.c_int64), ("ldw", C.c_int64), ("bits", C.c_int32),
+                ("group_size", C.c_int32), ("codes", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p)]
 
 
 class _LsParams(C.Structure):
@@ -99,6 +104,8 @@ def load_library():
                                               C.POINTER(dbl)]
     lib.admmq_quantize_layer_format.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_Format),
                                                 C.POINTER(_Schedule), vp, vp, C.POINTER(_Stats)]
+    lib.admmq_quantize_layers.argtypes = [vp, vp, i64, C.POINTER(_Layer), i32, C.POINTER(_Schedule),
+                                          C.POINTER(_Stats)]
     lib.admmq_grid_refresh.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, dbl, vp, vp, C.POINTER(i32),
                                        C.POINTER(dbl), C.POINTER(dbl)]
     for name in EXPORTED_SYMBOLS:
@@ -373,6 +380,47 @@ class Context:
                          st.n_ls_apply, st.ms_gemm, st.ms_tridiag, st.ms_project, st.ms_ls_apply, False, 0.0, 0.0,
                          st.j_recon)
         return codes, Wq, (scales, zeros) if kind == FORMAT_DUAL_GRID else None, out
+
+    def quantize_layers(self, H, W0s, bits, group_sizes=0, sched: Schedule | None = None, want_history=False,
+                        profile=False):
+        """Alg. 1 for several matrices that share H, in one call.  bits / group_sizes: one value or one per
+        matrix.  Returns a list of (codes, scales, zeros, stats), one per matrix."""
+        torch = self._torch
+        sched = sched or Schedule()
+        count = len(W0s)
+        n = H.shape[0]
+        bits = list(bits) if isinstance(bits, (list, tuple)) else [bits] * count
+        gs = list(group_sizes) if isinstance(group_sizes, (list, tuple)) else [group_sizes] * count
+        layers = (_Layer * max(count, 1))()
+        stats = (_Stats * max(count, 1))()
+        outs, keep = [], []
+        for i, W0 in enumerate(W0s):
+            p = W0.shape[1]
+            g = gs[i] if gs[i] else n
+            codes = torch.empty((n, p), dtype=torch.uint8, device=W0.device)
+            scales = torch.empty((max(n // g, 1), p), dtype=torch.float32, device=W0.device)
+            zeros = torch.empty((max(n // g, 1), p), dtype=torch.float32, device=W0.device)
+            layers[i] = _Layer(_ptr(W0), p, W0.stride(0), bits[i], gs[i], _ptr(codes), _ptr(scales), _ptr(zeros))
+            outs.append((codes, scales, zeros))
+            if want_history:
+                res = (C.c_float * sched.T)()
+                stats[i].primal_res = C.cast(res, C.POINTER(C.c_float))
+                keep.append(res)
+        stats[0].profile = int(bool(profile))
+        cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
+                       sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
+        _check(self._lib.admmq_quantize_layers(self._h, _ptr(H), n, layers, count, C.byref(cs), stats))
+        result = []
+        for i in range(count):
+            st = stats[i]
+            ls = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
+                            st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
+                            list(keep[i]) if want_history else [], [], st.n_gemm, st.n_tridiag, st.n_project,
+                            st.n_ls_apply, st.ms_gemm, st.ms_tridiag, st.ms_project, st.ms_ls_apply, False, 0.0, 0.0,
+                            st.j_recon)
+            result.append(outs[i] + (ls,))
+        return result
 
     def grid_refresh(self, W, V, d, bits, group_size, rho, scales, zeros):
         """scales/zeros are overwritten when the refit is accepted; returns (accepted, err_old, err_new)."""

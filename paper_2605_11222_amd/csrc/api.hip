@@ -657,7 +657,7 @@ extern "C" admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev_res, 0, 16));
     const float rf = (float)rho;
     ADMMQ_TRY(admmq_k_project_dual(ctx, W, V, n, p, d, inv_d, bits, g, scales, inv_scales, zeros, rf, 1.0f / rf,
-                                   1.0f / (float)rho_next, codes, 0, B_out, res_sq ? dev_res : nullptr, nullptr));
+                                   1.0f / (float)rho_next, codes, 0, B_out, res_sq ? dev_res : nullptr, nullptr, p));
     if (res_sq) ADMMQ_TRY(read_back(ctx, res_sq, dev_res, 8));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;
@@ -914,7 +914,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         ADMMQ_TRY(admmq_k_dual_grid_init(ctx, W0, n, p, ldw, bits, g, pj.flags, pj.scales, pj.zeros));
     if (pj.kind != ADMMQ_FORMAT_CODEBOOK) ADMMQ_TRY(admmq_k_recip(ctx, pj.scales, inv_scales, (int64_t)ng));
     // D^(0) = Ws, V^(0) = 0  =>  B^(0) = Ws
-    ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B));
+    ADMMQ_TRY(admmq_k_scale_rows(ctx, W0, ldw, f.d, n, p, B, p));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, flips, 0, (size_t)T * 8));
@@ -970,7 +970,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         if (uniform)
             ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.scales, inv_scales, pj.zeros,
                                            rf, 1.0f / rf, 1.0f / rf_next, (last || want_flips) ? codes : nullptr,
-                                           want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr));
+                                           want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr, p));
         else
             ADMMQ_TRY(admmq_k_project_format(ctx, pj.kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.flags, pj.scales,
                                              inv_scales, pj.zeros, pj.codebook, rf, 1.0f / rf, 1.0f / rf_next,
@@ -1046,6 +1046,218 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     return ADMMQ_OK;
 }
 
+// Several matrices on one Hessian: one factorisation, the W-update products over all columns at once, everything
+// that depends on a matrix's own grid matrix by matrix.  State W, B, C0, Y: [n][P] with the matrices side by side;
+// V, codes and grids: one contiguous array per matrix.
+admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const admmq_layer *L, int count,
+                                const admmq_schedule *sched, admmq_stats *stats) {
+    const int T = sched->T;
+    const bool want = stats != nullptr;
+    int64_t P = 0;
+    std::vector<int64_t> off((size_t)count), grp((size_t)count);
+    int64_t pmax = 0;
+    for (int i = 0; i < count; ++i) {
+        off[i] = P;
+        grp[i] = L[i].group_size > 0 ? L[i].group_size : n;
+        P += L[i].p;
+        if (L[i].p > pmax) pmax = L[i].p;
+    }
+    const size_t nP = (size_t)n * P;
+    Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
+    t_total.start();
+    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
+    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
+    prof_collect(ctx, prof_ms, prof_cnt);
+    ctx->prof.on = want && stats[0].profile != 0;
+
+    t_phase.start();
+    admmq_arena_reset_transient(ctx);
+    ADMMQ_TRY(admmq_arena_reserve(ctx, 8192));
+    {
+        double *dev = nullptr;
+        ADMMQ_TRY(take(ctx, dev, 2));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, dev, 0, 16));
+        for (int i = 0; i < count; ++i) ADMMQ_TRY(admmq_k_count_nonfinite(ctx, L[i].W0, n, L[i].p, L[i].ldw, dev));
+        double bad = 0.0;
+        ADMMQ_TRY(read_back(ctx, &bad, dev, 8));
+        if (bad > 0.0) return ADMMQ_ERR_NOT_FINITE;
+    }
+    float ms_setup = t_phase.stop();
+
+    // --- Alg. 1 lines 1-3, once ----------------------------------------------------------------
+    t_phase.start();
+    double lambda = 0.0;
+    if (sched->reuse_factor) {
+        const admmq_factor &have = ctx->fac;
+        if (!have.valid || have.n != n || have.H_src != H || have.damp != sched->damp ||
+            have.precondition != sched->precondition)
+            return ADMMQ_ERR_STATE;
+        lambda = have.lambda;
+        admmq_arena_reset_transient(ctx);
+    } else {
+        ADMMQ_TRY(do_factorize(ctx, H, n, sched->damp, sched->precondition, &lambda));
+    }
+    float ms_factor = t_phase.stop();
+    const admmq_factor &f = ctx->fac;
+
+    // --- grids, initial state, schedule -----------------------------------------------------------
+    t_phase.start();
+    LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
+    size_t ng_total = 0;
+    for (int i = 0; i < count; ++i) ng_total += admmq_align_up((size_t)(n / grp[i]) * L[i].p * 4);
+    size_t need = admm_transient_bytes(n, P, T) + ng_total + (size_t)count * (admmq_align_up((size_t)T * 8) + 1024);
+    if (plan.rounds > 0 && n >= 2) {
+        const size_t ls = ls_transient_bytes(n, pmax, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
+        if (ls > need) need = ls;
+    }
+    ADMMQ_TRY(admmq_arena_reserve(ctx, need));
+    float *B = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr;
+    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *jdev = nullptr;
+    std::vector<float *> V((size_t)count), inv_scales((size_t)count);
+    std::vector<double *> res((size_t)count);
+    ADMMQ_TRY(take(ctx, B, nP));
+    ADMMQ_TRY(take(ctx, W, nP));
+    ADMMQ_TRY(take(ctx, C0, nP));
+    ADMMQ_TRY(take(ctx, Y, nP));
+    ADMMQ_TRY(take(ctx, F, nP + (size_t)P));
+    for (int i = 0; i < count; ++i) {
+        ADMMQ_TRY(take(ctx, V[i], (size_t)n * L[i].p));
+        ADMMQ_TRY(take(ctx, inv_scales[i], (size_t)(n / grp[i]) * L[i].p));
+        ADMMQ_TRY(take(ctx, res[i], (size_t)T));
+    }
+    ADMMQ_TRY(take(ctx, rhos, (size_t)T));
+    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, jdev, 4));
+    for (int i = 0; i < count; ++i) {
+        const admmq_layer &l = L[i];
+        ADMMQ_TRY(admmq_k_grid_fit(ctx, l.W0, n, l.p, l.ldw, l.bits, grp[i], sched->symmetric != 0, sched->clip_points,
+                                   sched->clip_shrink, l.scales, l.zeros));
+        ADMMQ_TRY(admmq_k_recip(ctx, l.scales, inv_scales[i], (int64_t)((n / grp[i]) * l.p)));
+        ADMMQ_TRY(admmq_k_scale_rows(ctx, l.W0, l.ldw, f.d, n, l.p, B + off[i], P));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, V[i], 0, (size_t)n * l.p * 4));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, res[i], 0, (size_t)T * 8));
+    }
+    std::vector<double> hrho((size_t)T + 1);
+    {
+        double r = sched->rho0;
+        for (int t = 0; t <= T; ++t) {
+            hrho[t] = r;
+            r *= sched->gamma;
+        }
+    }
+    ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
+    ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
+    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
+    gemm_tn_args g0 = {};
+    g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = P; g0.M = n; g0.N = P; g0.K = n;
+    g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = P; g0.split_k = 1;
+    ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
+    if (want) {
+        // round-to-nearest on the initial grid as the baseline objective; W, Y and F are still free
+        for (int i = 0; i < count; ++i) {
+            const admmq_layer &l = L[i];
+            ADMMQ_TRY(admmq_k_quant_error(ctx, l.W0, l.ldw, (uint8_t *)F, n, l.p, grp[i], l.scales, l.zeros, l.bits, 2, W));
+            ADMMQ_TRY(objective_core(ctx, H, lambda, n, l.p, W, Y, jdev));
+            ADMMQ_TRY(read_back(ctx, &stats[i].j_damp_rtn, jdev, 8));
+        }
+    }
+    ms_setup += t_phase.stop();
+
+    // --- ADMM loop (Alg. 1 lines 5-9) -------------------------------------------------------------
+    t_phase.start();
+    float *Bcur = B, *Wcur = W;
+    for (int t = 0; t < T; ++t) {
+        const float rf = (float)hrho[t], rf_next = (float)hrho[t + 1];
+        if (t == 0)
+            ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, nP * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        else
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, P, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
+        const bool last = t == T - 1;
+        const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
+        for (int i = 0; i < count; ++i) {
+            const admmq_layer &l = L[i];
+            ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur + off[i], V[i], n, l.p, f.d, f.inv_d, l.bits, grp[i], l.scales,
+                                           inv_scales[i], l.zeros, rf, 1.0f / rf, 1.0f / rf_next,
+                                           last ? l.codes : nullptr, 0, Wcur + off[i], res[i] + t, nullptr, P));
+        }
+        admmq_prof_end(ctx, sp);
+        float *tmpp = Bcur;
+        Bcur = Wcur;
+        Wcur = tmpp;
+    }
+    float ms_admm = t_phase.stop();
+
+    if (want) {
+        for (int i = 0; i < count; ++i) {
+            const admmq_layer &l = L[i];
+            admmq_stats &st = stats[i];
+            st.iters_done = T;
+            st.lambda = lambda;
+            st.refresh_accepted = 0;
+            st.refresh_err_old = st.refresh_err_new = 0.0;
+            if (st.primal_res) {
+                std::vector<double> h((size_t)T);
+                ADMMQ_TRY(read_back(ctx, h.data(), res[i], (size_t)T * 8));
+                for (int t = 0; t < T; ++t) st.primal_res[t] = (float)sqrt(h[t]);
+            }
+            if (st.code_flips)
+                for (int t = 0; t < T; ++t) st.code_flips[t] = -1;       // not counted on this path
+            ADMMQ_TRY(admmq_k_quant_error(ctx, l.W0, l.ldw, l.codes, n, l.p, grp[i], l.scales, l.zeros, l.bits, 0, W));
+            ADMMQ_TRY(objectives_core(ctx, H, lambda, n, l.p, W, Y, jdev, &st.j_damp_admm, &st.j_recon));
+            st.j_damp = st.j_damp_admm;
+            st.ls_moves = 0;
+        }
+    }
+
+    // --- local search (Alg. 1 line 11), matrix by matrix ------------------------------------------
+    t_phase.start();
+    float ms_ls = 0.f;
+    if (plan.rounds > 0 && n >= 2) {
+        for (int i = 0; i < count; ++i) {
+            const admmq_layer &l = L[i];
+            admmq_arena_reset_transient(ctx);
+            int32_t moves = 0;
+            double drop = 0.0;
+            ADMMQ_TRY(local_search_core(ctx, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i], l.scales, l.zeros, l.codes,
+                                        plan, sched->seed, nullptr, &moves, &drop));
+            if (want) stats[i].ls_moves = moves;
+        }
+        ms_ls = t_phase.stop();
+        if (want) {
+            for (int i = 0; i < count; ++i) {
+                const admmq_layer &l = L[i];
+                admmq_arena_reset_transient(ctx);
+                float *E = nullptr, *tmp = nullptr;
+                double *jd = nullptr;
+                ADMMQ_TRY(take(ctx, E, (size_t)n * l.p));
+                ADMMQ_TRY(take(ctx, tmp, (size_t)n * l.p));
+                ADMMQ_TRY(take(ctx, jd, 2));
+                ADMMQ_TRY(admmq_k_quant_error(ctx, l.W0, l.ldw, l.codes, n, l.p, grp[i], l.scales, l.zeros, l.bits, 0, E));
+                ADMMQ_TRY(objectives_core(ctx, H, lambda, n, l.p, E, tmp, jd, &stats[i].j_damp, &stats[i].j_recon));
+            }
+        }
+    }
+    prof_collect(ctx, prof_ms, prof_cnt);
+    if (want) {
+        const float ms_all = t_total.stop();
+        for (int i = 0; i < count; ++i) {
+            admmq_stats &st = stats[i];
+            st.ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       st.n_gemm = prof_cnt[ADMMQ_TAG_GEMM];
+            st.ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; st.n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
+            st.ms_project = prof_ms[ADMMQ_TAG_PROJECT]; st.n_project = prof_cnt[ADMMQ_TAG_PROJECT];
+            st.ms_ls_apply = prof_ms[ADMMQ_TAG_LS_APPLY]; st.n_ls_apply = prof_cnt[ADMMQ_TAG_LS_APPLY];
+            st.ms_setup = ms_setup;
+            st.ms_factor = ms_factor;
+            st.ms_admm = ms_admm;
+            st.ms_local_search = ms_ls;
+            st.ms_total = ms_all;
+        }
+    }
+    admmq_arena_reset_transient(ctx);
+    return ADMMQ_OK;
+}
+
 bool schedule_ok(const admmq_schedule *s) {
     return s->T >= 1 && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
            isfinite(s->gamma) && isfinite(s->damp) && s->ls_rounds >= 0 && s->ls_batches >= 0 && s->ls_pairs >= 0 &&
@@ -1066,6 +1278,24 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     ADMMQ_HIP(hipSetDevice(ctx->device));
     Projection pj = {0, bits, group_size > 0 ? group_size : n, scales, zeros, nullptr, nullptr, nullptr};
     return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats);
+}
+
+extern "C" admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, int64_t n, const admmq_layer *layers,
+                                              int32_t count, const admmq_schedule *sched, admmq_stats *stats) {
+    if (!ctx || !sched || !layers || !H) return ADMMQ_ERR_NULL;
+    if (count < 1 || count > 64) return ADMMQ_ERR_SHAPE;
+    int64_t P = 0;
+    for (int i = 0; i < count; ++i) {
+        const admmq_layer &l = layers[i];
+        if (!l.codes || !l.scales || !l.zeros) return ADMMQ_ERR_NULL;
+        ADMMQ_TRY(check_layer_args(H, l.W0, n, l.p, l.ldw, l.bits, l.group_size));
+        P += l.p;
+    }
+    if (P > (1 << 24)) return ADMMQ_ERR_SHAPE;
+    if (!schedule_ok(sched) || sched->refresh_iter != -1) return ADMMQ_ERR_PARAM;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    return quantize_many_core(ctx, H, n, layers, count, sched, stats);
 }
 
 extern "C" admmq_status admmq_grid_init_dual(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,

@@ -106,7 +106,7 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   const float *inv_d, int bits, int64_t g, const float *scales,
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
-                                  double *dev_res_sq, unsigned long long *dev_flips);
+                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw);
 // grid refresh (App. B): refit by min/max of the projection target; both sides of eq. 12 as per-block partials
 admmq_status admmq_k_refit_grid(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
                                 const float *inv_d, float inv_rho, int bits, int64_t g, float *scales, float *zeros);
@@ -118,7 +118,7 @@ admmq_status admmq_k_refresh_error(admmq_ctx *ctx, const float *W, const float *
 // inv[i] = 1/x[i] in fp32 with IEEE division, 0 where x[i] == 0
 admmq_status admmq_k_recip(admmq_ctx *ctx, const float *x, float *inv, int64_t n);
 admmq_status admmq_k_scale_rows(admmq_ctx *ctx, const float *W0, int64_t ldw, const float *d, int64_t n, int64_t p,
-                                float *out);
+                                float *out, int64_t ldo);
 // B = D - V * inv_rho
 admmq_status admmq_k_form_b(admmq_ctx *ctx, const float *D, const float *V, float inv_rho, int64_t count,
                             float *B);

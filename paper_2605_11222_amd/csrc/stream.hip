@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
     const float *__restrict__ inv_d, float levels, long g, const float *__restrict__ scales,
     const float *__restrict__ inv_scales, const float *__restrict__ zeros, float rho, float inv_rho,
     float inv_rho_next, uint8_t *__restrict__ codes, float *B, double *__restrict__ res_sq,
-    unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal) {
+    unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal, long ldw) {
     __shared__ double sh[4];
     const long c0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
     const long row0 = (long)blockIdx.y * rows_per_block;
@@ -170,15 +170,15 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const long i = row0 + r4 + rr;
-                const long off = i * p + c0;
+                const long off = i * p + c0, offw = i * ldw + c0;
                 if (i < n) {
                     if (VEC) {
                         floatx4 tw, tv;
                         if (nontemporal) {
-                            tw = __builtin_nontemporal_load((const floatx4 *)(W + off));
+                            tw = __builtin_nontemporal_load((const floatx4 *)(W + offw));
                             tv = __builtin_nontemporal_load((const floatx4 *)(V + off));
                         } else {
-                            tw = *(const floatx4 *)(W + off);
+                            tw = *(const floatx4 *)(W + offw);
                             tv = *(const floatx4 *)(V + off);
                         }
                         w[rr][0] = tw.x; w[rr][1] = tw.y; w[rr][2] = tw.z; w[rr][3] = tw.w;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                     } else {
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            w[rr][c] = c < nc ? W[off + c] : 0.f;
+                            w[rr][c] = c < nc ? W[offw + c] : 0.f;
                             v[rr][c] = c < nc ? V[off + c] : 0.f;
                         }
                     }
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
             for (int rr = 0; rr < 4; ++rr) {
                 const long i = row0 + r4 + rr;
                 if (i >= n) break;
-                const long off = i * p + c0;
+                const long off = i * p + c0, offw = i * ldw + c0;
                 const long gi = i / g;
                 if (gi != grp) {
                     grp = gi;
@@ -236,10 +236,10 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                     floatx4 ob = {bn[0], bn[1], bn[2], bn[3]};
                     if (nontemporal) {
                         __builtin_nontemporal_store(ov, (floatx4 *)(V + off));
-                        __builtin_nontemporal_store(ob, (floatx4 *)(B + off));
+                        __builtin_nontemporal_store(ob, (floatx4 *)(B + offw));
                     } else {
                         *(floatx4 *)(V + off) = ov;
-                        *(floatx4 *)(B + off) = ob;
+                        *(floatx4 *)(B + offw) = ob;
                     }
                     if (CODES) {
                         uint32_t packed = (uint32_t)kq[0] | ((uint32_t)kq[1] << 8) | ((uint32_t)kq[2] << 16) |
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                     for (int c = 0; c < 4; ++c) {
                         if (c < nc) {
                             V[off + c] = vn[c];
-                            B[off + c] = bn[c];
+                            B[offw + c] = bn[c];
                             if (CODES) {
                                 if (FLIPS) nflip += codes[off + c] != kq[c];
                                 codes[off + c] = kq[c];
@@ -354,11 +354,11 @@ __global__ __launch_bounds__(256) void refresh_error_kernel(const float *__restr
 
 // ---- helpers ----------------------------------------------------------------------------------
 __global__ void scale_rows_kernel(const float *__restrict__ W0, long ldw, const float *__restrict__ d, long n,
-                                  long p, float *__restrict__ out) {
+                                  long p, float *__restrict__ out, long ldo) {
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx < n * p) {
         long i = idx / p, j = idx - i * p;
-        out[idx] = __fmul_rn(d[i], W0[i * ldw + j]);
+        out[i * ldo + j] = __fmul_rn(d[i], W0[i * ldw + j]);
     }
 }
 
@@ -489,7 +489,8 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   const float *inv_d, int bits, int64_t g, const float *scales,
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
-                                  double *dev_res_sq, unsigned long long *dev_flips) {
+                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw) {
+    // ldw: leading dimension of W and B_out (several matrices side by side); V, codes and the grid are [.][p]
     const long p4 = (p + 3) / 4;
     static int rows_cfg = -1, nt_cfg = 0;
     if (rows_cfg < 0) {
@@ -501,13 +502,13 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
     }
     const int rows_per_block = rows_cfg;
     dim3 block(256), grid((unsigned)((p4 + 255) / 256), (unsigned)((n + rows_per_block - 1) / rows_per_block));
-    const bool vec = (p % 4 == 0) && (((uintptr_t)W | (uintptr_t)V | (uintptr_t)B_out) % 16 == 0) &&
+    const bool vec = (p % 4 == 0) && (ldw % 4 == 0) && (((uintptr_t)W | (uintptr_t)V | (uintptr_t)B_out) % 16 == 0) &&
                      (codes == nullptr || (uintptr_t)codes % 4 == 0);
     const float levels = (float)((1 << bits) - 1);
 #define ADMMQ_PD(C, F, VV)                                                                                   \
     hipLaunchKernelGGL((project_dual_kernel<C, F, VV>), grid, block, 0, ctx->stream, W, V, (long)n, (long)p, d, \
                        inv_d, levels, (long)g, scales, inv_scales, zeros, rho, inv_rho, inv_rho_next, codes,  \
-                       B_out, dev_res_sq, dev_flips, rows_per_block, nt_cfg)
+                       B_out, dev_res_sq, dev_flips, rows_per_block, nt_cfg, (long)ldw)
     if (codes && count_flips) { if (vec) ADMMQ_PD(true, true, true); else ADMMQ_PD(true, true, false); }
     else if (codes)           { if (vec) ADMMQ_PD(true, false, true); else ADMMQ_PD(true, false, false); }
     else                      { if (vec) ADMMQ_PD(false, false, true); else ADMMQ_PD(false, false, false); }
@@ -517,9 +518,9 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
 }
 
 admmq_status admmq_k_scale_rows(admmq_ctx *ctx, const float *W0, int64_t ldw, const float *d, int64_t n, int64_t p,
-                                float *out) {
+                                float *out, int64_t ldo) {
     hipLaunchKernelGGL(scale_rows_kernel, dim3(blocks_for(n * p, 256)), dim3(256), 0, ctx->stream, W0, (long)ldw, d,
-                       (long)n, (long)p, out);
+                       (long)n, (long)p, out, (long)ldo);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

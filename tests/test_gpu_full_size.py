@@ -183,3 +183,54 @@ def test_format_projection_at_4096x4096_against_the_mirror(ctx, kind):
         np.testing.assert_array_equal(B[rows], Bn)
         ss_total += ss
     assert rs > ss_total > 0
+
+
+def test_cfg2_and_cfg3_in_one_call(ctx, hessian_16k):
+    """The two 4096-row workloads see the same activations: one call factorises once and runs every W-update as one
+    pair of products over 4096 + 1024 columns.  Each matrix must come out as from a call of its own (same grid,
+    objective equal to four digits, codes equal except near-midpoint roundings of the products)."""
+    import time
+    import paper_2605_11222_amd as admmq
+    c2, c3 = si.CONFIGS["cfg2"], si.CONFIGS["cfg3"]
+    H = to_dev(hessian_16k)
+    Wa, Wb = to_dev(si.layer_weights(c2)), to_dev(si.layer_weights(c3))
+    s = admmq.Schedule(T=c2.T, ls_rounds=0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a = ctx.quantize_layer(H, Wa, c2.bits, c2.group_size, s)
+    b = ctx.quantize_layer(H, Wb, c3.bits, c3.group_size, s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    both = ctx.quantize_layers(H, [Wa, Wb], [c2.bits, c3.bits], [c2.group_size, c3.group_size], s)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    print(f"two calls {t1 - t0:.3f} s (factorise {a[3].ms_factor + b[3].ms_factor:.0f} ms), one call {t2 - t1:.3f} s "
+          f"(factorise {both[0][3].ms_factor:.0f} ms, ADMM {both[0][3].ms_admm:.0f} ms)")
+    for (codes, scales, zeros, st), alone in zip(both, (a, b)):
+        assert torch.equal(scales, alone[1]) and torch.equal(zeros, alone[2])
+        mismatch = float((codes != alone[0]).float().mean())
+        print(f"p={codes.shape[1]}: codes differing from its own call {mismatch:.2e}; "
+              f"objective {st.j_damp:.8g} / {alone[3].j_damp:.8g}")
+        assert mismatch < 2e-3
+        assert st.j_damp == pytest.approx(alone[3].j_damp, rel=1e-3)
+        assert st.j_damp_rtn == pytest.approx(alone[3].j_damp_rtn, rel=1e-6)
+        assert st.j_damp <= st.j_damp_rtn
+    assert t2 - t1 < t1 - t0
+    # four narrow matrices (1024 columns each fill the chip only with the smaller, slower tile): together they run
+    # the products at the 4096-column rate
+    Wn = [Wb] + [to_dev(np.ascontiguousarray(si.layer_weights(c2)[:, 1024 * i:1024 * (i + 1)])) for i in range(3)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sep = [ctx.quantize_layer(H, W, c3.bits, c3.group_size, admmq.Schedule(T=c2.T, ls_rounds=0, reuse_factor=True))
+           for W in Wn]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tog = ctx.quantize_layers(H, Wn, c3.bits, c3.group_size, admmq.Schedule(T=c2.T, ls_rounds=0, reuse_factor=True))
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    print(f"4 x 1024 columns on one factorisation: four calls {t1 - t0:.3f} s (ADMM {sum(x[3].ms_admm for x in sep):.0f} ms), "
+          f"one call {t2 - t1:.3f} s (ADMM {tog[0][3].ms_admm:.0f} ms)")
+    for x, y in zip(sep, tog):
+        assert torch.equal(x[1], y[1]) and float((x[0] != y[0]).float().mean()) < 2e-3
+        assert y[3].j_damp == pytest.approx(x[3].j_damp, rel=1e-3)
+    assert tog[0][3].ms_admm < 0.9 * sum(x[3].ms_admm for x in sep)

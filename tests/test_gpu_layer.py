@@ -277,6 +277,13 @@ def test_device_side_input_checks_leave_outputs_untouched(ctx):
     b = ctx.quantize_layer_format(to_dev(H), to_dev(W0), admmq.FORMAT_DUAL_GRID, 3, group_size=4, flags=flags,
                                   sched=admmq.Schedule(T=5, ls_rounds=0))[0]
     assert torch.equal(a, b)
+    # several matrices in one call: the workspace of one layer with the summed width
+    wide = torch.empty(admmq.workspace_bytes(64, 32, 5), dtype=torch.uint8, device="cuda")
+    c2.set_workspace(wide)
+    s5 = admmq.Schedule(T=5, ls_rounds=1)
+    pair = c2.quantize_layers(to_dev(H), [to_dev(W0), to_dev(W0)], [4, 3], [0, 8], s5)
+    assert torch.equal(pair[0][0], ctx.quantize_layer(to_dev(H), to_dev(W0), 4, 0, s5)[0])
+    assert torch.equal(pair[1][0], ctx.quantize_layer(to_dev(H), to_dev(W0), 3, 8, s5)[0])
     c2.close()
 
 
@@ -357,3 +364,52 @@ def test_shared_hessian_reuses_the_factorisation(ctx):
     with pytest.raises(admmq.AdmmqError) as e:
         ctx.quantize_layer(other, to_dev(W1), 4, 0, s2)
     assert e.value.code == 7
+
+
+def test_batched_layers_on_a_shared_hessian(ctx):
+    """Three matrices of different width, bit width and group size in one call: the W-update products run over the
+    concatenated columns (offsets 0, 64, 114: the last one off the 16-byte vector path), everything else per
+    matrix.  Columns never interact (Sec. 3.5), so each matrix must get the grid of a call of its own, an
+    objective within the tolerance of the oracle's run on that matrix alone, and codes that differ from its own
+    call only where a product's rounding moved a near-midpoint value."""
+    import paper_2605_11222_amd as admmq
+    n, T = 192, 60
+    X, Wa = correlated_problem(n, 64, 600, 60, outliers=2)
+    _, Wb = correlated_problem(n, 50, 600, 61)
+    _, Wc = correlated_problem(n, 37, 600, 62)
+    Ws, bits, gs = [Wa, Wb, Wc], [3, 4, 2], [64, 0, 32]
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    H = to_dev(H32)
+    s = admmq.Schedule(T=T, ls_rounds=1, ls_pairs=16, seed=5)
+    alone = [ctx.quantize_layer(H, to_dev(W), b, g, s) for W, b, g in zip(Ws, bits, gs)]
+    both = ctx.quantize_layers(H, [to_dev(W) for W in Ws], bits, gs, s, want_history=True)
+    torch.cuda.synchronize()
+    assert len(both) == 3
+    for i, (W, b, g) in enumerate(zip(Ws, bits, gs)):
+        codes, scales, zeros, st = both[i]
+        a_codes, a_scales, a_zeros, a_st = alone[i]
+        assert torch.equal(scales, a_scales) and torch.equal(zeros, a_zeros)
+        k = codes.cpu().numpy()
+        assert k.max() <= 2 ** b - 1
+        mismatch = float(np.mean(k != a_codes.cpu().numpy()))
+        j64 = f64_objective(H32, st.lam, W, k, scales.cpu().numpy(), zeros.cpu().numpy(), g)
+        assert st.j_damp == pytest.approx(j64, rel=1e-4)
+        assert st.j_damp_rtn == pytest.approx(a_st.j_damp_rtn, rel=1e-6)
+        assert st.j_damp == pytest.approx(a_st.j_damp, rel=2e-3)
+        assert st.j_damp <= st.j_damp_admm * (1 + 1e-6) <= st.j_damp_rtn
+        ref = orc.quantize_layer(H32.astype(np.float64), W.astype(np.float64), b, g, T=T, ls_rounds=1, ls_pairs=16,
+                                 seed=5)
+        assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+        assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+        assert st.primal_res[0] == pytest.approx(ref.admm.primal[0], rel=1e-4)
+        assert st.iters_done == T and st.ms_factor == both[0][3].ms_factor
+        print(f"matrix {i}: p={W.shape[1]} b={b} g={g}: final {st.j_damp:.6g} alone {a_st.j_damp:.6g} oracle "
+              f"{ref.j_damp:.6g}; codes differing from its own call {mismatch:.2e}")
+        assert mismatch < 5e-3
+    # one matrix through the batched entry point is the single-layer call
+    one = ctx.quantize_layers(H, [to_dev(Wa)], 3, 64, s)[0]
+    assert torch.equal(one[0], alone[0][0])
+    # a refresh is a per-matrix decision: refused here
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layers(H, [to_dev(Wa), to_dev(Wb)], 3, 0, admmq.Schedule(T=20, ls_rounds=0, refresh_iter=5))
+    assert e.value.code == 3

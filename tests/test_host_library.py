@@ -127,6 +127,32 @@ def test_format_argument_validation_without_a_gpu(lib):
     lib.admmq_destroy(h)
 
 
+def test_batched_layers_argument_validation_without_a_gpu(lib):
+    h = _ctx(lib)
+    one = 256
+    sched = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0)
+    Lr = binding._Layer
+
+    def q(layers, count=None, sched=sched, n=8, H=one):
+        arr = (Lr * max(len(layers), 1))(*layers)
+        return lib.admmq_quantize_layers(h, C.c_void_p(H) if H else None, n, arr,
+                                         len(layers) if count is None else count, C.byref(sched), None)
+    good = Lr(one, 4, 4, 3, 0, one, one, one)
+    wide = Lr(one, 6, 8, 4, 4, one, one, one)
+    assert q([good]) == 8 and q([good, wide]) == 8                        # valid: stops at the missing device
+    assert q([good], count=0) == 2 and q([good], count=65) == 2
+    assert q([good], H=0) == 1
+    assert q([good, Lr(None, 4, 4, 3, 0, one, one, one)]) == 1            # every matrix needs its weights
+    assert q([good, Lr(one, 4, 4, 3, 0, None, one, one)]) == 1            # ... and its outputs
+    assert q([good, Lr(one, 4, 3, 3, 0, one, one, one)]) == 2             # ldw < p
+    assert q([good, Lr(one, 4, 4, 3, 3, one, one, one)]) == 2             # group does not divide n
+    assert q([good, Lr(one, 4, 4, 9, 0, one, one, one)]) == 3
+    with_refresh = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 5, 0, 0, 0.8, 0, 0)
+    assert q([good, wide], sched=with_refresh) == 3                       # the refresh is a per-matrix decision
+    assert lib.admmq_quantize_layers(h, C.c_void_p(one), 8, None, 1, C.byref(sched), None) == 1
+    lib.admmq_destroy(h)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libadmmq.so")
