@@ -144,8 +144,12 @@ typedef struct {
  * `layers` is a host array; outputs of different matrices must not overlap.  sched->refresh_iter must be -1
  * (the refresh decision of eq. 12 is taken per matrix, which a shared iteration cannot follow) ->
  * ADMMQ_ERR_PARAM otherwise.  The scratch needed is admmq_workspace_bytes(n, sum of p, T).
+ * The local searches of up to four matrices run side by side on streams of the library's own (default priority,
+ * created on first use, ordered after the context's stream) driven by short-lived host threads; the call returns
+ * after all of them have finished.
  * stats: NULL or a host array [count]; objectives, moves and residual arrays are per matrix, the timing and
- * profile fields describe the whole call and are repeated in every entry (profile is read from stats[0]). */
+ * profile fields describe the whole call and are repeated in every entry (profile is read from stats[0];
+ * ms_ls_apply / n_ls_apply are collected only when count is 1; code_flips, when given, is filled with -1). */
 admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, int64_t n, const admmq_layer *layers,
                                    int32_t count, const admmq_schedule *sched, admmq_stats *stats);
 

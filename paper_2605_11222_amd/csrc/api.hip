@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <thread>
 #include <vector>
 
 #include "common.h"
@@ -467,6 +468,12 @@ extern "C" void admmq_destroy(admmq_ctx *ctx) {
         int cnt[ADMMQ_TAGS];
         prof_collect(ctx, ms, cnt);
         (void)hipStreamSynchronize(ctx->stream);
+        for (hipStream_t st : ctx->side)
+            if (st) {
+                (void)hipStreamSynchronize(st);
+                (void)hipStreamDestroy(st);
+            }
+        if (ctx->side_ready) (void)hipEventDestroy(ctx->side_ready);
         if (ctx->arena && ctx->arena_owned) (void)hipFree(ctx->arena);
     }
     free(ctx->prof.spans);
@@ -1211,22 +1218,90 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     }
 
     // --- local search (Alg. 1 line 11), matrix by matrix ------------------------------------------
+    // The search is a chain of short dependent launches that leaves most of the chip idle, and the matrices'
+    // searches are independent of each other: up to four run side by side, each on a stream and a host thread of
+    // its own with its own slice of the scratch arena (the result of each is what it would be alone).
     t_phase.start();
     float ms_ls = 0.f;
     if (plan.rounds > 0 && n >= 2) {
-        for (int i = 0; i < count; ++i) {
-            const admmq_layer &l = L[i];
-            admmq_arena_reset_transient(ctx);
-            int32_t moves = 0;
-            double drop = 0.0;
-            ADMMQ_TRY(local_search_core(ctx, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i], l.scales, l.zeros, l.codes,
-                                        plan, sched->seed, nullptr, &moves, &drop));
-            if (want) stats[i].ls_moves = moves;
+        admmq_arena_reset_transient(ctx);
+        std::vector<int32_t> moves((size_t)count, 0);
+        const int64_t total_pairs = (int64_t)plan.rounds * plan.batches * plan.pairs;
+        int workers = count < 4 ? count : 4;
+        std::vector<size_t> slice((size_t)workers, 0), start((size_t)workers, 0);
+        size_t all = 0;
+        if (workers > 1) {
+            for (int i = 0; i < count; ++i) {
+                const size_t b = admmq_align_up(ls_transient_bytes(n, L[i].p, total_pairs, plan.pairs));
+                if (b > slice[i % workers]) slice[i % workers] = b;
+            }
+            for (int w = 0; w < workers; ++w) {
+                start[w] = all;
+                all += slice[w];
+            }
+            if (admmq_arena_reserve(ctx, all) != ADMMQ_OK) workers = 1;     // a caller's arena too small for that
+        }
+        if (workers > 1) {
+            if (!ctx->side_ready) ADMMQ_HIP(hipEventCreateWithFlags(&ctx->side_ready, hipEventDisableTiming));
+            for (int w = 1; w < workers; ++w)
+                if (!ctx->side[w - 1]) ADMMQ_HIP(hipStreamCreateWithFlags(&ctx->side[w - 1], hipStreamNonBlocking));
+            ADMMQ_HIP(hipEventRecord(ctx->side_ready, ctx->stream));          // the codes of the ADMM loop
+            for (int w = 1; w < workers; ++w) ADMMQ_HIP(hipStreamWaitEvent(ctx->side[w - 1], ctx->side_ready, 0));
+            char *base = ctx->arena + ctx->persist_top;
+            std::vector<admmq_status> result((size_t)workers, ADMMQ_OK);
+            auto run = [&](int w) {
+                if (hipSetDevice(ctx->device) != hipSuccess) {
+                    result[w] = ADMMQ_ERR_DEVICE;
+                    return;
+                }
+                admmq_ctx child;
+                child.device = ctx->device;
+                child.stream = w == 0 ? ctx->stream : ctx->side[w - 1];
+                child.arena = base + start[w];
+                child.arena_bytes = slice[w];
+                child.arena_owned = false;
+                for (int i = w; i < count; i += workers) {
+                    const admmq_layer &l = L[i];
+                    child.top = child.persist_top = 0;
+                    double drop = 0.0;
+                    const admmq_status s = local_search_core(&child, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i],
+                                                             l.scales, l.zeros, l.codes, plan, sched->seed, nullptr,
+                                                             &moves[i], &drop);
+                    if (s != ADMMQ_OK) {
+                        result[w] = s;
+                        break;
+                    }
+                }
+                // every search ends with a read-back on its stream; after a failure, drain what was queued
+                if (result[w] != ADMMQ_OK) (void)hipStreamSynchronize(child.stream);
+            };
+            std::vector<std::thread> helpers;
+            std::vector<int> inline_share;
+            for (int w = 1; w < workers; ++w) {
+                try {
+                    helpers.emplace_back(run, w);
+                } catch (...) {
+                    inline_share.push_back(w);          // no thread to be had: this share runs here, afterwards
+                }
+            }
+            run(0);
+            for (int w : inline_share) run(w);
+            for (auto &h : helpers) h.join();
+            for (int w = 0; w < workers; ++w) ADMMQ_TRY(result[w]);
+        } else {
+            for (int i = 0; i < count; ++i) {
+                const admmq_layer &l = L[i];
+                admmq_arena_reset_transient(ctx);
+                double drop = 0.0;
+                ADMMQ_TRY(local_search_core(ctx, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i], l.scales, l.zeros,
+                                            l.codes, plan, sched->seed, nullptr, &moves[i], &drop));
+            }
         }
         ms_ls = t_phase.stop();
         if (want) {
             for (int i = 0; i < count; ++i) {
                 const admmq_layer &l = L[i];
+                stats[i].ls_moves = moves[i];
                 admmq_arena_reset_transient(ctx);
                 float *E = nullptr, *tmp = nullptr;
                 double *jd = nullptr;

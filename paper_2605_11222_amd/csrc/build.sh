@@ -11,5 +11,5 @@ for f in gemm_tn stream factor householder local_search formats api; do
   pids+=($!)
 done
 for p in "${pids[@]}"; do wait $p; done
-/opt/rocm/bin/hipcc --offload-arch=gfx950 -shared -fPIC -o "$out" "$here"/_build/{gemm_tn,stream,factor,householder,local_search,formats,api}.o
+/opt/rocm/bin/hipcc --offload-arch=gfx950 -shared -fPIC -pthread -o "$out" "$here"/_build/{gemm_tn,stream,factor,householder,local_search,formats,api}.o
 echo "built $out"

@@ -57,6 +57,9 @@ struct admmq_ctx {
     admmq_factor fac;
     // small pinned host buffer for scalar read-backs
     double *host_scalars = nullptr;   // 64 doubles
+    // streams (default priority) on which independent local searches of one batched call run side by side
+    hipStream_t side[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t side_ready = nullptr;
 };
 
 // Returns a span index (or -1 when profiling is off); call admmq_prof_end with it after the launch.

@@ -234,3 +234,14 @@ def test_cfg2_and_cfg3_in_one_call(ctx, hessian_16k):
         assert torch.equal(x[1], y[1]) and float((x[0] != y[0]).float().mean()) < 2e-3
         assert y[3].j_damp == pytest.approx(x[3].j_damp, rel=1e-3)
     assert tog[0][3].ms_admm < 0.9 * sum(x[3].ms_admm for x in sep)
+    # with the local search: the three searches of one call run side by side and move what they move alone
+    s_ls = admmq.Schedule(T=20, ls_rounds=2, seed=7, reuse_factor=True)
+    sep = [ctx.quantize_layer(H, W, c3.bits, c3.group_size, s_ls) for W in Wn[:3]]
+    tog = ctx.quantize_layers(H, Wn[:3], c3.bits, c3.group_size, s_ls)
+    torch.cuda.synchronize()
+    print(f"local search of 3 x 1024 columns: one after the other {sum(x[3].ms_local_search for x in sep):.0f} ms, "
+          f"side by side {tog[0][3].ms_local_search:.0f} ms; moves {[x[3].ls_moves for x in tog]}")
+    for x, y in zip(sep, tog):
+        assert torch.equal(x[0], y[0]) and x[3].ls_moves == y[3].ls_moves > 0
+        assert y[3].j_damp == pytest.approx(x[3].j_damp, rel=1e-6) and y[3].j_damp < y[3].j_damp_admm
+    assert tog[0][3].ms_local_search < 0.7 * sum(x[3].ms_local_search for x in sep)
