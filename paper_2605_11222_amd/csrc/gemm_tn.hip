@@ -429,13 +429,13 @@ __global__ void sym_reduce_kernel(float *H, long n, const float *P, int slices, 
 
 namespace {
 // Launch rounds of a full-rectangle product in units of one 256 x 256 tile per compute unit, for the tile the
-// choice below makes (128 x 128 tiles run at 107 against 135 TFLOP/s, 64 x 64 tiles at about half of that).
+// choice below makes (128 x 128 tiles run at 118 against 135 TFLOP/s, 64 x 64 tiles at about half of that).
 double rounds_cost(long M, long N) {
     const long t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const long t128 = ((M + 127) / 128) * ((N + 127) / 128);
     const long t64 = ((M + 63) / 64) * ((N + 63) / 64);
     if (t256 >= 200) return (double)((t256 + 255) / 256);
-    if (t128 >= 128) return (double)((t128 + 255) / 256) * 0.315;
+    if (t128 >= 128) return (double)((t128 + 255) / 256) * 0.286;
     return (double)((t64 + 255) / 256) * 0.125;
 }
 }  // namespace
@@ -502,7 +502,21 @@ admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
             default: return launch_cfg<2, 4, 4, 2, 32>(ctx, a);
         }
     }
-    if (mid) return launch_cfg<2, 2, 2, 2, 16>(ctx, a);
+    if (mid) {
+        static int mid_variant = -1;
+        if (mid_variant < 0) {
+            const char *e = getenv("ADMMQ_GEMM_MID");
+            mid_variant = e ? atoi(e) : 0;
+        }
+        // 128 x 128 tiles, measured on MI355X at 4096 x 1024 x 4096 (256 tiles, one per compute unit): eight waves
+        // of 64 x 32 with 64-row stages 118 TFLOP/s, sixteen waves of 32 x 32 116, four waves of 64 x 64 with
+        // 16-row stages 106 (one wave per SIMD hides no latency)
+        switch (mid_variant) {
+            case 1: return launch_cfg<2, 2, 2, 2, 16>(ctx, a);
+            case 2: return launch_cfg<1, 1, 4, 4, 32>(ctx, a);
+            default: return launch_cfg<2, 1, 2, 4, 64>(ctx, a);
+        }
+    }
     return launch_cfg<1, 1, 2, 2, 16>(ctx, a);
 }
 
