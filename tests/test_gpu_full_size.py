@@ -245,3 +245,50 @@ def test_cfg2_and_cfg3_in_one_call(ctx, hessian_16k):
         assert torch.equal(x[0], y[0]) and x[3].ls_moves == y[3].ls_moves > 0
         assert y[3].j_damp == pytest.approx(x[3].j_damp, rel=1e-6) and y[3].j_damp < y[3].j_damp_admm
     assert tog[0][3].ms_local_search < 0.7 * sum(x[3].ms_local_search for x in sep)
+
+
+def test_two_contexts_on_two_streams(ctx, hessian_16k):
+    """Two layers driven from two host threads, each with a context on a stream of its own: the library keeps no
+    state outside a context, so both must return what they return alone.  Factorisation and local search are chains
+    of short launches that leave most of the chip idle, so two layers side by side finish sooner than one after the
+    other (printed, not asserted: it depends on how the hardware interleaves the two queues)."""
+    import threading
+    import time
+    import paper_2605_11222_amd as admmq
+    c2 = si.CONFIGS["cfg2"]
+    H = to_dev(hessian_16k)
+    W = si.layer_weights(c2)
+    Ws = [to_dev(np.ascontiguousarray(W[:, :2048])), to_dev(np.ascontiguousarray(W[:, 2048:]))]
+    s = admmq.Schedule(T=60, ls_rounds=2, seed=11)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    alone = [ctx.quantize_layer(H, w, c2.bits, c2.group_size, s) for w in Ws]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    out, err = [None, None], [None, None]
+
+    def work(i):
+        try:
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                with admmq.Context(0, st) as c:
+                    out[i] = c.quantize_layer(H, Ws[i], c2.bits, c2.group_size, s)
+                st.synchronize()
+        except Exception as e:          # noqa: BLE001 - reported below, in the test's own thread
+            err[i] = e
+
+    th = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    t2 = time.perf_counter()
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    assert err == [None, None]
+    for a, b in zip(alone, out):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+        # the reported objective is a sum of block partials added in arrival order: equal to rounding
+        assert a[3].ls_moves == b[3].ls_moves and a[3].j_damp == pytest.approx(b[3].j_damp, rel=1e-12)
+    print(f"two 4096 x 2048 layers: one after the other {t1 - t0:.3f} s, side by side on two streams {t3 - t2:.3f} s "
+          f"(the second figure includes creating two contexts and their arenas)")
