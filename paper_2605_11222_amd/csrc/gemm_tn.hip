@@ -91,8 +91,12 @@ __device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tile
     tn = in_grp / gsz;
 }
 
-template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16>
+// DIR: every tile is interior, rows are 16-byte aligned and every k-stage is whole (the launcher checks), fp32
+// operands: stages are filled by direct global -> LDS loads.  One path per instantiation on purpose: with both
+// in one loop the compiler joins them with register copies that wait for every outstanding load.
+template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16, bool DIR>
 __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 2 : 1) void gemm_tn_kernel(GemmParams P) {
+    static_assert(!DIR || (!ABF16 && !BBF16), "direct loads carry no conversion");
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
     constexpr int NT = 64 * WGM * WGN;
@@ -227,6 +231,37 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
         }
     };
 
+    // fp32 operands of an interior tile go from global memory straight into the LDS stage (16 bytes per lane,
+    // lane l of a wave lands at dst + 16 l, so one wave instruction fills 256 consecutive floats of the stage):
+    // no staging registers, and above all no LDS write instructions in front of the barrier, during which the
+    // matrix pipe would stand still (a register-only model of this loop on MI355X: 87 % of the fp32 peak with the
+    // eight 16-byte LDS writes per thread and stage, 94 % with the direct loads).
+    constexpr int NWAVES = NT / 64;
+    constexpr int CH_A = KT * BM / 256, CH_B = KT * BN / 256;      // 256-float chunks of a stage
+    static_assert((KT * BM) % 256 == 0 && (KT * BN) % 256 == 0, "stage must be whole 1 KB chunks");
+    auto fetch_direct = [&](long k0, int buf) {
+#pragma unroll
+        for (int i = 0; i < (CH_A + NWAVES - 1) / NWAVES; ++i) {
+            const int c = wave + i * NWAVES;
+            if (CH_A % NWAVES == 0 || c < CH_A) {
+                const int e = c * 256 + 4 * lane;
+                const float *gp = (const float *)P.A + (k0 + e / BM) * P.lda + m0 + e % BM;
+                __builtin_amdgcn_global_load_lds(gp, (__attribute__((address_space(3))) void *)(sA + buf * KT * BM + c * 256),
+                                                 16, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < (CH_B + NWAVES - 1) / NWAVES; ++i) {
+            const int c = wave + i * NWAVES;
+            if (CH_B % NWAVES == 0 || c < CH_B) {
+                const int e = c * 256 + 4 * lane;
+                const float *gp = (const float *)P.B + (k0 + e / BN) * P.ldb + n0 + e % BN;
+                __builtin_amdgcn_global_load_lds(gp, (__attribute__((address_space(3))) void *)(sB + buf * KT * BN + c * 256),
+                                                 16, 0, 0);
+            }
+        }
+    };
+
     const int l32 = lane & 31;
     const int khalf = lane >> 5;
     const int offA = wm * (32 * FA) + FA * l32 + khalf * BM;
@@ -266,17 +301,21 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     constexpr int KS = KT / 2;            // k-steps per stage
     float fa[2][FA], fb[2][FB];
     if (nkt > 0) {
-        fetch(kbeg);
-        stash(0);
+        if constexpr (DIR) {
+            fetch_direct(kbeg, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            fetch(kbeg);
+            stash(0);
+        }
     }
     __syncthreads();
     if (nkt > 0) read_frags(0, 0, fa[0], fb[0]);
     // Per stage: the fragments of step kk+1 are read while the matrix cores work on step kk; the next
     // stage is written to the other buffer, the barrier passed and its first fragments requested BEFORE the
     // last step's MFMAs are issued, so that neither the barrier nor the LDS latency leaves the pipe empty.
-    // The next stage's registers go to the other LDS buffer one 16-byte write per k-step, spread over the last
-    // steps before the barrier (nobody reads that buffer during this stage): the writes and their wait hide behind
-    // the MFMAs instead of standing between the last step and the barrier.
+    // Staged path: the next stage's registers go to the other LDS buffer one 16-byte write per k-step, spread over
+    // the last steps before the barrier (nobody reads that buffer during this stage).
     // (Measured on MI355X: worth 4 % for bf16 operands, whose loads carry a conversion; fp32 operands are 1 %
     // faster with all writes after the last-but-one step, so for them nothing is spread.)
     constexpr int NW = A_PER + B_PER;
@@ -285,20 +324,31 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     for (long kt = 0; kt < nkt; ++kt) {
         const int buf = (int)(kt & 1);
         const bool more = kt + 1 < nkt;
-        if (more) fetch(kbeg + (kt + 1) * KT);
+        // the other buffer is free from here on: its last readers finished before the barrier that ended the
+        // previous stage
+        if (more) {
+            if constexpr (DIR) fetch_direct(kbeg + (kt + 1) * KT, buf ^ 1);
+            else fetch(kbeg + (kt + 1) * KT);
+        }
 #pragma unroll
         for (int kk = 0; kk < KS - 1; ++kk) {
             read_frags(buf, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-            if (kk >= W0 && kk - W0 < NW) {
-                if (more) stash_one(buf ^ 1, kk - W0);
+            if constexpr (!DIR) {
+                if (kk >= W0 && kk - W0 < NW) {
+                    if (more) stash_one(buf ^ 1, kk - W0);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);      // keep the LDS traffic ahead of this step's MFMAs
             mfma_step(fa[kk & 1], fb[kk & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
+        if constexpr (DIR) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // this wave's rows have landed
+        } else {
+            if (more) {
 #pragma unroll
-            for (int i = (KS - 1 - W0); i < NW; ++i) stash_one(buf ^ 1, i);      // what did not fit above
+                for (int i = (KS - 1 - W0); i < NW; ++i) stash_one(buf ^ 1, i);      // what did not fit above
+            }
         }
         __syncthreads();
         if (more) read_frags(buf ^ 1, 0, fa[KS & 1], fb[KS & 1]);
@@ -382,9 +432,9 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
     }
     const size_t lds_bytes = (size_t)2 * KT * (BM + BN) * sizeof(float);
     dim3 grid((unsigned)(tiles * P.split_k)), block(64 * WGM * WGN);
-#define ADMMQ_GEMM_LAUNCH(AB, BB)                                                                      \
+#define ADMMQ_GEMM_LAUNCH(AB, BB, DR)                                                                  \
     do {                                                                                               \
-        auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, KT, AB, BB>;                                          \
+        auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, KT, AB, BB, DR>;                                      \
         static bool attr_set = false;                                                                  \
         if (!attr_set) {                                                                               \
             ADMMQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -393,9 +443,13 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
         }                                                                                              \
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, P);                              \
     } while (0)
-    if (a.a_bf16 && a.b_bf16) ADMMQ_GEMM_LAUNCH(true, true);
-    else if (!a.a_bf16 && !a.b_bf16) ADMMQ_GEMM_LAUNCH(false, false);
-    else return ADMMQ_ERR_PARAM;
+    // whole tiles, whole k-stages in every slice, aligned rows: the direct-load kernel
+    const bool direct = ok && !a.a_bf16 && !a.b_bf16 && a.M % BM == 0 && a.N % BN == 0 && a.K % KT == 0 && a.K > 0;
+    if (a.a_bf16 && a.b_bf16) ADMMQ_GEMM_LAUNCH(true, true, false);
+    else if (!a.a_bf16 && !a.b_bf16) {
+        if (direct) ADMMQ_GEMM_LAUNCH(false, false, true);
+        else ADMMQ_GEMM_LAUNCH(false, false, false);
+    } else return ADMMQ_ERR_PARAM;
 #undef ADMMQ_GEMM_LAUNCH
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
