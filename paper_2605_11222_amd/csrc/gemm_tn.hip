@@ -96,7 +96,10 @@ __device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tile
 // in one loop the compiler joins them with register copies that wait for every outstanding load.
 template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16, bool DIR>
 __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 2 : 1) void gemm_tn_kernel(GemmParams P) {
-    static_assert(!DIR || (!ABF16 && !BBF16), "direct loads carry no conversion");
+    static_assert(!DIR || (ABF16 == BBF16), "direct loads: both operands fp32, or both bf16 (kept as bf16 in LDS)");
+    // bf16 operands of the direct path stay bf16 in LDS (half the bytes through the load path and the LDS) and
+    // are widened when a fragment is read: two shifts / masks per pair, issued in the shadow of the MFMAs
+    constexpr bool LB = DIR && ABF16 && BBF16;
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
     constexpr int NT = 64 * WGM * WGN;
@@ -107,6 +110,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     extern __shared__ float lds[];
     float *sA = lds;                      // [2][KT][BM]
     float *sB = lds + 2 * KT * BM;        // [2][KT][BN]
+    unsigned short *hA = (unsigned short *)lds;       // the same two arrays as bf16 bit patterns (LB)
+    unsigned short *hB = hA + 2 * KT * BM;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -237,27 +242,40 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     // matrix pipe would stand still (a register-only model of this loop on MI355X: 87 % of the fp32 peak with the
     // eight 16-byte LDS writes per thread and stage, 94 % with the direct loads).
     constexpr int NWAVES = NT / 64;
-    constexpr int CH_A = KT * BM / 256, CH_B = KT * BN / 256;      // 256-float chunks of a stage
-    static_assert((KT * BM) % 256 == 0 && (KT * BN) % 256 == 0, "stage must be whole 1 KB chunks");
+    constexpr int CE = LB ? 512 : 256;                              // elements of a 1 KB chunk
+    constexpr int CH_A = KT * BM / CE, CH_B = KT * BN / CE;         // chunks of a stage
+    static_assert((KT * BM) % CE == 0 && (KT * BN) % CE == 0, "stage must be whole 1 KB chunks");
     auto fetch_direct = [&](long k0, int buf) {
 #pragma unroll
         for (int i = 0; i < (CH_A + NWAVES - 1) / NWAVES; ++i) {
             const int c = wave + i * NWAVES;
             if (CH_A % NWAVES == 0 || c < CH_A) {
-                const int e = c * 256 + 4 * lane;
-                const float *gp = (const float *)P.A + (k0 + e / BM) * P.lda + m0 + e % BM;
-                __builtin_amdgcn_global_load_lds(gp, (__attribute__((address_space(3))) void *)(sA + buf * KT * BM + c * 256),
-                                                 16, 0, 0);
+                const int e = c * CE + (CE / 64) * lane;
+                if constexpr (LB) {
+                    const unsigned short *gp = (const unsigned short *)P.A + (k0 + e / BM) * P.lda + m0 + e % BM;
+                    __builtin_amdgcn_global_load_lds(
+                        gp, (__attribute__((address_space(3))) void *)(hA + buf * KT * BM + c * CE), 16, 0, 0);
+                } else {
+                    const float *gp = (const float *)P.A + (k0 + e / BM) * P.lda + m0 + e % BM;
+                    __builtin_amdgcn_global_load_lds(
+                        gp, (__attribute__((address_space(3))) void *)(sA + buf * KT * BM + c * CE), 16, 0, 0);
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < (CH_B + NWAVES - 1) / NWAVES; ++i) {
             const int c = wave + i * NWAVES;
             if (CH_B % NWAVES == 0 || c < CH_B) {
-                const int e = c * 256 + 4 * lane;
-                const float *gp = (const float *)P.B + (k0 + e / BN) * P.ldb + n0 + e % BN;
-                __builtin_amdgcn_global_load_lds(gp, (__attribute__((address_space(3))) void *)(sB + buf * KT * BN + c * 256),
-                                                 16, 0, 0);
+                const int e = c * CE + (CE / 64) * lane;
+                if constexpr (LB) {
+                    const unsigned short *gp = (const unsigned short *)P.B + (k0 + e / BN) * P.ldb + n0 + e % BN;
+                    __builtin_amdgcn_global_load_lds(
+                        gp, (__attribute__((address_space(3))) void *)(hB + buf * KT * BN + c * CE), 16, 0, 0);
+                } else {
+                    const float *gp = (const float *)P.B + (k0 + e / BN) * P.ldb + n0 + e % BN;
+                    __builtin_amdgcn_global_load_lds(
+                        gp, (__attribute__((address_space(3))) void *)(sB + buf * KT * BN + c * CE), 16, 0, 0);
+                }
             }
         }
     };
@@ -267,7 +285,34 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     const int offA = wm * (32 * FA) + FA * l32 + khalf * BM;
     const int offB = wn * (32 * FB) + FB * l32 + khalf * BN;
     // fragments of k-step kk (rows 2kk, 2kk+1 of the stage) of buffer `buf`
+    auto widen2 = [](unsigned u, float &lo, float &hi) {
+        lo = __uint_as_float(u << 16);
+        hi = __uint_as_float(u & 0xFFFF0000u);
+    };
     auto read_frags = [&](int buf, int kk, float *fa, float *fb) {
+        if constexpr (LB) {
+            const unsigned short *cA = hA + buf * KT * BM + offA + 2 * kk * BM;
+            const unsigned short *cB = hB + buf * KT * BN + offB + 2 * kk * BN;
+            if constexpr (FA == 4) {
+                const uint2 t = *(const uint2 *)cA;
+                widen2(t.x, fa[0], fa[1]);
+                widen2(t.y, fa[2], fa[3]);
+            } else if constexpr (FA == 2) {
+                widen2(*(const unsigned *)cA, fa[0], fa[1]);
+            } else {
+                fa[0] = __uint_as_float((unsigned)cA[0] << 16);
+            }
+            if constexpr (FB == 4) {
+                const uint2 t = *(const uint2 *)cB;
+                widen2(t.x, fb[0], fb[1]);
+                widen2(t.y, fb[2], fb[3]);
+            } else if constexpr (FB == 2) {
+                widen2(*(const unsigned *)cB, fb[0], fb[1]);
+            } else {
+                fb[0] = __uint_as_float((unsigned)cB[0] << 16);
+            }
+            return;
+        }
         const float *cA = sA + buf * KT * BM + offA + 2 * kk * BM;
         const float *cB = sB + buf * KT * BN + offB + 2 * kk * BN;
         if constexpr (FA == 4) {
@@ -362,6 +407,56 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     float *outp = P.out + (long)slice * P.slice_stride;
     const long wm0 = m0 + wm * (32 * FA);
     const long wn0 = n0 + wn * (32 * FB);
+    if constexpr (DIR) {
+        // every tile is whole and aligned: no guards, and the rows of Z are requested ZB at a time (one load, one
+        // wait, one store per row would pay the memory latency 16 FA times); ZB keeps the kernel free of spills
+        constexpr int ZB = FA * FB >= 8 ? 8 : 16;
+        const long n = wn0 + FB * l32;
+#pragma unroll
+        for (int a = 0; a < FA; ++a) {
+#pragma unroll
+            for (int v0 = 0; v0 < 16; v0 += ZB) {
+                float z[ZB][FB];
+                if (P.Z) {
+#pragma unroll
+                    for (int u = 0; u < ZB; ++u) {
+                        const int v = v0 + u;
+                        const long m = wm0 + FA * (8 * (v / 4) + 4 * khalf + (v % 4)) + a;
+                        const float *zp = P.Z + m * P.ldz + n;
+                        if constexpr (FB == 4) {
+                            const floatx4 t = *(const floatx4 *)zp;
+                            z[u][0] = t.x; z[u][1] = t.y; z[u][2] = t.z; z[u][3] = t.w;
+                        } else if constexpr (FB == 2) {
+                            const floatx2 t = *(const floatx2 *)zp;
+                            z[u][0] = t.x; z[u][1] = t.y;
+                        } else {
+                            z[u][0] = zp[0];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < ZB; ++u) {
+                    const int v = v0 + u;
+                    const long m = wm0 + FA * (8 * (v / 4) + 4 * khalf + (v % 4)) + a;
+                    float r[FB];
+#pragma unroll
+                    for (int b = 0; b < FB; ++b) {
+                        r[b] = P.alpha * acc[a][b][v];
+                        if (P.Z) r[b] += P.beta * z[u][b];
+                    }
+                    float *op = outp + m * P.ldo + n;
+                    if constexpr (FB == 4) {
+                        *(floatx4 *)op = floatx4{r[0], r[1], r[2], r[3]};
+                    } else if constexpr (FB == 2) {
+                        *(floatx2 *)op = floatx2{r[0], r[1]};
+                    } else {
+                        op[0] = r[0];
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int a = 0; a < FA; ++a) {
 #pragma unroll
@@ -444,9 +539,13 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, P);                              \
     } while (0)
     // whole tiles, whole k-stages in every slice, aligned rows: the direct-load kernel
-    const bool direct = ok && !a.a_bf16 && !a.b_bf16 && a.M % BM == 0 && a.N % BN == 0 && a.K % KT == 0 && a.K > 0;
-    if (a.a_bf16 && a.b_bf16) ADMMQ_GEMM_LAUNCH(true, true, false);
-    else if (!a.a_bf16 && !a.b_bf16) {
+    bool direct = ok && a.M % BM == 0 && a.N % BN == 0 && a.K % KT == 0 && a.K > 0;
+    if (a.a_bf16)        // 16-byte loads of bf16 rows
+        direct = direct && a.lda % 8 == 0 && a.ldb % 8 == 0 && al16(a.A) && al16(a.B);
+    if (a.a_bf16 && a.b_bf16) {
+        if (direct) ADMMQ_GEMM_LAUNCH(true, true, true);
+        else ADMMQ_GEMM_LAUNCH(true, true, false);
+    } else if (!a.a_bf16 && !a.b_bf16) {
         if (direct) ADMMQ_GEMM_LAUNCH(false, false, true);
         else ADMMQ_GEMM_LAUNCH(false, false, false);
     } else return ADMMQ_ERR_PARAM;
@@ -483,13 +582,13 @@ __global__ void sym_reduce_kernel(float *H, long n, const float *P, int slices, 
 
 namespace {
 // Launch rounds of a full-rectangle product in units of one 256 x 256 tile per compute unit, for the tile the
-// choice below makes (128 x 128 tiles run at 118 against 135 TFLOP/s, 64 x 64 tiles at about half of that).
+// choice below makes (128 x 128 tiles run at 130 against 141 TFLOP/s, 64 x 64 tiles at about half of that).
 double rounds_cost(long M, long N) {
     const long t256 = ((M + 255) / 256) * ((N + 255) / 256);
     const long t128 = ((M + 127) / 128) * ((N + 127) / 128);
     const long t64 = ((M + 63) / 64) * ((N + 63) / 64);
     if (t256 >= 200) return (double)((t256 + 255) / 256);
-    if (t128 >= 128) return (double)((t128 + 255) / 256) * 0.286;
+    if (t128 >= 128) return (double)((t128 + 255) / 256) * 0.27;
     return (double)((t64 + 255) / 256) * 0.125;
 }
 }  // namespace
@@ -562,9 +661,9 @@ admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
             const char *e = getenv("ADMMQ_GEMM_MID");
             mid_variant = e ? atoi(e) : 0;
         }
-        // 128 x 128 tiles, measured on MI355X at 4096 x 1024 x 4096 (256 tiles, one per compute unit): eight waves
-        // of 64 x 32 with 64-row stages 118 TFLOP/s, sixteen waves of 32 x 32 116, four waves of 64 x 64 with
-        // 16-row stages 106 (one wave per SIMD hides no latency)
+        // 128 x 128 tiles, measured on MI355X at 4096 x 1024 x 4096 (256 tiles, one per compute unit) with staged
+        // loads: eight waves of 64 x 32 with 64-row stages 118 TFLOP/s, sixteen waves of 32 x 32 116, four waves of
+        // 64 x 64 with 16-row stages 106 (one wave per SIMD hides no latency); the first with direct loads: 130
         switch (mid_variant) {
             case 1: return launch_cfg<2, 2, 2, 2, 16>(ctx, a);
             case 2: return launch_cfg<1, 1, 4, 4, 32>(ctx, a);
