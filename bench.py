@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
 # calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
 PMC_TRAFFIC_BYTES = {
-    "cfg2": {"gemm": (227277.1 + 65536.0) * 1024, "project": (65775.1 + 131104.0) * 1024},
+    "cfg2": {"gemm": (227176.3 + 65536.0) * 1024, "project": (65784.5 + 131104.0) * 1024},
 }
 
 
