@@ -141,6 +141,51 @@ def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k):
         assert err < 1e-5
 
 
+@pytest.mark.parametrize("name,cols,rhos", [("cfg4", 1280, (0.1, 30.0)), ("cfg5", 512, (0.1,))])
+def test_w_update_at_the_large_workloads_sizes_against_literal_eq7(ctx, name, cols, rhos):
+    """The W-update at n = 12288 and n = 25600: the factorisation there reads only the lower triangle of the
+    trailing matrix (its path for large n), the products run 48 / 100 tile rows deep in the 256 x 256 tile
+    configuration.  The reference is eq. 7 as printed, W = (Hs + rho I)^{-1} (Hs Ws + rho D - V), solved in float64
+    by a Cholesky factorisation of Hs + rho I (an eigendecomposition of this size would take minutes); the Hessian
+    is formed in float64 from 4096 tokens of the workload's activations, so it is rank deficient and the damping
+    alone keeps it positive definite."""
+    import scipy.linalg as sla
+    cfg = si.CONFIGS[name]
+    n = cfg.n
+    H64 = np.zeros((n, n))
+    for _, xc in si.iter_x_chunks(cfg, 4096):
+        H64 += orc.hessian([si.chunk_as_f64(cfg, xc)])
+    H32 = H64.astype(np.float32)
+    del H64
+    print("hessian formed", flush=True)
+    Hs, lam = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    d64 = np.sqrt(np.diag(Hs))
+    Hs /= d64[:, None]
+    Hs /= d64[None, :]
+    dg, lam_g = ctx.factorize(to_dev(H32), 0.01, True)
+    torch.cuda.synchronize()
+    print("factorised", flush=True)
+    assert lam_g == pytest.approx(lam, rel=1e-6)
+    assert np.allclose(dg.cpu().numpy(), d64, rtol=1e-6)
+    W0 = si.layer_weights(cfg)[:, :cols]
+    Ws = (W0 * d64[:, None]).astype(np.float32)
+    HWs = Hs @ Ws.astype(np.float64)
+    rng = np.random.default_rng(78)
+    scale = np.abs(Ws).mean()
+    for rho in rhos:
+        D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        A = Hs.copy()
+        A[np.diag_indices(n)] += rho
+        cf = sla.cho_factor(A, lower=True, overwrite_a=True, check_finite=False)
+        Wref = sla.cho_solve(cf, HWs + rho * D.astype(np.float64) - V.astype(np.float64), check_finite=False)
+        del A, cf
+        err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
+        print(f"n={n} rho={rho:g}: relative W-update error {err:.2e}", flush=True)
+        assert err < 1e-5
+
+
 @pytest.mark.parametrize("kind", ["dual", "codebook"])
 def test_format_projection_at_4096x4096_against_the_mirror(ctx, kind):
     """Sec. 4.3 projections at the headline layer's size: codes, dual and B bit-exact against the oracle's fp32
