@@ -337,3 +337,32 @@ def test_two_contexts_on_two_streams(ctx, hessian_16k):
         assert a[3].ls_moves == b[3].ls_moves and a[3].j_damp == pytest.approx(b[3].j_damp, rel=1e-12)
     print(f"two 4096 x 2048 layers: one after the other {t1 - t0:.3f} s, side by side on two streams {t3 - t2:.3f} s "
           f"(the second figure includes creating two contexts and their arenas)")
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4", "cfg5"])
+def test_projection_at_full_size_bit_exact_against_fp32_mirror(ctx, name):
+    """The fused projection / dual / residual pass on whole n x p arrays of the workloads (16-byte vector path, the
+    grid shape the layer solver launches): codes, V and B bit for bit against the oracle's fp32 mirror of eqs. 8-10."""
+    cfg = si.CONFIGS[name]
+    n, p, bits, g = cfg.n, cfg.p, cfg.bits, cfg.group_size
+    rng = np.random.default_rng(cfg.seed + 1000)
+    W0 = si.layer_weights(cfg)
+    d = np.exp(0.5 * rng.standard_normal(n)).astype(np.float32)
+    scales, zeros = ctx.grid_init(to_dev(W0), bits, g)
+    sc, zr = scales.cpu().numpy(), zeros.cpu().numpy()
+    Ws = W0 * d[:, None]
+    a = np.float32(np.abs(Ws).mean())
+    W = Ws + np.float32(0.3) * a * rng.standard_normal((n, p), dtype=np.float32)
+    rho, rho_next = 2.5, 2.75
+    V = np.float32(rho * 0.05) * a * rng.standard_normal((n, p), dtype=np.float32)
+    del Ws
+    Vd = to_dev(V)
+    codes, B, rs = ctx.project_dual(to_dev(W), Vd, to_dev(d), bits, g, scales, zeros, rho, rho_next)
+    torch.cuda.synchronize()
+    k, Vn, Bn, ss = orc.project_dual_step_f32(W, V, rho, rho_next, d, sc, zr, sc == 0, bits)
+    assert np.array_equal(codes.cpu().numpy(), k)
+    assert np.array_equal(Vd.cpu().numpy(), Vn)
+    assert np.array_equal(B.cpu().numpy(), Bn)
+    assert rs == pytest.approx(ss, rel=1e-5)
+    assert k.max() == 2 ** bits - 1 and k.min() == 0
+    print(f"{name}: {n} x {p}, {bits} bits, group {g or n}: codes, V and B identical to the fp32 mirror")
