@@ -96,6 +96,23 @@ def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
     j64 = float(np.sum(E * (H64 @ E))) + st_full.lam * float(np.sum(E * E))
     assert st_full.j_damp_admm == pytest.approx(j64, rel=1e-4)
     assert st_full.j_damp_admm <= st_full.j_damp_rtn
+    # --- full width with one round of the local search: moves applied, objective lower and equal to its float64
+    #     recomputation, only rows of applied pairs touched ------------------------------------------------------
+    s_ls = admmq.Schedule(T=cfg.T, ls_rounds=1, seed=cfg.seed)
+    c_ls, sc_ls, zr_ls, st_ls = ctx.quantize_layer(Hd_, W0d, cfg.bits, g, s_ls)
+    assert torch.equal(sc_ls, scales) and torch.equal(zr_ls, zeros)
+    assert st_ls.j_damp_admm == pytest.approx(st_full.j_damp_admm, rel=1e-9)
+    assert st_ls.ls_moves > 0 and st_ls.j_damp < st_ls.j_damp_admm
+    k_ls = c_ls.cpu().numpy().astype(np.float64)
+    E = np.repeat(zr_ls.cpu().numpy().astype(np.float64), gg, 0) + k_ls * np.repeat(sc_ls.cpu().numpy().astype(np.float64), gg, 0) \
+        - W0.astype(np.float64)
+    j_ls = float(np.sum(E * (H64 @ E))) + st_ls.lam * float(np.sum(E * E))
+    assert st_ls.j_damp == pytest.approx(j_ls, rel=1e-4)
+    touched = int((c_ls != full_codes).any(dim=1).sum())
+    assert 0 < touched <= 2 * st_ls.ls_moves
+    assert int((c_ls.to(torch.int16) - full_codes.to(torch.int16)).abs().max()) <= st_ls.ls_moves
+    print(f"{name}: full-width local search, 1 round: {st_ls.ls_moves} moves on {touched} rows, objective "
+          f"{st_ls.j_damp_admm:.8g} -> {st_ls.j_damp:.8g}")
     # --- the oracle on the slice, whole algorithm incl. local search ---------------------------------------
     ls_rounds = 2
     ref = orc.quantize_layer(H64, W0s.astype(np.float64), cfg.bits, g, T=cfg.T, ls_rounds=ls_rounds, seed=cfg.seed)
