@@ -3,10 +3,23 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <new>
 #include <thread>
 #include <vector>
 
 #include "common.h"
+
+// No C++ exception may cross the C boundary (or leave a helper thread): host allocations that fail become an error code.
+template <class F>
+static admmq_status admmq_guarded(F &&body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return ADMMQ_ERR_WORKSPACE;
+    } catch (...) {
+        return ADMMQ_ERR_DEVICE;
+    }
+}
 
 // ---- declarations of launchers defined in the other translation units -----------------------
 admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double lambda, int precondition, float *d,
@@ -443,7 +456,8 @@ extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stre
     *out = nullptr;
     if (device == -1) {
         // validation-only context: every call still checks its arguments, then stops at the device
-        admmq_ctx *c = new admmq_ctx();
+        admmq_ctx *c = new (std::nothrow) admmq_ctx();
+        if (!c) return ADMMQ_ERR_WORKSPACE;
         c->device = -1;
         *out = c;
         return ADMMQ_OK;
@@ -454,7 +468,8 @@ extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stre
         return ADMMQ_ERR_DEVICE;
     }
     ADMMQ_HIP(hipSetDevice(device));
-    admmq_ctx *c = new admmq_ctx();
+    admmq_ctx *c = new (std::nothrow) admmq_ctx();
+    if (!c) return ADMMQ_ERR_WORKSPACE;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
     *out = c;
@@ -692,8 +707,10 @@ extern "C" admmq_status admmq_grid_refresh(admmq_ctx *ctx, const float *W, const
     ADMMQ_TRY(take(ctx, part, (size_t)2 * admmq_refresh_error_blocks()));
     ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
     int acc = 0;
-    ADMMQ_TRY(grid_refresh_core(ctx, W, V, n, p, d, inv_d, bits, g, rho, scales, zeros, nullptr, new_sc, new_zr, part,
-                                &acc, err_old, err_new));
+    ADMMQ_TRY(admmq_guarded([&] {
+        return grid_refresh_core(ctx, W, V, n, p, d, inv_d, bits, g, rho, scales, zeros, nullptr, new_sc, new_zr, part,
+                                 &acc, err_old, err_new);
+    }));
     *accepted = acc;
     ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
     admmq_arena_reset_transient(ctx);
@@ -778,8 +795,10 @@ extern "C" admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const
         ctx, ls_transient_bytes(n, p, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs)));
     double lambda = 0.0;
     ADMMQ_TRY(hessian_scalars(ctx, H, n, prm->damp, &lambda));
-    admmq_status s = local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, scales, zeros, codes, plan, prm->seed,
-                                       explicit_pairs, moves_out, drop_out);
+    admmq_status s = admmq_guarded([&] {
+        return local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, scales, zeros, codes, plan, prm->seed,
+                                 explicit_pairs, moves_out, drop_out);
+    });
     admmq_arena_reset_transient(ctx);
     return s;
 }
@@ -1264,9 +1283,10 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
                     const admmq_layer &l = L[i];
                     child.top = child.persist_top = 0;
                     double drop = 0.0;
-                    const admmq_status s = local_search_core(&child, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i],
-                                                             l.scales, l.zeros, l.codes, plan, sched->seed, nullptr,
-                                                             &moves[i], &drop);
+                    const admmq_status s = admmq_guarded([&] {
+                        return local_search_core(&child, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i], l.scales,
+                                                 l.zeros, l.codes, plan, sched->seed, nullptr, &moves[i], &drop);
+                    });
                     if (s != ADMMQ_OK) {
                         result[w] = s;
                         break;
@@ -1352,7 +1372,7 @@ extern "C" admmq_status admmq_quantize_layer(admmq_ctx *ctx, const float *H, con
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
     Projection pj = {0, bits, group_size > 0 ? group_size : n, scales, zeros, nullptr, nullptr, nullptr};
-    return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats);
+    return admmq_guarded([&] { return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats); });
 }
 
 extern "C" admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, int64_t n, const admmq_layer *layers,
@@ -1370,7 +1390,7 @@ extern "C" admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, in
     if (!schedule_ok(sched) || sched->refresh_iter != -1) return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
-    return quantize_many_core(ctx, H, n, layers, count, sched, stats);
+    return admmq_guarded([&] { return quantize_many_core(ctx, H, n, layers, count, sched, stats); });
 }
 
 extern "C" admmq_status admmq_grid_init_dual(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw,
@@ -1432,5 +1452,5 @@ extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float 
     ADMMQ_HIP(hipSetDevice(ctx->device));
     Projection pj = {fmt->kind, fmt->bits, fmt->group_size > 0 ? fmt->group_size : n, fmt->scales, fmt->zeros,
                      fmt->flags, fmt->codebook, Wq};
-    return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats);
+    return admmq_guarded([&] { return quantize_core(ctx, H, W0, n, p, ldw, pj, sched, codes, stats); });
 }
