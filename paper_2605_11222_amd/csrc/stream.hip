@@ -174,13 +174,10 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                 if (i < n) {
                     if (VEC) {
                         floatx4 tw, tv;
-                        if (nontemporal) {
-                            tw = __builtin_nontemporal_load((const floatx4 *)(W + offw));
-                            tv = __builtin_nontemporal_load((const floatx4 *)(V + off));
-                        } else {
-                            tw = *(const floatx4 *)(W + offw);
-                            tv = *(const floatx4 *)(V + off);
-                        }
+                        if (nontemporal & 1) tw = __builtin_nontemporal_load((const floatx4 *)(W + offw));
+                        else tw = *(const floatx4 *)(W + offw);
+                        if (nontemporal & 2) tv = __builtin_nontemporal_load((const floatx4 *)(V + off));
+                        else tv = *(const floatx4 *)(V + off);
                         w[rr][0] = tw.x; w[rr][1] = tw.y; w[rr][2] = tw.z; w[rr][3] = tw.w;
                         v[rr][0] = tv.x; v[rr][1] = tv.y; v[rr][2] = tv.z; v[rr][3] = tv.w;
                     } else {
@@ -234,13 +231,10 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                 if (VEC) {
                     floatx4 ov = {vn[0], vn[1], vn[2], vn[3]};
                     floatx4 ob = {bn[0], bn[1], bn[2], bn[3]};
-                    if (nontemporal) {
-                        __builtin_nontemporal_store(ov, (floatx4 *)(V + off));
-                        __builtin_nontemporal_store(ob, (floatx4 *)(B + offw));
-                    } else {
-                        *(floatx4 *)(V + off) = ov;
-                        *(floatx4 *)(B + offw) = ob;
-                    }
+                    if (nontemporal & 2) __builtin_nontemporal_store(ov, (floatx4 *)(V + off));
+                    else *(floatx4 *)(V + off) = ov;
+                    if (nontemporal & 4) __builtin_nontemporal_store(ob, (floatx4 *)(B + offw));
+                    else *(floatx4 *)(B + offw) = ob;
                     if (CODES) {
                         uint32_t packed = (uint32_t)kq[0] | ((uint32_t)kq[1] << 8) | ((uint32_t)kq[2] << 16) |
                                           ((uint32_t)kq[3] << 24);
