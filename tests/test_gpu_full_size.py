@@ -383,3 +383,37 @@ def test_projection_at_full_size_bit_exact_against_fp32_mirror(ctx, name):
     assert rs == pytest.approx(ss, rel=1e-5)
     assert k.max() == 2 ** bits - 1 and k.min() == 0
     print(f"{name}: {n} x {p}, {bits} bits, group {g or n}: codes, V and B identical to the fp32 mirror")
+
+
+def test_layer_at_n12288_against_oracle_slice(ctx):
+    """The whole algorithm at the 12288-row workload's depth (2 bits, groups of 64, factorisation from the lower
+    triangle, 48-tile-deep products, local search over 12288 rows) on a 16-column slice that the float64 oracle can
+    follow: same grid, objectives within the 0.5 % bar.  The Hessian is formed in float64 from 4096 of the
+    workload's tokens; iterations and search batches are cut so that the oracle's eigendecomposition of a
+    12288 x 12288 matrix dominates the test's time."""
+    import paper_2605_11222_amd as admmq
+    cfg = si.CONFIGS["cfg4"]
+    n, cols, T, batches = cfg.n, 16, 120, 384
+    H64 = np.zeros((n, n))
+    for _, xc in si.iter_x_chunks(cfg, 4096):
+        H64 += orc.hessian([si.chunk_as_f64(cfg, xc)])
+    H32 = H64.astype(np.float32)
+    del H64
+    W0 = np.ascontiguousarray(si.layer_weights(cfg)[:, :cols])
+    s = admmq.Schedule(T=T, ls_rounds=1, ls_batches=batches, ls_pairs=64, seed=cfg.seed)
+    codes, scales, zeros, st = ctx.quantize_layer(to_dev(H32), to_dev(W0), cfg.bits, cfg.group_size, s)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+    ref = orc.quantize_layer(H32.astype(np.float64), W0.astype(np.float64), cfg.bits, cfg.group_size, T=T, ls_rounds=1,
+                             ls_batches=batches, ls_pairs=64, seed=cfg.seed)
+    k = codes.cpu().numpy()
+    assert k.max() <= 2 ** cfg.bits - 1
+    assert np.array_equal(zeros.cpu().numpy(), ref.zeros.astype(np.float32))
+    assert np.allclose(scales.cpu().numpy(), ref.scales, rtol=3e-7)
+    print(f"n=12288 slice: rtn {st.j_damp_rtn:.6g}/{ref.j_damp_rtn:.6g} admm {st.j_damp_admm:.6g}/{ref.j_damp_admm:.6g} "
+          f"final {st.j_damp:.6g}/{ref.j_damp:.6g} moves {st.ls_moves}/{ref.ls.moves} "
+          f"code mismatch {np.mean(k != ref.codes):.2e}", flush=True)
+    assert st.j_damp_rtn == pytest.approx(ref.j_damp_rtn, rel=1e-4)
+    assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+    assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    assert st.j_damp <= st.j_damp_admm * (1 + 1e-6) <= st.j_damp_rtn
