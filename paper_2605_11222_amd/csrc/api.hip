@@ -35,7 +35,9 @@ admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const
                              const int32_t *pairs_prev, int npairs_prev, const float *partial_prev,
                              const uint8_t *mv_prev, int slot_prev, const int32_t *pairs_cur, int npairs_cur,
                              int npend, int32_t *pend_idx, float *pend_d, float *hcol, float *partial_cur,
-                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop);
+                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop,
+                             const int32_t *pairs_next, int npairs_next, const float *exs_cur, float *exs_next);
+int admmq_ls_fast_pairs();
 admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
                               int64_t p, const int32_t *pend_idx, const float *pend_d, int count);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
@@ -159,7 +161,8 @@ size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_p
     return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
            2 * admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
            admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) +
-           2 * admmq_align_up((size_t)pairs_per_batch * p) + admmq_align_up((size_t)2 * admmq_ls_defer() * n * 4) + 65536;
+           2 * admmq_align_up((size_t)pairs_per_batch * p) + admmq_align_up((size_t)2 * admmq_ls_defer() * n * 4) +
+           2 * admmq_align_up((size_t)admmq_ls_fast_pairs() * admmq_ls_fast_pairs() * 16) + 65536;
 }
 
 admmq_status read_back(admmq_ctx *ctx, void *host, const void *dev, size_t bytes) {
@@ -386,6 +389,13 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     ADMMQ_TRY(take(ctx, mv_b, (size_t)plan.pairs * p));
     ADMMQ_TRY(take(ctx, hcol, (size_t)2 * K * n));
     ADMMQ_TRY(take(ctx, pend_idx, (size_t)2 * K));
+    // coupling entries H'[own row of the next batch][candidate row of this batch], gathered one launch ahead
+    const int FP = admmq_ls_fast_pairs();
+    float *exs_a = nullptr, *exs_b = nullptr;
+    ADMMQ_TRY(take(ctx, exs_a, (size_t)FP * FP * 4));
+    ADMMQ_TRY(take(ctx, exs_b, (size_t)FP * FP * 4));
+    float *exs[2] = {exs_a, exs_b};
+    const bool ahead = plan.pairs <= FP;
     ADMMQ_TRY(take(ctx, choice, 4));
     ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double), scal[1] reinterpreted: moves (int)
     int *dev_moves = (int *)(scal + 1);
@@ -428,10 +438,14 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
             const int32_t *cur = s < plan.batches ? pairs + ((size_t)r * plan.batches + s) * plan.pairs * 2 : nullptr;
             const int32_t *prev = s > 0 ? pairs + ((size_t)r * plan.batches + s - 1) * plan.pairs * 2 : nullptr;
             const int slot_prev = s > 0 ? (s - 1) % K : 0;
+            const int32_t *next = (ahead && s + 1 < plan.batches)
+                                      ? pairs + ((size_t)r * plan.batches + s + 1) * plan.pairs * 2 : nullptr;
             ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, prev,
                                       s > 0 ? plan.pairs : 0, part[(s + 1) & 1], mv[(s + 1) & 1], slot_prev, cur,
                                       plan.pairs, s > 0 ? slot_prev : 0, pend_idx, pend_d, hcol, part[s & 1],
-                                      mv[s & 1], choice, dev_moves, scal));
+                                      mv[s & 1], choice, dev_moves, scal, next, plan.pairs,
+                                      (ahead && s > 0 && cur) ? exs[(s + 1) & 1] : nullptr,
+                                      next ? exs[s & 1] : nullptr));
             if (s > 0 && (slot_prev == K - 1 || s == plan.batches))
                 ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, slot_prev + 1));
         }
@@ -760,7 +774,7 @@ extern "C" admmq_status admmq_ls_evaluate(admmq_ctx *ctx, const float *H, double
     ADMMQ_TRY(take(ctx, partial, (size_t)npairs * chunks));
     ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, (uint8_t *)codes, n, p, bits, g, scales, nullptr, 0, nullptr,
                               nullptr, 0, pairs, npairs, 0, nullptr, nullptr, nullptr, partial, nullptr, nullptr,
-                              nullptr, nullptr));
+                              nullptr, nullptr, nullptr, 0, nullptr, nullptr));
     ADMMQ_TRY(admmq_k_ls_totals(ctx, partial, chunks, npairs, totals));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;

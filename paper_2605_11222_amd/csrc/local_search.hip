@@ -173,7 +173,10 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
                                                       int32_t *pend_idx, float *pend_d, float *hcol,
                                                       float *__restrict__ partial_cur, uint8_t *__restrict__ mv_cur,
                                                       int chunks, int32_t *__restrict__ choice,
-                                                      int *__restrict__ moves, double *__restrict__ drop) {
+                                                      int *__restrict__ moves, double *__restrict__ drop,
+                                                      const int32_t *__restrict__ pairs_next, int npairs_next,
+                                                      const float *__restrict__ exs_cur,
+                                                      float *__restrict__ exs_next) {
     __shared__ float coef_o[LS_K][4];
     __shared__ int which_o[LS_K];
     __shared__ int cand[2 * LS_FAST_PAIRS];
@@ -198,10 +201,25 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
     }
     const bool prev_fast = npairs_prev > 0 && fast;
     const bool mv_vec = fast && (p & 15) == 0;
-    // (1) the oldest request is the one a second request depends on: candidate row -> coupling entry of H'
+    // (1) the coupling entries of H' between the own pair and every candidate of the previous batch: gathered by
+    // the previous launch into exs_cur (one plain load here); without it, the oldest request is the one a second
+    // request depends on: candidate row -> coupling entry
     long ex_col = -1;
     const bool ex_on = prev_fast && own && tid < 4 * npairs_prev;
-    if (ex_on) ex_col = pairs_prev[2 * (tid >> 2) + (tid & 1)];
+    float ex_ready = 0.f;
+    if (ex_on) {
+        if (exs_cur) ex_ready = exs_cur[((long)blockIdx.y * LS_FAST_PAIRS) * 4 + tid];
+        else ex_col = pairs_prev[2 * (tid >> 2) + (tid & 1)];
+    }
+    // the same gather for the NEXT launch (own pairs of the next batch x candidates of this one): one entry per
+    // thread in the first block column, requested here and stored at the very end, off this launch's critical path
+    const bool gather = exs_next && pairs_next && pairs_cur && blockIdx.x == 0 && (int)blockIdx.y < npairs_next &&
+                        (int)gridDim.y <= LS_FAST_PAIRS && npairs_next <= LS_FAST_PAIRS && tid < 4 * (int)gridDim.y;
+    long g_row = -1, g_col = -1;
+    if (gather) {
+        g_row = pairs_next[2 * blockIdx.y + ((tid >> 1) & 1)];
+        g_col = pairs_cur[2 * (tid >> 2) + (tid & 1)];
+    }
     // (2) everything else
     int cand_r = 0;
     if (prev_fast && tid < 2 * npairs_prev) cand_r = pairs_prev[tid];
@@ -268,10 +286,16 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
         }
     }
     // (3) the dependent request, then the hand-over to LDS
+    float g_val = 0.f;
+    if (gather && g_row >= 0 && g_row < n && g_col >= 0 && g_col < n)
+        g_val = H[g_row * n + g_col] + (g_row == g_col ? lambda : 0.f);
     if (ex_on) {
-        const long row = (tid & 2) ? i2 : i1;
-        float h = 0.f;
-        if (ex_col >= 0 && ex_col < n) h = H[row * n + ex_col] + (row == ex_col ? lambda : 0.f);
+        float h = ex_ready;
+        if (!exs_cur) {
+            const long row = (tid & 2) ? i2 : i1;
+            h = 0.f;
+            if (ex_col >= 0 && ex_col < n) h = H[row * n + ex_col] + (row == ex_col ? lambda : 0.f);
+        }
         exs[tid >> 2][tid & 3] = h;
     }
     if (prev_fast && tid < 2 * npairs_prev) cand[tid] = cand_r;
@@ -372,6 +396,7 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
             *drop += (double)wtot;
         }
     }
+    if (gather) exs_next[((long)blockIdx.y * LS_FAST_PAIRS) * 4 + tid] = g_val;
     if (!pairs_cur) return;
     // ---- this block's candidate pair ----------------------------------------------------------------------
     float gain = 0.f;
@@ -488,6 +513,7 @@ __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__
 
 int admmq_ls_chunks(int64_t p) { return (int)((p + LS_CHUNK - 1) / LS_CHUNK); }
 int admmq_ls_defer() { return LS_K; }
+int admmq_ls_fast_pairs() { return LS_FAST_PAIRS; }
 
 // One step: plan the previous batch (if npairs_prev > 0) into pending slot slot_prev, and evaluate the current
 // batch (if pairs_cur) against the state after that move.  npend = pending slots already in memory, i.e. slots
@@ -498,14 +524,15 @@ admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const
                              const int32_t *pairs_prev, int npairs_prev, const float *partial_prev,
                              const uint8_t *mv_prev, int slot_prev, const int32_t *pairs_cur, int npairs_cur,
                              int npend, int32_t *pend_idx, float *pend_d, float *hcol, float *partial_cur,
-                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop) {
+                             uint8_t *mv_cur, int32_t *choice, int *dev_moves, double *dev_drop,
+                             const int32_t *pairs_next, int npairs_next, const float *exs_cur, float *exs_next) {
     const int chunks = admmq_ls_chunks(p);
     const int levels = (1 << bits) - 1;
     const unsigned gy = (unsigned)(pairs_cur ? npairs_cur : 1);
     hipLaunchKernelGGL(ls_step_kernel, dim3((unsigned)chunks, gy), dim3(256), 0, ctx->stream, H, lambda, G, codes,
                        (long)n, (long)p, levels, (long)g, scales, pairs_prev, npairs_prev, partial_prev, mv_prev,
                        slot_prev, pairs_cur, npend, pend_idx, pend_d, hcol, partial_cur, mv_cur, chunks, choice,
-                       dev_moves, dev_drop);
+                       dev_moves, dev_drop, pairs_next, npairs_next, exs_cur, exs_next);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
