@@ -93,7 +93,9 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
                                                                   float *__restrict__ S) {
     constexpr int NS = NT / C;                // segments per tile (SL rows each)
     constexpr int TR = NS * SL;               // rows per tile
-    __shared__ double s_a[TR], s_b[TR + 1], s_l[TR + 1], s_di[TR];
+    // the row coefficients of a tile, in two buffers: tile t lives in buffer t & 1 (both passes), and the next
+    // tile's are requested at the start of a tile and stored at its end, so no pass waits for them
+    __shared__ double s_a[2][TR], s_b[2][TR + 1], s_l[2][TR + 1], s_di[2][TR];
     __shared__ double endf[2][NS][C], endP[2][NS][C];
     const int tid = threadIdx.x;
     const int c = tid % C, sg = tid / C;
@@ -111,26 +113,43 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
         }
     };
     // s_a[r] = a_i, s_b[r] = b_{i-1}, s_l[r] = l_{i-1}, s_di[r] = 1/delta_i, i = i0 + r (s_l[r + 1] = l_i)
-    auto stage = [&](long i0) {
-        for (int r = tid; r <= TR; r += NT) {
+    constexpr int KR = (TR + NT) / NT;        // coefficient rows per thread (TR + 1 rows over NT threads)
+    double q_a[KR], q_b[KR], q_l[KR], q_d[KR];
+    auto coef_load = [&](long i0) {
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+            const int r = tid + k * NT;
             const long i = i0 + r;
+            const bool row = r < TR && i < n, link = r <= TR && i >= 1 && i < n;
+            q_a[k] = row ? ta[i] : 0.0;
+            q_d[k] = row ? dinv[i] : 0.0;
+            q_b[k] = link ? tb[i - 1] : 0.0;
+            q_l[k] = link ? lfac[i - 1] : 0.0;
+        }
+    };
+    auto coef_store = [&](int buf) {
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+            const int r = tid + k * NT;
             if (r < TR) {
-                s_a[r] = i < n ? ta[i] : 0.0;
-                s_di[r] = i < n ? dinv[i] : 0.0;
+                s_a[buf][r] = q_a[k];
+                s_di[buf][r] = q_d[k];
             }
-            s_b[r] = (i >= 1 && i < n) ? tb[i - 1] : 0.0;
-            s_l[r] = (i >= 1 && i < n) ? lfac[i - 1] : 0.0;
+            if (r <= TR) {
+                s_b[buf][r] = q_b[k];
+                s_l[buf][r] = q_l[k];
+            }
         }
     };
     // the segment's forward recurrence from zero: fl[u] = local f, Pl[u] = product of the -l up to row u
-    auto forward_local = [&](const float *y, double *fl, double *Pl) {
+    auto forward_local = [&](int cb, const float *y, double *fl, double *Pl) {
         double f = 0.0, P = 1.0;
         const int r0 = sg * SL;
 #pragma unroll
         for (int u = 0; u < SL; ++u) {
             const int r = r0 + u;
-            const double z = s_b[r] * (double)y[u] + s_a[r] * (double)y[u + 1] + s_b[r + 1] * (double)y[u + 2];
-            const double ml = -s_l[r];
+            const double z = s_b[cb][r] * (double)y[u] + s_a[cb][r] * (double)y[u + 1] + s_b[cb][r + 1] * (double)y[u + 2];
+            const double ml = -s_l[cb][r];
             f = fma(ml, f, z);
             P = ml * P;
             fl[u] = f;
@@ -140,19 +159,24 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
 
     // ---------------- forward: only the value of f entering each tile is kept ----------------
     double carry = 0.0;                       // f of the row just above the current tile
+    coef_load(0);
     load_y(0, ycur);
+    coef_store(0);
+    __syncthreads();
     for (long t = 0; t < ntile; ++t) {
-        const int par = (int)(t & 1);
-        stage(t * TR);
-        __syncthreads();
-        if (t + 1 < ntile) load_y(t + 1, ynext);
+        const int par = (int)(t & 1), cb = par;
+        if (t + 1 < ntile) {
+            load_y(t + 1, ynext);
+            coef_load((t + 1) * TR);
+        }
         if (jok && sg == 0) carries[t * p + j] = carry;
         {
             double fl[SL], Pl[SL];
-            forward_local(ycur, fl, Pl);
+            forward_local(cb, ycur, fl, Pl);
             endf[par][sg][c] = fl[SL - 1];
             endP[par][sg][c] = Pl[SL - 1];
         }
+        if (t + 1 < ntile) coef_store(cb ^ 1);      // its last readers passed the barrier of the tile before
         __syncthreads();
         double run = carry;
 #pragma unroll
@@ -163,17 +187,20 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
     }
 
     // ---------------- backward: each tile's f is formed again from Y, then consumed in registers --------
+    // (the last tile's coefficients are still in their buffer)
     __syncthreads();
     double below = 0.0;                       // s of the row just below the current tile
     load_y(ntile - 1, ycur);
     for (long t = ntile - 1; t >= 0; --t) {
         const long i0 = t * TR;
-        stage(i0);
-        __syncthreads();
-        if (t > 0) load_y(t - 1, ynext);
+        const int cb = (int)(t & 1);
+        if (t > 0) {
+            load_y(t - 1, ynext);
+            coef_load((t - 1) * TR);
+        }
         const double tile_in = jok ? carries[t * p + j] : 0.0;
         double fl[SL], Pl[SL];
-        forward_local(ycur, fl, Pl);
+        forward_local(cb, ycur, fl, Pl);
         endf[0][sg][c] = fl[SL - 1];
         endP[0][sg][c] = Pl[SL - 1];
         __syncthreads();
@@ -193,8 +220,8 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
 #pragma unroll
             for (int u = SL - 1; u >= 0; --u) {
                 const int r = r0 + u;
-                const double ml = -s_l[r + 1];                                 // l_i
-                sv = fma(ml, sv, fl[u] * s_di[r]);
+                const double ml = -s_l[cb][r + 1];                             // l_i
+                sv = fma(ml, sv, fl[u] * s_di[cb][r]);
                 P = ml * P;
                 fl[u] = sv;
                 Pl[u] = P;
@@ -202,6 +229,7 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
             endf[1][sg][c] = sv;
             endP[1][sg][c] = P;
         }
+        if (t > 0) coef_store(cb ^ 1);              // read last by the tile above this one's predecessor: done
         __syncthreads();
         double cin = below, run = below;
 #pragma unroll
@@ -272,6 +300,20 @@ admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const doubl
     }
     if (forced == 8 || forced == 16 || forced == 32 || forced == 64) C = forced;
     const unsigned nb = (unsigned)((p + C - 1) / C);
+    // 16-column strips: 512 threads run 32 segments of 16 rows (two waves per SIMD hide the latency of the dependent
+    // steps and of the LDS reads; 512-row tiles as before): 80 us against 100 us with 256 threads x 32 rows at
+    // n = p = 4096; 8-row segments or 1024 threads are slower (longer chain of segment ends, fewer registers)
+    static int narrow = -1;
+    if (narrow < 0) {
+        const char *e = getenv("ADMMQ_TRIDIAG_THREADS");
+        narrow = (e && atoi(e) == 256) ? 1 : 0;
+    }
+    if (C == 16 && !narrow) {
+        hipLaunchKernelGGL((tridiag_apply_split_kernel<16, 512, 16>), dim3(nb), dim3(512), 0, ctx->stream, ta, tb, dinv,
+                           lfac, (long)n, (long)p, Y, carries, S);
+        ADMMQ_HIP(hipGetLastError());
+        return ADMMQ_OK;
+    }
     if (C == 8)
         hipLaunchKernelGGL((tridiag_apply_split_kernel<8, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
                            lfac, (long)n, (long)p, Y, carries, S);
