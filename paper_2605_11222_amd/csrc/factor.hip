@@ -148,7 +148,7 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
 #pragma unroll
         for (int u = 0; u < SL; ++u) {
             const int r = r0 + u;
-            const double z = s_b[cb][r] * (double)y[u] + s_a[cb][r] * (double)y[u + 1] + s_b[cb][r + 1] * (double)y[u + 2];
+            const double z = fma(s_b[cb][r + 1], (double)y[u + 2], fma(s_a[cb][r], (double)y[u + 1], s_b[cb][r] * (double)y[u]));
             const double ml = -s_l[cb][r];
             f = fma(ml, f, z);
             P = ml * P;
