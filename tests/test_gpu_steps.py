@@ -141,8 +141,13 @@ def test_first_projection_of_dense_weights_is_round_to_nearest(ctx):
 # ---------------------------------------------------------------------------------------------
 # factorisation + W-update (eq. 7)
 # ---------------------------------------------------------------------------------------------
+# the later shapes walk the product launcher's paths: whole 64 / 128 / 256 tiles filled by direct loads (256 x 1280,
+# 1024 x 2048, 2048 x 2048), a ragged width on the staged path (1024 x 4100), a column split whose tail takes a
+# smaller tile (768 x 5120: 3 x 20 tiles), and the tridiagonal solve's 8- and 16-column strips
 @pytest.mark.parametrize("n,p,N,seed", [(128, 64, 512, 0), (300, 77, 900, 1), (3, 5, 10, 2), (2, 4, 9, 3),
-                                         (1, 3, 4, 4), (1024, 256, 3000, 5), (640, 130, 400, 6)])
+                                         (1, 3, 4, 4), (1024, 256, 3000, 5), (640, 130, 400, 6),
+                                         (256, 1280, 600, 7), (1024, 2048, 2100, 8), (1024, 4100, 2100, 9),
+                                         (2048, 2048, 4200, 10), (768, 5120, 1600, 11)])
 def test_w_update_matches_literal_eq7_in_float64(ctx, n, p, N, seed):
     X, W0 = correlated_problem(n, p, N, seed, outliers=2 if n > 100 else 0)   # N < n in the last case
     H64 = orc.hessian([X.astype(np.float64)])
