@@ -413,3 +413,57 @@ def test_batched_layers_on_a_shared_hessian(ctx):
     with pytest.raises(admmq.AdmmqError) as e:
         ctx.quantize_layers(H, [to_dev(Wa), to_dev(Wb)], 3, 0, admmq.Schedule(T=20, ls_rounds=0, refresh_iter=5))
     assert e.value.code == 3
+
+
+def test_batched_layers_edge_cases(ctx):
+    """The batched entry point at its limits: 64 one-column matrices (the maximum count; offsets off every vector
+    path), strided weights, a non-finite value in a later matrix (refused before anything is written), and the
+    schedule's symmetric / clipped grids passed through to every matrix."""
+    import paper_2605_11222_amd as admmq
+    n = 96
+    X, Wbig = correlated_problem(n, 70, 400, 70, outliers=1)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    s = admmq.Schedule(T=30, ls_rounds=1, ls_pairs=8, seed=2)
+    cols = [to_dev(np.ascontiguousarray(Wbig[:, i:i + 1])) for i in range(64)]
+    many = ctx.quantize_layers(H, cols, 3, 0, s)
+    assert len(many) == 64
+    for i in (0, 17, 63):
+        alone = ctx.quantize_layer(H, cols[i], 3, 0, s)
+        assert torch.equal(many[i][0], alone[0]) and torch.equal(many[i][1], alone[1])
+        assert many[i][3].j_damp == pytest.approx(alone[3].j_damp, rel=1e-9)
+    with pytest.raises(admmq.AdmmqError) as e:
+        ctx.quantize_layers(H, cols + [cols[0]], 3, 0, s)                 # 65 matrices
+    assert e.value.code == 2
+    # strided views: two matrices that are column ranges of one array (ldw = 70)
+    Wd = to_dev(Wbig)
+    views = [Wd[:, :33], Wd[:, 33:]]
+    strided = ctx.quantize_layers(H, views, [4, 2], [0, 32], s)
+    for v, b, g, got in zip(views, (4, 2), (0, 32), strided):
+        alone = ctx.quantize_layer(H, v.contiguous(), b, g, s)
+        assert torch.equal(got[0], alone[0]) and torch.equal(got[1], alone[1]) and torch.equal(got[2], alone[2])
+    # a non-finite weight in the second matrix: refused, outputs of both untouched
+    bad = Wbig[:, 33:].copy()
+    bad[5, 2] = np.nan
+    lib = admmq.load_library()
+    import ctypes as C
+    from paper_2605_11222_amd import binding
+    outs = [(torch.full((n, 33), 7, dtype=torch.uint8, device="cuda"), torch.full((1, 33), -1.0, device="cuda"),
+             torch.full((1, 33), -1.0, device="cuda")),
+            (torch.full((n, 37), 7, dtype=torch.uint8, device="cuda"), torch.full((1, 37), -1.0, device="cuda"),
+             torch.full((1, 37), -1.0, device="cuda"))]
+    Wa, Wb = to_dev(np.ascontiguousarray(Wbig[:, :33])), to_dev(bad)
+    layers = (binding._Layer * 2)(
+        binding._Layer(Wa.data_ptr(), 33, 33, 3, 0, outs[0][0].data_ptr(), outs[0][1].data_ptr(), outs[0][2].data_ptr()),
+        binding._Layer(Wb.data_ptr(), 37, 37, 3, 0, outs[1][0].data_ptr(), outs[1][1].data_ptr(), outs[1][2].data_ptr()))
+    cs = binding._Schedule(30, 0.1, 1.1, 0.01, 1, 1, 0, 8, -1, 0, 0, 0.8, 0, 2)
+    rc = lib.admmq_quantize_layers(ctx._h, C.c_void_p(H.data_ptr()), n, layers, 2, C.byref(cs), None)
+    torch.cuda.synchronize()
+    assert rc == 4
+    for codes, sc, zr in outs:
+        assert bool((codes == 7).all()) and bool((sc == -1.0).all()) and bool((zr == -1.0).all())
+    # symmetric, clipped grids reach every matrix of the call
+    s2 = admmq.Schedule(T=30, ls_rounds=0, symmetric=True, clip_points=20)
+    both = ctx.quantize_layers(H, [Wa, to_dev(np.ascontiguousarray(Wbig[:, 33:]))], 3, 32, s2)
+    for W, got in zip((Wa, to_dev(np.ascontiguousarray(Wbig[:, 33:]))), both):
+        alone = ctx.quantize_layer(H, W, 3, 32, s2)
+        assert torch.equal(got[0], alone[0]) and torch.equal(got[1], alone[1]) and torch.equal(got[2], alone[2])
