@@ -236,6 +236,7 @@ class AdmmResult:
     refresh_accepted_at: int = -1
     refresh_err_old: float = float("nan")           # ||D_old - Wt||_F^2 at the attempt
     refresh_err_new: float = float("nan")           # ||D_new - Wt||_F^2 at the attempt
+    iters: int = 0                                  # iterations run (T unless quiet_stop ended the loop)
 
 
 def refit_grid(x: np.ndarray, grid: Grid) -> Grid:
@@ -246,9 +247,16 @@ def refit_grid(x: np.ndarray, grid: Grid) -> Grid:
     return Grid.fit(x, grid.bits, 0 if g == n else g)
 
 
-def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refresh_iter=-1) -> AdmmResult:
+def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refresh_iter=-1,
+         quiet_stop=0) -> AdmmResult:
     """Alg. 1 lines 1-10 on the damped Hessian Hd.  rho_t = rho0 * gamma^t (Sec. 3.6), exactly T
-    iterations (no early stop).  Tiny negative eigenvalues from round-off are clamped at 0.
+    iterations (no early stop) unless ``quiet_stop`` is set.  Tiny negative eigenvalues from round-off are
+    clamped at 0.
+
+    quiet_stop = K > 0 (not in Alg. 1, which runs T iterations): stop after the first iteration t >= 1 at which the
+    codes have been equal to those of the iteration before for K iterations in a row.  Thm. 1 (Sec. 3.6) has the
+    discrete iterates D^(t) converge; on a finite grid a convergent sequence is constant from some iteration on,
+    and the read-out (line 10) only needs D.  ``iters`` records the iterations run.
 
     Grid refresh (Sec. 3.3 "Grid refresh", App. B).  Reading: the paper does not say when a refresh is tried
     nor which continuous weights are refitted; here one attempt is made at iteration ``refresh_iter`` (-1 = never),
@@ -265,7 +273,9 @@ def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refr
     rho = float(rho0)
     res = AdmmResult(codes=None, Wq=None, d=d, lam_eig=lam)
     k = None
+    quiet = 0
     for t in range(T):
+        k_before = k
         W = w_update(U, lam, HWs, D, V, rho)
         k, Dn, Wt = d_update(W, V, rho, d, grid)
         V_next = V + rho * (W - Dn)                                  # eq. 9 with the current grid
@@ -289,6 +299,11 @@ def admm(Hd, W0, grid: Grid, T=300, rho0=0.1, gamma=1.1, precondition=True, refr
             res.first_codes = k.copy()
         D = Dn
         rho = rho * gamma
+        res.iters = t + 1
+        if quiet_stop > 0 and t >= 1:
+            quiet = quiet + 1 if np.array_equal(k, k_before) else 0
+            if quiet >= quiet_stop:
+                break
     res.codes = k
     res.grid = grid
     if hasattr(grid, "project"):
@@ -621,14 +636,14 @@ class LayerResult:
 
 def quantize_layer(H, W0, bits, group_size=0, T=300, rho0=0.1, gamma=1.1, damp=0.01, precondition=True,
                    ls_rounds=5, ls_batches=None, ls_pairs=64, seed=0, refresh_iter=-1, symmetric=False,
-                   clip_points=0, clip_shrink=0.8) -> LayerResult:
+                   clip_points=0, clip_shrink=0.8, quiet_stop=0) -> LayerResult:
     """Alg. 1 end to end from the raw (undamped) Hessian H = X^T X."""
     H = np.asarray(H, dtype=np.float64)
     W0 = np.asarray(W0, dtype=np.float64)
     Hd, lam = damp_hessian(H, damp)
     grid = Grid.fit(W0, bits, group_size, symmetric, clip_points, clip_shrink)
     k_rtn, W_rtn = rtn(W0, grid)
-    a = admm(Hd, W0, grid, T, rho0, gamma, precondition, refresh_iter)
+    a = admm(Hd, W0, grid, T, rho0, gamma, precondition, refresh_iter, quiet_stop)
     j_admm = objective(Hd, W0, a.Wq)
     j_rtn = objective(Hd, W0, W_rtn)                # on the initial grid
     grid = a.grid                                    # the local search moves on the grid in force

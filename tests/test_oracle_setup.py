@@ -156,6 +156,38 @@ def test_key_inequality_residual_decay_and_rtn_no_worse_cfg1():
     assert j_admm_u <= orc.objective(H, W0, orc.rtn(W0, grid)[1])
 
 
+def test_quiet_stop_ends_where_the_dual_residual_history_says_the_codes_froze():
+    """The opt-in stopping rule (not in Alg. 1): stop once the codes have been constant for K iterations.  Pinned
+    against the full run's own record of ||D^(t+1) - D^(t)||_F (zero exactly when no code changed): the stop falls at
+    the first iteration that closes K zero entries in a row, and - the discrete iterates having converged there
+    (Thm. 1) - the codes are those of the full run.  K = 0 changes nothing."""
+    cfg, H, W0 = cfg1_problem()
+    Hd, _ = orc.damp_hessian(H)
+    grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
+    full = orc.admm(Hd, W0, grid, T=120)
+    assert full.iters == 120
+    same = orc.admm(Hd, W0, grid, T=120, quiet_stop=0)
+    assert np.array_equal(same.codes, full.codes) and same.iters == 120
+    dual = np.array(full.dual)
+    for K in (1, 3, 8):
+        run, expect = 0, None
+        for t in range(1, len(dual)):
+            run = run + 1 if dual[t] == 0.0 else 0
+            if run >= K:
+                expect = t + 1
+                break
+        assert expect is not None and expect < 120
+        early = orc.admm(Hd, W0, grid, T=120, quiet_stop=K)
+        assert early.iters == expect
+        assert len(early.primal) == expect and early.primal == full.primal[:expect]
+        if np.all(dual[expect:] == 0.0):                    # nothing moved afterwards in the full run
+            assert np.array_equal(early.codes, full.codes)
+    # a window that never closes runs all T iterations
+    assert orc.admm(Hd, W0, grid, T=6, quiet_stop=50).iters == 6
+    lay = orc.quantize_layer(H, W0, cfg.bits, cfg.group_size, T=120, ls_rounds=0, quiet_stop=3)
+    assert lay.admm.iters < 120 and np.array_equal(lay.codes, full.codes)
+
+
 def test_codes_invariant_under_hessian_rescaling_and_column_separable():
     cfg, H, W0 = cfg1_problem()
     grid = orc.Grid.fit(W0, cfg.bits, cfg.group_size)
