@@ -88,6 +88,11 @@ typedef struct {
                               already holds (admmq_factorize or an earlier layer): skip Alg. 1 lines 1-3.
                               Matrices that see the same activations (q/k/v, gate/up) share one Hessian. */
     uint64_t seed;         /* seed of the pair sampler                                        */
+    int32_t quiet_stop;    /* 0 = run exactly T iterations (Alg. 1).  K > 0 (not in the paper's listing): stop
+                              after the first iteration at which the codes have been unchanged for K iterations
+                              in a row - Thm. 1 (Sec. 3.6) has the discrete iterates converge, so on the finite
+                              grid they are constant from some iteration on.  Costs one scalar read-back (a
+                              stream synchronisation) per iteration; admmq_quantize_layer only.            */
 } admmq_schedule;
 
 typedef struct {            /* host struct, filled when the pointer is not NULL */
@@ -96,7 +101,7 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     double j_damp_admm;     /* same, before local search */
     double j_damp_rtn;      /* same, for round-to-nearest on the same grid */
     double lambda;          /* the damping added to the diagonal */
-    int32_t iters_done;
+    int32_t iters_done;     /* iterations run: T, or fewer when quiet_stop ended the loop */
     int32_t ls_moves;       /* applied row pairs */
     float *primal_res;      /* optional host array [T]: ||W - D||_F per iteration, or NULL */
     int64_t *code_flips;    /* optional host array [T]: codes changed per iteration, or NULL */
@@ -141,7 +146,8 @@ typedef struct {
  * [W0_1 | W0_2 | ...], and projection, dual update and local search matrix by matrix on each one's own grid.
  * Columns never interact in eqs. 7-11, so every matrix receives exactly what admmq_quantize_layer would give it
  * alone with the same schedule (the same codes when the local search is off or the seeds agree).
- * `layers` is a host array; outputs of different matrices must not overlap.  sched->refresh_iter must be -1
+ * `layers` is a host array; outputs of different matrices must not overlap.  sched->quiet_stop must be 0 and
+ * sched->refresh_iter must be -1
  * (the refresh decision of eq. 12 is taken per matrix, which a shared iteration cannot follow) ->
  * ADMMQ_ERR_PARAM otherwise.  The scratch needed is admmq_workspace_bytes(n, sum of p, T).
  * The local searches of up to four matrices run side by side on streams of the library's own (default priority,

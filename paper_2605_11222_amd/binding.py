@@ -32,7 +32,7 @@ class _Schedule(C.Structure):
                 ("precondition", C.c_int32), ("ls_rounds", C.c_int32), ("ls_batches", C.c_int32),
                 ("ls_pairs", C.c_int32), ("refresh_iter", C.c_int32), ("symmetric", C.c_int32),
                 ("clip_points", C.c_int32), ("clip_shrink", C.c_double), ("reuse_factor", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("quiet_stop", C.c_int32)]
 
 
 class _Stats(C.Structure):
@@ -147,6 +147,7 @@ class Schedule:
     clip_shrink: float = 0.8
     reuse_factor: bool = False
     seed: int = 0
+    quiet_stop: int = 0
 
 
 @dataclass
@@ -240,7 +241,7 @@ class Context:
         zeros = torch.empty((n // g, p), dtype=torch.float32, device=W0.device)
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
                        sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
-                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed, sched.quiet_stop)
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
@@ -366,7 +367,7 @@ class Context:
         Wq = torch.empty((n, p), dtype=torch.float32, device=W0.device)
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
                        sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
-                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed, sched.quiet_stop)
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
@@ -409,7 +410,7 @@ class Context:
         stats[0].profile = int(bool(profile))
         cs = _Schedule(sched.T, sched.rho0, sched.gamma, sched.damp, int(sched.precondition), sched.ls_rounds,
                        sched.ls_batches, sched.ls_pairs, sched.refresh_iter, int(sched.symmetric), sched.clip_points,
-                       sched.clip_shrink, int(sched.reuse_factor), sched.seed)
+                       sched.clip_shrink, int(sched.reuse_factor), sched.seed, sched.quiet_stop)
         _check(self._lib.admmq_quantize_layers(self._h, _ptr(H), n, layers, count, C.byref(cs), stats))
         result = []
         for i in range(count):

@@ -958,7 +958,10 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, V, 0, np * 4));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, res, 0, (size_t)T * 8));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, flips, 0, (size_t)T * 8));
-    const bool want_flips = uniform && want && stats->code_flips != nullptr;
+    // the stopping rule needs the number of codes that changed, every iteration (as the flip history does)
+    const int quiet_stop = uniform ? sched->quiet_stop : 0;
+    const bool report_flips = uniform && want && stats->code_flips != nullptr;
+    const bool want_flips = report_flips || quiet_stop > 0;
     if (want_flips) ADMMQ_TRY(admmq_k_fill_bytes(ctx, codes, 0, np));
     std::vector<double> hrho((size_t)T + 1);
     {
@@ -993,6 +996,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     t_phase.start();
     // W and B trade places every iteration: the projection pass writes B^(t+1) over the W it has just read
     float *Bcur = B, *Wcur = W;
+    int iters = 0, quiet = 0;
     for (int t = 0; t < T; ++t) {
         const float rf = (float)hrho[t], rf_next = (float)hrho[t + 1];
         if (t == 0) {
@@ -1019,11 +1023,18 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;
+        iters = t + 1;
+        if (quiet_stop > 0 && t >= 1) {
+            unsigned long long changed = 0;
+            ADMMQ_TRY(read_back(ctx, &changed, flips + t, 8));
+            quiet = changed == 0 ? quiet + 1 : 0;
+            if (quiet >= quiet_stop) break;           // the codes of this iteration are in `codes`
+        }
     }
     float ms_admm = t_phase.stop();
 
     if (want) {
-        stats->iters_done = T;
+        stats->iters_done = iters;
         stats->lambda = lambda;
         stats->refresh_accepted = refresh_accepted;
         stats->refresh_err_old = refresh_eo;
@@ -1033,7 +1044,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             ADMMQ_TRY(read_back(ctx, h.data(), res, (size_t)T * 8));
             for (int t = 0; t < T; ++t) stats->primal_res[t] = (float)sqrt(h[t]);
         }
-        if (want_flips) {
+        if (report_flips) {
             std::vector<unsigned long long> h((size_t)T);
             ADMMQ_TRY(read_back(ctx, h.data(), flips, (size_t)T * 8));
             for (int t = 0; t < T; ++t) stats->code_flips[t] = (int64_t)h[t];
@@ -1370,7 +1381,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
 bool schedule_ok(const admmq_schedule *s) {
     return s->T >= 1 && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
            isfinite(s->gamma) && isfinite(s->damp) && s->ls_rounds >= 0 && s->ls_batches >= 0 && s->ls_pairs >= 0 &&
-           s->refresh_iter >= -1 && s->clip_points >= 0 && s->clip_points <= 100000 &&
+           s->refresh_iter >= -1 && s->quiet_stop >= 0 && s->clip_points >= 0 && s->clip_points <= 100000 &&
            (s->clip_points == 0 || (s->clip_shrink >= 0.0 && s->clip_shrink < 1.0));
 }
 
@@ -1401,7 +1412,7 @@ extern "C" admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, in
         P += l.p;
     }
     if (P > (1 << 24)) return ADMMQ_ERR_SHAPE;
-    if (!schedule_ok(sched) || sched->refresh_iter != -1) return ADMMQ_ERR_PARAM;
+    if (!schedule_ok(sched) || sched->refresh_iter != -1 || sched->quiet_stop != 0) return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
     return admmq_guarded([&] { return quantize_many_core(ctx, H, n, layers, count, sched, stats); });
@@ -1459,7 +1470,7 @@ extern "C" admmq_status admmq_quantize_layer_format(admmq_ctx *ctx, const float 
     ADMMQ_TRY(check_format(fmt, n));
     ADMMQ_TRY(check_layer_args(H, W0, n, p, ldw, 2, fmt->group_size));
     if (!schedule_ok(sched) || sched->ls_rounds != 0 || sched->refresh_iter != -1 || sched->symmetric != 0 ||
-        sched->clip_points != 0)
+        sched->clip_points != 0 || sched->quiet_stop != 0)
         return ADMMQ_ERR_PARAM;
     if (stats && stats->code_flips) return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;

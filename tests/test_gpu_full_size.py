@@ -423,3 +423,23 @@ def test_layer_at_n12288_against_oracle_slice(ctx):
     assert abs(st.j_damp_admm - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
     assert abs(st.j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
     assert st.j_damp <= st.j_damp_admm * (1 + 1e-6) <= st.j_damp_rtn
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_quiet_stop_at_full_width(ctx, hessian_16k, name):
+    """The opt-in stopping rule at 4096 x 4096 / 4096 x 1024: the run that stops once the codes have been unchanged
+    for 8 iterations returns the codes of the run over all 200 iterations (in which, by its flip history, nothing
+    moved afterwards) in a fraction of the iterations."""
+    import paper_2605_11222_amd as admmq
+    cfg = si.CONFIGS[name]
+    H, W0 = to_dev(hessian_16k), to_dev(si.layer_weights(cfg))
+    full = ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size, admmq.Schedule(T=cfg.T, ls_rounds=0), want_history=True)
+    early = ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size, admmq.Schedule(T=cfg.T, ls_rounds=0, quiet_stop=8))
+    it = early[3].iters_done
+    flips = np.array(full[3].code_flips)
+    print(f"{name}: codes frozen after iteration {int(np.nonzero(flips)[0].max())}; stopped after {it} of {cfg.T} "
+          f"iterations, ADMM {early[3].ms_admm:.0f} ms against {full[3].ms_admm:.0f} ms")
+    assert it < cfg.T // 2
+    assert np.all(flips[it - 8:] == 0)
+    assert torch.equal(early[0], full[0]) and torch.equal(early[1], full[1])
+    assert early[3].j_damp == pytest.approx(full[3].j_damp, rel=1e-9)

@@ -467,3 +467,37 @@ def test_batched_layers_edge_cases(ctx):
     for W, got in zip((Wa, to_dev(np.ascontiguousarray(Wbig[:, 33:]))), both):
         alone = ctx.quantize_layer(H, W, 3, 32, s2)
         assert torch.equal(got[0], alone[0]) and torch.equal(got[1], alone[1]) and torch.equal(got[2], alone[2])
+
+
+@pytest.mark.parametrize("n,p,bits,g,seed", [(128, 64, 4, 0, 0), (256, 96, 3, 64, 1), (192, 130, 2, 32, 3)])
+def test_quiet_stop_returns_the_codes_of_the_full_run(ctx, n, p, bits, g, seed):
+    """The opt-in stopping rule (schedule.quiet_stop = K: stop once the codes have been unchanged for K iterations,
+    Thm. 1): fewer iterations, the codes, grid and objectives of the run over all T iterations (whose flip history
+    shows that nothing moved afterwards), and the iteration count the oracle's rule gives within a few iterations
+    (fp32 against float64 trajectories)."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(n, p, 4 * n, 40 + seed, outliers=2)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    Hd_, W0d = to_dev(H32), to_dev(W0)
+    T, K = 160, 6
+    full = ctx.quantize_layer(Hd_, W0d, bits, g, admmq.Schedule(T=T, ls_rounds=1, ls_pairs=16, seed=seed),
+                              want_history=True)
+    early = ctx.quantize_layer(Hd_, W0d, bits, g, admmq.Schedule(T=T, ls_rounds=1, ls_pairs=16, seed=seed, quiet_stop=K),
+                               want_history=True)
+    it = early[3].iters_done
+    assert K + 1 <= it < T and full[3].iters_done == T
+    flips = np.array(full[3].code_flips)
+    assert np.all(flips[it - K:it] == 0) and flips[it - K - 1] != 0         # the window closed exactly there
+    assert np.all(flips[it:] == 0)                                          # and nothing moved afterwards
+    assert torch.equal(early[0], full[0]) and torch.equal(early[1], full[1]) and torch.equal(early[2], full[2])
+    assert early[3].j_damp == pytest.approx(full[3].j_damp, rel=1e-9)
+    assert early[3].primal_res[:it] == full[3].primal_res[:it] and all(v == 0.0 for v in early[3].primal_res[it:])
+    assert early[3].code_flips[:it] == full[3].code_flips[:it]
+    ref = orc.quantize_layer(H32.astype(np.float64), W0.astype(np.float64), bits, g, T=T, ls_rounds=1, ls_pairs=16,
+                             seed=seed, quiet_stop=K)
+    print(f"n={n} p={p}: stopped after {it} iterations (oracle {ref.admm.iters}) of {T}")
+    assert abs(ref.admm.iters - it) <= 12
+    assert abs(early[3].j_damp - ref.j_damp) <= OBJ_TOL * ref.j_damp
+    # without the history arrays the rule works the same way
+    plain = ctx.quantize_layer(Hd_, W0d, bits, g, admmq.Schedule(T=T, ls_rounds=1, ls_pairs=16, seed=seed, quiet_stop=K))
+    assert plain[3].iters_done == it and torch.equal(plain[0], full[0])

@@ -70,7 +70,8 @@ def test_argument_validation_without_a_gpu(lib):
                 binding._Schedule(10, 0.1, 1.1, -1.0, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
                 binding._Schedule(10, float("nan"), 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0),
                 binding._Schedule(10, 0.1, 1.1, 0.01, 1, -1, 0, 0, -1, 0, 0, 0.8, 0, 0),
-                binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -2, 0, 0, 0.8, 0, 0)):
+                binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -2, 0, 0, 0.8, 0, 0),
+                binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0, -1)):      # quiet_stop < 0
         assert q(sched=bad) == 3
     assert q() == 8                       # valid arguments: stops at the missing device
     cnt = C.c_uint64(0)
@@ -113,6 +114,7 @@ def test_format_argument_validation_without_a_gpu(lib):
     with_ls = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 2, 0, 0, -1, 0, 0, 0.8, 0, 0)
     with_refresh = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 5, 0, 0, 0.8, 0, 0)
     assert q(book, sched=with_ls) == 3 and q(dual, sched=with_refresh) == 3
+    assert q(dual, sched=binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0, 2)) == 3    # quiet_stop
     st = binding._Stats()
     flips = (C.c_int64 * 10)()
     st.code_flips = C.cast(flips, C.POINTER(C.c_int64))
@@ -149,6 +151,8 @@ def test_batched_layers_argument_validation_without_a_gpu(lib):
     assert q([good, Lr(one, 4, 4, 9, 0, one, one, one)]) == 3
     with_refresh = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 5, 0, 0, 0.8, 0, 0)
     assert q([good, wide], sched=with_refresh) == 3                       # the refresh is a per-matrix decision
+    with_stop = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0, 3)
+    assert q([good, wide], sched=with_stop) == 3                          # ... and so is stopping early
     assert lib.admmq_quantize_layers(h, C.c_void_p(one), 8, None, 1, C.byref(sched), None) == 1
     lib.admmq_destroy(h)
 
