@@ -191,6 +191,14 @@ def main():
         "tridiag_ms_per_launch": tri_ms,
         "input_generation_s": gen_s,
     }
+    # informational, outside the timed region and not part of `value`: the same layer with the opt-in stopping
+    # rule (stop once the codes have been unchanged for 8 iterations); the timed steps above run all T iterations
+    early = ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size,
+                               admmq.Schedule(T=T, ls_rounds=args.ls_rounds, seed=cfg.seed, quiet_stop=8))[3]
+    line["with_quiet_stop_8"] = {"iterations_run": early.iters_done, "layer_quantize_time_s": early.ms_total * 1e-3,
+                                 "admm_s": early.ms_admm * 1e-3, "j_damp": early.j_damp,
+                                 "same_objective_as_full_run": bool(abs(early.j_damp - stats[-1].j_damp)
+                                                                    <= 1e-9 * abs(stats[-1].j_damp))}
     ctx.close()
     del X
     if not args.no_cpu_baseline:
