@@ -92,7 +92,7 @@ typedef struct {
                               after the first iteration at which the codes have been unchanged for K iterations
                               in a row - Thm. 1 (Sec. 3.6) has the discrete iterates converge, so on the finite
                               grid they are constant from some iteration on.  Costs one scalar read-back (a
-                              stream synchronisation) per iteration; admmq_quantize_layer only.            */
+                              stream synchronisation) per iteration; uniform grids only.                   */
 } admmq_schedule;
 
 typedef struct {            /* host struct, filled when the pointer is not NULL */
@@ -146,8 +146,8 @@ typedef struct {
  * [W0_1 | W0_2 | ...], and projection, dual update and local search matrix by matrix on each one's own grid.
  * Columns never interact in eqs. 7-11, so every matrix receives exactly what admmq_quantize_layer would give it
  * alone with the same schedule (the same codes when the local search is off or the seeds agree).
- * `layers` is a host array; outputs of different matrices must not overlap.  sched->quiet_stop must be 0 and
- * sched->refresh_iter must be -1
+ * `layers` is a host array; outputs of different matrices must not overlap.  sched->quiet_stop ends the loop once
+ * no matrix has changed a code for that many iterations.  sched->refresh_iter must be -1
  * (the refresh decision of eq. 12 is taken per matrix, which a shared iteration cannot follow) ->
  * ADMMQ_ERR_PARAM otherwise.  The scratch needed is admmq_workspace_bytes(n, sum of p, T).
  * The local searches of up to four matrices run side by side on streams of the library's own (default priority,

@@ -1156,7 +1156,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
     size_t ng_total = 0;
     for (int i = 0; i < count; ++i) ng_total += admmq_align_up((size_t)(n / grp[i]) * L[i].p * 4);
-    size_t need = admm_transient_bytes(n, P, T) + ng_total + (size_t)count * (admmq_align_up((size_t)T * 8) + 1024);
+    size_t need = admm_transient_bytes(n, P, T) + ng_total + (size_t)count * (2 * admmq_align_up((size_t)T * 8) + 1024);
     if (plan.rounds > 0 && n >= 2) {
         const size_t ls = ls_transient_bytes(n, pmax, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
         if (ls > need) need = ls;
@@ -1180,6 +1180,15 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
     ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
     ADMMQ_TRY(take(ctx, jdev, 4));
+    // the stopping rule: codes changed per iteration and matrix, [T][count]; the loop ends once no matrix has
+    // changed a code for quiet_stop iterations in a row
+    const int quiet_stop = sched->quiet_stop;
+    unsigned long long *flips = nullptr;
+    if (quiet_stop > 0) {
+        ADMMQ_TRY(take(ctx, flips, (size_t)T * count));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, flips, 0, (size_t)T * count * 8));
+        for (int i = 0; i < count; ++i) ADMMQ_TRY(admmq_k_fill_bytes(ctx, L[i].codes, 0, (size_t)n * L[i].p));
+    }
     for (int i = 0; i < count; ++i) {
         const admmq_layer &l = L[i];
         ADMMQ_TRY(admmq_k_grid_fit(ctx, l.W0, n, l.p, l.ldw, l.bits, grp[i], sched->symmetric != 0, sched->clip_points,
@@ -1218,6 +1227,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     // --- ADMM loop (Alg. 1 lines 5-9) -------------------------------------------------------------
     t_phase.start();
     float *Bcur = B, *Wcur = W;
+    int iters = 0, quiet = 0;
     for (int t = 0; t < T; ++t) {
         const float rf = (float)hrho[t], rf_next = (float)hrho[t + 1];
         if (t == 0)
@@ -1230,12 +1240,23 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             const admmq_layer &l = L[i];
             ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur + off[i], V[i], n, l.p, f.d, f.inv_d, l.bits, grp[i], l.scales,
                                            inv_scales[i], l.zeros, rf, 1.0f / rf, 1.0f / rf_next,
-                                           last ? l.codes : nullptr, 0, Wcur + off[i], res[i] + t, nullptr, P));
+                                           (last || quiet_stop > 0) ? l.codes : nullptr, quiet_stop > 0 ? 1 : 0,
+                                           Wcur + off[i], res[i] + t,
+                                           quiet_stop > 0 ? flips + (size_t)t * count + i : nullptr, P));
         }
         admmq_prof_end(ctx, sp);
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;
+        iters = t + 1;
+        if (quiet_stop > 0 && t >= 1) {
+            std::vector<unsigned long long> changed((size_t)count);
+            ADMMQ_TRY(read_back(ctx, changed.data(), flips + (size_t)t * count, (size_t)count * 8));
+            bool still = true;
+            for (int i = 0; i < count; ++i) still = still && changed[i] == 0;
+            quiet = still ? quiet + 1 : 0;
+            if (quiet >= quiet_stop) break;
+        }
     }
     float ms_admm = t_phase.stop();
 
@@ -1243,7 +1264,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
         for (int i = 0; i < count; ++i) {
             const admmq_layer &l = L[i];
             admmq_stats &st = stats[i];
-            st.iters_done = T;
+            st.iters_done = iters;
             st.lambda = lambda;
             st.refresh_accepted = 0;
             st.refresh_err_old = st.refresh_err_new = 0.0;
@@ -1412,7 +1433,7 @@ extern "C" admmq_status admmq_quantize_layers(admmq_ctx *ctx, const float *H, in
         P += l.p;
     }
     if (P > (1 << 24)) return ADMMQ_ERR_SHAPE;
-    if (!schedule_ok(sched) || sched->refresh_iter != -1 || sched->quiet_stop != 0) return ADMMQ_ERR_PARAM;
+    if (!schedule_ok(sched) || sched->refresh_iter != -1) return ADMMQ_ERR_PARAM;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
     return admmq_guarded([&] { return quantize_many_core(ctx, H, n, layers, count, sched, stats); });

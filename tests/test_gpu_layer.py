@@ -501,3 +501,24 @@ def test_quiet_stop_returns_the_codes_of_the_full_run(ctx, n, p, bits, g, seed):
     # without the history arrays the rule works the same way
     plain = ctx.quantize_layer(Hd_, W0d, bits, g, admmq.Schedule(T=T, ls_rounds=1, ls_pairs=16, seed=seed, quiet_stop=K))
     assert plain[3].iters_done == it and torch.equal(plain[0], full[0])
+
+
+def test_quiet_stop_in_the_batched_call(ctx):
+    """Several matrices in one call with the stopping rule: the loop ends once no matrix has changed a code for K
+    iterations, i.e. at the latest of the iterations at which each would stop alone; every matrix gets the codes of
+    its own full run."""
+    import paper_2605_11222_amd as admmq
+    n, T, K = 192, 160, 6
+    X, Wa = correlated_problem(n, 64, 800, 90, outliers=2)
+    _, Wb = correlated_problem(n, 50, 800, 91)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    Ws, bits, gs = [to_dev(Wa), to_dev(Wb)], [3, 2], [64, 0]
+    full = [ctx.quantize_layer(H, W, b, g, admmq.Schedule(T=T, ls_rounds=0)) for W, b, g in zip(Ws, bits, gs)]
+    alone = [ctx.quantize_layer(H, W, b, g, admmq.Schedule(T=T, ls_rounds=0, quiet_stop=K)) for W, b, g in zip(Ws, bits, gs)]
+    both = ctx.quantize_layers(H, Ws, bits, gs, admmq.Schedule(T=T, ls_rounds=0, quiet_stop=K))
+    its = [a[3].iters_done for a in alone]
+    print("stopped alone after", its, "iterations; together after", both[0][3].iters_done)
+    assert both[0][3].iters_done == both[1][3].iters_done == max(its) < T
+    for got, f in zip(both, full):
+        assert torch.equal(got[0], f[0]) and torch.equal(got[1], f[1]) and torch.equal(got[2], f[2])
+        assert got[3].j_damp == pytest.approx(f[3].j_damp, rel=1e-9)

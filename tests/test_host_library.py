@@ -152,7 +152,7 @@ def test_batched_layers_argument_validation_without_a_gpu(lib):
     with_refresh = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, 5, 0, 0, 0.8, 0, 0)
     assert q([good, wide], sched=with_refresh) == 3                       # the refresh is a per-matrix decision
     with_stop = binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0, 3)
-    assert q([good, wide], sched=with_stop) == 3                          # ... and so is stopping early
+    assert q([good, wide], sched=with_stop) == 8                          # stopping early is allowed (joint rule)
     assert lib.admmq_quantize_layers(h, C.c_void_p(one), 8, None, 1, C.byref(sched), None) == 1
     lib.admmq_destroy(h)
 
