@@ -72,7 +72,7 @@ admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const
 /* ---- whole layer (Alg. 1) ----------------------------------------------------------------- */
 
 typedef struct {
-    int32_t T;             /* ADMM iterations, run exactly (paper: 300)                      */
+    int32_t T;             /* ADMM iterations, run exactly unless quiet_stop is set (paper: 300) */
     double rho0;           /* initial penalty (paper: 0.1)                                   */
     double gamma;          /* growth factor > 1, or exactly 1 for a fixed penalty (paper: 1.1) */
     double damp;           /* lambda = damp * Tr(H)/n added to the diagonal (paper App. D: 0.01) */
