@@ -503,6 +503,8 @@ extern "C" void admmq_destroy(admmq_ctx *ctx) {
                 (void)hipStreamDestroy(st);
             }
         if (ctx->side_ready) (void)hipEventDestroy(ctx->side_ready);
+        for (int i = 0; i < ctx->panel_event_count; ++i) (void)hipEventDestroy(ctx->panel_events[i]);
+        free(ctx->panel_events);
         if (ctx->arena && ctx->arena_owned) (void)hipFree(ctx->arena);
     }
     free(ctx->prof.spans);

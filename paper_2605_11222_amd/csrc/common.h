@@ -60,6 +60,10 @@ struct admmq_ctx {
     // streams (default priority) on which independent local searches of one batched call run side by side
     hipStream_t side[3] = {nullptr, nullptr, nullptr};
     hipEvent_t side_ready = nullptr;
+    // events that order the accumulation of Q (on side[0]) after the panels of the factorisation: created on
+    // first use, kept for the context's lifetime
+    hipEvent_t *panel_events = nullptr;
+    int panel_event_count = 0;
 };
 
 // Returns a span index (or -1 when profiling is off); call admmq_prof_end with it after the launch.

@@ -733,50 +733,55 @@ __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__r
 // Gp[s][j][c] = sum over slice s of i of R[j][i] v_c[i]  for rows j >= k0+1 (the slices of the
 // contraction index give the chip enough blocks; they are added in a fixed order by the consumer).
 // Block: 64 rows x NB columns on the fp64 matrix cores (v_mfma_f64_16x16x4), one 16-row strip per wave.
-// grid (ceil((n-k0-1)/64), KS).
+// grid: any number of blocks up to row_tiles * ks.
 constexpr int WY_KS_MAX = 16;
 __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ R, const double *__restrict__ A,
                                                      long n, long k0, int nbc, long chunk,
-                                                     double *__restrict__ Gp) {
+                                                     double *__restrict__ Gp, long jstart, int row_tiles, int ks) {
     constexpr int KC = 32;
     __shared__ double Rs[64][KC + 1];
     __shared__ double Vs[NB][KC + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
-    const long j0 = k0 + 1 + (long)blockIdx.x * 64;
-    const long ibeg = k0 + 1 + (long)blockIdx.y * chunk;
-    const long iend = min(n, ibeg + chunk);
-    // wave w owns rows 16w..16w+15 of the block, both halves of the NB columns: two 16 x 16 accumulators
-    doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-    for (long i0 = ibeg; i0 < iend; i0 += KC) {
-        __syncthreads();
-        for (int e = tid; e < 64 * KC; e += 256) {
-            const int r = e / KC, q = e % KC;
-            const long j = j0 + r, i = i0 + q;
-            Rs[r][q] = (j < n && i < iend) ? R[j * n + i] : 0.0;
-        }
-        for (int e = tid; e < NB * KC; e += 256) {
-            const int c = e / KC, q = e % KC;
-            const long i = i0 + q;
-            Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
-        }
-        __syncthreads();
+    // (row block, slice) pairs are walked with the grid's stride: a launch with few blocks leaves the rest of the
+    // chip to the stream it runs beside
+    for (long id = blockIdx.x; id < (long)row_tiles * ks; id += gridDim.x) {
+        const long bx = id % row_tiles, by = id / row_tiles;
+        const long j0 = jstart + bx * 64;           // first row of the block (rows jstart .. n-1)
+        const long ibeg = k0 + 1 + by * chunk;
+        const long iend = min(n, ibeg + chunk);
+        // wave w owns rows 16w..16w+15 of the block, both halves of the NB columns: two 16 x 16 accumulators
+        doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+        for (long i0 = ibeg; i0 < iend; i0 += KC) {
+            __syncthreads();
+            for (int e = tid; e < 64 * KC; e += 256) {
+                const int r = e / KC, q = e % KC;
+                const long j = j0 + r, i = i0 + q;
+                Rs[r][q] = (j < n && i < iend) ? R[j * n + i] : 0.0;
+            }
+            for (int e = tid; e < NB * KC; e += 256) {
+                const int c = e / KC, q = e % KC;
+                const long i = i0 + q;
+                Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
+            }
+            __syncthreads();
 #pragma unroll
-        for (int q = 0; q < KC; q += 4) {
-            // matrix-core operands: A[row = lane%16][k = lane/16], B[k = lane/16][col = lane%16]
-            const double a = Rs[wave * 16 + l16][q + lq];
-            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[l16][q + lq], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[16 + l16][q + lq], acc1, 0, 0, 0);
+            for (int q = 0; q < KC; q += 4) {
+                // matrix-core operands: A[row = lane%16][k = lane/16], B[k = lane/16][col = lane%16]
+                const double a = Rs[wave * 16 + l16][q + lq];
+                acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[l16][q + lq], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[16 + l16][q + lq], acc1, 0, 0, 0);
+            }
         }
-    }
-    // accumulator register r of lane l holds row 4r + l/16, column l%16 of its 16 x 16 block
-    double *out = Gp + (long)blockIdx.y * n * NB;
+        // accumulator register r of lane l holds row 4r + l/16, column l%16 of its 16 x 16 block
+        double *out = Gp + by * n * NB;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const long j = j0 + wave * 16 + 4 * r + lq;
-        if (j < n) {
-            out[j * NB + l16] = acc0[r];
-            out[j * NB + 16 + l16] = acc1[r];
+        for (int r = 0; r < 4; ++r) {
+            const long j = j0 + wave * 16 + 4 * r + lq;
+            if (j < n) {
+                out[j * NB + l16] = acc0[r];
+                out[j * NB + 16 + l16] = acc1[r];
+            }
         }
     }
 }
@@ -786,12 +791,12 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
 // One thread per (row, c); block 256 = 8 rows.
 __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__ Gp, const double *__restrict__ T,
                                                       long n, long k0, int nbc, int ks,
-                                                      double *__restrict__ G2) {
+                                                      double *__restrict__ G2, long jstart, int forward) {
     __shared__ double Ts[NB][NB + 1];
     __shared__ double Gs[8][NB + 1];
     const int tid = threadIdx.x, c = tid & (NB - 1), r = tid / NB;
     for (int e = tid; e < NB * NB; e += 256) Ts[e / NB][e % NB] = T[e];
-    const long j = k0 + 1 + (long)blockIdx.x * 8 + r;
+    const long j = jstart + (long)blockIdx.x * 8 + r;
     double g = 0.0;
     if (j < n && c < nbc)
         for (int s = 0; s < ks; ++s) g += Gp[((long)s * n + j) * NB + c];
@@ -799,7 +804,11 @@ __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__
     __syncthreads();
     if (j < n) {
         double t = 0.0;
-        for (int q = c; q < nbc; ++q) t += Gs[r][q] * Ts[c][q];          // T is upper triangular
+        if (forward) {
+            for (int q = 0; q <= c && q < nbc; ++q) t += Gs[r][q] * Ts[q][c];      // (G T)[c]
+        } else {
+            for (int q = c; q < nbc; ++q) t += Gs[r][q] * Ts[c][q];      // (G T^T)[c]; T is upper triangular
+        }
         G2[j * NB + c] = t;
     }
 }
@@ -808,53 +817,58 @@ __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__
 // matrix cores: wave w owns rows 16w..16w+15 of the tile, four 16-column blocks, NB/4 steps each.
 __global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R, const double *__restrict__ A,
                                                           long n, long k0, int nbc,
-                                                          const double *__restrict__ G2) {
+                                                          const double *__restrict__ G2, long jstart, int col_tiles,
+                                                          int row_tiles) {
     __shared__ double G2s[64][NB + 1];
     __shared__ double Vs[NB][80];          // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
     const int tid = threadIdx.x;
-    const long j0 = k0 + 1 + (long)blockIdx.y * 64, i0 = k0 + 1 + (long)blockIdx.x * 64;
-    for (int e = tid; e < 64 * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        const long j = j0 + r;
-        G2s[r][c] = (j < n && c < nbc) ? G2[j * NB + c] : 0.0;
-    }
-    for (int e = tid; e < NB * 64; e += 256) {
-        const int c = e >> 6, o = e & 63;
-        const long i = i0 + o;
-        Vs[c][o] = (c < nbc && i < n && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
-    }
-    const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
-    // the tile's own entries are requested before the operands are waited for
-    double rv[4][4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const long j = j0 + wave * 16 + 4 * r + lq;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const long i = i0 + b * 16 + l16;
-            rv[r][b] = (j < n && i < n) ? R[j * n + i] : 0.0;
+    for (long id = blockIdx.x; id < (long)col_tiles * row_tiles; id += gridDim.x) {
+        const long bx = id % col_tiles, by = id / col_tiles;
+        const long j0 = jstart + by * 64, i0 = k0 + 1 + bx * 64;
+        for (int e = tid; e < 64 * NB; e += 256) {
+            const int r = e / NB, c = e % NB;
+            const long j = j0 + r;
+            G2s[r][c] = (j < n && c < nbc) ? G2[j * NB + c] : 0.0;
         }
-    }
-    __syncthreads();
-    doublex4 acc[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) acc[b] = doublex4{0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int c = 0; c < NB; c += 4) {
-        const double g = G2s[wave * 16 + l16][c + lq];
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-            acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(g, Vs[c + lq][b * 16 + l16], acc[b], 0, 0, 0);
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const long j = j0 + wave * 16 + 4 * r + lq;
-        if (j >= n) continue;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const long i = i0 + b * 16 + l16;
-            if (i < n) R[j * n + i] = rv[r][b] - acc[b][r];
+        for (int e = tid; e < NB * 64; e += 256) {
+            const int c = e >> 6, o = e & 63;
+            const long i = i0 + o;
+            Vs[c][o] = (c < nbc && i < n && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
         }
+        const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+        // the tile's own entries are requested before the operands are waited for
+        double rv[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const long j = j0 + wave * 16 + 4 * r + lq;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const long i = i0 + b * 16 + l16;
+                rv[r][b] = (j < n && i < n) ? R[j * n + i] : 0.0;
+            }
+        }
+        __syncthreads();
+        doublex4 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[b] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int c = 0; c < NB; c += 4) {
+            const double g = G2s[wave * 16 + l16][c + lq];
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(g, Vs[c + lq][b * 16 + l16], acc[b], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const long j = j0 + wave * 16 + 4 * r + lq;
+            if (j >= n) continue;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const long i = i0 + b * 16 + l16;
+                if (i < n) R[j * n + i] = rv[r][b] - acc[b][r];
+            }
+        }
+        __syncthreads();                   // the next tile refills the two LDS arrays
     }
 }
 
@@ -911,6 +925,71 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
            *G2 = cnt + 64, *Pb = G2 + (long)NB * N;
     unsigned *counters = (unsigned *)cnt;          // [0]: tri_row, [2]: tri_mat (8-byte slots)
     const long sym_min = symv_min_size();
+    // One block of NB reflectors applied to the accumulated matrix M (compact WY): M <- M (I - V T' V^T) on rows
+    // jstart .. n-1 and columns k0+1 .. n-1; T' = T^T when R = Q^T is built from the last block to the first,
+    // T' = T when Q is built from the first block on.
+    auto apply_block = [&](hipStream_t s2, long k0, int nbc, long jstart, int forward, long cap) {
+        hipLaunchKernelGGL(q_gram_kernel, dim3(nbc, nbc), dim3(256), 0, s2, A64, N, k0, nbc, S);
+        hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, s2, S, tau, k0, nbc, T);
+        const long m = N - k0 - 1;                 // length of the contraction
+        const long rows = N - jstart;
+        const unsigned row_tiles = blocks_for(rows, 64), col_tiles = blocks_for(m, 64);
+        long ks = (2048 + (long)row_tiles - 1) / (long)row_tiles;      // eight blocks per compute unit or more
+        if (ks > WY_KS_MAX) ks = WY_KS_MAX;
+        if (ks > m / 256) ks = m / 256;
+        if (ks < 1) ks = 1;
+        long chunk = (m + ks - 1) / ks;
+        chunk = (chunk + 31) / 32 * 32;
+        const long g_blocks = (long)row_tiles * ks, u_blocks = (long)col_tiles * row_tiles;
+        hipLaunchKernelGGL(q_wy_g_kernel, dim3((unsigned)(cap > 0 && g_blocks > cap ? cap : g_blocks)), dim3(256), 0, s2,
+                           R64, A64, N, k0, nbc, chunk, Gp, jstart, (int)row_tiles, (int)ks);
+        hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(rows, 8)), dim3(256), 0, s2, Gp, T, N, k0, nbc, (int)ks, G2,
+                           jstart, forward);
+        hipLaunchKernelGGL(q_wy_update_kernel, dim3((unsigned)(cap > 0 && u_blocks > cap ? cap : u_blocks)), dim3(256), 0,
+                           s2, R64, A64, N, k0, nbc, G2, jstart, (int)col_tiles, (int)row_tiles);
+    };
+    // While the trailing matrix fits the caches the panel chain above is bound by launch and memory latency and
+    // leaves the chip mostly idle: Q = H_0 H_1 ... is then accumulated from the first block on (2 n^3 flop instead of
+    // the (4/3) n^3 of the backward order), each block as soon as its panel is finished, on a stream of its own.
+    // ADMMQ_Q_OVERLAP=0 keeps the backward order on the main stream.
+    bool overlap = N >= 3 && N < sym_min;
+    {
+        const char *e = getenv("ADMMQ_Q_OVERLAP");
+        if (e && atoi(e) == 0) overlap = false;
+    }
+    // blocks per side-stream launch of the two products: few enough to leave the panel chain its compute units
+    long side_cap = 96;
+    {
+        const char *e = getenv("ADMMQ_Q_SIDE_BLOCKS");
+        if (e && atol(e) > 0) side_cap = atol(e);
+    }
+    const long nblk_all = N >= 3 ? (N - 2 + NB - 1) / NB : 0;
+    hipStream_t side = nullptr;
+    if (overlap) {
+        if (!ctx->side[0] && hipStreamCreateWithFlags(&ctx->side[0], hipStreamNonBlocking) != hipSuccess) overlap = false;
+        side = ctx->side[0];
+    }
+    if (overlap && ctx->panel_event_count < nblk_all + 2) {
+        const int want = (int)nblk_all + 2;
+        hipEvent_t *grown = (hipEvent_t *)realloc(ctx->panel_events, (size_t)want * sizeof(hipEvent_t));
+        if (!grown) overlap = false;
+        else {
+            ctx->panel_events = grown;
+            while (ctx->panel_event_count < want) {
+                if (hipEventCreateWithFlags(&ctx->panel_events[ctx->panel_event_count], hipEventDisableTiming) != hipSuccess) {
+                    overlap = false;
+                    break;
+                }
+                ++ctx->panel_event_count;
+            }
+        }
+    }
+    if (overlap) {
+        // the side stream starts behind everything queued so far (R64 and the scratch may still be in use)
+        ADMMQ_HIP(hipEventRecord(ctx->panel_events[nblk_all], st));
+        ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[nblk_all], 0));
+        hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, side, R64, N);
+    }
     bool was_sym = false;
     int parts_prev = 0;                            // block partials of p'.v left by the previous column's product
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, cnt, 0, 32));
@@ -953,6 +1032,13 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
             hipLaunchKernelGGL(tri_row_kernel, dim3(blocks_for(N - r0, ROW_CHUNK)), dim3(256), 0, st, A64, N, r0, nbc,
                                1, 0, Vp, Wp, pbuf, xbuf, tau, ta, tb, sc, part1, counters, part2, parts_prev,
                                sym ? 1 : 0, 1);
+            if (overlap) {
+                // the panel's reflectors (rows k0 .. r0-1 of A) and taus are final: its block joins Q
+                const long b = k0 / NB;
+                ADMMQ_HIP(hipEventRecord(ctx->panel_events[b], st));
+                ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[b], 0));
+                apply_block(side, k0, nbc, 1, 1, side_cap);
+            }
             const unsigned tiles = blocks_for(N - r0, 64);
             hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, nbc, Vp, Wp,
                                sym ? 1 : 0);
@@ -964,31 +1050,25 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
         hipLaunchKernelGGL(tri_tail_kernel, dim3(1), dim3(64), 0, st, A64, N, ta, tb);
     }
     ADMMQ_HIP(hipGetLastError());
-    hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, R64, N);
-    if (N >= 3) {
-        const long nref = N - 2;
-        const long nblk = (nref + NB - 1) / NB;
-        for (long b = nblk - 1; b >= 0; --b) {
-            const long k0 = b * NB;
-            const int nbc = (int)((nref - k0) < NB ? (nref - k0) : NB);
-            hipLaunchKernelGGL(q_gram_kernel, dim3(nbc, nbc), dim3(256), 0, st, A64, N, k0, nbc, S);
-            hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, st, S, tau, k0, nbc, T);
-            const long m = N - k0 - 1;
-            const unsigned tiles = blocks_for(m, 64);
-            long ks = (2048 + (long)tiles - 1) / (long)tiles;      // eight blocks per compute unit or more
-            if (ks > WY_KS_MAX) ks = WY_KS_MAX;
-            if (ks > m / 256) ks = m / 256;
-            if (ks < 1) ks = 1;
-            long chunk = (m + ks - 1) / ks;
-            chunk = (chunk + 31) / 32 * 32;
-            hipLaunchKernelGGL(q_wy_g_kernel, dim3(tiles, (unsigned)ks), dim3(256), 0, st, R64, A64, N, k0, nbc, chunk,
-                               Gp);
-            hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(m, 8)), dim3(256), 0, st, Gp, T, N, k0, nbc, (int)ks, G2);
-            hipLaunchKernelGGL(q_wy_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, R64, A64, N, k0, nbc, G2);
-        }
-    }
     dim3 tb32(32, 8), tg((unsigned)((N + 31) / 32), (unsigned)((N + 31) / 32));
-    hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
+    if (overlap) {
+        // R64 holds Q: the main stream waits for the last block, then writes Q as stored and Q^T transposed
+        ADMMQ_HIP(hipEventRecord(ctx->panel_events[nblk_all + 1], side));
+        ADMMQ_HIP(hipStreamWaitEvent(st, ctx->panel_events[nblk_all + 1], 0));
+        hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Qt, Q);
+    } else {
+        hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, R64, N);
+        if (N >= 3) {
+            const long nref = N - 2;
+            const long nblk = (nref + NB - 1) / NB;
+            for (long b = nblk - 1; b >= 0; --b) {
+                const long k0 = b * NB;
+                const int nbc = (int)((nref - k0) < NB ? (nref - k0) : NB);
+                apply_block(st, k0, nbc, k0 + 1, 0, 0);
+            }
+        }
+        hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
+    }
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
