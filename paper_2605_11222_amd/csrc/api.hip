@@ -562,6 +562,53 @@ extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64
     if (rows == 0) return ADMMQ_OK;
     if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
     ADMMQ_HIP(hipSetDevice(ctx->device));
+    // bf16 activations in whole 256-channel tiles: the bf16 matrix cores (products exact, fp32 accumulation)
+    static int bf16_cores = -1;
+    if (bf16_cores < 0) {
+        const char *e = getenv("ADMMQ_HESSIAN_BF16");
+        bf16_cores = e ? atoi(e) : 1;
+    }
+    if (xdt == ADMMQ_BF16 && bf16_cores && admmq_hessian_bf16_ok(X, n, ldx, rows)) {
+        const int64_t k_main = admmq_hessian_bf16_main_rows(rows), k_tail = rows - k_main;
+        const int64_t tm = n / 256, tiles = tm * (tm + 1) / 2;
+        const size_t slice = (size_t)n * n;
+        // Slices of the token axis: each XCD takes an eighth of the (slice, tile) list and runs it 32 blocks at a
+        // time; more slices fill the last round better, fewer leave less partial-sum traffic (written and read
+        // once, lower triangle only).  Both in seconds, from round numbers for this chip.
+        int64_t split = 1;
+        double best = 1e300;
+        for (int64_t sp = 1; sp <= 64 && sp * 256 <= k_main + 255; ++sp) {
+            if (sp > 1 && sp * slice * 4 > ((size_t)8 << 30)) break;
+            const int64_t per_xcd = (tiles * sp + 7) / 8, rounds = (per_xcd + 31) / 32;
+            const double t_mma = (double)rounds * (double)((k_main + sp - 1) / sp) * 131072.0 / 4.0e12;
+            const double t_sum = (double)sp * (double)slice * 4.0 / 4.0e12;
+            if (t_mma + t_sum < best) {
+                best = t_mma + t_sum;
+                split = sp;
+            }
+        }
+        const int64_t slices = split + (k_tail > 0 ? 1 : 0);
+        admmq_arena_reset_transient(ctx);
+        ADMMQ_TRY(admmq_arena_reserve(ctx, (size_t)slices * admmq_align_up(slice * 4) + 4096));
+        float *P = nullptr;
+        ADMMQ_TRY(take(ctx, P, (size_t)slices * slice));
+        ADMMQ_TRY(admmq_hessian_bf16(ctx, X, ldx, k_main, n, P, (int)split, (int64_t)slice));
+        if (k_tail > 0) {
+            // the last tokens (fewer than a stage) through the fp32 product, as one more slice
+            gemm_tn_args g = {};
+            g.A = g.B = (const unsigned short *)X + k_main * ldx;
+            g.lda = g.ldb = ldx;
+            g.a_bf16 = g.b_bf16 = 1;
+            g.M = n; g.N = n; g.K = k_tail; g.alpha = 1.f; g.beta = 0.f; g.Z = nullptr;
+            g.out = P + (size_t)split * slice; g.ldo = n; g.lower_only = 1; g.split_k = 1;
+            g.slice_stride = (int64_t)slice;
+            ADMMQ_TRY(admmq_gemm_tn(ctx, g));
+        }
+        ADMMQ_TRY(admmq_sym_reduce(ctx, H, n, P, (int)slices, (int64_t)slice, 1));
+        if (n_samples) *n_samples += (uint64_t)rows;
+        admmq_arena_reset_transient(ctx);
+        return ADMMQ_OK;
+    }
     // split the token axis so that the triangular tile set fills the chip a few times over
     const int64_t t256 = (n + 255) / 256, t128 = (n + 127) / 128, t64 = (n + 63) / 64;
     int64_t tiles = t256 * (t256 + 1) / 2;

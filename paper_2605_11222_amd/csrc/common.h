@@ -98,6 +98,12 @@ struct gemm_tn_args {
     int64_t slice_stride;
 };
 admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a);
+// bf16 matrix-core path of the Hessian (hessian_bf16.hip): usable when n is a multiple of 256, rows of X are 16-byte
+// aligned and there is at least one 32-token stage; handles the first main_rows(rows) tokens.
+bool admmq_hessian_bf16_ok(const void *X, int64_t n, int64_t ldx, int64_t rows);
+int64_t admmq_hessian_bf16_main_rows(int64_t rows);
+admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int64_t k_main, int64_t n, float *P,
+                                int split, int64_t slice_stride);
 // H[i][j] (+)= sum_s P[s][i][j] for i >= j and mirrors the result into the upper triangle.
 admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
                               int64_t slice_stride, int accumulate);

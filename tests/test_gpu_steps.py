@@ -28,11 +28,15 @@ def ctx():
 # ---------------------------------------------------------------------------------------------
 # Hessian accumulation
 # ---------------------------------------------------------------------------------------------
-# the last three shapes are whole tiles and whole k-stages in both chunks: the direct-load path, for bf16 with the
-# operands kept as bf16 in LDS
+# (256, 96, f32) and (384, 1536, bf16) are whole tiles and whole k-stages in both chunks: the direct-load path of the
+# fp32 matrix cores, for bf16 with the operands kept as bf16 in LDS; bf16 with n a multiple of 256 goes to the bf16
+# matrix cores: whole stages only, with a tail of fewer than 32 tokens, a chunk too short for a stage, several
+# token slices
 @pytest.mark.parametrize("n,rows,dtype", [(128, 512, "f32"), (200, 333, "f32"), (384, 1000, "bf16"),
                                            (1030, 777, "bf16"), (64, 1, "f32"), (1, 5, "f32"),
-                                           (512, 1536, "bf16"), (1024, 3072, "bf16"), (256, 96, "f32")])
+                                           (512, 1536, "bf16"), (1024, 3072, "bf16"), (256, 96, "f32"),
+                                           (384, 1536, "bf16"), (768, 1003, "bf16"), (256, 70, "bf16"),
+                                           (2304, 4500, "bf16")])
 def test_hessian_accumulate_matches_float64(ctx, n, rows, dtype):
     rng = np.random.default_rng(n + rows)
     X = (rng.standard_normal((rows, n)) * np.exp(rng.standard_normal(n))).astype(np.float32)
