@@ -44,13 +44,6 @@ struct HessParams {
     long slice_stride;
 };
 
-__device__ inline void wait_loads(int later_stages) {
-    // outstanding direct loads allowed: those of `later_stages` younger stages (8 per stage and wave)
-    if (later_stages >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (later_stages == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
 __global__ __launch_bounds__(256, 1) void hessian_bf16_kernel(HessParams P) {
     extern __shared__ __attribute__((aligned(16))) unsigned char hb_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -80,25 +73,19 @@ __global__ __launch_bounds__(256, 1) void hessian_bf16_kernel(HessParams P) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // stage s of this block: tokens kbeg + 32 s .. +31; wave w brings chunks w, w+4, w+8, w+12 of both operands
+    // Stage s of this block: tokens kbeg + 32 s .. +31; wave w brings chunks w, w+4, w+8, w+12 of both operands.
+    // Stages past the slice's end are loaded all the same, from the last real stage's rows, into a ring buffer
+    // nobody reads any more: every stage then costs every wave eight loads, the loop has no branches and one
+    // constant in its wait for the loads.
     const unsigned short *gA = P.X + (kbeg + (lane >> 5)) * P.ldx + m0 + (lane & 31) * 8;
     const unsigned short *gB = P.X + (kbeg + (lane >> 5)) * P.ldx + n0 + (lane & 31) * 8;
-    auto issue = [&](int s) {
-        unsigned char *dst = hb_lds + (s % HB_STAGES) * HB_STAGE;
-        const long row = (long)s * HB_KT;
-#pragma unroll
-        for (int i = 0; i < HB_CHUNKS / 4; ++i) {
-            const int c = wave + 4 * i;
-            __builtin_amdgcn_global_load_lds(gA + (row + 2 * c) * P.ldx,
-                                             (__attribute__((address_space(3))) void *)(dst + c * HB_CHUNK), 16, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < HB_CHUNKS / 4; ++i) {
-            const int c = wave + 4 * i;
-            __builtin_amdgcn_global_load_lds(
-                gB + (row + 2 * c) * P.ldx,
-                (__attribute__((address_space(3))) void *)(dst + HB_OPERAND + c * HB_CHUNK), 16, 0, 0);
-        }
+    // load number i (0..3: operand A, 4..7: operand B) of stage s
+    auto load_one = [&](int s, int i) {
+        const long row = (long)min(s, nst - 1) * HB_KT;
+        unsigned char *dst = hb_lds + (s % HB_STAGES) * HB_STAGE + (i >> 2) * HB_OPERAND;
+        const int c = wave + 4 * (i & 3);
+        __builtin_amdgcn_global_load_lds(((i >> 2) ? gB : gA) + (row + 2 * c) * P.ldx,
+                                         (__attribute__((address_space(3))) void *)(dst + c * HB_CHUNK), 16, 0, 0);
     };
 
     // Transposing read: in every group of 16 lanes, source lane 4 j + q points at 8 bytes (4 channels) of token j;
@@ -108,29 +95,27 @@ __global__ __launch_bounds__(256, 1) void hessian_bf16_kernel(HessParams P) {
     //
     // The reads are written as assembly: a read the compiler can see is made to wait for EVERY outstanding
     // global -> LDS load (it cannot tell the ring's buffers apart), which would undo the ring.  The waits for the
-    // loads and for the reads are therefore placed by hand (wait_loads, frags_ready).
+    // loads and for the reads are therefore placed by hand (vmcnt below, frags_ready).
     const int grp = lane >> 4, jrow = (lane & 15) >> 2, q = lane & 3;
     const int lane_off = (4 * (grp >> 1) + jrow) * HB_CHUNK + (16 * (grp & 1) + 4 * q) * 2;
     const unsigned lds0 = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char *)hb_lds;
     const unsigned offA = lds0 + lane_off + wm * 256;      // 128 channels = 256 bytes per quadrant
     const unsigned offB = lds0 + HB_OPERAND + lane_off + wn * 256;
-#define HB_RD(dst, addr, off) \
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #off : "=v"(dst) : "v"(addr) : "memory")
-    // fragments of step KK (0 or 1) of the stage whose LDS byte offsets are pa (A side) and pb (B side)
-#define HB_READ_STEP(F, pa, pb, K0)                                                                    \
-    do {                                                                                               \
-        HB_RD(F.a[0][0], pa, K0 + 0);   HB_RD(F.a[0][1], pa, K0 + 512);                                \
-        HB_RD(F.a[1][0], pa, K0 + 64);  HB_RD(F.a[1][1], pa, K0 + 576);                                \
-        HB_RD(F.a[2][0], pa, K0 + 128); HB_RD(F.a[2][1], pa, K0 + 640);                                \
-        HB_RD(F.a[3][0], pa, K0 + 192); HB_RD(F.a[3][1], pa, K0 + 704);                                \
-        HB_RD(F.b[0][0], pb, K0 + 0);   HB_RD(F.b[0][1], pb, K0 + 512);                                \
-        HB_RD(F.b[1][0], pb, K0 + 64);  HB_RD(F.b[1][1], pb, K0 + 576);                                \
-        HB_RD(F.b[2][0], pb, K0 + 128); HB_RD(F.b[2][1], pb, K0 + 640);                                \
-        HB_RD(F.b[3][0], pb, K0 + 192); HB_RD(F.b[3][1], pb, K0 + 704);                                \
-    } while (0)
     struct Frags {
         uintx2 a[4][2], b[4][2];
     };
+#define HB_RD(dst, addr, off) \
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #off : "=v"(dst) : "v"(addr) : "memory")
+    // the two reads (tokens of even and of odd parity) that make sub-tile I's operand of the step at offset K0
+#define HB_RD2(X, I, addr, K0)                    \
+    do {                                          \
+        HB_RD(X[I][0], addr, K0 + 64 * I);        \
+        HB_RD(X[I][1], addr, K0 + 64 * I + 512);  \
+    } while (0)
+#define HB_FRAG(X) __builtin_bit_cast(bf16x8, __builtin_shufflevector(X[0], X[1], 0, 1, 2, 3))
+#define HB_MFMA(F, A_, B_) \
+    acc[A_][B_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HB_FRAG(F.a[A_]), HB_FRAG(F.b[B_]), acc[A_][B_], 0, 0, 0)
+#define HB_SB __builtin_amdgcn_sched_barrier(0)
     // every read issued so far has delivered; naming the registers ties the products that use them to this wait
     auto frags_ready = [](Frags &f) {
         asm volatile("s_waitcnt lgkmcnt(0)"
@@ -141,55 +126,65 @@ __global__ __launch_bounds__(256, 1) void hessian_bf16_kernel(HessParams P) {
                      :
                      : "memory");
     };
-    auto mfma_step = [&](const Frags &f) {
-        bf16x8 fa[4], fb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f.a[i][0], f.a[i][1], 0, 1, 2, 3));
-            fb[i] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f.b[i][0], f.b[i][1], 0, 1, 2, 3));
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-    };
 
     Frags f0, f1;
     if (nst > 0) {
-        for (int s = 0; s < HB_STAGES && s < nst; ++s) issue(s);
-        // stage 0 has landed once at most the loads of the (up to three) younger stages are outstanding
-        const int younger = min(HB_STAGES - 1, nst - 1);
-        if (younger >= 3) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else wait_loads(younger);
+        for (int s = 0; s < HB_STAGES; ++s)
+#pragma unroll
+            for (int i = 0; i < HB_LOADS; ++i) load_one(s, i);
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");   // stage 0 has landed: three younger stages may be out
         __syncthreads();
-        HB_READ_STEP(f0, offA, offB, 0);
+        HB_RD2(f0.a, 0, offA, 0); HB_RD2(f0.a, 1, offA, 0); HB_RD2(f0.a, 2, offA, 0); HB_RD2(f0.a, 3, offA, 0);
+        HB_RD2(f0.b, 0, offB, 0); HB_RD2(f0.b, 1, offB, 0); HB_RD2(f0.b, 2, offB, 0); HB_RD2(f0.b, 3, offB, 0);
     }
-    // Per stage: the second step's fragments are read while the matrix cores work on the first; then the wave
-    // waits for the next stage's loads, passes the barrier (after which this stage's buffer is free and is handed
-    // to the loads of the stage four ahead), requests the next stage's first fragments and only then issues the
-    // second step's products, so that neither the barrier nor the LDS latency leaves the pipe empty.
+    // Per stage, two steps of 16 products.  Everything else is issued in the shadow of the products, one piece
+    // after each: during the first step the reads of the second step's fragments; then the wave waits for the next
+    // stage's loads and passes the barrier (after which this stage's buffer is free); during the second step the
+    // reads of the next stage's first fragments and the eight loads of the stage four ahead into the freed buffer.
     for (int t = 0; t < nst; ++t) {
         const unsigned cur = (unsigned)((t % HB_STAGES) * HB_STAGE);
         const unsigned nxt = (unsigned)(((t + 1) % HB_STAGES) * HB_STAGE);
-        const unsigned pa = offA + cur, pb = offB + cur;
+        const unsigned pa = offA + cur, pb = offB + cur, na = offA + nxt, nb = offB + nxt;
         frags_ready(f0);
-        HB_READ_STEP(f1, pa, pb, 8704);                   // 8 chunks on: tokens 16..31 of the stage
-        mfma_step(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        const bool more = t + 1 < nst;
-        if (more) wait_loads(min(2, nst - 2 - t));
-        frags_ready(f1);                                   // (also: this wave no longer reads the stage's buffer)
+        HB_SB;
+        HB_MFMA(f0, 0, 0); HB_RD2(f1.a, 0, pa, 8704); HB_SB;      // 8 chunks on: tokens 16..31 of the stage
+        HB_MFMA(f0, 0, 1); HB_RD2(f1.b, 0, pb, 8704); HB_SB;
+        HB_MFMA(f0, 0, 2); HB_RD2(f1.b, 1, pb, 8704); HB_SB;
+        HB_MFMA(f0, 0, 3); HB_RD2(f1.b, 2, pb, 8704); HB_SB;
+        HB_MFMA(f0, 1, 0); HB_RD2(f1.b, 3, pb, 8704); HB_SB;
+        HB_MFMA(f0, 1, 1); HB_RD2(f1.a, 1, pa, 8704); HB_SB;
+        HB_MFMA(f0, 1, 2); HB_RD2(f1.a, 2, pa, 8704); HB_SB;
+        HB_MFMA(f0, 1, 3); HB_RD2(f1.a, 3, pa, 8704); HB_SB;
+        HB_MFMA(f0, 2, 0); HB_MFMA(f0, 2, 1); HB_MFMA(f0, 2, 2); HB_MFMA(f0, 2, 3);
+        HB_MFMA(f0, 3, 0); HB_MFMA(f0, 3, 1); HB_MFMA(f0, 3, 2); HB_MFMA(f0, 3, 3);
+        HB_SB;
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // stage t+1 has landed: stages t+2, t+3 may be out
+        frags_ready(f1);                                    // (also: this wave no longer reads stage t's buffer)
         __syncthreads();
-        if (t + HB_STAGES < nst) issue(t + HB_STAGES);
-        if (more) {
-            const unsigned na = offA + nxt, nb = offB + nxt;
-            HB_READ_STEP(f0, na, nb, 0);
-        }
-        mfma_step(f1);
-        __builtin_amdgcn_sched_barrier(0);
+        HB_SB;
+        HB_MFMA(f1, 0, 0); HB_RD2(f0.a, 0, na, 0); HB_SB;
+        HB_MFMA(f1, 0, 1); HB_RD2(f0.b, 0, nb, 0); HB_SB;
+        HB_MFMA(f1, 0, 2); HB_RD2(f0.b, 1, nb, 0); HB_SB;
+        HB_MFMA(f1, 0, 3); HB_RD2(f0.b, 2, nb, 0); HB_SB;
+        HB_MFMA(f1, 1, 0); HB_RD2(f0.b, 3, nb, 0); HB_SB;
+        HB_MFMA(f1, 1, 1); HB_RD2(f0.a, 1, na, 0); HB_SB;
+        HB_MFMA(f1, 1, 2); HB_RD2(f0.a, 2, na, 0); HB_SB;
+        HB_MFMA(f1, 1, 3); HB_RD2(f0.a, 3, na, 0); HB_SB;
+        HB_MFMA(f1, 2, 0); load_one(t + HB_STAGES, 0); HB_SB;
+        HB_MFMA(f1, 2, 1); load_one(t + HB_STAGES, 1); HB_SB;
+        HB_MFMA(f1, 2, 2); load_one(t + HB_STAGES, 2); HB_SB;
+        HB_MFMA(f1, 2, 3); load_one(t + HB_STAGES, 3); HB_SB;
+        HB_MFMA(f1, 3, 0); load_one(t + HB_STAGES, 4); HB_SB;
+        HB_MFMA(f1, 3, 1); load_one(t + HB_STAGES, 5); HB_SB;
+        HB_MFMA(f1, 3, 2); load_one(t + HB_STAGES, 6); HB_SB;
+        HB_MFMA(f1, 3, 3); load_one(t + HB_STAGES, 7); HB_SB;
     }
-#undef HB_READ_STEP
+    // nothing of the ring is in flight when the wave retires (the last stages' loads were never read)
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef HB_SB
+#undef HB_MFMA
+#undef HB_FRAG
+#undef HB_RD2
 #undef HB_RD
 
     // Accumulator register v of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4 and column l % 32 of its 32 x 32
