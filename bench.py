@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 import synth_inputs as si  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
 # calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
@@ -159,6 +160,10 @@ def main():
     lsa_gbs = 8.0 * n * p / (lsa_ms * 1e-3) / 1e9 if lsa_ms > 0 else 0.0    # one read + one write of G per flush
     hess_ms = float(np.mean(hs))
     hess_tf = tokens * n * (n + 1) / (hess_ms * 1e-3) / 1e12
+    # bf16 activations in whole 256-channel tiles are multiplied on the bf16 matrix cores (exact products, fp32
+    # accumulation) and priced against that peak; anything else goes through the fp32 product
+    hess_bf16 = cfg.x_dtype == "bf16" and n % 256 == 0 and os.environ.get("ADMMQ_HESSIAN_BF16", "1") != "0"
+    hess_peak = PEAK_BF16_MFMA_TFLOPS if hess_bf16 else PEAK_FP32_MFMA_TFLOPS
 
     line = {
         "metric": "layer quantize time (s) & ADMM iters/s, 4096x4096 W3; % fp32 MFMA peak",
@@ -186,8 +191,10 @@ def main():
         "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
                               "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
-        "roofline_hessian": {"kernel": "gemm_tn (Hessian, lower triangle)", "bound": "mfma", "achieved": hess_tf,
-                             "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": hess_tf / PEAK_FP32_MFMA_TFLOPS},
+        "roofline_hessian": {"kernel": ("hessian_bf16 + sym_reduce (bf16 matrix cores, lower triangle)" if hess_bf16
+                                        else "gemm_tn + sym_reduce (fp32 matrix cores, lower triangle)"),
+                             "bound": "mfma", "achieved": hess_tf, "peak": hess_peak, "unit": "TFLOP/s",
+                             "frac": hess_tf / hess_peak, "ms_per_call": hess_ms},
         "tridiag_ms_per_launch": tri_ms,
         "input_generation_s": gen_s,
     }
