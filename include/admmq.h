@@ -64,8 +64,11 @@ admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /* H [n][n] (device fp32, caller zero-initialises before the first chunk) += X^T X for a chunk
  * X [rows][ldx] (device; fp32 or bf16 bit patterns), ldx >= n.  Both triangles of H are kept
- * up to date.  *n_samples (host, may be NULL) += rows.  bf16 inputs are widened to fp32 on the way
- * into the fp32 matrix-core contraction, so every product is exact. */
+ * up to date.  *n_samples (host, may be NULL) += rows.  Every product is exact and is added in
+ * fp32: bf16 inputs with n a multiple of 256 and 16-byte aligned rows are contracted on the bf16 matrix
+ * cores (fp32 accumulation), any other input on the fp32 ones (bf16 widened on the way in).  Scratch: one
+ * [n][n] fp32 partial sum per token slice (the library picks the number of slices; in a caller's workspace
+ * as many as fit, at least one, else ADMMQ_ERR_WORKSPACE with H untouched). */
 admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const void *X,
                                       admmq_dtype xdt, int64_t rows, int64_t ldx, uint64_t *n_samples);
 

@@ -554,6 +554,16 @@ extern "C" admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_
 }
 
 // ---- Hessian -----------------------------------------------------------------------------------
+namespace {
+// Bytes the partial sums of the token slices may take: whatever it needs in an arena the library grows itself,
+// what is left beside a kept factorisation in a caller's workspace (fewer slices then; one always has to fit).
+size_t hessian_slice_room(const admmq_ctx *ctx) {
+    if (ctx->arena_owned || !ctx->arena) return ~(size_t)0;
+    const size_t used = ctx->persist_top + 8192;
+    return ctx->arena_bytes > used ? ctx->arena_bytes - used : 0;
+}
+}  // namespace
+
 extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const void *X,
                                                  admmq_dtype xdt, int64_t rows, int64_t ldx, uint64_t *n_samples) {
     if (!ctx || !H || !X) return ADMMQ_ERR_NULL;
@@ -577,8 +587,12 @@ extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64
         // once, lower triangle only).  Both in seconds, from round numbers for this chip.
         int64_t split = 1;
         double best = 1e300;
+        const size_t room = hessian_slice_room(ctx);
+        const size_t tail_slice = k_tail > 0 ? 1 : 0;
         for (int64_t sp = 1; sp <= 64 && sp * 256 <= k_main + 255; ++sp) {
-            if (sp > 1 && sp * slice * 4 > ((size_t)8 << 30)) break;
+            if (sp > 1 && (sp * slice * 4 > ((size_t)8 << 30) ||
+                           (sp + tail_slice) * admmq_align_up(slice * 4) + 4096 > room))
+                break;
             const int64_t per_xcd = (tiles * sp + 7) / 8, rounds = (per_xcd + 31) / 32;
             const double t_mma = (double)rounds * (double)((k_main + sp - 1) / sp) * 131072.0 / 4.0e12;
             const double t_sum = (double)sp * (double)slice * 4.0 / 4.0e12;
@@ -630,7 +644,9 @@ extern "C" admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64
     }
     // the partial slices must fit the arena: shrink the split for very large n
     const size_t slice = (size_t)n * n;
-    while (split > 1 && split * slice * 4 > ((size_t)8 << 30)) --split;
+    while (split > 1 && (split * slice * 4 > ((size_t)8 << 30) ||
+                         (size_t)split * admmq_align_up(slice * 4) + 4096 > hessian_slice_room(ctx)))
+        --split;
     admmq_arena_reset_transient(ctx);
     ADMMQ_TRY(admmq_arena_reserve(ctx, (size_t)split * admmq_align_up(slice * 4) + 4096));
     float *P = nullptr;

@@ -63,6 +63,44 @@ def test_hessian_accumulate_matches_float64(ctx, n, rows, dtype):
     assert np.max(np.abs(Hg - Href) / scale) < 2e-6 * np.sqrt(max(rows, 16) / 16)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_hessian_in_a_callers_workspace_takes_fewer_token_slices(dtype):
+    """A caller's workspace bounds the partial sums of the token slices: with room for two slices the result is the
+    one an arena of the library's own gives, up to the order of the additions; with room for none the call fails
+    with the workspace error and leaves H alone."""
+    n, rows = 512, 8192
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((rows, n)).astype(np.float32)
+    if dtype == "bf16":
+        bits = si.f32_to_bf16_bits(X)
+        Xd = bf16_bits_to_dev(bits)
+        X64 = si.bf16_bits_to_f32(bits).astype(np.float64)
+    else:
+        Xd = to_dev(X)
+        X64 = X.astype(np.float64)
+    Href = orc.hessian([X64])
+    import paper_2605_11222_amd as admmq
+    c = admmq.Context(0)
+    try:
+        ws = torch.empty(2 * n * n * 4 + 16384, dtype=torch.uint8, device="cuda")
+        c.set_workspace(ws)
+        H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+        assert c.accumulate_hessian(H, Xd) == rows
+        torch.cuda.synchronize()
+        scale = np.sqrt(np.outer(np.diag(Href), np.diag(Href)))
+        assert np.max(np.abs(H.cpu().numpy() - Href) / scale) < 2e-6 * np.sqrt(rows / 16)
+        tiny = torch.empty(n * n * 2, dtype=torch.uint8, device="cuda")
+        c.set_workspace(tiny)
+        H2 = torch.full((n, n), 7.0, dtype=torch.float32, device="cuda")
+        with pytest.raises(admmq.AdmmqError) as err:
+            c.accumulate_hessian(H2, Xd)
+        assert err.value.code == 6                                   # ADMMQ_ERR_WORKSPACE
+        torch.cuda.synchronize()
+        assert bool((H2 == 7.0).all())
+    finally:
+        c.close()
+
+
 def test_hessian_cfg1_from_the_shared_generator(ctx):
     cfg = si.CONFIGS["cfg1"]
     H = torch.zeros((cfg.n, cfg.n), dtype=torch.float32, device="cuda")
