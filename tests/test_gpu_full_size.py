@@ -69,6 +69,39 @@ def test_hessian_full_token_count_sampled_entries(ctx):
     print("max scaled Hessian error", np.max(np.abs(got - want) / diag))
 
 
+@pytest.mark.parametrize("name,tokens", [("cfg4", 8192), ("cfg5", 4096 + 17)])
+def test_hessian_at_the_large_workloads_widths_sampled_entries(ctx, name, tokens):
+    """n = 12288 and 25600 (1176 and 5050 lower-triangle tiles, few token slices; cfg5's count leaves a tail of 17
+    tokens for the fp32 product): entries from the first, the last and random tiles, on and off the diagonal."""
+    cfg = si.CONFIGS[name]
+    n = cfg.n
+    rng = np.random.default_rng(77)
+    edge = np.array([0, 255, 256, n - 257, n - 256, n - 1])
+    ii = np.concatenate([rng.integers(0, n, 60), edge, edge, rng.integers(n - 256, n, 8)])
+    jj = np.concatenate([rng.integers(0, n, 60), edge, edge[::-1], rng.integers(0, 256, 8)])
+    want = np.zeros(len(ii))
+    X = torch.empty((tokens, n), dtype=torch.bfloat16, device="cuda")
+    row = 0
+    for c, xc in si.iter_x_chunks(cfg, tokens):
+        x64 = si.chunk_as_f64(cfg, xc)
+        want += np.einsum("rk,rk->k", x64[:, ii], x64[:, jj])
+        X[row:row + xc.shape[0]] = bf16_bits_to_dev(xc)
+        row += xc.shape[0]
+        print(f"{name}: chunk {c}", flush=True)
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    assert ctx.accumulate_hessian(H, X) == tokens
+    torch.cuda.synchronize()
+    got = H[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy().astype(np.float64)
+    mirrored = H[torch.from_numpy(jj).cuda(), torch.from_numpy(ii).cuda()].cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, mirrored)
+    dg = torch.diagonal(H).cpu().numpy().astype(np.float64)
+    err = np.max(np.abs(got - want) / np.sqrt(dg[ii] * dg[jj]))
+    print("max scaled Hessian error", err)
+    assert err < 2e-6 * np.sqrt(tokens / 16)
+    del H, X
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name", ["cfg2", "cfg3"])
 def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
     import paper_2605_11222_amd as admmq
