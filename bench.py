@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--iters", type=int, default=0, help="ADMM iterations (0 = the workload's T)")
     ap.add_argument("--ls-rounds", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fast-products", action="store_true",
+                    help="time the opt-in split-fp16 W-update products instead of the fp32 ones (not the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path would shard over output columns without "
@@ -120,6 +122,8 @@ def main():
     gen_s = time.perf_counter() - t0
     H = torch.empty((cfg.n, cfg.n), dtype=torch.float32, device="cuda")
     ctx = admmq.Context(0)
+    if args.fast_products:
+        ctx.set_fast_products(True)
     sched = admmq.Schedule(T=T, ls_rounds=args.ls_rounds, seed=cfg.seed)
 
     def step(profile):

@@ -60,6 +60,18 @@ size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T);
 /* Optional: use caller memory (device, 256-byte aligned) as the scratch arena from now on. */
 admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
 
+/* Opt-in, per context, off by default (on = 1 / 0): the two products of every W-update (eq. 7) whose output is whole
+ * 256 x 256 tiles, at least 200 of them (n and the column count multiples of 256), run on the fp16 matrix cores.
+ * Each fp32 operand is scaled by a power of two and split into an fp16 pair hi + lo (22 bits); the product is
+ * hiA hiB + hiA loB + loA hiB, every term exact, accumulated in fp32.  Against the fp32 product this drops the
+ * operands' last two bits and the lo-lo term (about 3e-7 of a term, an order of magnitude below the fp32
+ * accumulation error both share): the W-update stays within the 1e-5 relative Frobenius bar, but results are not
+ * bit-identical to the default.  Applies to admmq_quantize_layer, admmq_quantize_layers and admmq_w_update on
+ * uniform grids; other shapes and the other formats keep the fp32 products.  Needs
+ * admmq_fast_products_bytes(n, p) more scratch than admmq_workspace_bytes (0 when the shape does not qualify). */
+admmq_status admmq_set_fast_products(admmq_ctx *ctx, int32_t on);
+size_t admmq_fast_products_bytes(int64_t n, int64_t p);
+
 /* ---- Hessian accumulation (Sec. 3.1: H = X^T X) ------------------------------------------- */
 
 /* H [n][n] (device fp32, caller zero-initialises before the first chunk) += X^T X for a chunk

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     load_library,
     sample_pair,
     workspace_bytes,
+    fast_products_bytes,
     EXPORTED_SYMBOLS,
     FORMAT_DUAL_GRID,
     FORMAT_CODEBOOK,

@@ -14,6 +14,7 @@ EXPORTED_SYMBOLS = [
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
     "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit", "admmq_grid_init_dual",
     "admmq_project_dual_format", "admmq_quantize_layer_format", "admmq_quantize_layers",
+    "admmq_set_fast_products", "admmq_fast_products_bytes",
 ]
 
 FORMAT_DUAL_GRID, FORMAT_CODEBOOK = 1, 2
@@ -84,6 +85,9 @@ def load_library():
     lib.admmq_workspace_bytes.argtypes = [i64, i64, i32]
     lib.admmq_workspace_bytes.restype = C.c_size_t
     lib.admmq_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    lib.admmq_set_fast_products.argtypes = [vp, i32]
+    lib.admmq_fast_products_bytes.argtypes = [i64, i64]
+    lib.admmq_fast_products_bytes.restype = C.c_size_t
     lib.admmq_accumulate_hessian.argtypes = [vp, vp, i64, vp, C.c_int, i64, i64, C.POINTER(C.c_uint64)]
     lib.admmq_quantize_layer.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, C.POINTER(_Schedule), vp, vp, vp,
                                          C.POINTER(_Stats)]
@@ -110,7 +114,8 @@ def load_library():
                                        C.POINTER(dbl), C.POINTER(dbl)]
     for name in EXPORTED_SYMBOLS:
         fn = getattr(lib, name)
-        if name not in ("admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_sample_pair"):
+        if name not in ("admmq_destroy", "admmq_status_string", "admmq_workspace_bytes", "admmq_sample_pair",
+                        "admmq_fast_products_bytes"):
             fn.restype = C.c_int
     _LIB = lib
     return lib
@@ -123,6 +128,10 @@ def _check(code: int):
 
 def workspace_bytes(n: int, p: int, T: int) -> int:
     return int(load_library().admmq_workspace_bytes(n, p, T))
+
+
+def fast_products_bytes(n: int, p: int) -> int:
+    return int(load_library().admmq_fast_products_bytes(n, p))
 
 
 def sample_pair(seed: int, rnd: int, batch: int, slot: int, n: int):
@@ -216,6 +225,9 @@ class Context:
         self.close()
 
     # -- entry points (names follow include/admmq.h without the prefix) ------------------------
+    def set_fast_products(self, on: bool):
+        _check(self._lib.admmq_set_fast_products(self._h, 1 if on else 0))
+
     def set_workspace(self, buf):
         _check(self._lib.admmq_set_workspace(self._h, _ptr(buf), buf.numel() * buf.element_size()))
         self._ws = buf

@@ -272,11 +272,56 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
     return ADMMQ_OK;
 }
 
+// Opt-in fast products (admmq_set_fast_products): Q and Q^T split into fp16 pairs once per call, the state operand
+// before each product; all of it in the call's transient arena.
+struct FastBufs {
+    void *Q1 = nullptr, *Q2 = nullptr, *Qt1 = nullptr, *Qt2 = nullptr, *O1 = nullptr, *O2 = nullptr;
+    void *slotsQ = nullptr, *slotsQt = nullptr, *slotsO = nullptr;
+};
+size_t fast_products_bytes(int64_t n, int64_t p) {
+    return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) + 3 * 256 + 4096;
+}
+// true when this context asks for the fast products and the shape suits them (whole 256 x 256 tiles, enough of them)
+bool fast_wanted(const admmq_ctx *ctx, int64_t n, int64_t p) { return ctx->fast_on && admmq_gemm_f16x3_ok(n, p, n); }
+admmq_status fast_setup(admmq_ctx *ctx, int64_t n, int64_t p, FastBufs &fb) {
+    const admmq_factor &f = ctx->fac;
+    char *q = nullptr, *o = nullptr, *sl = nullptr;
+    ADMMQ_TRY(take(ctx, q, 4 * admmq_align_up((size_t)n * n * 2)));
+    ADMMQ_TRY(take(ctx, o, 2 * admmq_align_up((size_t)n * p * 2)));
+    ADMMQ_TRY(take(ctx, sl, 3 * 256));
+    const size_t qs = admmq_align_up((size_t)n * n * 2), os = admmq_align_up((size_t)n * p * 2);
+    fb.Q1 = q; fb.Q2 = q + qs; fb.Qt1 = q + 2 * qs; fb.Qt2 = q + 3 * qs;
+    fb.O1 = o; fb.O2 = o + os;
+    fb.slotsQ = sl; fb.slotsQt = sl + 256; fb.slotsO = sl + 512;
+    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Q, n, n, n, fb.Q1, fb.Q2, fb.slotsQ));
+    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Qt, n, n, n, fb.Qt1, fb.Qt2, fb.slotsQt));
+    return ADMMQ_OK;
+}
+
 // W = B + Q (T + rho I)^{-1} T (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho)
 // F: n p + p doubles of scratch: the solve's fp32 result [n][p] in front, its per-tile checkpoints behind
 admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const double *dinv,
-                           const double *lfac, float *Y, double *F, float *W) {
+                           const double *lfac, float *Y, double *F, float *W, const FastBufs *fb = nullptr) {
     const admmq_factor &f = ctx->fac;
+    if (fb) {
+        // the time of splitting the state operand is booked with its product
+        int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
+        ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, fb->slotsO));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, fb->slotsO, n, p, n, -1.f, 1.f, C0,
+                                   p, Y, p));
+        admmq_prof_end(ctx, sp);
+        float *S = (float *)F;
+        double *carries = F + ((size_t)n * p + 1) / 2;
+        sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
+        ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S));
+        admmq_prof_end(ctx, sp);
+        sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
+        ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, fb->slotsO));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, fb->slotsO, n, p, n, 1.f, 1.f, B,
+                                   p, W, p));
+        admmq_prof_end(ctx, sp);
+        return ADMMQ_OK;
+    }
     gemm_tn_args g1 = {};
     g1.A = f.Q; g1.lda = n; g1.B = B; g1.ldb = p; g1.M = n; g1.N = p; g1.K = n;
     g1.alpha = -1.f; g1.beta = 1.f; g1.Z = C0; g1.ldz = p; g1.out = Y; g1.ldo = p; g1.split_k = 1;
@@ -553,6 +598,18 @@ extern "C" admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_
     return ADMMQ_OK;
 }
 
+extern "C" admmq_status admmq_set_fast_products(admmq_ctx *ctx, int32_t on) {
+    if (!ctx) return ADMMQ_ERR_NULL;
+    if (on != 0 && on != 1) return ADMMQ_ERR_PARAM;
+    ctx->fast_on = on != 0;
+    return ADMMQ_OK;
+}
+
+extern "C" size_t admmq_fast_products_bytes(int64_t n, int64_t p) {
+    if (n < 1 || p < 1 || !admmq_gemm_f16x3_ok(n, p, n)) return 0;
+    return fast_products_bytes(n, p);
+}
+
 // ---- Hessian -----------------------------------------------------------------------------------
 namespace {
 // Bytes the partial sums of the token slices may take: whatever it needs in an arena the library grows itself,
@@ -709,8 +766,10 @@ extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const fl
     ADMMQ_HIP(hipSetDevice(ctx->device));
     admmq_arena_reset_transient(ctx);
     const size_t np = (size_t)n * p;
+    const bool fast = fast_wanted(ctx, n, p);
     ADMMQ_TRY(admmq_arena_reserve(ctx, 3 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) +
-                                           3 * admmq_align_up((size_t)n * 8) + 8192));
+                                           3 * admmq_align_up((size_t)n * 8) + 8192 +
+                                           (fast ? fast_products_bytes(n, p) : 0)));
     float *B = nullptr, *C0 = nullptr, *Y = nullptr;
     double *F = nullptr, *dinv = nullptr, *lfac = nullptr, *rho_dev = nullptr;
     ADMMQ_TRY(take(ctx, B, np));
@@ -730,7 +789,9 @@ extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const fl
     ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
     const float inv_rho = 1.0f / (float)rho;
     ADMMQ_TRY(admmq_k_form_b(ctx, D, V, inv_rho, (int64_t)np, B));
-    ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv, lfac, Y, F, W_out));
+    FastBufs fbufs;
+    if (fast) ADMMQ_TRY(fast_setup(ctx, n, p, fbufs));
+    ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv, lfac, Y, F, W_out, fast ? &fbufs : nullptr));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;
 }
@@ -981,8 +1042,9 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     // --- grid, initial state, schedule -----------------------------------------------------------
     t_phase.start();
     LsPlan plan = ls_plan(n, uniform ? sched->ls_rounds : 0, sched->ls_batches, sched->ls_pairs);
+    const bool fast = uniform && fast_wanted(ctx, n, p);
     size_t need = admm_transient_bytes(n, p, T) + 3 * admmq_align_up(ng * 4) +
-                  admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8);
+                  admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8) + (fast ? fast_products_bytes(n, p) : 0);
     if (plan.rounds > 0 && n >= 2) {
         const size_t ls = ls_transient_bytes(n, p, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
         if (ls > need) need = ls;
@@ -1011,6 +1073,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     ADMMQ_TRY(take(ctx, res, (size_t)T));
     ADMMQ_TRY(take(ctx, flips, (size_t)T));
     ADMMQ_TRY(take(ctx, jdev, 4));
+    FastBufs fbufs;
+    if (fast) ADMMQ_TRY(fast_setup(ctx, n, p, fbufs));
 
     if (uniform)
         ADMMQ_TRY(admmq_k_grid_fit(ctx, W0, n, p, ldw, bits, g, sched->symmetric != 0, sched->clip_points,
@@ -1068,7 +1132,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
         } else {
-            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur,
+                                    fast ? &fbufs : nullptr));
         }
         const bool last = t == T - 1;
         if (uniform && t == sched->refresh_iter)
@@ -1221,7 +1286,9 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     LsPlan plan = ls_plan(n, sched->ls_rounds, sched->ls_batches, sched->ls_pairs);
     size_t ng_total = 0;
     for (int i = 0; i < count; ++i) ng_total += admmq_align_up((size_t)(n / grp[i]) * L[i].p * 4);
-    size_t need = admm_transient_bytes(n, P, T) + ng_total + (size_t)count * (2 * admmq_align_up((size_t)T * 8) + 1024);
+    const bool fast = fast_wanted(ctx, n, P);
+    size_t need = admm_transient_bytes(n, P, T) + ng_total + (size_t)count * (2 * admmq_align_up((size_t)T * 8) + 1024) +
+                  (fast ? fast_products_bytes(n, P) : 0);
     if (plan.rounds > 0 && n >= 2) {
         const size_t ls = ls_transient_bytes(n, pmax, (int64_t)plan.rounds * plan.batches * plan.pairs, plan.pairs);
         if (ls > need) need = ls;
@@ -1245,6 +1312,8 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
     ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
     ADMMQ_TRY(take(ctx, jdev, 4));
+    FastBufs fbufs;
+    if (fast) ADMMQ_TRY(fast_setup(ctx, n, P, fbufs));
     // the stopping rule: codes changed per iteration and matrix, [T][count]; the loop ends once no matrix has
     // changed a code for quiet_stop iterations in a row
     const int quiet_stop = sched->quiet_stop;
@@ -1298,7 +1367,8 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
         if (t == 0)
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, nP * 4, hipMemcpyDeviceToDevice, ctx->stream));
         else
-            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, P, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur));
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, P, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur,
+                                    fast ? &fbufs : nullptr));
         const bool last = t == T - 1;
         const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);
         for (int i = 0; i < count; ++i) {

@@ -64,6 +64,8 @@ struct admmq_ctx {
     // first use, kept for the context's lifetime
     hipEvent_t *panel_events = nullptr;
     int panel_event_count = 0;
+    // opt-in: W-update products of whole 256 x 256 tiles as three fp16 matrix-core products of split operands
+    bool fast_on = false;
 };
 
 // Returns a span index (or -1 when profiling is off); call admmq_prof_end with it after the launch.
@@ -104,6 +106,16 @@ bool admmq_hessian_bf16_ok(const void *X, int64_t n, int64_t ldx, int64_t rows);
 int64_t admmq_hessian_bf16_main_rows(int64_t rows);
 admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int64_t k_main, int64_t n, float *P,
                                 int split, int64_t slice_stride);
+// Split-fp16 products (gemm_f16x3.hip).  split: hi = fp16(s x), lo = fp16(s x - hi), s the power of two that brings
+// the largest |x| into [2^14, 2^15); slots: 8 bytes of device scratch per matrix (largest |x| as bits, then s).
+// product: out = alpha * A^T B + beta * Z with A, B given by their fp16 pairs, k-major [K][M] and [K][N] with dense
+// rows; M, N multiples of 256 with at least 200 tiles, K a multiple of 32 (admmq_gemm_f16x3_ok).
+bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K);
+admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
+                               void *lo, void *slots);
+admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
+                              const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
+                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo);
 // H[i][j] (+)= sum_s P[s][i][j] for i >= j and mirrors the result into the upper triangle.
 admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
                               int64_t slice_stride, int accumulate);
