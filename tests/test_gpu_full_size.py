@@ -160,6 +160,24 @@ def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
     # codes themselves may differ: one near-midpoint rounding that falls the other way (fp32 / float64) changes
     # the later trajectory; both end points are valid and their objectives agree (asserted above)
     print(f"{name} slice: ADMM codes differing from the oracle's: {np.mean(sc != ref.admm.codes):.3f}")
+    # --- the opt-in split-fp16 products (full width only: they need 200 tiles) against the same oracle run: the
+    #     objective of the slice's columns, recomputed in float64 from the full-width codes ----------------------
+    if admmq.fast_products_bytes(cfg.n, cfg.p) > 0:
+        ctx.set_fast_products(True)
+        try:
+            f_codes, f_scales, f_zeros, st_fast = ctx.quantize_layer(Hd_, W0d, cfg.bits, g, s0)
+        finally:
+            ctx.set_fast_products(False)
+        assert torch.equal(f_scales, scales) and torch.equal(f_zeros, zeros)
+        kf = f_codes.cpu().numpy()[:, :SLICE].astype(np.float64)
+        Es = np.repeat(zeros.cpu().numpy()[:, :SLICE].astype(np.float64), gg, 0) + \
+            kf * np.repeat(scales.cpu().numpy()[:, :SLICE].astype(np.float64), gg, 0) - W0s.astype(np.float64)
+        j_fast = float(np.sum(Es * (H64 @ Es))) + st_full.lam * float(np.sum(Es * Es))
+        print(f"{name}: split-fp16 products, slice objective {j_fast:.6g} against the oracle's {ref.j_damp_admm:.6g}; "
+              f"codes differing from the oracle's {np.mean(kf != ref.admm.codes):.3f}; whole layer "
+              f"{st_fast.j_damp_admm:.8g} against {st_full.j_damp_admm:.8g} with the fp32 products")
+        assert abs(j_fast - ref.j_damp_admm) <= OBJ_TOL * ref.j_damp_admm
+        assert abs(st_fast.j_damp_admm - st_full.j_damp_admm) <= 1e-3 * st_full.j_damp_admm
 
 
 @pytest.mark.parametrize("fast", [False, True])
