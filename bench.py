@@ -210,6 +210,29 @@ def main():
                                  "admm_s": early.ms_admm * 1e-3, "j_damp": early.j_damp,
                                  "same_objective_as_full_run": bool(abs(early.j_damp - stats[-1].j_damp)
                                                                     <= 1e-9 * abs(stats[-1].j_damp))}
+    # informational as well: the same layer with the opt-in split-fp16 W-update products (fp16 matrix cores, three
+    # exact products of 22-bit operand pairs accumulated in fp32); the headline above is the fp32 products
+    if not args.fast_products and admmq.fast_products_bytes(n, p) > 0:
+        ctx.set_fast_products(True)
+        ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size, sched, want_stats=True, profile=False)
+        fs = [ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size, sched, want_stats=True, profile=True)[3]
+              for _ in range(2)]
+        fq = ctx.quantize_layer(H, W0, cfg.bits, cfg.group_size,
+                                admmq.Schedule(T=T, ls_rounds=args.ls_rounds, seed=cfg.seed, quiet_stop=8))[3]
+        ctx.set_fast_products(False)
+        f_admm = float(np.mean([s.ms_admm for s in fs]))
+        f_gemm = float(np.mean([s.ms_gemm / max(s.n_gemm, 1) for s in fs]))
+        f_tf = 2.0 * n * n * p / (f_gemm * 1e-3) / 1e12
+        line["with_fast_products"] = {
+            "admm_iterations_per_s": T / (f_admm * 1e-3),
+            "layer_quantize_time_s": float(np.mean([s.ms_total for s in fs])) * 1e-3,
+            "j_damp": fs[-1].j_damp, "j_damp_relative_to_fp32_products": fs[-1].j_damp / stats[-1].j_damp - 1.0,
+            "roofline": {"kernel": "split_f16 + gemm_f16x3 (W-update, 2 per iteration; operand split included)",
+                         "bound": "mfma", "achieved": 3.0 * f_tf, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                         "frac": 3.0 * f_tf / PEAK_BF16_MFMA_TFLOPS, "ms_per_product": f_gemm,
+                         "executed_flop_per_product": 6.0 * n * n * p,
+                         "fp32_equivalent_TFLOP/s": f_tf},
+            "and_quiet_stop_8": {"iterations_run": fq.iters_done, "layer_quantize_time_s": fq.ms_total * 1e-3}}
     ctx.close()
     del X
     if not args.no_cpu_baseline:

@@ -276,10 +276,11 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
 // before each product; all of it in the call's transient arena.
 struct FastBufs {
     void *Q1 = nullptr, *Q2 = nullptr, *Qt1 = nullptr, *Qt2 = nullptr, *O1 = nullptr, *O2 = nullptr;
-    void *slotsQ = nullptr, *slotsQt = nullptr, *slotsO = nullptr;
+    void *slotsQ = nullptr, *slotsQt = nullptr;
+    void *slotsO[2] = {nullptr, nullptr};      // the state operand's two splits per W-update: each zeroes the other's
 };
 size_t fast_products_bytes(int64_t n, int64_t p) {
-    return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) + 3 * 256 + 4096;
+    return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) + 4 * 256 + 4096;
 }
 // true when this context asks for the fast products and the shape suits them (whole 256 x 256 tiles, enough of them)
 bool fast_wanted(const admmq_ctx *ctx, int64_t n, int64_t p) { return ctx->fast_on && admmq_gemm_f16x3_ok(n, p, n); }
@@ -288,13 +289,14 @@ admmq_status fast_setup(admmq_ctx *ctx, int64_t n, int64_t p, FastBufs &fb) {
     char *q = nullptr, *o = nullptr, *sl = nullptr;
     ADMMQ_TRY(take(ctx, q, 4 * admmq_align_up((size_t)n * n * 2)));
     ADMMQ_TRY(take(ctx, o, 2 * admmq_align_up((size_t)n * p * 2)));
-    ADMMQ_TRY(take(ctx, sl, 3 * 256));
+    ADMMQ_TRY(take(ctx, sl, 4 * 256));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, sl, 0, 4 * 256));
     const size_t qs = admmq_align_up((size_t)n * n * 2), os = admmq_align_up((size_t)n * p * 2);
     fb.Q1 = q; fb.Q2 = q + qs; fb.Qt1 = q + 2 * qs; fb.Qt2 = q + 3 * qs;
     fb.O1 = o; fb.O2 = o + os;
-    fb.slotsQ = sl; fb.slotsQt = sl + 256; fb.slotsO = sl + 512;
-    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Q, n, n, n, fb.Q1, fb.Q2, fb.slotsQ));
-    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Qt, n, n, n, fb.Qt1, fb.Qt2, fb.slotsQt));
+    fb.slotsQ = sl; fb.slotsQt = sl + 256; fb.slotsO[0] = sl + 512; fb.slotsO[1] = sl + 768;
+    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Q, n, n, n, fb.Q1, fb.Q2, fb.slotsQ, nullptr));
+    ADMMQ_TRY(admmq_k_split_f16(ctx, f.Qt, n, n, n, fb.Qt1, fb.Qt2, fb.slotsQt, nullptr));
     return ADMMQ_OK;
 }
 
@@ -306,9 +308,9 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
     if (fb) {
         // the time of splitting the state operand is booked with its product
         int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
-        ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, fb->slotsO));
-        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, fb->slotsO, n, p, n, -1.f, 1.f, C0,
-                                   p, Y, p));
+        void *sb = fb->slotsO[0], *ss = fb->slotsO[1];
+        ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, sb, ss));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, sb, n, p, n, -1.f, 1.f, C0, p, Y, p));
         admmq_prof_end(ctx, sp);
         float *S = (float *)F;
         double *carries = F + ((size_t)n * p + 1) / 2;
@@ -316,9 +318,9 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
         ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S));
         admmq_prof_end(ctx, sp);
         sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
-        ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, fb->slotsO));
-        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, fb->slotsO, n, p, n, 1.f, 1.f, B,
-                                   p, W, p));
+        // (the second split zeroes the first one's slot again: the next W-update starts where this one did)
+        ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, ss, sb));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, ss, n, p, n, 1.f, 1.f, B, p, W, p));
         admmq_prof_end(ctx, sp);
         return ADMMQ_OK;
     }

@@ -107,12 +107,13 @@ int64_t admmq_hessian_bf16_main_rows(int64_t rows);
 admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int64_t k_main, int64_t n, float *P,
                                 int split, int64_t slice_stride);
 // Split-fp16 products (gemm_f16x3.hip).  split: hi = fp16(s x), lo = fp16(s x - hi), s the power of two that brings
-// the largest |x| into [2^14, 2^15); slots: 8 bytes of device scratch per matrix (largest |x| as bits, then s).
+// the largest |x| into [2^14, 2^15); slots: 8 bytes of device scratch per matrix (largest |x| as bits, zero on
+// entry, then s); next_slots (may be NULL): another matrix's slots, whose first word is zeroed for the split after.
 // product: out = alpha * A^T B + beta * Z with A, B given by their fp16 pairs, k-major [K][M] and [K][N] with dense
 // rows; M, N multiples of 256 with at least 200 tiles, K a multiple of 32 (admmq_gemm_f16x3_ok).
 bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K);
 admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
-                               void *lo, void *slots);
+                               void *lo, void *slots, void *next_slots);
 admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
                               const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
                               float beta, const float *Z, int64_t ldz, float *out, int64_t ldo);

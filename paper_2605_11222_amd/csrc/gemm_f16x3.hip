@@ -242,10 +242,15 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
 __global__ __launch_bounds__(256) void amax_kernel(const float *__restrict__ src, long rows, long cols, long ld,
                                                   unsigned *__restrict__ slot) {
     const long c4 = cols / 4, total = rows * c4;
+    const bool dense = ld == cols;                         // then the matrix is one run of floats: no row arithmetic
     unsigned best = 0;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
-        const long r = e / c4, c = (e - r * c4) * 4;
-        const floatx4 x = *(const floatx4 *)(src + r * ld + c);
+        long off = 4 * e;
+        if (!dense) {
+            const long r = e / c4;
+            off = r * ld + (e - r * c4) * 4;
+        }
+        const floatx4 x = *(const floatx4 *)(src + off);
         best = max(best, __float_as_uint(fabsf(x.x)));
         best = max(best, __float_as_uint(fabsf(x.y)));
         best = max(best, __float_as_uint(fabsf(x.z)));
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(256) void amax_kernel(const float *__restrict__ src
 __global__ __launch_bounds__(256) void split_f16_kernel(const float *__restrict__ src, long rows, long cols, long ld,
                                                        const unsigned *__restrict__ amax_slot,
                                                        unsigned short *__restrict__ hi, unsigned short *__restrict__ lo,
-                                                       float *__restrict__ scale_out) {
+                                                       float *__restrict__ scale_out, unsigned *__restrict__ zero_slot) {
     const unsigned bits = amax_slot[0];
     const int ex = (int)((bits >> 23) & 0xffu);
     float s = 1.0f;
@@ -276,12 +281,21 @@ __global__ __launch_bounds__(256) void split_f16_kernel(const float *__restrict_
         se = se > 120 ? 120 : (se < -120 ? -120 : se);
         s = __uint_as_float((unsigned)(se + 127) << 23);
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) scale_out[0] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        scale_out[0] = s;
+        if (zero_slot) zero_slot[0] = 0;                   // the slot of the NEXT matrix's maximum (nobody reads it now)
+    }
     const long c8 = cols / 8, total = rows * c8;
+    const bool dense = ld == cols;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
-        const long r = e / c8, c = (e - r * c8) * 8;
-        const floatx4 x0 = *(const floatx4 *)(src + r * ld + c);
-        const floatx4 x1 = *(const floatx4 *)(src + r * ld + c + 4);
+        long r = 0, c = 8 * e, off = 8 * e;
+        if (!dense) {
+            r = e / c8;
+            c = (e - r * c8) * 8;
+            off = r * ld + c;
+        }
+        const floatx4 x0 = *(const floatx4 *)(src + off);
+        const floatx4 x1 = *(const floatx4 *)(src + off + 4);
         const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
         halfx8 h, l;
 #pragma unroll
@@ -303,18 +317,21 @@ bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) {
     return (M / FX_TILE) * (N / FX_TILE) >= 200;           // fewer tiles would leave compute units idle
 }
 
-// hi, lo: [rows][cols] fp16 (dense rows); slots: 2 words of device scratch (word 0: largest |x| as bits, word 1: s)
+// hi, lo: [rows][cols] fp16 (dense rows); slots: 2 words of device scratch (word 0: largest |x| as bits, zero on
+// entry; word 1: receives s).  next_slots (may be NULL): the slots of the split that follows on this stream; its
+// word 0 is zeroed here, which saves that split a launch.
 admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
-                               void *lo, void *slots) {
-    if (cols % 8 != 0 || ld % 4 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)hi & 15) || ((uintptr_t)lo & 15))
+                               void *lo, void *slots, void *next_slots) {
+    if (cols % 8 != 0 || ld % 4 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)hi & 15) || ((uintptr_t)lo & 15) ||
+        next_slots == slots)
         return ADMMQ_ERR_PARAM;
-    ADMMQ_TRY(admmq_k_fill_bytes(ctx, slots, 0, 8));
     const long work = rows * (cols / 8);
     const unsigned blocks = (unsigned)(work / 256 + 1 < 2048 ? work / 256 + 1 : 2048);
     hipLaunchKernelGGL(amax_kernel, dim3(blocks), dim3(256), 0, ctx->stream, src, (long)rows, (long)cols, (long)ld,
                        (unsigned *)slots);
     hipLaunchKernelGGL(split_f16_kernel, dim3(blocks), dim3(256), 0, ctx->stream, src, (long)rows, (long)cols, (long)ld,
-                       (const unsigned *)slots, (unsigned short *)hi, (unsigned short *)lo, (float *)slots + 1);
+                       (const unsigned *)slots, (unsigned short *)hi, (unsigned short *)lo, (float *)slots + 1,
+                       (unsigned *)next_slots);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
