@@ -278,6 +278,7 @@ struct FastBufs {
     void *Q1 = nullptr, *Q2 = nullptr, *Qt1 = nullptr, *Qt2 = nullptr, *O1 = nullptr, *O2 = nullptr;
     void *slotsQ = nullptr, *slotsQt = nullptr;
     void *slotsO[2] = {nullptr, nullptr};      // the state operand's two splits per W-update: each zeroes the other's
+    mutable bool b_max_ready = false;          // the projection pass has left the largest |B| in slotsO[0]
 };
 size_t fast_products_bytes(int64_t n, int64_t p) {
     return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) + 4 * 256 + 4096;
@@ -309,17 +310,19 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
         // the time of splitting the state operand is booked with its product
         int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
         void *sb = fb->slotsO[0], *ss = fb->slotsO[1];
-        ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, sb, ss));
+        ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, sb, ss, fb->b_max_ready));
+        fb->b_max_ready = false;
         ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, sb, n, p, n, -1.f, 1.f, C0, p, Y, p));
         admmq_prof_end(ctx, sp);
         float *S = (float *)F;
         double *carries = F + ((size_t)n * p + 1) / 2;
         sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
-        ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S));
+        ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S, (unsigned *)ss));
         admmq_prof_end(ctx, sp);
         sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
-        // (the second split zeroes the first one's slot again: the next W-update starts where this one did)
-        ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, ss, sb));
+        // (the solve has left the largest |S| in its slot; the second split zeroes the first one's slot again: the
+        // next W-update, or the projection pass before it, starts where this one did)
+        ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, ss, sb, true));
         ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, ss, n, p, n, 1.f, 1.f, B, p, W, p));
         admmq_prof_end(ctx, sp);
         return ADMMQ_OK;
@@ -1146,12 +1149,14 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         if (uniform)
             ADMMQ_TRY(admmq_k_project_dual(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.scales, inv_scales, pj.zeros,
                                            rf, 1.0f / rf, 1.0f / rf_next, (last || want_flips) ? codes : nullptr,
-                                           want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr, p));
+                                           want_flips ? 1 : 0, Wcur, res + t, want_flips ? flips + t : nullptr, p,
+                                           fast ? (unsigned *)fbufs.slotsO[0] : nullptr));
         else
             ADMMQ_TRY(admmq_k_project_format(ctx, pj.kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.flags, pj.scales,
                                              inv_scales, pj.zeros, pj.codebook, rf, 1.0f / rf, 1.0f / rf_next,
                                              last ? 1 : 0, codes, Wcur, pj.Wq, res + t));
         admmq_prof_end(ctx, sp);
+        if (fast) fbufs.b_max_ready = true;
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;
@@ -1379,9 +1384,11 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
                                            inv_scales[i], l.zeros, rf, 1.0f / rf, 1.0f / rf_next,
                                            (last || quiet_stop > 0) ? l.codes : nullptr, quiet_stop > 0 ? 1 : 0,
                                            Wcur + off[i], res[i] + t,
-                                           quiet_stop > 0 ? flips + (size_t)t * count + i : nullptr, P));
+                                           quiet_stop > 0 ? flips + (size_t)t * count + i : nullptr, P,
+                                           fast ? (unsigned *)fbufs.slotsO[0] : nullptr));
         }
         admmq_prof_end(ctx, sp);
+        if (fast) fbufs.b_max_ready = true;
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;

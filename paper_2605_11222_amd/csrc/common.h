@@ -108,12 +108,13 @@ admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int6
                                 int split, int64_t slice_stride);
 // Split-fp16 products (gemm_f16x3.hip).  split: hi = fp16(s x), lo = fp16(s x - hi), s the power of two that brings
 // the largest |x| into [2^14, 2^15); slots: 8 bytes of device scratch per matrix (largest |x| as bits, zero on
-// entry, then s); next_slots (may be NULL): another matrix's slots, whose first word is zeroed for the split after.
+// entry, then s); next_slots (may be NULL): another matrix's slots, whose first word is zeroed for the split after;
+// have_max: the kernel that wrote src has already left the largest |x| in the slot.
 // product: out = alpha * A^T B + beta * Z with A, B given by their fp16 pairs, k-major [K][M] and [K][N] with dense
 // rows; M, N multiples of 256 with at least 200 tiles, K a multiple of 32 (admmq_gemm_f16x3_ok).
 bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K);
 admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
-                               void *lo, void *slots, void *next_slots);
+                               void *lo, void *slots, void *next_slots, bool have_max = false);
 admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
                               const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
                               float beta, const float *Z, int64_t ldz, float *out, int64_t ldo);
@@ -132,7 +133,8 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   const float *inv_d, int bits, int64_t g, const float *scales,
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
-                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw);
+                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw,
+                                  unsigned *amax_out = nullptr);   // amax_out: atomic max of |B| as float bits
 // grid refresh (App. B): refit by min/max of the projection target; both sides of eq. 12 as per-block partials
 admmq_status admmq_k_refit_grid(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,
                                 const float *inv_d, float inv_rho, int bits, int64_t g, float *scales, float *zeros);
@@ -170,4 +172,4 @@ admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const doub
 // S = (T + rho I)^{-1} T Y, column by column (Y, S fp32 [n][p]; may alias), F fp64 scratch [n][p]
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
                                    const double *lfac, int64_t n, int64_t p, const float *Y, double *carries,
-                                   float *S);
+                                   float *S, unsigned *amax_out = nullptr);   // atomic max of |S| as float bits

@@ -90,8 +90,10 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
                                                                   const double *__restrict__ lfac, long n, long p,
                                                                   const float *__restrict__ Y,
                                                                   double *__restrict__ carries,
-                                                                  float *__restrict__ S) {
+                                                                  float *__restrict__ S,
+                                                                  unsigned *__restrict__ amax_out) {
     constexpr int NS = NT / C;                // segments per tile (SL rows each)
+    unsigned smax = 0;                        // largest |S| written, as the float's bit pattern
     constexpr int TR = NS * SL;               // rows per tile
     // the row coefficients of a tile, in two buffers: tile t lives in buffer t & 1 (both passes), and the next
     // tile's are requested at the start of a tile and stored at its end, so no pass waits for them
@@ -243,11 +245,21 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
 #pragma unroll
             for (int u = 0; u < SL; ++u) {
                 const long i = a + u;
-                if (jok && i < n) S[i * p + j] = (float)fma(Pl[u], cin, fl[u]);
+                if (jok && i < n) {
+                    const float sv = (float)fma(Pl[u], cin, fl[u]);
+                    S[i * p + j] = sv;
+                    smax = max(smax, __float_as_uint(fabsf(sv)));
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < SL + 2; ++u) ycur[u] = ynext[u];
+    }
+    if (amax_out) {
+        // for the split-fp16 products: the largest |S| of the whole solve, one atomic per wave
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) smax = max(smax, (unsigned)__shfl_xor((int)smax, o));
+        if ((threadIdx.x & 63) == 0 && smax) atomicMax(amax_out, smax);
     }
 }
 
@@ -286,7 +298,7 @@ admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const doub
 
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
                                    const double *lfac, int64_t n, int64_t p, const float *Y, double *carries,
-                                   float *S) {
+                                   float *S, unsigned *amax_out) {
     if ((const float *)S == Y) return ADMMQ_ERR_PARAM;       // the second pass reads Y again: not in place
     // the widest column strip that still gives every CU a block
     int C = 64;
@@ -310,22 +322,22 @@ admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const doubl
     }
     if (C == 16 && !narrow) {
         hipLaunchKernelGGL((tridiag_apply_split_kernel<16, 512, 16>), dim3(nb), dim3(512), 0, ctx->stream, ta, tb, dinv,
-                           lfac, (long)n, (long)p, Y, carries, S);
+                           lfac, (long)n, (long)p, Y, carries, S, amax_out);
         ADMMQ_HIP(hipGetLastError());
         return ADMMQ_OK;
     }
     if (C == 8)
         hipLaunchKernelGGL((tridiag_apply_split_kernel<8, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
-                           lfac, (long)n, (long)p, Y, carries, S);
+                           lfac, (long)n, (long)p, Y, carries, S, amax_out);
     else if (C == 64)
         hipLaunchKernelGGL((tridiag_apply_split_kernel<64, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
-                           lfac, (long)n, (long)p, Y, carries, S);
+                           lfac, (long)n, (long)p, Y, carries, S, amax_out);
     else if (C == 32)
         hipLaunchKernelGGL((tridiag_apply_split_kernel<32, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
-                           lfac, (long)n, (long)p, Y, carries, S);
+                           lfac, (long)n, (long)p, Y, carries, S, amax_out);
     else
         hipLaunchKernelGGL((tridiag_apply_split_kernel<16, 256, 32>), dim3(nb), dim3(256), 0, ctx->stream, ta, tb, dinv,
-                           lfac, (long)n, (long)p, Y, carries, S);
+                           lfac, (long)n, (long)p, Y, carries, S, amax_out);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

@@ -319,16 +319,18 @@ bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) {
 
 // hi, lo: [rows][cols] fp16 (dense rows); slots: 2 words of device scratch (word 0: largest |x| as bits, zero on
 // entry; word 1: receives s).  next_slots (may be NULL): the slots of the split that follows on this stream; its
-// word 0 is zeroed here, which saves that split a launch.
+// word 0 is zeroed here, which saves that split a launch.  have_max: the producer of src has already accumulated
+// the largest |x| into word 0 (projection and tridiagonal solve do so on request), no reduction pass is needed.
 admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
-                               void *lo, void *slots, void *next_slots) {
+                               void *lo, void *slots, void *next_slots, bool have_max) {
     if (cols % 8 != 0 || ld % 4 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)hi & 15) || ((uintptr_t)lo & 15) ||
         next_slots == slots)
         return ADMMQ_ERR_PARAM;
     const long work = rows * (cols / 8);
     const unsigned blocks = (unsigned)(work / 256 + 1 < 2048 ? work / 256 + 1 : 2048);
-    hipLaunchKernelGGL(amax_kernel, dim3(blocks), dim3(256), 0, ctx->stream, src, (long)rows, (long)cols, (long)ld,
-                       (unsigned *)slots);
+    if (!have_max)
+        hipLaunchKernelGGL(amax_kernel, dim3(blocks), dim3(256), 0, ctx->stream, src, (long)rows, (long)cols, (long)ld,
+                           (unsigned *)slots);
     hipLaunchKernelGGL(split_f16_kernel, dim3(blocks), dim3(256), 0, ctx->stream, src, (long)rows, (long)cols, (long)ld,
                        (const unsigned *)slots, (unsigned short *)hi, (unsigned short *)lo, (float *)slots + 1,
                        (unsigned *)next_slots);

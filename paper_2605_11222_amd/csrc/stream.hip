@@ -154,12 +154,14 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
     const float *__restrict__ inv_d, float levels, long g, const float *__restrict__ scales,
     const float *__restrict__ inv_scales, const float *__restrict__ zeros, float rho, float inv_rho,
     float inv_rho_next, uint8_t *__restrict__ codes, float *B, double *__restrict__ res_sq,
-    unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal, long ldw) {
+    unsigned long long *__restrict__ flips, int rows_per_block, int nontemporal, long ldw,
+    unsigned *__restrict__ amax_out) {
     __shared__ double sh[4];
     const long c0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
     const long row0 = (long)blockIdx.y * rows_per_block;
     float acc = 0.f;
     unsigned nflip = 0;
+    unsigned bmax = 0;                   // largest |B| written, as the float's bit pattern (orders like the float)
     if (c0 < p) {
         const int nc = (int)min(4L, p - c0);
         long grp = -1;
@@ -226,7 +228,10 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
                     vn[c] = __fadd_rn(v[rr][c], __fmul_rn(rho, r));
                     bn[c] = __fsub_rn(Dn, __fmul_rn(vn[c], inv_rho_next));
                     kq[c] = (uint8_t)k;
-                    if (c < nc) acc += r * r;
+                    if (c < nc) {
+                        acc += r * r;
+                        bmax = max(bmax, __float_as_uint(fabsf(bn[c])));
+                    }
                 }
                 if (VEC) {
                     floatx4 ov = {vn[0], vn[1], vn[2], vn[3]};
@@ -269,6 +274,12 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
     if (FLIPS && flips) {
         double tot = block_sum((double)nflip, sh);
         if (threadIdx.x == 0 && tot > 0.0) atomicAdd(flips, (unsigned long long)tot);
+    }
+    if (amax_out) {
+        // for the split-fp16 products: the largest |B| of the whole pass, one atomic per wave
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) bmax = max(bmax, (unsigned)__shfl_xor((int)bmax, o));
+        if ((threadIdx.x & 63) == 0 && bmax) atomicMax(amax_out, bmax);
     }
 }
 
@@ -483,7 +494,7 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
                                   const float *inv_d, int bits, int64_t g, const float *scales,
                                   const float *inv_scales, const float *zeros, float rho, float inv_rho,
                                   float inv_rho_next, uint8_t *codes, int count_flips, float *B_out,
-                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw) {
+                                  double *dev_res_sq, unsigned long long *dev_flips, int64_t ldw, unsigned *amax_out) {
     // ldw: leading dimension of W and B_out (several matrices side by side); V, codes and the grid are [.][p]
     const long p4 = (p + 3) / 4;
     static int rows_cfg = -1, nt_cfg = 0;
@@ -502,7 +513,7 @@ admmq_status admmq_k_project_dual(admmq_ctx *ctx, const float *W, float *V, int6
 #define ADMMQ_PD(C, F, VV)                                                                                   \
     hipLaunchKernelGGL((project_dual_kernel<C, F, VV>), grid, block, 0, ctx->stream, W, V, (long)n, (long)p, d, \
                        inv_d, levels, (long)g, scales, inv_scales, zeros, rho, inv_rho, inv_rho_next, codes,  \
-                       B_out, dev_res_sq, dev_flips, rows_per_block, nt_cfg, (long)ldw)
+                       B_out, dev_res_sq, dev_flips, rows_per_block, nt_cfg, (long)ldw, amax_out)
     if (codes && count_flips) { if (vec) ADMMQ_PD(true, true, true); else ADMMQ_PD(true, true, false); }
     else if (codes)           { if (vec) ADMMQ_PD(true, false, true); else ADMMQ_PD(true, false, false); }
     else                      { if (vec) ADMMQ_PD(false, false, true); else ADMMQ_PD(false, false, false); }
