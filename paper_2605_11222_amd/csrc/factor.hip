@@ -259,7 +259,9 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
         // for the split-fp16 products: the largest |S| of the whole solve, one atomic per wave
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) smax = max(smax, (unsigned)__shfl_xor((int)smax, o));
-        if ((threadIdx.x & 63) == 0 && smax) atomicMax(amax_out, smax);
+        // (most waves find a value at least as large already there and skip the atomic: thousands of atomics on
+        // one address would take longer than the pass itself)
+        if ((threadIdx.x & 63) == 0 && smax > __atomic_load_n(amax_out, __ATOMIC_RELAXED)) atomicMax(amax_out, smax);
     }
 }
 

@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void amax_kernel(const float *__restrict__ src
     __syncthreads();
     if (threadIdx.x == 0) {
         best = max(max(part[0], part[1]), max(part[2], part[3]));
-        if (best) atomicMax(slot, best);
+        if (best > __atomic_load_n(slot, __ATOMIC_RELAXED)) atomicMax(slot, best);   // few blocks raise the maximum
     }
 }
 

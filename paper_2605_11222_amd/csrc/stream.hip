@@ -279,7 +279,9 @@ __global__ __launch_bounds__(256) void project_dual_kernel(
         // for the split-fp16 products: the largest |B| of the whole pass, one atomic per wave
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) bmax = max(bmax, (unsigned)__shfl_xor((int)bmax, o));
-        if ((threadIdx.x & 63) == 0 && bmax) atomicMax(amax_out, bmax);
+        // (most waves find a value at least as large already there and skip the atomic: thousands of atomics on
+        // one address would take longer than the pass itself)
+        if ((threadIdx.x & 63) == 0 && bmax > __atomic_load_n(amax_out, __ATOMIC_RELAXED)) atomicMax(amax_out, bmax);
     }
 }
 
