@@ -61,7 +61,8 @@ size_t admmq_workspace_bytes(int64_t n, int64_t p, int32_t T);
 admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /* Opt-in, per context, off by default (on = 1 / 0): the two products of every W-update (eq. 7) whose output is whole
- * 256 x 256 tiles, at least 200 of them (n and the column count multiples of 256), run on the fp16 matrix cores.
+ * 256 x 256 tiles (n and the column count multiples of 256; at least 200 tiles, or 25 and more with the contraction
+ * cut into up to eight slices of 512 rows or more) run on the fp16 matrix cores.
  * Each fp32 operand is scaled by a power of two and split into an fp16 pair hi + lo (22 bits); the product is
  * hiA hiB + hiA loB + loA hiB, every term exact, accumulated in fp32.  Against the fp32 product this drops the
  * operands' last two bits and the lo-lo term (about 3e-7 of a term, an order of magnitude below the fp32

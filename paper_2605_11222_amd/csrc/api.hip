@@ -276,12 +276,14 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
 // before each product; all of it in the call's transient arena.
 struct FastBufs {
     void *Q1 = nullptr, *Q2 = nullptr, *Qt1 = nullptr, *Qt2 = nullptr, *O1 = nullptr, *O2 = nullptr;
+    float *partial = nullptr;                  // partial sums of a product whose k axis is cut into slices
     void *slotsQ = nullptr, *slotsQt = nullptr;
     void *slotsO[2] = {nullptr, nullptr};      // the state operand's two splits per W-update: each zeroes the other's
     mutable bool b_max_ready = false;          // the projection pass has left the largest |B| in slotsO[0]
 };
 size_t fast_products_bytes(int64_t n, int64_t p) {
-    return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) + 4 * 256 + 4096;
+    return 4 * admmq_align_up((size_t)n * n * 2) + 2 * admmq_align_up((size_t)n * p * 2) +
+           admmq_align_up(admmq_gemm_f16x3_partial_bytes(n, p, n)) + 4 * 256 + 4096;
 }
 // true when this context asks for the fast products and the shape suits them (whole 256 x 256 tiles, enough of them)
 bool fast_wanted(const admmq_ctx *ctx, int64_t n, int64_t p) { return ctx->fast_on && admmq_gemm_f16x3_ok(n, p, n); }
@@ -290,6 +292,8 @@ admmq_status fast_setup(admmq_ctx *ctx, int64_t n, int64_t p, FastBufs &fb) {
     char *q = nullptr, *o = nullptr, *sl = nullptr;
     ADMMQ_TRY(take(ctx, q, 4 * admmq_align_up((size_t)n * n * 2)));
     ADMMQ_TRY(take(ctx, o, 2 * admmq_align_up((size_t)n * p * 2)));
+    if (admmq_gemm_f16x3_partial_bytes(n, p, n) > 0)
+        ADMMQ_TRY(take(ctx, fb.partial, admmq_gemm_f16x3_partial_bytes(n, p, n) / 4));
     ADMMQ_TRY(take(ctx, sl, 4 * 256));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, sl, 0, 4 * 256));
     const size_t qs = admmq_align_up((size_t)n * n * 2), os = admmq_align_up((size_t)n * p * 2);
@@ -312,7 +316,8 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
         void *sb = fb->slotsO[0], *ss = fb->slotsO[1];
         ADMMQ_TRY(admmq_k_split_f16(ctx, B, n, p, p, fb->O1, fb->O2, sb, ss, fb->b_max_ready));
         fb->b_max_ready = false;
-        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, sb, n, p, n, -1.f, 1.f, C0, p, Y, p));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Q1, fb->Q2, fb->slotsQ, fb->O1, fb->O2, sb, n, p, n, -1.f, 1.f, C0, p, Y, p,
+                                   fb->partial));
         admmq_prof_end(ctx, sp);
         float *S = (float *)F;
         double *carries = F + ((size_t)n * p + 1) / 2;
@@ -323,7 +328,8 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
         // (the solve has left the largest |S| in its slot; the second split zeroes the first one's slot again: the
         // next W-update, or the projection pass before it, starts where this one did)
         ADMMQ_TRY(admmq_k_split_f16(ctx, S, n, p, p, fb->O1, fb->O2, ss, sb, true));
-        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, ss, n, p, n, 1.f, 1.f, B, p, W, p));
+        ADMMQ_TRY(admmq_gemm_f16x3(ctx, fb->Qt1, fb->Qt2, fb->slotsQt, fb->O1, fb->O2, ss, n, p, n, 1.f, 1.f, B, p, W, p,
+                                   fb->partial));
         admmq_prof_end(ctx, sp);
         return ADMMQ_OK;
     }

@@ -111,13 +111,18 @@ admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int6
 // entry, then s); next_slots (may be NULL): another matrix's slots, whose first word is zeroed for the split after;
 // have_max: the kernel that wrote src has already left the largest |x| in the slot.
 // product: out = alpha * A^T B + beta * Z with A, B given by their fp16 pairs, k-major [K][M] and [K][N] with dense
-// rows; M, N multiples of 256 with at least 200 tiles, K a multiple of 32 (admmq_gemm_f16x3_ok).
+// rows; M, N multiples of 256, K a multiple of 32 (admmq_gemm_f16x3_ok).
+// With fewer than 200 tiles the k axis is cut into 2, 4 or 8 slices whose partial sums (partial_bytes of scratch,
+// passed as `partial`) a second kernel adds up.
 bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K);
+int admmq_gemm_f16x3_split(int64_t M, int64_t N, int64_t K);
+size_t admmq_gemm_f16x3_partial_bytes(int64_t M, int64_t N, int64_t K);
 admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, int64_t cols, int64_t ld, void *hi,
                                void *lo, void *slots, void *next_slots, bool have_max = false);
 admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
                               const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
-                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo);
+                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo,
+                              float *partial = nullptr);
 // H[i][j] (+)= sum_s P[s][i][j] for i >= j and mirrors the result into the upper triangle.
 admmq_status admmq_sym_reduce(admmq_ctx *ctx, float *H, int64_t n, const float *P, int slices,
                               int64_t slice_stride, int accumulate);

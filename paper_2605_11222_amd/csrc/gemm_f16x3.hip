@@ -40,6 +40,9 @@ struct F16x3Params {
     float *out;
     long ldo;
     int tiles_m, tiles_n;
+    int split;                                             // slices of the k axis (1: the block writes out itself)
+    long k_chunk;                                          // k-rows per slice, a multiple of 32
+    float *partial;                                        // split > 1: [split][M][N] unscaled partial sums
 };
 
 // Same block -> tile map as the fp32 products: the blocks of one XCD (ids equal mod 8) form a compact patch of
@@ -65,10 +68,14 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
     extern __shared__ __attribute__((aligned(16))) unsigned char fx_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;               // the wave's 128 x 128 quadrant of the tile
+    // with too few tiles to fill the chip the k axis is cut into slices: block = (slice, tile)
+    const int tiles_total = P.tiles_m * P.tiles_n;
+    const int slice = (int)(blockIdx.x / tiles_total);
     int tm, tn;
-    fx_tile_of_block(blockIdx.x, gridDim.x, P.tiles_m, P.tiles_n, tm, tn);
+    fx_tile_of_block((int)(blockIdx.x - slice * tiles_total), tiles_total, P.tiles_m, P.tiles_n, tm, tn);
     const long m0 = (long)tm * FX_TILE, n0 = (long)tn * FX_TILE;
-    const int nst = (int)(P.K / FX_KT);
+    const long kbeg = (long)slice * P.k_chunk;
+    const int nst = (int)(P.k_chunk / FX_KT);
 
     floatx16 acc[4][4];
 #pragma unroll
@@ -83,7 +90,7 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
     // buffer nobody reads: every stage costs every wave eight loads and the loop has no branches.
     const long lrow = lane >> 5, lcol = (lane & 31) * 8;
     auto load_one = [&](int s, int i) {
-        const long k0 = (long)min(s, nst - 1) * FX_KT;
+        const long k0 = kbeg + (long)min(s, nst - 1) * FX_KT;
         const int mat = i >> 1, c = wave + 4 * (i & 1);
         const unsigned short *src = mat == 0 ? P.A1 : mat == 1 ? P.A2 : mat == 2 ? P.B1 : P.B2;
         const long ld = mat < 2 ? P.M : P.N, c0 = mat < 2 ? m0 : n0;
@@ -204,9 +211,23 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
 
     // out = alpha / (sA sB) * acc + beta * Z.  Accumulator register v of lane l holds row 8 (v / 4) + 4 (l / 32) +
     // v % 4 and column l % 32 of its 32 x 32 sub-tile; the rows of Z are requested eight at a time.
-    const float sc = P.alpha * (1.0f / P.scaleA[0]) * (1.0f / P.scaleB[0]);
     const long wm0 = m0 + wm * 128, wn0 = n0 + wn * 128;
     const int l32 = lane & 31, khalf = lane >> 5;
+    if (P.split > 1) {
+        // the slice's unscaled partial sums; scaling, Z and the sum over slices are the reduction kernel's
+        float *pp = P.partial + (long)slice * P.M * P.N;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long m = wm0 + 32 * a + 8 * (v / 4) + 4 * khalf + (v % 4);
+                float *op = pp + m * P.N + wn0 + l32;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) op[32 * b] = acc[a][b][v];
+            }
+        return;
+    }
+    const float sc = P.alpha * (1.0f / P.scaleA[0]) * (1.0f / P.scaleB[0]);
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -235,6 +256,30 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
                 }
             }
         }
+}
+
+// out = alpha / (sA sB) * sum over slices of partial + beta * Z  (four columns per thread)
+__global__ __launch_bounds__(256) void f16x3_reduce_kernel(const float *__restrict__ partial, int split, long M, long N,
+                                                          const float *__restrict__ scaleA,
+                                                          const float *__restrict__ scaleB, float alpha, float beta,
+                                                          const float *__restrict__ Z, long ldz, float *__restrict__ out,
+                                                          long ldo) {
+    const float sc = alpha * (1.0f / scaleA[0]) * (1.0f / scaleB[0]);
+    const long n4 = N / 4, total = M * n4;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const long m = e / n4, c = (e - m * n4) * 4;
+        floatx4 sum = *(const floatx4 *)(partial + m * N + c);
+        for (int q = 1; q < split; ++q) {
+            const floatx4 t = *(const floatx4 *)(partial + (long)q * M * N + m * N + c);
+            sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+        }
+        floatx4 r = {sc * sum.x, sc * sum.y, sc * sum.z, sc * sum.w};
+        if (Z) {
+            const floatx4 z = *(const floatx4 *)(Z + m * ldz + c);
+            r.x += beta * z.x; r.y += beta * z.y; r.z += beta * z.z; r.w += beta * z.w;
+        }
+        *(floatx4 *)(out + m * ldo + c) = r;
+    }
 }
 
 // largest |x| of a [rows][cols] fp32 matrix (leading dimension ld) as the bit pattern of the float, by atomic max
@@ -312,9 +357,21 @@ __global__ __launch_bounds__(256) void split_f16_kernel(const float *__restrict_
 
 }  // namespace
 
-bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) {
-    if (M < FX_TILE || N < FX_TILE || M % FX_TILE || N % FX_TILE || K < 2 * FX_KT || K % (2 * FX_KT)) return false;
-    return (M / FX_TILE) * (N / FX_TILE) >= 200;           // fewer tiles would leave compute units idle
+// Slices of the k axis for an M x N x K product: 1 when the 256 x 256 tiles alone fill the chip (200 or more), else
+// the smallest of 2, 4, 8 that gets (tiles x slices) there with 512 or more k-rows per slice; 0: not for this kernel.
+int admmq_gemm_f16x3_split(int64_t M, int64_t N, int64_t K) {
+    if (M < FX_TILE || N < FX_TILE || M % FX_TILE || N % FX_TILE || K < 2 * FX_KT || K % (2 * FX_KT)) return 0;
+    const int64_t tiles = (M / FX_TILE) * (N / FX_TILE);
+    for (int sp = 1; sp <= 8; sp *= 2) {
+        if (K % (2 * FX_KT * sp) != 0 || (sp > 1 && K / sp < 512)) return 0;
+        if (tiles * sp >= 200) return sp;
+    }
+    return 0;
+}
+bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) { return admmq_gemm_f16x3_split(M, N, K) > 0; }
+size_t admmq_gemm_f16x3_partial_bytes(int64_t M, int64_t N, int64_t K) {
+    const int sp = admmq_gemm_f16x3_split(M, N, K);
+    return sp > 1 ? (size_t)sp * (size_t)M * (size_t)N * 4 : 0;
 }
 
 // hi, lo: [rows][cols] fp16 (dense rows); slots: 2 words of device scratch (word 0: largest |x| as bits, zero on
@@ -340,9 +397,13 @@ admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, i
 
 admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
                               const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
-                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo) {
-    if (!admmq_gemm_f16x3_ok(M, N, K)) return ADMMQ_ERR_PARAM;
+                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo, float *partial) {
+    const int split = admmq_gemm_f16x3_split(M, N, K);
+    if (split < 1 || (split > 1 && !partial)) return ADMMQ_ERR_PARAM;
+    if (split > 1 && (N % 4 || ldz % 4 || ldo % 4 || ((uintptr_t)out & 15) || (Z && ((uintptr_t)Z & 15))))
+        return ADMMQ_ERR_PARAM;
     F16x3Params P;
+    P.split = split; P.k_chunk = K / split; P.partial = partial;
     P.A1 = (const unsigned short *)A1; P.A2 = (const unsigned short *)A2;
     P.B1 = (const unsigned short *)B1; P.B2 = (const unsigned short *)B2;
     P.scaleA = (const float *)slotsA + 1; P.scaleB = (const float *)slotsB + 1;
@@ -354,7 +415,14 @@ admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, co
                                       FX_LDS));
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_f16x3_kernel, dim3((unsigned)(P.tiles_m * P.tiles_n)), dim3(256), FX_LDS, ctx->stream, P);
+    hipLaunchKernelGGL(gemm_f16x3_kernel, dim3((unsigned)(P.tiles_m * P.tiles_n * split)), dim3(256), FX_LDS,
+                       ctx->stream, P);
+    if (split > 1) {
+        const long work = M * (N / 4);
+        const unsigned blocks = (unsigned)(work / 256 + 1 < 4096 ? work / 256 + 1 : 4096);
+        hipLaunchKernelGGL(f16x3_reduce_kernel, dim3(blocks), dim3(256), 0, ctx->stream, partial, split, (long)M,
+                           (long)N, P.scaleA, P.scaleB, alpha, beta, Z, (long)ldz, out, (long)ldo);
+    }
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

@@ -180,14 +180,15 @@ def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
         assert abs(st_fast.j_damp_admm - st_full.j_damp_admm) <= 1e-3 * st_full.j_damp_admm
 
 
-@pytest.mark.parametrize("fast", [False, True])
-def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, fast):
+@pytest.mark.parametrize("fast,cols", [(False, 512), (True, 3328), (True, 512), (True, 1024)])
+def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, fast, cols):
     """The W-update of the 4096-wide workloads (factorisation of the full Hessian, both products in the tile
     configuration the layer uses, tridiagonal solve) against the oracle's literal eq. 7 through eigh, within the
-    1e-5 relative Frobenius bar.  fast: the opt-in split-fp16 products, which need 200 tiles (3328 columns)."""
+    1e-5 relative Frobenius bar.  fast: the opt-in split-fp16 products; 3328 columns give 208 tiles (one slice of
+    the k axis), 1024 columns 64 tiles (four slices), 512 columns 32 tiles (eight slices)."""
     cfg = si.CONFIGS["cfg2"]
     H32 = hessian_16k
-    n, cols = cfg.n, (3328 if fast else 512)              # 512 columns: the 256 x 256 tile path is taken
+    n = cfg.n                                             # fp32 with 512 columns: the 256 x 256 tile path is taken
     W0 = si.layer_weights(cfg)[:, :cols]
     ctx.set_fast_products(fast)
     try:
@@ -208,7 +209,7 @@ def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, fast):
             Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
             Wref = orc.w_update(U, lam_e, HWs, D.astype(np.float64), V.astype(np.float64), rho)
             err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
-            print(f"n=4096 rho={rho:g} fast={fast}: relative W-update error {err:.2e}")
+            print(f"n=4096 cols={cols} rho={rho:g} fast={fast}: relative W-update error {err:.2e}")
             assert err < 1e-5
     finally:
         ctx.set_fast_products(False)

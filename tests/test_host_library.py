@@ -159,7 +159,7 @@ def test_batched_layers_argument_validation_without_a_gpu(lib):
 
 def test_fast_products_switch_and_scratch_size(lib):
     """The opt-in split-fp16 products: the switch takes 0 or 1; the extra scratch is reported only for shapes the
-    products take (whole 256 x 256 tiles, at least 200 of them) and then holds the fp16 pairs of Q, Q^T (4 n^2
+    products take (whole 256 x 256 tiles, enough of them times k-slices to fill the chip) and then holds the fp16 pairs of Q, Q^T (4 n^2
     values) and of one n x p operand."""
     h = _ctx(lib)
     assert lib.admmq_set_fast_products(None, 1) == 1
@@ -168,8 +168,10 @@ def test_fast_products_switch_and_scratch_size(lib):
     fb = lib.admmq_fast_products_bytes
     assert fb(4096, 4096) >= 4 * 4096 * 4096 * 2 + 2 * 4096 * 4096 * 2
     assert fb(4096, 4096) < 4 * 4096 * 4096 * 2 + 2 * 4096 * 4096 * 2 + (1 << 16)
-    assert fb(4096, 1024) == 0                       # 64 tiles: too few
-    assert fb(4096, 3328) > 0 and fb(4096, 3072) == 0
+    # 64 tiles: the k axis is cut into four slices, whose partial sums need scratch as well
+    assert fb(4096, 1024) >= 4 * 4096 * 4096 * 2 + 2 * 4096 * 1024 * 2 + 4 * 4096 * 1024 * 4
+    assert fb(4096, 3328) > 0 and fb(4096, 3072) > 0
+    assert fb(512, 512) == 0 and fb(1024, 256) == 0  # too small to fill the chip even in eight slices
     assert fb(4100, 4096) == 0 and fb(4096, 4100) == 0 and fb(0, 4096) == 0
     assert fb(25600, 5120) > fb(12288, 4096) > fb(4096, 4096)
     lib.admmq_destroy(h)
