@@ -63,6 +63,24 @@ def test_hessian_accumulate_matches_float64(ctx, n, rows, dtype):
     assert np.max(np.abs(Hg - Href) / scale) < 2e-6 * np.sqrt(max(rows, 16) / 16)
 
 
+@pytest.mark.parametrize("col0", [0, 8, 4])
+def test_hessian_of_a_column_window_of_wider_activations(ctx, col0):
+    """X as a window of a wider bf16 tensor (row stride larger than n): columns from 0 and from 8 keep the rows
+    16-byte aligned and take the bf16 matrix-core kernel, from 4 they are 8-byte aligned and take the fp32 product;
+    all three must give the window's X^T X."""
+    n, rows, wide = 512, 1000, 512 + 264
+    rng = np.random.default_rng(col0 + 1)
+    bits = si.f32_to_bf16_bits(rng.standard_normal((rows, wide)).astype(np.float32))
+    Xw = bf16_bits_to_dev(bits)
+    X64 = si.bf16_bits_to_f32(bits).astype(np.float64)[:, col0:col0 + n]
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    assert ctx.accumulate_hessian(H, Xw[:, col0:col0 + n]) == rows
+    torch.cuda.synchronize()
+    Href = orc.hessian([X64])
+    scale = np.sqrt(np.outer(np.diag(Href), np.diag(Href)))
+    assert np.max(np.abs(H.cpu().numpy() - Href) / scale) < 2e-6 * np.sqrt(rows / 16)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_hessian_in_a_callers_workspace_takes_fewer_token_slices(dtype):
     """A caller's workspace bounds the partial sums of the token slices: with room for two slices the result is the
