@@ -305,14 +305,22 @@ def test_w_update_at_the_large_workloads_sizes_against_literal_eq7(ctx, name, co
         D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
         V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
         Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        # the same step with the opt-in split-fp16 products (240 and 200 tiles: they take it)
+        ctx.set_fast_products(True)
+        try:
+            Wf = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        finally:
+            ctx.set_fast_products(False)
         A = Hs.copy()
         A[np.diag_indices(n)] += rho
         cf = sla.cho_factor(A, lower=True, overwrite_a=True, check_finite=False)
         Wref = sla.cho_solve(cf, HWs + rho * D.astype(np.float64) - V.astype(np.float64), check_finite=False)
         del A, cf
         err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
-        print(f"n={n} rho={rho:g}: relative W-update error {err:.2e}", flush=True)
-        assert err < 1e-5
+        err_f = np.linalg.norm(Wf - Wref) / np.linalg.norm(Wref)
+        print(f"n={n} rho={rho:g}: relative W-update error {err:.2e}; split-fp16 products {err_f:.2e}", flush=True)
+        assert err < 1e-5 and err_f < 1e-5
+        assert not np.array_equal(Wf, Wg)                      # (the other products did run)
 
 
 @pytest.mark.parametrize("kind", ["dual", "codebook"])
