@@ -241,6 +241,42 @@ def test_w_update_matches_literal_eq7_in_float64(ctx, n, p, N, seed):
     print(f"n={n} p={p}: worst relative W-update error {worst:.2e}")
 
 
+@pytest.mark.parametrize("n,p,N,taken", [(1024, 6400, 2100, True), (2048, 3328, 4200, True), (1024, 1792, 2100, False)])
+def test_w_update_with_split_fp16_products_matches_literal_eq7(ctx, n, p, N, taken):
+    """The opt-in split-fp16 products against the same float64 reference and bar: 4 x 25 tiles cut into two slices
+    of the contraction, 8 x 13 tiles in two slices, and a shape the products do not take (28 tiles, too short a
+    contraction to slice), which must come out exactly as without the switch."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(n, p, N, seed=n + p, outliers=2)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+    Hd, _ = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    dg = d.cpu().numpy()
+    d64 = dg.astype(np.float64)
+    Hs = Hd / d64[:, None] / d64[None, :]
+    Ws = (W0 * dg[:, None]).astype(np.float32)
+    lam_e, U = np.linalg.eigh(Hs)
+    lam_e = np.maximum(lam_e, 0)
+    HWs = Hs @ Ws.astype(np.float64)
+    rng = np.random.default_rng(n)
+    scale = np.abs(Ws).mean()
+    assert (admmq.fast_products_bytes(n, p) > 0) == taken
+    for rho in (0.1, 37.0):
+        D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        W_fp32 = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho)
+        ctx.set_fast_products(True)
+        try:
+            W_fast = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho)
+        finally:
+            ctx.set_fast_products(False)
+        assert torch.equal(W_fp32, W_fast) == (not taken)
+        Wref = orc.w_update(U, lam_e, HWs, D.astype(np.float64), V.astype(np.float64), rho)
+        err = np.linalg.norm(W_fast.cpu().numpy().astype(np.float64) - Wref) / np.linalg.norm(Wref)
+        print(f"n={n} p={p} rho={rho:g}: relative W-update error with the split-fp16 products {err:.2e}")
+        assert err < W_UPDATE_TOL
+
+
 @pytest.mark.parametrize("n,p,N,switch", [(300, 40, 900, 128), (1030, 64, 2100, 512), (640, 33, 400, 128),
                                           (200, 16, 500, 129)])
 def test_factorisation_from_the_lower_triangle_matches_literal_eq7(ctx, monkeypatch, n, p, N, switch):
