@@ -34,6 +34,7 @@ struct F16x3Params {
     const unsigned short *A1, *A2, *B1, *B2;               // fp16 bit patterns, [K][M] and [K][N], dense rows
     const float *scaleA, *scaleB;                          // device: the power-of-two scalings of A and B
     long M, N, K;
+    long ldb;                                              // row length of B1, B2 (>= N: a column window of the pair)
     float alpha, beta;
     const float *Z;
     long ldz;
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256, 1) void gemm_f16x3_kernel(F16x3Params P) {
         const long k0 = kbeg + (long)min(s, nst - 1) * FX_KT;
         const int mat = i >> 1, c = wave + 4 * (i & 1);
         const unsigned short *src = mat == 0 ? P.A1 : mat == 1 ? P.A2 : mat == 2 ? P.B1 : P.B2;
-        const long ld = mat < 2 ? P.M : P.N, c0 = mat < 2 ? m0 : n0;
+        const long ld = mat < 2 ? P.M : P.ldb, c0 = mat < 2 ? m0 : n0;
         unsigned char *dst = fx_lds + (s % FX_STAGES) * FX_STAGE + mat * FX_MAT + c * FX_CHUNK;
         __builtin_amdgcn_global_load_lds(src + (k0 + 2 * c + lrow) * ld + c0 + lcol,
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
@@ -368,10 +369,55 @@ int admmq_gemm_f16x3_split(int64_t M, int64_t N, int64_t K) {
     }
     return 0;
 }
-bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) { return admmq_gemm_f16x3_split(M, N, K) > 0; }
+
+namespace {
+// How a product goes out.  A tile count just above a multiple of the 256 compute units would leave the last launch
+// round nearly empty (4096 x 5120: 320 tiles, two rounds for 1.25 rounds of work): then the leading columns that
+// fill whole rounds are one launch and the remaining columns a product of their own with the contraction in
+// slices.  Costs in launch rounds of whole-k tiles; a sliced part pays 0.15 for its partial sums.
+struct FxPlan {
+    int64_t n_head = 0;        // columns of the first (or only) launch
+    int sp_head = 0;           // its slices; 0: the kernel does not take this product
+    int64_t n_tail = 0;        // columns of the second launch (0: none)
+    int sp_tail = 0;
+};
+double fx_rounds(int64_t tiles, int sp) { return (double)((tiles * sp + 255) / 256) / sp + (sp > 1 ? 0.15 : 0.0); }
+FxPlan fx_plan(int64_t M, int64_t N, int64_t K) {
+    FxPlan pl;
+    pl.sp_head = admmq_gemm_f16x3_split(M, N, K);
+    if (pl.sp_head == 0) return pl;
+    pl.n_head = N;
+    const int64_t tm = M / FX_TILE, tn = N / FX_TILE, t = tm * tn;
+    if (pl.sp_head == 1 && t > 256 && t % 256 != 0) {
+        const int64_t c_full = (t / 256) * 256 / tm;              // column tiles that fill whole rounds
+        if (c_full >= 1 && c_full < tn) {
+            const int64_t n_head = c_full * FX_TILE;
+            const int sp_tail = admmq_gemm_f16x3_split(M, N - n_head, K);
+            if (sp_tail > 0 && admmq_gemm_f16x3_split(M, n_head, K) == 1) {
+                const double whole = fx_rounds(t, 1);
+                const double parts = fx_rounds(c_full * tm, 1) + fx_rounds((tn - c_full) * tm, sp_tail);
+                if (parts < 0.93 * whole) {
+                    pl.n_head = n_head;
+                    pl.n_tail = N - n_head;
+                    pl.sp_tail = sp_tail;
+                }
+            }
+        }
+    }
+    return pl;
+}
+}  // namespace
+
+bool admmq_gemm_f16x3_ok(int64_t M, int64_t N, int64_t K) { return fx_plan(M, N, K).sp_head > 0; }
 size_t admmq_gemm_f16x3_partial_bytes(int64_t M, int64_t N, int64_t K) {
-    const int sp = admmq_gemm_f16x3_split(M, N, K);
-    return sp > 1 ? (size_t)sp * (size_t)M * (size_t)N * 4 : 0;
+    const FxPlan pl = fx_plan(M, N, K);
+    size_t need = 0;
+    if (pl.sp_head > 1) need = (size_t)pl.sp_head * (size_t)M * (size_t)pl.n_head * 4;
+    if (pl.sp_tail > 1) {
+        const size_t t = (size_t)pl.sp_tail * (size_t)M * (size_t)pl.n_tail * 4;
+        if (t > need) need = t;
+    }
+    return need;
 }
 
 // hi, lo: [rows][cols] fp16 (dense rows); slots: 2 words of device scratch (word 0: largest |x| as bits, zero on
@@ -395,17 +441,19 @@ admmq_status admmq_k_split_f16(admmq_ctx *ctx, const float *src, int64_t rows, i
     return ADMMQ_OK;
 }
 
-admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
-                              const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
-                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo, float *partial) {
-    const int split = admmq_gemm_f16x3_split(M, N, K);
+namespace {
+// one launch (plus the reduction of its slices): columns [0, N) of B1 / B2 rows of length ldb
+admmq_status fx_launch(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const unsigned short *B1,
+                       const unsigned short *B2, const void *slotsB, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                       int split, float alpha, float beta, const float *Z, int64_t ldz, float *out, int64_t ldo,
+                       float *partial) {
     if (split < 1 || (split > 1 && !partial)) return ADMMQ_ERR_PARAM;
     if (split > 1 && (N % 4 || ldz % 4 || ldo % 4 || ((uintptr_t)out & 15) || (Z && ((uintptr_t)Z & 15))))
         return ADMMQ_ERR_PARAM;
     F16x3Params P;
     P.split = split; P.k_chunk = K / split; P.partial = partial;
     P.A1 = (const unsigned short *)A1; P.A2 = (const unsigned short *)A2;
-    P.B1 = (const unsigned short *)B1; P.B2 = (const unsigned short *)B2;
+    P.B1 = B1; P.B2 = B2; P.ldb = ldb;
     P.scaleA = (const float *)slotsA + 1; P.scaleB = (const float *)slotsB + 1;
     P.M = M; P.N = N; P.K = K; P.alpha = alpha; P.beta = beta; P.Z = Z; P.ldz = ldz; P.out = out; P.ldo = ldo;
     P.tiles_m = (int)(M / FX_TILE); P.tiles_n = (int)(N / FX_TILE);
@@ -424,5 +472,20 @@ admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, co
                            (long)N, P.scaleA, P.scaleB, alpha, beta, Z, (long)ldz, out, (long)ldo);
     }
     ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+}  // namespace
+
+admmq_status admmq_gemm_f16x3(admmq_ctx *ctx, const void *A1, const void *A2, const void *slotsA, const void *B1,
+                              const void *B2, const void *slotsB, int64_t M, int64_t N, int64_t K, float alpha,
+                              float beta, const float *Z, int64_t ldz, float *out, int64_t ldo, float *partial) {
+    const FxPlan pl = fx_plan(M, N, K);
+    if (pl.sp_head < 1) return ADMMQ_ERR_PARAM;
+    const unsigned short *b1 = (const unsigned short *)B1, *b2 = (const unsigned short *)B2;
+    ADMMQ_TRY(fx_launch(ctx, A1, A2, slotsA, b1, b2, slotsB, N, M, pl.n_head, K, pl.sp_head, alpha, beta, Z, ldz, out,
+                        ldo, partial));
+    if (pl.n_tail > 0)
+        ADMMQ_TRY(fx_launch(ctx, A1, A2, slotsA, b1 + pl.n_head, b2 + pl.n_head, slotsB, N, M, pl.n_tail, K, pl.sp_tail,
+                            alpha, beta, Z ? Z + pl.n_head : nullptr, ldz, out + pl.n_head, ldo, partial));
     return ADMMQ_OK;
 }
