@@ -74,6 +74,16 @@ void admmq_prof_end(admmq_ctx *ctx, int span);
 
 static inline size_t admmq_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Kernels with more than 64 KB of dynamic LDS need the attribute raised once per kernel and device; `done` is the
+// call site's own bit mask of the devices already served (a relaxed race between two threads sets it twice at worst).
+static inline hipError_t admmq_allow_lds(const void *kernel, int bytes, int device, unsigned long long *done) {
+    const unsigned long long bit = 1ull << (device & 63);
+    if (*done & bit) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) *done |= bit;
+    return e;
+}
+
 // Makes sure the arena can hold `bytes` above the persistent region; keeps the persistent region.
 admmq_status admmq_arena_reserve(admmq_ctx *ctx, size_t bytes);
 // Bump allocation inside the reserved arena (never fails after a sufficient reserve).

@@ -457,12 +457,8 @@ admmq_status fx_launch(admmq_ctx *ctx, const void *A1, const void *A2, const voi
     P.scaleA = (const float *)slotsA + 1; P.scaleB = (const float *)slotsB + 1;
     P.M = M; P.N = N; P.K = K; P.alpha = alpha; P.beta = beta; P.Z = Z; P.ldz = ldz; P.out = out; P.ldo = ldo;
     P.tiles_m = (int)(M / FX_TILE); P.tiles_n = (int)(N / FX_TILE);
-    static bool attr_set = false;
-    if (!attr_set) {
-        ADMMQ_HIP(hipFuncSetAttribute((const void *)gemm_f16x3_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      FX_LDS));
-        attr_set = true;
-    }
+    static unsigned long long lds_allowed = 0;
+    ADMMQ_HIP(admmq_allow_lds((const void *)gemm_f16x3_kernel, FX_LDS, ctx->device, &lds_allowed));
     hipLaunchKernelGGL(gemm_f16x3_kernel, dim3((unsigned)(P.tiles_m * P.tiles_n * split)), dim3(256), FX_LDS,
                        ctx->stream, P);
     if (split > 1) {

@@ -530,12 +530,8 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
 #define ADMMQ_GEMM_LAUNCH(AB, BB, DR)                                                                  \
     do {                                                                                               \
         auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, KT, AB, BB, DR>;                                      \
-        static bool attr_set = false;                                                                  \
-        if (!attr_set) {                                                                               \
-            ADMMQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                          (int)lds_bytes));                                            \
-            attr_set = true;                                                                           \
-        }                                                                                              \
+        static unsigned long long lds_allowed = 0;                                                     \
+        ADMMQ_HIP(admmq_allow_lds((const void *)kern, (int)lds_bytes, ctx->device, &lds_allowed));     \
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, P);                              \
     } while (0)
     // whole tiles, whole k-stages in every slice, aligned rows: the direct-load kernel

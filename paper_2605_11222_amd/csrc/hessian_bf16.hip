@@ -229,12 +229,8 @@ admmq_status admmq_hessian_bf16(admmq_ctx *ctx, const void *X, int64_t ldx, int6
     hp.per_xcd = (hp.total + 7) / 8;
     hp.P = P;
     hp.slice_stride = slice_stride;
-    static bool attr_set = false;
-    if (!attr_set) {
-        ADMMQ_HIP(hipFuncSetAttribute((const void *)hessian_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      HB_LDS));
-        attr_set = true;
-    }
+    static unsigned long long lds_allowed = 0;
+    ADMMQ_HIP(admmq_allow_lds((const void *)hessian_bf16_kernel, HB_LDS, ctx->device, &lds_allowed));
     hipLaunchKernelGGL(hessian_bf16_kernel, dim3((unsigned)(hp.per_xcd * 8)), dim3(256), HB_LDS, ctx->stream, hp);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
