@@ -21,12 +21,14 @@ sys.path.insert(0, ROOT)
 import synth_inputs as si  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
-PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (the fp16 peak is the same)
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
 # calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
 PMC_TRAFFIC_BYTES = {
-    "cfg2": {"gemm": (227176.3 + 65536.0) * 1024, "project": (65784.5 + 131104.0) * 1024},
+    "cfg2": {"gemm": (227176.3 + 65536.0) * 1024, "project": (65784.5 + 131104.0) * 1024,
+             # the opt-in products (profiles/bench_cfg2_fast_products_kernel_trace.txt): product kernel + operand split
+             "gemm_f16x3": (238850.1 + 83968.0 + 32909.4 + 65536.1) * 1024},
 }
 
 
@@ -231,6 +233,7 @@ def main():
             "roofline": {"kernel": "split_f16 + gemm_f16x3 (W-update, 2 per iteration; operand split included)",
                          "bound": "mfma", "achieved": 3.0 * f_tf, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                          "frac": 3.0 * f_tf / PEAK_BF16_MFMA_TFLOPS, "ms_per_product": f_gemm,
+                         "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm_f16x3"),
                          "executed_flop_per_product": 6.0 * n * n * p,
                          "fp32_equivalent_TFLOP/s": f_tf},
             "and_quiet_stop_8": {"iterations_run": fq.iters_done, "layer_quantize_time_s": fq.ms_total * 1e-3}}
