@@ -67,8 +67,8 @@ admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
  * hiA hiB + hiA loB + loA hiB, every term exact, accumulated in fp32.  Against the fp32 product this drops the
  * operands' last two bits and the lo-lo term (about 3e-7 of a term, an order of magnitude below the fp32
  * accumulation error both share): the W-update stays within the 1e-5 relative Frobenius bar, but results are not
- * bit-identical to the default.  Applies to admmq_quantize_layer, admmq_quantize_layers and admmq_w_update on
- * uniform grids; other shapes and the other formats keep the fp32 products.  Needs
+ * bit-identical to the default.  Applies to admmq_quantize_layer, admmq_quantize_layer_format,
+ * admmq_quantize_layers and admmq_w_update; other shapes keep the fp32 products.  Needs
  * admmq_fast_products_bytes(n, p) more scratch than admmq_workspace_bytes (0 when the shape does not qualify). */
 admmq_status admmq_set_fast_products(admmq_ctx *ctx, int32_t on);
 size_t admmq_fast_products_bytes(int64_t n, int64_t p);

@@ -1053,7 +1053,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     // --- grid, initial state, schedule -----------------------------------------------------------
     t_phase.start();
     LsPlan plan = ls_plan(n, uniform ? sched->ls_rounds : 0, sched->ls_batches, sched->ls_pairs);
-    const bool fast = uniform && fast_wanted(ctx, n, p);
+    const bool fast = fast_wanted(ctx, n, p);
     size_t need = admm_transient_bytes(n, p, T) + 3 * admmq_align_up(ng * 4) +
                   admmq_align_up((size_t)2 * admmq_refresh_error_blocks() * 8) + (fast ? fast_products_bytes(n, p) : 0);
     if (plan.rounds > 0 && n >= 2) {
@@ -1162,7 +1162,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
                                              inv_scales, pj.zeros, pj.codebook, rf, 1.0f / rf, 1.0f / rf_next,
                                              last ? 1 : 0, codes, Wcur, pj.Wq, res + t));
         admmq_prof_end(ctx, sp);
-        if (fast) fbufs.b_max_ready = true;
+        if (fast && uniform) fbufs.b_max_ready = true;     // (the other formats' pass leaves no maximum: reduced then)
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;
