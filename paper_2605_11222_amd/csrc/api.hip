@@ -49,7 +49,7 @@ admmq_status admmq_k_project_format(admmq_ctx *ctx, int kind, const float *W, fl
                                     const uint8_t *flags, const float *scales, const float *inv_scales,
                                     const float *zeros, const float *codebook, float rho, float inv_rho,
                                     float inv_rho_next, int last, uint8_t *codes, float *B_out, float *Xq,
-                                    double *dev_res_sq);
+                                    double *dev_res_sq, unsigned *amax_out = nullptr);
 admmq_status admmq_k_nearest_error(admmq_ctx *ctx, int kind, const float *W0, int64_t ldw, int64_t n, int64_t p,
                                    int bits, int64_t g, const uint8_t *flags, const float *scales,
                                    const float *zeros, const float *codebook, uint8_t *codes, float *E);
@@ -1160,9 +1160,10 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         else
             ADMMQ_TRY(admmq_k_project_format(ctx, pj.kind, Wcur, V, n, p, f.d, f.inv_d, bits, g, pj.flags, pj.scales,
                                              inv_scales, pj.zeros, pj.codebook, rf, 1.0f / rf, 1.0f / rf_next,
-                                             last ? 1 : 0, codes, Wcur, pj.Wq, res + t));
+                                             last ? 1 : 0, codes, Wcur, pj.Wq, res + t,
+                                             fast ? (unsigned *)fbufs.slotsO[0] : nullptr));
         admmq_prof_end(ctx, sp);
-        if (fast && uniform) fbufs.b_max_ready = true;     // (the other formats' pass leaves no maximum: reduced then)
+        if (fast) fbufs.b_max_ready = true;                // (the pass has left the largest |B| in its slot)
         float *tmpp = Bcur;
         Bcur = Wcur;
         Wcur = tmpp;

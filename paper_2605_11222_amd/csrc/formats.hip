@@ -105,11 +105,12 @@ __global__ __launch_bounds__(256) void project_format_kernel(
     const float *W, float *__restrict__ V, long n, long p, const float *__restrict__ d,
     const float *__restrict__ inv_d, const uint8_t *__restrict__ flags, DualGridCols dg,
     const float *__restrict__ codebook, float rho, float inv_rho, float inv_rho_next, uint8_t *__restrict__ codes,
-    float *B, float *__restrict__ Xq, double *__restrict__ res_sq, int vec_ok) {
+    float *B, float *__restrict__ Xq, double *__restrict__ res_sq, int vec_ok, unsigned *__restrict__ amax_out) {
     __shared__ double sh[4];
     const long c0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
     const long row0 = (long)blockIdx.y * FMT_ROWS;
     float acc = 0.f;
+    unsigned bmax = 0;                   // largest |B| written, as the float's bit pattern
     if (c0 < p) {
         const int nc = (int)min(4L, p - c0);
         const bool vec = vec_ok != 0;            // p % 4 == 0 and every array 16-byte aligned (codes, flags: 4)
@@ -170,7 +171,10 @@ __global__ __launch_bounds__(256) void project_format_kernel(
                     bn[c] = __fsub_rn(Dn, __fmul_rn(vn[c], inv_rho_next));
                     kq[c] = (uint8_t)k;
                     xo[c] = xq;
-                    if (c < nc) acc += r * r;
+                    if (c < nc) {
+                        acc += r * r;
+                        bmax = max(bmax, __float_as_uint(fabsf(bn[c])));
+                    }
                 }
                 if (vec) {
                     const floatx4 ov = {vn[0], vn[1], vn[2], vn[3]};
@@ -206,6 +210,13 @@ __global__ __launch_bounds__(256) void project_format_kernel(
         if (lane == 0) sh[w] = tot;
         __syncthreads();
         if (threadIdx.x == 0) atomicAdd(res_sq, (sh[0] + sh[1]) + (sh[2] + sh[3]));
+    }
+    if (amax_out) {
+        // for the split-fp16 products: the largest |B| of the whole pass; a wave whose maximum is already covered
+        // skips the atomic
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) bmax = max(bmax, (unsigned)__shfl_xor((int)bmax, o));
+        if ((threadIdx.x & 63) == 0 && bmax > __atomic_load_n(amax_out, __ATOMIC_RELAXED)) atomicMax(amax_out, bmax);
     }
 }
 
@@ -340,7 +351,7 @@ admmq_status admmq_k_project_format(admmq_ctx *ctx, int kind, const float *W, fl
                                     const uint8_t *flags, const float *scales, const float *inv_scales,
                                     const float *zeros, const float *codebook, float rho, float inv_rho,
                                     float inv_rho_next, int last, uint8_t *codes, float *B_out, float *Xq,
-                                    double *dev_res_sq) {
+                                    double *dev_res_sq, unsigned *amax_out) {
     const long p4 = (p + 3) / 4;
     dim3 block(256), grid((unsigned)((p4 + 255) / 256), (unsigned)((n + FMT_ROWS - 1) / FMT_ROWS));
     DualGridCols dg;
@@ -351,7 +362,7 @@ admmq_status admmq_k_project_format(admmq_ctx *ctx, int kind, const float *W, fl
                        (((uintptr_t)codes | (uintptr_t)flags) % 4 == 0);
 #define ADMMQ_PF(K, LL, LA)                                                                                      \
     hipLaunchKernelGGL((project_format_kernel<K, LL, LA>), grid, block, 0, ctx->stream, W, V, (long)n, (long)p, d, \
-                       inv_d, flags, dg, codebook, rho, inv_rho, inv_rho_next, codes, B_out, Xq, dev_res_sq, vec_ok)
+                       inv_d, flags, dg, codebook, rho, inv_rho, inv_rho_next, codes, B_out, Xq, dev_res_sq, vec_ok, amax_out)
 #define ADMMQ_PF2(K, LL) do { if (last) ADMMQ_PF(K, LL, true); else ADMMQ_PF(K, LL, false); } while (0)
     if (kind == 1) ADMMQ_PF2(1, 2);
     else if (kind == 2 && bits == 1) ADMMQ_PF2(2, 2);
