@@ -2,7 +2,7 @@
 
 The library's header states the scheme: every fp32 operand is scaled by the power of two that brings the matrix's
 largest entry into [2^14, 2^15), split into hi = fp16(s x) and lo = fp16(s x - hi), and the product is accumulated
-as hiA hiB + hiA loB + loA hiB.  These tests pin what the design claims about it: no overflow for any input range,
+as hiA hiB + hiA loB + loA hiB.  These tests pin what that statement promises: no overflow for any input range,
 22 bits kept for every entry within 2^-17 of the largest, each of the three partial products exact in fp32, and a
 product error around 3e-7 of a term - below what fp32 accumulation of a 4096-long sum costs anyway."""
 import numpy as np
