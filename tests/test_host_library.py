@@ -174,6 +174,11 @@ def test_fast_products_switch_and_scratch_size(lib):
     assert fb(512, 512) == 0 and fb(1024, 256) == 0  # too small to fill the chip even in eight slices
     assert fb(4100, 4096) == 0 and fb(4096, 4100) == 0 and fb(0, 4096) == 0
     assert fb(25600, 5120) > fb(12288, 4096) > fb(4096, 4096)
+    # 320 tiles: the 256 that fill a launch round go out whole, the other 64 (1024 columns) in four slices
+    base = 4 * 4096 * 4096 * 2 + 2 * 4096 * 5120 * 2
+    assert base + 4 * 4096 * 1024 * 4 <= fb(4096, 5120) < base + 4 * 4096 * 1024 * 4 + (1 << 16)
+    # 2000 tiles (7.8 rounds): nothing to gain from a split, no partial sums
+    assert fb(25600, 5120) < 4 * 25600 * 25600 * 2 + 2 * 25600 * 5120 * 2 + (1 << 16)
     lib.admmq_destroy(h)
 
 
