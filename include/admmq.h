@@ -233,6 +233,22 @@ admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float *V, int64_
                                 const float *zeros, double rho, double rho_next, uint8_t *codes,
                                 float *B_out, double *res_sq);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): admmq_project_dual without the context's arena.  Its scratch (the fp32 reciprocals of d and of
+ * scales: 4*(n + (n/g)*p) bytes, each rounded up to 256) lives in a fixed array inside the library's device image,
+ * ADMMQ_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends; a shape that needs more returns
+ * ADMMQ_ERR_WORKSPACE before any device work.  The call allocates and frees nothing, clears with a kernel rather
+ * than a memset, and never synchronises: res_sq is a DEVICE pointer here (8-byte aligned double, may be NULL)
+ * that receives ||W - D||_F^2 when the enqueued work completes.  All other arguments, the arithmetic and the
+ * results (codes, V, B_out bit for bit) are those of admmq_project_dual.  Every call on one GPU uses that GPU's
+ * one array, whatever the context or stream: calls that overlap in time on one GPU race - keep them in stream
+ * order. */
+#define ADMMQ_NOALLOC_SCRATCH_BYTES (8u << 20)
+admmq_status admmq_project_dual_noalloc(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                        const float *d, int32_t bits, int32_t group_size, const float *scales,
+                                        const float *zeros, double rho, double rho_next, uint8_t *codes,
+                                        float *B_out, double *res_sq);
+
 /* Grid refresh (Sec. 3.3, App. B) on the state of one iteration: refits (scales, zeros) by min/max of
  * the projection target Sigma (W + V/rho) per group, projects the target on the old and on the refitted
  * grid, and accepts the refit iff ||D_new - Wt||_F^2 <= ||D_old - Wt||_F^2 (eq. 12, scaled variables).

@@ -17,4 +17,5 @@ from .binding import (  # noqa: F401
     EXPORTED_SYMBOLS,
     FORMAT_DUAL_GRID,
     FORMAT_CODEBOOK,
+    NOALLOC_SCRATCH_BYTES,
 )

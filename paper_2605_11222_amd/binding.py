@@ -14,8 +14,10 @@ EXPORTED_SYMBOLS = [
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
     "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit", "admmq_grid_init_dual",
     "admmq_project_dual_format", "admmq_quantize_layer_format", "admmq_quantize_layers",
-    "admmq_set_fast_products", "admmq_fast_products_bytes",
+    "admmq_set_fast_products", "admmq_fast_products_bytes", "admmq_project_dual_noalloc",
 ]
+
+NOALLOC_SCRATCH_BYTES = 8 << 20
 
 FORMAT_DUAL_GRID, FORMAT_CODEBOOK = 1, 2
 
@@ -101,6 +103,7 @@ def load_library():
     lib.admmq_w_update.argtypes = [vp, vp, vp, vp, i64, i64, dbl, vp]
     lib.admmq_project_dual.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp,
                                        C.POINTER(dbl)]
+    lib.admmq_project_dual_noalloc.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp, vp]
     lib.admmq_objective.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.admmq_ls_evaluate.argtypes = [vp, vp, dbl, vp, vp, i64, i64, i32, i32, vp, vp, i32, vp]
     lib.admmq_grid_init_dual.argtypes = [vp, vp, i64, i64, i64, C.POINTER(_Format)]
@@ -334,6 +337,15 @@ class Context:
                                             _ptr(scales), _ptr(zeros), float(rho), float(rho_next), _ptr(codes),
                                             _ptr(B), C.byref(rs)))
         return codes, B, rs.value
+
+    def project_dual_noalloc(self, W, V, d, bits, group_size, scales, zeros, rho, rho_next, codes, B, res_sq):
+        """The same pass for callers that cannot allocate: every output is the caller's (codes u8 [n][p] or None,
+        B fp32 [n][p], res_sq a float64 device tensor of one element or None); V is updated in place.  Nothing is
+        allocated here or in the library, and nothing is synchronised."""
+        n, p = W.shape
+        _check(self._lib.admmq_project_dual_noalloc(self._h, _ptr(W), _ptr(V), n, p, _ptr(d), bits, group_size,
+                                                    _ptr(scales), _ptr(zeros), float(rho), float(rho_next),
+                                                    _ptr(codes), _ptr(B), _ptr(res_sq)))
 
     # ---- other formats (Sec. 4.3) -------------------------------------------------------------------------
     def _format(self, kind, bits, group_size, n, p, device, flags=None, codebook=None, scales=None, zeros=None):

@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -521,6 +522,31 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
 }  // namespace
 
 // ---- context -----------------------------------------------------------------------------------
+// Scratch of admmq_project_dual_noalloc: part of the library's device image, so every GPU the library runs on holds
+// a copy of its own at an address of its own.  In host code the name below is only a handle for
+// hipGetSymbolAddress; the address a kernel may use is looked up once per device (with that device current)
+// when a context is created on it, and only that address is ever passed on.
+static __device__ __align__(256) unsigned char scratch[ADMMQ_NOALLOC_SCRATCH_BYTES];
+enum { ADMMQ_MAX_DEVICES = 64 };
+static void *fixed_scratch_of_device[ADMMQ_MAX_DEVICES];
+static std::mutex fixed_scratch_lock;
+
+static admmq_status fixed_scratch_lookup(int device, void **out) {
+    *out = nullptr;
+    if (device < 0 || device >= ADMMQ_MAX_DEVICES) return ADMMQ_OK;   // the no-alloc call reports the missing array
+    std::lock_guard<std::mutex> hold(fixed_scratch_lock);
+    if (!fixed_scratch_of_device[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return ADMMQ_ERR_DEVICE;
+        }
+        fixed_scratch_of_device[device] = ptr;
+    }
+    *out = fixed_scratch_of_device[device];
+    return ADMMQ_OK;
+}
+
 extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stream) {
     if (!out) return ADMMQ_ERR_NULL;
     *out = nullptr;
@@ -538,10 +564,13 @@ extern "C" admmq_status admmq_create(admmq_ctx **out, int device, void *hip_stre
         return ADMMQ_ERR_DEVICE;
     }
     ADMMQ_HIP(hipSetDevice(device));
+    void *fixed = nullptr;
+    ADMMQ_TRY(fixed_scratch_lookup(device, &fixed));
     admmq_ctx *c = new (std::nothrow) admmq_ctx();
     if (!c) return ADMMQ_ERR_WORKSPACE;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    c->fixed_scratch = fixed;
     *out = c;
     return ADMMQ_OK;
 }
@@ -834,6 +863,33 @@ extern "C" admmq_status admmq_project_dual(admmq_ctx *ctx, const float *W, float
     if (res_sq) ADMMQ_TRY(read_back(ctx, res_sq, dev_res, 8));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;
+}
+
+// The same pass for callers that cannot allocate: reciprocals in the library's fixed per-GPU array, the residual
+// summed straight into the caller's device scalar (cleared by a kernel), no arena, no read-back, no synchronisation.
+extern "C" admmq_status admmq_project_dual_noalloc(admmq_ctx *ctx, const float *W, float *V, int64_t n, int64_t p,
+                                                   const float *d, int32_t bits, int32_t group_size,
+                                                   const float *scales, const float *zeros, double rho,
+                                                   double rho_next, uint8_t *codes, float *B_out, double *res_sq) {
+    if (!ctx || !W || !V || !d || !scales || !zeros || !B_out) return ADMMQ_ERR_NULL;
+    ADMMQ_TRY(check_layer_args(W, W, n, p, p, bits, group_size));
+    if (!(rho > 0.0) || !(rho_next > 0.0) || !isfinite(rho) || !isfinite(rho_next)) return ADMMQ_ERR_PARAM;
+    if (res_sq && ((uintptr_t)res_sq & 7) != 0) return ADMMQ_ERR_PARAM;
+    const int64_t g = group_size > 0 ? group_size : n;
+    const size_t ng = (size_t)(n / g) * p;
+    const size_t off_scales = admmq_align_up((size_t)n * 4);
+    if (off_scales + admmq_align_up(ng * 4) > (size_t)ADMMQ_NOALLOC_SCRATCH_BYTES) return ADMMQ_ERR_WORKSPACE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    if (!ctx->fixed_scratch) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    float *inv_d = (float *)ctx->fixed_scratch;
+    float *inv_scales = (float *)((char *)ctx->fixed_scratch + off_scales);
+    ADMMQ_TRY(admmq_k_recip(ctx, scales, inv_scales, (int64_t)ng));
+    ADMMQ_TRY(admmq_k_recip(ctx, d, inv_d, n));
+    if (res_sq) ADMMQ_TRY(admmq_k_fill_bytes(ctx, res_sq, 0, 8));
+    const float rf = (float)rho;
+    return admmq_k_project_dual(ctx, W, V, n, p, d, inv_d, bits, g, scales, inv_scales, zeros, rf, 1.0f / rf,
+                                1.0f / (float)rho_next, codes, 0, B_out, res_sq, nullptr, p);
 }
 
 extern "C" admmq_status admmq_grid_refresh(admmq_ctx *ctx, const float *W, const float *V, int64_t n, int64_t p,

@@ -66,6 +66,8 @@ struct admmq_ctx {
     int panel_event_count = 0;
     // opt-in: W-update products of whole 256 x 256 tiles as three fp16 matrix-core products of split operands
     bool fast_on = false;
+    // this device's copy of the library's fixed scratch array (the entry point that allocates nothing)
+    void *fixed_scratch = nullptr;
 };
 
 // Returns a span index (or -1 when profiling is off); call admmq_prof_end with it after the launch.

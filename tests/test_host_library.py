@@ -84,6 +84,14 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.admmq_w_update(h, one, one, one, 8, 4, -1.0, one) == 3
     assert lib.admmq_project_dual(h, one, one, 8, 4, one, 4, 3, one, one, 0.5, 0.55, None, one, None) == 2
     assert lib.admmq_project_dual(h, one, one, 8, 4, one, 4, 0, one, one, 0.0, 0.55, None, one, None) == 3
+    # the variant that allocates nothing: same validation, a misaligned residual pointer, and the size limit of its
+    # fixed scratch array (reciprocals of d and of the scales), all before any device work
+    na = lambda **k: lib.admmq_project_dual_noalloc(
+        h, k.get("W", one), one, k.get("n", 8), k.get("p", 4), one, 4, k.get("g", 0), one, one, k.get("rho", 0.5),
+        0.55, None, one, k.get("res", None))
+    assert na(W=None) == 1 and na(g=3) == 2 and na(rho=0.0) == 3 and na(res=C.c_void_p(260)) == 3
+    assert na(n=4096, p=4096, g=4) == 6 and na(n=1 << 20, p=(1 << 20) + 64, g=0) == 6
+    assert na(n=4096, p=4096, g=0) == 8 and na(n=1 << 20, p=1 << 20, g=0) == 8 and na(n=25600, p=5120, g=128, res=C.c_void_p(264)) == 8
     prm = binding._LsParams(1, 1, 4, 0.01, 0)
     assert lib.admmq_local_search(h, one, one, 1, 4, 4, 4, 0, one, one, one, C.byref(prm), None, None, None) == 2
     assert lib.admmq_set_workspace(h, C.c_void_p(100), 1 << 20) == 6
