@@ -90,7 +90,9 @@ admmq_status admmq_accumulate_hessian(admmq_ctx *ctx, float *H, int64_t n, const
 typedef struct {
     int32_t T;             /* ADMM iterations, run exactly unless quiet_stop is set (paper: 300) */
     double rho0;           /* initial penalty (paper: 0.1)                                   */
-    double gamma;          /* growth factor > 1, or exactly 1 for a fixed penalty (paper: 1.1) */
+    double gamma;          /* growth factor > 1, or exactly 1 for a fixed penalty (paper: 1.1).  The penalties reach
+                              the kernels in fp32: rho0 >= 1e-30 and rho0 * gamma^T <= 1e30, else ADMMQ_ERR_PARAM
+                              (the paper's schedule ends at 0.1 * 1.1^300 = 2.6e11) */
     double damp;           /* lambda = damp * Tr(H)/n added to the diagonal (paper App. D: 0.01) */
     int32_t precondition;  /* 1 = diagonal scaling Sigma = Diag(H')^{-1/2} (Sec. 3.2); 0 = Sigma = I */
     int32_t ls_rounds;     /* local-search rounds, 0 = none (paper: at most 5)                */
@@ -102,7 +104,10 @@ typedef struct {
     double clip_shrink;    /* largest shrink of the range searched (App. D: 0.8)                       */
     int32_t reuse_factor;  /* 1 = H, damp and precondition are those of the factorisation the context
                               already holds (admmq_factorize or an earlier layer): skip Alg. 1 lines 1-3.
-                              Matrices that see the same activations (q/k/v, gate/up) share one Hessian. */
+                              Matrices that see the same activations (q/k/v, gate/up) share one Hessian.
+                              The library checks the address of H, n, damp and precondition, not the contents
+                              of H: a Hessian accumulated further in place since it was factorised must be
+                              passed with reuse_factor = 0. */
     uint64_t seed;         /* seed of the pair sampler                                        */
     int32_t quiet_stop;    /* 0 = run exactly T iterations (Alg. 1).  K > 0 (not in the paper's listing): stop
                               after the first iteration at which the codes have been unchanged for K iterations

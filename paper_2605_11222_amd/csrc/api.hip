@@ -1606,8 +1606,16 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     return ADMMQ_OK;
 }
 
+// The loop hands rho_t and its reciprocal to the kernels in fp32, and the dual V = rho_t (W - D) is an fp32 array:
+// a schedule whose last penalty leaves [1e-30, 1e30] would turn them into 0, inf or NaN without any error.
+bool penalty_range_ok(const admmq_schedule *s) {
+    const double last = log(s->rho0) + (double)s->T * log(s->gamma);
+    return s->rho0 >= 1e-30 && last <= log(1e30);
+}
+
 bool schedule_ok(const admmq_schedule *s) {
-    return s->T >= 1 && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
+    return s->T >= 1 && s->T <= (1 << 20) && s->rho0 > 0.0 && s->gamma >= 1.0 && isfinite(s->rho0) &&
+           isfinite(s->gamma) && penalty_range_ok(s) && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
            isfinite(s->gamma) && isfinite(s->damp) && s->ls_rounds >= 0 && s->ls_batches >= 0 && s->ls_pairs >= 0 &&
            s->refresh_iter >= -1 && s->quiet_stop >= 0 && s->clip_points >= 0 && s->clip_points <= 100000 &&
            (s->clip_points == 0 || (s->clip_shrink >= 0.0 && s->clip_shrink < 1.0));

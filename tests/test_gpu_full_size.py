@@ -12,7 +12,7 @@ import pytest
 
 import synth_inputs as si
 from oracle import admmq_oracle as orc
-from gpu_util import to_dev, bf16_bits_to_dev
+from gpu_util import to_dev, bf16_bits_to_dev, assert_differs_only_at_midpoints
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -540,6 +540,12 @@ def test_projection_at_full_size_bit_exact_against_fp32_mirror(ctx, name):
     assert rs == pytest.approx(ss, rel=1e-5)
     assert k.max() == 2 ** bits - 1 and k.min() == 0
     print(f"{name}: {n} x {p}, {bits} bits, group {g or n}: codes, V and B identical to the fp32 mirror")
+    if name == "cfg2":
+        # and against eq. 10 in float64: the codes may differ only within the fp32 rounding band of a midpoint
+        grid = orc.Grid(sc.astype(np.float64), zr.astype(np.float64), bits, sc == 0)
+        k64, _, Wt = orc.d_update(W.astype(np.float64), V.astype(np.float64), rho, d.astype(np.float64), grid)
+        print(f"{name}: {int((k64 != k).sum())} of {k.size} codes differ from the float64 projection")
+        assert_differs_only_at_midpoints(k, k64, Wt, d, sc, zr, g)
 
 
 def test_layer_at_n12288_against_oracle_slice(ctx):

@@ -76,9 +76,11 @@ def test_layer_with_refresh_against_oracle(ctx, n, p, N, bits, g, it, seed):
     assert st.refresh_err_old == pytest.approx(ref.admm.refresh_err_old, rel=2e-2)
     assert st.refresh_err_new == pytest.approx(ref.admm.refresh_err_new, rel=2e-2)
     assert st.j_damp_rtn == pytest.approx(ref.j_damp_rtn, rel=1e-4)
-    # A refit grid hangs on the two extreme elements of each group of a target that already differs in its
-    # last bits between fp32 and float64, so a late attempt (iteration 12) moves the end point more than the
-    # 0.5 % of the base algorithm; early attempts stay inside it.
+    # A refitted grid hangs on the two extreme entries of each group of the projection target.  With the attempt
+    # at iteration 12 of this case the float64 oracle's own end objective moves by 0.6-0.8 % when every W-update
+    # is perturbed by 2e-6 (a fifth of what the W-update is allowed), against 2e-4 without a refresh and 8e-4
+    # with an early one (tests/test_oracle_refresh.py::test_a_late_refresh_amplifies_rounding_of_the_w_update):
+    # no fp32 W-update can be held to 0.5 % there, so the late attempt is compared at four times the bar.
     tol = OBJ_TOL if it <= 6 else 4 * OBJ_TOL
     assert abs(st.j_damp_admm - ref.j_damp_admm) <= tol * ref.j_damp_admm
     assert abs(st.j_damp - ref.j_damp) <= tol * ref.j_damp

@@ -7,7 +7,7 @@ import pytest
 
 import synth_inputs as si
 from oracle import admmq_oracle as orc
-from gpu_util import to_dev, bf16_bits_to_dev, correlated_problem
+from gpu_util import to_dev, bf16_bits_to_dev, correlated_problem, assert_differs_only_at_midpoints
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -175,12 +175,7 @@ def test_projection_codes_bit_exact_against_fp32_mirror(ctx, n, p, bits, g, rho)
     # against the float64 projection: differences only next to a rounding midpoint
     grid = orc.Grid(sc.astype(np.float64), zr.astype(np.float64), bits, sc == 0)
     k64, _, Wt = orc.d_update(W.astype(np.float64), V.astype(np.float64), rho, d.astype(np.float64), grid)
-    diff = k64 != k
-    if diff.any():
-        gg = n if g == 0 else g
-        t = (Wt / d[:, None] - np.repeat(zr, gg, 0)) / np.where(np.repeat(sc, gg, 0) == 0, 1, np.repeat(sc, gg, 0))
-        assert np.all(np.abs(t[diff] - np.floor(t[diff]) - 0.5) < 1e-3)
-    assert diff.mean() < 1e-3
+    assert_differs_only_at_midpoints(k, k64, Wt, d, sc, zr, g)
 
 
 def test_first_projection_of_dense_weights_is_round_to_nearest(ctx):

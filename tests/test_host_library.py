@@ -71,9 +71,12 @@ def test_argument_validation_without_a_gpu(lib):
                 binding._Schedule(10, float("nan"), 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0),
                 binding._Schedule(10, 0.1, 1.1, 0.01, 1, -1, 0, 0, -1, 0, 0, 0.8, 0, 0),
                 binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -2, 0, 0, 0.8, 0, 0),
+                binding._Schedule(930, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),       # 0.1 * 1.1^930 > 1e30
+                binding._Schedule(10, 1e-31, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0),
                 binding._Schedule(10, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0, -1)):      # quiet_stop < 0
         assert q(sched=bad) == 3
     assert q() == 8                       # valid arguments: stops at the missing device
+    assert q(sched=binding._Schedule(300, 0.1, 1.1, 0.01, 1, 0, 0, 0, -1, 0, 0, 0.8, 0, 0)) == 8   # the paper's schedule
     cnt = C.c_uint64(0)
     assert lib.admmq_accumulate_hessian(h, None, 8, one, 0, 4, 8, C.byref(cnt)) == 1
     assert lib.admmq_accumulate_hessian(h, one, 8, one, 0, 4, 7, C.byref(cnt)) == 2

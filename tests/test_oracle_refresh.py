@@ -101,3 +101,34 @@ def test_layer_with_refresh_keeps_bookkeeping_consistent():
     assert np.allclose(res.Wq, np.repeat(res.zeros, 16, axis=0) + res.codes * np.repeat(res.scales, 16, axis=0))
     assert res.j_damp <= res.j_damp_admm
     assert res.j_damp == pytest.approx(orc.objective(orc.damp_hessian(H)[0], W0, res.Wq), rel=1e-12)
+
+
+def test_a_late_refresh_amplifies_rounding_of_the_w_update():
+    """Why an fp32 implementation cannot be held to the base algorithm's 0.5 % objective bar when the refresh is
+    tried late: the refitted grid hangs on the two extreme entries of each group of the projection target, so a
+    relative perturbation of 2e-6 of every W-update (a fifth of the 1e-5 the W-update is allowed) moves the
+    float64 oracle's own end objective by close to 1 % with the attempt at iteration 12, against a few 1e-4
+    without a refresh.  The GPU test of that case therefore carries a wider tolerance."""
+    import sys
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from gpu_util import correlated_problem
+    n, p, N, bits, g, seed = 256, 130, 300, 4, 64, 5
+    X, W0 = correlated_problem(n, p, N, seed, outliers=2)
+    H = orc.hessian([X.astype(np.float64)])
+    exact = orc.w_update
+    spread = {}
+    try:
+        for it in (-1, 12):
+            js = []
+            for s in range(4):
+                rng = np.random.default_rng(200 + s)
+                orc.w_update = lambda *a, _r=rng: (lambda W: W * (1 + 2e-6 * _r.standard_normal(W.shape)))(exact(*a))
+                js.append(orc.quantize_layer(H, W0.astype(np.float64), bits, g, T=80, ls_rounds=0,
+                                             refresh_iter=it).j_damp_admm)
+            spread[it] = (max(js) - min(js)) / np.mean(js)
+    finally:
+        orc.w_update = exact
+    print(spread)
+    assert spread[-1] < 1e-3
+    assert spread[12] > 3 * spread[-1] and spread[12] > 2e-3

@@ -127,6 +127,42 @@ def test_first_iterate_is_dense_weights_and_rtn():
     assert np.array_equal(orc.rtn(W0, grid)[0], k_rtn)
 
 
+def test_second_iterate_in_closed_form_pins_the_dual_update_and_the_penalty_index():
+    """Eqs. 7-9 over the first two iterations, written out from what the first iteration is known to be: the first
+    W-update returns Ws (D0 = Ws, V0 = 0), so D1 = Sigma^{-1} RTN(W0), V1 = rho_0 (Ws - D1) by eq. 9, rho_1 = gamma
+    rho_0, and W2 solves (Hs + rho_1 I) W2 = Hs Ws + rho_1 D1 - V1 (eq. 7, through a dense solve here, not the
+    eigendecomposition).  The recorded residuals of a two-iteration run must be those of this closed form: a dual
+    update with the sign flipped, with rho_1 in place of rho_0, or a W-update that takes the penalty of the wrong
+    iteration, changes W2 and with it both residuals."""
+    X, W0 = tiny_problem(n=24, p=7, N=70, seed=11)
+    Hd, _ = orc.damp_hessian(orc.hessian([X]))
+    grid = orc.Grid.fit(W0, 3, 0)
+    rho0, gamma = 0.1, 1.1
+    res = orc.admm(Hd, W0, grid, T=2, rho0=rho0, gamma=gamma)
+    d = np.sqrt(np.diag(Hd))
+    Hs = Hd / np.outer(d, d)
+    Ws = W0 * d[:, None]
+    levels = grid.z0[0][None, :, None] + np.arange(8)[None, None, :] * grid.delta[0][None, :, None]
+    k1 = np.argmin(np.abs(levels - W0[:, :, None]), axis=2)               # round-to-nearest, brute force
+    D1 = d[:, None] * np.take_along_axis(levels, k1[:, :, None], axis=2)[:, :, 0]
+    V1 = rho0 * (Ws - D1)
+    rho1 = gamma * rho0
+    W2 = np.linalg.solve(Hs + rho1 * np.eye(len(d)), Hs @ Ws + rho1 * D1 - V1)
+    x2 = (W2 + V1 / rho1) / d[:, None]
+    k2 = np.argmin(np.abs(levels - x2[:, :, None]), axis=2)
+    D2 = d[:, None] * np.take_along_axis(levels, k2[:, :, None], axis=2)[:, :, 0]
+    assert res.rho == pytest.approx([rho0, rho1], rel=1e-15)
+    assert res.primal[0] == pytest.approx(np.linalg.norm(Ws - D1), rel=1e-10)
+    assert res.primal[1] == pytest.approx(np.linalg.norm(W2 - D2), rel=1e-9)
+    assert res.dual[1] == pytest.approx(np.linalg.norm(D2 - D1), rel=1e-9)
+    assert np.array_equal(res.codes, k2)
+    assert np.any(k2 != k1)                                               # the second iterate has moved
+    # the variants this is meant to catch do change the numbers (so the equalities above are not vacuous)
+    for V_bad, rho_bad in ((-V1, rho1), (rho1 * (Ws - D1), rho1), (V1, rho0)):
+        W_bad = np.linalg.solve(Hs + rho_bad * np.eye(len(d)), Hs @ Ws + rho_bad * D1 - V_bad)
+        assert np.linalg.norm(W_bad - W2) > 1e-6 * np.linalg.norm(W2)
+
+
 def test_key_inequality_residual_decay_and_rtn_no_worse_cfg1():
     cfg, H, W0 = cfg1_problem()
     Hd, _ = orc.damp_hessian(H)
