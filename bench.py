@@ -4,8 +4,9 @@
 A "step" is one pass of the whole hot path over one synthetic layer: Hessian accumulation over all
 calibration tokens, then admmq_quantize_layer (damping, scaling, factorisation, T ADMM iterations,
 pair-swap local search).  Inputs are resident in HBM before the timed region starts.  Prints ONE JSON
-line.  `value` is ADMM iterations per second over the ADMM loop alone; the layer time and the Hessian
-time are reported beside it.  The oracle (float64 NumPy) is timed on the host on a bounded sample.
+line.  `value` is ADMM iterations per second over the ADMM loop alone, counting the T-1 iterations that run the
+W-update products (the first iteration's W-update returns the dense weights and is skipped); the layer time and
+the Hessian time are reported beside it.  The oracle (float64 NumPy) is timed on the host on a bounded sample.
 """
 import argparse
 import json
@@ -24,7 +25,9 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (the fp16 peak is the same)
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, both
-# calibrated at 1.00 against plain fill / copy kernels of known size); see profiles/cfg2_hbm_traffic_pmc.txt
+# calibrated at 1.00 against plain fill / copy kernels of known size).  These are figures of those counter runs
+# (fewer tokens and iterations than the timed run: counters perturb timing), not of the run timed here.
+PMC_TRAFFIC_FROM = {"cfg2": "profiles/cfg2_hbm_traffic_pmc.txt (rocprofv3 --pmc, 16384 tokens, 6 iterations)"}
 PMC_TRAFFIC_BYTES = {
     "cfg2": {"gemm": (227176.3 + 65536.0) * 1024, "project": (65784.5 + 131104.0) * 1024,
              # the opt-in products (profiles/bench_cfg2_fast_products_kernel_trace.txt): product kernel + operand split
@@ -82,7 +85,21 @@ def cpu_baseline(cfg, sample_cols=1024, sample_iters=8, sample_tokens=8192):
         t_admm = float("nan")
     its_slice = sample_iters / t_admm
     its_full = its_slice * sample_cols / cfg.p      # the loop is linear in the number of columns
+    # local search (Sec. 3.5): one round of a bounded number of batches on the round-to-nearest codes of the slice
+    ls_batches = 96
+    k_rtn, _ = orc.rtn(W0, grid)
+    G0 = Hd @ (W0 - grid.dequant(k_rtn))             # the gradient product is set-up, not part of a batch
+    t0 = time.perf_counter()
+    ls = orc.local_search(Hd, W0, k_rtn, grid, rounds=1, batches_per_round=ls_batches, pairs_per_batch=64,
+                          seed=cfg.seed, G=G0)
+    t_ls = time.perf_counter() - t0
+    ls_slice = ls_batches / t_ls
     return {
+        "phases": {"hessian_tokens_per_s": min(sample_tokens, cfg.tokens) / t_h, "eig_s": t_eig,
+                   "admm_iterations_per_s": None if its_full != its_full else its_full,
+                   "local_search_batches_per_s": ls_slice * sample_cols / cfg.p,
+                   "local_search_sample": f"{ls_batches} batches of 64 pairs on {sample_cols} columns: "
+                                          f"{ls_slice:.1f} batches/s, {ls.moves} applied; scaled by {sample_cols}/{cfg.p}"},
         "value": None if its_full != its_full else its_full, "unit": "ADMM iterations/s", "cores": int(cores), "kind": "oracle",
         "sample": (f"{cfg.name}: first {sample_cols} of {cfg.p} columns, {sample_iters} of {cfg.T} iterations (a run of "
                    f"{2 + sample_iters} minus a run of 2), "
@@ -155,7 +172,7 @@ def main():
 
     mean = lambda f: float(np.mean([f(s) for s in stats]))
     admm_ms = mean(lambda s: s.ms_admm)
-    its = T / (admm_ms * 1e-3)
+    its = (T - 1) / (admm_ms * 1e-3) if T > 1 else T / (admm_ms * 1e-3)
     n, p = cfg.n, cfg.p
     gemm_ms = mean(lambda s: s.ms_gemm / max(s.n_gemm, 1))
     proj_ms = mean(lambda s: s.ms_project / max(s.n_project, 1))
@@ -171,13 +188,28 @@ def main():
     hess_bf16 = cfg.x_dtype == "bf16" and n % 256 == 0 and os.environ.get("ADMMQ_HESSIAN_BF16", "1") != "0"
     hess_peak = PEAK_BF16_MFMA_TFLOPS if hess_bf16 else PEAK_FP32_MFMA_TFLOPS
 
+    # what a plain streaming kernel of the library reaches on this machine: 1 GiB copied (1 GiB read + 1 GiB written)
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    ctx.stream_copy(dst, src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        ctx.stream_copy(dst, src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    assert torch.equal(dst, src)
+    del src, dst
+
     line = {
         "metric": "layer quantize time (s) & ADMM iters/s, 4096x4096 W3; % fp32 MFMA peak",
         "value": its, "unit": "ADMM iterations/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} p={p} tokens={tokens} W{cfg.bits} group={cfg.group_size or 'per-channel'} "
-                               f"T={T} ls_rounds={args.ls_rounds}"},
+                               f"T={T} ls_rounds={args.ls_rounds}",
+                   "iterations_counted": f"{max(T - 1, 1)} of {T}: those that run the two W-update products"},
         "layer_quantize_time_s": mean(lambda s: s.ms_total) * 1e-3,
         "phases_s": {"hessian": hess_ms * 1e-3, "setup": mean(lambda s: s.ms_setup) * 1e-3,
                      "factorise": mean(lambda s: s.ms_factor) * 1e-3, "admm": admm_ms * 1e-3,
@@ -189,11 +221,16 @@ def main():
                      "achieved": gemm_tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tf / PEAK_FP32_MFMA_TFLOPS,
                      "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm"),
+                     "traffic_from": PMC_TRAFFIC_FROM.get(cfg.name),
                      "ms_per_launch": gemm_ms, "flop_per_launch": 2.0 * n * n * p},
         "roofline_projection": {"kernel": "project_dual", "bound": "hbm", "achieved": proj_gbs, "peak": PEAK_HBM_GBS,
                                 "unit": "GB/s", "frac": proj_gbs / PEAK_HBM_GBS,
                                 "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("project"),
-                                "ms_per_launch": proj_ms, "bytes_per_launch": 16.0 * n * p},
+                                "traffic_from": PMC_TRAFFIC_FROM.get(cfg.name),
+                                "ms_per_launch": proj_ms, "bytes_per_launch": 16.0 * n * p,
+                                "copy_kernel_GBs": copy_gbs, "frac_of_copy_kernel": proj_gbs / copy_gbs,
+                                "copy_kernel": "admmq_stream_copy of 1 GiB (2 GiB moved), mean of 10 launches "
+                                               "between events, in this run"},
         "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
                               "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},

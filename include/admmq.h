@@ -73,6 +73,12 @@ admmq_status admmq_set_workspace(admmq_ctx *ctx, void *dev_ptr, size_t bytes);
 admmq_status admmq_set_fast_products(admmq_ctx *ctx, int32_t on);
 size_t admmq_fast_products_bytes(int64_t n, int64_t p);
 
+/* Measurement aid (no counterpart in the paper): copies `bytes` (a multiple of 16; both pointers device, 16-byte
+ * aligned, not overlapping) with a plain streaming kernel on the context's stream.  bench.py times it on 1 GiB as
+ * the bandwidth a kernel of this library reaches on the box at hand, beside the published HBM peak, and the
+ * hardware-counter runs use it to calibrate FETCH_SIZE / WRITE_SIZE. */
+admmq_status admmq_stream_copy(admmq_ctx *ctx, void *dst, const void *src, size_t bytes);
+
 /* ---- Hessian accumulation (Sec. 3.1: H = X^T X) ------------------------------------------- */
 
 /* H [n][n] (device fp32, caller zero-initialises before the first chunk) += X^T X for a chunk
@@ -196,6 +202,14 @@ admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const float *W0,
                                 int64_t ldw, int32_t bits, int32_t group_size, const float *scales,
                                 const float *zeros, uint8_t *codes, const admmq_ls_params *prm,
                                 const int32_t *explicit_pairs, int32_t *moves_out, double *drop_out);
+
+/* Diagnostic.  The search runs each group of 16 batches as one launch whose blocks hand their partial sums to one
+ * another through memory, with every wait bounded; a group that gives up a wait is left unapplied, and it and
+ * everything after it is redone with one launch per batch (same result, bit for bit).  Returns how many groups of
+ * the last local search on this context (stand-alone or inside a layer call) went that way; 0 is the normal case.
+ * Environment: ADMMQ_LS_PERSISTENT=0 turns the grouped form off; ADMMQ_LS_SPIN_TICKS sets the bound of a wait in
+ * ticks of the device's wall clock (default 20 ms; a negative value makes every block give up at once). */
+int32_t admmq_ls_fallback_count(const admmq_ctx *ctx);
 
 /* The pair sampler of the local search, on the host: SplitMix64 (Steele, Lea, Flood 2014) keyed by
  * (seed, round, batch, slot); writes i1 != i2 in [0, n). */

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "admmq_grid_init", "admmq_factorize", "admmq_w_update", "admmq_project_dual", "admmq_objective",
     "admmq_ls_evaluate", "admmq_grid_refresh", "admmq_grid_fit", "admmq_grid_init_dual",
     "admmq_project_dual_format", "admmq_quantize_layer_format", "admmq_quantize_layers",
-    "admmq_set_fast_products", "admmq_fast_products_bytes", "admmq_project_dual_noalloc",
+    "admmq_set_fast_products", "admmq_fast_products_bytes", "admmq_project_dual_noalloc", "admmq_stream_copy", "admmq_ls_fallback_count",
 ]
 
 NOALLOC_SCRATCH_BYTES = 8 << 20
@@ -104,6 +104,8 @@ def load_library():
     lib.admmq_project_dual.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp,
                                        C.POINTER(dbl)]
     lib.admmq_project_dual_noalloc.argtypes = [vp, vp, vp, i64, i64, vp, i32, i32, vp, vp, dbl, dbl, vp, vp, vp]
+    lib.admmq_stream_copy.argtypes = [vp, vp, vp, C.c_size_t]
+    lib.admmq_ls_fallback_count.argtypes = [vp]
     lib.admmq_objective.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, dbl, C.POINTER(dbl)]
     lib.admmq_ls_evaluate.argtypes = [vp, vp, dbl, vp, vp, i64, i64, i32, i32, vp, vp, i32, vp]
     lib.admmq_grid_init_dual.argtypes = [vp, vp, i64, i64, i64, C.POINTER(_Format)]
@@ -234,6 +236,16 @@ class Context:
     def set_workspace(self, buf):
         _check(self._lib.admmq_set_workspace(self._h, _ptr(buf), buf.numel() * buf.element_size()))
         self._ws = buf
+
+    def stream_copy(self, dst, src):
+        """dst <- src by the library's plain copy kernel (measurement aid); same byte size, a multiple of 16."""
+        nbytes = src.numel() * src.element_size()
+        assert nbytes == dst.numel() * dst.element_size()
+        _check(self._lib.admmq_stream_copy(self._h, _ptr(dst), _ptr(src), nbytes))
+
+    def ls_fallback_count(self):
+        """Groups of the last local search that were redone with one launch per batch (0 normally)."""
+        return int(self._lib.admmq_ls_fallback_count(self._h))
 
     def accumulate_hessian(self, H, X):
         """H fp32 [n][n] += X^T X for a chunk X [rows][n] (float32 or bfloat16 tensor)."""

@@ -40,7 +40,17 @@ admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const
                              const int32_t *pairs_next, int npairs_next, const float *exs_cur, float *exs_next);
 int admmq_ls_fast_pairs();
 admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
-                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count);
+                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count,
+                              const int *commit = nullptr, int commit_needed = 0);
+int admmq_ls_group_pairs_per_thread(admmq_ctx *ctx, int64_t p, int npairs);
+size_t admmq_ls_group_xch_words(int64_t p);
+int admmq_ls_group_max_blocks(int64_t p);
+admmq_status admmq_k_ls_group(admmq_ctx *ctx, int pairs_per_thread, const float *H, float lambda, const float *G,
+                              const uint8_t *codes, int64_t n, int64_t p, int bits, int64_t g, const float *scales,
+                              const int32_t *pairs, int npairs, int cnt, unsigned seq0, int group_seq,
+                              unsigned long long *xch, unsigned *fin, int *commit, int *abort_word,
+                              long long spin_ticks, int32_t *pend_idx, float *pend_d, int *dev_moves,
+                              double *dev_drop);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
 admmq_status admmq_k_dual_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
                                     int64_t g, const uint8_t *flags, float *scales, float *zeros);
@@ -163,7 +173,8 @@ size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_p
            2 * admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
            admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) +
            2 * admmq_align_up((size_t)pairs_per_batch * p) + admmq_align_up((size_t)2 * admmq_ls_defer() * n * 4) +
-           2 * admmq_align_up((size_t)admmq_ls_fast_pairs() * admmq_ls_fast_pairs() * 16) + 65536;
+           2 * admmq_align_up((size_t)admmq_ls_fast_pairs() * admmq_ls_fast_pairs() * 16) +
+           admmq_align_up(admmq_ls_group_xch_words(p) * 8) + admmq_align_up((size_t)admmq_ls_group_max_blocks(p) * 4) + 65536;
 }
 
 admmq_status read_back(admmq_ctx *ctx, void *host, const void *dev, size_t bytes) {
@@ -454,8 +465,36 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     float *exs[2] = {exs_a, exs_b};
     const bool ahead = plan.pairs <= FP;
     ADMMQ_TRY(take(ctx, choice, 4));
-    ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double), scal[1] reinterpreted: moves (int)
+    ADMMQ_TRY(take(ctx, scal, 4));      // scal[0] = drop (double); as ints: scal[1] -> moves, scal[2] -> commit, abort
     int *dev_moves = (int *)(scal + 1);
+    int *dev_commit = (int *)(scal + 2), *dev_abort = dev_commit + 1;
+    // groups of K batches as single launches (blocks exchange their partial sums through memory) where the shape
+    // allows; ADMMQ_LS_PERSISTENT=0 keeps one launch per batch; ADMMQ_LS_SPIN_TICKS sets the bound of a wait in
+    // ticks of the device's wall clock (negative: every block gives up at its first wait - exercises the fall-back)
+    const int group_pp = admmq_ls_group_pairs_per_thread(ctx, p, plan.pairs);
+    bool grouped = group_pp > 0;
+    {
+        const char *e = getenv("ADMMQ_LS_PERSISTENT");
+        if (e && atoi(e) == 0) grouped = false;
+    }
+    long long spin_ticks = 0;
+    unsigned long long *xch = nullptr;
+    unsigned *fin = nullptr;
+    if (grouped) {
+        int khz = 0;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, ctx->device) != hipSuccess || khz <= 0) {
+            (void)hipGetLastError();
+            khz = 100000;
+        }
+        spin_ticks = 20ll * khz;                                            // 20 ms
+        const char *e = getenv("ADMMQ_LS_SPIN_TICKS");
+        if (e) spin_ticks = atoll(e);
+        ADMMQ_TRY(take(ctx, xch, admmq_ls_group_xch_words(p)));
+        ADMMQ_TRY(take(ctx, fin, (size_t)admmq_ls_group_max_blocks(p)));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, xch, 0, admmq_ls_group_xch_words(p) * 8));
+        ADMMQ_TRY(admmq_k_fill_bytes(ctx, fin, 0, (size_t)admmq_ls_group_max_blocks(p) * 4));
+    }
+    ctx->ls_fallback_groups = 0;
 
     std::vector<int32_t> hp;
     const int32_t *src = explicit_pairs;
@@ -488,30 +527,65 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     int moves_total = 0;
     float *part[2] = {partial, partial_b};
     uint8_t *mv[2] = {mv_a, mv_b};
-    for (int r = 0; r < plan.rounds; ++r) {
-        // step s evaluates batch s (s < M) and plans batch s-1 (s > 0) in one launch; G is flushed after the
-        // step that fills the last pending slot, and at the end of the round
-        for (int s = 0; s <= plan.batches; ++s) {
-            const int32_t *cur = s < plan.batches ? pairs + ((size_t)r * plan.batches + s) * plan.pairs * 2 : nullptr;
-            const int32_t *prev = s > 0 ? pairs + ((size_t)r * plan.batches + s - 1) * plan.pairs * 2 : nullptr;
-            const int slot_prev = s > 0 ? (s - 1) % K : 0;
-            const int32_t *next = (ahead && s + 1 < plan.batches)
-                                      ? pairs + ((size_t)r * plan.batches + s + 1) * plan.pairs * 2 : nullptr;
-            ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, prev,
-                                      s > 0 ? plan.pairs : 0, part[(s + 1) & 1], mv[(s + 1) & 1], slot_prev, cur,
-                                      plan.pairs, s > 0 ? slot_prev : 0, pend_idx, pend_d, hcol, part[s & 1],
-                                      mv[s & 1], choice, dev_moves, scal, next, plan.pairs,
-                                      (ahead && s > 0 && cur) ? exs[(s + 1) & 1] : nullptr,
-                                      next ? exs[s & 1] : nullptr));
-            if (s > 0 && (slot_prev == K - 1 || s == plan.batches))
-                ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, slot_prev + 1));
+    auto batch_pairs = [&](int r, int b) { return pairs + ((size_t)r * plan.batches + b) * plan.pairs * 2; };
+    // The batches of a round go in groups of K.  A group starts from codes and a gradient that hold every earlier
+    // move, evaluates its batches one after the other against the moves of the batches before (kept as pending
+    // slots), and ends with one pass over G (the flush).
+    // One launch per batch: step s of a group evaluates its batch s (s < cnt) and plans its batch s-1 (s > 0).
+    auto run_stepwise = [&](int r, int b0) -> admmq_status {
+        for (int gb = b0; gb < plan.batches; gb += K) {
+            const int cnt = plan.batches - gb < K ? plan.batches - gb : K;
+            for (int s = 0; s <= cnt; ++s) {
+                const int32_t *cur = s < cnt ? batch_pairs(r, gb + s) : nullptr;
+                const int32_t *prev = s > 0 ? batch_pairs(r, gb + s - 1) : nullptr;
+                const int slot_prev = s > 0 ? s - 1 : 0;
+                const int32_t *next = (ahead && s + 1 < cnt) ? batch_pairs(r, gb + s + 1) : nullptr;
+                ADMMQ_TRY(admmq_k_ls_step(ctx, H, (float)lambda, G, codes, n, p, bits, g, scales, prev,
+                                          s > 0 ? plan.pairs : 0, part[(s + 1) & 1], mv[(s + 1) & 1], slot_prev, cur,
+                                          plan.pairs, slot_prev, pend_idx, pend_d, hcol, part[s & 1], mv[s & 1],
+                                          choice, dev_moves, scal, next, plan.pairs,
+                                          (ahead && s > 0 && cur) ? exs[(s + 1) & 1] : nullptr,
+                                          next ? exs[s & 1] : nullptr));
+            }
+            ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, cnt));
         }
-        double host[2];
-        ADMMQ_TRY(read_back(ctx, host, scal, 16));
-        int mv;
-        memcpy(&mv, &host[1], sizeof(int));
-        const bool none = mv == moves_total;
-        moves_total = mv;
+        return ADMMQ_OK;
+    };
+    int groups_launched = 0;       // group kernels issued so far in this call (= value the commit counter should reach)
+    for (int r = 0; r < plan.rounds; ++r) {
+        const int first_group = groups_launched;
+        if (grouped) {
+            for (int gb = 0; gb < plan.batches; gb += K) {
+                const int cnt = plan.batches - gb < K ? plan.batches - gb : K;
+                const unsigned seq0 = 1u + (unsigned)((size_t)r * plan.batches + gb);
+                ADMMQ_TRY(admmq_k_ls_group(ctx, group_pp, H, (float)lambda, G, codes, n, p, bits, g, scales, batch_pairs(r, gb),
+                                           plan.pairs, cnt, seq0, groups_launched, xch, fin, dev_commit, dev_abort,
+                                           spin_ticks, pend_idx, pend_d, dev_moves, scal));
+                ++groups_launched;
+                ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, cnt, dev_commit,
+                                           groups_launched));
+            }
+        } else {
+            ADMMQ_TRY(run_stepwise(r, 0));
+        }
+        double host[3];
+        ADMMQ_TRY(read_back(ctx, host, scal, 24));
+        if (grouped) {
+            int committed;
+            memcpy(&committed, &host[2], sizeof(int));
+            if (committed < groups_launched) {
+                // a group gave up waiting: nothing after it has run.  Its batches and the rest of the round go
+                // one launch per batch, and so does the rest of the search.
+                ctx->ls_fallback_groups += groups_launched - committed;
+                grouped = false;
+                ADMMQ_TRY(run_stepwise(r, (committed - first_group) * K));
+                ADMMQ_TRY(read_back(ctx, host, scal, 24));
+            }
+        }
+        int mvd;
+        memcpy(&mvd, &host[1], sizeof(int));
+        const bool none = mvd == moves_total;
+        moves_total = mvd;
         if (drop_out) *drop_out = host[0];
         if (none) break;
     }
@@ -648,6 +722,15 @@ extern "C" admmq_status admmq_set_fast_products(admmq_ctx *ctx, int32_t on) {
 extern "C" size_t admmq_fast_products_bytes(int64_t n, int64_t p) {
     if (n < 1 || p < 1 || !admmq_gemm_f16x3_ok(n, p, n)) return 0;
     return fast_products_bytes(n, p);
+}
+
+// Measurement aid: a plain device-to-device copy by a kernel of this library.
+extern "C" admmq_status admmq_stream_copy(admmq_ctx *ctx, void *dst, const void *src, size_t bytes) {
+    if (!ctx || !dst || !src) return ADMMQ_ERR_NULL;
+    if (bytes % 16 != 0 || (((uintptr_t)dst | (uintptr_t)src) & 15) != 0) return ADMMQ_ERR_SHAPE;
+    if (ctx->device < 0) return ADMMQ_ERR_DEVICE;
+    ADMMQ_HIP(hipSetDevice(ctx->device));
+    return admmq_k_stream_copy(ctx, dst, src, bytes);
 }
 
 // ---- Hessian -----------------------------------------------------------------------------------
@@ -982,6 +1065,8 @@ extern "C" void admmq_sample_pair(uint64_t seed, int32_t round, int32_t batch, i
     *i1 = (int32_t)a;
     *i2 = (int32_t)b;
 }
+
+extern "C" int32_t admmq_ls_fallback_count(const admmq_ctx *ctx) { return ctx ? ctx->ls_fallback_groups : 0; }
 
 // ---- local search alone --------------------------------------------------------------------------
 extern "C" admmq_status admmq_local_search(admmq_ctx *ctx, const float *H, const float *W0, int64_t n, int64_t p,
@@ -1521,6 +1606,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             for (int w = 1; w < workers; ++w) ADMMQ_HIP(hipStreamWaitEvent(ctx->side[w - 1], ctx->side_ready, 0));
             char *base = ctx->arena + ctx->persist_top;
             std::vector<admmq_status> result((size_t)workers, ADMMQ_OK);
+            std::vector<int> redone((size_t)workers, 0);
             auto run = [&](int w) {
                 if (hipSetDevice(ctx->device) != hipSuccess) {
                     result[w] = ADMMQ_ERR_DEVICE;
@@ -1532,6 +1618,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
                 child.arena = base + start[w];
                 child.arena_bytes = slice[w];
                 child.arena_owned = false;
+                child.ls_side_by_side = workers;      // the searches share the chip: each may hold its share of blocks
                 for (int i = w; i < count; i += workers) {
                     const admmq_layer &l = L[i];
                     child.top = child.persist_top = 0;
@@ -1544,6 +1631,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
                         result[w] = s;
                         break;
                     }
+                    redone[w] += child.ls_fallback_groups;
                 }
                 // every search ends with a read-back on its stream; after a failure, drain what was queued
                 if (result[w] != ADMMQ_OK) (void)hipStreamSynchronize(child.stream);
@@ -1560,15 +1648,22 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             run(0);
             for (int w : inline_share) run(w);
             for (auto &h : helpers) h.join();
-            for (int w = 0; w < workers; ++w) ADMMQ_TRY(result[w]);
+            ctx->ls_fallback_groups = 0;
+            for (int w = 0; w < workers; ++w) {
+                ADMMQ_TRY(result[w]);
+                ctx->ls_fallback_groups += redone[w];
+            }
         } else {
+            int redone_all = 0;
             for (int i = 0; i < count; ++i) {
                 const admmq_layer &l = L[i];
                 admmq_arena_reset_transient(ctx);
                 double drop = 0.0;
                 ADMMQ_TRY(local_search_core(ctx, H, lambda, l.W0, n, l.p, l.ldw, l.bits, grp[i], l.scales, l.zeros,
                                             l.codes, plan, sched->seed, nullptr, &moves[i], &drop));
+                redone_all += ctx->ls_fallback_groups;
             }
+            ctx->ls_fallback_groups = redone_all;
         }
         ms_ls = t_phase.stop();
         if (want) {

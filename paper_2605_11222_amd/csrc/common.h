@@ -66,6 +66,11 @@ struct admmq_ctx {
     int panel_event_count = 0;
     // opt-in: W-update products of whole 256 x 256 tiles as three fp16 matrix-core products of split operands
     bool fast_on = false;
+    // groups of the last local search on this context that gave up a bounded wait and were redone batch by batch
+    int ls_fallback_groups = 0;
+    // how many local searches run side by side on the device (the batched call's helper contexts): a search whose
+    // blocks wait for one another may only launch what fits beside the others
+    int ls_side_by_side = 1;
     // this device's copy of the library's fixed scratch array (the entry point that allocates nothing)
     void *fixed_scratch = nullptr;
 };
@@ -167,6 +172,8 @@ admmq_status admmq_k_scale_rows(admmq_ctx *ctx, const float *W0, int64_t ldw, co
 // B = D - V * inv_rho
 admmq_status admmq_k_form_b(admmq_ctx *ctx, const float *D, const float *V, float inv_rho, int64_t count,
                             float *B);
+// dst[0, bytes) = src[0, bytes), bytes a multiple of 16, both 16-byte aligned
+admmq_status admmq_k_stream_copy(admmq_ctx *ctx, void *dst, const void *src, size_t bytes);
 admmq_status admmq_k_fill_f32(admmq_ctx *ctx, float *x, float v, int64_t count);
 admmq_status admmq_k_fill_bytes(admmq_ctx *ctx, void *x, int v, size_t bytes);
 // mode 0: E = dequant(codes) - W0; mode 1: E = W0 - dequant(codes); mode 2: codes := round-to-nearest

@@ -421,12 +421,450 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
     if (tid == 0) partial_cur[(long)blockIdx.y * chunks + blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
+// ---- a whole group of up to LS_K batches in ONE launch ----------------------------------------------------------
+// The batches of a group depend on one another only through the winner of the batch before (its move changes the
+// gradient rows and codes the next candidates are evaluated against), and what the blocks of a batch owe one
+// another is one number per candidate pair: its summed gain.  So the group runs as one kernel whose blocks stay
+// on the chip and hand those sums to one another through a table in global memory:
+//   grid (ceil(p / 256), ceil(npairs / (4 PP))), block 1024: wave w works on the pairs 4 PP y + 4 i + w/4, i < PP,
+//   at the 64 columns 256 x + 64 (w%4) + lane.  PP = 1 (one candidate pair and one column per thread, as in the
+//   launch-per-batch kernel) unless that would be more blocks than the chip holds at once.
+//   Per batch: evaluate the own pair; the four wave sums of a pair add up to the block's 256-column sum, which
+//   one thread stores into table[pair][x] together with the batch's sequence number (one 8-byte word, so a
+//   reader that sees the number sees the value); every block reads the whole table, adds each pair's sums in
+//   chunk order and finds the winner - the same sums in the same order as the launch-per-batch kernels, hence
+//   the same winner everywhere.  The winner's steps at a block's 256 columns are not exchanged: four waves
+//   evaluate the winning pair again from the same inputs in the same order, which gives the same bits.
+//   Everything else a block needs is read-only during the group (H, G, codes, scales, the sampled pairs) or its
+//   own (the steps applied so far at its columns, in LDS).
+// Waiting is bounded: a poll that sees no progress for `spin_ticks` of the wall clock (or finds the abort word
+// set by another block) makes its block leave, and the group then stays uncommitted: the flush that follows and
+// all later group kernels check the commit counter and do nothing, and the host repeats the work from that group
+// on with one launch per batch.  All blocks must be resident at once: the host picks PP from the occupancy the
+// runtime reports for this kernel.
+constexpr int LSG_TILE = 256;                          // columns per block
+constexpr int LSG_PB_MAX = 8;                          // candidate pairs per block: 4 PP, PP = pairs per thread (1 or 2)
+constexpr int LSG_MAX_CHUNKS = 32;
+
+struct LsGroupArgs {
+    const float *H;
+    float lambda;
+    const float *G;
+    const uint8_t *codes;
+    long n, p;
+    int levels;
+    long g;
+    const float *scales;
+    const int32_t *pairs;           // [cnt][npairs][2]: the group's batches
+    int npairs, cnt;
+    unsigned seq0;                  // sequence number of the group's first batch (>= 1, unique within the call)
+    int group_seq;                  // how many groups must have been committed before this one
+    unsigned long long *xch;        // [2][LS_FAST_PAIRS][chunks]: (sequence number << 32) | float bits
+    unsigned *fin;                  // [blocks]: group_seq + 1 once a block is through
+    int *commit;                    // groups committed so far
+    int *abort_word;
+    long long spin_ticks;
+    int32_t *pend_idx;              // out [2 cnt]
+    float *pend_d;                  // out [2 cnt][p]
+    int *moves;
+    double *drop;
+};
+
+__device__ inline bool ls_wait_expired(long long t0, long long limit, const int *abort_word) {
+    if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return true;
+    return (long long)wall_clock64() - t0 > limit;
+}
+
+struct LsGroupLds {
+    float pd[LS_K][2][LSG_TILE];                  // 32 KB: steps applied so far in this group, at my columns
+    float tot[LS_FAST_PAIRS];                     // every candidate's summed gain
+    float e_own[LSG_PB_MAX][4];                   // H' between the own pairs and the rows of the pair that has just won
+    int pairs_l[LS_K][LS_FAST_PAIRS][2];          //  8 KB: the group's batches
+    float coef_own[LSG_PB_MAX][LS_K][4];          // H' between the own pairs and the rows of the applied slots
+    float coef_win[LS_K][4];                      // the same for the pair that has just won
+    int which_own[LSG_PB_MAX][LS_K];              // which rows of a slot are rows of the pair (4 bits)
+    int which_win[LS_K];
+    int prow[LS_K][2];                            // rows of the applied pairs, -1 = none
+    float wsum[LSG_PB_MAX][4];
+};
+
+// lane 0 of every 16-lane row: acc + v[lane 1] + v[lane 2] + ... + v[lane 15] of its row, added in that order
+template <int N>
+__device__ inline float row_lane(float v) {       // lane i <- lane i + N of the same row
+    return __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), 0x100 + N, 0xF, 0xF, true));
+}
+__device__ inline float row_ordered_sum(float acc, float v, bool with_lane0) {
+    if (with_lane0) acc += v;
+    acc += row_lane<1>(v);  acc += row_lane<2>(v);  acc += row_lane<3>(v);  acc += row_lane<4>(v);
+    acc += row_lane<5>(v);  acc += row_lane<6>(v);  acc += row_lane<7>(v);  acc += row_lane<8>(v);
+    acc += row_lane<9>(v);  acc += row_lane<10>(v); acc += row_lane<11>(v); acc += row_lane<12>(v);
+    acc += row_lane<13>(v); acc += row_lane<14>(v); acc += row_lane<15>(v);
+    return acc;
+}
+
+// one pair at one column: the values read from memory, then brought up to date slot by slot
+struct LsCell {
+    float g1, g2, sc1, sc2, h11, h22, h12;
+    int k1, k2;
+};
+
+__device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int r2, long j) {
+    const long i1 = r1, i2 = r2;
+    const int g = (int)a.g;               // (rows and group size fit 32 bits: a 64-bit division per load would cost more
+    c.g1 = a.G[i1 * a.p + j];             //  than the rest of the evaluation)
+    c.g2 = a.G[i2 * a.p + j];
+    c.k1 = a.codes[i1 * a.p + j];
+    c.k2 = a.codes[i2 * a.p + j];
+    c.sc1 = a.scales[(long)(r1 / g) * a.p + j];
+    c.sc2 = a.scales[(long)(r2 / g) * a.p + j];
+    c.h11 = a.H[i1 * a.n + i1] + a.lambda;
+    c.h22 = a.H[i2 * a.n + i2] + a.lambda;
+    c.h12 = a.H[i1 * a.n + i2];
+}
+
+// slot with steps (d1, d2) at this column, coefficients co = H'[i1][a], H'[i1][b], H'[i2][a], H'[i2][b] and row
+// coincidences wh (bit 0: a == i1, 1: b == i1, 2: a == i2, 3: b == i2)
+__device__ inline void ls_cell_apply(LsCell &c, const float *co, int wh, float d1, float d2) {
+    c.g1 -= co[0] * d1 + co[1] * d2;
+    c.g2 -= co[2] * d1 + co[3] * d2;
+    const int s1 = step_sign(d1), s2 = step_sign(d2);        // (no branch: the slots of a loop can then overlap)
+    c.k1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
+    c.k2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
+}
+
+__device__ inline int ls_which(long pa, long pb, long i1, long i2) {
+    return pa < 0 ? 0 : (int)((pa == i1) | ((pb == i1) << 1) | ((pa == i2) << 2) | ((pb == i2) << 3));
+}
+
+// the applied slots [0, count) onto a cell: coefficients and row coincidences from LDS (coef[k][4], which[k]; entries
+// beyond the slots in use are zero), steps of this column from pd.  Four slots are read at a time before any is
+// used, so that the LDS latency is paid once per four, not once per slot; the subtractions keep the slot order.
+template <int NCELL>
+__device__ inline void ls_apply_slots(LsCell *cells, const bool *on, const float (*const *coef)[4], const int *const *which,
+                                      const float (*pd)[2][LSG_TILE], int col, int count) {
+    constexpr int U = 4;
+    for (int k0 = 0; k0 < count; k0 += U) {
+        float d1[U], d2[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            d1[u] = pd[k0 + u][0][col];
+            d2[u] = pd[k0 + u][1][col];
+        }
+#pragma unroll
+        for (int i = 0; i < NCELL; ++i) {
+            floatx4 c[U];
+            int wh[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                c[u] = *(const floatx4 *)&coef[i][k0 + u][0];
+                wh[u] = which[i][k0 + u];
+            }
+            if (on[i]) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float co[4] = {c[u].x, c[u].y, c[u].z, c[u].w};
+                    ls_cell_apply(cells[i], co, wh[u], d1[u], d2[u]);
+                }
+            }
+        }
+    }
+}
+
+template <int PP>
+__global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
+    extern __shared__ __align__(16) unsigned char ls_group_lds[];
+    LsGroupLds &L = *reinterpret_cast<LsGroupLds *>(ls_group_lds);
+    if (*a.commit != a.group_seq) return;      // an earlier group did not complete; the host takes over from there
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int pl = wv >> 2, sub = wv & 3;                      // pair within the block, 64-column strip
+    const int chunks = gridDim.x;
+    const long n = a.n, p = a.p;
+    const int col = sub * 64 + lane;
+    const long j = (long)blockIdx.x * LSG_TILE + col;
+    const bool in = j < p;
+    const int npairs = a.npairs;
+    constexpr int PB = 4 * PP;                                 // pairs per block
+    const int q_base = (int)blockIdx.y * PB;                   // own pair i of this thread: q_base + 4 i + pl
+    const int block_id = (int)(blockIdx.y * gridDim.x + blockIdx.x), nblocks = (int)(gridDim.x * gridDim.y);
+
+    for (int e = tid; e < a.cnt * npairs * 2; e += 1024) {
+        const int s = e / (2 * npairs), r = e - s * 2 * npairs;
+        L.pairs_l[s][r >> 1][r & 1] = a.pairs[e];
+    }
+    // (zero steps, coefficients and coincidences for the slots not yet in use: the apply loops read whole fours)
+    for (int e = tid; e < LS_K * 2 * LSG_TILE; e += 1024) (&L.pd[0][0][0])[e] = 0.f;
+    for (int e = tid; e < LSG_PB_MAX * LS_K * 4; e += 1024) (&L.coef_own[0][0][0])[e] = 0.f;
+    for (int e = tid; e < LSG_PB_MAX * LS_K; e += 1024) (&L.which_own[0][0])[e] = 0;
+    if (tid < LS_K * 4) (&L.coef_win[0][0])[tid] = 0.f;
+    if (tid < LS_K) L.which_win[tid] = 0;
+    if (tid < 2 * LS_K) (&L.prow[0][0])[tid] = -1;
+    int moves_l = 0;
+    double drop_l = 0.0;
+    if (tid == 0) {
+        moves_l = *a.moves;
+        drop_l = *a.drop;
+    }
+    __syncthreads();
+
+    LsCell own[PP], own_n[PP];             // the own pairs of the batch in hand, and of the next one (on their way)
+    int i1[PP], i2[PP], i1n[PP], i2n[PP];
+    bool has[PP], hasn[PP];
+    auto load_cells = [&](int s, LsCell *cell, int *r1, int *r2, bool *ok) {
+#pragma unroll
+        for (int i = 0; i < PP; ++i) {
+            const int q = q_base + 4 * i + pl;
+            r1[i] = r2[i] = -1;
+            if (q < npairs) {
+                r1[i] = L.pairs_l[s][q][0];
+                r2[i] = L.pairs_l[s][q][1];
+            }
+            ok[i] = !(r1[i] < 0 || r2[i] < 0 || r1[i] >= n || r2[i] >= n || r1[i] == r2[i]) && in;
+            cell[i] = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
+            if (ok[i]) ls_cell_load(cell[i], a, r1[i], r2[i], j);
+        }
+    };
+    const float (*coef_rows[PP])[4];
+    const int *which_rows[PP];
+#pragma unroll
+    for (int i = 0; i < PP; ++i) {
+        coef_rows[i] = L.coef_own[4 * i + pl];
+        which_rows[i] = L.which_own[4 * i + pl];
+    }
+
+    load_cells(0, own, i1, i2, has);
+    for (int s = 0; s <= a.cnt; ++s) {
+        const bool nxt = s + 1 < a.cnt;
+        float c_next = 0.f;                // one coefficient of the pairs of batch s+1 against the slots 0 .. s-1
+        int c_pp = 0, c_k = 0, c_w = 0;
+        bool c_on = false;
+        if (s > 0) {
+            // ---- the winner of batch s-1: everybody's sums, added in chunk order ---------------------------------------
+            const unsigned seq = a.seq0 + (unsigned)(s - 1);
+            const unsigned long long *tab = a.xch + (size_t)(seq & 1u) * LS_FAST_PAIRS * chunks;
+            bool bad = a.spin_ticks < 0;          // a negative bound makes every block leave at its first wait
+            {
+                // sixteen lanes to a candidate: lane c of the row reads the sums of the chunks c and c + 16; chunks
+                // beyond the last count as zero (so does a candidate beyond the last, whose total stays zero)
+                const int q = tid >> 4, c0 = tid & 15;
+                float v[2] = {0.f, 0.f};
+                if (q < npairs && !bad) {
+                    const long long t0 = (long long)wall_clock64();
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int c = c0 + 16 * h;
+                        if (c < chunks && !bad) {
+                            const unsigned long long *src = tab + (size_t)q * chunks + c;
+                            unsigned it = 0;
+                            unsigned long long w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            while ((unsigned)(w >> 32) != seq) {
+                                if ((it++ & 7u) == 0u && ls_wait_expired(t0, a.spin_ticks, a.abort_word)) {
+                                    bad = true;
+                                    break;
+                                }
+                                w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+                            v[h] = __uint_as_float((unsigned)w);
+                        }
+                    }
+                }
+                // 0 + chunk 0 + chunk 1 + ... in index order, as the launch-per-batch kernel adds them
+                float tot = row_ordered_sum(0.f, v[0], true);
+                if (chunks > 16) tot = row_ordered_sum(tot, v[1], true);
+                if (c0 == 0) L.tot[q] = tot;
+            }
+            if (__syncthreads_or(bad ? 1 : 0)) {
+                if (tid == 0) __hip_atomic_store(a.abort_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return;
+            }
+            // every wave finds the winner for itself: lane = candidate
+            int win;
+            float win_tot;
+            {
+                float best = 0.f;
+                int bidx = -1;
+                if (lane < npairs) {
+                    const float t = L.tot[lane];
+                    if (t > 0.f) {
+                        best = t;
+                        bidx = lane;
+                    }
+                }
+                wave_best(best, bidx);
+                win = bidx;
+                win_tot = best;
+            }
+            const int wi1 = win >= 0 ? L.pairs_l[s - 1][win][0] : -1, wi2 = win >= 0 ? L.pairs_l[s - 1][win][1] : -1;
+            if (tid == 0) {
+                L.prow[s - 1][0] = wi1;
+                L.prow[s - 1][1] = wi2;
+                if (win >= 0) {
+                    moves_l += 1;
+                    drop_l += (double)win_tot;
+                }
+            }
+            // ---- requests, oldest first: what the winner's evaluation and the own pairs of batch s need of it (used
+            // right below), then everything for batch s+1 (used after batch s has been evaluated and published) --------
+            LsCell wc = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
+            float dep = 0.f;
+            if (win >= 0) {
+                // the winner's evaluation once more, from the same inputs in the same order: slots 0 .. s-3 as applied
+                // slots (H' read as row of the slot), slot s-2 as the move that had just been made (row of the pair)
+                if (pl == 0 && in) ls_cell_load(wc, a, wi1, wi2, j);
+                if (tid < 4 * (s - 1)) {
+                    const int k = tid >> 2, w = tid & 3;
+                    const long src = L.prow[k][w & 1], row = (w & 2) ? wi2 : wi1;
+                    if (src >= 0)
+                        dep = (k < s - 2 ? a.H[src * n + row] : a.H[row * n + src]) + (row == src ? a.lambda : 0.f);
+                } else if (tid >= 64 && tid < 64 + PB * 4 && s < a.cnt) {
+                    // H' between the own pairs of batch s and the winner's rows (row of the own pair)
+                    const int q = q_base + ((tid - 64) >> 2), w = tid & 3;
+                    if (q < npairs) {
+                        const long row = L.pairs_l[s][q][w >> 1], cr = (w & 1) ? wi2 : wi1;
+                        if (row >= 0 && row < n) dep = a.H[row * n + cr] + (row == cr ? a.lambda : 0.f);
+                    }
+                }
+            }
+            if (nxt) {
+                load_cells(s + 1, own_n, i1n, i2n, hasn);
+                if (tid >= 128 && tid < 128 + PB * 4 * s) {           // slots 0 .. s-1: PB * 4 * s <= 896
+                    const int e = tid - 128;
+                    c_pp = e / (4 * s);
+                    const int r = e - c_pp * 4 * s;
+                    c_k = r >> 2;
+                    c_w = r & 3;
+                    c_on = true;
+                    const int q = q_base + c_pp;
+                    const long src = c_k == s - 1 ? (c_w & 1 ? wi2 : wi1) : (long)L.prow[c_k][c_w & 1];
+                    if (q < npairs && src >= 0) {
+                        const long row = L.pairs_l[s + 1][q][c_w >> 1];
+                        if (row >= 0 && row < n) c_next = a.H[src * n + row] + (row == src ? a.lambda : 0.f);
+                    }
+                }
+            }
+            if (win >= 0) {
+                if (tid < 4 * (s - 1)) {
+                    L.coef_win[tid >> 2][tid & 3] = dep;
+                    if ((tid & 3) == 0) L.which_win[tid >> 2] = ls_which(L.prow[tid >> 2][0], L.prow[tid >> 2][1], wi1, wi2);
+                } else if (tid >= 64 && tid < 64 + PB * 4) {
+                    L.e_own[(tid - 64) >> 2][tid & 3] = dep;
+                }
+                __syncthreads();
+                if (pl == 0) {
+                    float st1 = 0.f, st2 = 0.f;
+                    if (in) {
+                        const bool on1[1] = {true};
+                        const float (*cw[1])[4] = {L.coef_win};
+                        const int *ww[1] = {L.which_win};
+                        ls_apply_slots<1>(&wc, on1, cw, ww, L.pd, col, s - 1);
+                        const PairEval ev = eval_column(wc.g1, wc.g2, wc.k1, wc.k2, wc.sc1, wc.sc2, wc.h11, wc.h22, wc.h12,
+                                                        a.levels);
+                        if (ev.combo >= 0) {
+                            st1 = (float)((ev.combo & 2) ? -1 : 1) * wc.sc1;
+                            st2 = (float)((ev.combo & 1) ? -1 : 1) * wc.sc2;
+                        }
+                    }
+                    L.pd[s - 1][0][col] = st1;
+                    L.pd[s - 1][1][col] = st2;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < PP; ++i)
+                    if (has[i] && s < a.cnt)
+                        ls_cell_apply(own[i], L.e_own[4 * i + pl], ls_which(wi1, wi2, i1[i], i2[i]), L.pd[s - 1][0][col],
+                                      L.pd[s - 1][1][col]);
+            }
+            if (s == a.cnt) break;
+        } else if (nxt) {
+            load_cells(1, own_n, i1n, i2n, hasn);
+        }
+        // ---- evaluate the own pairs of batch s and publish the block's 256-column sums ---------------------------------
+        {
+#pragma unroll
+            for (int i = 0; i < PP; ++i) {
+                float gain = 0.f;
+                if (has[i])
+                    gain = eval_column(own[i].g1, own[i].g2, own[i].k1, own[i].k2, own[i].sc1, own[i].sc2, own[i].h11,
+                                       own[i].h22, own[i].h12, a.levels).gain;
+                gain = wave_sum_f(gain);
+                if (lane == 0) L.wsum[4 * i + pl][sub] = gain;
+            }
+            __syncthreads();
+            if (tid < PB && q_base + tid < npairs) {
+                const unsigned seq = a.seq0 + (unsigned)s;
+                unsigned long long *tab = a.xch + (size_t)(seq & 1u) * LS_FAST_PAIRS * chunks;
+                const float tot = (L.wsum[tid][0] + L.wsum[tid][1]) + (L.wsum[tid][2] + L.wsum[tid][3]);
+                __hip_atomic_store(tab + (size_t)(q_base + tid) * chunks + blockIdx.x,
+                                   ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint(tot),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // ---- the pairs of batch s+1 have arrived: bring them up to date with the slots 0 .. s-1 ------------------------
+        if (nxt) {
+#pragma unroll
+            for (int i = 0; i < PP; ++i) {
+                own[i] = own_n[i];
+                i1[i] = i1n[i];
+                i2[i] = i2n[i];
+                has[i] = hasn[i];
+            }
+            if (c_on) L.coef_own[c_pp][c_k][c_w] = c_next;
+            if (tid < PB * s) {
+                const int pp = tid / s, k = tid - pp * s, q = q_base + pp;
+                L.which_own[pp][k] = q < npairs ? ls_which(L.prow[k][0], L.prow[k][1], L.pairs_l[s + 1][q][0], L.pairs_l[s + 1][q][1]) : 0;
+            }
+            __syncthreads();
+            ls_apply_slots<PP>(own, has, coef_rows, which_rows, L.pd, col, s);
+        }
+    }
+
+    // ---- hand the group's moves to the flush -------------------------------------------------------------------------
+    if (blockIdx.y == 0) {
+        for (int e = tid; e < a.cnt * 2 * LSG_TILE; e += 1024) {
+            const int kw = e / LSG_TILE, c = e - kw * LSG_TILE;
+            const long jj = (long)blockIdx.x * LSG_TILE + c;
+            if (jj < p) a.pend_d[(long)kw * p + jj] = (&L.pd[0][0][0])[e];
+        }
+        if (blockIdx.x == 0 && tid < 2 * a.cnt) a.pend_idx[tid] = (&L.prow[0][0])[tid];
+    }
+    // (what the blocks have written is read by later launches only, so no ordering is needed inside this one: the
+    // words below just tell block 0 that nobody gave up)
+    if (tid == 0)
+        __hip_atomic_store(a.fin + block_id, (unsigned)(a.group_seq + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (block_id != 0) return;
+    // block 0 commits the group once every block is through
+    bool bad = false;
+    {
+        const long long t0 = (long long)wall_clock64();
+        for (int b = tid; b < nblocks && !bad; b += 1024) {
+            unsigned it = 0;
+            while (__hip_atomic_load(a.fin + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (unsigned)(a.group_seq + 1)) {
+                if ((it++ & 7u) == 0u && ls_wait_expired(t0, a.spin_ticks, a.abort_word)) {
+                    bad = true;
+                    break;
+                }
+            }
+        }
+    }
+    if (__syncthreads_or(bad ? 1 : 0)) {
+        if (tid == 0) __hip_atomic_store(a.abort_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    if (tid == 0) {
+        *a.moves = moves_l;
+        *a.drop = drop_l;
+        *a.commit = a.group_seq + 1;
+    }
+}
+
 // grid (ceil(p/1024), ceil(n/8)), block 256: each thread 4 columns x 8 rows; applies `count` slots
 __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__ H, float lambda,
                                                        float *__restrict__ G, uint8_t *__restrict__ codes, long n,
                                                        long p,
                                                        const int32_t *__restrict__ pend_idx,
-                                                       const float *__restrict__ pend_d, int count) {
+                                                       const float *__restrict__ pend_d, int count,
+                                                       const int *__restrict__ commit, int commit_needed) {
+    // after a group kernel: apply its moves only if the group was committed
+    if (commit && *commit != commit_needed) return;
     // coefficients of this block's 8 rows for every pending slot: coef[k][0][rr] = H'[r0+rr][a_k],
     // coef[k][1][rr] = H'[r0+rr][b_k] (column a of the symmetric H' read as row a); an empty slot gives 0
     __shared__ float coef[LS_K][2][8];
@@ -538,13 +976,75 @@ admmq_status admmq_k_ls_step(admmq_ctx *ctx, const float *H, float lambda, const
 }
 
 admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, float *G, uint8_t *codes, int64_t n,
-                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count) {
+                              int64_t p, const int32_t *pend_idx, const float *pend_d, int count, const int *commit,
+                              int commit_needed) {
     if (count <= 0) return ADMMQ_OK;
     dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
     const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
     hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n, (long)p,
-                       pend_idx, pend_d, count);
+                       pend_idx, pend_d, count, commit, commit_needed);
     admmq_prof_end(ctx, sp);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+// How a search of this shape runs its groups as single launches: candidate pairs per thread (1 or 2: the fewer
+// for which all blocks are on the chip at once - blocks wait for one another), or 0 if it cannot.
+static int ls_group_chunks(int64_t p) { return (int)((p + LSG_TILE - 1) / LSG_TILE); }
+template <int PP>
+static int ls_group_resident_blocks(int device) {
+    static int cached[64];
+    int &slot = cached[device & 63];
+    if (slot == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ls_group_kernel<PP>, 1024, sizeof(LsGroupLds)) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) {
+            (void)hipGetLastError();
+            per_cu = 0;
+        }
+        slot = per_cu > 0 && cus > 0 ? per_cu * cus : -1;
+    }
+    return slot > 0 ? slot : 0;
+}
+int admmq_ls_group_pairs_per_thread(admmq_ctx *ctx, int64_t p, int npairs) {
+    if (npairs < 1 || npairs > LS_FAST_PAIRS || ls_group_chunks(p) > LSG_MAX_CHUNKS) return 0;
+    static unsigned long long lds_done[2] = {0, 0};
+    const int chunks = ls_group_chunks(p);
+    if (admmq_allow_lds((const void *)ls_group_kernel<1>, (int)sizeof(LsGroupLds), ctx->device, &lds_done[0]) != hipSuccess ||
+        admmq_allow_lds((const void *)ls_group_kernel<2>, (int)sizeof(LsGroupLds), ctx->device, &lds_done[1]) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    const int share = ctx->ls_side_by_side > 1 ? ctx->ls_side_by_side : 1;
+    if (chunks * ((npairs + 3) / 4) * share <= ls_group_resident_blocks<1>(ctx->device)) return 1;
+    if (chunks * ((npairs + 7) / 8) * share <= ls_group_resident_blocks<2>(ctx->device)) return 2;
+    return 0;
+}
+int admmq_ls_group_max_blocks(int64_t p) { return ls_group_chunks(p) * (LS_FAST_PAIRS / 4); }
+size_t admmq_ls_group_xch_words(int64_t p) { return 2 * (size_t)LS_FAST_PAIRS * ls_group_chunks(p); }
+
+// One group of `cnt` <= LS_K batches (pairs: device [cnt][npairs][2]) as one launch; see ls_group_kernel.
+// pairs_per_thread: from admmq_ls_group_pairs_per_thread.  xch: admmq_ls_group_xch_words(p) 8-byte words, fin: one
+// 4-byte word per block, commit, abort_word: 4-byte words, all zero at the start of a search.
+admmq_status admmq_k_ls_group(admmq_ctx *ctx, int pairs_per_thread, const float *H, float lambda, const float *G,
+                              const uint8_t *codes, int64_t n, int64_t p, int bits, int64_t g, const float *scales,
+                              const int32_t *pairs, int npairs, int cnt, unsigned seq0, int group_seq,
+                              unsigned long long *xch, unsigned *fin, int *commit, int *abort_word,
+                              long long spin_ticks, int32_t *pend_idx, float *pend_d, int *dev_moves,
+                              double *dev_drop) {
+    LsGroupArgs a;
+    a.H = H; a.lambda = lambda; a.G = G; a.codes = codes; a.n = (long)n; a.p = (long)p;
+    a.levels = (1 << bits) - 1; a.g = (long)g; a.scales = scales; a.pairs = pairs; a.npairs = npairs; a.cnt = cnt;
+    a.seq0 = seq0; a.group_seq = group_seq; a.xch = xch; a.fin = fin; a.commit = commit; a.abort_word = abort_word;
+    a.spin_ticks = spin_ticks; a.pend_idx = pend_idx; a.pend_d = pend_d; a.moves = dev_moves; a.drop = dev_drop;
+    const int pb = 4 * pairs_per_thread;
+    const dim3 grid((unsigned)ls_group_chunks(p), (unsigned)((npairs + pb - 1) / pb));
+    if (pairs_per_thread == 1)
+        hipLaunchKernelGGL(ls_group_kernel<1>, grid, dim3(1024), sizeof(LsGroupLds), ctx->stream, a);
+    else if (pairs_per_thread == 2)
+        hipLaunchKernelGGL(ls_group_kernel<2>, grid, dim3(1024), sizeof(LsGroupLds), ctx->stream, a);
+    else
+        return ADMMQ_ERR_PARAM;
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

@@ -390,6 +390,24 @@ __global__ void fill_u8_kernel(uint8_t *x, uint8_t v, long count) {
     if (idx < count) x[idx] = v;
 }
 
+// Plain copy, 16 bytes per lane, four rows of loads in flight per thread (the shape of the projection pass without
+// its arithmetic): the reference for what a streaming kernel of this library reaches on the memory system.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const floatx4 *__restrict__ src, floatx4 *__restrict__ dst,
+                                                          long count) {
+    const long base = ((long)blockIdx.x * 256) * 4 + threadIdx.x;
+    floatx4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const long i = base + (long)k * 256;
+        if (i < count) v[k] = src[i];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const long i = base + (long)k * 256;
+        if (i < count) dst[i] = v[k];
+    }
+}
+
 // mode 0: E = dequant(codes) - W0 ; mode 1: E = W0 - dequant(codes);
 // mode 2: codes are first set to round-to-nearest of W0 on the grid, then E = dequant - W0
 __global__ void quant_error_kernel(const float *__restrict__ W0, long ldw, uint8_t *__restrict__ codes, long n,
@@ -562,6 +580,15 @@ admmq_status admmq_k_fill_bytes(admmq_ctx *ctx, void *x, int v, size_t bytes) {
     if (head < bytes)
         hipLaunchKernelGGL(fill_u8_kernel, dim3(blocks_for((long)(bytes - head), 256)), dim3(256), 0, ctx->stream,
                            base + head, (uint8_t)b, (long)(bytes - head));
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+admmq_status admmq_k_stream_copy(admmq_ctx *ctx, void *dst, const void *src, size_t bytes) {
+    const long count = (long)(bytes / 16);
+    if (count == 0) return ADMMQ_OK;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks_for(count, 1024)), dim3(256), 0, ctx->stream,
+                       (const floatx4 *)src, (floatx4 *)dst, count);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }

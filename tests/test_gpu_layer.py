@@ -188,6 +188,47 @@ def test_local_search_against_oracle(ctx, n, p, bits, g, seed, pairs):
           f"identical codes: {np.array_equal(k, ref.codes)}")
 
 
+@pytest.mark.parametrize("n,p,bits,g,seed,pairs,batches", [
+    (64, 40, 3, 16, 1, 16, 0),        # one 256-column chunk, four blocks of 4 pairs, 32 batches: two full groups
+    (128, 300, 2, 0, 2, 64, 37),      # two chunks (the second ragged), groups of 16 + 16 + 5 batches
+    (96, 1100, 4, 24, 3, 64, 20),     # five chunks, 80 blocks
+    (80, 272, 3, 16, 5, 33, 9),       # a candidate count that is not a multiple of 4, one short group
+    (40, 4160, 3, 8, 7, 64, 16),      # 17 chunks: more blocks than compute units at one pair per thread
+    (40, 8200, 2, 0, 8, 64, 5)])      # 33 chunks: too wide for the grouped form, runs batch by batch
+def test_local_search_grouped_launches_equal_one_launch_per_batch(ctx, monkeypatch, n, p, bits, g, seed, pairs, batches):
+    """The search as one launch per group of 16 batches (blocks hand their partial sums to one another through
+    memory) against one launch per batch: same winners, so codes, move count and summed gain must be identical,
+    bit for bit.  Third run: every wait is made to give up at once (forced from the host through the wait bound),
+    so every kernel exits normally, no group is committed, and the host redoes everything batch by batch."""
+    H32, Hd, lam, W0 = ls_problem(n, p, bits, g, seed)
+    W0d, Hdv = to_dev(W0), to_dev(H32)
+    scales, zeros = ctx.grid_init(W0d, bits, g)
+    sc, zr = scales.cpu().numpy(), zeros.cpu().numpy()
+    grid = orc.Grid(sc.astype(np.float64), zr.astype(np.float64), bits, sc == 0)
+    k0, _ = orc.rtn(W0.astype(np.float64), grid)
+    out = {}
+    for mode, env in (("grouped", {}), ("stepwise", {"ADMMQ_LS_PERSISTENT": "0"}), ("gave_up", {"ADMMQ_LS_SPIN_TICKS": "-1"})):
+        monkeypatch.delenv("ADMMQ_LS_PERSISTENT", raising=False)
+        monkeypatch.delenv("ADMMQ_LS_SPIN_TICKS", raising=False)
+        for k_, v_ in env.items():
+            monkeypatch.setenv(k_, v_)
+        codes = to_dev(k0.astype(np.uint8))
+        moves, drop = ctx.local_search(Hdv, W0d, bits, g, scales, zeros, codes, rounds=3, batches_per_round=batches,
+                                       pairs_per_batch=pairs, seed=seed)
+        out[mode] = (codes.cpu().numpy(), moves, drop, ctx.ls_fallback_count())
+        print(f"{mode}: moves {moves} drop {drop:.6g} groups redone {out[mode][3]}", flush=True)
+    assert out["grouped"][3] == 0 and out["stepwise"][3] == 0 and (out["gave_up"][3] > 0 or p > 8192)
+    assert out["grouped"][1] > 0
+    for mode in ("stepwise", "gave_up"):
+        assert np.array_equal(out[mode][0], out["grouped"][0])
+        assert out[mode][1] == out["grouped"][1] and out[mode][2] == out["grouped"][2]
+    ref = orc.local_search(Hd, W0.astype(np.float64), k0, grid, rounds=3, batches_per_round=batches or None,
+                           pairs_per_batch=pairs, seed=seed)
+    j1 = orc.objective(Hd, W0.astype(np.float64), grid.dequant(out["grouped"][0].astype(np.int64)))
+    jr = orc.objective(Hd, W0.astype(np.float64), grid.dequant(ref.codes))
+    assert abs(j1 - jr) <= OBJ_TOL * jr
+
+
 def test_local_search_tiny_exhaustive_matches_oracle_moves(ctx):
     """n = 6, 2-bit, every ordered pair in every batch: gains are well separated, so the GPU must
     apply the same moves as the oracle, whose result the CPU suite checks against enumeration."""

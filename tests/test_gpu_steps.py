@@ -304,3 +304,13 @@ def test_factorisation_from_the_lower_triangle_matches_literal_eq7(ctx, monkeypa
             err = np.linalg.norm(got[mode][idx] - Wref) / np.linalg.norm(Wref)
             assert err < W_UPDATE_TOL, (mode, rho, err)
         assert np.linalg.norm(got["lower"][idx] - got["plain"][idx]) <= 2e-6 * np.linalg.norm(Wref)
+
+
+def test_stream_copy_copies(ctx):
+    """The plain copy kernel bench.py uses as its bandwidth reference: whole blocks, a ragged tail, a tiny size."""
+    for count in (4 * 1024 * 37, 4 * 1024 * 3 + 52, 4):
+        src = torch.randn(count, device="cuda")
+        dst = torch.zeros(count + 8, device="cuda")
+        ctx.stream_copy(dst[:count], src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:count], src) and float(dst[count:].abs().sum()) == 0.0

@@ -95,6 +95,8 @@ def test_argument_validation_without_a_gpu(lib):
     assert na(W=None) == 1 and na(g=3) == 2 and na(rho=0.0) == 3 and na(res=C.c_void_p(260)) == 3
     assert na(n=4096, p=4096, g=4) == 6 and na(n=1 << 20, p=(1 << 20) + 64, g=0) == 6
     assert na(n=4096, p=4096, g=0) == 8 and na(n=1 << 20, p=1 << 20, g=0) == 8 and na(n=25600, p=5120, g=128, res=C.c_void_p(264)) == 8
+    assert lib.admmq_stream_copy(h, one, None, 64) == 1 and lib.admmq_stream_copy(h, one, one, 24) == 2
+    assert lib.admmq_stream_copy(h, C.c_void_p(264), one, 64) == 2 and lib.admmq_stream_copy(h, one, one, 64) == 8
     prm = binding._LsParams(1, 1, 4, 0.01, 0)
     assert lib.admmq_local_search(h, one, one, 1, 4, 4, 4, 0, one, one, one, C.byref(prm), None, None, None) == 2
     assert lib.admmq_set_workspace(h, C.c_void_p(100), 1 << 20) == 6
