@@ -27,7 +27,8 @@ admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double l
                              float *inv_d, double *dev_flags);
 admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double lambda, const float *d,
                                double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
-                               double *tb);
+                               double *tb, double *band);
+size_t admmq_band_scratch_doubles(int64_t n);
 size_t admmq_householder_scratch_doubles(int64_t n);
 int admmq_ls_chunks(int64_t p);
 int admmq_ls_defer();
@@ -129,7 +130,7 @@ admmq_status admmq_arena_reserve(admmq_ctx *ctx, size_t bytes) {
             admmq_factor &f = ctx->fac;
             auto mvf = [shift](float *&ptr) { if (ptr) ptr = (float *)((char *)ptr + shift); };
             auto mvd = [shift](double *&ptr) { if (ptr) ptr = (double *)((char *)ptr + shift); };
-            mvf(f.d); mvf(f.inv_d); mvf(f.Q); mvf(f.Qt); mvd(f.ta); mvd(f.tb);
+            mvf(f.d); mvf(f.inv_d); mvf(f.Q); mvf(f.Qt); mvd(f.ta); mvd(f.tb); mvd(f.band);
         }
         ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
         ADMMQ_HIP(hipFree(ctx->arena));
@@ -154,17 +155,34 @@ admmq_status take(admmq_ctx *ctx, T *&ptr, size_t count) {
     return ptr ? ADMMQ_OK : ADMMQ_ERR_WORKSPACE;
 }
 
+size_t band_doubles(int64_t n) { return 17 * (((size_t)n + 15) / 16 * 16); }
 size_t factor_persist_bytes(int64_t n) {
     const size_t N = (size_t)n;
-    return 2 * admmq_align_up(N * 4) + 2 * admmq_align_up(N * N * 4) + 2 * admmq_align_up(N * 8) + 4096;
+    return 2 * admmq_align_up(N * 4) + 2 * admmq_align_up(N * N * 4) + 2 * admmq_align_up(N * 8) +
+           admmq_align_up(band_doubles(n) * 8) + 4096;
+}
+size_t factor_scratch_doubles(int64_t n) {
+    const size_t a = admmq_householder_scratch_doubles(n), b = admmq_band_scratch_doubles(n);
+    return a > b ? a : b;
 }
 size_t factor_transient_bytes(int64_t n) {
     const size_t N = (size_t)n;
-    return 2 * admmq_align_up(N * N * 8) + admmq_align_up(admmq_householder_scratch_doubles(n) * 8) + 4096;
+    return 2 * admmq_align_up(N * N * 8) + admmq_align_up(factor_scratch_doubles(n) * 8) + 4096;
+}
+// The factors of the middle matrix plus rho_t I for a whole schedule: two n-vectors per penalty for the tridiagonal
+// form (LDL^T), three 16 x 16 matrices per block row and penalty for the band form.
+struct MidFactors {
+    double *a = nullptr, *b = nullptr;
+    size_t stride = 0;          // doubles per penalty
+};
+size_t mid_factor_bytes(int64_t n, int32_t T) {
+    // (room for either form: the choice can be forced through the environment between two calls)
+    const size_t a = admmq_align_up(admmq_band_factor_doubles(n, T) * 8), b = 2 * admmq_align_up((size_t)T * n * 8);
+    return admmq_factor_is_band(n) ? (a > b ? a : b) : b;
 }
 size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
     const size_t np = (size_t)n * (size_t)p;
-    return 6 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) + 2 * admmq_align_up((size_t)T * n * 8) +
+    return 6 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) + mid_factor_bytes(n, T) +
            4 * admmq_align_up((size_t)T * 8) + 65536;
 }
 size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
@@ -252,6 +270,7 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
     ADMMQ_TRY(take(ctx, f.Qt, (size_t)n * n));
     ADMMQ_TRY(take(ctx, f.ta, (size_t)n));
     ADMMQ_TRY(take(ctx, f.tb, (size_t)n));
+    if (admmq_factor_is_band(n)) ADMMQ_TRY(take(ctx, f.band, band_doubles(n)));
     ctx->persist_top = admmq_align_up(ctx->top);
     ctx->top = ctx->persist_top;
 
@@ -271,8 +290,8 @@ admmq_status do_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp
     double *A64 = nullptr, *R64 = nullptr, *vecs = nullptr;
     ADMMQ_TRY(take(ctx, A64, (size_t)n * n));
     ADMMQ_TRY(take(ctx, R64, (size_t)n * n));
-    ADMMQ_TRY(take(ctx, vecs, admmq_householder_scratch_doubles(n)));
-    ADMMQ_TRY(admmq_k_factorize(ctx, H, n, lambda, f.d, A64, R64, vecs, f.Q, f.Qt, f.ta, f.tb));
+    ADMMQ_TRY(take(ctx, vecs, factor_scratch_doubles(n)));
+    ADMMQ_TRY(admmq_k_factorize(ctx, H, n, lambda, f.d, A64, R64, vecs, f.Q, f.Qt, f.ta, f.tb, f.band));
     f.n = n;
     f.lambda = lambda;
     f.H_src = H;
@@ -317,10 +336,35 @@ admmq_status fast_setup(admmq_ctx *ctx, int64_t n, int64_t p, FastBufs &fb) {
     return ADMMQ_OK;
 }
 
-// W = B + Q (T + rho I)^{-1} T (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho)
+admmq_status mid_factors_take(admmq_ctx *ctx, int64_t n, int32_t T, MidFactors &mf) {
+    if (ctx->fac.band) {
+        mf.stride = admmq_band_factor_doubles(n, 1);
+        ADMMQ_TRY(take(ctx, mf.a, mf.stride * (size_t)T));
+        return ADMMQ_OK;
+    }
+    mf.stride = (size_t)n;
+    ADMMQ_TRY(take(ctx, mf.a, (size_t)T * n));
+    ADMMQ_TRY(take(ctx, mf.b, (size_t)T * n));
+    return ADMMQ_OK;
+}
+admmq_status mid_factors_compute(admmq_ctx *ctx, int64_t n, const double *rhos_dev, int32_t T, const MidFactors &mf) {
+    const admmq_factor &f = ctx->fac;
+    if (f.band) return admmq_k_band_factor(ctx, f.band, n, rhos_dev, T, mf.a);
+    return admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos_dev, T, mf.a, mf.b);
+}
+// S = (M + rho_t I)^-1 M Y; carries: the tridiagonal solve's per-tile checkpoints
+admmq_status mid_apply(admmq_ctx *ctx, const MidFactors &mf, int t, int64_t n, int64_t p, const float *Y, double *carries,
+                       float *S, unsigned *amax_out) {
+    const admmq_factor &f = ctx->fac;
+    if (f.band) return admmq_k_band_apply(ctx, mf.a + (size_t)t * mf.stride, n, p, Y, S, amax_out);
+    return admmq_k_tridiag_apply(ctx, f.ta, f.tb, mf.a + (size_t)t * mf.stride, mf.b + (size_t)t * mf.stride, n, p, Y,
+                                 carries, S, amax_out);
+}
+
+// W = B + Q (M + rho I)^{-1} M (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho; Hs = Q M Q^T)
 // F: n p + p doubles of scratch: the solve's fp32 result [n][p] in front, its per-tile checkpoints behind
-admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const double *dinv,
-                           const double *lfac, float *Y, double *F, float *W, const FastBufs *fb = nullptr) {
+admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const MidFactors &mf,
+                           int t, float *Y, double *F, float *W, const FastBufs *fb = nullptr) {
     const admmq_factor &f = ctx->fac;
     if (fb) {
         // the time of splitting the state operand is booked with its product
@@ -334,7 +378,7 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
         float *S = (float *)F;
         double *carries = F + ((size_t)n * p + 1) / 2;
         sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
-        ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S, (unsigned *)ss));
+        ADMMQ_TRY(mid_apply(ctx, mf, t, n, p, Y, carries, S, (unsigned *)ss));
         admmq_prof_end(ctx, sp);
         sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
         // (the solve has left the largest |S| in its slot; the second split zeroes the first one's slot again: the
@@ -354,7 +398,7 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
     float *S = (float *)F;
     double *carries = F + ((size_t)n * p + 1) / 2;
     sp = admmq_prof_begin(ctx, ADMMQ_TAG_TRIDIAG);
-    ADMMQ_TRY(admmq_k_tridiag_apply(ctx, f.ta, f.tb, dinv, lfac, n, p, Y, carries, S));
+    ADMMQ_TRY(mid_apply(ctx, mf, t, n, p, Y, carries, S, nullptr));
     admmq_prof_end(ctx, sp);
     gemm_tn_args g2 = {};
     g2.A = f.Qt; g2.lda = n; g2.B = S; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
@@ -891,21 +935,21 @@ extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const fl
     const size_t np = (size_t)n * p;
     const bool fast = fast_wanted(ctx, n, p);
     ADMMQ_TRY(admmq_arena_reserve(ctx, 3 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) +
-                                           3 * admmq_align_up((size_t)n * 8) + 8192 +
+                                           mid_factor_bytes(n, 1) + admmq_align_up((size_t)n * 8) + 8192 +
                                            (fast ? fast_products_bytes(n, p) : 0)));
     float *B = nullptr, *C0 = nullptr, *Y = nullptr;
-    double *F = nullptr, *dinv = nullptr, *lfac = nullptr, *rho_dev = nullptr;
+    double *F = nullptr, *rho_dev = nullptr;
+    MidFactors mf;
     ADMMQ_TRY(take(ctx, B, np));
     ADMMQ_TRY(take(ctx, C0, np));
     ADMMQ_TRY(take(ctx, Y, np));
     ADMMQ_TRY(take(ctx, F, np + (size_t)p));
-    ADMMQ_TRY(take(ctx, dinv, (size_t)n));
-    ADMMQ_TRY(take(ctx, lfac, (size_t)n));
+    ADMMQ_TRY(mid_factors_take(ctx, n, 1, mf));
     ADMMQ_TRY(take(ctx, rho_dev, 1));
     const admmq_factor &f = ctx->fac;
     ADMMQ_HIP(hipMemcpyAsync(rho_dev, &rho, 8, hipMemcpyHostToDevice, ctx->stream));
     ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
-    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rho_dev, 1, dinv, lfac));
+    ADMMQ_TRY(mid_factors_compute(ctx, n, rho_dev, 1, mf));
     gemm_tn_args g0 = {};
     g0.A = f.Q; g0.lda = n; g0.B = Ws; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
@@ -914,7 +958,7 @@ extern "C" admmq_status admmq_w_update(admmq_ctx *ctx, const float *Ws, const fl
     ADMMQ_TRY(admmq_k_form_b(ctx, D, V, inv_rho, (int64_t)np, B));
     FastBufs fbufs;
     if (fast) ADMMQ_TRY(fast_setup(ctx, n, p, fbufs));
-    ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, dinv, lfac, Y, F, W_out, fast ? &fbufs : nullptr));
+    ADMMQ_TRY(w_update_core(ctx, C0, B, n, p, mf, 0, Y, F, W_out, fast ? &fbufs : nullptr));
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;
 }
@@ -1203,7 +1247,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     }
     ADMMQ_TRY(admmq_arena_reserve(ctx, need));
     float *B = nullptr, *V = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr, *inv_scales = nullptr;
-    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *res = nullptr, *jdev = nullptr;
+    double *F = nullptr, *rhos = nullptr, *res = nullptr, *jdev = nullptr;
+    MidFactors mf;
     unsigned long long *flips = nullptr;
     ADMMQ_TRY(take(ctx, B, np));
     ADMMQ_TRY(take(ctx, V, np));
@@ -1220,8 +1265,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     int refresh_accepted = 0;
     double refresh_eo = 0.0, refresh_en = 0.0;
     ADMMQ_TRY(take(ctx, rhos, (size_t)T));
-    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
-    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
+    ADMMQ_TRY(mid_factors_take(ctx, n, T, mf));
     ADMMQ_TRY(take(ctx, res, (size_t)T));
     ADMMQ_TRY(take(ctx, flips, (size_t)T));
     ADMMQ_TRY(take(ctx, jdev, 4));
@@ -1254,7 +1298,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     }
     ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
     ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
-    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
+    ADMMQ_TRY(mid_factors_compute(ctx, n, rhos, T, mf));
     // C0 = Q^T Ws
     gemm_tn_args g0 = {};
     g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
@@ -1284,7 +1328,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
         } else {
-            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur,
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, mf, t, Y, F, Wcur,
                                     fast ? &fbufs : nullptr));
         }
         const bool last = t == T - 1;
@@ -1450,7 +1494,8 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     }
     ADMMQ_TRY(admmq_arena_reserve(ctx, need));
     float *B = nullptr, *W = nullptr, *C0 = nullptr, *Y = nullptr;
-    double *F = nullptr, *rhos = nullptr, *dinv = nullptr, *lfac = nullptr, *jdev = nullptr;
+    double *F = nullptr, *rhos = nullptr, *jdev = nullptr;
+    MidFactors mf;
     std::vector<float *> V((size_t)count), inv_scales((size_t)count);
     std::vector<double *> res((size_t)count);
     ADMMQ_TRY(take(ctx, B, nP));
@@ -1464,8 +1509,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
         ADMMQ_TRY(take(ctx, res[i], (size_t)T));
     }
     ADMMQ_TRY(take(ctx, rhos, (size_t)T));
-    ADMMQ_TRY(take(ctx, dinv, (size_t)T * n));
-    ADMMQ_TRY(take(ctx, lfac, (size_t)T * n));
+    ADMMQ_TRY(mid_factors_take(ctx, n, T, mf));
     ADMMQ_TRY(take(ctx, jdev, 4));
     FastBufs fbufs;
     if (fast) ADMMQ_TRY(fast_setup(ctx, n, P, fbufs));
@@ -1497,7 +1541,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     }
     ADMMQ_HIP(hipMemcpyAsync(rhos, hrho.data(), (size_t)T * 8, hipMemcpyHostToDevice, ctx->stream));
     ADMMQ_HIP(hipStreamSynchronize(ctx->stream));
-    ADMMQ_TRY(admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos, T, dinv, lfac));
+    ADMMQ_TRY(mid_factors_compute(ctx, n, rhos, T, mf));
     gemm_tn_args g0 = {};
     g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = P; g0.M = n; g0.N = P; g0.K = n;
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = P; g0.split_k = 1;
@@ -1522,7 +1566,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
         if (t == 0)
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, nP * 4, hipMemcpyDeviceToDevice, ctx->stream));
         else
-            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, P, dinv + (size_t)t * n, lfac + (size_t)t * n, Y, F, Wcur,
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, P, mf, t, Y, F, Wcur,
                                     fast ? &fbufs : nullptr));
         const bool last = t == T - 1;
         const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_PROJECT);

@@ -19,7 +19,8 @@
         if (s_ != ADMMQ_OK) return s_;      \
     } while (0)
 
-// Factorisation of the scaled, damped Hessian kept between calls:  Hs = Q T Q^T.
+// Factorisation of the scaled, damped Hessian kept between calls:  Hs = Q M Q^T with M a band matrix of
+// half-bandwidth 16 (`band`: large n) or tridiagonal (`ta`, `tb`: small n); see admmq_factor_is_band.
 struct admmq_factor {
     int64_t n = 0;
     double lambda = 0.0;
@@ -29,6 +30,7 @@ struct admmq_factor {
     float *Qt = nullptr;      // [n][n] fp32, row-major Q^T
     double *ta = nullptr;     // [n]   diagonal of T
     double *tb = nullptr;     // [n]   sub-diagonal of T (tb[n-1] = 0)
+    double *band = nullptr;   // [17][npad] band[t][j] = M[j + t][j], npad = n rounded up to 16; NULL for the tridiagonal form
     bool valid = false;
     const float *H_src = nullptr;   // the raw Hessian it was made from (identity check for reuse)
     double damp = 0.0;
@@ -194,6 +196,14 @@ admmq_status admmq_k_count_nonfinite(admmq_ctx *ctx, const float *A, int64_t row
 admmq_status admmq_k_tridiag_factor(admmq_ctx *ctx, const double *ta, const double *tb, int64_t n,
                                     const double *rhos_dev, int count, double *dinv, double *lfac);
 // S = (T + rho I)^{-1} T Y, column by column (Y, S fp32 [n][p]; may alias), F fp64 scratch [n][p]
+// The same two steps for the band form (band.hip): block-elimination factors of M + rho_t I, and the solve.
+size_t admmq_band_factor_doubles(int64_t n, int count);
+admmq_status admmq_k_band_factor(admmq_ctx *ctx, const double *bd, int64_t n, const double *rhos_dev, int count,
+                                 double *fac);
+admmq_status admmq_k_band_apply(admmq_ctx *ctx, const double *fac, int64_t n, int64_t p, const float *Y, float *S,
+                                unsigned *amax_out = nullptr);
+// which form the factorisation of an n x n Hessian takes (band from n = 8192 on; ADMMQ_FACTOR=band / tridiag forces one)
+bool admmq_factor_is_band(int64_t n);
 admmq_status admmq_k_tridiag_apply(admmq_ctx *ctx, const double *ta, const double *tb, const double *dinv,
                                    const double *lfac, int64_t n, int64_t p, const float *Y, double *carries,
                                    float *S, unsigned *amax_out = nullptr);   // atomic max of |S| as float bits

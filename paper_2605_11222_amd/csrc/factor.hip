@@ -279,14 +279,31 @@ admmq_status admmq_k_scaling(admmq_ctx *ctx, const float *H, int64_t n, double l
 
 admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double *R64, double *vecs, float *Q,
                                  float *Qt, double *ta, double *tb);
+admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double *R64, double *vecs, float *Q, float *Qt,
+                                 double *bd);
 
+// The form of the factorisation for an n x n Hessian.  The band form costs a fraction of the one-stage tridiagonal
+// reduction (block reflectors: one pass over the trailing matrix per 16 columns instead of one per column), but its
+// per-iteration solve is 16 x 16 block elimination on the fp64 matrix cores, several times the cost of the scalar
+// recurrence of the tridiagonal form.  Small layers run thousands of short iterations, so they keep the tridiagonal
+// form; from n = 8192 on the reduction dominates and the band form wins (measured: DESIGN notes).
+// ADMMQ_FACTOR=band / tridiag forces one form (read at every call).
+bool admmq_factor_is_band(int64_t n) {
+    const char *e = getenv("ADMMQ_FACTOR");
+    if (e && e[0] == 't') return false;
+    if (e && e[0] == 'b') return true;
+    return n >= 8192;
+}
+
+// band != NULL: reduction to band form (ta, tb unused); else to tridiagonal form
 admmq_status admmq_k_factorize(admmq_ctx *ctx, const float *H, int64_t n, double lambda, const float *d,
                                double *A64, double *R64, double *vecs, float *Q, float *Qt, double *ta,
-                               double *tb) {
+                               double *tb, double *band) {
     const long N = (long)n;
     hipLaunchKernelGGL(build_scaled_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, ctx->stream, H, N, lambda, d,
                        A64);
     ADMMQ_HIP(hipGetLastError());
+    if (band) return admmq_k_band_reduce(ctx, A64, n, R64, vecs, Q, Qt, band);
     return admmq_k_householder(ctx, A64, n, R64, vecs, Q, Qt, ta, tb);
 }
 

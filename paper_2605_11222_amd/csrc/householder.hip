@@ -683,16 +683,17 @@ __global__ void identity_kernel(double *__restrict__ R, long n) {
     R[idx] = (idx - i * n == i) ? 1.0 : 0.0;
 }
 
-// Reflector k0+c is row k0+c of A on indices >= k0+c+1 (leading 1 stored).  S[c1][c2] = v_c1 . v_c2.
+// Reflector k0+c is row k0+c of A on indices >= k0+c+off (leading 1 stored); off = 1 for the tridiagonal
+// reduction, the band width for the reduction to band form.  S[c1][c2] = v_c1 . v_c2.
 // grid (nbc, nbc), block 256; only c1 <= c2 is computed (and mirrored).
 __global__ __launch_bounds__(256) void q_gram_kernel(const double *__restrict__ A, long n, long k0, int nbc,
-                                                     double *__restrict__ S) {
+                                                     double *__restrict__ S, int off) {
     __shared__ double sh[4];
     const int c1 = blockIdx.y, c2 = blockIdx.x;
     if (c1 > c2) return;
     const double *v1 = A + (k0 + c1) * n, *v2 = A + (k0 + c2) * n;
     double s = 0.0;
-    for (long i = k0 + c2 + 1 + threadIdx.x; i < n; i += 256) s += v1[i] * v2[i];
+    for (long i = k0 + c2 + off + threadIdx.x; i < n; i += 256) s += v1[i] * v2[i];
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
     __syncthreads();
@@ -730,14 +731,15 @@ __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__r
     for (int c = 0; c < NB; ++c) T[r * NB + c] = Ts[r][c];
 }
 
-// Gp[s][j][c] = sum over slice s of i of R[j][i] v_c[i]  for rows j >= k0+1 (the slices of the
+// Gp[s][j][c] = sum over slice s of i of R[j][i] v_c[i]  for rows j >= jstart (the slices of the
 // contraction index give the chip enough blocks; they are added in a fixed order by the consumer).
 // Block: 64 rows x NB columns on the fp64 matrix cores (v_mfma_f64_16x16x4), one 16-row strip per wave.
 // grid: any number of blocks up to row_tiles * ks.
 constexpr int WY_KS_MAX = 16;
 __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ R, const double *__restrict__ A,
                                                      long n, long k0, int nbc, long chunk,
-                                                     double *__restrict__ Gp, long jstart, int row_tiles, int ks) {
+                                                     double *__restrict__ Gp, long jstart, int row_tiles, int ks,
+                                                     int off) {
     constexpr int KC = 32;
     __shared__ double Rs[64][KC + 1];
     __shared__ double Vs[NB][KC + 1];
@@ -748,7 +750,7 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
     for (long id = blockIdx.x; id < (long)row_tiles * ks; id += gridDim.x) {
         const long bx = id % row_tiles, by = id / row_tiles;
         const long j0 = jstart + bx * 64;           // first row of the block (rows jstart .. n-1)
-        const long ibeg = k0 + 1 + by * chunk;
+        const long ibeg = k0 + off + by * chunk;
         const long iend = min(n, ibeg + chunk);
         // wave w owns rows 16w..16w+15 of the block, both halves of the NB columns: two 16 x 16 accumulators
         doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
@@ -762,7 +764,7 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
             for (int e = tid; e < NB * KC; e += 256) {
                 const int c = e / KC, q = e % KC;
                 const long i = i0 + q;
-                Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
+                Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + off) ? A[(k0 + c) * n + i] : 0.0;
             }
             __syncthreads();
 #pragma unroll
@@ -813,18 +815,18 @@ __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__
     }
 }
 
-// R[j][i] -= sum_c G2[j][c] v_c[i]  for j, i >= k0+1.  64 x 64 tile per block; the product runs on the fp64
+// R[j][i] -= sum_c G2[j][c] v_c[i]  for j >= jstart, i >= k0+off.  64 x 64 tile per block; the product runs on the fp64
 // matrix cores: wave w owns rows 16w..16w+15 of the tile, four 16-column blocks, NB/4 steps each.
 __global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R, const double *__restrict__ A,
                                                           long n, long k0, int nbc,
                                                           const double *__restrict__ G2, long jstart, int col_tiles,
-                                                          int row_tiles) {
+                                                          int row_tiles, int off) {
     __shared__ double G2s[64][NB + 1];
     __shared__ double Vs[NB][80];          // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
     const int tid = threadIdx.x;
     for (long id = blockIdx.x; id < (long)col_tiles * row_tiles; id += gridDim.x) {
         const long bx = id % col_tiles, by = id / col_tiles;
-        const long j0 = jstart + by * 64, i0 = k0 + 1 + bx * 64;
+        const long j0 = jstart + by * 64, i0 = k0 + off + bx * 64;
         for (int e = tid; e < 64 * NB; e += 256) {
             const int r = e / NB, c = e % NB;
             const long j = j0 + r;
@@ -833,7 +835,7 @@ __global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R
         for (int e = tid; e < NB * 64; e += 256) {
             const int c = e >> 6, o = e & 63;
             const long i = i0 + o;
-            Vs[c][o] = (c < nbc && i < n && i >= k0 + c + 1) ? A[(k0 + c) * n + i] : 0.0;
+            Vs[c][o] = (c < nbc && i < n && i >= k0 + c + off) ? A[(k0 + c) * n + i] : 0.0;
         }
         const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
         // the tile's own entries are requested before the operands are waited for
@@ -896,6 +898,609 @@ __global__ void emit_q_kernel(const double *__restrict__ R, long n, float *__res
 
 inline unsigned blocks_for(long count, int bs) { return (unsigned)((count + bs - 1) / bs); }
 
+// ---- reduction to band form (block reflectors) -------------------------------------------------------------------
+// Hs = Q Bd Q^T with Bd of half-bandwidth BW.  Per panel of BW columns c0 .. c0+BW-1 (r0 = c0 + BW, m = n - r0):
+//   factor : the m x BW block below the band, P = A[r0:, c0:c0+BW], gets its QR factorisation from two rounds of
+//            Cholesky-QR (Gram matrix over all rows on the matrix cores, 16 x 16 Cholesky, P R^-1), which costs three
+//            passes over P by the whole chip instead of BW dependent column steps; the Householder form
+//            I - Y T Y^T of the orthonormal factor is then rebuilt from an LU factorisation of its top BW x BW block
+//            (signs chosen so that every pivot is at least 1) and one triangular solve per row below it
+//   symm   : X = A[r0:, r0:] Y on the fp64 matrix cores, the contraction cut into slices
+//   finish : K = Y^T X, S = T^T K T, W = X T - 1/2 Y S
+//   update : A[r0:, r0:] -= Y W^T + W Y^T                       (the rank-2 BW kernel of the tridiagonal path)
+// so every panel costs one read and one read+write of the trailing matrix, against one read per COLUMN for the
+// one-stage tridiagonalisation, and no step depends on a single column's reduction.
+// A panel whose Gram matrix is not safely positive definite (a rank-deficient block), and the last panels (fewer
+// than 64 rows), take plain Householder steps in one block instead.
+constexpr int BW = 16;
+enum { BS_R1 = 0, BS_R1INV = 256, BS_Z = 512, BS_Y1 = 768, BS_T = 1024, BS_S2 = 1280, BS_FLAG = 1536, BS_COUNT = 1600 };
+
+// entry `tid` of the per-block partial sums, added in block order; sixteen loads are in flight at a time (one load
+// per trip would pay the memory latency once per block)
+__device__ inline double sum_block_partials(const double *part, unsigned nb, int tid) {
+    double g = 0.0;
+    unsigned b = 0;
+    for (; b + 16 <= nb; b += 16) {
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = coherent_load(part + (long)(b + u) * 256 + tid);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) g += v[u];
+    }
+    for (; b < nb; ++b) g += coherent_load(part + (long)b * 256 + tid);
+    return g;
+}
+
+// 16 x 16 factorisations in the registers of one wave.  "Column layout": lane j < 16 holds column j of the matrix,
+// a[i] = M[i][j]; an entry another lane needs comes by v_readlane (the loops are fully unrolled, so every source
+// lane is a constant).  Lanes 16 .. 63 run along on zeros; nothing of theirs is ever read.
+__device__ inline double lane_bcast(double v, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src), hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+// G = R^T R: in a = G (symmetric), out a = upper R (zeros below the diagonal).  False when a pivot is not safely
+// positive (below 1e-12 of its diagonal entry: the panel's columns are close to dependent).
+__device__ inline bool chol16_cols(double (&a)[16], int lane) {
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const double g0 = lane_bcast(a[k], k);
+        double acc = g0;                               // G[k][k] - sum_{i<k} R[i][k]^2, left-looking on the diagonal
+#pragma unroll
+        for (int i = 0; i < k; ++i) {
+            const double rik = lane_bcast(a[i], k);
+            acc -= rik * rik;
+        }
+        if (!(acc > 1e-12 * g0)) ok = false;
+        const double inv = 1.0 / sqrt(acc > 0.0 ? acc : 1.0);
+        // row k: R[k][j] = (G[k][j] - sum_{i<k} R[i][k] R[i][j]) / R[k][k] for j >= k
+        double s = a[k];
+#pragma unroll
+        for (int i = 0; i < k; ++i) s -= lane_bcast(a[i], k) * a[i];
+        a[k] = lane >= k ? s * inv : 0.0;
+    }
+    return ok;
+}
+// inverse of an upper triangular matrix, column layout in and out (x[i] = (R^-1)[i][lane])
+__device__ inline void triu_inverse16_cols(const double (&a)[16], double (&x)[16], int lane) {
+#pragma unroll
+    for (int i = 15; i >= 0; --i) {
+        double s = lane == i ? 1.0 : 0.0;
+#pragma unroll
+        for (int k = i + 1; k < 16; ++k) s -= lane_bcast(a[i], k) * x[k];       // R[i][k] sits in lane k
+        x[i] = lane >= i ? s / lane_bcast(a[i], i) : 0.0;
+    }
+}
+// LU without pivoting of Q - S, S = diag(sg) chosen against the sign of each pivot as it comes up, so that every
+// pivot is at least 1 in size: a = Q in, out a = U on and above the diagonal, the multipliers (Y1 without its unit
+// diagonal) below it.
+__device__ inline void lu16_signed_cols(double (&a)[16], double (&sg)[16], int lane) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const double p0 = lane_bcast(a[k], k);
+        sg[k] = p0 >= 0.0 ? -1.0 : 1.0;
+        const double inv = 1.0 / (p0 - sg[k]);
+        if (lane == k) {
+            a[k] -= sg[k];
+#pragma unroll
+            for (int i = k + 1; i < 16; ++i) a[i] *= inv;
+        }
+#pragma unroll
+        for (int i = k + 1; i < 16; ++i) {
+            const double lik = lane_bcast(a[i], k);
+            if (lane > k) a[i] -= lik * a[k];
+        }
+    }
+}
+
+// Gram matrix of a row panel (PASS 1: P = A[r0:, c0:c0+16]; PASS 2: Q1 = P R1^-1, which is also written to Pq
+// [m][16]) as per-block partials, 64 rows per block (thread = row, four columns); the block that finishes last adds
+// them in block order, factorises and leaves in `small`
+//   PASS 1: R1, R1^-1
+//   PASS 2: with R2 the factor of the second round and Q = Q1 R2^-1 (orthonormal columns, P = Q R, R = R2 R1): the
+//           Householder form of Q from its top 16 x 16 block.  With S = diag(+-1) chosen against the sign of each
+//           pivot, Q - [S; 0] = Y U (LU without pivoting, Y unit lower trapezoidal, every pivot at least 1 in size),
+//           T = -U S Y1^-T, and (I - Y T Y^T)^T P = [S R; 0].  Left behind: Z = R2^-1 U^-1 (so that the rows below
+//           the top block are Y = Q1 Z), Y1, T, tau = diag T, and the block S R in the band array;
+// or raises small[BS_FLAG].  PASS 1 also writes the panel's diagonal block into the band array.  Needs m >= 16.
+template <int PASS>
+__global__ __launch_bounds__(256) void band_gram_kernel(const double *__restrict__ A, long n, long c0, long m,
+                                                        double *__restrict__ Pq, double *__restrict__ small,
+                                                        double *__restrict__ part, unsigned *__restrict__ counter,
+                                                        double *__restrict__ bd, long npad,
+                                                        double *__restrict__ tau) {
+    __shared__ double tile[64][17];
+    __shared__ double Ms[16][17], Rs[16][17], Ri[16][17], Lu[16][17], Ts[16][17];
+    __shared__ double red[4][256];
+    __shared__ double sg[16];
+    __shared__ int flag_sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    const long r0 = c0 + BW;
+    if (PASS == 2 && small[BS_FLAG] != 0.0) return;
+    if (PASS == 1 && blockIdx.x == 0) {
+        const int s = tid >> 4, u = tid & 15;
+        if (s >= u && c0 + s < n) bd[(long)(s - u) * npad + c0 + u] = A[(c0 + s) * n + c0 + u];
+    }
+    if (PASS == 2) Ms[tid >> 4][tid & 15] = small[BS_R1INV + tid];
+    const int rr = tid >> 2, cq = (tid & 3) * 4;
+    const long row = (long)blockIdx.x * 64 + rr;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[rr][cq + e] = row < m ? A[(r0 + row) * n + c0 + cq + e] : 0.0;
+    __syncthreads();
+    if (PASS == 2) {
+        double q[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int t = cq + e;
+            double s = 0.0;
+            for (int u = 0; u <= t; ++u) s += tile[rr][u] * Ms[u][t];
+            q[e] = s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tile[rr][cq + e] = q[e];
+            if (row < m) Pq[row * 16 + cq + e] = q[e];
+        }
+        __syncthreads();
+    }
+    doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const double x = tile[16 * wave + 4 * s + lq][l16];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, x, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][(4 * r + lq) * 16 + l16] = acc[r];
+    __syncthreads();
+    part[(long)blockIdx.x * 256 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+    if (!last_block_done(counter, gridDim.x)) return;
+    const double g = sum_block_partials(part, gridDim.x, tid);
+    Ms[tid >> 4][tid & 15] = g;
+    if (tid == 0) {
+        *counter = 0u;
+        flag_sh = 0;
+    }
+    __syncthreads();
+    const int i = tid >> 4, j = tid & 15;
+    // the serial part, by the first wave in registers: Cholesky, R^-1 and (PASS 2) the signed LU of the top block of
+    // Q, T and U^-1; the small products around it by all threads through LDS
+    if (wave == 0) {
+        double a[16], x[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[r] = lane < 16 ? Ms[r][lane] : 0.0;
+        const bool ok = chol16_cols(a, lane);
+        if (__any(lane < 16 && !ok)) flag_sh = 1;
+        triu_inverse16_cols(a, x, lane);
+        if (lane < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                Rs[r][lane] = a[r];
+                Ri[r][lane] = x[r];
+            }
+        }
+    }
+    __syncthreads();
+    if (flag_sh) {
+        if (tid == 0) small[BS_FLAG] = 1.0;
+        return;
+    }
+    if (PASS == 1) {
+        small[BS_R1 + tid] = Rs[i][j];
+        small[BS_R1INV + tid] = Ri[i][j];
+        return;
+    }
+    // top block of Q = Q1 R2^-1 (the rows another block has just written are read past the caches)
+    {
+        double pq[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) pq[u] = coherent_load(Pq + (long)i * 16 + u);
+        double q = 0.0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (u <= j) q += pq[u] * Ri[u][j];
+        Lu[i][j] = q;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        double a[16], sgn[16], x[16], u[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[r] = lane < 16 ? Lu[r][lane] : (r == 0 ? 1.0 : 0.0);
+        lu16_signed_cols(a, sgn, lane);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) u[r] = (lane < 16 && r <= lane) ? a[r] : (lane >= 16 && r == 0 ? 1.0 : 0.0);
+        if (lane < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Lu[r][lane] = a[r];
+            sg[lane] = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (r == lane) sg[lane] = sgn[r];
+        }
+        // T = -U S Y1^-T, lane r = row r: t[c] = -U[r][c] s_c - sum_{k<c} t[k] Y1[c][k]   (Y1[c][k]: lane k, entry c)
+        double t[16];
+        const int rl = lane & 15;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            double sacc = c >= rl ? -Lu[rl][c] * sgn[c] : 0.0;      // (LDS written above by this wave: same wave, in order)
+#pragma unroll
+            for (int k = 0; k < c; ++k) sacc -= t[k] * lane_bcast(a[c], k);
+            t[c] = sacc;
+        }
+        triu_inverse16_cols(u, x, lane);
+        if (lane < 16) {
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                Ts[lane][c] = t[c];
+                Ms[c][lane] = x[c];                   // U^-1
+            }
+        }
+    }
+    __syncthreads();
+    {
+        double z = 0.0, rfull = 0.0;
+        for (int k = i; k <= j; ++k) {
+            z += Ri[i][k] * Ms[k][j];                               // Z = R2^-1 U^-1
+            rfull += Rs[i][k] * small[BS_R1 + k * 16 + j];           // R = R2 R1
+        }
+        small[BS_Z + tid] = z;
+        small[BS_Y1 + tid] = i > j ? Lu[i][j] : (i == j ? 1.0 : 0.0);
+        small[BS_T + tid] = Ts[i][j];
+        if (i <= j) bd[(long)(16 + i - j) * npad + c0 + j] = sg[i] * rfull;
+    }
+    if (tid < 16) tau[c0 + tid] = Ts[tid][tid];
+}
+
+// Plain Householder QR of the panel P = A[r0:, c0:c0+16] by one block (256 threads), in a row-major copy Pq [m][16]:
+// the path of the last panels and of panels the Cholesky-QR route gave up on.  Leaves the same results as
+// band_yt_kernel: Y in Vp[c][r0 + i] and in row c0+c of A (from its leading 1 on), tau[c0 + c], T in
+// small[BS_T], and the new block below the band (R) in the band array.
+__device__ void band_house_panel(double *__restrict__ A, long n, long c0, long m, double *__restrict__ Pq,
+                                 double *__restrict__ small, double *__restrict__ Vp, double *__restrict__ tau,
+                                 double *__restrict__ bd, long npad) {
+    __shared__ double w_sh[4][16];
+    __shared__ double sc_sh[4];
+    __shared__ double Ts[16][17], Gv[16][17], taus[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long r0 = c0 + BW;
+    for (long e = tid; e < m * 16; e += 256) Pq[e] = A[(r0 + e / 16) * n + c0 + (e & 15)];
+    if (tid < 16) taus[tid] = 0.0;
+    __syncthreads();
+    const int nr = (int)(m - 1 < 16 ? (m - 1 > 0 ? m - 1 : 0) : 16);
+    for (int t = 0; t < nr; ++t) {
+        double ssq = 0.0;
+        for (long i = t + 1 + tid; i < m; i += 256) {
+            const double x = Pq[i * 16 + t];
+            ssq += x * x;
+        }
+        ssq = wave_sum(ssq);
+        if (lane == 0) sc_sh[wave] = ssq;
+        __syncthreads();
+        ssq = (sc_sh[0] + sc_sh[1]) + (sc_sh[2] + sc_sh[3]);
+        const double alpha = Pq[(long)t * 16 + t];
+        __syncthreads();
+        if (ssq == 0.0) continue;                    // nothing below the diagonal: H = I, tau = 0 (uniform branch)
+        const double beta = -copysign(sqrt(alpha * alpha + ssq), alpha);
+        const double tq = (beta - alpha) / beta, scale = 1.0 / (alpha - beta);
+        // v = (1, P[t+1:, t] * scale); w_u = v . P[t:, u] for u > t
+        double w[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) w[u] = 0.0;
+        for (long i = t + tid; i < m; i += 256) {
+            const double v = i == t ? 1.0 : Pq[i * 16 + t] * scale;
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (u > t) w[u] += v * Pq[i * 16 + u];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const double s = wave_sum(w[u]);
+            if (lane == 0) w_sh[wave][u] = s;
+        }
+        __syncthreads();
+        for (long i = t + tid; i < m; i += 256) {
+            const double v = i == t ? 1.0 : Pq[i * 16 + t] * scale;
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (u > t) {
+                    const double wu = (w_sh[0][u] + w_sh[1][u]) + (w_sh[2][u] + w_sh[3][u]);
+                    Pq[i * 16 + u] -= tq * wu * v;
+                }
+            Pq[i * 16 + t] = i == t ? beta : v;
+        }
+        if (tid == 0) taus[t] = tq;
+        __syncthreads();
+    }
+    // Gram matrix of the reflectors (unit diagonal, zeros above it), then T column by column
+    for (int a = 0; a < 16; ++a)
+        for (int b = a; b < 16; ++b) {
+            double s = 0.0;
+            for (long i = b + tid; i < m; i += 256) {
+                const double va = i == a ? 1.0 : (i > a ? Pq[i * 16 + a] : 0.0);
+                const double vb = i == b ? 1.0 : Pq[i * 16 + b];
+                s += va * vb;
+            }
+            s = wave_sum(s);
+            if (lane == 0) sc_sh[wave] = s;
+            __syncthreads();
+            if (tid == 0) Gv[a][b] = (sc_sh[0] + sc_sh[1]) + (sc_sh[2] + sc_sh[3]);
+            __syncthreads();
+        }
+    if (tid < 16) {
+        const int r = tid;
+        for (int c = 0; c < 16; ++c) Ts[r][c] = 0.0;
+    }
+    __syncthreads();
+    for (int c = 0; c < 16; ++c) {
+        if (tid < 16) {
+            const int r = tid;
+            if (r < c) {
+                double s = 0.0;
+                for (int q = r; q < c; ++q) s += Ts[r][q] * Gv[q][c];
+                Ts[r][c] = -taus[c] * s;
+            } else if (r == c) {
+                Ts[r][c] = taus[c];
+            }
+        }
+        __syncthreads();
+    }
+    small[BS_T + tid] = Ts[tid >> 4][tid & 15];
+    if (tid < 16 && c0 + tid < n) tau[c0 + tid] = taus[tid];
+    {
+        const int s = tid >> 4, u = tid & 15;          // the block below the band: R[s][u], s <= u
+        if (s <= u && s < m) bd[(long)(16 + s - u) * npad + c0 + u] = Pq[(long)s * 16 + u];
+    }
+    for (long e = tid; e < m * 16; e += 256) {
+        const long i = e / 16;
+        const int c = (int)(e & 15);
+        const double y = i == c ? 1.0 : (i > c && c < nr ? Pq[e] : 0.0);
+        Vp[(long)c * n + r0 + i] = y;
+        if (i >= c) A[(c0 + c) * n + r0 + i] = y;
+    }
+}
+
+__global__ __launch_bounds__(256) void band_house_kernel(double *__restrict__ A, long n, long c0, long m,
+                                                         double *__restrict__ Pq, double *__restrict__ small,
+                                                         double *__restrict__ Vp, double *__restrict__ tau,
+                                                         double *__restrict__ bd, long npad) {
+    {
+        const int s = threadIdx.x >> 4, u = threadIdx.x & 15;       // the panel's diagonal block
+        if (s >= u && c0 + s < n) bd[(long)(s - u) * npad + c0 + u] = A[(c0 + s) * n + c0 + u];
+    }
+    band_house_panel(A, n, c0, m, Pq, small, Vp, tau, bd, npad);
+}
+
+// The reflectors of a panel from what the second Gram pass left: Y = Q1 Z below the top 16 x 16 block, Y1 in it;
+// written to Vp[c][r0 + i] and to row c0+c of A (from its leading 1 on).  64 rows per block, thread = row, four
+// columns.  A flagged panel (Cholesky-QR gave up) is done by the first block with plain Householder steps.
+__global__ __launch_bounds__(256) void band_yt_kernel(double *__restrict__ A, long n, long c0, long m,
+                                                      double *__restrict__ Pq, double *__restrict__ small,
+                                                      double *__restrict__ Vp, double *__restrict__ tau,
+                                                      double *__restrict__ bd, long npad) {
+    __shared__ double Zs[16][17], tile[64][17];
+    const int tid = threadIdx.x;
+    const long r0 = c0 + BW;
+    if (small[BS_FLAG] != 0.0) {
+        if (blockIdx.x != 0) return;
+        band_house_panel(A, n, c0, m, Pq, small, Vp, tau, bd, npad);
+        __syncthreads();
+        if (tid == 0) small[BS_FLAG] = 0.0;
+        return;
+    }
+    Zs[tid >> 4][tid & 15] = small[BS_Z + tid];
+    const int rr = tid >> 2, cq = (tid & 3) * 4;
+    const long i = (long)blockIdx.x * 64 + rr;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[rr][cq + e] = i < m ? Pq[i * 16 + cq + e] : 0.0;
+    __syncthreads();
+    if (i >= m) return;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int c = cq + e;
+        double y = 0.0;
+        if (i >= 16) {
+            for (int u = 0; u <= c; ++u) y += tile[rr][u] * Zs[u][c];
+        } else {
+            y = small[BS_Y1 + (int)i * 16 + c];
+        }
+        Vp[(long)c * n + r0 + i] = y;
+        if (i >= c) A[(c0 + c) * n + r0 + i] = y;
+    }
+}
+
+// Xp[slice][i][c] = sum over the slice's k of A[r0+i][r0+k] Y[k][c]: 64 rows x 16 columns per block on the fp64
+// matrix cores, one 16-row strip per wave; the slices of the contraction give the chip enough blocks.
+constexpr int SYMM_KS_MAX = 16;
+__global__ __launch_bounds__(256) void band_symm_kernel(const double *__restrict__ A, long n, long r0, long m,
+                                                        const double *__restrict__ Vp, long chunk,
+                                                        double *__restrict__ Xp, int row_tiles, int ks) {
+    constexpr int KC = 64;
+    __shared__ double As[64][KC + 1];
+    __shared__ double Vs[16][KC + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    for (long id = blockIdx.x; id < (long)row_tiles * ks; id += gridDim.x) {
+        const long bx = id % row_tiles, by = id / row_tiles;
+        const long i0 = bx * 64;
+        const long kbeg = by * chunk, kend = min(m, kbeg + chunk);
+        // a stage = 64 columns of the contraction; the next stage travels to registers while this one is multiplied
+        double ra[16], rv[4];
+        auto fetch = [&](long k0) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int e = tid + 256 * u, r = e >> 6, q = e & 63;
+                const long i = i0 + r, k = k0 + q;
+                ra[u] = (i < m && k < kend) ? A[(r0 + i) * n + r0 + k] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = tid + 256 * u, c = e >> 6, q = e & 63;
+                const long k = k0 + q;
+                rv[u] = k < kend ? Vp[(long)c * n + r0 + k] : 0.0;
+            }
+        };
+        doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+        if (kbeg < kend) fetch(kbeg);
+        for (long k0 = kbeg; k0 < kend; k0 += KC) {
+            __syncthreads();                       // the stage before has been read
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int e = tid + 256 * u;
+                As[e >> 6][e & 63] = ra[u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = tid + 256 * u;
+                Vs[e >> 6][e & 63] = rv[u];
+            }
+            __syncthreads();
+            if (k0 + KC < kend) fetch(k0 + KC);
+#pragma unroll
+            for (int q = 0; q < KC; q += 4)
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(As[wave * 16 + l16][q + lq], Vs[l16][q + lq], acc, 0, 0, 0);
+        }
+        double *out = Xp + by * m * 16;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const long i = i0 + wave * 16 + 4 * r + lq;
+            if (i < m) out[i * 16 + l16] = acc[r];
+        }
+    }
+}
+
+// X = sum of the slices (written to Xa [m][16]); K = Y^T X as per-block partials (64 rows per block); the last
+// block adds them in block order and leaves S = T^T K T in small[BS_S2].
+__global__ __launch_bounds__(256) void band_k_kernel(const double *__restrict__ Xp, int ks, long m, long n, long r0,
+                                                     const double *__restrict__ Vp, double *__restrict__ Xa,
+                                                     double *__restrict__ small, double *__restrict__ part,
+                                                     unsigned *__restrict__ counter) {
+    __shared__ double xt[64][17], vt[64][17];
+    __shared__ double red[4][256];
+    __shared__ double Ks[16][17], Ts[16][17], KT[16][17];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    const int rr = tid >> 2, cq = (tid & 3) * 4;
+    const long i = (long)blockIdx.x * 64 + rr;
+    {
+        double x[4] = {0.0, 0.0, 0.0, 0.0};
+        if (i < m)
+#pragma unroll 4
+            for (int s = 0; s < ks; ++s) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] += Xp[((long)s * m + i) * 16 + cq + e];
+            }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xt[rr][cq + e] = x[e];
+            if (i < m) Xa[i * 16 + cq + e] = x[e];
+        }
+        // Y[row][c] of the block's rows: thread = (column c = tid / 16, four rows)
+        const int c = tid >> 4, r4 = (tid & 15) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const long ii = (long)blockIdx.x * 64 + r4 + e;
+            vt[r4 + e][c] = ii < m ? Vp[(long)c * n + r0 + ii] : 0.0;
+        }
+    }
+    __syncthreads();
+    doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int r = 16 * wave + 4 * s + lq;
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(vt[r][l16], xt[r][l16], acc, 0, 0, 0);      // K[a][b] += Y[r][a] X[r][b]
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][(4 * r + lq) * 16 + l16] = acc[r];
+    __syncthreads();
+    part[(long)blockIdx.x * 256 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+    if (!last_block_done(counter, gridDim.x)) return;
+    const double g = sum_block_partials(part, gridDim.x, tid);
+    const int a = tid >> 4, b = tid & 15;
+    Ks[a][b] = g;
+    Ts[a][b] = small[BS_T + tid];
+    if (tid == 0) *counter = 0u;
+    __syncthreads();
+    double s = 0.0;
+    for (int k = 0; k < 16; ++k) s += Ks[a][k] * Ts[k][b];
+    KT[a][b] = s;
+    __syncthreads();
+    s = 0.0;
+    for (int k = 0; k < 16; ++k) s += Ts[k][a] * KT[k][b];
+    small[BS_S2 + tid] = s;
+}
+
+// W = X T - 1/2 Y S; written as Wp[c][r0 + i].  64 rows per block: thread = (column c, four rows).
+__global__ __launch_bounds__(256) void band_w_kernel(const double *__restrict__ Xa, long m, long n, long r0,
+                                                     const double *__restrict__ Vp, const double *__restrict__ small,
+                                                     double *__restrict__ Wp) {
+    __shared__ double Ts[16][17], Ss[16][17], xt[64][17], yt[64][17];
+    const int tid = threadIdx.x;
+    Ts[tid >> 4][tid & 15] = small[BS_T + tid];
+    Ss[tid >> 4][tid & 15] = small[BS_S2 + tid];
+    const long i0 = (long)blockIdx.x * 64;
+    {
+        const int rr = tid >> 2, cq = (tid & 3) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) xt[rr][cq + e] = i0 + rr < m ? Xa[(i0 + rr) * 16 + cq + e] : 0.0;
+    }
+    const int c = tid >> 4, r4 = (tid & 15) * 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) yt[r4 + e][c] = i0 + r4 + e < m ? Vp[(long)c * n + r0 + i0 + r4 + e] : 0.0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int r = r4 + e;
+        if (i0 + r >= m) break;
+        double s = 0.0, h = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            if (k <= c) s += xt[r][k] * Ts[k][c];         // T is upper triangular
+            h += yt[r][k] * Ss[k][c];
+        }
+        Wp[(long)c * n + r0 + i0 + r] = s - 0.5 * h;
+    }
+}
+
+// band array: zero, with a unit diagonal on the padded columns; then the last diagonal block
+__global__ void band_init_kernel(double *__restrict__ bd, long n, long npad) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (BW + 1) * npad) return;
+    const long t = idx / npad, j = idx - t * npad;
+    bd[idx] = (t == 0 && j >= n) ? 1.0 : 0.0;
+}
+__global__ void band_tail_kernel(const double *__restrict__ A, long n, long c_end, double *__restrict__ bd,
+                                 long npad) {
+    for (int e = threadIdx.x; e < 32 * 32; e += blockDim.x) {
+        const long s = e >> 5, u = e & 31;
+        if (s >= u && s - u <= BW && c_end + s < n) bd[(s - u) * npad + c_end + u] = A[(c_end + s) * n + c_end + u];
+    }
+}
+
+// One block of up to NB reflectors applied to the accumulated matrix M (compact WY): M <- M (I - V T' V^T) on rows
+// jstart .. n-1 and columns k0+off .. n-1; T' = T^T when R = Q^T is built from the last block to the first,
+// T' = T when Q is built from the first block on.  cap > 0 bounds the blocks per launch of the two products.
+static void wy_apply_block(hipStream_t s2, const double *A64, double *R64, long N, const double *tau, double *S,
+                           double *T, double *Gp, double *G2, long k0, int nbc, long jstart, int forward, long cap,
+                           int off) {
+    hipLaunchKernelGGL(q_gram_kernel, dim3(nbc, nbc), dim3(256), 0, s2, A64, N, k0, nbc, S, off);
+    hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, s2, S, tau, k0, nbc, T);
+    const long m = N - k0 - off;               // length of the contraction
+    const long rows = N - jstart;
+    if (m < 1 || rows < 1) return;
+    const unsigned row_tiles = blocks_for(rows, 64), col_tiles = blocks_for(m, 64);
+    long ks = (2048 + (long)row_tiles - 1) / (long)row_tiles;      // eight blocks per compute unit or more
+    if (ks > WY_KS_MAX) ks = WY_KS_MAX;
+    if (ks > m / 256) ks = m / 256;
+    if (ks < 1) ks = 1;
+    long chunk = (m + ks - 1) / ks;
+    chunk = (chunk + 31) / 32 * 32;
+    const long g_blocks = (long)row_tiles * ks, u_blocks = (long)col_tiles * row_tiles;
+    hipLaunchKernelGGL(q_wy_g_kernel, dim3((unsigned)(cap > 0 && g_blocks > cap ? cap : g_blocks)), dim3(256), 0, s2,
+                       R64, A64, N, k0, nbc, chunk, Gp, jstart, (int)row_tiles, (int)ks, off);
+    hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(rows, 8)), dim3(256), 0, s2, Gp, T, N, k0, nbc, (int)ks, G2,
+                       jstart, forward);
+    hipLaunchKernelGGL(q_wy_update_kernel, dim3((unsigned)(cap > 0 && u_blocks > cap ? cap : u_blocks)), dim3(256), 0,
+                       s2, R64, A64, N, k0, nbc, G2, jstart, (int)col_tiles, (int)row_tiles, off);
+}
+
 }  // namespace
 
 size_t admmq_householder_scratch_doubles(int64_t n) {
@@ -929,24 +1534,7 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
     // jstart .. n-1 and columns k0+1 .. n-1; T' = T^T when R = Q^T is built from the last block to the first,
     // T' = T when Q is built from the first block on.
     auto apply_block = [&](hipStream_t s2, long k0, int nbc, long jstart, int forward, long cap) {
-        hipLaunchKernelGGL(q_gram_kernel, dim3(nbc, nbc), dim3(256), 0, s2, A64, N, k0, nbc, S);
-        hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, s2, S, tau, k0, nbc, T);
-        const long m = N - k0 - 1;                 // length of the contraction
-        const long rows = N - jstart;
-        const unsigned row_tiles = blocks_for(rows, 64), col_tiles = blocks_for(m, 64);
-        long ks = (2048 + (long)row_tiles - 1) / (long)row_tiles;      // eight blocks per compute unit or more
-        if (ks > WY_KS_MAX) ks = WY_KS_MAX;
-        if (ks > m / 256) ks = m / 256;
-        if (ks < 1) ks = 1;
-        long chunk = (m + ks - 1) / ks;
-        chunk = (chunk + 31) / 32 * 32;
-        const long g_blocks = (long)row_tiles * ks, u_blocks = (long)col_tiles * row_tiles;
-        hipLaunchKernelGGL(q_wy_g_kernel, dim3((unsigned)(cap > 0 && g_blocks > cap ? cap : g_blocks)), dim3(256), 0, s2,
-                           R64, A64, N, k0, nbc, chunk, Gp, jstart, (int)row_tiles, (int)ks);
-        hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(rows, 8)), dim3(256), 0, s2, Gp, T, N, k0, nbc, (int)ks, G2,
-                           jstart, forward);
-        hipLaunchKernelGGL(q_wy_update_kernel, dim3((unsigned)(cap > 0 && u_blocks > cap ? cap : u_blocks)), dim3(256), 0,
-                           s2, R64, A64, N, k0, nbc, G2, jstart, (int)col_tiles, (int)row_tiles);
+        wy_apply_block(s2, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, jstart, forward, cap, 1);
     };
     // While the trailing matrix fits the caches the panel chain above is bound by launch and memory latency and
     // leaves the chip mostly idle: Q = H_0 H_1 ... is then accumulated from the first block on (2 n^3 flop instead of
@@ -1066,6 +1654,123 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
                 const int nbc = (int)((nref - k0) < NB ? (nref - k0) : NB);
                 apply_block(st, k0, nbc, k0 + 1, 0, 0);
             }
+        }
+        hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
+    }
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+
+size_t admmq_band_scratch_doubles(int64_t n) {
+    const size_t N = (size_t)n;
+    return (1 + 2 * BW + SYMM_KS_MAX * BW + 2 * BW + WY_KS_MAX * NB + NB) * N + 2 * (N / 64 + 2) * 256 + 2 * NB * NB + 4096;
+}
+
+// Hs = Q Bd Q^T with Bd symmetric of half-bandwidth 16.  A64: [n][n] scaled Hessian (destroyed: reflectors end up in its
+// rows); R64: [n][n] scratch; vecs: admmq_band_scratch_doubles(n) doubles.  Outputs: Q, Qt (fp32 [n][n]) and the
+// band bd[t][j] = Bd[j + t][j], t = 0 .. 16, j < npad = n rounded up to a multiple of 16 (unit diagonal beyond n).
+admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double *R64, double *vecs, float *Q, float *Qt,
+                                 double *bd) {
+    hipStream_t st = ctx->stream;
+    const long N = (long)n, npad = (N + BW - 1) / BW * BW;
+    double *tau = vecs, *Vp = tau + N, *Wp = Vp + (long)BW * N, *Xp = Wp + (long)BW * N,
+           *Xa = Xp + (long)SYMM_KS_MAX * BW * N, *Pq = Xa + (long)BW * N, *Gp = Pq + (long)BW * N,
+           *G2 = Gp + (long)WY_KS_MAX * NB * N, *part1 = G2 + (long)NB * N, *part2 = part1 + (N / 64 + 2) * 256,
+           *S = part2 + (N / 64 + 2) * 256, *T = S + NB * NB, *small = T + NB * NB;
+    unsigned *counters = (unsigned *)(small + BS_COUNT);      // [0]: Gram kernels, [2]: K kernel
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, small, 0, 2048 * 8));
+    ADMMQ_TRY(admmq_k_fill_bytes(ctx, tau, 0, (size_t)N * 8));
+    hipLaunchKernelGGL(band_init_kernel, dim3(blocks_for((BW + 1) * npad, 256)), dim3(256), 0, st, bd, N, npad);
+    const long nref = N > BW + 1 ? N - BW - 1 : 0;            // reflector g has its leading 1 at index g + 16 <= n - 2
+    const long nblk_all = (nref + NB - 1) / NB;
+    // The accumulation of Q: as in the tridiagonal reduction, from the first block on and on a stream of its own
+    // while the matrix fits the caches (the panel chain is a string of short launches), else from the last block back
+    // on the main stream afterwards.
+    bool overlap = nref > 0 && N < symv_min_size();
+    {
+        const char *e = getenv("ADMMQ_Q_OVERLAP");
+        if (e && atoi(e) == 0) overlap = false;
+    }
+    long side_cap = 0;
+    {
+        const char *e = getenv("ADMMQ_Q_SIDE_BLOCKS");
+        if (e && atol(e) > 0) side_cap = atol(e);
+    }
+    hipStream_t side = nullptr;
+    if (overlap) {
+        if (!ctx->side[0] && hipStreamCreateWithFlags(&ctx->side[0], hipStreamNonBlocking) != hipSuccess) overlap = false;
+        side = ctx->side[0];
+    }
+    if (overlap && ctx->panel_event_count < nblk_all + 2) {
+        const int want = (int)nblk_all + 2;
+        hipEvent_t *grown = (hipEvent_t *)realloc(ctx->panel_events, (size_t)want * sizeof(hipEvent_t));
+        if (!grown) overlap = false;
+        else {
+            ctx->panel_events = grown;
+            while (ctx->panel_event_count < want) {
+                if (hipEventCreateWithFlags(&ctx->panel_events[ctx->panel_event_count], hipEventDisableTiming) != hipSuccess) {
+                    overlap = false;
+                    break;
+                }
+                ++ctx->panel_event_count;
+            }
+        }
+    }
+    if (overlap) {
+        ADMMQ_HIP(hipEventRecord(ctx->panel_events[nblk_all], st));
+        ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[nblk_all], 0));
+        hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, side, R64, N);
+    }
+    for (long c0 = 0; c0 < nref; c0 += BW) {
+        const long r0 = c0 + BW, m = N - r0;                  // m >= 2
+        const unsigned rb = blocks_for(m, 64);
+        if (m >= 64) {
+            hipLaunchKernelGGL(band_gram_kernel<1>, dim3(rb), dim3(256), 0, st, A64, N, c0, m, Pq, small, part1, counters,
+                               bd, npad, tau);
+            hipLaunchKernelGGL(band_gram_kernel<2>, dim3(rb), dim3(256), 0, st, A64, N, c0, m, Pq, small, part1, counters,
+                               bd, npad, tau);
+            hipLaunchKernelGGL(band_yt_kernel, dim3(rb), dim3(256), 0, st, A64, N, c0, m, Pq, small, Vp, tau, bd, npad);
+        } else {
+            hipLaunchKernelGGL(band_house_kernel, dim3(1), dim3(256), 0, st, A64, N, c0, m, Pq, small, Vp, tau, bd, npad);
+        }
+        const long row_tiles = (m + 63) / 64;
+        long ks = (1024 + row_tiles - 1) / row_tiles;
+        if (ks > SYMM_KS_MAX) ks = SYMM_KS_MAX;
+        if (ks > m / 256) ks = m / 256;
+        if (ks < 1) ks = 1;
+        long chunk = (m + ks - 1) / ks;
+        chunk = (chunk + 63) / 64 * 64;
+        hipLaunchKernelGGL(band_symm_kernel, dim3((unsigned)(row_tiles * ks)), dim3(256), 0, st, A64, N, r0, m, Vp, chunk,
+                           Xp, (int)row_tiles, (int)ks);
+        hipLaunchKernelGGL(band_k_kernel, dim3(rb), dim3(256), 0, st, Xp, (int)ks, m, N, r0, Vp, Xa, small, part2,
+                           counters + 2);
+        hipLaunchKernelGGL(band_w_kernel, dim3(rb), dim3(256), 0, st, Xa, m, N, r0, Vp, small, Wp);
+        const unsigned tiles = blocks_for(m, 64);
+        hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, BW, Vp, Wp, 0);
+        const long done = c0 + BW < nref ? c0 + BW : nref;     // reflectors finished so far
+        if (overlap && (done % NB == 0 || done == nref)) {
+            const long b = (done - 1) / NB, k0 = b * NB;
+            ADMMQ_HIP(hipEventRecord(ctx->panel_events[b], st));
+            ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[b], 0));
+            wy_apply_block(side, A64, R64, N, tau, S, T, Gp, G2, k0, (int)(done - k0), BW, 1, side_cap, BW);
+        }
+    }
+    {
+        const long c_end = (nref + BW - 1) / BW * BW;
+        hipLaunchKernelGGL(band_tail_kernel, dim3(1), dim3(256), 0, st, A64, N, c_end, bd, npad);
+    }
+    ADMMQ_HIP(hipGetLastError());
+    dim3 tb32(32, 8), tg((unsigned)((N + 31) / 32), (unsigned)((N + 31) / 32));
+    if (overlap) {
+        ADMMQ_HIP(hipEventRecord(ctx->panel_events[nblk_all + 1], side));
+        ADMMQ_HIP(hipStreamWaitEvent(st, ctx->panel_events[nblk_all + 1], 0));
+        hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Qt, Q);
+    } else {
+        hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, R64, N);
+        for (long b = nblk_all - 1; b >= 0; --b) {
+            const long k0 = b * NB;
+            const int nbc = (int)((nref - k0) < NB ? (nref - k0) : NB);
+            wy_apply_block(st, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, k0 + BW, 0, 0, BW);
         }
         hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
     }

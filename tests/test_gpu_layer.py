@@ -97,10 +97,12 @@ def test_one_iteration_returns_round_to_nearest(ctx):
     assert st.j_damp_admm == pytest.approx(st.j_damp_rtn, rel=1e-3)
 
 
+@pytest.mark.parametrize("form", ["tridiag", "band"])      # both forms of the factorisation (the library picks by size)
 @pytest.mark.parametrize("n,p,N,bits,g,T,seed", [(256, 96, 800, 3, 64, 120, 1), (384, 200, 1500, 2, 32, 150, 2),
                                                   (192, 130, 150, 4, 0, 100, 3)])
-def test_layer_objective_parity_other_shapes(ctx, n, p, N, bits, g, T, seed):
+def test_layer_objective_parity_other_shapes(ctx, monkeypatch, n, p, N, bits, g, T, seed, form):
     import paper_2605_11222_amd as admmq
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     X, W0 = correlated_problem(n, p, N, seed, outliers=3)
     H64 = orc.hessian([X.astype(np.float64)])
     H32 = H64.astype(np.float32)
@@ -119,8 +121,10 @@ def test_layer_objective_parity_other_shapes(ctx, n, p, N, bits, g, T, seed):
           f" rtn {st.j_damp_rtn:.5g} code mismatch {np.mean(k != ref.codes):.4f}")
 
 
-def test_layer_is_deterministic(ctx):
+@pytest.mark.parametrize("form", ["tridiag", "band"])
+def test_layer_is_deterministic(ctx, monkeypatch, form):
     import paper_2605_11222_amd as admmq
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     X, W0 = correlated_problem(256, 64, 700, 9)
     H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
     sched = admmq.Schedule(T=60, ls_rounds=2, ls_pairs=16, seed=4)

@@ -201,12 +201,22 @@ def test_first_projection_of_dense_weights_is_round_to_nearest(ctx):
 # ---------------------------------------------------------------------------------------------
 # the later shapes walk the product launcher's paths: whole 64 / 128 / 256 tiles filled by direct loads (256 x 1280,
 # 1024 x 2048, 2048 x 2048), a ragged width on the staged path (1024 x 4100), a column split whose tail takes a
-# smaller tile (768 x 5120: 3 x 20 tiles), and the tridiagonal solve's 8- and 16-column strips
+# smaller tile (768 x 5120: 3 x 20 tiles), and the tridiagonal solve's 8- and 16-column strips.
+# Both forms of the factorisation at every shape (the library picks by size; the environment forces one): the
+# tridiagonal form with its scalar recurrence, and the band form (block reflectors, 16 x 16 block elimination), for
+# which the shapes also cover n below one band width, n = 17 .. 19 (no, one and two reflectors), n not a multiple of
+# 16, a Hessian of rank n/3 + damping (640 x 130 with 400 tokens: panels close to rank-deficient) and the last
+# panels' plain Householder path.
+@pytest.mark.parametrize("form", ["tridiag", "band"])
 @pytest.mark.parametrize("n,p,N,seed", [(128, 64, 512, 0), (300, 77, 900, 1), (3, 5, 10, 2), (2, 4, 9, 3),
                                          (1, 3, 4, 4), (1024, 256, 3000, 5), (640, 130, 400, 6),
                                          (256, 1280, 600, 7), (1024, 2048, 2100, 8), (1024, 4100, 2100, 9),
-                                         (2048, 2048, 4200, 10), (768, 5120, 1600, 11)])
-def test_w_update_matches_literal_eq7_in_float64(ctx, n, p, N, seed):
+                                         (2048, 2048, 4200, 10), (768, 5120, 1600, 11),
+                                         (17, 20, 60, 12), (18, 33, 60, 13), (19, 16, 70, 14), (100, 50, 300, 15)])
+def test_w_update_matches_literal_eq7_in_float64(ctx, monkeypatch, n, p, N, seed, form):
+    if form == "tridiag" and seed >= 12:
+        pytest.skip("shapes added for the band form")
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     X, W0 = correlated_problem(n, p, N, seed, outliers=2 if n > 100 else 0)   # N < n in the last case
     H64 = orc.hessian([X.astype(np.float64)])
     H32 = H64.astype(np.float32)
@@ -233,7 +243,29 @@ def test_w_update_matches_literal_eq7_in_float64(ctx, n, p, N, seed):
         err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
         worst = max(worst, err)
         assert err < W_UPDATE_TOL, (rho, err)
-    print(f"n={n} p={p}: worst relative W-update error {worst:.2e}")
+    print(f"n={n} p={p} {form}: worst relative W-update error {worst:.2e}")
+
+
+def test_w_update_band_form_of_a_diagonal_hessian(ctx, monkeypatch):
+    """Uncorrelated channels: every block below the band is zero, the Gram matrix of a panel is singular, and the
+    reduction must fall back to plain Householder steps that find nothing to eliminate (Q = I).  eq. 7 is then
+    diagonal and has a closed form to compare with."""
+    monkeypatch.setenv("ADMMQ_FACTOR", "band")
+    n, p = 200, 48
+    rng = np.random.default_rng(5)
+    hd = (0.5 + rng.random(n)).astype(np.float32)
+    H32 = np.diag(hd).astype(np.float32)
+    W0 = rng.standard_normal((n, p)).astype(np.float32)
+    d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+    dg = d.cpu().numpy()
+    Ws = (W0 * dg[:, None]).astype(np.float32)
+    for rho in (0.1, 5.0):
+        D = (Ws + 0.1 * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.05 * rng.standard_normal(Ws.shape)).astype(np.float32)
+        Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        # Hs = I: W = (Ws + rho D - V) / (1 + rho)
+        Wref = (Ws.astype(np.float64) + rho * D.astype(np.float64) - V.astype(np.float64)) / (1.0 + rho)
+        assert np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref) < W_UPDATE_TOL
 
 
 @pytest.mark.parametrize("n,p,N,taken", [(1024, 6400, 2100, True), (2048, 3328, 4200, True), (1024, 1792, 2100, False)])
