@@ -486,6 +486,7 @@ struct LsGroupLds {
     int which_win[LS_K];
     int prow[LS_K][2];                            // rows of the applied pairs, -1 = none
     float wsum[LSG_PB_MAX][4];
+    int bad;                                      // set by a thread whose wait ran out
 };
 
 // lane 0 of every 16-lane row: acc + v[lane 1] + v[lane 2] + ... + v[lane 15] of its row, added in that order
@@ -598,6 +599,12 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     if (tid < LS_K * 4) (&L.coef_win[0][0])[tid] = 0.f;
     if (tid < LS_K) L.which_win[tid] = 0;
     if (tid < 2 * LS_K) (&L.prow[0][0])[tid] = -1;
+    if (tid == 0) L.bad = 0;
+    // A barrier that orders LDS traffic only.  __syncthreads() also waits for every global load and store the wave
+    // has in flight - here the requests for the next batch and the words just published - which put a trip to
+    // memory into every barrier of a step.  Global loads are waited for where their values are used, and the
+    // published words validate themselves.
+    auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     int moves_l = 0;
     double drop_l = 0.0;
     if (tid == 0) {
@@ -672,7 +679,9 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 if (chunks > 16) tot = row_ordered_sum(tot, v[1], true);
                 if (c0 == 0) L.tot[q] = tot;
             }
-            if (__syncthreads_or(bad ? 1 : 0)) {
+            if (bad) L.bad = 1;
+            lds_barrier();
+            if (L.bad) {
                 if (tid == 0) __hip_atomic_store(a.abort_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 return;
             }
@@ -748,7 +757,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 } else if (tid >= 64 && tid < 64 + PB * 4) {
                     L.e_own[(tid - 64) >> 2][tid & 3] = dep;
                 }
-                __syncthreads();
+                lds_barrier();
                 if (pl == 0) {
                     float st1 = 0.f, st2 = 0.f;
                     if (in) {
@@ -766,7 +775,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                     L.pd[s - 1][0][col] = st1;
                     L.pd[s - 1][1][col] = st2;
                 }
-                __syncthreads();
+                lds_barrier();
 #pragma unroll
                 for (int i = 0; i < PP; ++i)
                     if (has[i] && s < a.cnt)
@@ -788,7 +797,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 gain = wave_sum_f(gain);
                 if (lane == 0) L.wsum[4 * i + pl][sub] = gain;
             }
-            __syncthreads();
+            lds_barrier();
             if (tid < PB && q_base + tid < npairs) {
                 const unsigned seq = a.seq0 + (unsigned)s;
                 unsigned long long *tab = a.xch + (size_t)(seq & 1u) * LS_FAST_PAIRS * chunks;
@@ -812,7 +821,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 const int pp = tid / s, k = tid - pp * s, q = q_base + pp;
                 L.which_own[pp][k] = q < npairs ? ls_which(L.prow[k][0], L.prow[k][1], L.pairs_l[s + 1][q][0], L.pairs_l[s + 1][q][1]) : 0;
             }
-            __syncthreads();
+            lds_barrier();
             ls_apply_slots<PP>(own, has, coef_rows, which_rows, L.pd, col, s);
         }
     }
