@@ -1310,7 +1310,8 @@ __global__ __launch_bounds__(256) void band_yt_kernel(double *__restrict__ A, lo
 
 // Xp[slice][i][c] = sum over the slice's k of A[r0+i][r0+k] Y[k][c]: 64 rows x 16 columns per block on the fp64
 // matrix cores, one 16-row strip per wave; the slices of the contraction give the chip enough blocks.
-constexpr int SYMM_KS_MAX = 16;
+constexpr int SYMM_KS_MAX = 16;      // slices of the full-square product
+constexpr int SYMM_SLOTS_MAX = 64;   // slots of the lower-triangle product
 __global__ __launch_bounds__(256) void band_symm_kernel(const double *__restrict__ A, long n, long r0, long m,
                                                         const double *__restrict__ Vp, long chunk,
                                                         double *__restrict__ Xp, int row_tiles, int ks) {
@@ -1363,6 +1364,118 @@ __global__ __launch_bounds__(256) void band_symm_kernel(const double *__restrict
         for (int r = 0; r < 4; ++r) {
             const long i = i0 + wave * 16 + 4 * r + lq;
             if (i < m) out[i * 16 + l16] = acc[r];
+        }
+    }
+}
+
+// The same product from the lower triangle alone, for trailing matrices too large for the caches (the pass is then
+// bound by reading them): only entries A[i][j] with i >= j are read, and only those are kept up to date by the
+// rank-32 update in this mode.  A block owns a square of TS x TS tiles of 64 x 64 on or below the diagonal, (P, Q)
+// in units of that square; tile (ti, tj) below the diagonal adds A_t Y_cols to the rows of ti and A_t^T Y_rows to the
+// rows of tj, a diagonal tile is made symmetric in LDS and used once.  The square's two results go to slots of
+// their own, Xp[Q][rows of P] and Xp[P][rows of Q] (one slot when P == Q), so that every block of rows receives
+// exactly one piece per slot 0 .. S-1 and band_k_kernel adds them in slot order: no atomics, a fixed order.
+template <int TS>
+__global__ __launch_bounds__(256) void band_symm_lower_kernel(const double *__restrict__ A, long n, long r0, long m,
+                                                              const double *__restrict__ Vp, double *__restrict__ Xp) {
+    __shared__ double As[64][65];
+    __shared__ double Vc[16][65], Vr[16][65];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
+    int P, Q;
+    tri_tile_of((int)blockIdx.x, P, Q);
+    const long ntile = (m + 63) / 64;
+    doublex4 acc_n[TS], acc_t[TS];
+#pragma unroll
+    for (int t = 0; t < TS; ++t) {
+        acc_n[t] = doublex4{0.0, 0.0, 0.0, 0.0};
+        acc_t[t] = doublex4{0.0, 0.0, 0.0, 0.0};
+    }
+    double ra[16], rc[4], rr[4];
+    auto valid = [&](int ti, int tj) {
+        const long gi = (long)P * TS + ti, gj = (long)Q * TS + tj;
+        return gi < ntile && gj <= gi;
+    };
+    auto fetch = [&](int ti, int tj) {
+        const long i0 = ((long)P * TS + ti) * 64, j0 = ((long)Q * TS + tj) * 64;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int e = tid + 256 * u, r = e >> 6, q = e & 63;
+            const long i = i0 + r, j = j0 + q;
+            ra[u] = (i < m && j <= i) ? A[(r0 + i) * n + r0 + j] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = tid + 256 * u, c = e >> 6, q = e & 63;
+            rc[u] = j0 + q < m ? Vp[(long)c * n + r0 + j0 + q] : 0.0;
+            rr[u] = i0 + q < m ? Vp[(long)c * n + r0 + i0 + q] : 0.0;
+        }
+    };
+    // the valid tiles of the square in row-major order; the next one travels to registers while this one is multiplied
+    int ti = 0, tj = 0;
+    auto advance = [&](int &a, int &b) {          // next valid tile after (a, b), or a = TS
+        do {
+            if (++b == TS) {
+                b = 0;
+                ++a;
+            }
+        } while (a < TS && !valid(a, b));
+    };
+    if (!valid(0, 0)) advance(ti, tj);
+    if (ti < TS) fetch(ti, tj);
+    while (ti < TS) {
+        __syncthreads();                       // the tile before has been read
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int e = tid + 256 * u;
+            As[e >> 6][e & 63] = ra[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = tid + 256 * u;
+            Vc[e >> 6][e & 63] = rc[u];
+            Vr[e >> 6][e & 63] = rr[u];
+        }
+        const bool diag = (long)P * TS + ti == (long)Q * TS + tj;
+        __syncthreads();
+        if (diag) {
+            // the stored upper half of a diagonal tile may be stale: mirror the lower half
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int e = tid + 256 * u, r = e >> 6, q = e & 63;
+                if (q > r) As[r][q] = As[q][r];
+            }
+            __syncthreads();
+        }
+        const int ci = ti, cj = tj;
+        advance(ti, tj);
+        if (ti < TS) fetch(ti, tj);
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            if (t == ci) {
+#pragma unroll
+                for (int q = 0; q < 64; q += 4)
+                    acc_n[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(As[wave * 16 + l16][q + lq], Vc[l16][q + lq], acc_n[t], 0, 0, 0);
+            }
+            if (t == cj && !diag) {
+#pragma unroll
+                for (int q = 0; q < 64; q += 4)
+                    acc_t[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(As[q + lq][wave * 16 + l16], Vr[l16][q + lq], acc_t[t], 0, 0, 0);
+            }
+        }
+    }
+    // results: rows of P into slot Q, rows of Q into slot P (summed into one piece when P == Q)
+#pragma unroll
+    for (int t = 0; t < TS; ++t) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const long in_n = ((long)P * TS + t) * 64 + wave * 16 + 4 * r + lq;
+            const long in_t = ((long)Q * TS + t) * 64 + wave * 16 + 4 * r + lq;
+            if (P == Q) {
+                if (in_n < m) Xp[((long)Q * m + in_n) * 16 + l16] = acc_n[t][r] + acc_t[t][r];
+            } else {
+                if (in_n < m) Xp[((long)Q * m + in_n) * 16 + l16] = acc_n[t][r];
+                if (in_t < m) Xp[((long)P * m + in_t) * 16 + l16] = acc_t[t][r];
+            }
         }
     }
 }
@@ -1663,7 +1776,7 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
 
 size_t admmq_band_scratch_doubles(int64_t n) {
     const size_t N = (size_t)n;
-    return (1 + 2 * BW + SYMM_KS_MAX * BW + 2 * BW + WY_KS_MAX * NB + NB) * N + 2 * (N / 64 + 2) * 256 + 2 * NB * NB + 4096;
+    return (1 + 2 * BW + SYMM_SLOTS_MAX * BW + 2 * BW + WY_KS_MAX * NB + NB) * N + 2 * (N / 64 + 2) * 256 + 2 * NB * NB + 4096;
 }
 
 // Hs = Q Bd Q^T with Bd symmetric of half-bandwidth 16.  A64: [n][n] scaled Hessian (destroyed: reflectors end up in its
@@ -1674,7 +1787,7 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
     hipStream_t st = ctx->stream;
     const long N = (long)n, npad = (N + BW - 1) / BW * BW;
     double *tau = vecs, *Vp = tau + N, *Wp = Vp + (long)BW * N, *Xp = Wp + (long)BW * N,
-           *Xa = Xp + (long)SYMM_KS_MAX * BW * N, *Pq = Xa + (long)BW * N, *Gp = Pq + (long)BW * N,
+           *Xa = Xp + (long)SYMM_SLOTS_MAX * BW * N, *Pq = Xa + (long)BW * N, *Gp = Pq + (long)BW * N,
            *G2 = Gp + (long)WY_KS_MAX * NB * N, *part1 = G2 + (long)NB * N, *part2 = part1 + (N / 64 + 2) * 256,
            *S = part2 + (N / 64 + 2) * 256, *T = S + NB * NB, *small = T + NB * NB;
     unsigned *counters = (unsigned *)(small + BS_COUNT);      // [0]: Gram kernels, [2]: K kernel
@@ -1721,6 +1834,14 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
         ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[nblk_all], 0));
         hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, side, R64, N);
     }
+    // trailing size from which the passes over the trailing matrix use its lower triangle only (ADMMQ_BAND_LOWER_MIN;
+    // with 64 slots of 256 rows the mode ends at 16384, where squares of 512 rows begin)
+    long lower_min = 6144;
+    {
+        const char *e = getenv("ADMMQ_BAND_LOWER_MIN");
+        if (e) lower_min = atol(e) < 128 ? (1L << 60) : atol(e);
+    }
+    bool was_lower = false;
     for (long c0 = 0; c0 < nref; c0 += BW) {
         const long r0 = c0 + BW, m = N - r0;                  // m >= 2
         const unsigned rb = blocks_for(m, 64);
@@ -1733,20 +1854,41 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
         } else {
             hipLaunchKernelGGL(band_house_kernel, dim3(1), dim3(256), 0, st, A64, N, c0, m, Pq, small, Vp, tau, bd, npad);
         }
-        const long row_tiles = (m + 63) / 64;
-        long ks = (1024 + row_tiles - 1) / row_tiles;
-        if (ks > SYMM_KS_MAX) ks = SYMM_KS_MAX;
-        if (ks > m / 256) ks = m / 256;
-        if (ks < 1) ks = 1;
-        long chunk = (m + ks - 1) / ks;
-        chunk = (chunk + 63) / 64 * 64;
-        hipLaunchKernelGGL(band_symm_kernel, dim3((unsigned)(row_tiles * ks)), dim3(256), 0, st, A64, N, r0, m, Vp, chunk,
-                           Xp, (int)row_tiles, (int)ks);
+        // While the trailing matrix is larger than the caches the two passes over it read and update its lower
+        // triangle only; below that size the upper triangle is restored once and the full-square kernels take over.
+        const int ts = m >= 16384 ? 8 : 4;                     // tiles per side of a block's square
+        const long S2 = (m + 64 * ts - 1) / (64 * ts);
+        const bool lower = m >= lower_min && S2 <= SYMM_SLOTS_MAX;
+        if (was_lower && !lower) {
+            const long t32 = (m + 31) / 32;
+            hipLaunchKernelGGL(tri_mirror_kernel, dim3((unsigned)(t32 * (t32 + 1) / 2)), dim3(32, 8), 0, st, A64, N, r0);
+        }
+        was_lower = lower;
+        long ks;
+        if (lower) {
+            ks = S2;
+            if (ts == 8)
+                hipLaunchKernelGGL(band_symm_lower_kernel<8>, dim3((unsigned)(S2 * (S2 + 1) / 2)), dim3(256), 0, st, A64, N, r0,
+                                   m, Vp, Xp);
+            else
+                hipLaunchKernelGGL(band_symm_lower_kernel<4>, dim3((unsigned)(S2 * (S2 + 1) / 2)), dim3(256), 0, st, A64, N, r0,
+                                   m, Vp, Xp);
+        } else {
+            const long row_tiles = (m + 63) / 64;
+            ks = (1024 + row_tiles - 1) / row_tiles;
+            if (ks > SYMM_KS_MAX) ks = SYMM_KS_MAX;
+            if (ks > m / 256) ks = m / 256;
+            if (ks < 1) ks = 1;
+            long chunk = (m + ks - 1) / ks;
+            chunk = (chunk + 63) / 64 * 64;
+            hipLaunchKernelGGL(band_symm_kernel, dim3((unsigned)(row_tiles * ks)), dim3(256), 0, st, A64, N, r0, m, Vp, chunk,
+                               Xp, (int)row_tiles, (int)ks);
+        }
         hipLaunchKernelGGL(band_k_kernel, dim3(rb), dim3(256), 0, st, Xp, (int)ks, m, N, r0, Vp, Xa, small, part2,
                            counters + 2);
         hipLaunchKernelGGL(band_w_kernel, dim3(rb), dim3(256), 0, st, Xa, m, N, r0, Vp, small, Wp);
         const unsigned tiles = blocks_for(m, 64);
-        hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, BW, Vp, Wp, 0);
+        hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, BW, Vp, Wp, lower ? 1 : 0);
         const long done = c0 + BW < nref ? c0 + BW : nref;     // reflectors finished so far
         if (overlap && (done % NB == 0 || done == nref)) {
             const long b = (done - 1) / NB, k0 = b * NB;
