@@ -105,7 +105,7 @@ struct BandStageRegs {
     doublex4 m[(GS * 2 * 256) / (64 * WPB * 4)];      // this thread's share of a stage's matrices (two per block row at most)
 };
 
-template <bool BACKWARD, int WPB>
+template <bool BACKWARD, int WPB, bool FULL>
 struct BandSweep {
     const double *fac;
     int nbk;
@@ -130,7 +130,7 @@ struct BandSweep {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const long row = (long)I * 16 + 4 * s + kq;
-                const bool ok = jok && I >= 0 && I < nbk && row < n;
+                const bool ok = FULL || (jok && I >= 0 && I < nbk && row < n);
                 R.y[q][s] = ok ? Y[row * p + j] : 0.f;
                 if (BACKWARD) R.r[q][s] = ok ? S[row * p + j] : 0.f;
             }
@@ -141,7 +141,7 @@ struct BandSweep {
             const int e = (tid + NT * v) * 4, mat = e >> 8, i = e & 255, q = mat / NM, w = mat - q * NM;
             const int I = row_of(k, q);
             doublex4 z = {0.0, 0.0, 0.0, 0.0};
-            if (I >= 0 && I < nbk) z = *(const doublex4 *)(fac + ((long)I * 3 + (BACKWARD ? 1 + w : 0)) * 256 + i);
+            if (FULL || (I >= 0 && I < nbk)) z = *(const doublex4 *)(fac + ((long)I * 3 + (BACKWARD ? 1 + w : 0)) * 256 + i);
             R.m[v] = z;
         }
     }
@@ -152,7 +152,11 @@ struct BandSweep {
     }
 };
 
-template <int WPB>
+// FULL: n a multiple of 16, the number of block rows a multiple of GS and p a multiple of 16 WPB, so that no access
+// needs a guard: the sweeps are then free of branches (a stage is one basic block, which lets the compiler overlap
+// one block row's stores with the next one's products), and the backward sweep issues the product that does not
+// hang on the recurrence, (rho Delta^-1) yh of the NEXT block row, between the steps of the one that does.
+template <int WPB, bool FULL>
 __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 1))) void band_apply_kernel(const double *__restrict__ fac, int nbk, long n, long p,
                                                          const float *__restrict__ Y, float *__restrict__ S,
                                                          unsigned *__restrict__ amax_out) {
@@ -163,11 +167,12 @@ __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int nst = (nbk + GS - 1) / GS;
     unsigned smax = 0;
     BandStageRegs<WPB> RA, RB, RC;
-    auto lds_barrier = [&]() { __syncthreads(); };
+    // (a barrier that orders LDS traffic only: __syncthreads() would also wait for the requests two stages ahead)
+    auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
     // ---- forward: yh_I = y_I - F_I yh_{I-1}; r_I = yh_I - y_I goes to S ---------------------------------------
     {
-        BandSweep<false, WPB> sw{fac, nbk, n, p, Y, S, lane, wave, tid, col, kq, j, jok, lds};
+        BandSweep<false, WPB, FULL> sw{fac, nbk, n, p, Y, S, lane, wave, tid, col, kq, j, jok, lds};
         double yh[4] = {0.0, 0.0, 0.0, 0.0};
         auto stage = [&](int k, BandStageRegs<WPB> &cur, BandStageRegs<WPB> &nxt, BandStageRegs<WPB> &far) __attribute__((always_inline)) {
             // cur: stage k (its matrices are in LDS already); nxt: stage k+1 (requested a stage ago); far: free
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 1))
                     const long row = (long)I * 16 + 4 * s + kq;
                     const float r = (float)(-acc[s]);
                     yh[s] = (double)cur.y[q][s] + (double)r;       // (the backward sweep forms yh from the same rounded r)
-                    if (jok && I < nbk && row < n) S[row * p + j] = r;
+                    if (FULL || (jok && I < nbk && row < n)) S[row * p + j] = r;
                 }
             }
             if (k + 1 < nst) sw.deposit(k + 1, nxt);
@@ -204,11 +209,39 @@ __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 1))
     // (every thread reads back below exactly the entries of r it has written itself)
     // ---- backward: u_I = (rho Delta_I^-1) yh_I - G_I u_{I+1}; S_I = y_I - u_I ----------------------------------------
     {
-        BandSweep<true, WPB> sw{fac, nbk, n, p, Y, S, lane, wave, tid, col, kq, j, jok, lds};
+        BandSweep<true, WPB, FULL> sw{fac, nbk, n, p, Y, S, lane, wave, tid, col, kq, j, jok, lds};
         double un[4] = {0.0, 0.0, 0.0, 0.0};
         auto stage = [&](int k, BandStageRegs<WPB> &cur, BandStageRegs<WPB> &nxt, BandStageRegs<WPB> &far) __attribute__((always_inline)) {
             if (k + 2 < nst) sw.request(k + 2, far);
             const double *mat = lds[k & 1];
+            if (FULL) {
+                // pa: (rho Delta^-1) yh of the block row in hand, formed while the row before it was on the recurrence
+                doublex4 pa = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    pa = __builtin_amdgcn_mfma_f64_16x16x4f64(mat[s * 64 + lane], (double)cur.y[0][s] + (double)cur.r[0][s], pa, 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < GS; ++q) {
+                    const int I = nbk - 1 - (k * GS + q);
+                    doublex4 acc2 = {0.0, 0.0, 0.0, 0.0}, pn = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        acc2 = __builtin_amdgcn_mfma_f64_16x16x4f64(mat[(q * 2 + 1) * 256 + s * 64 + lane], un[s], acc2, 0, 0, 0);
+                        if (q + 1 < GS)
+                            pn = __builtin_amdgcn_mfma_f64_16x16x4f64(mat[((q + 1) * 2) * 256 + s * 64 + lane],
+                                                                      (double)cur.y[q + 1][s] + (double)cur.r[q + 1][s], pn, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const long row = (long)I * 16 + 4 * s + kq;
+                        un[s] = pa[s] - acc2[s];
+                        const float sv = (float)((double)cur.y[q][s] - un[s]);
+                        S[row * p + j] = sv;
+                        smax = max(smax, __float_as_uint(fabsf(sv)));
+                    }
+                    pa = pn;
+                }
+            } else {
 #pragma unroll
             for (int q = 0; q < GS; ++q) {
                 const int I = nbk - 1 - (k * GS + q);
@@ -229,6 +262,7 @@ __global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, 1))
                         smax = max(smax, __float_as_uint(fabsf(sv)));
                     }
                 }
+            }
             }
             if (k + 1 < nst) sw.deposit(k + 1, nxt);
             lds_barrier();
@@ -278,19 +312,20 @@ admmq_status admmq_k_band_apply(admmq_ctx *ctx, const double *fac, int64_t n, in
     static int wpb = 0;
     if (wpb == 0) {
         const char *e = getenv("ADMMQ_BAND_WAVES");
-        wpb = e ? atoi(e) : 4;
-        if (wpb != 1 && wpb != 2 && wpb != 4) wpb = 4;
+        wpb = e ? atoi(e) : 2;              // measured at 12288 x 4096: 0.66 ms with two strips per block, 0.72 ms with four
+        if (wpb != 2 && wpb != 4) wpb = 2;
     }
     const long strips = (p + 15) / 16;
-    if (wpb == 1)
-        hipLaunchKernelGGL(band_apply_kernel<1>, dim3((unsigned)strips), dim3(64), 0, ctx->stream, fac, nbk, (long)n, (long)p,
-                           Y, S, amax_out);
-    else if (wpb == 2)
-        hipLaunchKernelGGL(band_apply_kernel<2>, dim3((unsigned)((strips + 1) / 2)), dim3(128), 0, ctx->stream, fac, nbk,
-                           (long)n, (long)p, Y, S, amax_out);
-    else
-        hipLaunchKernelGGL(band_apply_kernel<4>, dim3((unsigned)((strips + 3) / 4)), dim3(256), 0, ctx->stream, fac, nbk,
-                           (long)n, (long)p, Y, S, amax_out);
+    const bool full = n % BW == 0 && nbk % GS == 0 && p % (16 * wpb) == 0;
+#define ADMMQ_BAND_LAUNCH(W, F)                                                                                          \
+    hipLaunchKernelGGL((band_apply_kernel<W, F>), dim3((unsigned)((strips + W - 1) / W)), dim3(64 * W), 0, ctx->stream, fac, \
+                       nbk, (long)n, (long)p, Y, S, amax_out)
+    if (wpb == 2) {
+        if (full) ADMMQ_BAND_LAUNCH(2, true); else ADMMQ_BAND_LAUNCH(2, false);
+    } else {
+        if (full) ADMMQ_BAND_LAUNCH(4, true); else ADMMQ_BAND_LAUNCH(4, false);
+    }
+#undef ADMMQ_BAND_LAUNCH
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
 }
