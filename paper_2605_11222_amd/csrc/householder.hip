@@ -683,9 +683,12 @@ __global__ void identity_kernel(double *__restrict__ R, long n) {
     R[idx] = (idx - i * n == i) ? 1.0 : 0.0;
 }
 
+// The accumulation works on blocks of NBT reflectors: 32 beside the tridiagonal chain (one panel), 64 for the band
+// form (four panels: R is read and written once per 64 reflectors instead of once per 32).
 // Reflector k0+c is row k0+c of A on indices >= k0+c+off (leading 1 stored); off = 1 for the tridiagonal
 // reduction, the band width for the reduction to band form.  S[c1][c2] = v_c1 . v_c2.
 // grid (nbc, nbc), block 256; only c1 <= c2 is computed (and mirrored).
+template <int NBT>
 __global__ __launch_bounds__(256) void q_gram_kernel(const double *__restrict__ A, long n, long k0, int nbc,
                                                      double *__restrict__ S, int off) {
     __shared__ double sh[4];
@@ -699,21 +702,24 @@ __global__ __launch_bounds__(256) void q_gram_kernel(const double *__restrict__ 
     __syncthreads();
     if (threadIdx.x == 0) {
         const double t = (sh[0] + sh[1]) + (sh[2] + sh[3]);
-        S[c1 * NB + c2] = t;
-        S[c2 * NB + c1] = t;
+        S[c1 * NBT + c2] = t;
+        S[c2 * NBT + c1] = t;
     }
 }
 
 // T of the compact WY form (forward, column-wise): T[c][c] = tau_c,
-// T[0:c, c] = -tau_c T[0:c, 0:c] S[0:c, c].  One block of NB threads (thread r owns row r).
+// T[0:c, c] = -tau_c T[0:c, 0:c] S[0:c, c].  One block of NBT threads (thread r owns row r); the Gram matrix is kept
+// as its packed upper triangle (two full 64 x 64 arrays of doubles would not fit the static LDS limit).
+template <int NBT>
 __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__restrict__ tau, long k0, int nbc,
                                  double *__restrict__ T) {
-    __shared__ double Ts[NB][NB + 1], Ss[NB][NB + 1];
-    __shared__ double taus[NB];
+    __shared__ double Ts[NBT][NBT + 1];
+    __shared__ double Sp[NBT * (NBT + 1) / 2];          // S[q][c], q <= c, at c (c + 1) / 2 + q
+    __shared__ double taus[NBT];
     const int r = threadIdx.x;
-    for (int c = 0; c < NB; ++c) {
+    for (int c = 0; c < NBT; ++c) {
         Ts[r][c] = 0.0;
-        Ss[c][r] = S[c * NB + r];                  // the Gram matrix and the taus are fetched once, up front
+        if (r <= c) Sp[c * (c + 1) / 2 + r] = S[r * NBT + c];      // the Gram matrix and the taus are fetched once, up front
     }
     taus[r] = r < nbc ? tau[k0 + r] : 0.0;
     __syncthreads();
@@ -721,28 +727,29 @@ __global__ void q_tfactor_kernel(const double *__restrict__ S, const double *__r
         const double tc = taus[c];
         if (r < c) {
             double s = 0.0;
-            for (int q = r; q < c; ++q) s += Ts[r][q] * Ss[q][c];
+            for (int q = r; q < c; ++q) s += Ts[r][q] * Sp[c * (c + 1) / 2 + q];
             Ts[r][c] = -tc * s;
         } else if (r == c) {
             Ts[r][c] = tc;
         }
         __syncthreads();
     }
-    for (int c = 0; c < NB; ++c) T[r * NB + c] = Ts[r][c];
+    for (int c = 0; c < NBT; ++c) T[r * NBT + c] = Ts[r][c];
 }
 
 // Gp[s][j][c] = sum over slice s of i of R[j][i] v_c[i]  for rows j >= jstart (the slices of the
 // contraction index give the chip enough blocks; they are added in a fixed order by the consumer).
-// Block: 64 rows x NB columns on the fp64 matrix cores (v_mfma_f64_16x16x4), one 16-row strip per wave.
+// Block: 64 rows x NBT columns on the fp64 matrix cores (v_mfma_f64_16x16x4), one 16-row strip per wave.
 // grid: any number of blocks up to row_tiles * ks.
 constexpr int WY_KS_MAX = 16;
+template <int NBT>
 __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ R, const double *__restrict__ A,
                                                      long n, long k0, int nbc, long chunk,
                                                      double *__restrict__ Gp, long jstart, int row_tiles, int ks,
                                                      int off) {
     constexpr int KC = 32;
     __shared__ double Rs[64][KC + 1];
-    __shared__ double Vs[NB][KC + 1];
+    __shared__ double Vs[NBT][KC + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, lq = lane >> 4;
     // (row block, slice) pairs are walked with the grid's stride: a launch with few blocks leaves the rest of the
@@ -752,8 +759,10 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
         const long j0 = jstart + bx * 64;           // first row of the block (rows jstart .. n-1)
         const long ibeg = k0 + off + by * chunk;
         const long iend = min(n, ibeg + chunk);
-        // wave w owns rows 16w..16w+15 of the block, both halves of the NB columns: two 16 x 16 accumulators
-        doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+        // wave w owns rows 16w..16w+15 of the block, all NBT columns: NBT / 16 accumulators of 16 x 16
+        doublex4 acc[NBT / 16];
+#pragma unroll
+        for (int b = 0; b < NBT / 16; ++b) acc[b] = doublex4{0.0, 0.0, 0.0, 0.0};
         for (long i0 = ibeg; i0 < iend; i0 += KC) {
             __syncthreads();
             for (int e = tid; e < 64 * KC; e += 256) {
@@ -761,7 +770,7 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
                 const long j = j0 + r, i = i0 + q;
                 Rs[r][q] = (j < n && i < iend) ? R[j * n + i] : 0.0;
             }
-            for (int e = tid; e < NB * KC; e += 256) {
+            for (int e = tid; e < NBT * KC; e += 256) {
                 const int c = e / KC, q = e % KC;
                 const long i = i0 + q;
                 Vs[c][q] = (c < nbc && i < iend && i >= k0 + c + off) ? A[(k0 + c) * n + i] : 0.0;
@@ -771,37 +780,40 @@ __global__ __launch_bounds__(256) void q_wy_g_kernel(const double *__restrict__ 
             for (int q = 0; q < KC; q += 4) {
                 // matrix-core operands: A[row = lane%16][k = lane/16], B[k = lane/16][col = lane%16]
                 const double a = Rs[wave * 16 + l16][q + lq];
-                acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[l16][q + lq], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[16 + l16][q + lq], acc1, 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < NBT / 16; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, Vs[16 * b + l16][q + lq], acc[b], 0, 0, 0);
             }
         }
         // accumulator register r of lane l holds row 4r + l/16, column l%16 of its 16 x 16 block
-        double *out = Gp + by * n * NB;
+        double *out = Gp + by * n * NBT;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const long j = j0 + wave * 16 + 4 * r + lq;
             if (j < n) {
-                out[j * NB + l16] = acc0[r];
-                out[j * NB + 16 + l16] = acc1[r];
+#pragma unroll
+                for (int b = 0; b < NBT / 16; ++b) out[j * NBT + 16 * b + l16] = acc[b][r];
             }
         }
     }
 }
 
-// G2[j][c] = sum_q (sum_s Gp[s][j][q]) T[c][q] for rows j >= k0+1: the slices of the contraction are added in
+// G2[j][c] = sum_q (sum_s Gp[s][j][q]) T[c][q] for rows j >= jstart: the slices of the contraction are added in
 // index order and the small triangular factor applied once per row (not once per tile of the update).
-// One thread per (row, c); block 256 = 8 rows.
+// One thread per (row, c); block 256 = 256 / NBT rows.
+template <int NBT>
 __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__ Gp, const double *__restrict__ T,
                                                       long n, long k0, int nbc, int ks,
                                                       double *__restrict__ G2, long jstart, int forward) {
-    __shared__ double Ts[NB][NB + 1];
-    __shared__ double Gs[8][NB + 1];
-    const int tid = threadIdx.x, c = tid & (NB - 1), r = tid / NB;
-    for (int e = tid; e < NB * NB; e += 256) Ts[e / NB][e % NB] = T[e];
-    const long j = jstart + (long)blockIdx.x * 8 + r;
+    constexpr int RPB = 256 / NBT;
+    __shared__ double Ts[NBT][NBT + 1];
+    __shared__ double Gs[RPB][NBT + 1];
+    const int tid = threadIdx.x, c = tid & (NBT - 1), r = tid / NBT;
+    for (int e = tid; e < NBT * NBT; e += 256) Ts[e / NBT][e % NBT] = T[e];
+    const long j = jstart + (long)blockIdx.x * RPB + r;
     double g = 0.0;
     if (j < n && c < nbc)
-        for (int s = 0; s < ks; ++s) g += Gp[((long)s * n + j) * NB + c];
+        for (int s = 0; s < ks; ++s) g += Gp[((long)s * n + j) * NBT + c];
     Gs[r][c] = g;
     __syncthreads();
     if (j < n) {
@@ -811,32 +823,25 @@ __global__ __launch_bounds__(256) void q_wy_g2_kernel(const double *__restrict__
         } else {
             for (int q = c; q < nbc; ++q) t += Gs[r][q] * Ts[c][q];      // (G T^T)[c]; T is upper triangular
         }
-        G2[j * NB + c] = t;
+        G2[j * NBT + c] = t;
     }
 }
 
 // R[j][i] -= sum_c G2[j][c] v_c[i]  for j >= jstart, i >= k0+off.  64 x 64 tile per block; the product runs on the fp64
-// matrix cores: wave w owns rows 16w..16w+15 of the tile, four 16-column blocks, NB/4 steps each.
+// matrix cores: wave w owns rows 16w..16w+15 of the tile, four 16-column blocks; the reflectors go through LDS 32 at
+// a time.
+template <int NBT>
 __global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R, const double *__restrict__ A,
                                                           long n, long k0, int nbc,
                                                           const double *__restrict__ G2, long jstart, int col_tiles,
                                                           int row_tiles, int off) {
-    __shared__ double G2s[64][NB + 1];
-    __shared__ double Vs[NB][80];          // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
+    constexpr int CH = 32;
+    __shared__ double G2s[64][CH + 1];
+    __shared__ double Vs[CH][80];          // row stride 640 B: the two k-rows a half-wave reads use disjoint banks
     const int tid = threadIdx.x;
     for (long id = blockIdx.x; id < (long)col_tiles * row_tiles; id += gridDim.x) {
         const long bx = id % col_tiles, by = id / col_tiles;
         const long j0 = jstart + by * 64, i0 = k0 + off + bx * 64;
-        for (int e = tid; e < 64 * NB; e += 256) {
-            const int r = e / NB, c = e % NB;
-            const long j = j0 + r;
-            G2s[r][c] = (j < n && c < nbc) ? G2[j * NB + c] : 0.0;
-        }
-        for (int e = tid; e < NB * 64; e += 256) {
-            const int c = e >> 6, o = e & 63;
-            const long i = i0 + o;
-            Vs[c][o] = (c < nbc && i < n && i >= k0 + c + off) ? A[(k0 + c) * n + i] : 0.0;
-        }
         const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, lq = lane >> 4;
         // the tile's own entries are requested before the operands are waited for
         double rv[4][4];
@@ -849,16 +854,29 @@ __global__ __launch_bounds__(256) void q_wy_update_kernel(double *__restrict__ R
                 rv[r][b] = (j < n && i < n) ? R[j * n + i] : 0.0;
             }
         }
-        __syncthreads();
         doublex4 acc[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[b] = doublex4{0.0, 0.0, 0.0, 0.0};
+        for (int cb = 0; cb < NBT; cb += CH) {
+            if (cb > 0) __syncthreads();           // the chunk before has been read
+            for (int e = tid; e < 64 * CH; e += 256) {
+                const int r = e / CH, c = e % CH;
+                const long j = j0 + r;
+                G2s[r][c] = (j < n && cb + c < nbc) ? G2[j * NBT + cb + c] : 0.0;
+            }
+            for (int e = tid; e < CH * 64; e += 256) {
+                const int c = e >> 6, o = e & 63;
+                const long i = i0 + o;
+                Vs[c][o] = (cb + c < nbc && i < n && i >= k0 + cb + c + off) ? A[(k0 + cb + c) * n + i] : 0.0;
+            }
+            __syncthreads();
 #pragma unroll
-        for (int c = 0; c < NB; c += 4) {
-            const double g = G2s[wave * 16 + l16][c + lq];
+            for (int c = 0; c < CH; c += 4) {
+                const double g = G2s[wave * 16 + l16][c + lq];
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(g, Vs[c + lq][b * 16 + l16], acc[b], 0, 0, 0);
+                for (int b = 0; b < 4; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(g, Vs[c + lq][b * 16 + l16], acc[b], 0, 0, 0);
+            }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -913,6 +931,7 @@ inline unsigned blocks_for(long count, int bs) { return (unsigned)((count + bs -
 // A panel whose Gram matrix is not safely positive definite (a rank-deficient block), and the last panels (fewer
 // than 64 rows), take plain Householder steps in one block instead.
 constexpr int BW = 16;
+constexpr int QB = 64;           // reflectors per block of the accumulation of Q (four panels)
 enum { BS_R1 = 0, BS_R1INV = 256, BS_Z = 512, BS_Y1 = 768, BS_T = 1024, BS_S2 = 1280, BS_FLAG = 1536, BS_COUNT = 1600 };
 
 // entry `tid` of the per-block partial sums, added in block order; sixteen loads are in flight at a time (one load
@@ -1587,14 +1606,16 @@ __global__ void band_tail_kernel(const double *__restrict__ A, long n, long c_en
     }
 }
 
-// One block of up to NB reflectors applied to the accumulated matrix M (compact WY): M <- M (I - V T' V^T) on rows
+// One block of up to NBT reflectors applied to the accumulated matrix M (compact WY): M <- M (I - V T' V^T) on rows
 // jstart .. n-1 and columns k0+off .. n-1; T' = T^T when R = Q^T is built from the last block to the first,
 // T' = T when Q is built from the first block on.  cap > 0 bounds the blocks per launch of the two products.
+// S, T: NBT x NBT doubles; Gp: WY_KS_MAX x N x NBT; G2: N x NBT.
+template <int NBT>
 static void wy_apply_block(hipStream_t s2, const double *A64, double *R64, long N, const double *tau, double *S,
                            double *T, double *Gp, double *G2, long k0, int nbc, long jstart, int forward, long cap,
                            int off) {
-    hipLaunchKernelGGL(q_gram_kernel, dim3(nbc, nbc), dim3(256), 0, s2, A64, N, k0, nbc, S, off);
-    hipLaunchKernelGGL(q_tfactor_kernel, dim3(1), dim3(NB), 0, s2, S, tau, k0, nbc, T);
+    hipLaunchKernelGGL(q_gram_kernel<NBT>, dim3(nbc, nbc), dim3(256), 0, s2, A64, N, k0, nbc, S, off);
+    hipLaunchKernelGGL(q_tfactor_kernel<NBT>, dim3(1), dim3(NBT), 0, s2, S, tau, k0, nbc, T);
     const long m = N - k0 - off;               // length of the contraction
     const long rows = N - jstart;
     if (m < 1 || rows < 1) return;
@@ -1606,11 +1627,11 @@ static void wy_apply_block(hipStream_t s2, const double *A64, double *R64, long 
     long chunk = (m + ks - 1) / ks;
     chunk = (chunk + 31) / 32 * 32;
     const long g_blocks = (long)row_tiles * ks, u_blocks = (long)col_tiles * row_tiles;
-    hipLaunchKernelGGL(q_wy_g_kernel, dim3((unsigned)(cap > 0 && g_blocks > cap ? cap : g_blocks)), dim3(256), 0, s2,
+    hipLaunchKernelGGL(q_wy_g_kernel<NBT>, dim3((unsigned)(cap > 0 && g_blocks > cap ? cap : g_blocks)), dim3(256), 0, s2,
                        R64, A64, N, k0, nbc, chunk, Gp, jstart, (int)row_tiles, (int)ks, off);
-    hipLaunchKernelGGL(q_wy_g2_kernel, dim3(blocks_for(rows, 8)), dim3(256), 0, s2, Gp, T, N, k0, nbc, (int)ks, G2,
-                       jstart, forward);
-    hipLaunchKernelGGL(q_wy_update_kernel, dim3((unsigned)(cap > 0 && u_blocks > cap ? cap : u_blocks)), dim3(256), 0,
+    hipLaunchKernelGGL(q_wy_g2_kernel<NBT>, dim3(blocks_for(rows, 256 / NBT)), dim3(256), 0, s2, Gp, T, N, k0, nbc, (int)ks,
+                       G2, jstart, forward);
+    hipLaunchKernelGGL(q_wy_update_kernel<NBT>, dim3((unsigned)(cap > 0 && u_blocks > cap ? cap : u_blocks)), dim3(256), 0,
                        s2, R64, A64, N, k0, nbc, G2, jstart, (int)col_tiles, (int)row_tiles, off);
 }
 
@@ -1647,7 +1668,7 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
     // jstart .. n-1 and columns k0+1 .. n-1; T' = T^T when R = Q^T is built from the last block to the first,
     // T' = T when Q is built from the first block on.
     auto apply_block = [&](hipStream_t s2, long k0, int nbc, long jstart, int forward, long cap) {
-        wy_apply_block(s2, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, jstart, forward, cap, 1);
+        wy_apply_block<NB>(s2, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, jstart, forward, cap, 1);
     };
     // While the trailing matrix fits the caches the panel chain above is bound by launch and memory latency and
     // leaves the chip mostly idle: Q = H_0 H_1 ... is then accumulated from the first block on (2 n^3 flop instead of
@@ -1776,7 +1797,7 @@ admmq_status admmq_k_householder(admmq_ctx *ctx, double *A64, int64_t n, double 
 
 size_t admmq_band_scratch_doubles(int64_t n) {
     const size_t N = (size_t)n;
-    return (1 + 2 * BW + SYMM_SLOTS_MAX * BW + 2 * BW + WY_KS_MAX * NB + NB) * N + 2 * (N / 64 + 2) * 256 + 2 * NB * NB + 4096;
+    return (1 + 2 * BW + SYMM_SLOTS_MAX * BW + 2 * BW + WY_KS_MAX * QB + QB) * N + 2 * (N / 64 + 2) * 256 + 2 * QB * QB + 4096;
 }
 
 // Hs = Q Bd Q^T with Bd symmetric of half-bandwidth 16.  A64: [n][n] scaled Hessian (destroyed: reflectors end up in its
@@ -1788,14 +1809,14 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
     const long N = (long)n, npad = (N + BW - 1) / BW * BW;
     double *tau = vecs, *Vp = tau + N, *Wp = Vp + (long)BW * N, *Xp = Wp + (long)BW * N,
            *Xa = Xp + (long)SYMM_SLOTS_MAX * BW * N, *Pq = Xa + (long)BW * N, *Gp = Pq + (long)BW * N,
-           *G2 = Gp + (long)WY_KS_MAX * NB * N, *part1 = G2 + (long)NB * N, *part2 = part1 + (N / 64 + 2) * 256,
-           *S = part2 + (N / 64 + 2) * 256, *T = S + NB * NB, *small = T + NB * NB;
+           *G2 = Gp + (long)WY_KS_MAX * QB * N, *part1 = G2 + (long)QB * N, *part2 = part1 + (N / 64 + 2) * 256,
+           *S = part2 + (N / 64 + 2) * 256, *T = S + QB * QB, *small = T + QB * QB;
     unsigned *counters = (unsigned *)(small + BS_COUNT);      // [0]: Gram kernels, [2]: K kernel
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, small, 0, 2048 * 8));
     ADMMQ_TRY(admmq_k_fill_bytes(ctx, tau, 0, (size_t)N * 8));
     hipLaunchKernelGGL(band_init_kernel, dim3(blocks_for((BW + 1) * npad, 256)), dim3(256), 0, st, bd, N, npad);
     const long nref = N > BW + 1 ? N - BW - 1 : 0;            // reflector g has its leading 1 at index g + 16 <= n - 2
-    const long nblk_all = (nref + NB - 1) / NB;
+    const long nblk_all = (nref + QB - 1) / QB;
     // The accumulation of Q: as in the tridiagonal reduction, from the first block on and on a stream of its own
     // while the matrix fits the caches (the panel chain is a string of short launches), else from the last block back
     // on the main stream afterwards.
@@ -1890,11 +1911,11 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
         const unsigned tiles = blocks_for(m, 64);
         hipLaunchKernelGGL(tri_update_kernel, dim3(tiles, tiles), dim3(256), 0, st, A64, N, r0, BW, Vp, Wp, lower ? 1 : 0);
         const long done = c0 + BW < nref ? c0 + BW : nref;     // reflectors finished so far
-        if (overlap && (done % NB == 0 || done == nref)) {
-            const long b = (done - 1) / NB, k0 = b * NB;
+        if (overlap && (done % QB == 0 || done == nref)) {
+            const long b = (done - 1) / QB, k0 = b * QB;
             ADMMQ_HIP(hipEventRecord(ctx->panel_events[b], st));
             ADMMQ_HIP(hipStreamWaitEvent(side, ctx->panel_events[b], 0));
-            wy_apply_block(side, A64, R64, N, tau, S, T, Gp, G2, k0, (int)(done - k0), BW, 1, side_cap, BW);
+            wy_apply_block<QB>(side, A64, R64, N, tau, S, T, Gp, G2, k0, (int)(done - k0), BW, 1, side_cap, BW);
         }
     }
     {
@@ -1910,9 +1931,9 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
     } else {
         hipLaunchKernelGGL(identity_kernel, dim3(blocks_for(N * N, 256)), dim3(256), 0, st, R64, N);
         for (long b = nblk_all - 1; b >= 0; --b) {
-            const long k0 = b * NB;
-            const int nbc = (int)((nref - k0) < NB ? (nref - k0) : NB);
-            wy_apply_block(st, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, k0 + BW, 0, 0, BW);
+            const long k0 = b * QB;
+            const int nbc = (int)((nref - k0) < QB ? (nref - k0) : QB);
+            wy_apply_block<QB>(st, A64, R64, N, tau, S, T, Gp, G2, k0, nbc, k0 + BW, 0, 0, BW);
         }
         hipLaunchKernelGGL(emit_q_kernel, tg, tb32, 0, st, R64, N, Q, Qt);
     }
