@@ -137,7 +137,7 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     int32_t profile;
     int32_t n_gemm, n_tridiag, n_project, n_ls_apply;
     float ms_gemm;          /* the two n x n x p products of each W-update (eq. 7)            */
-    float ms_tridiag;       /* the tridiagonal solve between them                             */
+    float ms_tridiag;       /* the solve with the middle factor between them (either form)    */
     float ms_project;       /* fused projection + dual + residual pass (eqs. 8-10, 9)         */
     float ms_ls_apply;      /* rank-2 gradient correction passes of the local search          */
     int32_t refresh_accepted;          /* 1 if the grid refresh was tried and accepted (eq. 12)  */
@@ -233,8 +233,10 @@ admmq_status admmq_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t 
 
 /* Alg. 1 lines 1-3: damp, scale and factorise H once; the result stays in the context and serves
  * every rho.  d_out (device fp32 [n], may be NULL) receives d_i = sqrt(H'_ii) = 1/Sigma_ii.
- * The factorisation is Hs = Q T Q^T with T tridiagonal (Householder, fp64): (Hs + rho I)^{-1} =
- * Q (T + rho I)^{-1} Q^T for any rho, which plays the part of the eigendecomposition of Sec. 3.3. */
+ * The factorisation is an orthogonal similarity Hs = Q M Q^T in fp64 (Householder reflectors) with M tridiagonal for
+ * n < 8192 and a band matrix of half-bandwidth 16 from there on: (Hs + rho I)^{-1} = Q (M + rho I)^{-1} Q^T for any
+ * rho, which plays the part of the eigendecomposition of Sec. 3.3.  The environment variable ADMMQ_FACTOR
+ * (tridiag / band, read at every call) forces one form. */
 admmq_status admmq_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp,
                              int32_t precondition, float *d_out, double *lambda_out);
 

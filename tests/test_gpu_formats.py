@@ -124,8 +124,10 @@ def test_codebook_must_ascend(ctx):
                                                   ("codebook", 128, 64, 512, 3, 0, 50),
                                                   ("codebook_kept", 256, 96, 1024, 2, 0, 60),
                                                   ("codebook_kept", 192, 130, 700, 4, 0, 40)])
-def test_layer_with_another_format_matches_the_oracle(ctx, kind, n, p, N, bits, g, T):
+@pytest.mark.parametrize("form", ["tridiag", "band"])      # both forms of the factorisation
+def test_layer_with_another_format_matches_the_oracle(ctx, monkeypatch, kind, n, p, N, bits, g, T, form):
     import paper_2605_11222_amd as admmq
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     X, W0 = correlated_problem(n, p, N, seed=n + T, outliers=2)
     rng = np.random.default_rng(1)
     W0[rng.integers(0, n, p), np.arange(p)] *= 8.0

@@ -389,10 +389,13 @@ def test_bit_width_extremes(ctx, bits):
     assert st.j_damp == pytest.approx(f64_objective(H32, st.lam, W0, k, scales.cpu().numpy(), zeros.cpu().numpy(), 32), rel=1e-4)
 
 
-def test_shared_hessian_reuses_the_factorisation(ctx):
+@pytest.mark.parametrize("form", ["tridiag", "band"])
+def test_shared_hessian_reuses_the_factorisation(ctx, monkeypatch, form):
     """Two weight matrices that see the same activations: the second call skips Alg. 1 lines 1-3 and must return
-    exactly what a call with its own factorisation returns; a different H is refused."""
+    exactly what a call with its own factorisation returns; a different H is refused.  Both forms of the
+    factorisation (the kept one decides how the later call solves)."""
     import paper_2605_11222_amd as admmq
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     X, W0 = correlated_problem(192, 64, 600, 50)
     _, W1 = correlated_problem(192, 40, 600, 51)
     H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
@@ -411,13 +414,15 @@ def test_shared_hessian_reuses_the_factorisation(ctx):
     assert e.value.code == 7
 
 
-def test_batched_layers_on_a_shared_hessian(ctx):
+@pytest.mark.parametrize("form", ["tridiag", "band"])
+def test_batched_layers_on_a_shared_hessian(ctx, monkeypatch, form):
     """Three matrices of different width, bit width and group size in one call: the W-update products run over the
     concatenated columns (offsets 0, 64, 114: the last one off the 16-byte vector path), everything else per
     matrix.  Columns never interact (Sec. 3.5), so each matrix must get the grid of a call of its own, an
     objective within the tolerance of the oracle's run on that matrix alone, and codes that differ from its own
     call only where a product's rounding moved a near-midpoint value."""
     import paper_2605_11222_amd as admmq
+    monkeypatch.setenv("ADMMQ_FACTOR", form)
     n, T = 192, 60
     X, Wa = correlated_problem(n, 64, 600, 60, outliers=2)
     _, Wb = correlated_problem(n, 50, 600, 61)

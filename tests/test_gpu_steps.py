@@ -246,6 +246,34 @@ def test_w_update_matches_literal_eq7_in_float64(ctx, monkeypatch, n, p, N, seed
     print(f"n={n} p={p} {form}: worst relative W-update error {worst:.2e}")
 
 
+@pytest.mark.parametrize("n,p,N,seed", [(1024, 96, 3000, 21), (700, 64, 250, 22)])
+def test_w_update_band_form_with_lower_triangle_passes(ctx, monkeypatch, n, p, N, seed):
+    """The band reduction's two trailing passes read and update only the lower triangle while the trailing matrix
+    is large (6144 rows and up by default); here the mode is switched on for small matrices, so that the step is
+    compared with eq. 7 in float64 through that path too: squares of 4 x 4 tiles with ragged edges, the
+    hand-over to the full-square kernels (upper triangle restored) at 128 rows, a Hessian of rank N < n."""
+    monkeypatch.setenv("ADMMQ_FACTOR", "band")
+    monkeypatch.setenv("ADMMQ_BAND_LOWER_MIN", "128")
+    X, W0 = correlated_problem(n, p, N, seed, outliers=2)
+    H32 = orc.hessian([X.astype(np.float64)]).astype(np.float32)
+    d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+    Hd, _ = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    dg = d.cpu().numpy()
+    d64 = dg.astype(np.float64)
+    Hs = Hd / d64[:, None] / d64[None, :]
+    Ws = (W0 * dg[:, None]).astype(np.float32)
+    lam_e, U = np.linalg.eigh(Hs)
+    lam_e = np.maximum(lam_e, 0)
+    rng = np.random.default_rng(seed)
+    scale = np.abs(Ws).mean()
+    for rho in (0.1, 37.0):
+        D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        Wref = orc.w_update(U, lam_e, Hs @ Ws.astype(np.float64), D.astype(np.float64), V.astype(np.float64), rho)
+        assert np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref) < W_UPDATE_TOL
+
+
 def test_w_update_band_form_of_a_diagonal_hessian(ctx, monkeypatch):
     """Uncorrelated channels: every block below the band is zero, the Gram matrix of a panel is singular, and the
     reduction must fall back to plain Householder steps that find nothing to eliminate (Q = I).  eq. 7 is then
