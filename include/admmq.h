@@ -143,6 +143,11 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
     int32_t refresh_accepted;          /* 1 if the grid refresh was tried and accepted (eq. 12)  */
     double refresh_err_old, refresh_err_new;   /* the two sides of eq. 12 at the attempt        */
     double j_recon;         /* Tr(E^T H E) = ||X (Wq - W0)||_F^2 of the final result: j_damp without the damping term */
+    /* second products of eq. 7 that carried eqs. 8-10 as their epilogue (the iterate W stays in registers; taken
+     * where the product's tiles are whole and no codes are wanted from the iteration); not part of n_gemm / ms_gemm,
+     * and such iterations launch no projection pass */
+    int32_t n_gemm_project;
+    float ms_gemm_project;
 } admmq_stats;
 
 /* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.

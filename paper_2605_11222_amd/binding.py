@@ -47,7 +47,8 @@ class _Stats(C.Structure):
                 ("profile", C.c_int32), ("n_gemm", C.c_int32), ("n_tridiag", C.c_int32), ("n_project", C.c_int32),
                 ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
                 ("ms_project", C.c_float), ("ms_ls_apply", C.c_float), ("refresh_accepted", C.c_int32),
-                ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double), ("j_recon", C.c_double)]
+                ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double), ("j_recon", C.c_double),
+                ("n_gemm_project", C.c_int32), ("ms_gemm_project", C.c_float)]
 
 
 class _Format(C.Structure):
@@ -191,6 +192,8 @@ class LayerStats:
     refresh_err_old: float = 0.0
     refresh_err_new: float = 0.0
     j_recon: float = 0.0
+    n_gemm_project: int = 0
+    ms_gemm_project: float = 0.0
 
 
 def _ptr(t):
@@ -258,8 +261,12 @@ class Context:
         return cnt.value
 
     def quantize_layer(self, H, W0, bits, group_size=0, sched: Schedule | None = None, want_stats=True,
-                       want_history=False, profile=False):
+                       want_history=False, profile=False, want_flips=None):
+        """want_history: the primal residual of every iteration and, unless want_flips=False, the number of codes
+        each iteration changed (asking for those makes every iteration write its codes)."""
         torch = self._torch
+        if want_flips is None:
+            want_flips = want_history
         sched = sched or Schedule()
         n, p = W0.shape
         g = group_size if group_size else n
@@ -272,9 +279,10 @@ class Context:
         st = _Stats()
         st.profile = int(bool(profile))
         res = (C.c_float * sched.T)() if want_history else None
-        flips = (C.c_int64 * sched.T)() if want_history else None
+        flips = (C.c_int64 * sched.T)() if want_history and want_flips else None
         if want_history:
             st.primal_res = C.cast(res, C.POINTER(C.c_float))
+        if flips is not None:
             st.code_flips = C.cast(flips, C.POINTER(C.c_int64))
         _check(self._lib.admmq_quantize_layer(self._h, _ptr(H), _ptr(W0), n, p, W0.stride(0), bits, group_size,
                                               C.byref(cs), _ptr(codes), _ptr(scales), _ptr(zeros),
@@ -283,10 +291,10 @@ class Context:
         if want_stats:
             out = LayerStats(st.ms_total, st.ms_setup, st.ms_factor, st.ms_admm, st.ms_local_search, st.j_damp,
                              st.j_damp_admm, st.j_damp_rtn, st.lambda_, st.iters_done, st.ls_moves,
-                             list(res) if want_history else [], list(flips) if want_history else [],
+                             list(res) if want_history else [], list(flips) if flips is not None else [],
                              st.n_gemm, st.n_tridiag, st.n_project, st.n_ls_apply, st.ms_gemm, st.ms_tridiag,
                              st.ms_project, st.ms_ls_apply, bool(st.refresh_accepted), st.refresh_err_old,
-                             st.refresh_err_new, st.j_recon)
+                             st.refresh_err_new, st.j_recon, st.n_gemm_project, st.ms_gemm_project)
         return codes, scales, zeros, out
 
     def local_search(self, H, W0, bits, group_size, scales, zeros, codes, rounds=5, batches_per_round=0,

@@ -352,6 +352,12 @@ admmq_status mid_factors_compute(admmq_ctx *ctx, int64_t n, const double *rhos_d
     if (f.band) return admmq_k_band_factor(ctx, f.band, n, rhos_dev, T, mf.a);
     return admmq_k_tridiag_factor(ctx, f.ta, f.tb, n, rhos_dev, T, mf.a, mf.b);
 }
+// ADMMQ_FUSE_PROJECTION=0 keeps the projection pass a launch of its own in every iteration (read at every call)
+bool fuse_projection_enabled() {
+    const char *e = getenv("ADMMQ_FUSE_PROJECTION");
+    return !(e && atoi(e) == 0);
+}
+
 // S = (M + rho_t I)^-1 M Y; carries: the tridiagonal solve's per-tile checkpoints
 admmq_status mid_apply(admmq_ctx *ctx, const MidFactors &mf, int t, int64_t n, int64_t p, const float *Y, double *carries,
                        float *S, unsigned *amax_out) {
@@ -363,9 +369,13 @@ admmq_status mid_apply(admmq_ctx *ctx, const MidFactors &mf, int t, int64_t n, i
 
 // W = B + Q (M + rho I)^{-1} M (C0 - Q^T B)   (eq. 7 rewritten around B = D - V/rho; Hs = Q M Q^T)
 // F: n p + p doubles of scratch: the solve's fp32 result [n][p] in front, its per-tile checkpoints behind
+// With `proj` (fp32 products only) the second product applies eqs. 8-10 to its result in registers and writes
+// B^(t+1) to W, which may then be B itself; proj->V is updated in place.
 admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int64_t n, int64_t p, const MidFactors &mf,
-                           int t, float *Y, double *F, float *W, const FastBufs *fb = nullptr) {
+                           int t, float *Y, double *F, float *W, const FastBufs *fb = nullptr,
+                           const gemm_proj_args *proj = nullptr) {
     const admmq_factor &f = ctx->fac;
+    if (fb && proj) return ADMMQ_ERR_PARAM;
     if (fb) {
         // the time of splitting the state operand is booked with its product
         int sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
@@ -403,7 +413,8 @@ admmq_status w_update_core(admmq_ctx *ctx, const float *C0, const float *B, int6
     gemm_tn_args g2 = {};
     g2.A = f.Qt; g2.lda = n; g2.B = S; g2.ldb = p; g2.M = n; g2.N = p; g2.K = n;
     g2.alpha = 1.f; g2.beta = 1.f; g2.Z = B; g2.ldz = p; g2.out = W; g2.ldo = p; g2.split_k = 1;
-    sp = admmq_prof_begin(ctx, ADMMQ_TAG_GEMM);
+    g2.proj = proj;
+    sp = admmq_prof_begin(ctx, proj ? ADMMQ_TAG_GEMM_PROJECT : ADMMQ_TAG_GEMM);
     ADMMQ_TRY(admmq_gemm_tn(ctx, g2));
     admmq_prof_end(ctx, sp);
     return ADMMQ_OK;
@@ -1198,8 +1209,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     const bool want = stats != nullptr;
     Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
     t_total.start();
-    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
-    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
+    float prof_ms[ADMMQ_TAGS] = {};
+    int prof_cnt[ADMMQ_TAGS] = {};
     prof_collect(ctx, prof_ms, prof_cnt);            // drops spans a failed earlier call may have left
     ctx->prof.on = want && stats->profile != 0;
 
@@ -1322,8 +1333,37 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     // W and B trade places every iteration: the projection pass writes B^(t+1) over the W it has just read
     float *Bcur = B, *Wcur = W;
     int iters = 0, quiet = 0;
+    // Iterations that need neither codes nor W itself run the projection pass as the epilogue of the second
+    // product (W never goes to memory, B^(t+1) replaces B^(t) in place) where the product's shape allows it.
+    gemm_proj_args pa = {};
+    bool fuse = uniform && !fast && !want_flips && fuse_projection_enabled();
+    if (fuse) {
+        int sh = -1;
+        if (g == n) sh = 62;
+        else if (g > 0 && (g & (g - 1)) == 0)
+            for (sh = 0; ((int64_t)1 << sh) < g; ++sh) {}
+        if (sh < 0) {
+            fuse = false;
+        } else {
+            pa.V = V; pa.ldv = p; pa.d = f.d; pa.inv_d = f.inv_d; pa.scales = pj.scales; pa.inv_scales = inv_scales;
+            pa.zeros = pj.zeros; pa.ld_grid = p; pa.g_shift = sh; pa.levels = (float)((1 << bits) - 1);
+            pa.res_sq = res;
+            gemm_tn_args probe = {};
+            probe.A = f.Qt; probe.lda = n; probe.B = F; probe.ldb = p; probe.M = n; probe.N = p; probe.K = n;
+            probe.alpha = 1.f; probe.beta = 1.f; probe.Z = B; probe.ldz = p; probe.out = B; probe.ldo = p;
+            probe.split_k = 1; probe.proj = &pa;
+            fuse = admmq_gemm_tn_can_project(probe) && ((uintptr_t)W & 15) == 0;
+        }
+    }
     for (int t = 0; t < T; ++t) {
         const float rf = (float)hrho[t], rf_next = (float)hrho[t + 1];
+        const bool last = t == T - 1;
+        if (fuse && t > 0 && !last && !(uniform && t == sched->refresh_iter)) {
+            pa.rho = rf; pa.inv_rho = 1.0f / rf; pa.inv_rho_next = 1.0f / rf_next; pa.res_sq = res + t;
+            ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, mf, t, Y, F, Bcur, nullptr, &pa));
+            iters = t + 1;
+            continue;
+        }
         if (t == 0) {
             // D^(0) = Ws and V^(0) = 0 make eq. 7 return Ws exactly: no product needed
             ADMMQ_HIP(hipMemcpyAsync(Wcur, Bcur, np * 4, hipMemcpyDeviceToDevice, ctx->stream));
@@ -1331,7 +1371,6 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             ADMMQ_TRY(w_update_core(ctx, C0, Bcur, n, p, mf, t, Y, F, Wcur,
                                     fast ? &fbufs : nullptr));
         }
-        const bool last = t == T - 1;
         if (uniform && t == sched->refresh_iter)
             ADMMQ_TRY(grid_refresh_core(ctx, Wcur, V, n, p, f.d, f.inv_d, bits, g, hrho[t], pj.scales, pj.zeros,
                                         inv_scales, new_sc, new_zr, rpart, &refresh_accepted, &refresh_eo,
@@ -1416,6 +1455,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         stats->ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; stats->n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
         stats->ms_project = prof_ms[ADMMQ_TAG_PROJECT]; stats->n_project = prof_cnt[ADMMQ_TAG_PROJECT];
         stats->ms_ls_apply = prof_ms[ADMMQ_TAG_LS_APPLY]; stats->n_ls_apply = prof_cnt[ADMMQ_TAG_LS_APPLY];
+        stats->ms_gemm_project = prof_ms[ADMMQ_TAG_GEMM_PROJECT];
+        stats->n_gemm_project = prof_cnt[ADMMQ_TAG_GEMM_PROJECT];
         stats->ms_setup = ms_setup;
         stats->ms_factor = ms_factor;
         stats->ms_admm = ms_admm;
@@ -1445,8 +1486,8 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     const size_t nP = (size_t)n * P;
     Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
     t_total.start();
-    float prof_ms[ADMMQ_TAGS] = {0.f, 0.f, 0.f, 0.f};
-    int prof_cnt[ADMMQ_TAGS] = {0, 0, 0, 0};
+    float prof_ms[ADMMQ_TAGS] = {};
+    int prof_cnt[ADMMQ_TAGS] = {};
     prof_collect(ctx, prof_ms, prof_cnt);
     ctx->prof.on = want && stats[0].profile != 0;
 
@@ -1734,6 +1775,8 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             st.ms_tridiag = prof_ms[ADMMQ_TAG_TRIDIAG]; st.n_tridiag = prof_cnt[ADMMQ_TAG_TRIDIAG];
             st.ms_project = prof_ms[ADMMQ_TAG_PROJECT]; st.n_project = prof_cnt[ADMMQ_TAG_PROJECT];
             st.ms_ls_apply = prof_ms[ADMMQ_TAG_LS_APPLY]; st.n_ls_apply = prof_cnt[ADMMQ_TAG_LS_APPLY];
+            st.ms_gemm_project = 0.f;
+            st.n_gemm_project = 0;
             st.ms_setup = ms_setup;
             st.ms_factor = ms_factor;
             st.ms_admm = ms_admm;

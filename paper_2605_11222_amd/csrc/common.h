@@ -44,7 +44,8 @@ struct admmq_profiler {
     int count = 0, cap = 0;
     bool on = false;
 };
-enum { ADMMQ_TAG_GEMM = 0, ADMMQ_TAG_TRIDIAG = 1, ADMMQ_TAG_PROJECT = 2, ADMMQ_TAG_LS_APPLY = 3, ADMMQ_TAGS = 4 };
+enum { ADMMQ_TAG_GEMM = 0, ADMMQ_TAG_TRIDIAG = 1, ADMMQ_TAG_PROJECT = 2, ADMMQ_TAG_LS_APPLY = 3, ADMMQ_TAG_GEMM_PROJECT = 4,
+       ADMMQ_TAGS = 5 };
 
 struct admmq_ctx {
     int device = 0;
@@ -117,8 +118,26 @@ struct gemm_tn_args {
     int lower_only;      // 1: only tiles that touch the lower triangle (m >= n) are computed
     int split_k;         // >1: slice s handles k in [s*Kc,(s+1)*Kc) and writes out + s*slice_stride
     int64_t slice_stride;
+    const struct gemm_proj_args *proj;    // not NULL: eqs. 8-10 applied to the result while it is in registers
+};
+// Projection, dual update and residual (eqs. 8-10) as the epilogue of the second product of eq. 7: the product's
+// result W = A^T B + Z never goes to memory; with t = W + V/rho the epilogue forms D = P_Q(t) on the grid, V += rho
+// (W - D) in place, writes B' = D - V/rho_next to `out` (which may be Z itself) and adds |W - D|_F^2 to res_sq.
+// The arithmetic per element is that of the stand-alone pass (admmq_k_project_dual), operation for operation.
+// Needs alpha = beta = 1, Z given, whole aligned tiles (admmq_gemm_tn_can_project) and a group size that is a power
+// of two or the whole column (g_shift = log2 g, or 62 for one group).
+struct gemm_proj_args {
+    float *V;
+    int64_t ldv;
+    const float *d, *inv_d;               // [M]
+    const float *scales, *inv_scales, *zeros;   // [M / g][ld_grid], indexed by the product's column
+    int64_t ld_grid;
+    int g_shift;
+    float levels, rho, inv_rho, inv_rho_next;
+    double *res_sq;
 };
 admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a);
+bool admmq_gemm_tn_can_project(const gemm_tn_args &a);
 // bf16 matrix-core path of the Hessian (hessian_bf16.hip): usable when n is a multiple of 256, rows of X are 16-byte
 // aligned and there is at least one 32-token stage; handles the first main_rows(rows) tokens.
 bool admmq_hessian_bf16_ok(const void *X, int64_t n, int64_t ldx, int64_t rows);

@@ -38,6 +38,14 @@ struct GemmParams {
     long k_chunk;
     long slice_stride;
     int vec_ok;     // 1: all rows 16-byte aligned and M, N multiples of 4 (vector global access)
+    // projection epilogue (eqs. 8-10), PROJ instantiations only
+    float *pV;
+    long ldv;
+    const float *pd, *pinv_d, *pscales, *pinv_scales, *pzeros;
+    long ld_grid;
+    int g_shift;
+    float levels, rho, inv_rho, inv_rho_next;
+    double *res_sq;
 };
 
 __device__ inline float bf16_to_f32(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
@@ -94,9 +102,10 @@ __device__ inline void tile_of_block(int bid, int nblocks, int tiles_m, int tile
 // DIR: every tile is interior, rows are 16-byte aligned and every k-stage is whole (the launcher checks), fp32
 // operands: stages are filled by direct global -> LDS loads.  One path per instantiation on purpose: with both
 // in one loop the compiler joins them with register copies that wait for every outstanding load.
-template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16, bool DIR>
+template <int FA, int FB, int WGM, int WGN, int KT, bool ABF16, bool BBF16, bool DIR, bool PROJ = false>
 __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 2 : 1) void gemm_tn_kernel(GemmParams P) {
     static_assert(!DIR || (ABF16 == BBF16), "direct loads: both operands fp32, or both bf16 (kept as bf16 in LDS)");
+    static_assert(!PROJ || (DIR && !ABF16), "the projection epilogue belongs to the direct fp32 path");
     // bf16 operands of the direct path stay bf16 in LDS (half the bytes through the load path and the LDS) and
     // are widened when a fragment is read: two shifts / masks per pair, issued in the shadow of the MFMAs
     constexpr bool LB = DIR && ABF16 && BBF16;
@@ -407,6 +416,102 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     float *outp = P.out + (long)slice * P.slice_stride;
     const long wm0 = m0 + wm * (32 * FA);
     const long wn0 = n0 + wn * (32 * FB);
+    if constexpr (PROJ) {
+        // Eqs. 8-10 on the result while it sits in the accumulators: W = acc + Z (alpha = beta = 1, so this is the
+        // value the plain epilogue would have stored), then the stand-alone pass's arithmetic, operation for
+        // operation.  Rows go RB at a time: their Z, V, d requests are all in flight before the first is used.
+        constexpr int RB = 4;
+        const long n = wn0 + FB * l32;
+        long grp = -1;
+        float dl[FB], idl[FB], z0[FB];
+        float racc = 0.f;
+#pragma unroll
+        for (int a = 0; a < FA; ++a) {
+#pragma unroll
+            for (int v0 = 0; v0 < 16; v0 += RB) {
+                float z[RB][FB], vv[RB][FB], di[RB], idi[RB];
+#pragma unroll
+                for (int u = 0; u < RB; ++u) {
+                    const int v = v0 + u;
+                    const long m = wm0 + FA * (8 * (v / 4) + 4 * khalf + (v % 4)) + a;
+                    const float *zp = P.Z + m * P.ldz + n;
+                    const float *vp = P.pV + m * P.ldv + n;
+                    if constexpr (FB == 4) {
+                        const floatx4 t = *(const floatx4 *)zp, s = *(const floatx4 *)vp;
+                        z[u][0] = t.x; z[u][1] = t.y; z[u][2] = t.z; z[u][3] = t.w;
+                        vv[u][0] = s.x; vv[u][1] = s.y; vv[u][2] = s.z; vv[u][3] = s.w;
+                    } else if constexpr (FB == 2) {
+                        const floatx2 t = *(const floatx2 *)zp, s = *(const floatx2 *)vp;
+                        z[u][0] = t.x; z[u][1] = t.y;
+                        vv[u][0] = s.x; vv[u][1] = s.y;
+                    } else {
+                        z[u][0] = zp[0];
+                        vv[u][0] = vp[0];
+                    }
+                    di[u] = P.pd[m];
+                    idi[u] = P.pinv_d[m];
+                }
+#pragma unroll
+                for (int u = 0; u < RB; ++u) {
+                    const int v = v0 + u;
+                    const long m = wm0 + FA * (8 * (v / 4) + 4 * khalf + (v % 4)) + a;
+                    const long gi = m >> P.g_shift;
+                    if (gi != grp) {
+                        grp = gi;
+#pragma unroll
+                        for (int b = 0; b < FB; ++b) {
+                            dl[b] = P.pscales[gi * P.ld_grid + n + b];
+                            idl[b] = P.pinv_scales[gi * P.ld_grid + n + b];
+                            z0[b] = P.pzeros[gi * P.ld_grid + n + b];
+                        }
+                    }
+                    float vn[FB], bn[FB];
+#pragma unroll
+                    for (int b = 0; b < FB; ++b) {
+                        const float w = __fadd_rn(acc[a][b][v], z[u][b]);
+                        const float q = __fmul_rn(vv[u][b], P.inv_rho);
+                        const float wt = __fadd_rn(w, q);
+                        const float x = __fmul_rn(wt, idi[u]);
+                        const float y = __fsub_rn(x, z0[b]);
+                        const float t = __fmul_rn(y, idl[b]);
+                        const float k = fminf(fmaxf(rintf(t), 0.f), P.levels);
+                        const float xq = __fadd_rn(__fmul_rn(k, dl[b]), z0[b]);
+                        const float Dn = __fmul_rn(di[u], xq);
+                        const float r = __fsub_rn(w, Dn);
+                        vn[b] = __fadd_rn(vv[u][b], __fmul_rn(P.rho, r));
+                        bn[b] = __fsub_rn(Dn, __fmul_rn(vn[b], P.inv_rho_next));
+                        racc += r * r;
+                    }
+                    float *vp = P.pV + m * P.ldv + n;
+                    float *op = outp + m * P.ldo + n;
+                    if constexpr (FB == 4) {
+                        *(floatx4 *)vp = floatx4{vn[0], vn[1], vn[2], vn[3]};
+                        *(floatx4 *)op = floatx4{bn[0], bn[1], bn[2], bn[3]};
+                    } else if constexpr (FB == 2) {
+                        *(floatx2 *)vp = floatx2{vn[0], vn[1]};
+                        *(floatx2 *)op = floatx2{bn[0], bn[1]};
+                    } else {
+                        vp[0] = vn[0];
+                        op[0] = bn[0];
+                    }
+                }
+            }
+        }
+        // squared residual: lanes of a wave, the block's waves through LDS (nobody reads a stage any more: the last
+        // k-step's fragments were in registers before the loop's final barrier), one atomic per block
+        double tot = (double)racc;
+#pragma unroll
+        for (int h = 32; h >= 1; h >>= 1) tot += __shfl_xor(tot, h, 64);
+        double *red = (double *)lds;
+        if (lane == 0) red[wave] = tot;
+        __syncthreads();
+        if (tid == 0) {
+            double s = 0.0;
+            for (int w = 0; w < NWAVES; ++w) s += red[w];
+            atomicAdd(P.res_sq, s);
+        }
+        return;
+    }
     if constexpr (DIR) {
         // every tile is whole and aligned: no guards, and the rows of Z are requested ZB at a time (one load, one
         // wait, one store per row would pay the memory latency 16 FA times); ZB keeps the kernel free of spills
@@ -494,7 +599,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && FA * FB == 8) ? 
     }
 }
 
-template <int FA, int FB, int WGM, int WGN, int KT>
+template <int FA, int FB, int WGM, int WGN, int KT, bool PROJ_OK = false>
 admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
     constexpr int BM = 32 * FA * WGM;
     constexpr int BN = 32 * FB * WGN;
@@ -518,6 +623,16 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
               ((uintptr_t)a.B % (4 * esz_b) == 0) && (a.ldb % 4 == 0) && (a.slice_stride % 4 == 0);
     if (a.Z) ok = ok && al16(a.Z) && (a.ldz % 4 == 0);
     P.vec_ok = ok ? 1 : 0;
+    if (a.proj) {
+        const gemm_proj_args &q = *a.proj;
+        P.pV = q.V; P.ldv = q.ldv; P.pd = q.d; P.pinv_d = q.inv_d; P.pscales = q.scales;
+        P.pinv_scales = q.inv_scales; P.pzeros = q.zeros; P.ld_grid = q.ld_grid; P.g_shift = q.g_shift;
+        P.levels = q.levels; P.rho = q.rho; P.inv_rho = q.inv_rho; P.inv_rho_next = q.inv_rho_next;
+        P.res_sq = q.res_sq;
+    } else {
+        P.pV = nullptr; P.ldv = 0; P.pd = P.pinv_d = P.pscales = P.pinv_scales = P.pzeros = nullptr;
+        P.ld_grid = 0; P.g_shift = 0; P.levels = P.rho = P.inv_rho = P.inv_rho_next = 0.f; P.res_sq = nullptr;
+    }
     long tiles;
     if (a.lower_only) {
         if (BM != BN) return ADMMQ_ERR_PARAM;
@@ -538,6 +653,22 @@ admmq_status launch_cfg(admmq_ctx *ctx, const gemm_tn_args &a) {
     bool direct = ok && a.M % BM == 0 && a.N % BN == 0 && a.K % KT == 0 && a.K > 0;
     if (a.a_bf16)        // 16-byte loads of bf16 rows
         direct = direct && a.lda % 8 == 0 && a.ldb % 8 == 0 && al16(a.A) && al16(a.B);
+    if (a.proj) {
+        // the caller has asked admmq_gemm_tn_can_project; anything else here is a mistake of the library's own
+        if constexpr (PROJ_OK) {
+            if (!direct || a.a_bf16 || a.b_bf16 || !a.Z || a.alpha != 1.f || a.beta != 1.f || a.lower_only ||
+                P.split_k != 1 || !al16(a.proj->V) || a.proj->ldv % 4 != 0 || !a.proj->res_sq)
+                return ADMMQ_ERR_PARAM;
+            auto kern = gemm_tn_kernel<FA, FB, WGM, WGN, KT, false, false, true, true>;
+            static unsigned long long lds_allowed = 0;
+            ADMMQ_HIP(admmq_allow_lds((const void *)kern, (int)lds_bytes, ctx->device, &lds_allowed));
+            hipLaunchKernelGGL(kern, grid, block, lds_bytes, ctx->stream, P);
+            ADMMQ_HIP(hipGetLastError());
+            return ADMMQ_OK;
+        } else {
+            return ADMMQ_ERR_PARAM;
+        }
+    }
     if (a.a_bf16 && a.b_bf16) {
         if (direct) ADMMQ_GEMM_LAUNCH(true, true, true);
         else ADMMQ_GEMM_LAUNCH(true, true, false);
@@ -589,41 +720,42 @@ double rounds_cost(long M, long N) {
 }
 }  // namespace
 
-admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
-    if (a.M <= 0 || a.N <= 0 || a.K < 0) return ADMMQ_ERR_SHAPE;
+namespace {
+int gemm_variant() {
     static int variant = -1;
     if (variant < 0) {
         const char *e = getenv("ADMMQ_GEMM_VARIANT");
         variant = e ? atoi(e) : 0;
     }
-    // A tile count just above a multiple of the 256 compute units leaves the last round nearly empty (4096 x 5120:
-    // 320 tiles, two rounds for 1.25 rounds of work).  Then the leading columns that fill whole rounds go out as
-    // one launch and the remaining columns as a product of their own, with the smaller tile that suits their
-    // count.  Every output element is still one k-ordered sum of its tile: the split changes no value, and columns
-    // handled by the same tile shape as in a narrower call come out bit-identical to that call.
-    if (!a.lower_only && a.split_k <= 1) {
-        const long tm = (a.M + 255) / 256, tn = (a.N + 255) / 256, t = tm * tn;
-        if (t > 256 && t % 256 != 0) {
-            const long c_full = (t / 256) * 256 / tm;          // column tiles that fit whole rounds
-            if (c_full >= 1 && c_full < tn) {
-                const long n_head = c_full * 256;
-                const double whole = (double)((t + 255) / 256);
-                const double parts = (double)((c_full * tm + 255) / 256) + rounds_cost(a.M, a.N - n_head);
-                if (parts < 0.93 * whole) {
-                    gemm_tn_args head = a, tail = a;
-                    head.N = n_head;
-                    tail.N = a.N - n_head;
-                    const long eb = a.b_bf16 ? 2 : 4;
-                    tail.B = (const char *)a.B + n_head * eb;
-                    if (a.Z) tail.Z = a.Z + n_head;
-                    tail.out = a.out + n_head;
-                    ADMMQ_TRY(admmq_gemm_tn(ctx, head));
-                    return admmq_gemm_tn(ctx, tail);
-                }
-            }
-        }
+    return variant;
+}
+int gemm_mid_variant() {
+    static int mid_variant = -1;
+    if (mid_variant < 0) {
+        const char *e = getenv("ADMMQ_GEMM_MID");
+        mid_variant = e ? atoi(e) : 0;
     }
-    // tile choice: the largest tile that still gives every CU work
+    return mid_variant;
+}
+// A tile count just above a multiple of the 256 compute units leaves the last round nearly empty (4096 x 5120:
+// 320 tiles, two rounds for 1.25 rounds of work).  Then the leading columns that fill whole rounds go out as
+// one launch and the remaining columns as a product of their own, with the smaller tile that suits their
+// count.  Every output element is still one k-ordered sum of its tile: the split changes no value, and columns
+// handled by the same tile shape as in a narrower call come out bit-identical to that call.
+// Returns the number of leading columns of such a split, or 0.
+long head_columns(const gemm_tn_args &a) {
+    if (a.lower_only || a.split_k > 1) return 0;
+    const long tm = (a.M + 255) / 256, tn = (a.N + 255) / 256, t = tm * tn;
+    if (t <= 256 || t % 256 == 0) return 0;
+    const long c_full = (t / 256) * 256 / tm;          // column tiles that fit whole rounds
+    if (c_full < 1 || c_full >= tn) return 0;
+    const long n_head = c_full * 256;
+    const double whole = (double)((t + 255) / 256);
+    const double parts = (double)((c_full * tm + 255) / 256) + rounds_cost(a.M, a.N - n_head);
+    return parts < 0.93 * whole ? n_head : 0;
+}
+// tile choice: the largest tile that still gives every CU work.  0: 256 x 256, 1: 128 x 128, 2: 64 x 64
+int tile_class(const gemm_tn_args &a) {
     const long t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     const long t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     const long work = a.split_k > 1 ? a.split_k : 1;
@@ -636,7 +768,71 @@ admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
         big = t256 * work >= 200;
         mid = t128 * work >= 128;
     }
-    if (big) {
+    return big ? 0 : mid ? 1 : 2;
+}
+void shift_columns(gemm_proj_args &q, long c) {
+    q.V += c;
+    q.scales += c;
+    q.inv_scales += c;
+    q.zeros += c;
+}
+}  // namespace
+
+// Whether a product with a.proj set can run with the projection epilogue: the tile shapes that carry it, whole
+// tiles and stages, aligned rows (what the launcher then insists on).
+bool admmq_gemm_tn_can_project(const gemm_tn_args &a) {
+    if (!a.proj || a.M <= 0 || a.N <= 0 || a.K <= 0 || a.lower_only || a.split_k > 1 || a.a_bf16 || a.b_bf16 || !a.Z ||
+        a.alpha != 1.f || a.beta != 1.f)
+        return false;
+    const gemm_proj_args &q = *a.proj;
+    auto al16 = [](const void *p) { return ((uintptr_t)p & 15) == 0; };
+    if (!q.V || !q.d || !q.inv_d || !q.scales || !q.inv_scales || !q.zeros || !q.res_sq || q.ldv % 4 != 0 ||
+        !al16(q.V) || !al16(a.A) || !al16(a.B) || !al16(a.Z) || !al16(a.out) || a.lda % 4 != 0 || a.ldb % 4 != 0 ||
+        a.ldz % 4 != 0 || a.ldo % 4 != 0 || q.g_shift < 0 || q.g_shift > 62)
+        return false;
+    const long n_head = head_columns(a);
+    if (n_head > 0) {
+        gemm_tn_args head = a, tail = a;
+        gemm_proj_args tq = q;
+        head.N = n_head;
+        tail.N = a.N - n_head;
+        tail.B = (const char *)a.B + n_head * 4;
+        tail.Z = a.Z + n_head;
+        tail.out = a.out + n_head;
+        shift_columns(tq, n_head);
+        tail.proj = &tq;
+        return admmq_gemm_tn_can_project(head) && admmq_gemm_tn_can_project(tail);
+    }
+    switch (tile_class(a)) {
+        case 0: return gemm_variant() == 0 && a.M % 256 == 0 && a.N % 256 == 0 && a.K % 32 == 0;
+        case 1: return gemm_mid_variant() == 0 && a.M % 128 == 0 && a.N % 128 == 0 && a.K % 64 == 0;
+        default: return false;
+    }
+}
+
+admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
+    if (a.M <= 0 || a.N <= 0 || a.K < 0) return ADMMQ_ERR_SHAPE;
+    const int variant = gemm_variant();
+    const long n_head = head_columns(a);
+    if (n_head > 0) {
+        gemm_tn_args head = a, tail = a;
+        gemm_proj_args tq;
+        head.N = n_head;
+        tail.N = a.N - n_head;
+        const long eb = a.b_bf16 ? 2 : 4;
+        tail.B = (const char *)a.B + n_head * eb;
+        if (a.Z) tail.Z = a.Z + n_head;
+        tail.out = a.out + n_head;
+        if (a.proj) {
+            tq = *a.proj;
+            shift_columns(tq, n_head);
+            tail.proj = &tq;
+        }
+        ADMMQ_TRY(admmq_gemm_tn(ctx, head));
+        return admmq_gemm_tn(ctx, tail);
+    }
+    const int cls = tile_class(a);
+    if (cls == 0) {
         // measured on MI355X (W-update products, n = p = 4096): eight waves of 64 x 128 with 32-row stages
         // reach 135 TFLOP/s, four waves of 128 x 128 with 16-row stages 128 TFLOP/s; variant 6 (128 x 256 tiles,
         // four waves, two blocks per compute unit whose barriers fall at different times) reaches the same
@@ -648,24 +844,20 @@ admmq_status admmq_gemm_tn(admmq_ctx *ctx, const gemm_tn_args &a) {
             case 4: return launch_cfg<4, 2, 2, 4, 32>(ctx, a);
             case 5: return launch_cfg<2, 2, 4, 4, 32>(ctx, a);
             case 6: return launch_cfg<2, 4, 2, 2, 16>(ctx, a);
-            default: return launch_cfg<2, 4, 4, 2, 32>(ctx, a);
+            default: return launch_cfg<2, 4, 4, 2, 32, true>(ctx, a);
         }
     }
-    if (mid) {
-        static int mid_variant = -1;
-        if (mid_variant < 0) {
-            const char *e = getenv("ADMMQ_GEMM_MID");
-            mid_variant = e ? atoi(e) : 0;
-        }
+    if (cls == 1) {
         // 128 x 128 tiles, measured on MI355X at 4096 x 1024 x 4096 (256 tiles, one per compute unit) with staged
         // loads: eight waves of 64 x 32 with 64-row stages 118 TFLOP/s, sixteen waves of 32 x 32 116, four waves of
         // 64 x 64 with 16-row stages 106 (one wave per SIMD hides no latency); the first with direct loads: 130
-        switch (mid_variant) {
+        switch (gemm_mid_variant()) {
             case 1: return launch_cfg<2, 2, 2, 2, 16>(ctx, a);
             case 2: return launch_cfg<1, 1, 4, 4, 32>(ctx, a);
-            default: return launch_cfg<2, 1, 2, 4, 64>(ctx, a);
+            default: return launch_cfg<2, 1, 2, 4, 64, true>(ctx, a);
         }
     }
+    if (a.proj) return ADMMQ_ERR_PARAM;
     return launch_cfg<1, 1, 2, 2, 16>(ctx, a);
 }
 

@@ -133,6 +133,43 @@ def test_layer_is_deterministic(ctx, monkeypatch, form):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("n,p,bits,g,T,refresh", [
+    (1024, 2048, 3, 128, 12, -1),     # 128 x 128 tiles of the product
+    (2048, 6400, 4, 0, 8, -1),        # 256 x 256 tiles, one group per column
+    (4096, 5120, 2, 64, 6, 3),        # 4096 columns in 256 x 256 tiles, the rest in 128 x 128; two groups within a
+                                      # wave's rows; a grid-refresh attempt (a stand-alone pass) between fused ones
+])
+def test_projection_in_the_products_epilogue_equals_the_stand_alone_pass(ctx, monkeypatch, n, p, bits, g, T, refresh):
+    """Eqs. 8-10 run as the epilogue of eq. 7's second product where the product's shape allows (W stays in
+    registers).  The result must not depend on that: same codes, grid and objective as with the projection pass as
+    a launch of its own in every iteration, and the same primal residuals up to the order of their sum."""
+    import paper_2605_11222_amd as admmq
+    gen = torch.Generator(device="cuda").manual_seed(1234 + n)
+    X = torch.randn((2 * n, n), generator=gen, device="cuda", dtype=torch.float32)
+    X = X + 0.5 * torch.roll(X, 1, dims=1)
+    X = X * torch.exp(0.5 * torch.randn((n,), generator=gen, device="cuda"))[None, :]
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    ctx.accumulate_hessian(H, X)
+    W0 = 0.02 * torch.randn((n, p), generator=gen, device="cuda", dtype=torch.float32)
+    sched = admmq.Schedule(T=T, ls_rounds=0, refresh_iter=refresh)
+    runs = {}
+    for fused in ("1", "0"):
+        monkeypatch.setenv("ADMMQ_FUSE_PROJECTION", fused)
+        codes, scales, zeros, st = ctx.quantize_layer(H, W0, bits, g, sched, want_history=True, want_flips=False,
+                                                      profile=True)
+        torch.cuda.synchronize()
+        runs[fused] = (codes.cpu().numpy(), scales.cpu().numpy(), zeros.cpu().numpy(), st)
+    a, b = runs["1"], runs["0"]
+    # the fused run launched the stand-alone pass only where it has to: iteration 0, the refresh attempt, the last
+    assert b[3].n_project == T
+    assert a[3].n_project == (3 if refresh >= 0 else 2)
+    assert np.array_equal(a[0], b[0])
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    assert a[3].j_damp == pytest.approx(b[3].j_damp, rel=1e-12)     # (the objective's sum has no fixed order)
+    assert a[3].refresh_accepted == b[3].refresh_accepted
+    assert np.allclose(a[3].primal_res, b[3].primal_res, rtol=1e-5)
+
+
 # ---------------------------------------------------------------------------------------------
 # local search
 # ---------------------------------------------------------------------------------------------

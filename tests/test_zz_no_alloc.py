@@ -2,6 +2,8 @@
 fixed array inside the library's device image) against admmq_project_dual (reciprocals in the context's arena) on
 the same inputs: codes, V and B bit for bit, the residual to rounding of its block sums.  Two calls in a row on the
 one array, the second on a smaller input, so stale contents of the first would show."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -40,11 +42,14 @@ def test_project_dual_noalloc_matches_project_dual_twice_in_a_row():
             codes = torch.full((n, p), 255, dtype=torch.uint8, device=dev)
             B = torch.full((n, p), float("nan"), dtype=torch.float32, device=dev)
             res = torch.full((1,), float("nan"), dtype=torch.float64, device=dev)
+            # (tensors that earlier tests left in reference cycles are freed now, not somewhere inside the call;
+            # a collection during the call can still only lower the figure, an allocation would raise it)
+            gc.collect()
             torch.cuda.synchronize()
             before = torch.cuda.memory_allocated()
             ctx.project_dual_noalloc(Wd, V_new, dd, bits, g, scales, zeros, rho, rho_next, codes, B, res)
             torch.cuda.synchronize()
-            assert torch.cuda.memory_allocated() == before
+            assert torch.cuda.memory_allocated() <= before
             assert torch.equal(codes, codes_ref)
             assert torch.equal(V_new, V_ref)
             assert torch.equal(B, B_ref)
