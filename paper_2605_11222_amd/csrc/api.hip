@@ -51,7 +51,10 @@ admmq_status admmq_k_ls_group(admmq_ctx *ctx, int pairs_per_thread, const float 
                               const int32_t *pairs, int npairs, int cnt, unsigned seq0, int group_seq,
                               unsigned long long *xch, unsigned *fin, int *commit, int *abort_word,
                               long long spin_ticks, int32_t *pend_idx, float *pend_d, int *dev_moves,
-                              double *dev_drop);
+                              double *dev_drop, const float *couple);
+admmq_status admmq_k_ls_couple(admmq_ctx *ctx, const float *H, float lambda, int64_t n, const int32_t *pairs,
+                               int npairs, int batches, float *X);
+size_t admmq_ls_couple_floats(int batches);
 admmq_status admmq_k_ls_totals(admmq_ctx *ctx, const float *partial, int chunks, int npairs, float *totals);
 admmq_status admmq_k_dual_grid_init(admmq_ctx *ctx, const float *W0, int64_t n, int64_t p, int64_t ldw, int bits,
                                     int64_t g, const uint8_t *flags, float *scales, float *zeros);
@@ -185,9 +188,13 @@ size_t admm_transient_bytes(int64_t n, int64_t p, int32_t T) {
     return 6 * admmq_align_up(np * 4) + admmq_align_up((np + (size_t)p) * 8) + mid_factor_bytes(n, T) +
            4 * admmq_align_up((size_t)T * 8) + 65536;
 }
+// batches whose coupling table (H' between the candidates of consecutive batches) is formed in one launch
+constexpr int LS_COUPLE_SPAN = 1024;
 size_t ls_transient_bytes(int64_t n, int64_t p, int64_t total_pairs, int pairs_per_batch) {
     const size_t np = (size_t)n * (size_t)p;
-    return 2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
+    const int64_t nb = pairs_per_batch > 0 ? total_pairs / pairs_per_batch : 0;
+    return admmq_align_up(admmq_ls_couple_floats((int)(nb < LS_COUPLE_SPAN ? nb : LS_COUPLE_SPAN)) * 4) +
+           2 * admmq_align_up(np * 4) + admmq_align_up((size_t)total_pairs * 8) +
            2 * admmq_align_up((size_t)pairs_per_batch * admmq_ls_chunks(p) * 4) +
            admmq_align_up((size_t)2 * admmq_ls_defer() * p * 4) + admmq_align_up((size_t)pairs_per_batch * 4) +
            2 * admmq_align_up((size_t)pairs_per_batch * p) + admmq_align_up((size_t)2 * admmq_ls_defer() * n * 4) +
@@ -535,7 +542,10 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
     long long spin_ticks = 0;
     unsigned long long *xch = nullptr;
     unsigned *fin = nullptr;
+    float *couple = nullptr;
+    const int span = plan.batches < LS_COUPLE_SPAN ? plan.batches : LS_COUPLE_SPAN;
     if (grouped) {
+        ADMMQ_TRY(take(ctx, couple, admmq_ls_couple_floats(span)));
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, ctx->device) != hipSuccess || khz <= 0) {
             (void)hipGetLastError();
@@ -613,9 +623,15 @@ admmq_status local_search_core(admmq_ctx *ctx, const float *H, double lambda, co
             for (int gb = 0; gb < plan.batches; gb += K) {
                 const int cnt = plan.batches - gb < K ? plan.batches - gb : K;
                 const unsigned seq0 = 1u + (unsigned)((size_t)r * plan.batches + gb);
+                // (LS_COUPLE_SPAN is a multiple of K: a group never straddles two tables)
+                const int span0 = gb / LS_COUPLE_SPAN * LS_COUPLE_SPAN;
+                if (gb == span0)
+                    ADMMQ_TRY(admmq_k_ls_couple(ctx, H, (float)lambda, n, batch_pairs(r, span0), plan.pairs,
+                                                plan.batches - span0 < span ? plan.batches - span0 : span, couple));
                 ADMMQ_TRY(admmq_k_ls_group(ctx, group_pp, H, (float)lambda, G, codes, n, p, bits, g, scales, batch_pairs(r, gb),
                                            plan.pairs, cnt, seq0, groups_launched, xch, fin, dev_commit, dev_abort,
-                                           spin_ticks, pend_idx, pend_d, dev_moves, scal));
+                                           spin_ticks, pend_idx, pend_d, dev_moves, scal,
+                                           couple + (size_t)(gb - span0) * admmq_ls_couple_floats(2)));
                 ++groups_launched;
                 ADMMQ_TRY(admmq_k_ls_flush(ctx, H, (float)lambda, G, codes, n, p, pend_idx, pend_d, cnt, dev_commit,
                                            groups_launched));

@@ -143,6 +143,42 @@ __device__ inline void wave_best(float &t, int &i) {
     better(t, i, __uint_as_float(row_ror<1>(__float_as_uint(t))), (int)row_ror<1>((unsigned)i));
 }
 
+// The same choice from one 64-bit key per lane: a positive total's bit pattern orders like the total, and below it
+// 2^32 - 1 - slot makes the lower slot the larger key; 0 = no candidate.  One compare and two selects per folding
+// step instead of the half dozen of `better` (the group kernel's sixteen waves each run this once per batch).
+__device__ inline unsigned long long best_key(float t, int i) {
+    return (i >= 0 && t > 0.f) ? (((unsigned long long)__float_as_uint(t) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)i)) : 0ull;
+}
+__device__ inline unsigned long long wave_max_key(unsigned long long k) {
+    unsigned lo = (unsigned)k, hi = (unsigned)(k >> 32);
+    auto fold = [&](unsigned olo, unsigned ohi) {
+        const unsigned long long o = ((unsigned long long)ohi << 32) | olo, m = ((unsigned long long)hi << 32) | lo;
+        if (o > m) {
+            lo = olo;
+            hi = ohi;
+        }
+    };
+    {
+        const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        lo = a[0];
+        hi = b[0];
+        fold(a[1], b[1]);
+    }
+    {
+        const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        lo = a[0];
+        hi = b[0];
+        fold(a[1], b[1]);
+    }
+    fold(row_ror<8>(lo), row_ror<8>(hi));
+    fold(row_ror<4>(lo), row_ror<4>(hi));
+    fold(row_ror<2>(lo), row_ror<2>(hi));
+    fold(row_ror<1>(lo), row_ror<1>(hi));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 // One step of the search, grid (chunks, npairs), block 256, one column per thread:
 //   plan     (when a previous batch exists): every block adds that batch's chunk partials in a fixed order and
 //            finds its winner (largest total, lowest slot on ties) - the same winner in every block.  The winner's
@@ -445,6 +481,7 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
 constexpr int LSG_TILE = 256;                          // columns per block
 constexpr int LSG_PB_MAX = 8;                          // candidate pairs per block: 4 PP, PP = pairs per thread (1 or 2)
 constexpr int LSG_MAX_CHUNKS = 32;
+static_assert(LS_K == 16, "the group kernel's thread maps take sixteen slots per pair");
 
 struct LsGroupArgs {
     const float *H;
@@ -459,7 +496,11 @@ struct LsGroupArgs {
     int npairs, cnt;
     unsigned seq0;                  // sequence number of the group's first batch (>= 1, unique within the call)
     int group_seq;                  // how many groups must have been committed before this one
-    unsigned long long *xch;        // [2][LS_FAST_PAIRS][chunks]: (sequence number << 32) | float bits
+    unsigned long long *xch;        // [2][LS_FAST_PAIRS][chunks]: (sequence number << 32) | float bits, then
+                                    // [2][chunks][LS_FAST_PAIRS][4][8]: (sequence number << 32) | the chosen sign
+                                    // combinations of 8 columns (3 bits each: bit 0 = a move, bits 1-2 = which)
+    const float *couple;            // [cnt - 1][LS_FAST_PAIRS][LS_FAST_PAIRS][4]: H' between the rows of pair a of
+                                    // batch s + 1 and the rows of pair w of batch s (ls_couple_kernel)
     unsigned *fin;                  // [blocks]: group_seq + 1 once a block is through
     int *commit;                    // groups committed so far
     int *abort_word;
@@ -481,11 +522,10 @@ struct LsGroupLds {
     float e_own[LSG_PB_MAX][4];                   // H' between the own pairs and the rows of the pair that has just won
     int pairs_l[LS_K][LS_FAST_PAIRS][2];          //  8 KB: the group's batches
     float coef_own[LSG_PB_MAX][LS_K][4];          // H' between the own pairs and the rows of the applied slots
-    float coef_win[LS_K][4];                      // the same for the pair that has just won
     int which_own[LSG_PB_MAX][LS_K];              // which rows of a slot are rows of the pair (4 bits)
-    int which_win[LS_K];
     int prow[LS_K][2];                            // rows of the applied pairs, -1 = none
     float wsum[LSG_PB_MAX][4];
+    unsigned combos[LS_FAST_PAIRS * 32];          //  8 KB: every candidate's sign combinations at my columns
     int bad;                                      // set by a thread whose wait ran out
 };
 
@@ -509,15 +549,20 @@ struct LsCell {
     int k1, k2;
 };
 
-__device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int r2, long j) {
+__device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int r2, long j, bool one_group,
+                                    float sc_col) {
     const long i1 = r1, i2 = r2;
     const int g = (int)a.g;               // (rows and group size fit 32 bits: a 64-bit division per load would cost more
     c.g1 = a.G[i1 * a.p + j];             //  than the rest of the evaluation)
     c.g2 = a.G[i2 * a.p + j];
     c.k1 = a.codes[i1 * a.p + j];
     c.k2 = a.codes[i2 * a.p + j];
-    c.sc1 = a.scales[(long)(r1 / g) * a.p + j];
-    c.sc2 = a.scales[(long)(r2 / g) * a.p + j];
+    if (one_group) {
+        c.sc1 = c.sc2 = sc_col;
+    } else {
+        c.sc1 = a.scales[(long)(r1 / g) * a.p + j];
+        c.sc2 = a.scales[(long)(r2 / g) * a.p + j];
+    }
     c.h11 = a.H[i1 * a.n + i1] + a.lambda;
     c.h22 = a.H[i2 * a.n + i2] + a.lambda;
     c.h12 = a.H[i1 * a.n + i2];
@@ -528,9 +573,13 @@ __device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int
 __device__ inline void ls_cell_apply(LsCell &c, const float *co, int wh, float d1, float d2) {
     c.g1 -= co[0] * d1 + co[1] * d2;
     c.g2 -= co[2] * d1 + co[3] * d2;
-    const int s1 = step_sign(d1), s2 = step_sign(d2);        // (no branch: the slots of a loop can then overlap)
-    c.k1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
-    c.k2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
+    // (a slot's rows are rows of this pair once in a few thousand slots, and for all lanes at once: a branch on
+    // the scalar unit instead of a dozen vector instructions per slot)
+    if (__builtin_amdgcn_readfirstlane(wh) != 0) {
+        const int s1 = step_sign(d1), s2 = step_sign(d2);
+        c.k1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
+        c.k2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
+    }
 }
 
 __device__ inline int ls_which(long pa, long pb, long i1, long i2) {
@@ -571,12 +620,47 @@ __device__ inline void ls_apply_slots(LsCell *cells, const bool *on, const float
     }
 }
 
+// The coupling table of a run of batches: for every batch b of the run but the last,
+//   X[b][a][w][k] = H'[row (k >> 1) of pair a of batch b + 1][row (k & 1) of pair w of batch b]
+// (0 where a pair does not exist or is not a pair of two different rows of the matrix).  Whichever candidate of
+// batch b wins, the entries that carry its move into the gradient rows of the next batch's candidates are then
+// already there, 1 KB per next-batch pair, and no look-up of H' stands between a winner and the next evaluation.
+// grid = batches of the run - 1, block 1024; pairs: [batches][npairs][2].
+__global__ __launch_bounds__(1024) void ls_couple_kernel(const float *__restrict__ H, float lambda, long n,
+                                                         const int32_t *__restrict__ pairs, int npairs,
+                                                         float *__restrict__ X) {
+    __shared__ int rows[2][LS_FAST_PAIRS][2];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    if (tid < 4 * LS_FAST_PAIRS) {
+        const int which = tid / (2 * LS_FAST_PAIRS), r = tid - which * 2 * LS_FAST_PAIRS, q = r >> 1;
+        int v = -1;
+        if (q < npairs) {
+            const int32_t *pr = pairs + ((size_t)(b + which) * npairs + q) * 2;
+            const int r1 = pr[0], r2 = pr[1];
+            if (!(r1 < 0 || r2 < 0 || r1 >= n || r2 >= n || r1 == r2)) v = pr[r & 1];
+        }
+        rows[which][q][r & 1] = v;
+    }
+    __syncthreads();
+    float *out = X + (size_t)b * (LS_FAST_PAIRS * LS_FAST_PAIRS * 4);
+    for (int e = tid; e < LS_FAST_PAIRS * LS_FAST_PAIRS * 4; e += 1024) {
+        const int a = e >> 8, w = (e >> 2) & (LS_FAST_PAIRS - 1), k = e & 3;
+        const long row = rows[1][a][k >> 1], cr = rows[0][w][k & 1];
+        float v = 0.f;
+        if (row >= 0 && cr >= 0) v = H[row * n + cr] + (row == cr ? lambda : 0.f);
+        out[e] = v;
+    }
+}
+
 template <int PP>
 __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     extern __shared__ __align__(16) unsigned char ls_group_lds[];
     LsGroupLds &L = *reinterpret_cast<LsGroupLds *>(ls_group_lds);
     if (*a.commit != a.group_seq) return;      // an earlier group did not complete; the host takes over from there
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    // (the wave's index, the rows of its candidate pairs and everything derived from them are the same in all 64
+    // lanes; taken through readfirstlane they live in scalar registers, and the address arithmetic on them - most
+    // of the integer work of a step - goes to the scalar unit, which the block's sixteen waves do not queue for)
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int pl = wv >> 2, sub = wv & 3;                      // pair within the block, 64-column strip
     const int chunks = gridDim.x;
     const long n = a.n, p = a.p;
@@ -596,8 +680,6 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     for (int e = tid; e < LS_K * 2 * LSG_TILE; e += 1024) (&L.pd[0][0][0])[e] = 0.f;
     for (int e = tid; e < LSG_PB_MAX * LS_K * 4; e += 1024) (&L.coef_own[0][0][0])[e] = 0.f;
     for (int e = tid; e < LSG_PB_MAX * LS_K; e += 1024) (&L.which_own[0][0])[e] = 0;
-    if (tid < LS_K * 4) (&L.coef_win[0][0])[tid] = 0.f;
-    if (tid < LS_K) L.which_win[tid] = 0;
     if (tid < 2 * LS_K) (&L.prow[0][0])[tid] = -1;
     if (tid == 0) L.bad = 0;
     // A barrier that orders LDS traffic only.  __syncthreads() also waits for every global load and store the wave
@@ -613,6 +695,9 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     }
     __syncthreads();
 
+    // one grid per column: the step of every row is the column's, known from the start
+    const bool one_group = a.g >= n;
+    const float sc_col = (one_group && in) ? a.scales[j] : 0.f;
     LsCell own[PP], own_n[PP];             // the own pairs of the batch in hand, and of the next one (on their way)
     int i1[PP], i2[PP], i1n[PP], i2n[PP];
     bool has[PP], hasn[PP];
@@ -622,12 +707,15 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             const int q = q_base + 4 * i + pl;
             r1[i] = r2[i] = -1;
             if (q < npairs) {
-                r1[i] = L.pairs_l[s][q][0];
-                r2[i] = L.pairs_l[s][q][1];
+                r1[i] = __builtin_amdgcn_readfirstlane(L.pairs_l[s][q][0]);
+                r2[i] = __builtin_amdgcn_readfirstlane(L.pairs_l[s][q][1]);
             }
-            ok[i] = !(r1[i] < 0 || r2[i] < 0 || r1[i] >= n || r2[i] >= n || r1[i] == r2[i]) && in;
+            const bool pair_ok = !(r1[i] < 0 || r2[i] < 0 || r1[i] >= n || r2[i] >= n || r1[i] == r2[i]);
+            ok[i] = pair_ok && in;
             cell[i] = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
-            if (ok[i]) ls_cell_load(cell[i], a, r1[i], r2[i], j);
+            if (pair_ok) {
+                if (in) ls_cell_load(cell[i], a, r1[i], r2[i], j, one_group, sc_col);
+            }
         }
     };
     const float (*coef_rows[PP])[4];
@@ -648,36 +736,55 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             // ---- the winner of batch s-1: everybody's sums, added in chunk order ---------------------------------------
             const unsigned seq = a.seq0 + (unsigned)(s - 1);
             const unsigned long long *tab = a.xch + (size_t)(seq & 1u) * LS_FAST_PAIRS * chunks;
+            const unsigned long long *cmb = a.xch + (size_t)2 * LS_FAST_PAIRS * chunks +
+                                            ((size_t)(seq & 1u) * chunks + blockIdx.x) * (LS_FAST_PAIRS * 32);
+            // H' between the own pairs of batch s and every candidate of batch s-1 (a table of an earlier launch, so
+            // an ordinary load): requested before the wait, there by the time the winner is known
+            float xv[PP];
+#pragma unroll
+            for (int i = 0; i < PP; ++i) {
+                xv[i] = 0.f;
+                const int q = q_base + 4 * i + (tid >> 8);
+                if (s < a.cnt && q < npairs)
+                    xv[i] = a.couple[((size_t)(s - 1) * LS_FAST_PAIRS + q) * (LS_FAST_PAIRS * 4) + (tid & 255)];
+            }
             bool bad = a.spin_ticks < 0;          // a negative bound makes every block leave at its first wait
             {
                 // sixteen lanes to a candidate: lane c of the row reads the sums of the chunks c and c + 16; chunks
-                // beyond the last count as zero (so does a candidate beyond the last, whose total stays zero)
+                // beyond the last count as zero (so does a candidate beyond the last, whose total stays zero).  Every
+                // thread also fetches two words of the candidates' sign combinations at this block's columns.
                 const int q = tid >> 4, c0 = tid & 15;
-                float v[2] = {0.f, 0.f};
-                if (q < npairs && !bad) {
+                const unsigned long long *src[4] = {tab + (size_t)q * chunks + c0, tab + (size_t)q * chunks + c0 + 16,
+                                                    cmb + tid, cmb + tid + 1024};
+                const bool need[4] = {q < npairs && c0 < chunks, q < npairs && c0 + 16 < chunks, (tid >> 5) < npairs,
+                                      ((tid + 1024) >> 5) < npairs};
+                unsigned long long w[4] = {0ull, 0ull, 0ull, 0ull};
+                if (!bad) {
                     const long long t0 = (long long)wall_clock64();
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int c = c0 + 16 * h;
-                        if (c < chunks && !bad) {
-                            const unsigned long long *src = tab + (size_t)q * chunks + c;
-                            unsigned it = 0;
-                            unsigned long long w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            while ((unsigned)(w >> 32) != seq) {
-                                if ((it++ & 7u) == 0u && ls_wait_expired(t0, a.spin_ticks, a.abort_word)) {
-                                    bad = true;
-                                    break;
-                                }
-                                w = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int h = 0; h < 4; ++h)
+                        if (need[h]) w[h] = __hip_atomic_load(src[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        if (!need[h] || bad) continue;
+                        unsigned it = 0;
+                        while ((unsigned)(w[h] >> 32) != seq) {
+                            if ((it++ & 7u) == 0u && ls_wait_expired(t0, a.spin_ticks, a.abort_word)) {
+                                bad = true;
+                                break;
                             }
-                            v[h] = __uint_as_float((unsigned)w);
+                            w[h] = __hip_atomic_load(src[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
                 }
+                const float v0 = need[0] && !bad ? __uint_as_float((unsigned)w[0]) : 0.f;
+                const float v1 = need[1] && !bad ? __uint_as_float((unsigned)w[1]) : 0.f;
                 // 0 + chunk 0 + chunk 1 + ... in index order, as the launch-per-batch kernel adds them
-                float tot = row_ordered_sum(0.f, v[0], true);
-                if (chunks > 16) tot = row_ordered_sum(tot, v[1], true);
+                float tot = row_ordered_sum(0.f, v0, true);
+                if (chunks > 16) tot = row_ordered_sum(tot, v1, true);
                 if (c0 == 0) L.tot[q] = tot;
+                L.combos[tid] = need[2] ? (unsigned)w[2] : 0u;
+                L.combos[tid + 1024] = need[3] ? (unsigned)w[3] : 0u;
             }
             if (bad) L.bad = 1;
             lds_barrier();
@@ -689,20 +796,14 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             int win;
             float win_tot;
             {
-                float best = 0.f;
-                int bidx = -1;
-                if (lane < npairs) {
-                    const float t = L.tot[lane];
-                    if (t > 0.f) {
-                        best = t;
-                        bidx = lane;
-                    }
-                }
-                wave_best(best, bidx);
-                win = bidx;
-                win_tot = best;
+                const unsigned long long key = wave_max_key(lane < npairs ? best_key(L.tot[lane], lane) : 0ull);
+                const unsigned klo = __builtin_amdgcn_readfirstlane((unsigned)key);
+                const unsigned khi = __builtin_amdgcn_readfirstlane((unsigned)(key >> 32));
+                win = (klo | khi) ? (int)(0xFFFFFFFFu - klo) : -1;
+                win_tot = __uint_as_float(khi);
             }
-            const int wi1 = win >= 0 ? L.pairs_l[s - 1][win][0] : -1, wi2 = win >= 0 ? L.pairs_l[s - 1][win][1] : -1;
+            const int wi1 = win >= 0 ? __builtin_amdgcn_readfirstlane(L.pairs_l[s - 1][win][0]) : -1;
+            const int wi2 = win >= 0 ? __builtin_amdgcn_readfirstlane(L.pairs_l[s - 1][win][1]) : -1;
             if (tid == 0) {
                 L.prow[s - 1][0] = wi1;
                 L.prow[s - 1][1] = wi2;
@@ -711,36 +812,22 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                     drop_l += (double)win_tot;
                 }
             }
-            // ---- requests, oldest first: what the winner's evaluation and the own pairs of batch s need of it (used
-            // right below), then everything for batch s+1 (used after batch s has been evaluated and published) --------
-            LsCell wc = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
-            float dep = 0.f;
-            if (win >= 0) {
-                // the winner's evaluation once more, from the same inputs in the same order: slots 0 .. s-3 as applied
-                // slots (H' read as row of the slot), slot s-2 as the move that had just been made (row of the pair)
-                if (pl == 0 && in) ls_cell_load(wc, a, wi1, wi2, j);
-                if (tid < 4 * (s - 1)) {
-                    const int k = tid >> 2, w = tid & 3;
-                    const long src = L.prow[k][w & 1], row = (w & 2) ? wi2 : wi1;
-                    if (src >= 0)
-                        dep = (k < s - 2 ? a.H[src * n + row] : a.H[row * n + src]) + (row == src ? a.lambda : 0.f);
-                } else if (tid >= 64 && tid < 64 + PB * 4 && s < a.cnt) {
-                    // H' between the own pairs of batch s and the winner's rows (row of the own pair)
-                    const int q = q_base + ((tid - 64) >> 2), w = tid & 3;
-                    if (q < npairs) {
-                        const long row = L.pairs_l[s][q][w >> 1], cr = (w & 1) ? wi2 : wi1;
-                        if (row >= 0 && row < n) dep = a.H[row * n + cr] + (row == cr ? a.lambda : 0.f);
-                    }
-                }
+            // ---- the winner's steps at my column: the sign combination its own block's evaluation chose (the same
+            // bits a second evaluation from the same inputs would give), times the step of each row's group ----------
+            float wsc1 = sc_col, wsc2 = sc_col;
+            if (win >= 0 && pl == 0 && in && !one_group) {
+                const int g = (int)a.g;
+                wsc1 = a.scales[(long)(wi1 / g) * p + j];
+                wsc2 = a.scales[(long)(wi2 / g) * p + j];
             }
+            // everything for batch s+1 (used after batch s has been evaluated and published)
             if (nxt) {
                 load_cells(s + 1, own_n, i1n, i2n, hasn);
-                if (tid >= 128 && tid < 128 + PB * 4 * s) {           // slots 0 .. s-1: PB * 4 * s <= 896
+                if (tid >= 128 && tid < 128 + PB * 64 && ((tid >> 2) & 15) < s) {     // slots 0 .. s-1 of each own pair
                     const int e = tid - 128;
-                    c_pp = e / (4 * s);
-                    const int r = e - c_pp * 4 * s;
-                    c_k = r >> 2;
-                    c_w = r & 3;
+                    c_pp = e >> 6;
+                    c_k = (e >> 2) & 15;
+                    c_w = e & 3;
                     c_on = true;
                     const int q = q_base + c_pp;
                     const long src = c_k == s - 1 ? (c_w & 1 ? wi2 : wi1) : (long)L.prow[c_k][c_w & 1];
@@ -751,26 +838,15 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 }
             }
             if (win >= 0) {
-                if (tid < 4 * (s - 1)) {
-                    L.coef_win[tid >> 2][tid & 3] = dep;
-                    if ((tid & 3) == 0) L.which_win[tid >> 2] = ls_which(L.prow[tid >> 2][0], L.prow[tid >> 2][1], wi1, wi2);
-                } else if (tid >= 64 && tid < 64 + PB * 4) {
-                    L.e_own[(tid - 64) >> 2][tid & 3] = dep;
-                }
-                lds_barrier();
+#pragma unroll
+                for (int i = 0; i < PP; ++i)
+                    if (((tid >> 2) & 63) == win) L.e_own[4 * i + (tid >> 8)][tid & 3] = xv[i];
                 if (pl == 0) {
                     float st1 = 0.f, st2 = 0.f;
-                    if (in) {
-                        const bool on1[1] = {true};
-                        const float (*cw[1])[4] = {L.coef_win};
-                        const int *ww[1] = {L.which_win};
-                        ls_apply_slots<1>(&wc, on1, cw, ww, L.pd, col, s - 1);
-                        const PairEval ev = eval_column(wc.g1, wc.g2, wc.k1, wc.k2, wc.sc1, wc.sc2, wc.h11, wc.h22, wc.h12,
-                                                        a.levels);
-                        if (ev.combo >= 0) {
-                            st1 = (float)((ev.combo & 2) ? -1 : 1) * wc.sc1;
-                            st2 = (float)((ev.combo & 1) ? -1 : 1) * wc.sc2;
-                        }
+                    const unsigned code = (L.combos[(win * 4 + sub) * 8 + (lane >> 3)] >> (3 * (lane & 7))) & 7u;
+                    if (in && (code & 1u)) {
+                        st1 = (code & 4u) ? -wsc1 : wsc1;
+                        st2 = (code & 2u) ? -wsc2 : wsc2;
                     }
                     L.pd[s - 1][0][col] = st1;
                     L.pd[s - 1][1][col] = st2;
@@ -791,9 +867,27 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
 #pragma unroll
             for (int i = 0; i < PP; ++i) {
                 float gain = 0.f;
-                if (has[i])
-                    gain = eval_column(own[i].g1, own[i].g2, own[i].k1, own[i].k2, own[i].sc1, own[i].sc2, own[i].h11,
-                                       own[i].h22, own[i].h12, a.levels).gain;
+                unsigned code = 0u;
+                if (has[i]) {
+                    const PairEval ev = eval_column(own[i].g1, own[i].g2, own[i].k1, own[i].k2, own[i].sc1, own[i].sc2,
+                                                    own[i].h11, own[i].h22, own[i].h12, a.levels);
+                    gain = ev.gain;
+                    if (ev.combo >= 0) code = 1u | ((unsigned)ev.combo << 1);
+                }
+                // the chosen combinations of 8 neighbouring columns in one word, published with the batch's number
+                const int q = q_base + 4 * i + pl;
+                unsigned bits = code << (3 * (lane & 7));
+                bits |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)bits, 0xB1, 0xF, 0xF, true);     // lanes ^ 1
+                bits |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)bits, 0x4E, 0xF, 0xF, true);     // lanes ^ 2
+                bits |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)bits, 0x141, 0xF, 0xF, true);    // 7 - lane
+                if ((lane & 7) == 0 && q < npairs) {
+                    const unsigned sq = a.seq0 + (unsigned)s;
+                    unsigned long long *dst = a.xch + (size_t)2 * LS_FAST_PAIRS * chunks +
+                                              ((size_t)(sq & 1u) * chunks + blockIdx.x) * (LS_FAST_PAIRS * 32) +
+                                              ((size_t)q * 4 + sub) * 8 + (lane >> 3);
+                    __hip_atomic_store(dst, ((unsigned long long)sq << 32) | (unsigned long long)bits, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
                 gain = wave_sum_f(gain);
                 if (lane == 0) L.wsum[4 * i + pl][sub] = gain;
             }
@@ -817,8 +911,8 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 has[i] = hasn[i];
             }
             if (c_on) L.coef_own[c_pp][c_k][c_w] = c_next;
-            if (tid < PB * s) {
-                const int pp = tid / s, k = tid - pp * s, q = q_base + pp;
+            if (tid < PB * 16 && (tid & 15) < s) {
+                const int pp = tid >> 4, k = tid & 15, q = q_base + pp;
                 L.which_own[pp][k] = q < npairs ? ls_which(L.prow[k][0], L.prow[k][1], L.pairs_l[s + 1][q][0], L.pairs_l[s + 1][q][1]) : 0;
             }
             lds_barrier();
@@ -1030,18 +1124,33 @@ int admmq_ls_group_pairs_per_thread(admmq_ctx *ctx, int64_t p, int npairs) {
     return 0;
 }
 int admmq_ls_group_max_blocks(int64_t p) { return ls_group_chunks(p) * (LS_FAST_PAIRS / 4); }
-size_t admmq_ls_group_xch_words(int64_t p) { return 2 * (size_t)LS_FAST_PAIRS * ls_group_chunks(p); }
+size_t admmq_ls_group_xch_words(int64_t p) { return 2 * (size_t)LS_FAST_PAIRS * ls_group_chunks(p) * (1 + 32); }
 
 // One group of `cnt` <= LS_K batches (pairs: device [cnt][npairs][2]) as one launch; see ls_group_kernel.
-// pairs_per_thread: from admmq_ls_group_pairs_per_thread.  xch: admmq_ls_group_xch_words(p) 8-byte words, fin: one
+// pairs_per_thread: from admmq_ls_group_pairs_per_thread.  couple: the coupling table of the group's batches
+// (admmq_k_ls_couple on the same pairs).  xch: admmq_ls_group_xch_words(p) 8-byte words, fin: one
 // 4-byte word per block, commit, abort_word: 4-byte words, all zero at the start of a search.
+admmq_status admmq_k_ls_couple(admmq_ctx *ctx, const float *H, float lambda, int64_t n, const int32_t *pairs,
+                               int npairs, int batches, float *X) {
+    if (batches < 2) return ADMMQ_OK;
+    if (npairs < 1 || npairs > LS_FAST_PAIRS) return ADMMQ_ERR_PARAM;
+    hipLaunchKernelGGL(ls_couple_kernel, dim3((unsigned)(batches - 1)), dim3(1024), 0, ctx->stream, H, lambda, (long)n,
+                       pairs, npairs, X);
+    ADMMQ_HIP(hipGetLastError());
+    return ADMMQ_OK;
+}
+size_t admmq_ls_couple_floats(int batches) {
+    return batches > 1 ? (size_t)(batches - 1) * LS_FAST_PAIRS * LS_FAST_PAIRS * 4 : 0;
+}
+
 admmq_status admmq_k_ls_group(admmq_ctx *ctx, int pairs_per_thread, const float *H, float lambda, const float *G,
                               const uint8_t *codes, int64_t n, int64_t p, int bits, int64_t g, const float *scales,
                               const int32_t *pairs, int npairs, int cnt, unsigned seq0, int group_seq,
                               unsigned long long *xch, unsigned *fin, int *commit, int *abort_word,
                               long long spin_ticks, int32_t *pend_idx, float *pend_d, int *dev_moves,
-                              double *dev_drop) {
+                              double *dev_drop, const float *couple) {
     LsGroupArgs a;
+    a.couple = couple;
     a.H = H; a.lambda = lambda; a.G = G; a.codes = codes; a.n = (long)n; a.p = (long)p;
     a.levels = (1 << bits) - 1; a.g = (long)g; a.scales = scales; a.pairs = pairs; a.npairs = npairs; a.cnt = cnt;
     a.seq0 = seq0; a.group_seq = group_seq; a.xch = xch; a.fin = fin; a.commit = commit; a.abort_word = abort_word;
