@@ -519,7 +519,6 @@ __device__ inline bool ls_wait_expired(long long t0, long long limit, const int 
 struct LsGroupLds {
     float pd[LS_K][2][LSG_TILE];                  // 32 KB: steps applied so far in this group, at my columns
     float tot[LS_FAST_PAIRS];                     // every candidate's summed gain
-    float e_own[LSG_PB_MAX][4];                   // H' between the own pairs and the rows of the pair that has just won
     int pairs_l[LS_K][LS_FAST_PAIRS][2];          //  8 KB: the group's batches
     float coef_own[LSG_PB_MAX][LS_K][4];          // H' between the own pairs and the rows of the applied slots
     int which_own[LSG_PB_MAX][LS_K];              // which rows of a slot are rows of the pair (4 bits)
@@ -549,8 +548,11 @@ struct LsCell {
     int k1, k2;
 };
 
+// vz: a zero the compiler cannot see through, in a vector register.  The three entries of H' have the same address
+// in all lanes and would otherwise be fetched by the scalar unit, whose loads share a counter with the LDS: the
+// next LDS read would then wait out their whole trip to memory.  As vector loads they are waited for where used.
 __device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int r2, long j, bool one_group,
-                                    float sc_col) {
+                                    float sc_col, int vz) {
     const long i1 = r1, i2 = r2;
     const int g = (int)a.g;               // (rows and group size fit 32 bits: a 64-bit division per load would cost more
     c.g1 = a.G[i1 * a.p + j];             //  than the rest of the evaluation)
@@ -563,9 +565,9 @@ __device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int
         c.sc1 = a.scales[(long)(r1 / g) * a.p + j];
         c.sc2 = a.scales[(long)(r2 / g) * a.p + j];
     }
-    c.h11 = a.H[i1 * a.n + i1] + a.lambda;
-    c.h22 = a.H[i2 * a.n + i2] + a.lambda;
-    c.h12 = a.H[i1 * a.n + i2];
+    c.h11 = a.H[i1 * a.n + i1 + vz] + a.lambda;
+    c.h22 = a.H[i2 * a.n + i2 + vz] + a.lambda;
+    c.h12 = a.H[i1 * a.n + i2 + vz];
 }
 
 // slot with steps (d1, d2) at this column, coefficients co = H'[i1][a], H'[i1][b], H'[i2][a], H'[i2][b] and row
@@ -652,6 +654,11 @@ __global__ __launch_bounds__(1024) void ls_couple_kernel(const float *__restrict
     }
 }
 
+// the value lane `l` (the same in all lanes) holds, in every lane
+__device__ inline float lane_value(float v, int l) {
+    return __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(v), l));
+}
+
 template <int PP>
 __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     extern __shared__ __align__(16) unsigned char ls_group_lds[];
@@ -695,6 +702,8 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
     }
     __syncthreads();
 
+    int vz;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vz));
     // one grid per column: the step of every row is the column's, known from the start
     const bool one_group = a.g >= n;
     const float sc_col = (one_group && in) ? a.scales[j] : 0.f;
@@ -714,7 +723,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             ok[i] = pair_ok && in;
             cell[i] = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
             if (pair_ok) {
-                if (in) ls_cell_load(cell[i], a, r1[i], r2[i], j, one_group, sc_col);
+                if (in) ls_cell_load(cell[i], a, r1[i], r2[i], j, one_group, sc_col, vz);
             }
         }
     };
@@ -740,13 +749,15 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                                             ((size_t)(seq & 1u) * chunks + blockIdx.x) * (LS_FAST_PAIRS * 32);
             // H' between the own pairs of batch s and every candidate of batch s-1 (a table of an earlier launch, so
             // an ordinary load): requested before the wait, there by the time the winner is known
-            float xv[PP];
+            // (lane w of a wave holds the four entries of its pair against candidate w: the winner's are then one
+            // lane's registers, read by all lanes without a pass through LDS)
+            floatx4 xv[PP];
 #pragma unroll
             for (int i = 0; i < PP; ++i) {
-                xv[i] = 0.f;
-                const int q = q_base + 4 * i + (tid >> 8);
+                xv[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+                const int q = q_base + 4 * i + pl;
                 if (s < a.cnt && q < npairs)
-                    xv[i] = a.couple[((size_t)(s - 1) * LS_FAST_PAIRS + q) * (LS_FAST_PAIRS * 4) + (tid & 255)];
+                    xv[i] = *(const floatx4 *)(a.couple + ((size_t)(s - 1) * LS_FAST_PAIRS + q) * (LS_FAST_PAIRS * 4) + 4 * lane);
             }
             bool bad = a.spin_ticks < 0;          // a negative bound makes every block leave at its first wait
             {
@@ -815,7 +826,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             // ---- the winner's steps at my column: the sign combination its own block's evaluation chose (the same
             // bits a second evaluation from the same inputs would give), times the step of each row's group ----------
             float wsc1 = sc_col, wsc2 = sc_col;
-            if (win >= 0 && pl == 0 && in && !one_group) {
+            if (win >= 0 && in && !one_group) {
                 const int g = (int)a.g;
                 wsc1 = a.scales[(long)(wi1 / g) * p + j];
                 wsc2 = a.scales[(long)(wi2 / g) * p + j];
@@ -838,25 +849,22 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 }
             }
             if (win >= 0) {
-#pragma unroll
-                for (int i = 0; i < PP; ++i)
-                    if (((tid >> 2) & 63) == win) L.e_own[4 * i + (tid >> 8)][tid & 3] = xv[i];
-                if (pl == 0) {
-                    float st1 = 0.f, st2 = 0.f;
-                    const unsigned code = (L.combos[(win * 4 + sub) * 8 + (lane >> 3)] >> (3 * (lane & 7))) & 7u;
-                    if (in && (code & 1u)) {
-                        st1 = (code & 4u) ? -wsc1 : wsc1;
-                        st2 = (code & 2u) ? -wsc2 : wsc2;
-                    }
+                float st1 = 0.f, st2 = 0.f;
+                const unsigned code = (L.combos[(win * 4 + sub) * 8 + (lane >> 3)] >> (3 * (lane & 7))) & 7u;
+                if (in && (code & 1u)) {
+                    st1 = (code & 4u) ? -wsc1 : wsc1;
+                    st2 = (code & 2u) ? -wsc2 : wsc2;
+                }
+                if (pl == 0) {              // kept for the batches after the next (read behind a later barrier)
                     L.pd[s - 1][0][col] = st1;
                     L.pd[s - 1][1][col] = st2;
                 }
-                lds_barrier();
 #pragma unroll
-                for (int i = 0; i < PP; ++i)
-                    if (has[i] && s < a.cnt)
-                        ls_cell_apply(own[i], L.e_own[4 * i + pl], ls_which(wi1, wi2, i1[i], i2[i]), L.pd[s - 1][0][col],
-                                      L.pd[s - 1][1][col]);
+                for (int i = 0; i < PP; ++i) {
+                    const float eo[4] = {lane_value(xv[i].x, win), lane_value(xv[i].y, win), lane_value(xv[i].z, win),
+                                         lane_value(xv[i].w, win)};
+                    if (has[i] && s < a.cnt) ls_cell_apply(own[i], eo, ls_which(wi1, wi2, i1[i], i2[i]), st1, st2);
+                }
             }
             if (s == a.cnt) break;
         } else if (nxt) {
