@@ -542,10 +542,14 @@ __device__ inline float row_ordered_sum(float acc, float v, bool with_lane0) {
     return acc;
 }
 
-// one pair at one column: the values read from memory, then brought up to date slot by slot
+// one pair at one column: the values read from memory, then brought up to date slot by slot.  Codes and diagonal
+// entries stay as loaded (raw bytes, H without the damping) and what is done to them is kept beside them (dk, the
+// damping added where the cell is evaluated): an operation on a loaded value at the place of the load would make
+// the wave wait there for the whole trip to memory, which is what issuing the loads a step ahead is meant to hide.
 struct LsCell {
     float g1, g2, sc1, sc2, h11, h22, h12;
-    int k1, k2;
+    unsigned k1, k2;
+    int dk1, dk2;
 };
 
 // vz: a zero the compiler cannot see through, in a vector register.  The three entries of H' have the same address
@@ -565,8 +569,8 @@ __device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int
         c.sc1 = a.scales[(long)(r1 / g) * a.p + j];
         c.sc2 = a.scales[(long)(r2 / g) * a.p + j];
     }
-    c.h11 = a.H[i1 * a.n + i1 + vz] + a.lambda;
-    c.h22 = a.H[i2 * a.n + i2 + vz] + a.lambda;
+    c.h11 = a.H[i1 * a.n + i1 + vz];
+    c.h22 = a.H[i2 * a.n + i2 + vz];
     c.h12 = a.H[i1 * a.n + i2 + vz];
 }
 
@@ -579,8 +583,8 @@ __device__ inline void ls_cell_apply(LsCell &c, const float *co, int wh, float d
     // the scalar unit instead of a dozen vector instructions per slot)
     if (__builtin_amdgcn_readfirstlane(wh) != 0) {
         const int s1 = step_sign(d1), s2 = step_sign(d2);
-        c.k1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
-        c.k2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
+        c.dk1 += ((wh & 1) ? s1 : 0) + ((wh & 2) ? s2 : 0);
+        c.dk2 += ((wh & 4) ? s1 : 0) + ((wh & 8) ? s2 : 0);
     }
 }
 
@@ -721,7 +725,7 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
             }
             const bool pair_ok = !(r1[i] < 0 || r2[i] < 0 || r1[i] >= n || r2[i] >= n || r1[i] == r2[i]);
             ok[i] = pair_ok && in;
-            cell[i] = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0, 0};
+            cell[i] = LsCell{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0u, 0u, 0, 0};
             if (pair_ok) {
                 if (in) ls_cell_load(cell[i], a, r1[i], r2[i], j, one_group, sc_col, vz);
             }
@@ -877,8 +881,9 @@ __global__ __launch_bounds__(1024) void ls_group_kernel(LsGroupArgs a) {
                 float gain = 0.f;
                 unsigned code = 0u;
                 if (has[i]) {
-                    const PairEval ev = eval_column(own[i].g1, own[i].g2, own[i].k1, own[i].k2, own[i].sc1, own[i].sc2,
-                                                    own[i].h11, own[i].h22, own[i].h12, a.levels);
+                    const PairEval ev = eval_column(own[i].g1, own[i].g2, (int)(own[i].k1 & 0xFFu) + own[i].dk1,
+                                                    (int)(own[i].k2 & 0xFFu) + own[i].dk2, own[i].sc1, own[i].sc2,
+                                                    own[i].h11 + a.lambda, own[i].h22 + a.lambda, own[i].h12, a.levels);
                     gain = ev.gain;
                     if (ev.combo >= 0) code = 1u | ((unsigned)ev.combo << 1);
                 }
