@@ -1813,8 +1813,8 @@ bool penalty_range_ok(const admmq_schedule *s) {
 
 bool schedule_ok(const admmq_schedule *s) {
     return s->T >= 1 && s->T <= (1 << 20) && s->rho0 > 0.0 && s->gamma >= 1.0 && isfinite(s->rho0) &&
-           isfinite(s->gamma) && penalty_range_ok(s) && s->rho0 > 0.0 && s->gamma >= 1.0 && s->damp >= 0.0 && isfinite(s->rho0) &&
-           isfinite(s->gamma) && isfinite(s->damp) && s->ls_rounds >= 0 && s->ls_batches >= 0 && s->ls_pairs >= 0 &&
+           isfinite(s->gamma) && penalty_range_ok(s) && s->damp >= 0.0 && isfinite(s->damp) && s->ls_rounds >= 0 &&
+           s->ls_batches >= 0 && s->ls_pairs >= 0 &&
            s->refresh_iter >= -1 && s->quiet_stop >= 0 && s->clip_points >= 0 && s->clip_points <= 100000 &&
            (s->clip_points == 0 || (s->clip_shrink >= 0.0 && s->clip_shrink < 1.0));
 }
