@@ -30,6 +30,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
 PMC_TRAFFIC_FROM = {"cfg2": "profiles/cfg2_hbm_traffic_pmc.txt (rocprofv3 --pmc, 16384 tokens, 6 iterations)"}
 PMC_TRAFFIC_BYTES = {
     "cfg2": {"gemm": (227176.3 + 65536.0) * 1024, "project": (65784.5 + 131104.0) * 1024,
+             "gemm_project": (262509.7 + 131080.0) * 1024,
              # the opt-in products (profiles/bench_cfg2_fast_products_kernel_trace.txt): product kernel + operand split
              "gemm_f16x3": (238850.1 + 83968.0 + 32909.4 + 65536.1) * 1024},
 }
@@ -257,7 +258,9 @@ def main():
             "bound": "mfma", "achieved": 2.0 * n * n * p / (fused_ms * 1e-3) / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS,
             "unit": "TFLOP/s", "frac": 2.0 * n * n * p / (fused_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
             "ms_per_launch": fused_ms, "flop_per_launch": 2.0 * n * n * p,
-            "epilogue_bytes_per_launch": 16.0 * n * p, "launches_per_layer": fused_n},
+            "epilogue_bytes_per_launch": 16.0 * n * p, "launches_per_layer": fused_n,
+            "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm_project"),
+            "traffic_from": PMC_TRAFFIC_FROM.get(cfg.name)},
         "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
                               "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
