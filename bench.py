@@ -269,7 +269,7 @@ def main():
                              "bound": "mfma", "achieved": hess_tf, "peak": hess_peak, "unit": "TFLOP/s",
                              "frac": hess_tf / hess_peak, "ms_per_call": hess_ms},
         "middle_solve_ms_per_launch": tri_ms,
-        "factor_form": "band16" if cfg.n >= 8192 and os.environ.get("ADMMQ_FACTOR", "")[:1] != "t" or os.environ.get("ADMMQ_FACTOR", "")[:1] == "b" else "tridiagonal",
+        "factor_form": "band16" if cfg.n >= 4096 and os.environ.get("ADMMQ_FACTOR", "")[:1] != "t" or os.environ.get("ADMMQ_FACTOR", "")[:1] == "b" else "tridiagonal",
         "input_generation_s": gen_s,
     }
     # informational, outside the timed region and not part of `value`: the same layer with the opt-in stopping

@@ -283,17 +283,17 @@ admmq_status admmq_k_band_reduce(admmq_ctx *ctx, double *A64, int64_t n, double 
                                  double *bd);
 
 // The form of the factorisation for an n x n Hessian.  The band form costs a fraction of the one-stage tridiagonal
-// reduction (block reflectors: one pass over the trailing matrix per 16 columns instead of one per column), but its
-// per-iteration solve is 16 x 16 block elimination on the fp64 matrix cores, several times the cost of the scalar
-// recurrence of the tridiagonal form.  Small layers run thousands of short iterations, so they keep the tridiagonal
-// form; from n = 8192 on the reduction dominates and the band form wins (measured at n = 12288: layer 6.2 s against
-// 6.7 s; at n = 4096 the band solve alone would cost more per iteration than the tridiagonal one).
+// reduction (block reflectors: one pass over the trailing matrix per 16 columns instead of one per column: 34 ms
+// against 92 ms at n = 4096, 0.38 s against 1.0 s at n = 12288), but its per-iteration solve is 16 x 16 block
+// elimination on the fp64 matrix cores, about twice the cost of the scalar recurrence of the tridiagonal form
+// (0.15 against 0.08 ms at 4096 x 4096).  From n = 4096 on the reduction's saving outweighs that for any schedule
+// of fewer than about 800 iterations; below, the chain of the tridiagonal form is short anyway.
 // ADMMQ_FACTOR=band / tridiag forces one form (read at every call).
 bool admmq_factor_is_band(int64_t n) {
     const char *e = getenv("ADMMQ_FACTOR");
     if (e && e[0] == 't') return false;
     if (e && e[0] == 'b') return true;
-    return n >= 8192;
+    return n >= 4096;
 }
 
 // band != NULL: reduction to band form (ta, tb unused); else to tridiagonal form

@@ -180,12 +180,19 @@ def test_layer_full_width_against_oracle_slice(ctx, hessian_16k, name):
         assert abs(st_fast.j_damp_admm - st_full.j_damp_admm) <= 1e-3 * st_full.j_damp_admm
 
 
-@pytest.mark.parametrize("fast,cols", [(False, 512), (True, 3328), (True, 512), (True, 1024)])
-def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, fast, cols):
+@pytest.mark.parametrize("fast,cols,form", [(False, 512, "default"), (False, 512, "tridiag"), (False, 512, "chain"),
+                                            (True, 3328, "default"), (True, 512, "default"), (True, 1024, "default")])
+def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, monkeypatch, fast, cols, form):
     """The W-update of the 4096-wide workloads (factorisation of the full Hessian, both products in the tile
-    configuration the layer uses, tridiagonal solve) against the oracle's literal eq. 7 through eigh, within the
-    1e-5 relative Frobenius bar.  fast: the opt-in split-fp16 products; 3328 columns give 208 tiles (one slice of
-    the k axis), 1024 columns 64 tiles (four slices), 512 columns 32 tiles (eight slices)."""
+    configuration the layer uses, solve with the middle factor) against the oracle's literal eq. 7 through eigh,
+    within the 1e-5 relative Frobenius bar.  form: the factorisation's form at this size by default (the band form
+    with the split sweeps), the tridiagonal form, or the band form with the unsplit sweeps.  fast: the opt-in
+    split-fp16 products; 3328 columns give 208 tiles (one slice of the k axis), 1024 columns 64 tiles (four slices),
+    512 columns 32 tiles (eight slices)."""
+    if form == "tridiag":
+        monkeypatch.setenv("ADMMQ_FACTOR", "tridiag")
+    if form == "chain":
+        monkeypatch.setenv("ADMMQ_BAND_SOLVE", "chain")
     cfg = si.CONFIGS["cfg2"]
     H32 = hessian_16k
     n = cfg.n                                             # fp32 with 512 columns: the 256 x 256 tile path is taken
