@@ -345,7 +345,11 @@ __global__ __launch_bounds__(64 * SW) void band_apply_split_kernel(const double 
     __shared__ __align__(32) double chm[SW][256];                  // the tile's chain matrices: the propagator over each segment
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, kq = lane >> 4;
-    const long j = (long)blockIdx.x * 16 + col;
+    // blocks whose ids are congruent mod 8 run on the same XCD: they get neighbouring strips, so that the two halves
+    // of a 128-byte line of Y (two strips' worth of a row) are asked for by the same L2
+    long strip = blockIdx.x;
+    if ((gridDim.x & 7) == 0) strip = (long)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const long j = strip * 16 + col;
     const bool jok = j < p;
     const int ntile = (nbk + TB - 1) / TB;
     unsigned smax = 0;

@@ -101,7 +101,11 @@ __global__ __launch_bounds__(NT) void tridiag_apply_split_kernel(const double *_
     __shared__ double endf[2][NS][C], endP[2][NS][C];
     const int tid = threadIdx.x;
     const int c = tid % C, sg = tid / C;
-    const long j = (long)blockIdx.x * C + c;
+    // blocks whose ids are congruent mod 8 run on the same XCD: they get neighbouring strips, so that the pieces of a
+    // 128-byte line of Y that belong to two strips are asked for by the same L2
+    long strip = blockIdx.x;
+    if ((gridDim.x & 7) == 0) strip = (long)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const long j = strip * C + c;
     const bool jok = j < p;
     const long ntile = (n + TR - 1) / TR;
 
