@@ -239,7 +239,7 @@ admmq_status admmq_grid_fit(admmq_ctx *ctx, const float *W0, int64_t n, int64_t 
 /* Alg. 1 lines 1-3: damp, scale and factorise H once; the result stays in the context and serves
  * every rho.  d_out (device fp32 [n], may be NULL) receives d_i = sqrt(H'_ii) = 1/Sigma_ii.
  * The factorisation is an orthogonal similarity Hs = Q M Q^T in fp64 (Householder reflectors) with M tridiagonal for
- * n < 8192 and a band matrix of half-bandwidth 16 from there on: (Hs + rho I)^{-1} = Q (M + rho I)^{-1} Q^T for any
+ * n < 4096 and a band matrix of half-bandwidth 16 from there on: (Hs + rho I)^{-1} = Q (M + rho I)^{-1} Q^T for any
  * rho, which plays the part of the eigendecomposition of Sec. 3.3.  The environment variable ADMMQ_FACTOR
  * (tridiag / band, read at every call) forces one form. */
 admmq_status admmq_factorize(admmq_ctx *ctx, const float *H, int64_t n, double damp,
