@@ -571,23 +571,13 @@ admmq_status admmq_k_band_apply(admmq_ctx *ctx, const double *fac, int64_t n, in
     if ((const float *)S == Y) return ADMMQ_ERR_PARAM;
     const int nbk = (int)((n + BW - 1) / BW);
     // the split sweeps (eight segments per tile; sixteen, in blocks of 1024 threads with half the registers each, are
-    // slower: 0.19 against 0.15 ms at 4096 x 4096); ADMMQ_BAND_SOLVE=chain: the unsplit ones, one wave per strip;
-    // ADMMQ_BAND_SOLVE=split: the split ones whatever the shape
+    // slower: 0.19 against 0.15 ms at 4096 x 4096); ADMMQ_BAND_SOLVE=chain: the unsplit ones, one wave per strip
     // (read at every call).  A block of the split sweeps fills a compute unit's registers, so its strips go in rounds
-    // of one per unit: with more strips than units (25600 x 5120: 320 against 256, 1.56 ms) the unsplit sweeps, whose
-    // blocks are small, are as fast or faster (1.47 ms) and stay the default.
+    // of one per unit; with more strips than units (25600 x 5120: 320 against 256) the unsplit sweeps, whose blocks
+    // are small, are a little faster (1.47 against 1.56 ms).  The split ones are used all the same: a column's
+    // result must not depend on how many columns share the call (several matrices on one Hessian).
     const char *solve_env = getenv("ADMMQ_BAND_SOLVE");
-    bool split = !(solve_env && solve_env[0] == 'c');
-    if (split && !(solve_env && solve_env[0] == 's')) {
-        static int cus[64];
-        int &units = cus[ctx->device & 63];
-        if (units == 0 && (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess ||
-                           units <= 0)) {
-            (void)hipGetLastError();
-            units = 256;
-        }
-        split = (p + 15) / 16 <= units;
-    }
+    const bool split = !(solve_env && solve_env[0] == 'c');
     if (split) {
         constexpr int SW = 8;
         const unsigned blocks = (unsigned)((p + 15) / 16);
