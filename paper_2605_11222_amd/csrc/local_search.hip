@@ -92,6 +92,15 @@ __device__ inline void load_pending_col(const float *__restrict__ pend_d, long p
     }
 }
 
+// One applied pair's steps (d1, d2) onto the gradient entries of a row pair: g -= H'[row][a] d1 + H'[row][b] d2,
+// co = H'[i1][a], H'[i1][b], H'[i2][a], H'[i2][b].  Fused multiply-adds in a fixed order: half the vector
+// instructions of separate products and sums, and the one place where both forms of the search (one launch per
+// batch, one launch per group) take this step, so that they round alike.
+__device__ inline void pending_onto(float &g1, float &g2, const float *co, float d1, float d2) {
+    g1 = __fmaf_rn(-co[1], d2, __fmaf_rn(-co[0], d1, g1));
+    g2 = __fmaf_rn(-co[3], d2, __fmaf_rn(-co[2], d1, g2));
+}
+
 // stored gradient entries and codes of a row pair at one column -> those of the CURRENT codes: the pending
 // moves are added (codes and G are both brought up to date by the flush)
 __device__ inline void apply_pending(const PendCol &pc, int npend, const float (*coef)[4], const int *which,
@@ -99,8 +108,7 @@ __device__ inline void apply_pending(const PendCol &pc, int npend, const float (
 #pragma unroll
     for (int k = 0; k < LS_K; ++k) {
         if (k < npend) {
-            g1 -= coef[k][0] * pc.d1[k] + coef[k][1] * pc.d2[k];
-            g2 -= coef[k][2] * pc.d1[k] + coef[k][3] * pc.d2[k];
+            pending_onto(g1, g2, coef[k], pc.d1[k], pc.d2[k]);
             const int wh = which[k];
             if (wh) {
                 const int s1 = step_sign(pc.d1[k]), s2 = step_sign(pc.d2[k]);
@@ -441,8 +449,7 @@ __global__ __launch_bounds__(256) void ls_step_kernel(const float *__restrict__ 
         apply_pending(pc, npend, coef_o, which_o, og1, og2, ok1, ok2);
         if (win >= 0) {
             // the move planned above changes the own pair's gradient rows by H'[i][wi1] nd1 + H'[i][wi2] nd2
-            og1 -= ex[0] * nd1 + ex[1] * nd2;
-            og2 -= ex[2] * nd1 + ex[3] * nd2;
+            pending_onto(og1, og2, ex, nd1, nd2);
             ok1 += i1 == wi1 ? ws1 : (i1 == wi2 ? ws2 : 0);
             ok2 += i2 == wi1 ? ws1 : (i2 == wi2 ? ws2 : 0);
         }
@@ -577,8 +584,7 @@ __device__ inline void ls_cell_load(LsCell &c, const LsGroupArgs &a, int r1, int
 // slot with steps (d1, d2) at this column, coefficients co = H'[i1][a], H'[i1][b], H'[i2][a], H'[i2][b] and row
 // coincidences wh (bit 0: a == i1, 1: b == i1, 2: a == i2, 3: b == i2)
 __device__ inline void ls_cell_apply(LsCell &c, const float *co, int wh, float d1, float d2) {
-    c.g1 -= co[0] * d1 + co[1] * d2;
-    c.g2 -= co[2] * d1 + co[3] * d2;
+    pending_onto(c.g1, c.g2, co, d1, d2);
     // (a slot's rows are rows of this pair once in a few thousand slots, and for all lanes at once: a branch on
     // the scalar unit instead of a dozen vector instructions per slot)
     if (__builtin_amdgcn_readfirstlane(wh) != 0) {
