@@ -194,6 +194,15 @@ def main():
     gemm_tf = 2.0 * n * n * p / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     proj_gbs = 16.0 * n * p / (proj_ms * 1e-3) / 1e9 if proj_ms > 0 else 0.0
     lsa_gbs = 8.0 * n * p / (lsa_ms * 1e-3) / 1e9 if lsa_ms > 0 else 0.0    # one read + one write of G per flush
+    # the search apart from its flushes (group kernels, their launch gaps and the one gradient product), per batch:
+    # an upper bound of a batch's time in the group kernel, priced against the bytes an evaluation has to touch
+    # (pairs x 2 rows x p columns x (4 B of G + 1 B of codes))
+    ls_flushes = mean(lambda s: s.n_ls_apply)
+    groups_per_round = -(-(-(-n // 2)) // 16)
+    ls_batches_run = (ls_flushes / groups_per_round) * (-(-n // 2)) if groups_per_round > 0 else 0.0
+    ls_rest_ms = mean(lambda s: s.ms_local_search) - ls_flushes * lsa_ms
+    ls_batch_us = ls_rest_ms * 1e3 / ls_batches_run if ls_batches_run > 0 else 0.0
+    ls_eval_gbs = 64 * 2 * p * 5.0 / (ls_batch_us * 1e-6) / 1e9 if ls_batch_us > 0 else 0.0
     hess_ms = float(np.mean(hs))
     hess_tf = tokens * n * (n + 1) / (hess_ms * 1e-3) / 1e12
     # bf16 activations in whole 256-channel tiles are multiplied on the bf16 matrix cores (exact products, fp32
@@ -264,6 +273,15 @@ def main():
         "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
                               "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
+        "roofline_ls_group": None if ls_batches_run <= 0 else {
+            "kernel": "ls_group (evaluate eq. 11, choose, apply: one launch per 16 batches)", "bound": "hbm",
+            "achieved": ls_eval_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ls_eval_gbs / PEAK_HBM_GBS,
+            "us_per_batch": ls_batch_us, "batches": ls_batches_run,
+            "measured_as": "search time minus its flushes, over the batches run (includes launch gaps and the "
+                           "gradient product): an upper bound of the kernel's own time per batch",
+            "what_bounds_it": "not the bytes: a batch is one exchange of sums between all blocks plus the vector "
+                              "instructions between a winner's arrival and the next sums; vector ALU busy 61 % of "
+                              "the kernel (profiles/ls_group_cfg2_pmc.txt)"},
         "roofline_hessian": {"kernel": ("hessian_bf16 + sym_reduce (bf16 matrix cores, lower triangle)" if hess_bf16
                                         else "gemm_tn + sym_reduce (fp32 matrix cores, lower triangle)"),
                              "bound": "mfma", "achieved": hess_tf, "peak": hess_peak, "unit": "TFLOP/s",
