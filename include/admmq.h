@@ -148,6 +148,9 @@ typedef struct {            /* host struct, filled when the pointer is not NULL 
      * and such iterations launch no projection pass */
     int32_t n_gemm_project;
     float ms_gemm_project;
+    /* in: non-zero = do not evaluate the objectives (j_damp, j_damp_admm, j_damp_rtn, j_recon are left 0).  They are
+     * not part of Alg. 1: each costs one n x n x p product, inside ms_total (j_damp_rtn also inside ms_setup) */
+    int32_t skip_objectives;
 } admmq_stats;
 
 /* H: raw X^T X (device fp32 [n][n], undamped, read only).  W0: device fp32 [n][ldw], ldw >= p.

@@ -48,7 +48,7 @@ class _Stats(C.Structure):
                 ("n_ls_apply", C.c_int32), ("ms_gemm", C.c_float), ("ms_tridiag", C.c_float),
                 ("ms_project", C.c_float), ("ms_ls_apply", C.c_float), ("refresh_accepted", C.c_int32),
                 ("refresh_err_old", C.c_double), ("refresh_err_new", C.c_double), ("j_recon", C.c_double),
-                ("n_gemm_project", C.c_int32), ("ms_gemm_project", C.c_float)]
+                ("n_gemm_project", C.c_int32), ("ms_gemm_project", C.c_float), ("skip_objectives", C.c_int32)]
 
 
 class _Format(C.Structure):
@@ -261,9 +261,10 @@ class Context:
         return cnt.value
 
     def quantize_layer(self, H, W0, bits, group_size=0, sched: Schedule | None = None, want_stats=True,
-                       want_history=False, profile=False, want_flips=None):
+                       want_history=False, profile=False, want_flips=None, objectives=True):
         """want_history: the primal residual of every iteration and, unless want_flips=False, the number of codes
-        each iteration changed (asking for those makes every iteration write its codes)."""
+        each iteration changed (asking for those makes every iteration write its codes).  objectives=False: the
+        statistics without the objective values (each costs a product of the Hessian with the error matrix)."""
         torch = self._torch
         if want_flips is None:
             want_flips = want_history
@@ -278,6 +279,7 @@ class Context:
                        sched.clip_shrink, int(sched.reuse_factor), sched.seed, sched.quiet_stop)
         st = _Stats()
         st.profile = int(bool(profile))
+        st.skip_objectives = 0 if objectives else 1
         res = (C.c_float * sched.T)() if want_history else None
         flips = (C.c_int64 * sched.T)() if want_history and want_flips else None
         if want_history:

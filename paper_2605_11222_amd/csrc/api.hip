@@ -1223,6 +1223,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     const size_t np = (size_t)n * p;
     const size_t ng = (size_t)(n / g) * p * (pj.kind == ADMMQ_FORMAT_DUAL_GRID ? 2 : 1);     // grid entries
     const bool want = stats != nullptr;
+    const bool want_obj = want && stats->skip_objectives == 0;        // the objectives are reports, not steps of Alg. 1
     Timer t_total(ctx->stream, want), t_phase(ctx->stream, want);
     t_total.start();
     float prof_ms[ADMMQ_TAGS] = {};
@@ -1331,7 +1332,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
     g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = p; g0.M = n; g0.N = p; g0.K = n;
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = p; g0.split_k = 1;
     ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
-    if (want) {
+    if (want_obj) {
         // the plain projection of W0 (round-to-nearest on the initial grid) as the baseline objective; W, Y and F
         // are still free
         if (uniform)
@@ -1434,11 +1435,15 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             for (int t = 0; t < T; ++t) stats->code_flips[t] = (int64_t)h[t];
         }
         // objective of the ADMM result; W, Y are free now
-        if (uniform)
-            ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, pj.scales, pj.zeros, bits, 0, W));
-        else
-            ADMMQ_TRY(admmq_k_diff(ctx, pj.Wq, W0, ldw, n, p, W));
-        ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
+        stats->j_damp_admm = stats->j_recon = 0.0;
+        if (!want_obj) stats->j_damp_rtn = 0.0;
+        if (want_obj) {
+            if (uniform)
+                ADMMQ_TRY(admmq_k_quant_error(ctx, W0, ldw, codes, n, p, g, pj.scales, pj.zeros, bits, 0, W));
+            else
+                ADMMQ_TRY(admmq_k_diff(ctx, pj.Wq, W0, ldw, n, p, W));
+            ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, W, Y, jdev, &stats->j_damp_admm, &stats->j_recon));
+        }
         stats->j_damp = stats->j_damp_admm;
         stats->ls_moves = 0;
     }
@@ -1453,8 +1458,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         ADMMQ_TRY(local_search_core(ctx, H, lambda, W0, n, p, ldw, bits, g, pj.scales, pj.zeros, codes, plan,
                                     sched->seed, nullptr, &moves, &drop));
         ms_ls = t_phase.stop();
-        if (want) {
-            stats->ls_moves = moves;
+        if (want) stats->ls_moves = moves;
+        if (want_obj) {
             admmq_arena_reset_transient(ctx);
             float *E = nullptr, *tmp = nullptr;
             double *jd = nullptr;
@@ -1465,6 +1470,8 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
             ADMMQ_TRY(objectives_core(ctx, H, lambda, n, p, E, tmp, jd, &stats->j_damp, &stats->j_recon));
         }
     }
+    // (the call's time ends here: reading the per-launch events back is the caller's measurement, not the method)
+    const float ms_call = want ? t_total.stop() : 0.f;
     prof_collect(ctx, prof_ms, prof_cnt);
     if (want) {
         stats->ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       stats->n_gemm = prof_cnt[ADMMQ_TAG_GEMM];
@@ -1477,7 +1484,7 @@ admmq_status quantize_core(admmq_ctx *ctx, const float *H, const float *W0, int6
         stats->ms_factor = ms_factor;
         stats->ms_admm = ms_admm;
         stats->ms_local_search = ms_ls;
-        stats->ms_total = t_total.stop();
+        stats->ms_total = ms_call;
     }
     admmq_arena_reset_transient(ctx);
     return ADMMQ_OK;
@@ -1490,6 +1497,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
                                 const admmq_schedule *sched, admmq_stats *stats) {
     const int T = sched->T;
     const bool want = stats != nullptr;
+    const bool want_obj = want && stats[0].skip_objectives == 0;
     int64_t P = 0;
     std::vector<int64_t> off((size_t)count), grp((size_t)count);
     int64_t pmax = 0;
@@ -1603,7 +1611,7 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
     g0.A = f.Q; g0.lda = n; g0.B = B; g0.ldb = P; g0.M = n; g0.N = P; g0.K = n;
     g0.alpha = 1.f; g0.Z = nullptr; g0.out = C0; g0.ldo = P; g0.split_k = 1;
     ADMMQ_TRY(admmq_gemm_tn(ctx, g0));
-    if (want) {
+    if (want_obj) {
         // round-to-nearest on the initial grid as the baseline objective; W, Y and F are still free
         for (int i = 0; i < count; ++i) {
             const admmq_layer &l = L[i];
@@ -1668,8 +1676,12 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             }
             if (st.code_flips)
                 for (int t = 0; t < T; ++t) st.code_flips[t] = -1;       // not counted on this path
-            ADMMQ_TRY(admmq_k_quant_error(ctx, l.W0, l.ldw, l.codes, n, l.p, grp[i], l.scales, l.zeros, l.bits, 0, W));
-            ADMMQ_TRY(objectives_core(ctx, H, lambda, n, l.p, W, Y, jdev, &st.j_damp_admm, &st.j_recon));
+            st.j_damp_admm = st.j_recon = 0.0;
+            if (!want_obj) st.j_damp_rtn = 0.0;
+            if (want_obj) {
+                ADMMQ_TRY(admmq_k_quant_error(ctx, l.W0, l.ldw, l.codes, n, l.p, grp[i], l.scales, l.zeros, l.bits, 0, W));
+                ADMMQ_TRY(objectives_core(ctx, H, lambda, n, l.p, W, Y, jdev, &st.j_damp_admm, &st.j_recon));
+            }
             st.j_damp = st.j_damp_admm;
             st.ls_moves = 0;
         }
@@ -1767,10 +1779,11 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             ctx->ls_fallback_groups = redone_all;
         }
         ms_ls = t_phase.stop();
-        if (want) {
+        if (want)
+            for (int i = 0; i < count; ++i) stats[i].ls_moves = moves[i];
+        if (want_obj) {
             for (int i = 0; i < count; ++i) {
                 const admmq_layer &l = L[i];
-                stats[i].ls_moves = moves[i];
                 admmq_arena_reset_transient(ctx);
                 float *E = nullptr, *tmp = nullptr;
                 double *jd = nullptr;
@@ -1782,9 +1795,9 @@ admmq_status quantize_many_core(admmq_ctx *ctx, const float *H, int64_t n, const
             }
         }
     }
+    const float ms_all = want ? t_total.stop() : 0.f;
     prof_collect(ctx, prof_ms, prof_cnt);
     if (want) {
-        const float ms_all = t_total.stop();
         for (int i = 0; i < count; ++i) {
             admmq_stats &st = stats[i];
             st.ms_gemm = prof_ms[ADMMQ_TAG_GEMM];       st.n_gemm = prof_cnt[ADMMQ_TAG_GEMM];

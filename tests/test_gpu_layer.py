@@ -133,6 +133,24 @@ def test_layer_is_deterministic(ctx, monkeypatch, form):
     assert np.array_equal(a, b)
 
 
+def test_statistics_without_objectives_give_the_same_codes(ctx):
+    """The objective values in the statistics are reports (each a product of the Hessian with the error matrix),
+    no step of Alg. 1: asked to leave them out, a call returns the same codes and grid, zeros for the objectives,
+    and still the timings, iteration count and moves."""
+    import paper_2605_11222_amd as admmq
+    X, W0 = correlated_problem(256, 96, 700, 12)
+    H = to_dev(orc.hessian([X.astype(np.float64)]).astype(np.float32))
+    sched = admmq.Schedule(T=40, ls_rounds=2, ls_pairs=16, seed=3)
+    ca, sa, za, st_a = ctx.quantize_layer(H, to_dev(W0), 3, 64, sched)
+    cb, sb, zb, st_b = ctx.quantize_layer(H, to_dev(W0), 3, 64, sched, objectives=False)
+    assert np.array_equal(ca.cpu().numpy(), cb.cpu().numpy())
+    assert np.array_equal(sa.cpu().numpy(), sb.cpu().numpy()) and np.array_equal(za.cpu().numpy(), zb.cpu().numpy())
+    assert st_a.j_damp > 0 and st_a.j_damp_rtn > 0 and st_a.j_damp_admm > 0 and st_a.j_recon > 0
+    assert st_b.j_damp == 0 and st_b.j_damp_rtn == 0 and st_b.j_damp_admm == 0 and st_b.j_recon == 0
+    assert st_b.iters_done == st_a.iters_done == 40 and st_b.ls_moves == st_a.ls_moves
+    assert st_b.ms_total > 0 and st_b.ms_admm > 0
+
+
 @pytest.mark.parametrize("n,p,bits,g,T,refresh", [
     (1024, 2048, 3, 128, 12, -1),     # 128 x 128 tiles of the product
     (2048, 6400, 4, 0, 8, -1),        # 256 x 256 tiles, one group per column
