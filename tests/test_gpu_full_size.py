@@ -222,6 +222,38 @@ def test_w_update_at_n4096_against_literal_eq7(ctx, hessian_16k, monkeypatch, fa
         ctx.set_fast_products(False)
 
 
+def test_w_update_just_above_the_size_switch_with_ragged_shapes_against_literal_eq7(ctx):
+    """n = 4100 takes the band form by default (the switch is at 4096) with nothing aligned: n is no multiple of 16
+    (the last block row of the band is padded, the solve's guarded sweeps run), of 4 (no 16-byte rows for the
+    products) or of the tiles, and p = 200 is no multiple of a strip of 16 columns.  Against the oracle's literal
+    eq. 7 through eigh, 1e-5 relative Frobenius, at both ends of the penalty's range."""
+    from gpu_util import correlated_problem
+    n, p = 4100, 200
+    X, W0 = correlated_problem(n, p, 6000, seed=41, outliers=4)
+    X64 = X.astype(np.float64)
+    H32 = (X64.T @ X64).astype(np.float32)
+    d, lam = ctx.factorize(to_dev(H32), 0.01, True)
+    dg = d.cpu().numpy()
+    Hd, lam64 = orc.damp_hessian(H32.astype(np.float64), 0.01)
+    assert lam == pytest.approx(lam64, rel=1e-6)
+    d64 = dg.astype(np.float64)
+    Hs = Hd / d64[:, None] / d64[None, :]
+    lam_e, U = np.linalg.eigh(Hs)
+    lam_e = np.maximum(lam_e, 0)
+    Ws = (W0 * dg[:, None]).astype(np.float32)
+    HWs = Hs @ Ws.astype(np.float64)
+    rng = np.random.default_rng(78)
+    scale = np.abs(Ws).mean()
+    for rho in (0.1, 3.0e5):
+        D = (Ws + 0.3 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        V = (rho * 0.1 * scale * rng.standard_normal(Ws.shape)).astype(np.float32)
+        Wg = ctx.w_update(to_dev(Ws), to_dev(D), to_dev(V), rho).cpu().numpy().astype(np.float64)
+        Wref = orc.w_update(U, lam_e, HWs, D.astype(np.float64), V.astype(np.float64), rho)
+        err = np.linalg.norm(Wg - Wref) / np.linalg.norm(Wref)
+        print(f"n={n} p={p} rho={rho:g}: relative W-update error {err:.2e}", flush=True)
+        assert err < 1e-5
+
+
 def test_fast_products_layer_matches_the_default_layer(ctx, hessian_16k):
     """cfg2 at full width with the opt-in split-fp16 products: the trajectory differs from the fp32 products' in
     the last bits of every W, and the iteration amplifies such differences as it does those between fp32 and the
