@@ -281,7 +281,7 @@ def main():
             "epilogue_bytes_per_launch": 16.0 * n * p, "launches_per_layer": fused_n,
             "traffic": PMC_TRAFFIC_BYTES.get(cfg.name, {}).get("gemm_project"),
             "traffic_from": PMC_TRAFFIC_FROM.get(cfg.name)},
-        "roofline_ls_flush": {"kernel": "ls_flush (gradient correction, once per 16 batches)", "bound": "hbm",
+        "roofline_ls_flush": {"kernel": "ls_flush_rows (gradient correction, once per 16 batches)", "bound": "hbm",
                               "achieved": lsa_gbs, "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": lsa_gbs / PEAK_HBM_GBS, "ms_per_launch": lsa_ms},
         "roofline_ls_group": None if ls_batches_run <= 0 else {

@@ -1069,6 +1069,112 @@ __global__ __launch_bounds__(256) void ls_flush_kernel(const float *__restrict__
     }
 }
 
+// The same pass for rows of whole 16-byte pieces (p a multiple of 4), organised around what is re-read: a thread
+// keeps the steps of all slots at its four columns in registers (2 K x 4 values) and walks 32 rows of G with them,
+// so the pending step rows come through the caches once per 32 rows of G instead of once per 8; the rows'
+// coefficients sit in LDS (every lane reads the same word), the next eight rows of G are on their way while eight are
+// worked on, and each slot enters a sum by two fused multiply-adds in slot order.
+// grid (ceil(p/1024), ceil(n/LSF_ROWS)), block 256; LSF_ROWS = 32, or 16 or 8 where 32 would leave the chip short of
+// blocks (narrow matrices).
+template <int LSF_ROWS>
+__global__ __launch_bounds__(256, 2) void ls_flush_rows_kernel(const float *__restrict__ H, float lambda,
+                                                               float *__restrict__ G, uint8_t *__restrict__ codes,
+                                                               long n, long p, const int32_t *__restrict__ pend_idx,
+                                                               const float *__restrict__ pend_d, int count,
+                                                               const int *__restrict__ commit, int commit_needed) {
+    typedef floatx4 vec;
+    constexpr int CPT = 4;                               // columns per thread
+    if (commit && *commit != commit_needed) return;
+    constexpr int R = LSF_ROWS, S2 = 2 * LS_K;
+    __shared__ __align__(16) float coef[R][S2];          // coef[rr][2 k + w] = H'[r0 + rr][row w of slot k], 0 for an empty slot
+    __shared__ int any_sh;
+    const int tid = threadIdx.x;
+    const long r0 = (long)blockIdx.y * R;
+    const long j0 = ((long)blockIdx.x * 256 + tid) * CPT;
+    if (tid == 0) any_sh = 0;
+    __syncthreads();
+    for (int e = tid; e < R * S2; e += 256) {
+        const int kw = e / R, rr = e - kw * R, k = kw >> 1;          // neighbouring threads: neighbouring entries of a row of H'
+        const long i = r0 + rr;
+        float h = 0.f;
+        if (k < count && pend_idx[2 * k] >= 0 && i < n) {
+            const long src = pend_idx[kw];
+            h = H[src * n + i];
+            if (i == src) h += lambda;
+            any_sh = 1;
+        }
+        coef[rr][kw] = h;
+    }
+    const bool cols = j0 < p;
+    vec zero;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) zero[c] = 0.f;
+    vec d[S2];
+#pragma unroll
+    for (int kw = 0; kw < S2; ++kw) {
+        d[kw] = zero;
+        if (cols && (kw >> 1) < count) d[kw] = *(const vec *)(pend_d + (long)kw * p + j0);
+    }
+    // (the first rows of G are asked for before the barrier: they travel while the coefficients are gathered)
+    constexpr int PF = 8;
+    vec g[2][PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) g[0][u] = (cols && r0 + u < n) ? *(const vec *)(G + (r0 + u) * p + j0) : zero;
+    __syncthreads();
+    if (any_sh == 0 || !cols) return;
+    // the block that owns a pending row brings its stored codes up to date (one owner per row and column, slots in
+    // order: a row may sit in several slots)
+    for (int k = 0; k < count; ++k) {
+        const long a = pend_idx[2 * k], b = pend_idx[2 * k + 1];
+        if (a < 0) continue;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const long row = w ? b : a;
+            if (row >= r0 && row < r0 + R) {
+                vec dv = d[0];
+#pragma unroll
+                for (int kk = 0; kk < LS_K; ++kk)
+                    if (kk == k) dv = d[2 * kk + w];                  // (register array: selected, not indexed)
+#pragma unroll
+                for (int c = 0; c < CPT; ++c)
+                    if (dv[c] != 0.f) codes[row * p + j0 + c] = (uint8_t)((int)codes[row * p + j0 + c] + step_sign(dv[c]));
+            }
+        }
+    }
+#pragma unroll
+    for (int c8 = 0; c8 < R / PF; ++c8) {
+        const int cur = c8 & 1;
+        if (c8 + 1 < R / PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const long i = r0 + (c8 + 1) * PF + u;
+                g[cur ^ 1][u] = i < n ? *(const vec *)(G + i * p + j0) : zero;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int rr = c8 * PF + u;
+            const long i = r0 + rr;
+            if (i >= n) break;
+            vec acc = zero;
+#pragma unroll
+            for (int q4 = 0; q4 < S2 / 4; ++q4) {
+                const floatx4 cf = *(const floatx4 *)&coef[rr][4 * q4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const vec dv = d[4 * q4 + t];
+#pragma unroll
+                    for (int c = 0; c < CPT; ++c) acc[c] = __fmaf_rn(cf[t], dv[c], acc[c]);
+                }
+            }
+            vec gq = g[cur][u];
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) gq[c] -= acc[c];
+            *(vec *)(G + i * p + j0) = gq;
+        }
+    }
+}
+
 }  // namespace
 
 int admmq_ls_chunks(int64_t p) { return (int)((p + LS_CHUNK - 1) / LS_CHUNK); }
@@ -1101,10 +1207,26 @@ admmq_status admmq_k_ls_flush(admmq_ctx *ctx, const float *H, float lambda, floa
                               int64_t p, const int32_t *pend_idx, const float *pend_d, int count, const int *commit,
                               int commit_needed) {
     if (count <= 0) return ADMMQ_OK;
-    dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
     const int sp = admmq_prof_begin(ctx, ADMMQ_TAG_LS_APPLY);
-    hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n, (long)p,
-                       pend_idx, pend_d, count, commit, commit_needed);
+    if (p % 4 == 0) {
+        // 32 rows per block where that still gives two blocks per compute unit, else 16, else 8
+        const long cb = (p + 1023) / 1024;
+        const int R = cb * ((n + 31) / 32) >= 512 ? 32 : (cb * ((n + 15) / 16) >= 512 ? 16 : 8);
+        dim3 grid((unsigned)cb, (unsigned)((n + R - 1) / R));
+        if (R == 32)
+            hipLaunchKernelGGL(ls_flush_rows_kernel<32>, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n,
+                               (long)p, pend_idx, pend_d, count, commit, commit_needed);
+        else if (R == 16)
+            hipLaunchKernelGGL(ls_flush_rows_kernel<16>, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n,
+                               (long)p, pend_idx, pend_d, count, commit, commit_needed);
+        else
+            hipLaunchKernelGGL(ls_flush_rows_kernel<8>, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n,
+                               (long)p, pend_idx, pend_d, count, commit, commit_needed);
+    } else {
+        dim3 grid((unsigned)((p + 1023) / 1024), (unsigned)((n + 7) / 8));
+        hipLaunchKernelGGL(ls_flush_kernel, grid, dim3(256), 0, ctx->stream, H, lambda, G, codes, (long)n, (long)p,
+                           pend_idx, pend_d, count, commit, commit_needed);
+    }
     admmq_prof_end(ctx, sp);
     ADMMQ_HIP(hipGetLastError());
     return ADMMQ_OK;
